@@ -1,0 +1,275 @@
+/*
+ * gbt.h -- C ABI of libgbt: quantised-histogram decision-tree construction
+ * (the data-parallel hot path of arXiv 1806.11248) for AMD MI355X (gfx950).
+ *
+ * Conventions
+ * -----------
+ *  - Plain C, no exceptions.  Every call returns an int32_t status:
+ *      GBT_OK, GBT_EINVAL (null pointer / bad shape / value out of range),
+ *      GBT_ENOMEM (caller's workspace too small), GBT_EHIP (a HIP runtime call
+ *      failed; text in gbt_last_error), GBT_EUNSUPPORTED (e.g. bits > 16).
+ *    On an argument error nothing has been enqueued and outputs are untouched.
+ *  - Pointers marked [dev] are device (HBM) addresses, [host] are host
+ *    addresses.  The caller owns every buffer, including workspaces: the
+ *    library allocates no device memory after gbt_create (which takes a few KB
+ *    of pinned host staging).  Pointers are borrowed for the call only.
+ *  - Work is enqueued on the stream given to gbt_create.  A call that returns
+ *    a host value (a count, split records, a tree) synchronises that stream
+ *    before returning; every other call is asynchronous.
+ *  - One gbt_ctx must not be used from two threads at once.
+ *
+ * Data layout
+ * -----------
+ *  - Symbols: sym(r,f) in [0, nb[f]) is the quantile bin of feature f in row r;
+ *    a missing value has the one global symbol missing_sym = max_f nb[f].
+ *  - Packed matrix (Sec. 2.2): element e = r*F + f occupies bits
+ *    [e*bits, (e+1)*bits) of a little-endian bit stream stored in uint32 words,
+ *    rows back to back without padding, unused tail bits zero, followed by one
+ *    zero word (so an 8-byte read at the last element stays in bounds).
+ *    bits = number of bits of the largest symbol present, 1..16.
+ *  - Gradient pairs: float2 (g, h) per row.  Histograms are summed in 64-bit
+ *    fixed point: each g is rounded once to an int32 multiple of 1/scale_g
+ *    (scale a power of two with |g*scale_g| <= 2^30 for every row; same for h),
+ *    and all later sums are exact integers, so a histogram does not depend on
+ *    the order of accumulation and "parent - child" is exactly the sibling.
+ *  - Histogram of one node: int64 hist[F][B][2] (g then h), B = max_bins.
+ */
+#ifndef GBT_H
+#define GBT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GBT_API __attribute__((visibility("default")))
+
+#define GBT_OK 0
+#define GBT_EINVAL (-1)
+#define GBT_ENOMEM (-2)
+#define GBT_EHIP (-3)
+#define GBT_EUNSUPPORTED (-4)
+
+#define GBT_OBJ_SQUARED 0
+#define GBT_OBJ_LOGISTIC 1
+
+#define GBT_MAX_BITS 16
+#define GBT_GAIN_FLOOR 1e-6 /* a node is split only if gain > max(gamma, GBT_GAIN_FLOOR) */
+
+typedef struct gbt_ctx gbt_ctx;
+
+typedef struct gbt_params {
+    int32_t max_depth;       /* edges from the root to the deepest leaf, 0..16 */
+    int32_t max_bins;        /* B: stride of the bin axis, >= every nb[f], 2..4096 */
+    double lambda;           /* L2 term in gain and leaf weight, >= 0 */
+    double gamma;            /* minimum gain of a split */
+    double min_child_weight; /* minimum hessian mass of a child */
+    double eta;              /* learning rate used by gbt_predict callers */
+    int32_t objective;       /* GBT_OBJ_* */
+    float base_margin;
+} gbt_params;
+
+/* One split candidate (the best of a node), Alg. 1 "EvaluateSplit". */
+typedef struct gbt_split {
+    int32_t feature;      /* -1: no valid candidate */
+    int32_t bin;          /* rows with symbol <= bin go left */
+    int32_t default_left; /* 1: rows with the missing symbol go left */
+    int32_t valid;
+    double gain;          /* GL^2/(HL+l) + GR^2/(HR+l) - G^2/(H+l) */
+    double GL, HL, GR, HR;
+    int64_t GLq, HLq;     /* left sums in fixed point (exact) */
+} gbt_split;
+
+/* A tree as caller-allocated host arrays of `capacity` >= 2^(max_depth+1)-1
+ * entries each.  Node 0 is the root; children are numbered in creation order,
+ * level by level, left to right. */
+typedef struct gbt_tree {
+    int32_t capacity;
+    int32_t n_nodes;       /* out */
+    int32_t *feature;      /* -1 = leaf */
+    int32_t *bin;
+    int32_t *default_left;
+    int32_t *left, *right; /* child ids, -1 for a leaf */
+    float *threshold;      /* raw-value form of the split: left iff x < threshold
+                              (= cuts[feature][bin]; +inf when bin is the last bin) */
+    double *weight;        /* -G/(H+lambda) of every node */
+    double *gain;          /* gain of the node's split, 0 for a leaf */
+    double *sumG, *sumH;
+    int64_t *n_rows;
+} gbt_tree;
+
+/* ---- context ----------------------------------------------------------- */
+
+/* Creates a context on HIP device `device`; `stream` is a hipStream_t (NULL =
+ * the default stream).  Loads nothing lazily: a missing or wrong-architecture
+ * GPU makes this call fail with GBT_EHIP. */
+GBT_API int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream);
+GBT_API int32_t gbt_destroy(gbt_ctx *ctx);
+/* Text of the last error of this context ("" if none).  [host], owned by ctx. */
+GBT_API const char *gbt_last_error(const gbt_ctx *ctx);
+GBT_API const char *gbt_version(void);
+
+/* ---- Sec. 2.1 feature quantile generation ------------------------------ */
+
+/* Bytes of workspace gbt_quantise needs. n_values = n*F for dense input, the
+ * number of stored values for CSR. */
+GBT_API size_t gbt_quantise_workspace_bytes(int64_t n, int32_t F, int64_t n_values, int32_t max_bins);
+
+/*
+ * Per-feature quantile cuts and binning.  Input is EITHER dense row-major
+ * X[n][F] [dev] with NaN = missing (indptr = indices = values = NULL) OR CSR
+ * (X = NULL; indptr int64[n+1], indices int32[nnz] column ids, values
+ * float[nnz], all [dev]; absent entries are missing).
+ *   cuts_out  [dev] float[F][max_bins-1], strictly increasing, +inf padded.
+ *             With m present values v[0..m) sorted and d distinct ones:
+ *             d <= max_bins: every distinct value but the smallest is a cut;
+ *             else the distinct values among v[floor(k*m/max_bins)], k=1..B-1,
+ *             without any equal to v[0].  Cuts are data values.
+ *   nb_out    [dev] int32[F]   bins per feature = cuts + 1 (1 if nothing present)
+ *   sym_out   [dev] uint16[n][F]  sym = #{cuts <= x}; missing -> missing_sym
+ *   max_value_out, missing_sym_out  [host] largest symbol written; max_f nb[f]
+ * Synchronises the stream.
+ */
+GBT_API int32_t gbt_quantise(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
+                     const float *values, int64_t n, int32_t F, int32_t max_bins, float *cuts_out,
+                     int32_t *nb_out, uint16_t *sym_out, int32_t *max_value_out,
+                     int32_t *missing_sym_out, void *workspace, size_t workspace_bytes);
+
+/* ---- Sec. 2.2 data compression ----------------------------------------- */
+
+/* Bits per element for a largest symbol max_value: its bit length, at least 1. */
+GBT_API int32_t gbt_bits(uint32_t max_value);
+/* uint32 words of the packed matrix, including the trailing zero word. */
+GBT_API int64_t gbt_packed_words(int64_t n, int32_t F, int32_t bits);
+/* Packs sym[n][F] [dev] into packed_out [dev] (gbt_packed_words words) at
+ * bits = gbt_bits(max_value), returned in *bits_out [host].  Asynchronous. */
+GBT_API int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, uint32_t max_value,
+                     uint32_t *packed_out, int32_t *bits_out);
+
+/* ---- Sec. 2.5 gradient evaluation (Eq. 1, Eq. 2) ------------------------ */
+
+/* gpair_out[i] = (g, h) of margin[i], label[i]: logistic g = s - y, h = s(1-s)
+ * with s = sigmoid(margin); squared error g = margin - y, h = 1.  All [dev],
+ * n entries.  Asynchronous. */
+GBT_API int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *margin, const float *label,
+                      int64_t n, float *gpair_out);
+
+/* ---- Alg. 1 BuildPartialHistograms ------------------------------------- */
+
+/* Rounds gpair[n] [dev] to fixed point: gq_out [dev] int32[n][2] =
+ * (rint(g*scale[0]), rint(h*scale[1])), scale_out [host] double[2] the two
+ * powers of two (chosen from max|g|, max|h| over the n rows).
+ * workspace [dev] >= 4096 bytes.  Synchronises the stream. */
+GBT_API int32_t gbt_gpair_fixed(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq_out,
+                        double *scale_out, void *workspace, size_t workspace_bytes);
+
+/* Exact sums of gq over the node's rows -> sums_out [host] int64[2].
+ * row_idx NULL = rows 0..n_rows-1.  workspace [dev] >= 4096 bytes.  Synchronises. */
+GBT_API int32_t gbt_sum_gpair(gbt_ctx *ctx, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,
+                      int64_t *sums_out, void *workspace, size_t workspace_bytes);
+
+/*
+ * hist_out[f][b] = (sum gq_g, sum gq_h) over the node's rows r with
+ * sym(r,f) = b; the missing symbol is not accumulated (Sec. 2.1: tree
+ * construction as gradient summation into histograms).
+ *   packed, bits, n, F : the packed matrix [dev]
+ *   B                  : bin stride (max_bins); every non-missing symbol < B
+ *   row_idx [dev]      : the node's rows (uint32 ids < n), NULL = all n rows
+ *   n_node_rows        : length of row_idx (ignored when NULL)
+ *   gq [dev]           : int32[n][2] from gbt_gpair_fixed
+ *   hist_out [dev]     : int64[F][B][2], overwritten
+ * Asynchronous.
+ */
+GBT_API int32_t gbt_build_hist(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                       int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_node_rows,
+                       const int32_t *gq, int64_t *hist_out);
+
+/* out = parent - child, elementwise over `count` int64 values [dev] (the
+ * sibling-subtraction trick: the larger child's histogram).  Asynchronous. */
+GBT_API int32_t gbt_hist_subtract(gbt_ctx *ctx, const int64_t *parent, const int64_t *child, int64_t *out,
+                          int64_t count);
+
+/* out[f][b][c] = hist[f][b][c] / scale[c] as fp64 [dev].  Asynchronous. */
+GBT_API int32_t gbt_hist_export_f64(gbt_ctx *ctx, const int64_t *hist, int32_t F, int32_t B,
+                            const double *scale /* [host] double[2] */, double *out);
+
+/* ---- Alg. 1 EvaluateSplit ---------------------------------------------- */
+
+/*
+ * Best split of one node from its histogram: an inclusive prefix scan over the
+ * bins of every feature gives (GL, HL) of each candidate (Sec. 2.3), gain in
+ * fp64.  The node's missing mass for feature f is (Gq, Hq) - sum_b hist[f][b];
+ * it is tried on the right and, when non-zero, on the left.  Candidates are
+ * ordered (feature, bin, right-before-left); a later one wins only with a
+ * strictly larger gain.  A candidate needs HL, HR >= min_child_weight.
+ *   hist [dev], nb [dev] int32[F], Gq/Hq node totals (gbt_sum_gpair),
+ *   scale [host] double[2], split_out [host].  workspace [dev] >= 4096 bytes.
+ * Synchronises the stream.
+ */
+GBT_API int32_t gbt_eval_split(gbt_ctx *ctx, const int64_t *hist, const int32_t *nb, int32_t F, int32_t B,
+                       int64_t Gq, int64_t Hq, const double *scale, const gbt_params *params,
+                       gbt_split *split_out, void *workspace, size_t workspace_bytes);
+
+/* ---- Alg. 1 RepartitionInstances --------------------------------------- */
+
+GBT_API size_t gbt_partition_workspace_bytes(int64_t n_rows);
+
+/*
+ * Stable partition of row_idx[begin, end) [dev, in place]: first the rows with
+ * sym(r, feature) <= bin (or the missing symbol when default_left), then the
+ * others, both in their previous order.  *n_left_out [host] = size of the first
+ * part.  Synchronises the stream.
+ */
+GBT_API int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                      uint32_t *row_idx, int64_t begin, int64_t end, int32_t feature, int32_t bin,
+                      int32_t default_left, int32_t missing_sym, void *workspace,
+                      size_t workspace_bytes, int64_t *n_left_out);
+
+/* ---- Alg. 1 as a whole -------------------------------------------------- */
+
+GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t max_bins, int32_t max_depth);
+
+/*
+ * Grows one tree depth-wise (Alg. 1 with the "closest to the root first"
+ * policy): root histogram; per level evaluate the open nodes, partition the
+ * rows of those that split, build the histogram of each split's smaller child
+ * (fewer rows, tie -> left) and get the larger one by subtraction.  A node is
+ * split iff it has a valid candidate with gain > max(gamma, GBT_GAIN_FLOOR) and
+ * depth < max_depth.  Leaf weight = -G/(H+lambda).
+ *   packed, bits, n, F, missing_sym : packed matrix [dev]
+ *   nb [dev] int32[F]; cuts [dev] float[F][max_bins-1] (for thresholds)
+ *   gpair [dev] float2[n]
+ *   tree_out [host]              caller-allocated arrays, see gbt_tree
+ *   row_idx_out [dev] uint32[n]  final row order: each node's rows are one
+ *                                ascending run, left child's run first
+ *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL)
+ * Synchronises the stream.
+ */
+GBT_API int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                      int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
+                      const gbt_params *params, gbt_tree *tree_out, uint32_t *row_idx_out,
+                      int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
+
+/* ---- Sec. 2.4 prediction ------------------------------------------------ */
+
+GBT_API size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_trees);
+
+/*
+ * margin[r] += eta * weight[leaf_t(r)] for t = 0..n_trees-1 in order, one row
+ * per thread walking each tree from its root.  Rows come EITHER as the packed
+ * symbols (packed != NULL: left iff sym <= bin, missing symbol -> default
+ * child) OR as raw floats X[n][F] [dev] (packed == NULL: left iff
+ * x < threshold, NaN -> default child); both give the same leaves on the
+ * training matrix.  trees [host].  Synchronises the stream (the trees are
+ * staged through the workspace).
+ */
+GBT_API int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
+                    int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F,
+                    double eta, float *margin_inout, void *workspace, size_t workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GBT_H */

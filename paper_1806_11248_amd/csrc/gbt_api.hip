@@ -1,0 +1,789 @@
+// The C ABI of libgbt (see include/gbt.h) and the host side of Alg. 1.
+#include "gbt_internal.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+// ---------------------------------------------------------------- plumbing --
+int32_t gbt_fail(gbt_ctx *ctx, int32_t code, const char *fmt, ...) {
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof ctx->err, fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+namespace {
+
+constexpr size_t kUploadBytes = GBT_STAGING_BYTES / 2;   // first half of the pinned staging
+constexpr size_t kReadbackOff = GBT_STAGING_BYTES / 2;   // second half
+constexpr int kMaxDepth = 16;
+
+inline char *up(gbt_ctx *c) { return c->pinned; }
+inline char *rb(gbt_ctx *c) { return c->pinned + kReadbackOff; }
+
+int32_t check_matrix(gbt_ctx *ctx, const void *packed, int32_t bits, int64_t n, int32_t F) {
+    GBT_REQUIRE(ctx, packed != nullptr, GBT_EINVAL, "packed is NULL");
+    GBT_REQUIRE(ctx, bits >= 1, GBT_EINVAL, "bits = %d < 1", bits);
+    GBT_REQUIRE(ctx, bits <= GBT_MAX_BITS, GBT_EUNSUPPORTED, "bits = %d > %d", bits, GBT_MAX_BITS);
+    GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32), GBT_EINVAL, "n = %lld out of range", (long long)n);
+    GBT_REQUIRE(ctx, F >= 1 && F <= (1 << 20), GBT_EINVAL, "F = %d out of range", F);
+    return GBT_OK;
+}
+
+int32_t check_bins(gbt_ctx *ctx, int32_t F, int32_t B) {
+    GBT_REQUIRE(ctx, B >= 2 && B <= 4096, GBT_EINVAL, "max_bins = %d outside 2..4096", B);
+    GBT_REQUIRE(ctx, (int64_t)F * B < ((int64_t)1 << 31), GBT_EINVAL, "F*max_bins too large");
+    return GBT_OK;
+}
+
+// Power-of-two scale s with |x|*s <= 2^30 for every |x| <= vmax.
+double fixed_scale(float vmax) {
+    if (!(vmax > 0.0f)) return 1.0;
+    int e;
+    frexp((double)vmax, &e);   // vmax = m * 2^e, m in [0.5, 1)
+    return ldexp(1.0, 30 - e);
+}
+
+// Uniform job split of a dense or listed row range for the histogram kernel.
+struct HistPlan {
+    int ft_max, n_ftiles, ft;
+};
+bool plan_tiles(const gbt_ctx *ctx, int F, int B, HistPlan *p) {
+    p->ft_max = gbt_hist_feature_tile(ctx, F, B);
+    if (p->ft_max < 1) return false;
+    p->n_ftiles = (F + p->ft_max - 1) / p->ft_max;
+    p->ft = (F + p->n_ftiles - 1) / p->n_ftiles;
+    return true;
+}
+
+// Appends the jobs of one node; rows_per_job > 0.
+void add_hist_jobs(std::vector<HistJob> &jobs, uint64_t hist_off, uint32_t begin, uint32_t len, int F,
+                   const HistPlan &pl, uint32_t rows_per_job) {
+    for (uint32_t r0 = 0; r0 < len; r0 += rows_per_job) {
+        uint32_t nr = std::min(rows_per_job, len - r0);
+        for (int t = 0; t < pl.n_ftiles; ++t) {
+            HistJob j;
+            j.hist_off = hist_off;
+            j.row_begin = begin + r0;
+            j.n_rows = nr;
+            j.f0 = (uint32_t)(t * pl.ft);
+            j.ft = (uint32_t)std::min(pl.ft, F - t * pl.ft);
+            j.pad0 = j.pad1 = 0;
+            if (j.ft > 0) jobs.push_back(j);
+        }
+    }
+}
+
+uint32_t pick_rows_per_job(const gbt_ctx *ctx, int64_t total_rows) {
+    int64_t target_jobs = (int64_t)ctx->num_cu * 4;
+    int64_t rpj = (total_rows + target_jobs - 1) / target_jobs;
+    if (rpj < 4096) rpj = 4096;
+    if (rpj > (1 << 30)) rpj = 1 << 30;
+    return (uint32_t)rpj;
+}
+
+// The first half of the pinned staging is a ring of upload slots: a slot may be
+// overwritten only after the copy (or kernel) that reads it has finished, which
+// a stream synchronisation guarantees; wrapping therefore synchronises first.
+int32_t sync(gbt_ctx *ctx) {
+    GBT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->up_off = 0;
+    return GBT_OK;
+}
+
+int32_t stage(gbt_ctx *ctx, const void *host, size_t bytes, char **slot) {
+    GBT_REQUIRE(ctx, bytes <= kUploadBytes, GBT_EUNSUPPORTED, "job table of %zu bytes exceeds staging", bytes);
+    const size_t need = gbt_align(bytes ? bytes : 1);
+    if (ctx->up_off + need > kUploadBytes) {
+        int32_t st = sync(ctx);
+        if (st != GBT_OK) return st;
+    }
+    *slot = up(ctx) + ctx->up_off;
+    memcpy(*slot, host, bytes);
+    ctx->up_off += need;
+    return GBT_OK;
+}
+
+#define GBT_SYNC(ctx)                      \
+    do {                                   \
+        int32_t st_ = sync(ctx);           \
+        if (st_ != GBT_OK) return st_;     \
+    } while (0)
+
+// Uploads `bytes` of job descriptors through the pinned staging into `dev`.
+int32_t upload(gbt_ctx *ctx, const void *host, size_t bytes, void *dev) {
+    char *slot;
+    int32_t st = stage(ctx, host, bytes, &slot);
+    if (st != GBT_OK) return st;
+    GBT_HIP(ctx, hipMemcpyAsync(dev, slot, bytes, hipMemcpyHostToDevice, ctx->stream));
+    return GBT_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ context --
+extern "C" const char *gbt_version(void) { return "libgbt 0.1 (gfx950)"; }
+
+extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
+    if (!ctx_out) return GBT_EINVAL;
+    *ctx_out = nullptr;
+    gbt_ctx *c = new (std::nothrow) gbt_ctx();
+    if (!c) return GBT_ENOMEM;
+    memset(c, 0, sizeof *c);
+    c->device = device;
+    c->stream = (hipStream_t)stream;
+    hipError_t e = hipSetDevice(device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+    if (e == hipSuccess && strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+        fprintf(stderr, "libgbt: device %d is %s, this library is built for gfx950 only\n", device,
+                prop.gcnArchName);
+        delete c;
+        return GBT_EHIP;
+    }
+    if (e == hipSuccess) {
+        c->num_cu = prop.multiProcessorCount;
+        size_t lds = prop.sharedMemPerBlock;
+        int optin = 0;
+        if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess &&
+            (size_t)optin > lds)
+            lds = (size_t)optin;
+        if (lds > 128u * 1024u) lds = 128u * 1024u;   // leave room for a second resident workgroup's statics
+        c->lds_per_block = lds;
+        e = hipHostMalloc((void **)&c->pinned, GBT_STAGING_BYTES, hipHostMallocDefault);
+        c->pinned_bytes = GBT_STAGING_BYTES;
+    }
+    if (e != hipSuccess) {
+        fprintf(stderr, "libgbt: gbt_create failed: %s\n", hipGetErrorString(e));
+        (void)hipGetLastError();
+        delete c;
+        return GBT_EHIP;
+    }
+    *ctx_out = c;
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_destroy(gbt_ctx *ctx) {
+    if (!ctx) return GBT_EINVAL;
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    delete ctx;
+    return GBT_OK;
+}
+
+extern "C" const char *gbt_last_error(const gbt_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+// ------------------------------------------------------------- compression --
+extern "C" int32_t gbt_bits(uint32_t max_value) {
+    int32_t b = 1;
+    while (b < 32 && (max_value >> b) != 0) ++b;
+    return b;
+}
+
+extern "C" int64_t gbt_packed_words(int64_t n, int32_t F, int32_t bits) {
+    if (n < 0 || F < 0 || bits < 1) return -1;
+    return (n * (int64_t)F * bits + 31) / 32 + 1;
+}
+
+extern "C" int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, uint32_t max_value,
+                                uint32_t *packed_out, int32_t *bits_out) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, sym && packed_out && bits_out, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, n >= 0 && F >= 1, GBT_EINVAL, "bad shape");
+    int32_t bits = gbt_bits(max_value);
+    GBT_REQUIRE(ctx, bits <= GBT_MAX_BITS, GBT_EUNSUPPORTED, "max_value %u needs %d bits", max_value, bits);
+    GBT_HIP(ctx, gbt_launch_compress(ctx->stream, sym, n * (int64_t)F, bits, packed_out,
+                                     gbt_packed_words(n, F, bits)));
+    *bits_out = bits;
+    return GBT_OK;
+}
+
+// --------------------------------------------------------------- gradients --
+extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *margin, const float *label,
+                                 int64_t n, float *gpair_out) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, margin && label && gpair_out, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, n >= 0, GBT_EINVAL, "n < 0");
+    GBT_REQUIRE(ctx, objective == GBT_OBJ_SQUARED || objective == GBT_OBJ_LOGISTIC, GBT_EINVAL,
+                "unknown objective %d", objective);
+    GBT_HIP(ctx, gbt_launch_gradients(ctx->stream, objective, margin, label, n, gpair_out));
+    return GBT_OK;
+}
+
+// ------------------------------------------------------- fixed-point gpair --
+static int32_t gpair_fixed_impl(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq, double *scale,
+                                void *ws) {
+    GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 8, hipMemcpyDeviceToHost, ctx->stream));
+    GBT_SYNC(ctx);
+    uint32_t bits2[2];
+    memcpy(bits2, rb(ctx), 8);
+    GBT_REQUIRE(ctx, bits2[0] < 0x7f800000u && bits2[1] < 0x7f800000u, GBT_EINVAL,
+                "gradient pairs contain a non-finite value");
+    float mg, mh;
+    memcpy(&mg, &bits2[0], 4);
+    memcpy(&mh, &bits2[1], 4);
+    scale[0] = fixed_scale(mg);
+    scale[1] = fixed_scale(mh);
+    GBT_HIP(ctx, gbt_launch_to_fixed(ctx->stream, gpair, n, scale[0], scale[1], gq));
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_gpair_fixed(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq_out,
+                                   double *scale_out, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, gpair && gq_out && scale_out && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, n >= 0, GBT_EINVAL, "n < 0");
+    GBT_REQUIRE(ctx, workspace_bytes >= 4096, GBT_ENOMEM, "workspace < 4096 bytes");
+    int32_t st = gpair_fixed_impl(ctx, gpair, n, gq_out, scale_out, workspace);
+    if (st != GBT_OK) return st;
+    GBT_SYNC(ctx);
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_sum_gpair(gbt_ctx *ctx, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,
+                                 int64_t *sums_out, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, gq && sums_out && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, n_rows >= 0, GBT_EINVAL, "n_rows < 0");
+    GBT_REQUIRE(ctx, workspace_bytes >= 4096, GBT_ENOMEM, "workspace < 4096 bytes");
+    GBT_HIP(ctx, gbt_launch_sum_gq(ctx->stream, gq, row_idx, n_rows, (int64_t *)workspace));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), workspace, 16, hipMemcpyDeviceToHost, ctx->stream));
+    GBT_SYNC(ctx);
+    memcpy(sums_out, rb(ctx), 16);
+    return GBT_OK;
+}
+
+// --------------------------------------------------------------- histogram --
+// Enqueues the histogram of one row range split uniformly into jobs that the
+// kernel derives from its block index (no job table).
+static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                            int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
+                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs /* may be NULL */);
+
+extern "C" int32_t gbt_build_hist(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                  int32_t B, int32_t missing_sym, const uint32_t *row_idx,
+                                  int64_t n_node_rows, const int32_t *gq, int64_t *hist_out) {
+    if (!ctx) return GBT_EINVAL;
+    int32_t st = check_matrix(ctx, packed, bits, n, F);
+    if (st != GBT_OK) return st;
+    st = check_bins(ctx, F, B);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, gq && hist_out, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, missing_sym >= 0, GBT_EINVAL, "missing_sym < 0");
+    int64_t rows = row_idx ? n_node_rows : n;
+    GBT_REQUIRE(ctx, rows >= 0 && rows <= n, GBT_EINVAL, "n_node_rows = %lld out of range", (long long)rows);
+    return hist_uniform(ctx, packed, bits, n, F, B, missing_sym, row_idx, rows, gq, hist_out, nullptr);
+}
+
+extern "C" int32_t gbt_hist_subtract(gbt_ctx *ctx, const int64_t *parent, const int64_t *child, int64_t *out,
+                                     int64_t count) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, parent && child && out, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, count >= 0, GBT_EINVAL, "count < 0");
+    GBT_HIP(ctx, gbt_launch_subtract_one(ctx->stream, parent, child, out, count));
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_hist_export_f64(gbt_ctx *ctx, const int64_t *hist, int32_t F, int32_t B,
+                                       const double *scale, double *out) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, hist && scale && out, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, F >= 1 && B >= 1, GBT_EINVAL, "bad shape");
+    GBT_REQUIRE(ctx, scale[0] > 0 && scale[1] > 0, GBT_EINVAL, "scale must be positive");
+    GBT_HIP(ctx, gbt_launch_export(ctx->stream, hist, (int64_t)F * B * 2, 1.0 / scale[0], 1.0 / scale[1], out));
+    return GBT_OK;
+}
+
+// ------------------------------------------------------------------- split --
+extern "C" int32_t gbt_eval_split(gbt_ctx *ctx, const int64_t *hist, const int32_t *nb, int32_t F, int32_t B,
+                                  int64_t Gq, int64_t Hq, const double *scale, const gbt_params *params,
+                                  gbt_split *split_out, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, hist && nb && scale && params && split_out && workspace, GBT_EINVAL, "NULL argument");
+    int32_t st = check_bins(ctx, F, B);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, F >= 1, GBT_EINVAL, "F < 1");
+    GBT_REQUIRE(ctx, workspace_bytes >= 4096, GBT_ENOMEM, "workspace < 4096 bytes");
+    GBT_REQUIRE(ctx, scale[0] > 0 && scale[1] > 0, GBT_EINVAL, "scale must be positive");
+    EvalNode nd;
+    nd.hist_off = 0;
+    nd.Gq = Gq;
+    nd.Hq = Hq;
+    char *ws = (char *)workspace;
+    st = upload(ctx, &nd, sizeof nd, ws);
+    if (st != GBT_OK) return st;
+    gbt_split *dsplit = (gbt_split *)(ws + 256);
+    GBT_HIP(ctx, gbt_launch_eval(ctx->stream, hist, (const EvalNode *)ws, 1, nb, F, B, 1.0 / scale[0],
+                                 1.0 / scale[1], params->lambda, params->min_child_weight, dsplit));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), dsplit, sizeof(gbt_split), hipMemcpyDeviceToHost, ctx->stream));
+    GBT_SYNC(ctx);
+    memcpy(split_out, rb(ctx), sizeof(gbt_split));
+    return GBT_OK;
+}
+
+// --------------------------------------------------------------- partition --
+namespace {
+struct PartLayout {
+    size_t dst, masks, tile_left, jobs, n_left, total;
+};
+PartLayout part_layout(int64_t n_rows) {
+    PartLayout L;
+    int64_t tiles = (n_rows + GBT_PART_TILE - 1) / GBT_PART_TILE + 1;
+    size_t o = 0;
+    L.dst = o;       o += gbt_align((size_t)n_rows * 4);
+    L.masks = o;     o += gbt_align((size_t)tiles * (GBT_PART_TILE / 64) * 8);
+    L.tile_left = o; o += gbt_align((size_t)tiles * 4);
+    L.jobs = o;      o += gbt_align(sizeof(PartJob));
+    L.n_left = o;    o += gbt_align(4);
+    L.total = o;
+    return L;
+}
+}  // namespace
+
+extern "C" size_t gbt_partition_workspace_bytes(int64_t n_rows) {
+    return n_rows < 0 ? 0 : part_layout(n_rows).total;
+}
+
+extern "C" int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                 uint32_t *row_idx, int64_t begin, int64_t end, int32_t feature, int32_t bin,
+                                 int32_t default_left, int32_t missing_sym, void *workspace,
+                                 size_t workspace_bytes, int64_t *n_left_out) {
+    if (!ctx) return GBT_EINVAL;
+    int32_t st = check_matrix(ctx, packed, bits, n, F);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, row_idx && workspace && n_left_out, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, 0 <= begin && begin <= end && end - begin <= n, GBT_EINVAL, "bad segment [%lld, %lld)",
+                (long long)begin, (long long)end);
+    GBT_REQUIRE(ctx, feature >= 0 && feature < F, GBT_EINVAL, "feature %d outside [0, %d)", feature, F);
+    GBT_REQUIRE(ctx, bin >= 0 && missing_sym >= 0, GBT_EINVAL, "negative bin or missing symbol");
+    int64_t len = end - begin;
+    PartLayout L = part_layout(len);
+    GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
+    if (len == 0) {
+        *n_left_out = 0;
+        return GBT_OK;
+    }
+    char *ws = (char *)workspace;
+    PartJob job;
+    job.seg_begin = 0;
+    job.seg_len = (uint32_t)len;
+    job.feature = (uint32_t)feature;
+    job.bin = (uint32_t)bin;
+    job.default_left = default_left ? 1u : 0u;
+    job.tile_begin = 0;
+    job.n_tiles = (uint32_t)((len + GBT_PART_TILE - 1) / GBT_PART_TILE);
+    job.pad = 0;
+    st = upload(ctx, &job, sizeof job, ws + L.jobs);
+    if (st != GBT_OK) return st;
+    uint32_t *seg = row_idx + begin;
+    GBT_HIP(ctx, gbt_launch_partition(ctx->stream, packed, bits, n, F, (uint32_t)missing_sym, seg,
+                                      (uint32_t *)(ws + L.dst), (const PartJob *)(ws + L.jobs), 1,
+                                      (int)job.n_tiles, (uint64_t *)(ws + L.masks),
+                                      (uint32_t *)(ws + L.tile_left), (uint32_t *)(ws + L.n_left)));
+    GBT_HIP(ctx, hipMemcpyAsync(seg, ws + L.dst, (size_t)len * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, 4, hipMemcpyDeviceToHost, ctx->stream));
+    GBT_SYNC(ctx);
+    uint32_t nl;
+    memcpy(&nl, rb(ctx), 4);
+    *n_left_out = nl;
+    return GBT_OK;
+}
+
+// ------------------------------------------------------------ histogram job --
+static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                            int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
+                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs) {
+    HistPlan pl;
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, &pl), GBT_EUNSUPPORTED,
+                "max_bins = %d: one feature's bins (%d bytes) exceed the LDS budget", B, B * 16);
+    GBT_HIP(ctx, gbt_launch_fill_u64(ctx->stream, (uint64_t *)hist_out, 0, (int64_t)F * B * 2));
+    if (n_rows == 0) return GBT_OK;
+    std::vector<HistJob> jobs;
+    add_hist_jobs(jobs, 0, 0, (uint32_t)n_rows, F, pl, pick_rows_per_job(ctx, n_rows));
+    // Without a caller workspace the job table is read straight from the pinned
+    // staging, which the device can address; it is small (a few KB).
+    size_t bytes = jobs.size() * sizeof(HistJob);
+    if (dev_jobs) {
+        int32_t st = upload(ctx, jobs.data(), bytes, dev_jobs);
+        if (st != GBT_OK) return st;
+    } else {
+        char *slot;
+        int32_t st = stage(ctx, jobs.data(), bytes, &slot);
+        if (st != GBT_OK) return st;
+        dev_jobs = (HistJob *)slot;
+    }
+    GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, n, F, B, (uint32_t)missing_sym, row_idx, gq, hist_out,
+                                 dev_jobs, (int)jobs.size(), pl.ft));
+    return GBT_OK;
+}
+
+// -------------------------------------------------------------------- grow --
+namespace {
+
+struct GrowLayout {
+    size_t gq, buf0, buf1, masks, tile_left, n_left, pool, eval_nodes, splits, jobs, scratch, total;
+    int64_t hist_nodes, level_nodes, tiles;
+};
+
+GrowLayout grow_layout(int64_t n, int F, int B, int max_depth) {
+    GrowLayout L;
+    L.hist_nodes = max_depth == 0 ? 1 : (((int64_t)1 << max_depth) - 1);
+    L.level_nodes = (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0);   // most nodes evaluated in one level
+    L.tiles = n / GBT_PART_TILE + L.level_nodes + 1;
+    size_t o = 0;
+    L.gq = o;         o += gbt_align((size_t)n * 8);
+    L.buf0 = o;       o += gbt_align((size_t)n * 4);
+    L.buf1 = o;       o += gbt_align((size_t)n * 4);
+    L.masks = o;      o += gbt_align((size_t)L.tiles * (GBT_PART_TILE / 64) * 8);
+    L.tile_left = o;  o += gbt_align((size_t)L.tiles * 4);
+    L.n_left = o;     o += gbt_align((size_t)L.level_nodes * 4);
+    L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
+    L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * sizeof(EvalNode));
+    L.splits = o;     o += gbt_align((size_t)L.level_nodes * sizeof(gbt_split));
+    L.jobs = o;       o += gbt_align(kUploadBytes);
+    L.scratch = o;    o += 4096;
+    L.total = o;
+    return L;
+}
+
+struct HNode {
+    int32_t id;
+    uint32_t begin, len;
+    int64_t Gq, Hq;
+};
+
+}  // namespace
+
+extern "C" size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t max_bins, int32_t max_depth) {
+    if (n < 0 || F < 1 || max_bins < 2 || max_depth < 0 || max_depth > kMaxDepth) return 0;
+    return grow_layout(n, F, max_bins, max_depth).total;
+}
+
+extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                 int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
+                                 const gbt_params *params, gbt_tree *tree, uint32_t *row_idx_out,
+                                 int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    int32_t st = check_matrix(ctx, packed, bits, n, F);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, nb && cuts && gpair && params && tree && row_idx_out && workspace, GBT_EINVAL, "NULL argument");
+    const int B = params->max_bins, max_depth = params->max_depth;
+    st = check_bins(ctx, F, B);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, max_depth >= 0, GBT_EINVAL, "max_depth < 0");
+    GBT_REQUIRE(ctx, max_depth <= kMaxDepth, GBT_EUNSUPPORTED, "max_depth %d > %d", max_depth, kMaxDepth);
+    GBT_REQUIRE(ctx, n >= 1, GBT_EINVAL, "n < 1");
+    GBT_REQUIRE(ctx, missing_sym >= 0, GBT_EINVAL, "missing_sym < 0");
+    GBT_REQUIRE(ctx, params->lambda >= 0.0, GBT_EINVAL, "lambda < 0");
+    const int64_t cap = ((int64_t)1 << (max_depth + 1)) - 1;
+    GBT_REQUIRE(ctx, tree->capacity >= cap, GBT_EINVAL, "tree capacity %d < %lld", tree->capacity, (long long)cap);
+    GBT_REQUIRE(ctx, tree->feature && tree->bin && tree->default_left && tree->left && tree->right &&
+                         tree->threshold && tree->weight && tree->gain && tree->sumG && tree->sumH && tree->n_rows,
+                GBT_EINVAL, "tree arrays must be allocated");
+    const GrowLayout L = grow_layout(n, F, B, max_depth);
+    GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
+    HistPlan pl;
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, &pl), GBT_EUNSUPPORTED,
+                "max_bins = %d: one feature's bins exceed the LDS budget", B);
+
+    char *ws = (char *)workspace;
+    int32_t *gq = (int32_t *)(ws + L.gq);
+    uint32_t *buf[2] = {(uint32_t *)(ws + L.buf0), (uint32_t *)(ws + L.buf1)};
+    int64_t *pool = (int64_t *)(ws + L.pool);
+    const int64_t hist_len = (int64_t)F * B * 2;
+    hipStream_t s = ctx->stream;
+
+    // thresholds come from the cut table
+    std::vector<float> hcuts((size_t)F * (B - 1));
+    GBT_HIP(ctx, hipMemcpyAsync(hcuts.data(), cuts, hcuts.size() * sizeof(float), hipMemcpyDeviceToHost, s));
+
+    double scale[2];
+    st = gpair_fixed_impl(ctx, gpair, n, gq, scale, ws + L.scratch);
+    if (st != GBT_OK) return st;
+    const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
+    const double lambda = params->lambda;
+    const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
+
+    GBT_HIP(ctx, gbt_launch_sum_gq(s, gq, nullptr, n, (int64_t *)(ws + L.scratch)));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.scratch, 16, hipMemcpyDeviceToHost, s));
+    GBT_HIP(ctx, gbt_launch_iota_u32(s, buf[0], n));
+    if (max_depth > 0) {
+        st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
+                          (HistJob *)(ws + L.jobs));
+        if (st != GBT_OK) return st;
+    }
+    GBT_SYNC(ctx);
+    int64_t root_sums[2];
+    memcpy(root_sums, rb(ctx), 16);
+
+    auto set_node = [&](const HNode &nd) {
+        const double G = (double)nd.Gq * inv_sg, H = (double)nd.Hq * inv_sh;
+        tree->feature[nd.id] = -1;
+        tree->bin[nd.id] = 0;
+        tree->default_left[nd.id] = 0;
+        tree->left[nd.id] = tree->right[nd.id] = -1;
+        tree->threshold[nd.id] = INFINITY;
+        tree->gain[nd.id] = 0.0;
+        tree->sumG[nd.id] = G;
+        tree->sumH[nd.id] = H;
+        tree->weight[nd.id] = -G / (H + lambda);
+        tree->n_rows[nd.id] = nd.len;
+    };
+
+    std::vector<HNode> level, next;
+    std::vector<LeafSeg> leaves;
+    HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1]};
+    set_node(root);
+    level.push_back(root);
+    int32_t n_nodes = 1;
+    int cur = 0;   // buffer holding the current level's segments
+
+    std::vector<EvalNode> enodes;
+    std::vector<PartJob> pjobs;
+    std::vector<HistJob> hjobs;
+    std::vector<SubJob> sjobs;
+    std::vector<gbt_split> splits;
+    std::vector<int> split_of;   // index into `level` of every splitting node
+
+    for (int depth = 0; depth < max_depth && !level.empty(); ++depth) {
+        // ---- EvaluateSplit for every open node of the level
+        enodes.resize(level.size());
+        for (size_t i = 0; i < level.size(); ++i)
+            enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
+        st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
+        if (st != GBT_OK) return st;
+        GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)level.size(), nb, F, B,
+                                     inv_sg, inv_sh, lambda, params->min_child_weight,
+                                     (gbt_split *)(ws + L.splits)));
+        const size_t sbytes = level.size() * sizeof(gbt_split);
+        GBT_REQUIRE(ctx, sbytes <= GBT_STAGING_BYTES - kReadbackOff, GBT_EUNSUPPORTED, "level too wide");
+        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
+        GBT_SYNC(ctx);
+        splits.resize(level.size());
+        memcpy(splits.data(), rb(ctx), sbytes);
+
+        // ---- which nodes split; RepartitionInstances for those
+        pjobs.clear();
+        split_of.clear();
+        uint32_t tile_cursor = 0;
+        for (size_t i = 0; i < level.size(); ++i) {
+            const gbt_split &sp = splits[i];
+            const HNode &nd = level[i];
+            const bool ok = sp.valid && sp.gain > min_gain && sp.feature >= 0 && sp.feature < F &&
+                            sp.bin >= 0 && sp.bin < B && nd.len > 0;
+            if (!ok) {
+                leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)cur, nd.len});
+                continue;
+            }
+            PartJob j;
+            j.seg_begin = nd.begin;
+            j.seg_len = nd.len;
+            j.feature = (uint32_t)sp.feature;
+            j.bin = (uint32_t)sp.bin;
+            j.default_left = (uint32_t)sp.default_left;
+            j.tile_begin = tile_cursor;
+            j.n_tiles = (nd.len + GBT_PART_TILE - 1) / GBT_PART_TILE;
+            j.pad = 0;
+            tile_cursor += j.n_tiles;
+            pjobs.push_back(j);
+            split_of.push_back((int)i);
+        }
+        next.clear();
+        if (pjobs.empty()) {
+            level.clear();
+            break;
+        }
+        GBT_REQUIRE(ctx, (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
+        st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
+        if (st != GBT_OK) return st;
+        GBT_HIP(ctx, gbt_launch_partition(s, packed, bits, n, F, (uint32_t)missing_sym, buf[cur], buf[cur ^ 1],
+                                          (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
+                                          (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
+                                          (uint32_t *)(ws + L.n_left)));
+        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
+        GBT_SYNC(ctx);
+        const uint32_t *n_left = (const uint32_t *)rb(ctx);
+
+        // ---- children, in creation order
+        const bool children_need_hist = depth + 1 < max_depth;
+        hjobs.clear();
+        sjobs.clear();
+        int64_t built_rows = 0;
+        struct Built { uint64_t off; uint32_t begin, len; };
+        std::vector<Built> built;
+        const int32_t first_child = n_nodes;
+        for (size_t k = 0; k < pjobs.size(); ++k) {
+            const HNode &nd = level[split_of[k]];
+            const gbt_split &sp = splits[split_of[k]];
+            const uint32_t nl = n_left[k];
+            GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
+            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq};
+            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq};
+            n_nodes += 2;
+            tree->feature[nd.id] = sp.feature;
+            tree->bin[nd.id] = sp.bin;
+            tree->default_left[nd.id] = sp.default_left;
+            tree->left[nd.id] = lc.id;
+            tree->right[nd.id] = rc.id;
+            tree->gain[nd.id] = sp.gain;
+            tree->threshold[nd.id] = sp.bin < B - 1 ? hcuts[(size_t)sp.feature * (B - 1) + sp.bin] : INFINITY;
+            set_node(lc);
+            set_node(rc);
+            if (children_need_hist) {
+                const bool left_small = lc.len <= rc.len;
+                const HNode &sm = left_small ? lc : rc, &lg = left_small ? rc : lc;
+                built.push_back(Built{(uint64_t)sm.id * (uint64_t)hist_len, sm.begin, sm.len});
+                built_rows += sm.len;
+                sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)sm.id * (uint64_t)hist_len,
+                                       (uint64_t)lg.id * (uint64_t)hist_len});
+                next.push_back(lc);
+                next.push_back(rc);
+            } else {
+                leaves.push_back(LeafSeg{lc.begin, (uint32_t)lc.id, (uint32_t)(cur ^ 1), lc.len});
+                leaves.push_back(LeafSeg{rc.begin, (uint32_t)rc.id, (uint32_t)(cur ^ 1), rc.len});
+            }
+        }
+        cur ^= 1;
+        if (children_need_hist) {
+            // ---- BuildPartialHistograms for the smaller children, siblings by subtraction
+            const int32_t n_children = n_nodes - first_child;
+            GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
+                                             (int64_t)n_children * hist_len));
+            const uint32_t rpj = pick_rows_per_job(ctx, built_rows);
+            for (const Built &b : built) add_hist_jobs(hjobs, b.off, b.begin, b.len, F, pl, rpj);
+            const size_t per_launch = kUploadBytes / sizeof(HistJob);
+            for (size_t j0 = 0; j0 < hjobs.size(); j0 += per_launch) {
+                const size_t nj = std::min(per_launch, hjobs.size() - j0);
+                st = upload(ctx, hjobs.data() + j0, nj * sizeof(HistJob), ws + L.jobs);
+                if (st != GBT_OK) return st;
+                GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, n, F, B, (uint32_t)missing_sym, buf[cur], gq, pool,
+                                             (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
+            }
+            GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
+            st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
+            if (st != GBT_OK) return st;
+            GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
+        }
+        level.swap(next);
+    }
+    // nodes still open when the depth limit (or an empty level) ended the loop are leaves
+    for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)cur, nd.len});
+
+    std::sort(leaves.begin(), leaves.end(),
+              [](const LeafSeg &a, const LeafSeg &b) {   // an empty segment sorts before the one that starts at the same place
+                  return a.seg_begin != b.seg_begin ? a.seg_begin < b.seg_begin : (a.len != 0) < (b.len != 0);
+              });
+    st = upload(ctx, leaves.data(), leaves.size() * sizeof(LeafSeg), ws + L.jobs);
+    if (st != GBT_OK) return st;
+    GBT_HIP(ctx, gbt_launch_leaf_gather(s, buf[0], buf[1], (const LeafSeg *)(ws + L.jobs), (int)leaves.size(), n,
+                                        row_idx_out, leaf_of_row_out));
+    GBT_SYNC(ctx);
+    tree->n_nodes = n_nodes;
+    return GBT_OK;
+}
+
+// ----------------------------------------------------------------- predict --
+namespace {
+size_t tree_bytes(int32_t n_nodes) { return gbt_align((size_t)n_nodes * 4) * 6 + gbt_align((size_t)n_nodes * 8); }
+}
+
+extern "C" size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_trees) {
+    if (!trees || n_trees < 0) return 0;
+    size_t o = gbt_align((size_t)n_trees * sizeof(DevTree));
+    for (int t = 0; t < n_trees; ++t) o += tree_bytes(trees[t].n_nodes);
+    return o + 256;
+}
+
+extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
+                               int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
+                               float *margin, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, trees && margin && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, (packed != nullptr) != (X != nullptr), GBT_EINVAL, "give exactly one of packed and X");
+    GBT_REQUIRE(ctx, n >= 0 && F >= 1 && n_trees >= 0, GBT_EINVAL, "bad shape");
+    if (packed) {
+        int32_t st = check_matrix(ctx, packed, bits, n, F);
+        if (st != GBT_OK) return st;
+    } else {
+        bits = 1;
+    }
+    GBT_REQUIRE(ctx, workspace_bytes >= gbt_predict_workspace_bytes(trees, n_trees), GBT_ENOMEM, "workspace too small");
+    // stage the trees: table of offsets, then each tree's arrays
+    std::vector<char> host(gbt_predict_workspace_bytes(trees, n_trees), 0);
+    DevTree *tab = (DevTree *)host.data();
+    size_t o = gbt_align((size_t)n_trees * sizeof(DevTree));
+    for (int t = 0; t < n_trees; ++t) {
+        const gbt_tree &T = trees[t];
+        GBT_REQUIRE(ctx, T.n_nodes >= 1 && T.n_nodes <= T.capacity, GBT_EINVAL, "tree %d: bad n_nodes", t);
+        for (int i = 0; i < T.n_nodes; ++i) {
+            if (T.feature[i] < 0) continue;
+            GBT_REQUIRE(ctx, T.feature[i] < F && T.left[i] >= 0 && T.left[i] < T.n_nodes && T.right[i] >= 0 &&
+                                 T.right[i] < T.n_nodes,
+                        GBT_EINVAL, "tree %d node %d: bad feature or child id", t, i);
+        }
+        const size_t a4 = gbt_align((size_t)T.n_nodes * 4);
+        tab[t].n_nodes = T.n_nodes;
+        tab[t].pad = 0;
+        const void *src4[6] = {T.feature, T.bin, T.default_left, T.left, T.right, T.threshold};
+        uint64_t *dst4[6] = {&tab[t].feature, &tab[t].bin, &tab[t].default_left, &tab[t].left, &tab[t].right,
+                             &tab[t].threshold};
+        for (int k = 0; k < 6; ++k) {
+            memcpy(host.data() + o, src4[k], (size_t)T.n_nodes * 4);
+            *dst4[k] = o;
+            o += a4;
+        }
+        memcpy(host.data() + o, T.weight, (size_t)T.n_nodes * 8);
+        tab[t].weight = o;
+        o += gbt_align((size_t)T.n_nodes * 8);
+    }
+    GBT_HIP(ctx, hipMemcpyAsync(workspace, host.data(), o, hipMemcpyHostToDevice, ctx->stream));
+    GBT_HIP(ctx, gbt_launch_predict(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees, packed,
+                                    bits, (uint32_t)missing_sym, X, n, F, eta, margin));
+    GBT_SYNC(ctx);
+    return GBT_OK;
+}
+
+// ---------------------------------------------------------------- quantise --
+extern "C" size_t gbt_quantise_workspace_bytes(int64_t n, int32_t F, int64_t n_values, int32_t max_bins) {
+    if (n < 0 || F < 1 || n_values < 0 || max_bins < 2) return 0;
+    return gbt_quantise_ws(n, F, n_values, max_bins);
+}
+
+extern "C" int32_t gbt_quantise(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
+                                const float *values, int64_t n, int32_t F, int32_t max_bins, float *cuts_out,
+                                int32_t *nb_out, uint16_t *sym_out, int32_t *max_value_out,
+                                int32_t *missing_sym_out, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    const bool dense = X != nullptr;
+    GBT_REQUIRE(ctx, dense != (indptr != nullptr), GBT_EINVAL, "give exactly one of X and (indptr, indices, values)");
+    GBT_REQUIRE(ctx, dense || (indices && values), GBT_EINVAL, "CSR input needs indices and values");
+    GBT_REQUIRE(ctx, cuts_out && nb_out && sym_out && max_value_out && missing_sym_out && workspace, GBT_EINVAL,
+                "NULL argument");
+    GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) && F >= 1 && F <= (1 << 20), GBT_EINVAL, "bad shape");
+    GBT_REQUIRE(ctx, max_bins >= 2 && max_bins <= 4096, GBT_EINVAL, "max_bins = %d outside 2..4096", max_bins);
+    int64_t n_values = n * (int64_t)F;
+    if (!dense) {
+        // the number of stored values is the last row pointer
+        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), indptr + n, 8, hipMemcpyDeviceToHost, ctx->stream));
+        GBT_SYNC(ctx);
+        memcpy(&n_values, rb(ctx), 8);
+        GBT_REQUIRE(ctx, n_values >= 0 && n_values <= n * (int64_t)F, GBT_EINVAL, "indptr[n] = %lld out of range",
+                    (long long)n_values);
+    }
+    GBT_REQUIRE(ctx, workspace_bytes >= gbt_quantise_ws(n, F, n_values, max_bins), GBT_ENOMEM,
+                "workspace %zu < %zu bytes", workspace_bytes, gbt_quantise_ws(n, F, n_values, max_bins));
+    int32_t status = GBT_OK;
+    hipError_t e = gbt_quantise_run(ctx, X, indptr, indices, values, n, F, n_values, max_bins, cuts_out, nb_out,
+                                    sym_out, max_value_out, missing_sym_out, (char *)workspace, workspace_bytes,
+                                    &status);
+    if (e != hipSuccess) return gbt_fail(ctx, GBT_EHIP, "gbt_quantise: %s", hipGetErrorString(e));
+    return status;
+}

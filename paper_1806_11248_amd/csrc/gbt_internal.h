@@ -1,0 +1,138 @@
+// Internal declarations shared by the translation units of libgbt.
+// Not part of the ABI; include/gbt.h is.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "gbt.h"
+
+struct gbt_ctx {
+    int device;
+    hipStream_t stream;
+    int num_cu;
+    size_t lds_per_block;   // largest dynamic LDS a workgroup may ask for
+    char *pinned;           // host staging for job tables and small read-backs
+    size_t pinned_bytes;
+    size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
+    char err[512];
+};
+
+#define GBT_STAGING_BYTES (8u << 20)
+
+// ---- error plumbing -------------------------------------------------------
+int32_t gbt_fail(gbt_ctx *ctx, int32_t code, const char *fmt, ...);
+
+#define GBT_HIP(ctx, call)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return gbt_fail((ctx), GBT_EHIP, "%s: %s (%s:%d)", #call, hipGetErrorString(e_), \
+                            __FILE__, __LINE__);                                            \
+    } while (0)
+
+#define GBT_REQUIRE(ctx, cond, code, ...) \
+    do {                                  \
+        if (!(cond)) return gbt_fail((ctx), (code), __VA_ARGS__); \
+    } while (0)
+
+static inline size_t gbt_align(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---- job descriptors (host-built, read by kernels) --------------------------
+// One workgroup of the histogram kernel: rows [row_begin, row_begin+n_rows) of
+// the level's row-id buffer (or of the matrix itself when there is no row-id
+// buffer), features [f0, f0+ft), accumulated into the histogram at hist_off.
+struct HistJob {
+    uint64_t hist_off;   // offset of the node's histogram in int64 units
+    uint32_t row_begin;
+    uint32_t n_rows;
+    uint32_t f0, ft;
+    uint32_t pad0, pad1;
+};
+
+// One node for the split kernel.
+struct EvalNode {
+    uint64_t hist_off;
+    int64_t Gq, Hq;
+};
+
+// One segment for the partition kernels.
+struct PartJob {
+    uint32_t seg_begin, seg_len;
+    uint32_t feature, bin;
+    uint32_t default_left;
+    uint32_t tile_begin;   // index of the segment's first tile in the level's tile arrays
+    uint32_t n_tiles;
+    uint32_t pad;
+};
+
+// One "out = parent - child" for the subtraction kernel (int64 units).
+struct SubJob {
+    uint64_t parent_off, child_off, out_off;
+};
+
+// One leaf segment for the final gather.
+struct LeafSeg {
+    uint32_t seg_begin;
+    uint32_t node;
+    uint32_t buf;   // which of the two row-id buffers holds the segment
+    uint32_t len;
+};
+
+#define GBT_PART_TILE 2048   // rows per partition workgroup
+#define GBT_PART_BLOCK 256
+
+// ---- kernel launchers (each returns the hipGetLastError of its launches) ---
+hipError_t gbt_launch_fill_u64(hipStream_t s, uint64_t *p, uint64_t v, int64_t count);
+hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count);
+hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2);
+hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, double sg, double sh,
+                               int32_t *gq);
+hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,
+                             int64_t *out2 /* zeroed by the launcher */);
+hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margin, const float *label,
+                                int64_t n, float *gpair);
+hipError_t gbt_launch_subtract(hipStream_t s, int64_t *pool, const SubJob *jobs, int n_jobs,
+                               int64_t count);
+hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const int64_t *child,
+                                   int64_t *out, int64_t count);
+hipError_t gbt_launch_export(hipStream_t s, const int64_t *hist, int64_t count, double inv_sg,
+                             double inv_sh, double *out);
+
+hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t n, int F, int B,
+                           uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
+                           int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft);
+// Largest feature tile whose LDS histogram fits, and the per-job row count to aim for.
+int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B);
+
+hipError_t gbt_launch_eval(hipStream_t s, const int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
+                           const int32_t *nb, int F, int B, double inv_sg, double inv_sh, double lambda,
+                           double mcw, gbt_split *out);
+
+hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t n, int F,
+                                uint32_t missing, const uint32_t *src, uint32_t *dst,
+                                const PartJob *jobs, int n_jobs, int total_tiles, uint64_t *masks,
+                                uint32_t *tile_left, uint32_t *n_left_out);
+hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
+                                  const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,
+                                  int32_t *leaf_of_row);
+
+hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_elems, int bits,
+                               uint32_t *packed, int64_t n_words);
+
+struct DevTree {   // one tree's arrays inside the predict workspace (offsets in bytes)
+    int32_t n_nodes;
+    int32_t pad;
+    uint64_t feature, bin, default_left, left, right, threshold, weight;
+};
+hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
+                              const uint32_t *packed, int bits, uint32_t missing, const float *X,
+                              int64_t n, int F, double eta, float *margin);
+
+// quantise
+hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
+                            const float *values, int64_t n, int F, int64_t n_values, int B, float *cuts,
+                            int32_t *nb, uint16_t *sym, int32_t *max_value, int32_t *missing_sym,
+                            char *ws, size_t ws_bytes, int32_t *status);
+size_t gbt_quantise_ws(int64_t n, int F, int64_t n_values, int B);

@@ -1,0 +1,299 @@
+// Small streaming kernels around the tree builder: fills, fixed-point
+// conversion of the gradient pairs, node totals, gradients (Eq. 1-2), sibling
+// subtraction, export, bit packing (Sec. 2.2), prediction (Sec. 2.4) and the
+// final leaf gather.  All are bandwidth-trivial next to the histogram kernel.
+#include "gbt_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+
+inline int grid_for(int64_t count, int per_block, int cap = 1 << 20) {
+    int64_t g = (count + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+__global__ void fill_u64_kernel(uint64_t *p, uint64_t v, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+__global__ void iota_u32_kernel(uint32_t *p, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = (uint32_t)i;
+}
+
+// max |g| and max |h| as raw float bits (non-negative floats order like their
+// bit patterns; NaN sorts above +inf, so a non-finite input is detected).
+__global__ void absmax_kernel(const float2 *gp, int64_t n, uint32_t *out2) {
+    uint32_t mg = 0, mh = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        float2 v = gp[i];
+        uint32_t a = __float_as_uint(v.x) & 0x7fffffffu;
+        uint32_t b = __float_as_uint(v.y) & 0x7fffffffu;
+        mg = a > mg ? a : mg;
+        mh = b > mh ? b : mh;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        uint32_t a = __shfl_xor(mg, o), b = __shfl_xor(mh, o);
+        mg = a > mg ? a : mg;
+        mh = b > mh ? b : mh;
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicMax(&out2[0], mg);
+        atomicMax(&out2[1], mh);
+    }
+}
+
+__global__ void to_fixed_kernel(const float2 *gp, int64_t n, double sg, double sh, int2 *gq) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        float2 v = gp[i];
+        int2 q;
+        q.x = __double2int_rn((double)v.x * sg);
+        q.y = __double2int_rn((double)v.y * sh);
+        gq[i] = q;
+    }
+}
+
+__device__ inline int64_t wave_sum_i64(int64_t v) {
+    for (int o = 32; o > 0; o >>= 1) {
+        int lo = __shfl_xor((int)(v & 0xffffffff), o);
+        int hi = __shfl_xor((int)(v >> 32), o);
+        v += (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+    }
+    return v;
+}
+
+__global__ void sum_gq_kernel(const int2 *gq, const uint32_t *row_idx, int64_t n_rows, int64_t *out2) {
+    int64_t g = 0, h = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_rows;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int64_t r = row_idx ? (int64_t)row_idx[i] : i;
+        int2 q = gq[r];
+        g += q.x;
+        h += q.y;
+    }
+    g = wave_sum_i64(g);
+    h = wave_sum_i64(h);
+    if ((threadIdx.x & 63) == 0) {
+        atomicAdd((unsigned long long *)&out2[0], (unsigned long long)g);
+        atomicAdd((unsigned long long *)&out2[1], (unsigned long long)h);
+    }
+}
+
+// Eq. 1 and Eq. 2 (logistic) and the squared-error pair, one instance per
+// thread.  Evaluated in fp64 and rounded once so that the fp32 pair does not
+// depend on a fast-math exp.
+__global__ void gradients_kernel(int objective, const float *margin, const float *label, int64_t n,
+                                 float2 *gp) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        double m = margin[i], y = label[i], g, h;
+        if (objective == GBT_OBJ_LOGISTIC) {
+            double p = 1.0 / (1.0 + exp(-m));
+            g = p - y;
+            h = p * (1.0 - p);
+        } else {
+            g = m - y;
+            h = 1.0;
+        }
+        gp[i] = make_float2((float)g, (float)h);
+    }
+}
+
+__global__ void subtract_jobs_kernel(int64_t *pool, const SubJob *jobs, int64_t count) {
+    SubJob j = jobs[blockIdx.y];
+    const int64_t *p = pool + j.parent_off, *c = pool + j.child_off;
+    int64_t *o = pool + j.out_off;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        o[i] = p[i] - c[i];
+}
+
+__global__ void subtract_one_kernel(const int64_t *p, const int64_t *c, int64_t *o, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        o[i] = p[i] - c[i];
+}
+
+__global__ void export_kernel(const int64_t *hist, int64_t count, double inv_sg, double inv_sh,
+                              double *out) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = (double)hist[i] * ((i & 1) ? inv_sh : inv_sg);
+}
+
+// Sec. 2.2: one thread assembles one 32-bit word of the bit stream from the
+// elements that overlap it (no atomics; the trailing pad word comes out zero).
+__global__ void compress_kernel(const uint16_t *sym, int64_t n_elems, int bits, uint32_t *packed,
+                                int64_t n_words) {
+    for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < n_words;
+         w += (int64_t)gridDim.x * blockDim.x) {
+        int64_t bit0 = w * 32;
+        int64_t e = bit0 / bits;
+        uint32_t word = 0;
+        for (; e < n_elems; ++e) {
+            int64_t pos = e * bits - bit0;   // may be negative for the first element
+            if (pos >= 32) break;
+            uint32_t s = sym[e];
+            word |= pos >= 0 ? (s << pos) : (s >> (-pos));
+        }
+        packed[w] = word;
+    }
+}
+
+__device__ inline uint32_t load_symbol(const uint32_t *packed, uint64_t elem, int bits, uint32_t mask) {
+    uint64_t bp = elem * (uint64_t)bits;
+    const uint32_t *w = packed + (bp >> 5);
+    uint64_t v = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    return (uint32_t)(v >> (bp & 31)) & mask;
+}
+
+// Sec. 2.4: one instance per thread, trees in order, walking from the root.
+__global__ void predict_kernel(const char *ws, const DevTree *trees, int n_trees,
+                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
+                               int64_t n, int F, double eta, float *margin) {
+    const uint32_t mask = (1u << bits) - 1u;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n;
+         r += (int64_t)gridDim.x * blockDim.x) {
+        double m = margin[r];
+        for (int t = 0; t < n_trees; ++t) {
+            DevTree T = trees[t];
+            const int32_t *feature = (const int32_t *)(ws + T.feature);
+            const int32_t *bin = (const int32_t *)(ws + T.bin);
+            const int32_t *dl = (const int32_t *)(ws + T.default_left);
+            const int32_t *left = (const int32_t *)(ws + T.left);
+            const int32_t *right = (const int32_t *)(ws + T.right);
+            const float *thr = (const float *)(ws + T.threshold);
+            const double *weight = (const double *)(ws + T.weight);
+            int node = 0;
+            // a well-formed tree ends in fewer than n_nodes steps; the bound keeps a
+            // malformed one from spinning
+            for (int step = 0; step < T.n_nodes; ++step) {
+                int f = feature[node];
+                if (f < 0) break;
+                bool go_left;
+                if (packed) {
+                    uint32_t s = load_symbol(packed, (uint64_t)r * F + f, bits, mask);
+                    go_left = (s == missing) ? (dl[node] != 0) : ((int)s <= bin[node]);
+                } else {
+                    float x = X[r * F + f];
+                    go_left = (x != x) ? (dl[node] != 0) : (x < thr[node]);
+                }
+                node = go_left ? left[node] : right[node];
+            }
+            m = (double)(float)(m + eta * weight[node]);
+        }
+        margin[r] = (float)m;
+    }
+}
+
+// Final row order and leaf ids: every position of [0, n) lies in exactly one
+// leaf segment; segments are sorted by seg_begin.
+__global__ void leaf_gather_kernel(const uint32_t *buf0, const uint32_t *buf1, const LeafSeg *segs,
+                                   int n_segs, int64_t n, uint32_t *row_idx_out, int32_t *leaf_of_row) {
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n;
+         p += (int64_t)gridDim.x * blockDim.x) {
+        int lo = 0, hi = n_segs;   // last segment with seg_begin <= p
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if ((int64_t)segs[mid].seg_begin <= p) lo = mid; else hi = mid;
+        }
+        LeafSeg s = segs[lo];
+        uint32_t r = (s.buf ? buf1 : buf0)[p];
+        row_idx_out[p] = r;
+        if (leaf_of_row && (int64_t)r < n) leaf_of_row[r] = (int32_t)s.node;
+    }
+}
+
+}  // namespace
+
+hipError_t gbt_launch_fill_u64(hipStream_t s, uint64_t *p, uint64_t v, int64_t count) {
+    if (count <= 0) return hipSuccess;
+    fill_u64_kernel<<<grid_for(count, kBlock * 4, 4096), kBlock, 0, s>>>(p, v, count);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count) {
+    if (count <= 0) return hipSuccess;
+    iota_u32_kernel<<<grid_for(count, kBlock * 4, 8192), kBlock, 0, s>>>(p, count);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2) {
+    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)out2, 0, 1);
+    if (e != hipSuccess || n <= 0) return e;
+    absmax_kernel<<<grid_for(n, kBlock * 8, 2048), kBlock, 0, s>>>((const float2 *)gpair, n, out2);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, double sg, double sh,
+                               int32_t *gq) {
+    if (n <= 0) return hipSuccess;
+    to_fixed_kernel<<<grid_for(n, kBlock * 4, 8192), kBlock, 0, s>>>((const float2 *)gpair, n, sg, sh,
+                                                                      (int2 *)gq);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,
+                             int64_t *out2) {
+    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)out2, 0, 2);
+    if (e != hipSuccess || n_rows <= 0) return e;
+    sum_gq_kernel<<<grid_for(n_rows, kBlock * 8, 2048), kBlock, 0, s>>>((const int2 *)gq, row_idx, n_rows,
+                                                                        out2);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margin, const float *label,
+                                int64_t n, float *gpair) {
+    if (n <= 0) return hipSuccess;
+    gradients_kernel<<<grid_for(n, kBlock * 2, 8192), kBlock, 0, s>>>(objective, margin, label, n,
+                                                                      (float2 *)gpair);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_subtract(hipStream_t s, int64_t *pool, const SubJob *jobs, int n_jobs,
+                               int64_t count) {
+    if (n_jobs <= 0 || count <= 0) return hipSuccess;
+    for (int j0 = 0; j0 < n_jobs; j0 += 65535) {   // grid.y limit
+        int nj = n_jobs - j0 < 65535 ? n_jobs - j0 : 65535;
+        dim3 grid(grid_for(count, kBlock * 4, 256), nj);
+        subtract_jobs_kernel<<<grid, kBlock, 0, s>>>(pool, jobs + j0, count);
+    }
+    return hipGetLastError();
+}
+hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const int64_t *child,
+                                   int64_t *out, int64_t count) {
+    if (count <= 0) return hipSuccess;
+    subtract_one_kernel<<<grid_for(count, kBlock * 4, 4096), kBlock, 0, s>>>(parent, child, out, count);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_export(hipStream_t s, const int64_t *hist, int64_t count, double inv_sg,
+                             double inv_sh, double *out) {
+    if (count <= 0) return hipSuccess;
+    export_kernel<<<grid_for(count, kBlock * 4, 4096), kBlock, 0, s>>>(hist, count, inv_sg, inv_sh, out);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_elems, int bits,
+                               uint32_t *packed, int64_t n_words) {
+    if (n_words <= 0) return hipSuccess;
+    compress_kernel<<<grid_for(n_words, kBlock * 4, 16384), kBlock, 0, s>>>(sym, n_elems, bits, packed,
+                                                                            n_words);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
+                              const uint32_t *packed, int bits, uint32_t missing, const float *X,
+                              int64_t n, int F, double eta, float *margin) {
+    if (n <= 0) return hipSuccess;
+    predict_kernel<<<grid_for(n, kBlock, 1 << 16), kBlock, 0, s>>>(ws, trees, n_trees, packed, bits,
+                                                                    missing, X, n, F, eta, margin);
+    return hipGetLastError();
+}
+hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
+                                  const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,
+                                  int32_t *leaf_of_row) {
+    if (n <= 0 || n_segs <= 0) return hipSuccess;
+    leaf_gather_kernel<<<grid_for(n, kBlock * 4, 16384), kBlock, 0, s>>>(buf0, buf1, segs, n_segs, n,
+                                                                         row_idx_out, leaf_of_row);
+    return hipGetLastError();
+}

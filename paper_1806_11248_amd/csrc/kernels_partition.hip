@@ -1,0 +1,162 @@
+// RepartitionInstances (Alg. 1: "sort training instances into leaf nodes based
+// on previous split") as a stable partition of row-id segments.
+//
+// All splitting nodes of a level are handled by the same three launches:
+//   1. flag   : one workgroup per 2048-row tile gathers the split feature's
+//               symbol of each row from the packed matrix, decides left/right,
+//               stores the decision as wave ballots (one bit per row) and the
+//               tile's count of left rows;
+//   2. scan   : one workgroup per segment turns its tile counts into exclusive
+//               offsets and the segment's n_left;
+//   3. scatter: each tile recomputes every row's rank from the ballots
+//               (popcounts below the lane + an LDS scan over the tile's 32
+//               ballot words) and writes it to its place in the other buffer.
+// Ranks are taken in row order, so both halves keep their order (stable).
+// No workgroup waits on another one.
+#include "gbt_internal.h"
+
+namespace {
+
+constexpr int kTile = GBT_PART_TILE;
+constexpr int kBlock = GBT_PART_BLOCK;
+constexpr int kWordsPerTile = kTile / 64;       // 32 ballot words
+constexpr int kRowsPerThread = kTile / kBlock;  // 8
+static_assert(kBlock == 256 && kTile == 2048, "index arithmetic below assumes 4 waves x 8 steps");
+
+// the job whose tile range contains `tile` (jobs are sorted by tile_begin)
+__device__ inline int find_job(const PartJob *jobs, int n_jobs, uint32_t tile) {
+    int lo = 0, hi = n_jobs;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (jobs[mid].tile_begin <= tile) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ inline uint32_t load_symbol(const uint32_t *packed, uint64_t elem, int bits, uint32_t mask) {
+    uint64_t bp = elem * (uint64_t)bits;
+    const uint32_t *w = packed + (bp >> 5);
+    uint64_t v = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    return (uint32_t)(v >> (bp & 31)) & mask;
+}
+
+__global__ __launch_bounds__(kBlock) void part_flag_kernel(
+    const uint32_t *__restrict__ packed, int bits, int64_t n, int F, uint32_t missing,
+    const uint32_t *__restrict__ src, const PartJob *__restrict__ jobs, int n_jobs,
+    uint64_t *__restrict__ masks, uint32_t *__restrict__ tile_left) {
+    const uint32_t tile = blockIdx.x;
+    const PartJob job = jobs[find_job(jobs, n_jobs, tile)];
+    const uint32_t t_in_seg = tile - job.tile_begin;
+    const uint32_t base = t_in_seg * kTile;   // first row of the tile inside the segment
+    const uint32_t mask = (1u << bits) - 1u;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t count = 0;
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        const uint32_t off = base + (uint32_t)j * kBlock + threadIdx.x;
+        bool left = false;
+        if (off < job.seg_len) {
+            const uint64_t r = src[(uint64_t)job.seg_begin + off];
+            if (r < (uint64_t)n) {
+                const uint32_t s = load_symbol(packed, r * (uint64_t)F + job.feature, bits, mask);
+                left = (s == missing) ? (job.default_left != 0) : (s <= job.bin);
+            }
+        }
+        const uint64_t ballot = __ballot(left);
+        if (lane == 0) masks[(uint64_t)tile * kWordsPerTile + (j * (kBlock / 64) + wave)] = ballot;
+        count += (uint32_t)__popcll(ballot);   // same value in every lane of the wave
+    }
+    __shared__ uint32_t wsum[kBlock / 64];
+    if (lane == 0) wsum[wave] = count;
+    __syncthreads();
+    if (threadIdx.x == 0) tile_left[tile] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+__global__ __launch_bounds__(kBlock) void part_scan_kernel(const PartJob *__restrict__ jobs,
+                                                           uint32_t *__restrict__ tile_left,
+                                                           uint32_t *__restrict__ n_left_out) {
+    const PartJob job = jobs[blockIdx.x];
+    __shared__ uint32_t wtot[kBlock / 64];
+    __shared__ uint32_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint32_t t0 = 0; t0 < job.n_tiles; t0 += kBlock) {
+        const uint32_t t = t0 + threadIdx.x;
+        const uint32_t v = t < job.n_tiles ? tile_left[job.tile_begin + t] : 0;
+        uint32_t x = v;
+        for (int d = 1; d < 64; d <<= 1) {
+            uint32_t y = (uint32_t)__shfl_up((int)x, d);
+            if (lane >= d) x += y;
+        }
+        if (lane == 63) wtot[wave] = x;
+        __syncthreads();
+        uint32_t before = carry_s;
+        for (int w = 0; w < wave; ++w) before += wtot[w];
+        if (t < job.n_tiles) tile_left[job.tile_begin + t] = before + x - v;   // exclusive
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s += wtot[0] + wtot[1] + wtot[2] + wtot[3];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) n_left_out[blockIdx.x] = carry_s;
+}
+
+__global__ __launch_bounds__(kBlock) void part_scatter_kernel(
+    const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, const PartJob *__restrict__ jobs,
+    int n_jobs, const uint64_t *__restrict__ masks, const uint32_t *__restrict__ tile_left_off,
+    const uint32_t *__restrict__ n_left) {
+    const uint32_t tile = blockIdx.x;
+    const int ji = find_job(jobs, n_jobs, tile);
+    const PartJob job = jobs[ji];
+    const uint32_t base = (tile - job.tile_begin) * kTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    __shared__ uint64_t words[kWordsPerTile];
+    __shared__ uint32_t lefts_before[kWordsPerTile];
+    if (threadIdx.x < kWordsPerTile) words[threadIdx.x] = masks[(uint64_t)tile * kWordsPerTile + threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0;
+        for (int w = 0; w < kWordsPerTile; ++w) {
+            lefts_before[w] = acc;
+            acc += (uint32_t)__popcll(words[w]);
+        }
+    }
+    __syncthreads();
+
+    const uint32_t left_base = tile_left_off[tile];   // lefts of this segment before this tile
+    const uint32_t right_base = base - left_base;     // rights of this segment before this tile
+    const uint32_t seg_n_left = n_left[ji];
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        const int w = j * (kBlock / 64) + wave;
+        const uint32_t off = base + (uint32_t)w * 64u + (uint32_t)lane;
+        if (off < job.seg_len) {
+            const uint64_t m = words[w];
+            const uint32_t below = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            const uint32_t r = src[(uint64_t)job.seg_begin + off];
+            uint32_t pos;
+            if ((m >> lane) & 1ull) {
+                pos = left_base + lefts_before[w] + below;
+            } else {
+                const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[w];
+                pos = seg_n_left + right_base + rights_before_word + ((uint32_t)lane - below);
+            }
+            dst[(uint64_t)job.seg_begin + pos] = r;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t n, int F,
+                                uint32_t missing, const uint32_t *src, uint32_t *dst,
+                                const PartJob *jobs, int n_jobs, int total_tiles, uint64_t *masks,
+                                uint32_t *tile_left, uint32_t *n_left_out) {
+    if (n_jobs <= 0 || total_tiles <= 0) return hipSuccess;
+    part_flag_kernel<<<total_tiles, kBlock, 0, s>>>(packed, bits, n, F, missing, src, jobs, n_jobs, masks,
+                                                    tile_left);
+    part_scan_kernel<<<n_jobs, kBlock, 0, s>>>(jobs, tile_left, n_left_out);
+    part_scatter_kernel<<<total_tiles, kBlock, 0, s>>>(src, dst, jobs, n_jobs, masks, tile_left, n_left_out);
+    return hipGetLastError();
+}

@@ -1,0 +1,476 @@
+// Feature quantile generation (Sec. 2.1) on the GPU: exact per-feature order
+// statistics by a segmented LSD radix sort of the order-preserving integer
+// image of the fp32 values, then cuts, then binning.
+//
+//   1. keys: every feature's values become one contiguous segment of uint32
+//      keys (dense input: an LDS-tiled transpose, a missing value becomes the
+//      largest key; CSR input: counted, offset and scattered by column);
+//   2. sort: four 8-bit passes; per pass a per-tile digit histogram, one
+//      workgroup per segment turning the tile histograms into offsets, and a
+//      stable scatter (ranks from wave ballots, tiles and waves in order);
+//   3. cuts: one thread per feature walks the sorted segment (distinct values
+//      by upper-bound jumps, else the order statistics v[floor(k*m/B)]);
+//   4. bin: symbol = number of cuts <= x by bisection over the feature's cuts.
+#include "gbt_internal.h"
+
+#include <string.h>
+
+#include <vector>
+
+namespace {
+
+constexpr int kSortBlock = 256;
+constexpr int kSortTile = 4096;                       // keys per workgroup and pass
+constexpr int kKeysPerWave = kSortTile / (kSortBlock / 64);   // 1024
+constexpr int kRounds = kKeysPerWave / 64;            // 16
+constexpr uint32_t kMissingKey = 0xffffffffu;
+
+__device__ inline uint32_t float_key(float x) {
+    if (x != x) return kMissingKey;
+    x = x + 0.0f;   // -0.0 -> +0.0: the two compare equal and must share a key
+    uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float key_float(uint32_t k) {
+    uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __uint_as_float(u);
+}
+
+// ---- 1a. dense input: transpose into per-feature key segments -------------
+constexpr int kTrRows = 64, kTrCols = 64;
+__global__ __launch_bounds__(256) void dense_keys_kernel(const float *__restrict__ X, int64_t n, int F,
+                                                         uint32_t *__restrict__ keys) {
+    __shared__ uint32_t tile[kTrRows][kTrCols + 1];
+    const int64_t r0 = (int64_t)blockIdx.x * kTrRows;
+    const int f0 = blockIdx.y * kTrCols;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 64 x 4
+    for (int i = ty; i < kTrRows; i += 4) {
+        const int64_t r = r0 + i;
+        const int f = f0 + tx;
+        tile[i][tx] = (r < n && f < F) ? float_key(X[r * F + f]) : kMissingKey;
+    }
+    __syncthreads();
+    for (int j = ty; j < kTrCols; j += 4) {
+        const int f = f0 + j;
+        const int64_t r = r0 + tx;
+        if (f < F && r < n) keys[(int64_t)f * n + r] = tile[tx][j];
+    }
+}
+
+// ---- 1b. CSR input: count, offset, scatter by column -----------------------
+__global__ void csr_count_kernel(const int32_t *__restrict__ indices, int64_t nnz, int F,
+                                 uint32_t *__restrict__ counts) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int f = indices[i];
+        if (f >= 0 && f < F) atomicAdd(&counts[f], 1u);
+    }
+}
+
+// seg_off[f] = exclusive prefix of counts; blk_off[f] = exclusive prefix of tiles
+__global__ void offsets_kernel(const uint32_t *counts, int F, int64_t fixed_len, uint64_t *seg_off,
+                               uint32_t *blk_off) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    uint64_t o = 0;
+    uint32_t b = 0;
+    for (int f = 0; f < F; ++f) {
+        seg_off[f] = o;
+        blk_off[f] = b;
+        const uint64_t len = counts ? (uint64_t)counts[f] : (uint64_t)fixed_len;
+        o += len;
+        b += (uint32_t)((len + kSortTile - 1) / kSortTile);
+    }
+    seg_off[F] = o;
+    blk_off[F] = b;
+}
+
+__global__ void csr_scatter_kernel(const int32_t *__restrict__ indices, const float *__restrict__ values,
+                                   int64_t nnz, int F, const uint64_t *__restrict__ seg_off,
+                                   uint32_t *__restrict__ cursor, uint32_t *__restrict__ keys) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int f = indices[i];
+        if (f < 0 || f >= F) continue;
+        const uint32_t slot = atomicAdd(&cursor[f], 1u);   // order inside a segment is irrelevant before the sort
+        keys[seg_off[f] + slot] = float_key(values[i]);
+    }
+}
+
+// ---- 2. segmented radix sort ----------------------------------------------
+__device__ inline int find_segment(const uint32_t *blk_off, int F, uint32_t blk) {
+    int lo = 0, hi = F;   // last f with blk_off[f] <= blk and a non-empty tile range
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (blk_off[mid] <= blk) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const uint32_t *__restrict__ keys,
+                                                               const uint64_t *__restrict__ seg_off,
+                                                               const uint32_t *__restrict__ blk_off, int F,
+                                                               int shift, uint32_t *__restrict__ tile_hist) {
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t blk = blockIdx.x;
+    const int f = find_segment(blk_off, F, blk);
+    const uint64_t base = seg_off[f], len = seg_off[f + 1] - base;
+    const uint64_t t0 = (uint64_t)(blk - blk_off[f]) * kSortTile;
+    for (int i = threadIdx.x; i < kSortTile; i += kSortBlock) {
+        const uint64_t p = t0 + i;
+        if (p < len) atomicAdd(&h[(keys[base + p] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    tile_hist[(uint64_t)blk * 256 + threadIdx.x] = h[threadIdx.x];
+}
+
+// One workgroup per segment, thread d owns digit d: tile_hist[blk][d] becomes the
+// position (inside the segment) of the first key of tile blk with digit d.
+__global__ __launch_bounds__(256) void sort_scan_kernel(const uint32_t *__restrict__ blk_off,
+                                                        uint32_t *__restrict__ tile_hist) {
+    const int f = blockIdx.x, d = threadIdx.x;
+    const uint32_t b0 = blk_off[f], b1 = blk_off[f + 1];
+    uint32_t run = 0;
+    uint32_t b = b0;
+    for (; b + 8 <= b1; b += 8) {   // eight independent loads in flight per step
+        uint32_t c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u] = tile_hist[(uint64_t)(b + u) * 256 + d];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            tile_hist[(uint64_t)(b + u) * 256 + d] = run;
+            run += c[u];
+        }
+    }
+    for (; b < b1; ++b) {
+        const uint32_t c = tile_hist[(uint64_t)b * 256 + d];
+        tile_hist[(uint64_t)b * 256 + d] = run;
+        run += c;
+    }
+    // exclusive scan of the digit totals over the 256 threads
+    __shared__ uint32_t tot[256];
+    tot[d] = run;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+        uint32_t v = d >= o ? tot[d - o] : 0;
+        __syncthreads();
+        tot[d] += v;
+        __syncthreads();
+    }
+    const uint32_t base = tot[d] - run;
+    for (b = b0; b < b1; ++b) tile_hist[(uint64_t)b * 256 + d] += base;
+}
+
+__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const uint32_t *__restrict__ src,
+                                                                  uint32_t *__restrict__ dst,
+                                                                  const uint64_t *__restrict__ seg_off,
+                                                                  const uint32_t *__restrict__ blk_off, int F,
+                                                                  int shift,
+                                                                  const uint32_t *__restrict__ tile_hist) {
+    __shared__ uint32_t cnt[kSortBlock / 64][256];   // per wave: running count per digit
+    const uint32_t blk = blockIdx.x;
+    const int f = find_segment(blk_off, F, blk);
+    const uint64_t base = seg_off[f], len = seg_off[f + 1] - base;
+    const uint64_t t0 = (uint64_t)(blk - blk_off[f]) * kSortTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < (kSortBlock / 64) * 256; i += kSortBlock) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+
+    // the wave's 1024 keys, 64 per round, kept in registers
+    uint32_t key[kRounds];
+    const uint64_t w0 = t0 + (uint64_t)wave * kKeysPerWave;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const uint64_t p = w0 + (uint64_t)r * 64 + lane;
+        key[r] = p < len ? src[base + p] : 0;
+        if (p < len) atomicAdd(&cnt[wave][(key[r] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    // cnt[w][d] -> number of digit-d keys in the waves before w (exclusive over waves),
+    // plus the tile's position for digit d
+    {
+        const int d = threadIdx.x;   // 256 threads, one digit each
+        uint32_t run = tile_hist[(uint64_t)blk * 256 + d];
+        for (int w = 0; w < kSortBlock / 64; ++w) {
+            const uint32_t c = cnt[w][d];
+            cnt[w][d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const uint64_t p = w0 + (uint64_t)r * 64 + lane;
+        const bool live = p < len;
+        const uint32_t dgt = (key[r] >> shift) & 255u;
+        // lanes of this round with the same digit
+        uint64_t peers = __ballot(live);
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t m = __ballot((dgt >> b) & 1u);
+            peers &= ((dgt >> b) & 1u) ? m : ~m;
+        }
+        volatile uint32_t *wc = cnt[wave];   // touched by this wave only from here on
+        const uint32_t below = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+        uint32_t first = 0;
+        if (live) first = wc[dgt];            // every peer reads the same count ...
+        __builtin_amdgcn_wave_barrier();
+        if (live && below == 0) wc[dgt] = first + (uint32_t)__popcll(peers);   // ... before the leader bumps it
+        __builtin_amdgcn_wave_barrier();
+        if (live) dst[base + first + below] = key[r];
+    }
+}
+
+// ---- 3. cuts ----------------------------------------------------------------
+__device__ inline uint64_t upper_bound_u32(const uint32_t *a, uint64_t lo, uint64_t hi, uint32_t v) {
+    while (lo < hi) {   // first index in [lo, hi) with a[i] > v
+        const uint64_t mid = lo + ((hi - lo) >> 1);
+        if (a[mid] <= v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void cuts_kernel(const uint32_t *__restrict__ keys, const uint64_t *__restrict__ seg_off, int F, int B,
+                            float *__restrict__ cuts, int32_t *__restrict__ nb) {
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= F) return;
+    const uint32_t *v = keys + seg_off[f];
+    const uint64_t len = seg_off[f + 1] - seg_off[f];
+    float *c = cuts + (int64_t)f * (B - 1);
+    for (int k = 0; k < B - 1; ++k) c[k] = __uint_as_float(0x7f800000u);   // +inf
+    // present values = keys below the missing key
+    uint64_t m = 0;
+    {
+        uint64_t lo = 0, hi = len;
+        while (lo < hi) {
+            const uint64_t mid = lo + ((hi - lo) >> 1);
+            if (v[mid] < kMissingKey) lo = mid + 1; else hi = mid;
+        }
+        m = lo;
+    }
+    if (m == 0) {
+        nb[f] = 1;
+        return;
+    }
+    // distinct values, counted up to B+1; the first B-1 after the smallest are
+    // written as tentative cuts
+    int d = 0, nc = 0;
+    uint64_t pos = 0;
+    while (pos < m && d <= B) {
+        const uint32_t key = v[pos];
+        if (d >= 1 && d <= B - 1) c[d - 1] = key_float(key);
+        ++d;
+        pos = upper_bound_u32(v, pos + 1, m, key);
+    }
+    if (d <= B) {
+        nc = d - 1;
+    } else {
+        const uint32_t vmin = v[0];
+        uint32_t prev = 0;
+        for (int k = 1; k < B; ++k) {
+            const uint32_t key = v[(uint64_t)k * m / (uint64_t)B];
+            if (key == vmin) continue;
+            if (nc > 0 && key == prev) continue;
+            c[nc++] = key_float(key);
+            prev = key;
+        }
+        for (int k = nc; k < B - 1; ++k) c[k] = __uint_as_float(0x7f800000u);
+    }
+    nb[f] = nc + 1;
+}
+
+// ---- 4. binning -------------------------------------------------------------
+__device__ inline uint32_t bin_of(const float *c, int ncut, float x) {
+    int lo = 0, hi = ncut;   // number of cuts <= x
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (c[mid] <= x) lo = mid + 1; else hi = mid;
+    }
+    return (uint32_t)lo;
+}
+
+__global__ void bin_dense_kernel(const float *__restrict__ X, int64_t n_elems, int F, int B,
+                                 const float *__restrict__ cuts, const int32_t *__restrict__ nb,
+                                 uint32_t missing, uint16_t *__restrict__ sym, uint32_t *__restrict__ max_out) {
+    uint32_t mx = 0;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_elems;
+         e += (int64_t)gridDim.x * blockDim.x) {
+        const int f = (int)(e % F);
+        const float x = X[e];
+        const uint32_t s = (x != x) ? missing : bin_of(cuts + (int64_t)f * (B - 1), nb[f] - 1, x);
+        sym[e] = (uint16_t)s;
+        mx = s > mx ? s : mx;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = (uint32_t)__shfl_xor((int)mx, o);
+        mx = t > mx ? t : mx;
+    }
+    if ((threadIdx.x & 63) == 0) atomicMax(max_out, mx);
+}
+
+__global__ void fill_u16_kernel(uint16_t *p, uint16_t v, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+__global__ void bin_csr_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                               const float *__restrict__ values, int64_t n, int64_t nnz, int F, int B,
+                               const float *__restrict__ cuts, const int32_t *__restrict__ nb, uint32_t missing,
+                               uint16_t *__restrict__ sym, uint32_t *__restrict__ max_out) {
+    uint32_t mx = 0;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n;
+         r += (int64_t)gridDim.x * blockDim.x) {
+        int64_t a = indptr[r], b = indptr[r + 1];
+        if (a < 0) a = 0;
+        if (b > nnz) b = nnz;
+        bool any_missing = (b - a) < F;
+        for (int64_t i = a; i < b; ++i) {
+            const int f = indices[i];
+            if (f < 0 || f >= F) continue;
+            const float x = values[i];
+            const uint32_t s = (x != x) ? missing : bin_of(cuts + (int64_t)f * (B - 1), nb[f] - 1, x);
+            sym[r * F + f] = (uint16_t)s;
+            mx = s > mx ? s : mx;
+        }
+        if (any_missing) mx = missing > mx ? missing : mx;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = (uint32_t)__shfl_xor((int)mx, o);
+        mx = t > mx ? t : mx;
+    }
+    if ((threadIdx.x & 63) == 0) atomicMax(max_out, mx);
+}
+
+struct QLayout {
+    size_t keys_a, keys_b, tile_hist, seg_off, blk_off, counts, cursor, misc, total;
+    int64_t max_tiles;
+};
+QLayout q_layout(int64_t n, int F, int64_t n_values) {
+    (void)n;
+    QLayout L;
+    L.max_tiles = n_values / kSortTile + F + 1;
+    size_t o = 0;
+    L.keys_a = o;    o += gbt_align((size_t)n_values * 4 + 4);
+    L.keys_b = o;    o += gbt_align((size_t)n_values * 4 + 4);
+    L.tile_hist = o; o += gbt_align((size_t)L.max_tiles * 256 * 4);
+    L.seg_off = o;   o += gbt_align((size_t)(F + 1) * 8);
+    L.blk_off = o;   o += gbt_align((size_t)(F + 1) * 4);
+    L.counts = o;    o += gbt_align((size_t)F * 4);
+    L.cursor = o;    o += gbt_align((size_t)F * 4);
+    L.misc = o;      o += 256;
+    L.total = o;
+    return L;
+}
+
+inline int grid_for(int64_t count, int per_block, int cap) {
+    int64_t g = (count + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+}  // namespace
+
+size_t gbt_quantise_ws(int64_t n, int F, int64_t n_values, int B) {
+    (void)B;
+    return q_layout(n, F, n_values).total;
+}
+
+#define Q_HIP(call)                        \
+    do {                                   \
+        hipError_t e_ = (call);            \
+        if (e_ != hipSuccess) return e_;   \
+    } while (0)
+
+hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
+                            const float *values, int64_t n, int F, int64_t n_values, int B, float *cuts,
+                            int32_t *nb, uint16_t *sym, int32_t *max_value, int32_t *missing_sym, char *ws,
+                            size_t ws_bytes, int32_t *status) {
+    (void)ws_bytes;
+    *status = GBT_OK;
+    hipStream_t s = ctx->stream;
+    const QLayout L = q_layout(n, F, n_values);
+    uint32_t *keys_a = (uint32_t *)(ws + L.keys_a), *keys_b = (uint32_t *)(ws + L.keys_b);
+    uint32_t *tile_hist = (uint32_t *)(ws + L.tile_hist);
+    uint64_t *seg_off = (uint64_t *)(ws + L.seg_off);
+    uint32_t *blk_off = (uint32_t *)(ws + L.blk_off);
+    uint32_t *counts = (uint32_t *)(ws + L.counts), *cursor = (uint32_t *)(ws + L.cursor);
+    uint32_t *misc = (uint32_t *)(ws + L.misc);
+    const bool dense = X != nullptr;
+
+    // 1. key segments
+    if (dense) {
+        offsets_kernel<<<1, 1, 0, s>>>(nullptr, F, n, seg_off, blk_off);
+        if (n > 0) {
+            dim3 grid((unsigned)((n + kTrRows - 1) / kTrRows), (unsigned)((F + kTrCols - 1) / kTrCols));
+            dense_keys_kernel<<<grid, 256, 0, s>>>(X, n, F, keys_a);
+        }
+    } else {
+        Q_HIP(gbt_launch_fill_u64(s, (uint64_t *)counts, 0, (int64_t)(gbt_align((size_t)F * 4) / 8)));
+        Q_HIP(gbt_launch_fill_u64(s, (uint64_t *)cursor, 0, (int64_t)(gbt_align((size_t)F * 4) / 8)));
+        if (n_values > 0) csr_count_kernel<<<grid_for(n_values, 1024, 4096), 256, 0, s>>>(indices, n_values, F, counts);
+        offsets_kernel<<<1, 1, 0, s>>>(counts, F, 0, seg_off, blk_off);
+        if (n_values > 0)
+            csr_scatter_kernel<<<grid_for(n_values, 1024, 4096), 256, 0, s>>>(indices, values, n_values, F, seg_off,
+                                                                              cursor, keys_a);
+    }
+    Q_HIP(hipGetLastError());
+    // number of sort tiles
+    Q_HIP(hipMemcpyAsync(ctx->pinned + GBT_STAGING_BYTES / 2, blk_off + F, 4, hipMemcpyDeviceToHost, s));
+    Q_HIP(hipStreamSynchronize(s));
+    uint32_t n_tiles;
+    memcpy(&n_tiles, ctx->pinned + GBT_STAGING_BYTES / 2, 4);
+    if ((int64_t)n_tiles > L.max_tiles) {
+        *status = gbt_fail(ctx, GBT_EINVAL, "gbt_quantise: inconsistent input (tile count)");
+        return hipSuccess;
+    }
+
+    // 2. four stable 8-bit passes: a -> b -> a -> b -> a
+    uint32_t *src = keys_a, *dst = keys_b;
+    for (int pass = 0; pass < 4 && n_tiles > 0; ++pass) {
+        const int shift = pass * 8;
+        sort_hist_kernel<<<n_tiles, kSortBlock, 0, s>>>(src, seg_off, blk_off, F, shift, tile_hist);
+        sort_scan_kernel<<<F, 256, 0, s>>>(blk_off, tile_hist);
+        sort_scatter_kernel<<<n_tiles, kSortBlock, 0, s>>>(src, dst, seg_off, blk_off, F, shift, tile_hist);
+        uint32_t *t = src;
+        src = dst;
+        dst = t;
+    }
+    Q_HIP(hipGetLastError());
+
+    // 3. cuts
+    cuts_kernel<<<(F + 63) / 64, 64, 0, s>>>(src, seg_off, F, B, cuts, nb);
+    Q_HIP(hipGetLastError());
+    std::vector<int32_t> hnb((size_t)F);
+    Q_HIP(hipMemcpyAsync(hnb.data(), nb, (size_t)F * 4, hipMemcpyDeviceToHost, s));
+    Q_HIP(hipStreamSynchronize(s));
+    int32_t miss = 1;
+    for (int f = 0; f < F; ++f) miss = hnb[f] > miss ? hnb[f] : miss;
+    if (miss > 65535) {
+        *status = gbt_fail(ctx, GBT_EUNSUPPORTED, "gbt_quantise: %d bins do not fit a 16-bit symbol", miss);
+        return hipSuccess;
+    }
+
+    // 4. symbols
+    Q_HIP(gbt_launch_fill_u64(s, (uint64_t *)misc, 0, 1));
+    if (n > 0) {
+        if (dense) {
+            bin_dense_kernel<<<grid_for(n * (int64_t)F, 1024, 16384), 256, 0, s>>>(X, n * (int64_t)F, F, B, cuts, nb,
+                                                                                    (uint32_t)miss, sym, misc);
+        } else {
+            fill_u16_kernel<<<grid_for(n * (int64_t)F, 2048, 16384), 256, 0, s>>>(sym, (uint16_t)miss,
+                                                                                   n * (int64_t)F);
+            bin_csr_kernel<<<grid_for(n, 256, 16384), 256, 0, s>>>(indptr, indices, values, n, n_values, F, B, cuts,
+                                                                   nb, (uint32_t)miss, sym, misc);
+        }
+    }
+    Q_HIP(hipGetLastError());
+    Q_HIP(hipMemcpyAsync(ctx->pinned + GBT_STAGING_BYTES / 2, misc, 4, hipMemcpyDeviceToHost, s));
+    Q_HIP(hipStreamSynchronize(s));
+    uint32_t mx;
+    memcpy(&mx, ctx->pinned + GBT_STAGING_BYTES / 2, 4);
+    *max_value = (int32_t)mx;
+    *missing_sym = miss;
+    return hipSuccess;
+}

@@ -1,0 +1,177 @@
+// EvaluateSplit (Alg. 1; Sec. 2.3: "the split gain may be calculated for each
+// feature and each quantile by performing a scan over the gradient histogram ...
+// a parallel prefix sum").
+//
+// One workgroup per node; each wave takes whole features.  For a feature the
+// wave first reduces the bins to get the node's missing mass for that feature,
+// then runs an inclusive wave-level prefix scan (64 bins per step, carry between
+// steps) over the exact int64 sums and prices every (bin, direction) candidate
+// in fp64.  The best candidate is kept per lane in candidate order, so a strict
+// '>' keeps the first of equal gains; lanes and waves are then merged with
+// (gain descending, candidate index ascending).
+//
+// Compiled with -ffp-contract=off: the gain must be the same sequence of
+// rounded fp64 operations a plain C compiler produces.
+#include "gbt_internal.h"
+
+#include <math.h>
+
+namespace {
+
+constexpr int kEvalBlock = 256;
+constexpr int kEvalWaves = kEvalBlock / 64;
+
+__device__ inline int64_t shfl_i64(int64_t v, int src) {
+    int lo = __shfl((int)(v & 0xffffffff), src);
+    int hi = __shfl((int)(v >> 32), src);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+__device__ inline int64_t shfl_up_i64(int64_t v, int d) {
+    int lo = __shfl_up((int)(v & 0xffffffff), d);
+    int hi = __shfl_up((int)(v >> 32), d);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+__device__ inline int64_t shfl_xor_i64(int64_t v, int m) {
+    int lo = __shfl_xor((int)(v & 0xffffffff), m);
+    int hi = __shfl_xor((int)(v >> 32), m);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+__device__ inline double shfl_xor_f64(double v, int m) {
+    return __longlong_as_double(shfl_xor_i64(__double_as_longlong(v), m));
+}
+
+struct Best {
+    double gain;
+    uint32_t key;   // (feature * B + bin) * 2 + direction; 0xffffffff = none
+    int64_t GLq, HLq;
+};
+
+__device__ inline bool better(double ga, uint32_t ka, double gb, uint32_t kb) {
+    return ga > gb || (ga == gb && ka < kb);
+}
+
+__global__ __launch_bounds__(kEvalBlock) void eval_kernel(
+    const int64_t *__restrict__ pool, const EvalNode *__restrict__ nodes, const int32_t *__restrict__ nb,
+    int F, int B, double inv_sg, double inv_sh, double lambda, double mcw, gbt_split *__restrict__ out) {
+    const EvalNode nd = nodes[blockIdx.x];
+    const int64_t *hist = pool + nd.hist_off;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t Gq = nd.Gq, Hq = nd.Hq;
+    const double G = (double)Gq * inv_sg, H = (double)Hq * inv_sh;
+    const double parent = G * G / (H + lambda);
+
+    Best best;
+    best.gain = -INFINITY;
+    best.key = 0xffffffffu;
+    best.GLq = 0;
+    best.HLq = 0;
+
+    for (int f = wave; f < F; f += kEvalWaves) {
+        int nbf = nb[f];
+        if (nbf > B) nbf = B;
+        const int64_t *hf = hist + (int64_t)f * B * 2;
+        // pass 1: the feature's present mass -> the node's missing mass
+        int64_t sg = 0, sh = 0;
+        for (int b = lane; b < nbf; b += 64) {
+            sg += hf[2 * b];
+            sh += hf[2 * b + 1];
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            sg += shfl_xor_i64(sg, o);
+            sh += shfl_xor_i64(sh, o);
+        }
+        const int64_t Gm = Gq - sg, Hm = Hq - sh;
+        const bool has_missing = (Gm != 0) || (Hm != 0);
+        // pass 2: inclusive scan over bins, 64 at a time
+        int64_t cg = 0, ch = 0;
+        for (int b0 = 0; b0 < nbf; b0 += 64) {
+            const int b = b0 + lane;
+            int64_t pg = b < nbf ? hf[2 * b] : 0;
+            int64_t ph = b < nbf ? hf[2 * b + 1] : 0;
+            for (int d = 1; d < 64; d <<= 1) {
+                int64_t tg = shfl_up_i64(pg, d), th = shfl_up_i64(ph, d);
+                if (lane >= d) {
+                    pg += tg;
+                    ph += th;
+                }
+            }
+            pg += cg;
+            ph += ch;
+            cg = shfl_i64(pg, 63);
+            ch = shfl_i64(ph, 63);
+            if (b < nbf) {
+                for (int dir = 0; dir <= (has_missing ? 1 : 0); ++dir) {
+                    if (b == nbf - 1 && (dir == 1 || !has_missing)) continue;   // right side empty
+                    const int64_t GLq = pg + (dir ? Gm : 0), HLq = ph + (dir ? Hm : 0);
+                    const double GL = (double)GLq * inv_sg, HL = (double)HLq * inv_sh;
+                    const double GR = (double)(Gq - GLq) * inv_sg, HR = (double)(Hq - HLq) * inv_sh;
+                    if (!(HL >= mcw) || !(HR >= mcw)) continue;
+                    const double a = GL * GL / (HL + lambda);
+                    const double c = GR * GR / (HR + lambda);
+                    const double gain = (a + c) - parent;
+                    if (gain > best.gain) {
+                        best.gain = gain;
+                        best.key = ((uint32_t)f * (uint32_t)B + (uint32_t)b) * 2u + (uint32_t)dir;
+                        best.GLq = GLq;
+                        best.HLq = HLq;
+                    }
+                }
+            }
+        }
+    }
+
+    // merge lanes, then waves
+    for (int o = 32; o > 0; o >>= 1) {
+        double g2 = shfl_xor_f64(best.gain, o);
+        uint32_t k2 = (uint32_t)__shfl_xor((int)best.key, o);
+        int64_t gl2 = shfl_xor_i64(best.GLq, o), hl2 = shfl_xor_i64(best.HLq, o);
+        if (better(g2, k2, best.gain, best.key)) {
+            best.gain = g2;
+            best.key = k2;
+            best.GLq = gl2;
+            best.HLq = hl2;
+        }
+    }
+    __shared__ Best wb[kEvalWaves];
+    if (lane == 0) wb[wave] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Best r = wb[0];
+        for (int w = 1; w < kEvalWaves; ++w)
+            if (better(wb[w].gain, wb[w].key, r.gain, r.key)) r = wb[w];
+        gbt_split s;
+        if (r.key == 0xffffffffu) {
+            s.feature = -1;
+            s.bin = 0;
+            s.default_left = 0;
+            s.valid = 0;
+            s.gain = -INFINITY;
+            s.GL = s.HL = s.GR = s.HR = 0.0;
+            s.GLq = s.HLq = 0;
+        } else {
+            const uint32_t fb = r.key >> 1;
+            s.feature = (int32_t)(fb / (uint32_t)B);
+            s.bin = (int32_t)(fb % (uint32_t)B);
+            s.default_left = (int32_t)(r.key & 1u);
+            s.valid = 1;
+            s.gain = r.gain;
+            s.GLq = r.GLq;
+            s.HLq = r.HLq;
+            s.GL = (double)r.GLq * inv_sg;
+            s.HL = (double)r.HLq * inv_sh;
+            s.GR = (double)(Gq - r.GLq) * inv_sg;
+            s.HR = (double)(Hq - r.HLq) * inv_sh;
+        }
+        out[blockIdx.x] = s;
+    }
+}
+
+}  // namespace
+
+hipError_t gbt_launch_eval(hipStream_t s, const int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
+                           const int32_t *nb, int F, int B, double inv_sg, double inv_sh, double lambda,
+                           double mcw, gbt_split *out) {
+    if (n_nodes <= 0) return hipSuccess;
+    eval_kernel<<<n_nodes, kEvalBlock, 0, s>>>(hist_pool, nodes, nb, F, B, inv_sg, inv_sh, lambda, mcw, out);
+    return hipGetLastError();
+}

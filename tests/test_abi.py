@@ -1,0 +1,51 @@
+"""The C-ABI library loads and exports every symbol include/gbt.h declares
+(no compute calls: this runs without a GPU)."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_1806_11248_amd as g
+    if not os.path.exists(g.LIB_PATH):
+        from paper_1806_11248_amd import build
+        build.build()
+    return g.load()
+
+
+def test_header_symbols_are_exported(lib):
+    import paper_1806_11248_amd as g
+    hdr = open(os.path.join(ROOT, "include", "gbt.h")).read()
+    declared = sorted(set(re.findall(r"GBT_API[^;(]*?\b(gbt_\w+)\s*\(", hdr)))
+    assert len(declared) >= 20
+    assert sorted(g.SYMBOLS) == declared
+    for s in declared:
+        assert hasattr(lib, s), s
+
+
+def test_host_only_calls(lib):
+    import paper_1806_11248_amd as g
+    assert lib.gbt_version().decode().startswith("libgbt")
+    # Sec. 2.2: bit length of the largest symbol
+    for mv, b in {0: 1, 1: 1, 15: 4, 63: 6, 255: 8, 256: 9, 65535: 16}.items():
+        assert g.bits_for(mv) == b
+    assert g.packed_words(10_000, 8, 4) * 4 == 40_004
+    assert g.packed_words(115_000_000, 13, 8) == (115_000_000 * 13 * 8 + 31) // 32 + 1
+    assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 16, 3) > 1000 * 16
+    assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 16, 99) == 0     # unsupported depth
+    assert lib.gbt_partition_workspace_bytes(10_000) >= 40_000
+    # a null context is refused, not dereferenced
+    assert lib.gbt_destroy(None) == g.binding.EINVAL
+    assert lib.gbt_gradients(None, 0, None, None, 0, None) == g.binding.EINVAL
+
+
+def test_struct_layouts_match_header():
+    import ctypes as C
+    import paper_1806_11248_amd as g
+    assert C.sizeof(g.binding.Split) == 72
+    assert C.sizeof(g.binding.Params) == 48
+    assert C.sizeof(g.binding.Tree) == 8 + 11 * 8

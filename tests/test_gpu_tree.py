@@ -1,0 +1,147 @@
+"""GPU parity of whole trees and of the boosting loop against the CPU oracle
+(-m gpu).  Every input goes through the GPU's own quantise -> compress first, and
+each stage is compared with the oracle before the next one is trusted."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from gpu_util import dev, host_u32, oracle_prep, tree_kw
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_1806_11248_amd as g
+    c = g.Context(0)
+    yield c
+    c.close()
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def gpu_prep(ctx, oracle, d, use_csr=False):
+    """GPU quantise + compress of workload d, checked bit-exactly against the oracle."""
+    X = d["X"]
+    B = d["params"]["max_bins"]
+    o = oracle_prep(oracle, X, B)
+    if use_csr:
+        indptr, indices, values = synth.dense_to_csr(X)
+        cuts, nb, sym, mv, ms = ctx.quantise(csr=(dev(indptr), dev(indices), dev(values)), max_bins=B,
+                                             n=X.shape[0], F=X.shape[1])
+    else:
+        cuts, nb, sym, mv, ms = ctx.quantise(dev(X), max_bins=B)
+    assert np.array_equal(nb.cpu().numpy(), o["nb"])
+    assert np.array_equal(cuts.cpu().numpy(), o["cuts"])
+    assert (mv, ms) == (o["max_value"], o["missing"])
+    packed, bits = ctx.compress(sym, mv)
+    assert bits == o["bits"]
+    assert np.array_equal(host_u32(packed), o["words"])
+    del sym
+    return o, dict(cuts=cuts, nb=nb, packed=packed, bits=bits, missing=ms)
+
+
+def grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, nodes=None):
+    import paper_1806_11248_amd as g
+    params = g.make_params(max_depth=p["max_depth"], max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
+                           min_child_weight=p["min_child_weight"])
+    gp_t = dev(gp)
+    tree, row_idx, leaf = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"],
+                                        gdev["cuts"], gp_t, params)
+    _, scale = ctx.gpair_fixed(gp_t)
+    rep = oracle.replay_tree(tree, o["sym"], o["nb"], o["missing"], gp, **tree_kw(p),
+                             sum_atol_per_row=0.5 / min(scale), nodes=nodes)
+    assert rep["ok"], rep["errors"][:5]
+    assert np.array_equal(host_u32(row_idx), rep["row_idx"])           # partitions: bit-exact
+    assert np.array_equal(leaf.cpu().numpy(), rep["leaf_of_row"])
+    nn = tree["n_nodes"]
+    for i in range(nn):                                                  # thresholds are the cuts
+        if tree["feature"][i] >= 0:
+            f, b = tree["feature"][i], tree["bin"][i]
+            want = o["cuts"][f, b] if b < p["max_bins"] - 1 else np.inf
+            assert tree["threshold"][i] == want
+    return tree, rep
+
+
+CASES = [  # config, rows, kwargs, csr
+    (1, None, {}, False),                 # the tiny workload at its full size: 10,000 x 8, 4-bit, depth 3
+    (2, 60_000, {}, False),               # 8-bit, 28 features, depth 6
+    (3, 60_000, {}, True),                # 9-bit with missing values, CSR input, depth 8
+    (4, 200_000, {}, False),              # 8-bit, 13 features (skewed categorical columns), depth 8
+    (5, 6_000, {"F": 300}, False),        # 6-bit, wide, depth 10: many small nodes, feature tiles
+]
+
+
+@pytest.mark.parametrize("cfg,n,kw,csr", CASES)
+def test_tree_matches_oracle(ctx, oracle, cfg, n, kw, csr):
+    d = synth.make(cfg, n, **kw)
+    p = d["params"]
+    X = d["X"]
+    n, F = X.shape
+    _say(f"tree C{cfg} n={n} F={F} depth={p['max_depth']}")
+    o, gdev = gpu_prep(ctx, oracle, d, use_csr=csr)
+    if p["objective"] == "given":
+        gp = np.stack([d["g"], d["h"]], 1)
+    else:
+        gp = oracle.gradients(p["objective"], np.zeros(n, np.float32), d["y"])
+        gp_gpu = ctx.gradients(p["objective"], dev(np.zeros(n, np.float32)), dev(d["y"])).cpu().numpy()
+        assert np.allclose(gp_gpu, gp, rtol=1e-6, atol=1e-7)
+    tree, rep = grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
+    # an independently grown oracle tree has the same structure unless a legal tie intervened
+    t_ref, rows_ref, leaf_ref = oracle.grow_tree(o["sym"], o["nb"], o["cuts"], o["missing"], gp, **tree_kw(p))
+    if rep["identical"]:
+        nn = t_ref["n_nodes"]
+        assert tree["n_nodes"] == nn
+        for k in ("feature", "bin", "default_left", "left", "right", "n_rows"):
+            assert np.array_equal(tree[k][:nn], t_ref[k][:nn]), k
+        assert np.allclose(tree["weight"][:nn], t_ref["weight"][:nn], rtol=1e-5, atol=1e-9)
+        assert np.allclose(tree["gain"][:nn], t_ref["gain"][:nn], rtol=1e-5, atol=1e-7)
+    _say(f"  nodes={tree['n_nodes']} identical={rep['identical']} ties={len(rep['ties'])}")
+
+    # prediction: packed symbols, raw floats, oracle -- same leaves, same margins
+    m0 = np.zeros(n, np.float32)
+    ref = oracle.predict_sym(tree, o["sym"], o["missing"], 0.3, m0)
+    got_p = ctx.predict([tree], dev(m0), 0.3, packed=gdev["packed"], bits=gdev["bits"], missing_sym=gdev["missing"],
+                        n=n, F=F).cpu().numpy()
+    got_x = ctx.predict([tree], dev(m0), 0.3, X=dev(X)).cpu().numpy()
+    assert np.array_equal(got_p, ref) and np.array_equal(got_x, ref)
+
+
+def test_depth_zero_and_gamma(ctx, oracle):
+    d = synth.make(1)
+    p = dict(d["params"])
+    n, F = d["X"].shape
+    o, gdev = gpu_prep(ctx, oracle, d)
+    gp = np.stack([d["g"], d["h"]], 1)
+    for change in (dict(max_depth=0), dict(gamma=1e9), dict(min_child_weight=1e9)):
+        q = dict(p); q.update(change)
+        _say(f"degenerate tree {change}")
+        tree, rep = grow_and_judge(ctx, oracle, o, gdev, gp, q, n, F)
+        assert tree["n_nodes"] == 1 and tree["feature"][0] == -1
+
+
+def test_boosting_rounds_in_lock_step(ctx, oracle):
+    """Each round: the GPU's gradients are checked against the oracle's, then the
+    SAME fp32 pairs feed both tree builders; margins are compared after the update."""
+    import paper_1806_11248_amd as g
+    for cfg, n, rounds, csr in ((2, 50_000, 4, False), (3, 50_000, 3, True)):
+        d = synth.make(cfg, n)
+        p = d["params"]
+        n, F = d["X"].shape
+        o, gdev = gpu_prep(ctx, oracle, d, use_csr=csr)
+        y_t = dev(d["y"])
+        margin_gpu = torch.zeros(n, dtype=torch.float32, device="cuda")
+        margin_ref = np.zeros(n, np.float32)
+        for r in range(rounds):
+            _say(f"boost C{cfg} round {r}")
+            gp_ref = oracle.gradients(p["objective"], margin_ref, d["y"])
+            gp_gpu = ctx.gradients(p["objective"], margin_gpu, y_t).cpu().numpy()
+            assert np.allclose(gp_gpu, gp_ref, rtol=1e-5, atol=1e-6)
+            tree, rep = grow_and_judge(ctx, oracle, o, gdev, gp_ref, p, n, F)
+            ctx.predict([tree], margin_gpu, p["eta"], packed=gdev["packed"], bits=gdev["bits"],
+                        missing_sym=gdev["missing"], n=n, F=F)
+            margin_ref = oracle.predict_sym(tree, o["sym"], o["missing"], p["eta"], margin_ref)
+            assert np.allclose(margin_gpu.cpu().numpy(), margin_ref, rtol=1e-5, atol=1e-6)
