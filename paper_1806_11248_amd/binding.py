@@ -242,18 +242,25 @@ class Context:
         self._check(self.lib.gbt_gpair_fixed(self.h, _ptr(gpair), n, _ptr(gq), scale, _ptr(ws), ws.numel()))
         return gq, (scale[0], scale[1])
 
+    def _rows_ptr(self, row_idx):
+        # NULL means "all rows"; an empty list still needs a non-null address
+        if row_idx is not None and row_idx.numel() == 0:
+            return _ptr(self.workspace("small", 4096))
+        return _ptr(row_idx)
+
     def sum_gpair(self, gq, row_idx=None):
         n_rows = gq.shape[0] if row_idx is None else row_idx.numel()
         out = (C.c_int64 * 2)()
         ws = self.workspace("small", 4096)
-        self._check(self.lib.gbt_sum_gpair(self.h, _ptr(gq), _ptr(row_idx), n_rows, out, _ptr(ws), ws.numel()))
+        self._check(self.lib.gbt_sum_gpair(self.h, _ptr(gq), self._rows_ptr(row_idx), n_rows, out, _ptr(ws),
+                                           ws.numel()))
         return int(out[0]), int(out[1])
 
     def build_hist(self, packed, bits, n, F, B, missing_sym, gq, row_idx=None, out=None):
         hist = out if out is not None else self.empty((F, B, 2), torch.int64)
         n_rows = 0 if row_idx is None else row_idx.numel()
-        self._check(self.lib.gbt_build_hist(self.h, _ptr(packed), bits, n, F, B, missing_sym, _ptr(row_idx),
-                                            n_rows, _ptr(gq), _ptr(hist)))
+        self._check(self.lib.gbt_build_hist(self.h, _ptr(packed), bits, n, F, B, missing_sym,
+                                            self._rows_ptr(row_idx), n_rows, _ptr(gq), _ptr(hist)))
         return hist
 
     def hist_subtract(self, parent, child):

@@ -195,8 +195,8 @@ extern "C" int64_t gbt_packed_words(int64_t n, int32_t F, int32_t bits) {
 extern "C" int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, uint32_t max_value,
                                 uint32_t *packed_out, int32_t *bits_out) {
     if (!ctx) return GBT_EINVAL;
-    GBT_REQUIRE(ctx, sym && packed_out && bits_out, GBT_EINVAL, "NULL argument");
     GBT_REQUIRE(ctx, n >= 0 && F >= 1, GBT_EINVAL, "bad shape");
+    GBT_REQUIRE(ctx, (sym || n == 0) && packed_out && bits_out, GBT_EINVAL, "NULL argument");
     int32_t bits = gbt_bits(max_value);
     GBT_REQUIRE(ctx, bits <= GBT_MAX_BITS, GBT_EUNSUPPORTED, "max_value %u needs %d bits", max_value, bits);
     GBT_HIP(ctx, gbt_launch_compress(ctx->stream, sym, n * (int64_t)F, bits, packed_out,
@@ -209,8 +209,8 @@ extern "C" int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, in
 extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *margin, const float *label,
                                  int64_t n, float *gpair_out) {
     if (!ctx) return GBT_EINVAL;
-    GBT_REQUIRE(ctx, margin && label && gpair_out, GBT_EINVAL, "NULL argument");
     GBT_REQUIRE(ctx, n >= 0, GBT_EINVAL, "n < 0");
+    GBT_REQUIRE(ctx, n == 0 || (margin && label && gpair_out), GBT_EINVAL, "NULL argument");
     GBT_REQUIRE(ctx, objective == GBT_OBJ_SQUARED || objective == GBT_OBJ_LOGISTIC, GBT_EINVAL,
                 "unknown objective %d", objective);
     GBT_HIP(ctx, gbt_launch_gradients(ctx->stream, objective, margin, label, n, gpair_out));
