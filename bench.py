@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantised-histogram tree-construction path on one MI355X.
+
+Workload: the 115,000,000 x 13 "large tabular" configuration (8-bit packing,
+256 bins, depth 8, lambda 1, logistic objective) on seeded synthetic data of
+that shape.  One step is one boosting iteration of the whole hot path with all
+inputs resident in HBM: gradients (Eq. 1-2) -> grow one tree (root histogram,
+per level: split evaluation, row partition, histograms of the smaller
+children, sibling subtraction) -> margin update by prediction.  Quantisation and
+compression run once before the loop, as in the paper's pipeline, and are
+reported separately.
+
+Prints one JSON line.  `value` = rows*features per second of a whole step;
+`roofline` = achieved algorithmic HBM bandwidth of the histogram kernel over
+all its launches in the timed region (HIP events around each launch on the
+library's stream); `roofline_root` the same for the root-node launch alone;
+`cpu_baseline` = the CPU oracle's tree on a bounded row sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def load_workload(cfg, rows, cache_dir):
+    import numpy as np
+    import synth
+    if cache_dir:
+        os.makedirs(cache_dir, exist_ok=True)
+        fx = os.path.join(cache_dir, f"c{cfg}_{rows}_X.npy")
+        fy = os.path.join(cache_dir, f"c{cfg}_{rows}_y.npy")
+        if os.path.exists(fx) and os.path.exists(fy):
+            d = synth.make(cfg, 1)
+            d["X"], d["y"] = np.load(fx), np.load(fy)
+            return d
+    d = synth.make(cfg, rows)
+    if cache_dir:
+        np.save(fx, d["X"])
+        np.save(fy, d["y"])
+    return d
+
+
+def cpu_baseline(d, sample_rows):
+    """The oracle's tree (its own quantisation, fp64 histograms, exhaustive
+    split search) on the first `sample_rows` rows, timed on the host cores."""
+    import numpy as np
+    import oracle
+    p = d["params"]
+    X = np.ascontiguousarray(d["X"][:sample_rows])
+    y = d["y"][:sample_rows]
+    n, F = X.shape
+    t0 = time.time()
+    cuts, nb = oracle.cuts(X, p["max_bins"])
+    sym, missing, _ = oracle.bin_matrix(X, cuts, nb)
+    t_q = time.time() - t0
+    gp = oracle.gradients(p["objective"], np.zeros(n, np.float32), y)
+    t0 = time.time()
+    oracle.hist(sym, p["max_bins"], missing, None, gp)
+    t_hist = time.time() - t0
+    t0 = time.time()
+    tree, _, _ = oracle.grow_tree(sym, nb, cuts, missing, gp, max_depth=p["max_depth"], max_bins=p["max_bins"],
+                                  lam=p["lam"], gamma=p["gamma"], min_child_weight=p["min_child_weight"])
+    t_tree = time.time() - t0
+    threads = min(F, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+    return {"value": n * F / t_tree, "unit": "rows*features/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {n} rows of the workload: one depth-{p['max_depth']} tree in {t_tree:.2f} s "
+                      f"(root histogram alone {t_hist:.3f} s = {n * F / t_hist:.3g} rows*features/s; "
+                      f"quantisation {t_q:.2f} s not included)",
+            "seconds_per_tree": t_tree, "hist_root_rows_features_per_s": n * F / t_hist}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4: 115M x 13)")
+    ap.add_argument("--rows", type=int, default=None, help="fewer rows than the workload's own size")
+    ap.add_argument("--data-cache", default=None, help="directory to keep the generated inputs in")
+    ap.add_argument("--cpu-sample-rows", type=int, default=4_000_000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_1806_11248_amd as g
+
+    t0 = time.time()
+    d = load_workload(a.config, a.rows, a.data_cache)
+    p = d["params"]
+    X = d["X"]
+    n, F = X.shape
+    log(f"workload C{a.config}: {n} x {F}, generated in {time.time() - t0:.1f} s")
+    if p["objective"] == "given":
+        raise SystemExit("workload 1 carries its own gradient pairs; bench configs 2..5")
+
+    ctx = g.Context(0)
+    dev = ctx.device
+    # ---- one-off preprocessing: quantise + compress (Sec. 2.1, 2.2)
+    t0 = time.time()
+    Xd = torch.from_numpy(X).to(dev)
+    torch.cuda.synchronize()
+    t_h2d = time.time() - t0
+    t0 = time.time()
+    cuts, nb, sym, mv, ms = ctx.quantise(Xd, max_bins=p["max_bins"])
+    torch.cuda.synchronize()
+    t_quant = time.time() - t0
+    t0 = time.time()
+    packed, bits = ctx.compress(sym, mv)
+    torch.cuda.synchronize()
+    t_comp = time.time() - t0
+    del Xd, sym
+    torch.cuda.empty_cache()
+    log(f"H2D {t_h2d:.2f} s, quantise {t_quant * 1e3:.1f} ms, compress {t_comp * 1e3:.1f} ms, bits={bits}")
+
+    y = torch.from_numpy(d["y"]).to(dev)
+    margin = torch.zeros(n, dtype=torch.float32, device=dev)
+    gp = torch.empty((n, 2), dtype=torch.float32, device=dev)
+    row_idx = torch.empty(n, dtype=torch.int32, device=dev)
+    leaf = torch.empty(n, dtype=torch.int32, device=dev)
+    params = g.make_params(max_depth=p["max_depth"], max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
+                           min_child_weight=p["min_child_weight"], eta=p["eta"], objective=p["objective"])
+    single_tree = p["rounds"] == 1   # such a workload is ONE tree from margin 0: every step repeats exactly that
+    eta = p["eta"]
+    trees = []
+
+    def step():
+        if single_tree:
+            margin.zero_()
+        ctx.gradients(p["objective"], margin, y, out=gp)
+        tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, row_idx_out=row_idx, leaf_out=leaf)
+        ctx.predict([tree], margin, eta, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
+        trees.append(tree)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    ctx.profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    ms_per_step = dt * 1e3 / a.steps
+    log("per-class device ms per step: " +
+        ", ".join(f"{k}={v['ms'] / a.steps:.3f}" for k, v in prof.items()))
+    log(f"nodes per tree: {[t['n_nodes'] for t in trees[-a.steps:]]}")
+
+    def roof(classes):
+        ms_ = sum(prof[c]["ms"] for c in classes)
+        by = sum(prof[c]["bytes"] for c in classes)
+        launches = sum(prof[c]["launches"] for c in classes)
+        if ms_ <= 0:
+            return None
+        ach = by / (ms_ * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
+                "traffic": None, "kernel": "hist_generic_kernel", "launches": launches,
+                "avg_launch_ms": ms_ / max(launches, 1), "algorithmic_bytes_per_launch": by / max(launches, 1)}
+
+    roofline = roof(["hist_root", "hist_node"])
+    roofline_root = roof(["hist_root"])
+    root_ms = prof["hist_root"]["ms"] / max(prof["hist_root"]["launches"], 1)
+
+    out = {
+        "metric": "histogram-tree build throughput: rows*features/s of one boosting step "
+                  "(gradients + one depth-%d tree + margin update)" % p["max_depth"],
+        "value": n * F / (ms_per_step * 1e-3),
+        "unit": "rows*features/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64 fixed-point sums of fp32 gradient pairs; fp64 gain",
+        "data": "synthetic",
+        "config": {"workload": f"C{a.config}: {n} rows x {F} features, {p['max_bins']} bins, {bits}-bit packing, "
+                               f"depth {p['max_depth']}, lambda {p['lam']}, {p['objective']} objective",
+                   "rows": n, "features": F, "bits": bits, "max_depth": p["max_depth"]},
+        "seconds_per_tree": ms_per_step * 1e-3,
+        "hist_root_ms": root_ms,
+        "hist_root_rows_features_per_s": (n * F / (root_ms * 1e-3)) if root_ms > 0 else None,
+        "roofline": roofline,
+        "roofline_root": roofline_root,
+        "device_ms_per_step": {k: v["ms"] / a.steps for k, v in prof.items()},
+        "preprocess_ms": {"quantise": t_quant * 1e3, "compress": t_comp * 1e3, "h2d_raw_matrix": t_h2d * 1e3},
+    }
+    if not a.no_cpu_baseline:
+        t0 = time.time()
+        out["cpu_baseline"] = cpu_baseline(d, min(a.cpu_sample_rows, n))
+        log(f"cpu baseline in {time.time() - t0:.1f} s")
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

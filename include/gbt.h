@@ -27,11 +27,12 @@
  *    rows back to back without padding, unused tail bits zero, followed by one
  *    zero word (so an 8-byte read at the last element stays in bounds).
  *    bits = number of bits of the largest symbol present, 1..16.
- *  - Gradient pairs: float2 (g, h) per row.  Histograms are summed in 64-bit
- *    fixed point: each g is rounded once to an int32 multiple of 1/scale_g
- *    (scale a power of two with |g*scale_g| <= 2^30 for every row; same for h),
- *    and all later sums are exact integers, so a histogram does not depend on
- *    the order of accumulation and "parent - child" is exactly the sibling.
+ *  - Gradient pairs: float2 (g, h) per row, h >= 0.  Histograms are summed in
+ *    64-bit fixed point: each g is rounded once to an int32 multiple of
+ *    1/scale_g and each h to a multiple of 1/scale_h (scales are powers of two
+ *    with |g*scale_g| <= 2^26 and h*scale_h <= 2^22 for every row), and all
+ *    later sums are exact integers, so a histogram does not depend on the order
+ *    of accumulation and "parent - child" is exactly the sibling.
  *  - Histogram of one node: int64 hist[F][B][2] (g then h), B = max_bins.
  */
 #ifndef GBT_H
@@ -160,7 +161,8 @@ GBT_API int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *marg
 
 /* Rounds gpair[n] [dev] to fixed point: gq_out [dev] int32[n][2] =
  * (rint(g*scale[0]), rint(h*scale[1])), scale_out [host] double[2] the two
- * powers of two (chosen from max|g|, max|h| over the n rows).
+ * powers of two (chosen from max|g|, max h over the n rows).  A non-finite
+ * value or a negative h is refused with GBT_EINVAL.
  * workspace [dev] >= 4096 bytes.  Synchronises the stream. */
 GBT_API int32_t gbt_gpair_fixed(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq_out,
                         double *scale_out, void *workspace, size_t workspace_bytes);
@@ -178,7 +180,7 @@ GBT_API int32_t gbt_sum_gpair(gbt_ctx *ctx, const int32_t *gq, const uint32_t *r
  *   B                  : bin stride (max_bins); every non-missing symbol < B
  *   row_idx [dev]      : the node's rows (uint32 ids < n), NULL = all n rows
  *   n_node_rows        : length of row_idx (ignored when NULL)
- *   gq [dev]           : int32[n][2] from gbt_gpair_fixed
+ *   gq [dev]           : int32[n][2] from gbt_gpair_fixed (|g| <= 2^26, 0 <= h <= 2^22)
  *   hist_out [dev]     : int64[F][B][2], overwritten
  * Asynchronous.
  */
@@ -268,6 +270,31 @@ GBT_API size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_tree
 GBT_API int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                     int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F,
                     double eta, float *margin_inout, void *workspace, size_t workspace_bytes);
+
+/* ---- measurement -------------------------------------------------------- */
+
+/* Kernel classes timed by the optional profiler. */
+#define GBT_PROF_HIST_ROOT 0 /* histogram of all rows (no row-id list) */
+#define GBT_PROF_HIST_NODE 1 /* histogram of listed rows (levels >= 1) */
+#define GBT_PROF_PARTITION 2 /* flag + scan + scatter */
+#define GBT_PROF_EVAL 3      /* split evaluation */
+#define GBT_PROF_SUBTRACT 4  /* histogram zero-fill and sibling subtraction */
+#define GBT_PROF_OTHER 5     /* fixed-point conversion, totals, row-id init, leaf gather */
+#define GBT_PROF_CLASSES 6
+
+typedef struct gbt_profile {
+    double ms[GBT_PROF_CLASSES];        /* device time between HIP events around the launches */
+    double bytes[GBT_PROF_CLASSES];     /* algorithmic HBM bytes of those launches (histogram:
+                                           rows * (F*bits/8 + 8 [+ 4 with a row-id list])) */
+    int64_t launches[GBT_PROF_CLASSES]; /* timed launch groups */
+} gbt_profile;
+
+/* Turns per-class device timing on or off (off by default).  While on, every
+ * launch group of gbt_build_hist and gbt_grow_tree is bracketed by HIP events on
+ * the context's stream.  gbt_profile_read synchronises the stream, adds up what
+ * was recorded since the last reset into *out [host] and resets. */
+GBT_API int32_t gbt_profile_enable(gbt_ctx *ctx, int32_t on);
+GBT_API int32_t gbt_profile_read(gbt_ctx *ctx, gbt_profile *out);
 
 #ifdef __cplusplus
 }

@@ -26,7 +26,10 @@ SYMBOLS = [
     "gbt_gradients", "gbt_gpair_fixed", "gbt_sum_gpair", "gbt_build_hist", "gbt_hist_subtract",
     "gbt_hist_export_f64", "gbt_eval_split", "gbt_partition_workspace_bytes", "gbt_partition",
     "gbt_grow_tree_workspace_bytes", "gbt_grow_tree", "gbt_predict_workspace_bytes", "gbt_predict",
+    "gbt_profile_enable", "gbt_profile_read",
 ]
+
+PROF_CLASSES = ["hist_root", "hist_node", "partition", "eval", "subtract", "other"]
 
 
 class GbtError(RuntimeError):
@@ -45,6 +48,10 @@ class Split(C.Structure):
     _fields_ = [("feature", C.c_int32), ("bin", C.c_int32), ("default_left", C.c_int32),
                 ("valid", C.c_int32), ("gain", C.c_double), ("GL", C.c_double), ("HL", C.c_double),
                 ("GR", C.c_double), ("HR", C.c_double), ("GLq", C.c_int64), ("HLq", C.c_int64)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("ms", C.c_double * 6), ("bytes", C.c_double * 6), ("launches", C.c_int64 * 6)]
 
 
 class Tree(C.Structure):
@@ -99,6 +106,8 @@ def load():
     L.gbt_partition.argtypes = [vp, vp, i32, i64, i32, vp, i64, i64, i32, i32, i32, i32, vp, sz, vp]
     L.gbt_grow_tree.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
     L.gbt_predict.argtypes = [vp, vp, i32, vp, i32, i32, vp, i64, i32, f64, vp, vp, sz]
+    L.gbt_profile_enable.argtypes = [vp, i32]
+    L.gbt_profile_read.argtypes = [vp, vp]
     _lib = L
     return L
 
@@ -188,6 +197,15 @@ class Context:
 
     def empty(self, shape, dtype):
         return torch.empty(shape, dtype=dtype, device=self.device)
+
+    # -- measurement -----------------------------------------------------------
+    def profile_enable(self, on: bool = True):
+        self._check(self.lib.gbt_profile_enable(self.h, int(on)))
+
+    def profile_read(self) -> dict:
+        p = Profile()
+        self._check(self.lib.gbt_profile_read(self.h, C.byref(p)))
+        return {nm: dict(ms=p.ms[i], bytes=p.bytes[i], launches=p.launches[i]) for i, nm in enumerate(PROF_CLASSES)}
 
     # -- Sec. 2.1 ------------------------------------------------------------
     def quantise(self, X=None, csr=None, *, max_bins: int, n=None, F=None):

@@ -44,12 +44,13 @@ int32_t check_bins(gbt_ctx *ctx, int32_t F, int32_t B) {
     return GBT_OK;
 }
 
-// Power-of-two scale s with |x|*s <= 2^30 for every |x| <= vmax.
-double fixed_scale(float vmax) {
+// Power-of-two scale s with |x|*s <= 2^top for every |x| <= vmax.
+constexpr int kGBits = 26, kHBits = 22;   // |g*scale_g| <= 2^26, h*scale_h <= 2^22: the packed LDS word's fields
+double fixed_scale(float vmax, int top) {
     if (!(vmax > 0.0f)) return 1.0;
     int e;
     frexp((double)vmax, &e);   // vmax = m * 2^e, m in [0.5, 1)
-    return ldexp(1.0, 30 - e);
+    return ldexp(1.0, top - e);
 }
 
 // Uniform job split of a dense or listed row range for the histogram kernel.
@@ -86,7 +87,7 @@ uint32_t pick_rows_per_job(const gbt_ctx *ctx, int64_t total_rows) {
     int64_t target_jobs = (int64_t)ctx->num_cu * 4;
     int64_t rpj = (total_rows + target_jobs - 1) / target_jobs;
     if (rpj < 4096) rpj = 4096;
-    if (rpj > (1 << 30)) rpj = 1 << 30;
+    if (rpj > (1 << 21)) rpj = 1 << 21;   // the per-bin event counters of the histogram kernel are 16 bits wide
     return (uint32_t)rpj;
 }
 
@@ -138,6 +139,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
     gbt_ctx *c = new (std::nothrow) gbt_ctx();
     if (!c) return GBT_ENOMEM;
     memset(c, 0, sizeof *c);
+    c->spans = new std::vector<ProfSpan>();
+    c->free_events = new std::vector<hipEvent_t>();
     c->device = device;
     c->stream = (hipStream_t)stream;
     hipError_t e = hipSetDevice(device);
@@ -146,6 +149,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
     if (e == hipSuccess && strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
         fprintf(stderr, "libgbt: device %d is %s, this library is built for gfx950 only\n", device,
                 prop.gcnArchName);
+        delete c->spans;
+        delete c->free_events;
         delete c;
         return GBT_EHIP;
     }
@@ -164,6 +169,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
     if (e != hipSuccess) {
         fprintf(stderr, "libgbt: gbt_create failed: %s\n", hipGetErrorString(e));
         (void)hipGetLastError();
+        delete c->spans;
+        delete c->free_events;
         delete c;
         return GBT_EHIP;
     }
@@ -174,11 +181,73 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
 extern "C" int32_t gbt_destroy(gbt_ctx *ctx) {
     if (!ctx) return GBT_EINVAL;
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    for (ProfSpan &sp : *ctx->spans) {
+        (void)hipEventDestroy(sp.start);
+        (void)hipEventDestroy(sp.stop);
+    }
+    for (hipEvent_t e : *ctx->free_events) (void)hipEventDestroy(e);
+    delete ctx->spans;
+    delete ctx->free_events;
     delete ctx;
     return GBT_OK;
 }
 
 extern "C" const char *gbt_last_error(const gbt_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+// --------------------------------------------------------------- profiling --
+static hipEvent_t prof_event(gbt_ctx *ctx) {
+    if (!ctx->free_events->empty()) {
+        hipEvent_t e = ctx->free_events->back();
+        ctx->free_events->pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void gbt_prof_begin(gbt_ctx *ctx, int cls, double bytes) {
+    if (!ctx->profiling) return;
+    ProfSpan sp;
+    sp.cls = cls;
+    sp.bytes = bytes;
+    sp.start = prof_event(ctx);
+    sp.stop = prof_event(ctx);
+    if (!sp.start || !sp.stop) return;
+    (void)hipEventRecord(sp.start, ctx->stream);
+    ctx->spans->push_back(sp);
+}
+
+void gbt_prof_end(gbt_ctx *ctx) {
+    if (!ctx->profiling || ctx->spans->empty()) return;
+    (void)hipEventRecord(ctx->spans->back().stop, ctx->stream);
+}
+
+extern "C" int32_t gbt_profile_enable(gbt_ctx *ctx, int32_t on) {
+    if (!ctx) return GBT_EINVAL;
+    ctx->profiling = on != 0;
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_profile_read(gbt_ctx *ctx, gbt_profile *out) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, out != nullptr, GBT_EINVAL, "NULL argument");
+    GBT_SYNC(ctx);
+    memset(out, 0, sizeof *out);
+    for (ProfSpan &sp : *ctx->spans) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sp.start, sp.stop) == hipSuccess && sp.cls >= 0 && sp.cls < GBT_PROF_CLASSES) {
+            out->ms[sp.cls] += ms;
+            out->bytes[sp.cls] += sp.bytes;
+            out->launches[sp.cls] += 1;
+        }
+        ctx->free_events->push_back(sp.start);
+        ctx->free_events->push_back(sp.stop);
+    }
+    (void)hipGetLastError();
+    ctx->spans->clear();
+    return GBT_OK;
+}
 
 // ------------------------------------------------------------- compression --
 extern "C" int32_t gbt_bits(uint32_t max_value) {
@@ -221,17 +290,18 @@ extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *m
 static int32_t gpair_fixed_impl(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq, double *scale,
                                 void *ws) {
     GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 8, hipMemcpyDeviceToHost, ctx->stream));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 12, hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
-    uint32_t bits2[2];
-    memcpy(bits2, rb(ctx), 8);
+    uint32_t bits2[3];
+    memcpy(bits2, rb(ctx), 12);
     GBT_REQUIRE(ctx, bits2[0] < 0x7f800000u && bits2[1] < 0x7f800000u, GBT_EINVAL,
                 "gradient pairs contain a non-finite value");
+    GBT_REQUIRE(ctx, bits2[2] == 0, GBT_EINVAL, "gradient pairs contain a negative hessian");
     float mg, mh;
     memcpy(&mg, &bits2[0], 4);
     memcpy(&mh, &bits2[1], 4);
-    scale[0] = fixed_scale(mg);
-    scale[1] = fixed_scale(mh);
+    scale[0] = fixed_scale(mg, kGBits);
+    scale[1] = fixed_scale(mh, kHBits);
     GBT_HIP(ctx, gbt_launch_to_fixed(ctx->stream, gpair, n, scale[0], scale[1], gq));
     return GBT_OK;
 }
@@ -420,8 +490,11 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
         if (st != GBT_OK) return st;
         dev_jobs = (HistJob *)slot;
     }
+    gbt_prof_begin(ctx, row_idx ? GBT_PROF_HIST_NODE : GBT_PROF_HIST_ROOT,
+                   (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0)));
     GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, n, F, B, (uint32_t)missing_sym, row_idx, gq, hist_out,
                                  dev_jobs, (int)jobs.size(), pl.ft));
+    gbt_prof_end(ctx);
     return GBT_OK;
 }
 
@@ -506,15 +579,19 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     GBT_HIP(ctx, hipMemcpyAsync(hcuts.data(), cuts, hcuts.size() * sizeof(float), hipMemcpyDeviceToHost, s));
 
     double scale[2];
+    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 24.0);
     st = gpair_fixed_impl(ctx, gpair, n, gq, scale, ws + L.scratch);
+    gbt_prof_end(ctx);
     if (st != GBT_OK) return st;
     const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
     const double lambda = params->lambda;
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
 
+    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
     GBT_HIP(ctx, gbt_launch_sum_gq(s, gq, nullptr, n, (int64_t *)(ws + L.scratch)));
     GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.scratch, 16, hipMemcpyDeviceToHost, s));
     GBT_HIP(ctx, gbt_launch_iota_u32(s, buf[0], n));
+    gbt_prof_end(ctx);
     if (max_depth > 0) {
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
                           (HistJob *)(ws + L.jobs));
@@ -560,9 +637,11 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
         st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
         if (st != GBT_OK) return st;
+        gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)level.size() * (double)hist_len * 8.0);
         GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)level.size(), nb, F, B,
                                      inv_sg, inv_sh, lambda, params->min_child_weight,
                                      (gbt_split *)(ws + L.splits)));
+        gbt_prof_end(ctx);
         const size_t sbytes = level.size() * sizeof(gbt_split);
         GBT_REQUIRE(ctx, sbytes <= GBT_STAGING_BYTES - kReadbackOff, GBT_EUNSUPPORTED, "level too wide");
         GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
@@ -604,10 +683,16 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         GBT_REQUIRE(ctx, (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
         if (st != GBT_OK) return st;
+        {
+            double part_rows = 0;
+            for (const PartJob &j : pjobs) part_rows += j.seg_len;
+            gbt_prof_begin(ctx, GBT_PROF_PARTITION, part_rows * (8.0 + bits / 8.0));
+        }
         GBT_HIP(ctx, gbt_launch_partition(s, packed, bits, n, F, (uint32_t)missing_sym, buf[cur], buf[cur ^ 1],
                                           (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
                                           (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
                                           (uint32_t *)(ws + L.n_left)));
+        gbt_prof_end(ctx);
         GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
         GBT_SYNC(ctx);
         const uint32_t *n_left = (const uint32_t *)rb(ctx);
@@ -655,8 +740,10 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         if (children_need_hist) {
             // ---- BuildPartialHistograms for the smaller children, siblings by subtraction
             const int32_t n_children = n_nodes - first_child;
+            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
             GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
                                              (int64_t)n_children * hist_len));
+            gbt_prof_end(ctx);
             const uint32_t rpj = pick_rows_per_job(ctx, built_rows);
             for (const Built &b : built) add_hist_jobs(hjobs, b.off, b.begin, b.len, F, pl, rpj);
             const size_t per_launch = kUploadBytes / sizeof(HistJob);
@@ -664,13 +751,18 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 const size_t nj = std::min(per_launch, hjobs.size() - j0);
                 st = upload(ctx, hjobs.data() + j0, nj * sizeof(HistJob), ws + L.jobs);
                 if (st != GBT_OK) return st;
+                gbt_prof_begin(ctx, GBT_PROF_HIST_NODE,
+                               j0 == 0 ? (double)built_rows * ((double)F * bits / 8.0 + 12.0) : 0.0);
                 GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, n, F, B, (uint32_t)missing_sym, buf[cur], gq, pool,
                                              (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
+                gbt_prof_end(ctx);
             }
             GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
             st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
             if (st != GBT_OK) return st;
+            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
             GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
+            gbt_prof_end(ctx);
         }
         level.swap(next);
     }
@@ -683,8 +775,10 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
               });
     st = upload(ctx, leaves.data(), leaves.size() * sizeof(LeafSeg), ws + L.jobs);
     if (st != GBT_OK) return st;
+    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
     GBT_HIP(ctx, gbt_launch_leaf_gather(s, buf[0], buf[1], (const LeafSeg *)(ws + L.jobs), (int)leaves.size(), n,
                                         row_idx_out, leaf_of_row_out));
+    gbt_prof_end(ctx);
     GBT_SYNC(ctx);
     tree->n_nodes = n_nodes;
     return GBT_OK;

@@ -6,7 +6,15 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <vector>
+
 #include "gbt.h"
+
+struct ProfSpan {
+    int cls;
+    double bytes;
+    hipEvent_t start, stop;
+};
 
 struct gbt_ctx {
     int device;
@@ -17,7 +25,14 @@ struct gbt_ctx {
     size_t pinned_bytes;
     size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
     char err[512];
+    bool profiling;
+    std::vector<ProfSpan> *spans;       // recorded, not yet read
+    std::vector<hipEvent_t> *free_events;
 };
+
+// Brackets a launch group with events when profiling is on (no-ops otherwise).
+void gbt_prof_begin(gbt_ctx *ctx, int cls, double bytes);
+void gbt_prof_end(gbt_ctx *ctx);
 
 #define GBT_STAGING_BYTES (8u << 20)
 

@@ -29,8 +29,9 @@ __global__ void iota_u32_kernel(uint32_t *p, int64_t count) {
 
 // max |g| and max |h| as raw float bits (non-negative floats order like their
 // bit patterns; NaN sorts above +inf, so a non-finite input is detected).
+// out2[2] becomes non-zero if any h is negative.
 __global__ void absmax_kernel(const float2 *gp, int64_t n, uint32_t *out2) {
-    uint32_t mg = 0, mh = 0;
+    uint32_t mg = 0, mh = 0, neg = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * blockDim.x) {
         float2 v = gp[i];
@@ -38,15 +39,18 @@ __global__ void absmax_kernel(const float2 *gp, int64_t n, uint32_t *out2) {
         uint32_t b = __float_as_uint(v.y) & 0x7fffffffu;
         mg = a > mg ? a : mg;
         mh = b > mh ? b : mh;
+        neg |= v.y < 0.0f ? 1u : 0u;
     }
     for (int o = 32; o > 0; o >>= 1) {
         uint32_t a = __shfl_xor(mg, o), b = __shfl_xor(mh, o);
         mg = a > mg ? a : mg;
         mh = b > mh ? b : mh;
+        neg |= __shfl_xor(neg, o);
     }
     if ((threadIdx.x & 63) == 0) {
         atomicMax(&out2[0], mg);
         atomicMax(&out2[1], mh);
+        if (neg) atomicOr(&out2[2], 1u);
     }
 }
 
@@ -225,7 +229,7 @@ hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count) {
     return hipGetLastError();
 }
 hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2) {
-    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)out2, 0, 1);
+    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)out2, 0, 2);
     if (e != hipSuccess || n <= 0) return e;
     absmax_kernel<<<grid_for(n, kBlock * 8, 2048), kBlock, 0, s>>>((const float2 *)gpair, n, out2);
     return hipGetLastError();
