@@ -492,8 +492,8 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
     }
     gbt_prof_begin(ctx, row_idx ? GBT_PROF_HIST_NODE : GBT_PROF_HIST_ROOT,
                    (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0)));
-    GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, n, F, B, (uint32_t)missing_sym, row_idx, gq, hist_out,
-                                 dev_jobs, (int)jobs.size(), pl.ft));
+    GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
+                                 (uint32_t)missing_sym, row_idx, gq, hist_out, dev_jobs, (int)jobs.size(), pl.ft));
     gbt_prof_end(ctx);
     return GBT_OK;
 }
@@ -753,7 +753,8 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 if (st != GBT_OK) return st;
                 gbt_prof_begin(ctx, GBT_PROF_HIST_NODE,
                                j0 == 0 ? (double)built_rows * ((double)F * bits / 8.0 + 12.0) : 0.0);
-                GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, n, F, B, (uint32_t)missing_sym, buf[cur], gq, pool,
+                GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
+                                             (uint32_t)missing_sym, buf[cur], gq, pool,
                                              (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
                 gbt_prof_end(ctx);
             }

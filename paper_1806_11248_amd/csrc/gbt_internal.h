@@ -115,8 +115,11 @@ hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const i
 hipError_t gbt_launch_export(hipStream_t s, const int64_t *hist, int64_t count, double inv_sg,
                              double inv_sh, double *out);
 
-hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t n, int F, int B,
-                           uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
+// packed: a bit stream whose row r starts at bit r*stride_bits (the canonical packed matrix has
+// stride_bits = F*bits; the word-aligned working copy of the grow loop 32*ceil(F*bits/32));
+// n_words: readable 32-bit words of `packed`; row_idx NULL: job rows are matrix rows.
+hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n_words,
+                           int64_t n, int B, uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
                            int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft);
 // Largest feature tile whose LDS histogram fits, and the per-job row count to aim for.
 int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B);

@@ -29,21 +29,13 @@ constexpr int kHistBlock = 1024;
 constexpr int kHShift = 30;                        // width of the h field
 constexpr uint32_t kHMask = (1u << kHShift) - 1u;
 
+__device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long long old,
+                                         unsigned long long addv, uint32_t hq);
+
 __device__ __forceinline__ void pk_add(unsigned long long *main_, uint32_t *side, int idx,
                                        unsigned long long addv, uint32_t hq) {
     const unsigned long long old = atomicAdd(&main_[idx], addv);
-    const uint32_t olo = (uint32_t)old, ohi = (uint32_t)(old >> 32);
-    // carry possible only if h-field bits 22..29 are all ones; wrap possible only if the
-    // g field is within 2^27 of +-2^33 (top seven bits of the word are 0111111 or 1000000)
-    const bool danger = ((olo & 0x3FC00000u) == 0x3FC00000u) | ((ohi + 0x82000000u) < 0x04000000u);
-    if (danger) {
-        const uint32_t carry = ((olo & kHMask) + hq) >> kHShift;
-        const unsigned long long nw = old + addv;
-        const uint32_t nhi = (uint32_t)(nw >> 32), ahi = (uint32_t)(addv >> 32);
-        const int32_t ovf = (int32_t)((ohi ^ nhi) & (ahi ^ nhi));   // sign bit set: the g field wrapped
-        const int32_t delta = ovf < 0 ? ((int32_t)nhi < 0 ? 1 : -1) : 0;
-        if (carry != 0 || delta != 0) atomicAdd(&side[idx], (uint32_t)(delta * 65536 + (int32_t)carry));
-    }
+    pk_check(side, idx, old, addv, hq);
 }
 
 __device__ __forceinline__ unsigned long long pack_pair(int2 q) {
@@ -76,14 +68,14 @@ __device__ __forceinline__ void flush_tile(const unsigned long long *main_, cons
 // ---------------------------------------------------------------------------
 template <bool LIST>
 __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
-    const uint32_t *__restrict__ packed, int64_t n_words, int bits, uint32_t inv_bits, int64_t n, int F, int B,
-    int Bp, uint32_t missing, const uint32_t *__restrict__ row_idx, const int2 *__restrict__ gq,
-    int64_t *__restrict__ pool, const HistJob *__restrict__ jobs) {
+    const uint32_t *__restrict__ packed, int64_t n_words, int bits, uint32_t inv_bits, int64_t stride_bits,
+    int64_t n, int B, int Bp, uint32_t missing, const uint32_t *__restrict__ row_idx,
+    const int2 *__restrict__ gq, int64_t *__restrict__ pool, const HistJob *__restrict__ jobs) {
     extern __shared__ unsigned long long lds[];
     const HistJob job = jobs[blockIdx.x];
     const int ft = (int)job.ft;
     unsigned long long *main_ = lds;
-    uint32_t *side = (uint32_t *)(lds + ft * Bp);
+    uint32_t *side = (uint32_t *)(lds + ft * Bp + 256);   // same layout as the 8-bit kernels (trash row unused)
     for (int i = threadIdx.x; i < ft * Bp; i += kHistBlock) {
         main_[i] = 0;
         side[i] = 0;
@@ -100,17 +92,18 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
         const int2 q = gq[r];
         const unsigned long long addv = pack_pair(q);
         const uint32_t hq = (uint32_t)q.y;
-        const uint64_t bit0 = (r * (uint64_t)F + job.f0) * (uint64_t)bits;
+        const uint64_t bit0 = r * (uint64_t)stride_bits + (uint64_t)job.f0 * (uint64_t)bits;
         const int64_t w0 = (int64_t)(bit0 >> 5);
         const int sh = (int)(bit0 & 31);
         const int nchunks = (sh + nbits + 127) >> 7;
         int c = (lane * nchunks) >> 6;   // lanes of a wave start at different windows
         for (int cc = 0; cc < nchunks; ++cc) {
+            // words past the end of the buffer hold no bit of this row: read the last word instead
             uint32_t w[5];
 #pragma unroll
             for (int k = 0; k < 5; ++k) {
                 const int64_t wi = w0 + 4 * c + k;
-                w[k] = wi < n_words ? packed[wi] : 0u;
+                w[k] = packed[wi < n_words ? wi : n_words - 1];
             }
             // elements whose first bit lies in this window: t in [t_lo, t_hi)
             const int lo_bits = 128 * c - sh;   // window start relative to the slice
@@ -139,31 +132,88 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
 
 // ---------------------------------------------------------------------------
 // 8-bit symbols (one byte per element).  lane = one row; the row's bytes are
-// loaded once into a 16-byte register window, realigned to the row's first byte
-// with byte-funnel shifts, and ROTATED by a lane-dependent number of bytes, so
-// that the sixteen unrolled extraction slots of a wave touch sixteen different
-// features at the same time: rows that share the heavy bin of a skewed column do
-// not meet at one LDS address in the same instruction.
+// loaded once into a 16-byte register window and realigned to the row's first
+// byte with byte-funnel shifts.
+//
+// SINGLE (the tile has at most 16 features, one window per row): the window is
+// then PERMUTED per lane with v_perm_b32 so that unrolled slot j of lane l holds
+// feature (j + l) mod ft.  The lanes of a wave therefore work on different
+// features in the same instruction, and rows that share the heavy bin of a
+// skewed column do not meet at one LDS address.  The byte selectors and the
+// slots' LDS offsets depend on the lane only and live in registers.
+// Wider tiles are walked window by window, lanes starting at different windows.
+//
+// All atomics of a window are issued before the first returned word is examined,
+// so their latencies overlap.  A missing symbol, or a symbol >= B, is sent to a
+// spare "trash" row of 256 words behind the histogram instead of being
+// predicated.
+//   NS  : unrolled slots per window.  0: wide tile (16 slots, no permutation);
+//         otherwise the tile has at most NS <= 16 features (slots past the last
+//         feature fall into the trash row)
+//   CHK : a symbol may be the missing symbol, or >= B (B < 256)
 // ---------------------------------------------------------------------------
-template <bool LIST>
+__device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long long old,
+                                         unsigned long long addv, uint32_t hq) {
+    uint32_t olo = (uint32_t)old, ohi = (uint32_t)(old >> 32);
+    // carry possible only if h-field bits 22..29 are all ones; wrap possible only if the
+    // g field is within 2^27 of +-2^33 (top seven bits of the word are 0111111 or 1000000)
+    const bool danger = ((olo & 0x3FC00000u) == 0x3FC00000u) | ((ohi + 0x82000000u) < 0x04000000u);
+    if (danger) {
+        asm volatile("" : "+v"(olo), "+v"(ohi));   // keep the rare bookkeeping inside the branch
+        const uint32_t carry = ((olo & kHMask) + hq) >> kHShift;
+        const uint32_t alo = (uint32_t)addv, ahi = (uint32_t)(addv >> 32);
+        const uint32_t nlo = olo + alo;
+        const uint32_t nhi = ohi + ahi + (nlo < olo ? 1u : 0u);
+        const int32_t ovf = (int32_t)((ohi ^ nhi) & (ahi ^ nhi));   // sign bit set: the g field wrapped
+        const int32_t delta = ovf < 0 ? ((int32_t)nhi < 0 ? 1 : -1) : 0;
+        if (carry != 0 || delta != 0) atomicAdd(&side[idx], (uint32_t)(delta * 65536 + (int32_t)carry));
+    }
+}
+
+template <bool LIST, int NS, bool CHK>
 __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
-    const uint32_t *__restrict__ packed, int64_t n_words, int64_t n, int F, int B, int Bp, uint32_t missing,
-    const uint32_t *__restrict__ row_idx, const int2 *__restrict__ gq, int64_t *__restrict__ pool,
-    const HistJob *__restrict__ jobs) {
+    const uint32_t *__restrict__ packed, int64_t n_words, int64_t stride_bytes, int64_t n, int B, int Bp,
+    uint32_t missing, const uint32_t *__restrict__ row_idx, const int2 *__restrict__ gq,
+    int64_t *__restrict__ pool, const HistJob *__restrict__ jobs) {
     extern __shared__ unsigned long long lds[];
     const HistJob job = jobs[blockIdx.x];
     const int ft = (int)job.ft;
+    const int trash = ft * Bp;                       // first word of the trash row
+    const int n_acc = trash + 256;
     unsigned long long *main_ = lds;
-    uint32_t *side = (uint32_t *)(lds + ft * Bp);
-    for (int i = threadIdx.x; i < ft * Bp; i += kHistBlock) {
+    uint32_t *side = (uint32_t *)(lds + n_acc);
+    for (int i = threadIdx.x; i < n_acc; i += kHistBlock) {
         main_[i] = 0;
         side[i] = 0;
     }
     __syncthreads();
 
+    constexpr bool SINGLE = NS != 0;
+    constexpr int SLOTS = SINGLE ? NS : 16;
     const int lane = threadIdx.x & 63;
-    const int rot = lane & 15;                 // bytes this lane's window is rotated by
     const int nchunks = (ft + 15) >> 4;        // 16-byte windows per row slice (same for every lane)
+    // SINGLE: slot j of this lane handles feature (j + lane) mod ft
+    uint32_t selA[4], selB[4];                 // v_perm selectors for window words (1:0) and (3:2)
+    int pre[16];                               // word offset of the slot's feature in the LDS histogram
+    if (SINGLE) {
+        const int l0 = lane % ft;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            selA[k] = 0;
+            selB[k] = 0;
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            int t = j + l0;
+            t = t >= ft ? t - ft : t;          // (j + lane) mod ft for j < ft
+            const bool live = j < ft;
+            pre[j] = live ? t * Bp : trash;
+            const uint32_t a = (live && t < 8) ? (uint32_t)t : 0x0Cu;           // 0x0C selects a zero byte
+            const uint32_t b = (live && t >= 8) ? (uint32_t)(t - 8) : 0x0Cu;
+            selA[j >> 2] |= a << (8 * (j & 3));
+            selB[j >> 2] |= b << (8 * (j & 3));
+        }
+    }
     for (uint32_t i = threadIdx.x; i < job.n_rows; i += kHistBlock) {
         const uint64_t pos_in = (uint64_t)job.row_begin + i;
         const uint64_t r = LIST ? (uint64_t)row_idx[pos_in] : pos_in;
@@ -171,38 +221,44 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
         const int2 q = gq[r];
         const unsigned long long addv = pack_pair(q);
         const uint32_t hq = (uint32_t)q.y;
-        const uint64_t byte0 = r * (uint64_t)F + job.f0;
+        const uint64_t byte0 = r * (uint64_t)stride_bytes + job.f0;
         const int64_t w0 = (int64_t)(byte0 >> 2);
         const uint32_t a = (uint32_t)(byte0 & 3);
-        int c = (lane * nchunks) >> 6;
-        for (int cc = 0; cc < nchunks; ++cc) {
+        int c = SINGLE ? 0 : (lane * nchunks) >> 6;
+        for (int cc = 0; cc < (SINGLE ? 1 : nchunks); ++cc) {
+            // words past the end of the buffer hold no bit of this row: read the last word instead
             uint32_t w[5];
 #pragma unroll
             for (int k = 0; k < 5; ++k) {
                 const int64_t wi = w0 + 4 * c + k;
-                w[k] = wi < n_words ? packed[wi] : 0u;
+                w[k] = packed[wi < n_words ? wi : n_words - 1];
             }
             // realign: W = bytes [16c, 16c+16) of the row slice
-            uint32_t W[4];
+            uint32_t W[4], V[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) W[k] = __builtin_amdgcn_alignbyte(w[k + 1], w[k], a);
-            // rotate the window by `rot` bytes: whole words first, then a byte funnel
-            uint32_t X[4], Y[4], V[4];
+            if (SINGLE) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) X[k] = (rot & 4) ? W[(k + 1) & 3] : W[k];
+                for (int k = 0; k < 4; ++k)
+                    V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
+            } else {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) Y[k] = (rot & 8) ? X[(k + 2) & 3] : X[k];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) V[k] = __builtin_amdgcn_alignbyte(Y[(k + 1) & 3], Y[k], (uint32_t)(rot & 3));
-            const int nv = ft - 16 * c < 16 ? ft - 16 * c : 16;   // valid bytes in this window
-            const int tbase = 16 * c;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int tt = (j + rot) & 15;   // slot j holds byte tt of the window
-                const uint32_t s = (V[j >> 2] >> (8 * (j & 3))) & 0xffu;
-                if (tt < nv && s != missing && s < (uint32_t)B)
-                    pk_add(main_, side, (tbase + tt) * Bp + (int)s, addv, hq);
+                for (int k = 0; k < 4; ++k) V[k] = W[k];
             }
+            const int nv = ft - 16 * c;              // wide tile: features left from this window on
+            int idx[SLOTS];
+            unsigned long long old[SLOTS];
+#pragma unroll
+            for (int j = 0; j < SLOTS; ++j) {
+                const uint32_t s = (V[j >> 2] >> (8 * (j & 3))) & 0xffu;
+                const int base = SINGLE ? pre[j] : (j < nv ? (16 * c + j) * Bp : trash);
+                bool bad = false;
+                if (CHK) bad = (s == missing) | (s >= (uint32_t)B);
+                idx[j] = (bad ? trash : base) + (int)s;
+                old[j] = atomicAdd(&main_[idx[j]], addv);
+            }
+#pragma unroll
+            for (int j = 0; j < SLOTS; ++j) pk_check(side, idx[j], old[j], addv, hq);
             ++c;
             if (c == nchunks) c = 0;
         }
@@ -217,43 +273,82 @@ inline int padded_bins(int B) { return B | 1; }   // odd stride: see the note on
 
 int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B) {
     const size_t per_feature = (size_t)padded_bins(B) * 12;   // 8-byte word + 4-byte side counter per bin
-    int ft = (int)(ctx->lds_per_block / per_feature);
+    const size_t budget = ctx->lds_per_block - 256 * 12;      // the trash row
+    int ft = (int)(budget / per_feature);
     if (ft > F) ft = F;
     return ft;   // 0: one feature's bins do not fit in LDS
 }
 
-hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t n, int F, int B,
-                           uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
+namespace {
+struct B8Args {
+    hipStream_t s;
+    int n_jobs;
+    size_t lds;
+    const uint32_t *packed;
+    int64_t n_words, stride_bytes, n;
+    int B, Bp;
+    uint32_t missing;
+    const uint32_t *row_idx;
+    const int2 *gq;
+    int64_t *pool;
+    const HistJob *jobs;
+};
+template <bool LIST, int NS, bool CHK>
+hipError_t launch_b8(const B8Args &a) {
+    static size_t configured = 0;
+    if (a.lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)hist_b8_kernel<LIST, NS, CHK>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+        if (e != hipSuccess) return e;
+        configured = a.lds;
+    }
+    hist_b8_kernel<LIST, NS, CHK><<<a.n_jobs, kHistBlock, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bytes, a.n, a.B,
+                                                                         a.Bp, a.missing, a.row_idx, a.gq, a.pool,
+                                                                         a.jobs);
+    return hipGetLastError();
+}
+template <bool LIST, bool CHK>
+hipError_t pick_slots(int max_ft, const B8Args &a) {
+    if (max_ft > 16) return launch_b8<LIST, 0, CHK>(a);
+    if (max_ft <= 4) return launch_b8<LIST, 4, CHK>(a);
+    if (max_ft <= 8) return launch_b8<LIST, 8, CHK>(a);
+    if (max_ft <= 12) return launch_b8<LIST, 12, CHK>(a);
+    if (max_ft == 13) return launch_b8<LIST, 13, CHK>(a);
+    return launch_b8<LIST, 16, CHK>(a);
+}
+template <bool LIST>
+hipError_t launch_generic(hipStream_t s, int n_jobs, size_t lds, const uint32_t *packed, int64_t n_words, int bits,
+                          int64_t stride_bits, int64_t n, int B, int Bp, uint32_t missing,
+                          const uint32_t *row_idx, const int2 *gq, int64_t *pool, const HistJob *jobs) {
+    static size_t configured = 0;
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)hist_generic_kernel<LIST>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = lds;
+    }
+    const uint32_t inv_bits = (uint32_t)((((uint64_t)1 << 32) + (uint32_t)bits - 1) / (uint32_t)bits);
+    hist_generic_kernel<LIST><<<n_jobs, kHistBlock, lds, s>>>(packed, n_words, bits, inv_bits, stride_bits, n, B, Bp,
+                                                               missing, row_idx, gq, pool, jobs);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n_words,
+                           int64_t n, int B, uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
                            int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft) {
     if (n_jobs <= 0) return hipSuccess;
     const int Bp = padded_bins(B);
-    const size_t lds = (size_t)max_ft * Bp * 12;
-    const int64_t n_words = (n * (int64_t)F * bits + 31) / 32 + 1;
-    const void *fn[4] = {(const void *)hist_generic_kernel<false>, (const void *)hist_generic_kernel<true>,
-                         (const void *)hist_b8_kernel<false>, (const void *)hist_b8_kernel<true>};
-    static size_t configured[4] = {0, 0, 0, 0};
-    const int which = (bits == 8 ? 2 : 0) + (row_idx ? 1 : 0);
-    if (lds > configured[which]) {
-        hipError_t e = hipFuncSetAttribute(fn[which], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        configured[which] = lds;
-    }
+    const size_t lds = ((size_t)max_ft * Bp + 256) * 12;
     const int2 *g2 = (const int2 *)gq;
-    if (bits == 8) {
-        if (row_idx)
-            hist_b8_kernel<true><<<n_jobs, kHistBlock, lds, ctx->stream>>>(packed, n_words, n, F, B, Bp, missing,
-                                                                            row_idx, g2, hist_pool, jobs);
-        else
-            hist_b8_kernel<false><<<n_jobs, kHistBlock, lds, ctx->stream>>>(packed, n_words, n, F, B, Bp, missing,
-                                                                             row_idx, g2, hist_pool, jobs);
-    } else {
-        const uint32_t inv_bits = (uint32_t)((((uint64_t)1 << 32) + (uint32_t)bits - 1) / (uint32_t)bits);
-        if (row_idx)
-            hist_generic_kernel<true><<<n_jobs, kHistBlock, lds, ctx->stream>>>(
-                packed, n_words, bits, inv_bits, n, F, B, Bp, missing, row_idx, g2, hist_pool, jobs);
-        else
-            hist_generic_kernel<false><<<n_jobs, kHistBlock, lds, ctx->stream>>>(
-                packed, n_words, bits, inv_bits, n, F, B, Bp, missing, row_idx, g2, hist_pool, jobs);
+    hipStream_t s = ctx->stream;
+    if (bits == 8 && (stride_bits & 7) == 0) {
+        const bool chk = missing < 256u || B < 256;
+        const B8Args a{s, n_jobs, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing, row_idx, g2, hist_pool, jobs};
+        if (row_idx) return chk ? pick_slots<true, true>(max_ft, a) : pick_slots<true, false>(max_ft, a);
+        return chk ? pick_slots<false, true>(max_ft, a) : pick_slots<false, false>(max_ft, a);
     }
-    return hipGetLastError();
+    if (row_idx)
+        return launch_generic<true>(s, n_jobs, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
+    return launch_generic<false>(s, n_jobs, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
 }
