@@ -231,13 +231,16 @@ GBT_API int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t bits
 
 /* ---- Alg. 1 as a whole -------------------------------------------------- */
 
-GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t max_bins, int32_t max_depth);
+GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits, int32_t max_bins,
+                                             int32_t max_depth);
 
 /*
  * Grows one tree depth-wise (Alg. 1 with the "closest to the root first"
  * policy): root histogram; per level evaluate the open nodes, partition the
- * rows of those that split, build the histogram of each split's smaller child
- * (fewer rows, tie -> left) and get the larger one by subtraction.  A node is
+ * rows of those that split (whole records -- symbols, gradient pair, row id --
+ * move inside the workspace so that each node's rows stay contiguous), build
+ * the histogram of each split's smaller child (fewer rows, tie -> left) and get
+ * the larger one by subtraction.  A node is
  * split iff it has a valid candidate with gain > max(gamma, GBT_GAIN_FLOOR) and
  * depth < max_depth.  Leaf weight = -G/(H+lambda).
  *   packed, bits, n, F, missing_sym : packed matrix [dev]

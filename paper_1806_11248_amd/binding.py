@@ -91,7 +91,7 @@ def load():
         getattr(L, nm).restype = C.c_size_t
     L.gbt_quantise_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.c_int32]
     L.gbt_partition_workspace_bytes.argtypes = [C.c_int64]
-    L.gbt_grow_tree_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32]
+    L.gbt_grow_tree_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     L.gbt_predict_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
     vp, i32, i64, u32, f64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_double, C.c_size_t
     L.gbt_quantise.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, sz]
@@ -321,7 +321,7 @@ class Context:
         ts = _tree_struct(t)
         row_idx = row_idx_out if row_idx_out is not None else self.empty((n,), torch.int32)
         leaf = (leaf_out if leaf_out is not None else self.empty((n,), torch.int32)) if want_leaf else None
-        ws_bytes = self.lib.gbt_grow_tree_workspace_bytes(n, F, params.max_bins, params.max_depth)
+        ws_bytes = self.lib.gbt_grow_tree_workspace_bytes(n, F, bits, params.max_bins, params.max_depth)
         if ws_bytes == 0:
             raise GbtError(EINVAL, "gbt_grow_tree_workspace_bytes rejected the shape")
         ws = self.workspace("grow", ws_bytes)

@@ -3,6 +3,7 @@
 
 #include <math.h>
 #include <stdarg.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -84,7 +85,7 @@ void add_hist_jobs(std::vector<HistJob> &jobs, uint64_t hist_off, uint32_t begin
 }
 
 uint32_t pick_rows_per_job(const gbt_ctx *ctx, int64_t total_rows) {
-    int64_t target_jobs = (int64_t)ctx->num_cu * 4;
+    int64_t target_jobs = (int64_t)ctx->num_cu * ctx->hist_jobs_per_cu;
     int64_t rpj = (total_rows + target_jobs - 1) / target_jobs;
     if (rpj < 4096) rpj = 4096;
     if (rpj > (1 << 21)) rpj = 1 << 21;   // the per-bin event counters of the histogram kernel are 16 bits wide
@@ -156,6 +157,10 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
     }
     if (e == hipSuccess) {
         c->num_cu = prop.multiProcessorCount;
+        c->hist_block = 512;
+        c->hist_jobs_per_cu = 8;
+        if (const char *e1 = getenv("GBT_TUNE_HIST_BLOCK")) { int v = atoi(e1); if (v == 256 || v == 512 || v == 1024) c->hist_block = v; }
+        if (const char *e2 = getenv("GBT_TUNE_HIST_JOBS")) { int v = atoi(e2); if (v >= 1 && v <= 64) c->hist_jobs_per_cu = v; }
         size_t lds = prop.sharedMemPerBlock;
         int optin = 0;
         if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess &&
@@ -288,7 +293,7 @@ extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *m
 
 // ------------------------------------------------------- fixed-point gpair --
 static int32_t gpair_fixed_impl(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq, double *scale,
-                                void *ws) {
+                                void *ws, int64_t *sums_dev /* may be NULL */) {
     GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
     GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 12, hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
@@ -302,7 +307,7 @@ static int32_t gpair_fixed_impl(gbt_ctx *ctx, const float *gpair, int64_t n, int
     memcpy(&mh, &bits2[1], 4);
     scale[0] = fixed_scale(mg, kGBits);
     scale[1] = fixed_scale(mh, kHBits);
-    GBT_HIP(ctx, gbt_launch_to_fixed(ctx->stream, gpair, n, scale[0], scale[1], gq));
+    GBT_HIP(ctx, gbt_launch_to_fixed(ctx->stream, gpair, n, scale[0], scale[1], gq, sums_dev));
     return GBT_OK;
 }
 
@@ -312,7 +317,7 @@ extern "C" int32_t gbt_gpair_fixed(gbt_ctx *ctx, const float *gpair, int64_t n, 
     GBT_REQUIRE(ctx, gpair && gq_out && scale_out && workspace, GBT_EINVAL, "NULL argument");
     GBT_REQUIRE(ctx, n >= 0, GBT_EINVAL, "n < 0");
     GBT_REQUIRE(ctx, workspace_bytes >= 4096, GBT_ENOMEM, "workspace < 4096 bytes");
-    int32_t st = gpair_fixed_impl(ctx, gpair, n, gq_out, scale_out, workspace);
+    int32_t st = gpair_fixed_impl(ctx, gpair, n, gq_out, scale_out, workspace, nullptr);
     if (st != GBT_OK) return st;
     GBT_SYNC(ctx);
     return GBT_OK;
@@ -454,7 +459,7 @@ extern "C" int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     st = upload(ctx, &job, sizeof job, ws + L.jobs);
     if (st != GBT_OK) return st;
     uint32_t *seg = row_idx + begin;
-    GBT_HIP(ctx, gbt_launch_partition(ctx->stream, packed, bits, n, F, (uint32_t)missing_sym, seg,
+    GBT_HIP(ctx, gbt_launch_partition(ctx->stream, packed, bits, (int64_t)F * bits, n, (uint32_t)missing_sym, seg,
                                       (uint32_t *)(ws + L.dst), (const PartJob *)(ws + L.jobs), 1,
                                       (int)job.n_tiles, (uint64_t *)(ws + L.masks),
                                       (uint32_t *)(ws + L.tile_left), (uint32_t *)(ws + L.n_left)));
@@ -502,19 +507,25 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
 namespace {
 
 struct GrowLayout {
-    size_t gq, buf0, buf1, masks, tile_left, n_left, pool, eval_nodes, splits, jobs, scratch, total;
-    int64_t hist_nodes, level_nodes, tiles;
+    size_t gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, pool, eval_nodes, splits, jobs, scratch, total;
+    int64_t hist_nodes, level_nodes, tiles, w_words;
+    int sw;   // 32-bit words per row of the working copies
 };
 
-GrowLayout grow_layout(int64_t n, int F, int B, int max_depth) {
+GrowLayout grow_layout(int64_t n, int F, int bits, int B, int max_depth) {
     GrowLayout L;
     L.hist_nodes = max_depth == 0 ? 1 : (((int64_t)1 << max_depth) - 1);
     L.level_nodes = (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0);   // most nodes evaluated in one level
     L.tiles = n / GBT_PART_TILE + L.level_nodes + 1;
+    L.sw = (int)(((int64_t)F * bits + 31) / 32);
+    L.w_words = n * L.sw + 4;
     size_t o = 0;
     L.gq = o;         o += gbt_align((size_t)n * 8);
-    L.buf0 = o;       o += gbt_align((size_t)n * 4);
-    L.buf1 = o;       o += gbt_align((size_t)n * 4);
+    for (int k = 0; k < 2; ++k) {
+        L.wsym[k] = o; o += gbt_align((size_t)L.w_words * 4);
+        L.wgq[k] = o;  o += gbt_align((size_t)n * 8);
+        L.wid[k] = o;  o += gbt_align((size_t)n * 4);
+    }
     L.masks = o;      o += gbt_align((size_t)L.tiles * (GBT_PART_TILE / 64) * 8);
     L.tile_left = o;  o += gbt_align((size_t)L.tiles * 4);
     L.n_left = o;     o += gbt_align((size_t)L.level_nodes * 4);
@@ -535,9 +546,11 @@ struct HNode {
 
 }  // namespace
 
-extern "C" size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t max_bins, int32_t max_depth) {
-    if (n < 0 || F < 1 || max_bins < 2 || max_depth < 0 || max_depth > kMaxDepth) return 0;
-    return grow_layout(n, F, max_bins, max_depth).total;
+extern "C" size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits, int32_t max_bins,
+                                                int32_t max_depth) {
+    if (n < 0 || F < 1 || bits < 1 || bits > GBT_MAX_BITS || max_bins < 2 || max_depth < 0 || max_depth > kMaxDepth)
+        return 0;
+    return grow_layout(n, F, bits, max_bins, max_depth).total;
 }
 
 extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
@@ -561,7 +574,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     GBT_REQUIRE(ctx, tree->feature && tree->bin && tree->default_left && tree->left && tree->right &&
                          tree->threshold && tree->weight && tree->gain && tree->sumG && tree->sumH && tree->n_rows,
                 GBT_EINVAL, "tree arrays must be allocated");
-    const GrowLayout L = grow_layout(n, F, B, max_depth);
+    const GrowLayout L = grow_layout(n, F, bits, B, max_depth);
     GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
     HistPlan pl;
     GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, &pl), GBT_EUNSUPPORTED,
@@ -569,10 +582,35 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
 
     char *ws = (char *)workspace;
     int32_t *gq = (int32_t *)(ws + L.gq);
-    uint32_t *buf[2] = {(uint32_t *)(ws + L.buf0), (uint32_t *)(ws + L.buf1)};
     int64_t *pool = (int64_t *)(ws + L.pool);
     const int64_t hist_len = (int64_t)F * B * 2;
+    const int row_bits = F * bits;
     hipStream_t s = ctx->stream;
+
+    // The rows in their current order.  Level 0 reads the caller's packed matrix; every
+    // partition then moves whole records (symbols, gradient pair, id) into the other of two
+    // word-aligned working copies, so that each node's rows stay contiguous.
+    GbtRows W[2];
+    for (int k = 0; k < 2; ++k) {
+        W[k].sym_rw = (uint32_t *)(ws + L.wsym[k]);
+        W[k].gq_rw = (int32_t *)(ws + L.wgq[k]);
+        W[k].id_rw = (uint32_t *)(ws + L.wid[k]);
+        W[k].sym = W[k].sym_rw;
+        W[k].gq = W[k].gq_rw;
+        W[k].id = W[k].id_rw;
+        W[k].stride_bits = 32 * (int64_t)L.sw;
+        W[k].n_words = L.w_words;
+    }
+    GbtRows cur;
+    cur.sym = packed;
+    cur.stride_bits = row_bits;
+    cur.n_words = gbt_packed_words(n, F, bits);
+    cur.gq = gq;
+    cur.id = nullptr;
+    cur.sym_rw = nullptr;
+    cur.gq_rw = nullptr;
+    cur.id_rw = nullptr;
+    int wcur = 2;   // which id buffer describes the current order: 0/1 = W[k], 2 = identity
 
     // thresholds come from the cut table
     std::vector<float> hcuts((size_t)F * (B - 1));
@@ -580,18 +618,13 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
 
     double scale[2];
     gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 24.0);
-    st = gpair_fixed_impl(ctx, gpair, n, gq, scale, ws + L.scratch);
+    st = gpair_fixed_impl(ctx, gpair, n, gq, scale, ws + L.scratch, (int64_t *)(ws + L.scratch + 256));
     gbt_prof_end(ctx);
     if (st != GBT_OK) return st;
     const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
     const double lambda = params->lambda;
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
-
-    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
-    GBT_HIP(ctx, gbt_launch_sum_gq(s, gq, nullptr, n, (int64_t *)(ws + L.scratch)));
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.scratch, 16, hipMemcpyDeviceToHost, s));
-    GBT_HIP(ctx, gbt_launch_iota_u32(s, buf[0], n));
-    gbt_prof_end(ctx);
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.scratch + 256, 16, hipMemcpyDeviceToHost, s));
     if (max_depth > 0) {
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
                           (HistJob *)(ws + L.jobs));
@@ -621,7 +654,6 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     set_node(root);
     level.push_back(root);
     int32_t n_nodes = 1;
-    int cur = 0;   // buffer holding the current level's segments
 
     std::vector<EvalNode> enodes;
     std::vector<PartJob> pjobs;
@@ -653,13 +685,14 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         pjobs.clear();
         split_of.clear();
         uint32_t tile_cursor = 0;
+        double part_rows = 0;
         for (size_t i = 0; i < level.size(); ++i) {
             const gbt_split &sp = splits[i];
             const HNode &nd = level[i];
             const bool ok = sp.valid && sp.gain > min_gain && sp.feature >= 0 && sp.feature < F &&
                             sp.bin >= 0 && sp.bin < B && nd.len > 0;
             if (!ok) {
-                leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)cur, nd.len});
+                leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)wcur, nd.len});
                 continue;
             }
             PartJob j;
@@ -672,6 +705,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             j.n_tiles = (nd.len + GBT_PART_TILE - 1) / GBT_PART_TILE;
             j.pad = 0;
             tile_cursor += j.n_tiles;
+            part_rows += nd.len;
             pjobs.push_back(j);
             split_of.push_back((int)i);
         }
@@ -683,19 +717,18 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         GBT_REQUIRE(ctx, (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
         if (st != GBT_OK) return st;
-        {
-            double part_rows = 0;
-            for (const PartJob &j : pjobs) part_rows += j.seg_len;
-            gbt_prof_begin(ctx, GBT_PROF_PARTITION, part_rows * (8.0 + bits / 8.0));
-        }
-        GBT_HIP(ctx, gbt_launch_partition(s, packed, bits, n, F, (uint32_t)missing_sym, buf[cur], buf[cur ^ 1],
-                                          (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
-                                          (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
-                                          (uint32_t *)(ws + L.n_left)));
+        const int wnext = wcur == 0 ? 1 : 0;
+        gbt_prof_begin(ctx, GBT_PROF_PARTITION, part_rows * (2.0 * (row_bits / 8.0 + 12.0)));
+        GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym,
+                                                  (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
+                                                  (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
+                                                  (uint32_t *)(ws + L.n_left)));
         gbt_prof_end(ctx);
         GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
         GBT_SYNC(ctx);
         const uint32_t *n_left = (const uint32_t *)rb(ctx);
+        wcur = wnext;
+        cur = W[wcur];
 
         // ---- children, in creation order
         const bool children_need_hist = depth + 1 < max_depth;
@@ -732,13 +765,13 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 next.push_back(lc);
                 next.push_back(rc);
             } else {
-                leaves.push_back(LeafSeg{lc.begin, (uint32_t)lc.id, (uint32_t)(cur ^ 1), lc.len});
-                leaves.push_back(LeafSeg{rc.begin, (uint32_t)rc.id, (uint32_t)(cur ^ 1), rc.len});
+                leaves.push_back(LeafSeg{lc.begin, (uint32_t)lc.id, (uint32_t)wcur, lc.len});
+                leaves.push_back(LeafSeg{rc.begin, (uint32_t)rc.id, (uint32_t)wcur, rc.len});
             }
         }
-        cur ^= 1;
         if (children_need_hist) {
-            // ---- BuildPartialHistograms for the smaller children, siblings by subtraction
+            // ---- BuildPartialHistograms for the smaller children (their rows are now one
+            //      contiguous run of the working copy), siblings by subtraction
             const int32_t n_children = n_nodes - first_child;
             gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
             GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
@@ -752,9 +785,9 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 st = upload(ctx, hjobs.data() + j0, nj * sizeof(HistJob), ws + L.jobs);
                 if (st != GBT_OK) return st;
                 gbt_prof_begin(ctx, GBT_PROF_HIST_NODE,
-                               j0 == 0 ? (double)built_rows * ((double)F * bits / 8.0 + 12.0) : 0.0);
-                GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
-                                             (uint32_t)missing_sym, buf[cur], gq, pool,
+                               j0 == 0 ? (double)built_rows * ((double)row_bits / 8.0 + 8.0) : 0.0);
+                GBT_HIP(ctx, gbt_launch_hist(ctx, cur.sym, bits, cur.stride_bits, cur.n_words, n, B,
+                                             (uint32_t)missing_sym, nullptr, cur.gq, pool,
                                              (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
                 gbt_prof_end(ctx);
             }
@@ -768,7 +801,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         level.swap(next);
     }
     // nodes still open when the depth limit (or an empty level) ended the loop are leaves
-    for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)cur, nd.len});
+    for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)wcur, nd.len});
 
     std::sort(leaves.begin(), leaves.end(),
               [](const LeafSeg &a, const LeafSeg &b) {   // an empty segment sorts before the one that starts at the same place
@@ -777,7 +810,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     st = upload(ctx, leaves.data(), leaves.size() * sizeof(LeafSeg), ws + L.jobs);
     if (st != GBT_OK) return st;
     gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
-    GBT_HIP(ctx, gbt_launch_leaf_gather(s, buf[0], buf[1], (const LeafSeg *)(ws + L.jobs), (int)leaves.size(), n,
+    GBT_HIP(ctx, gbt_launch_leaf_gather(s, W[0].id, W[1].id, (const LeafSeg *)(ws + L.jobs), (int)leaves.size(), n,
                                         row_idx_out, leaf_of_row_out));
     gbt_prof_end(ctx);
     GBT_SYNC(ctx);

@@ -23,6 +23,8 @@ struct gbt_ctx {
     size_t lds_per_block;   // largest dynamic LDS a workgroup may ask for
     char *pinned;           // host staging for job tables and small read-backs
     size_t pinned_bytes;
+    int hist_block;         // threads per histogram workgroup
+    int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
     size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
     char err[512];
     bool profiling;
@@ -102,8 +104,9 @@ struct LeafSeg {
 hipError_t gbt_launch_fill_u64(hipStream_t s, uint64_t *p, uint64_t v, int64_t count);
 hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count);
 hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2);
+// sums_out (may be NULL): int64[2] [dev] receiving the exact totals of gq (zeroed by the launcher).
 hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, double sg, double sh,
-                               int32_t *gq);
+                               int32_t *gq, int64_t *sums_out);
 hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,
                              int64_t *out2 /* zeroed by the launcher */);
 hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margin, const float *label,
@@ -128,10 +131,29 @@ hipError_t gbt_launch_eval(hipStream_t s, const int64_t *hist_pool, const EvalNo
                            const int32_t *nb, int F, int B, double inv_sg, double inv_sh, double lambda,
                            double mcw, gbt_split *out);
 
-hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t n, int F,
+hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n,
                                 uint32_t missing, const uint32_t *src, uint32_t *dst,
                                 const PartJob *jobs, int n_jobs, int total_tiles, uint64_t *masks,
                                 uint32_t *tile_left, uint32_t *n_left_out);
+
+// A set of rows in some order: symbols (row p starts at bit p*stride_bits), fixed-point gradient
+// pairs and original row ids (NULL: the id of position p is p).  The *_rw members are the same
+// addresses for a set that may be written.
+struct GbtRows {
+    const uint32_t *sym;
+    int64_t stride_bits, n_words;
+    const int32_t *gq;
+    const uint32_t *id;
+    uint32_t *sym_rw;
+    int32_t *gq_rw;
+    uint32_t *id_rw;
+};
+// Stable partition of the jobs' segments of `src` into `dst` (records move, see kernels_partition.hip).
+hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
+                                        int64_t n, uint32_t missing, const PartJob *jobs, int n_jobs,
+                                        int total_tiles, uint64_t *masks, uint32_t *tile_left,
+                                        uint32_t *n_left_out);
+// LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,
                                   int32_t *leaf_of_row);

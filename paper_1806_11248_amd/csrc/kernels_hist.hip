@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
     const int ft = (int)job.ft;
     unsigned long long *main_ = lds;
     uint32_t *side = (uint32_t *)(lds + ft * Bp + 256);   // same layout as the 8-bit kernels (trash row unused)
-    for (int i = threadIdx.x; i < ft * Bp; i += kHistBlock) {
+    for (int i = threadIdx.x; i < ft * Bp; i += (int)blockDim.x) {
         main_[i] = 0;
         side[i] = 0;
     }
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
     const uint32_t mask = (1u << bits) - 1u;
     const int nbits = ft * bits;
     const int lane = threadIdx.x & 63;
-    for (uint32_t i = threadIdx.x; i < job.n_rows; i += kHistBlock) {
+    for (uint32_t i = threadIdx.x; i < job.n_rows; i += blockDim.x) {
         const uint64_t pos_in = (uint64_t)job.row_begin + i;
         const uint64_t r = LIST ? (uint64_t)row_idx[pos_in] : pos_in;
         if (r >= (uint64_t)n) continue;   // a malformed row id is skipped, never dereferenced
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
         }
     }
     __syncthreads();
-    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, kHistBlock);
+    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
     const int n_acc = trash + 256;
     unsigned long long *main_ = lds;
     uint32_t *side = (uint32_t *)(lds + n_acc);
-    for (int i = threadIdx.x; i < n_acc; i += kHistBlock) {
+    for (int i = threadIdx.x; i < n_acc; i += (int)blockDim.x) {
         main_[i] = 0;
         side[i] = 0;
     }
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
             selB[j >> 2] |= b << (8 * (j & 3));
         }
     }
-    for (uint32_t i = threadIdx.x; i < job.n_rows; i += kHistBlock) {
+    for (uint32_t i = threadIdx.x; i < job.n_rows; i += blockDim.x) {
         const uint64_t pos_in = (uint64_t)job.row_begin + i;
         const uint64_t r = LIST ? (uint64_t)row_idx[pos_in] : pos_in;
         if (r >= (uint64_t)n) continue;
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
         }
     }
     __syncthreads();
-    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, kHistBlock);
+    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
 }
 
 inline int padded_bins(int B) { return B | 1; }   // odd stride: see the note on LDS banks above
@@ -282,7 +282,7 @@ int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B) {
 namespace {
 struct B8Args {
     hipStream_t s;
-    int n_jobs;
+    int n_jobs, block;
     size_t lds;
     const uint32_t *packed;
     int64_t n_words, stride_bytes, n;
@@ -302,7 +302,7 @@ hipError_t launch_b8(const B8Args &a) {
         if (e != hipSuccess) return e;
         configured = a.lds;
     }
-    hist_b8_kernel<LIST, NS, CHK><<<a.n_jobs, kHistBlock, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bytes, a.n, a.B,
+    hist_b8_kernel<LIST, NS, CHK><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bytes, a.n, a.B,
                                                                          a.Bp, a.missing, a.row_idx, a.gq, a.pool,
                                                                          a.jobs);
     return hipGetLastError();
@@ -317,7 +317,7 @@ hipError_t pick_slots(int max_ft, const B8Args &a) {
     return launch_b8<LIST, 16, CHK>(a);
 }
 template <bool LIST>
-hipError_t launch_generic(hipStream_t s, int n_jobs, size_t lds, const uint32_t *packed, int64_t n_words, int bits,
+hipError_t launch_generic(hipStream_t s, int n_jobs, int block, size_t lds, const uint32_t *packed, int64_t n_words, int bits,
                           int64_t stride_bits, int64_t n, int B, int Bp, uint32_t missing,
                           const uint32_t *row_idx, const int2 *gq, int64_t *pool, const HistJob *jobs) {
     static size_t configured = 0;
@@ -328,7 +328,7 @@ hipError_t launch_generic(hipStream_t s, int n_jobs, size_t lds, const uint32_t 
         configured = lds;
     }
     const uint32_t inv_bits = (uint32_t)((((uint64_t)1 << 32) + (uint32_t)bits - 1) / (uint32_t)bits);
-    hist_generic_kernel<LIST><<<n_jobs, kHistBlock, lds, s>>>(packed, n_words, bits, inv_bits, stride_bits, n, B, Bp,
+    hist_generic_kernel<LIST><<<n_jobs, block, lds, s>>>(packed, n_words, bits, inv_bits, stride_bits, n, B, Bp,
                                                                missing, row_idx, gq, pool, jobs);
     return hipGetLastError();
 }
@@ -344,11 +344,11 @@ hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64
     hipStream_t s = ctx->stream;
     if (bits == 8 && (stride_bits & 7) == 0) {
         const bool chk = missing < 256u || B < 256;
-        const B8Args a{s, n_jobs, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing, row_idx, g2, hist_pool, jobs};
+        const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing, row_idx, g2, hist_pool, jobs};
         if (row_idx) return chk ? pick_slots<true, true>(max_ft, a) : pick_slots<true, false>(max_ft, a);
         return chk ? pick_slots<false, true>(max_ft, a) : pick_slots<false, false>(max_ft, a);
     }
     if (row_idx)
-        return launch_generic<true>(s, n_jobs, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
-    return launch_generic<false>(s, n_jobs, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
+        return launch_generic<true>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
+    return launch_generic<false>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
 }

@@ -54,17 +54,6 @@ __global__ void absmax_kernel(const float2 *gp, int64_t n, uint32_t *out2) {
     }
 }
 
-__global__ void to_fixed_kernel(const float2 *gp, int64_t n, double sg, double sh, int2 *gq) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        float2 v = gp[i];
-        int2 q;
-        q.x = __double2int_rn((double)v.x * sg);
-        q.y = __double2int_rn((double)v.y * sh);
-        gq[i] = q;
-    }
-}
-
 __device__ inline int64_t wave_sum_i64(int64_t v) {
     for (int o = 32; o > 0; o >>= 1) {
         int lo = __shfl_xor((int)(v & 0xffffffff), o);
@@ -72,6 +61,28 @@ __device__ inline int64_t wave_sum_i64(int64_t v) {
         v += (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
     }
     return v;
+}
+
+__global__ void to_fixed_kernel(const float2 *gp, int64_t n, double sg, double sh, int2 *gq, int64_t *sums) {
+    int64_t g = 0, h = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        float2 v = gp[i];
+        int2 q;
+        q.x = __double2int_rn((double)v.x * sg);
+        q.y = __double2int_rn((double)v.y * sh);
+        gq[i] = q;
+        g += q.x;
+        h += q.y;
+    }
+    if (sums) {
+        g = wave_sum_i64(g);
+        h = wave_sum_i64(h);
+        if ((threadIdx.x & 63) == 0) {
+            atomicAdd((unsigned long long *)&sums[0], (unsigned long long)g);
+            atomicAdd((unsigned long long *)&sums[1], (unsigned long long)h);
+        }
+    }
 }
 
 __global__ void sum_gq_kernel(const int2 *gq, const uint32_t *row_idx, int64_t n_rows, int64_t *out2) {
@@ -210,7 +221,7 @@ __global__ void leaf_gather_kernel(const uint32_t *buf0, const uint32_t *buf1, c
             if ((int64_t)segs[mid].seg_begin <= p) lo = mid; else hi = mid;
         }
         LeafSeg s = segs[lo];
-        uint32_t r = (s.buf ? buf1 : buf0)[p];
+        uint32_t r = s.buf == 2 ? (uint32_t)p : (s.buf ? buf1 : buf0)[p];
         row_idx_out[p] = r;
         if (leaf_of_row && (int64_t)r < n) leaf_of_row[r] = (int32_t)s.node;
     }
@@ -235,10 +246,14 @@ hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint3
     return hipGetLastError();
 }
 hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, double sg, double sh,
-                               int32_t *gq) {
+                               int32_t *gq, int64_t *sums_out) {
+    if (sums_out) {
+        hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)sums_out, 0, 2);
+        if (e != hipSuccess) return e;
+    }
     if (n <= 0) return hipSuccess;
-    to_fixed_kernel<<<grid_for(n, kBlock * 4, 8192), kBlock, 0, s>>>((const float2 *)gpair, n, sg, sh,
-                                                                      (int2 *)gq);
+    to_fixed_kernel<<<grid_for(n, kBlock * 4, 4096), kBlock, 0, s>>>((const float2 *)gpair, n, sg, sh,
+                                                                      (int2 *)gq, sums_out);
     return hipGetLastError();
 }
 hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,

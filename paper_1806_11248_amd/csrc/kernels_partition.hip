@@ -13,6 +13,14 @@
 //               ballot words) and writes it to its place in the other buffer.
 // Ranks are taken in row order, so both halves keep their order (stable).
 // No workgroup waits on another one.
+//
+// Two scatter flavours share the flag and scan kernels:
+//   * ids only  (gbt_partition): row ids move, the matrix stays where it is;
+//   * records   (the grow loop): each row's symbols, fixed-point gradient pair
+//     and id move together into a second set of buffers, so that every node's
+//     rows stay physically contiguous and the next level's histogram and flag
+//     passes stream through HBM instead of gathering 64-byte sectors per row.
+//     Destination rows start on 32-bit word boundaries.
 #include "gbt_internal.h"
 
 namespace {
@@ -33,15 +41,15 @@ __device__ inline int find_job(const PartJob *jobs, int n_jobs, uint32_t tile) {
     return lo;
 }
 
-__device__ inline uint32_t load_symbol(const uint32_t *packed, uint64_t elem, int bits, uint32_t mask) {
-    uint64_t bp = elem * (uint64_t)bits;
+__device__ inline uint32_t load_symbol(const uint32_t *packed, uint64_t bp, int bits, uint32_t mask) {
     const uint32_t *w = packed + (bp >> 5);
     uint64_t v = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
     return (uint32_t)(v >> (bp & 31)) & mask;
 }
 
+// src == NULL: the segment's rows are matrix rows seg_begin .. seg_begin+seg_len-1
 __global__ __launch_bounds__(kBlock) void part_flag_kernel(
-    const uint32_t *__restrict__ packed, int bits, int64_t n, int F, uint32_t missing,
+    const uint32_t *__restrict__ packed, int bits, int64_t stride_bits, int64_t n, uint32_t missing,
     const uint32_t *__restrict__ src, const PartJob *__restrict__ jobs, int n_jobs,
     uint64_t *__restrict__ masks, uint32_t *__restrict__ tile_left) {
     const uint32_t tile = blockIdx.x;
@@ -56,9 +64,10 @@ __global__ __launch_bounds__(kBlock) void part_flag_kernel(
         const uint32_t off = base + (uint32_t)j * kBlock + threadIdx.x;
         bool left = false;
         if (off < job.seg_len) {
-            const uint64_t r = src[(uint64_t)job.seg_begin + off];
+            const uint64_t p = (uint64_t)job.seg_begin + off;
+            const uint64_t r = src ? (uint64_t)src[p] : p;
             if (r < (uint64_t)n) {
-                const uint32_t s = load_symbol(packed, r * (uint64_t)F + job.feature, bits, mask);
+                const uint32_t s = load_symbol(packed, r * (uint64_t)stride_bits + (uint64_t)job.feature * bits, bits, mask);
                 left = (s == missing) ? (job.default_left != 0) : (s <= job.bin);
             }
         }
@@ -147,16 +156,124 @@ __global__ __launch_bounds__(kBlock) void part_scatter_kernel(
     }
 }
 
+// Scatter of whole records.  dst rows are SW words each; src rows start at bit
+// p*src_stride_bits (any alignment).  src_id == NULL: the id of the row at
+// position p is p itself.
+__global__ __launch_bounds__(kBlock) void part_move_kernel(
+    const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words,
+    uint32_t *__restrict__ dst_sym, int SW, int row_bits, const int2 *__restrict__ src_gq,
+    int2 *__restrict__ dst_gq, const uint32_t *__restrict__ src_id, uint32_t *__restrict__ dst_id,
+    const PartJob *__restrict__ jobs, int n_jobs, const uint64_t *__restrict__ masks,
+    const uint32_t *__restrict__ tile_left_off, const uint32_t *__restrict__ n_left) {
+    const uint32_t tile = blockIdx.x;
+    const int ji = find_job(jobs, n_jobs, tile);
+    const PartJob job = jobs[ji];
+    const uint32_t base = (tile - job.tile_begin) * kTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    __shared__ uint64_t words[kWordsPerTile];
+    __shared__ uint32_t lefts_before[kWordsPerTile];
+    __shared__ uint32_t dstpos[kTile];   // destination position of each row of the tile
+    if (threadIdx.x < kWordsPerTile) words[threadIdx.x] = masks[(uint64_t)tile * kWordsPerTile + threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0;
+        for (int w = 0; w < kWordsPerTile; ++w) {
+            lefts_before[w] = acc;
+            acc += (uint32_t)__popcll(words[w]);
+        }
+    }
+    __syncthreads();
+    const uint32_t left_base = tile_left_off[tile];
+    const uint32_t right_base = base - left_base;
+    const uint32_t seg_n_left = n_left[ji];
+    const uint32_t tile_rows = job.seg_len - base < (uint32_t)kTile ? job.seg_len - base : (uint32_t)kTile;
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        const int w = j * (kBlock / 64) + wave;
+        const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+        if (in_tile < tile_rows) {
+            const uint64_t m = words[w];
+            const uint32_t below = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            uint32_t pos;
+            if ((m >> lane) & 1ull) {
+                pos = left_base + lefts_before[w] + below;
+            } else {
+                const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[w];
+                pos = seg_n_left + right_base + rights_before_word + ((uint32_t)lane - below);
+            }
+            const uint32_t q = job.seg_begin + pos;
+            dstpos[in_tile] = q;
+            const uint64_t p = (uint64_t)job.seg_begin + base + in_tile;
+            dst_id[q] = src_id ? src_id[p] : (uint32_t)p;
+            dst_gq[q] = src_gq[p];
+        }
+    }
+    __syncthreads();
+    const uint32_t tail_bits = (uint32_t)(row_bits - 32 * (SW - 1));   // valid bits of a row's last word, 1..32
+    const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
+    const uint64_t p0 = (uint64_t)job.seg_begin + base;
+    if (SW <= 16) {
+        // short rows: one lane copies one row
+        for (uint32_t in_tile = threadIdx.x; in_tile < tile_rows; in_tile += kBlock) {
+            const uint64_t sb = (p0 + in_tile) * (uint64_t)src_stride_bits;
+            const int64_t s0 = (int64_t)(sb >> 5);
+            const uint32_t sh = (uint32_t)(sb & 31);
+            uint32_t *d = dst_sym + (uint64_t)dstpos[in_tile] * (uint64_t)SW;
+            uint32_t lo = src_sym[s0 < src_words ? s0 : src_words - 1];
+            for (int k = 0; k < SW; ++k) {
+                const int64_t si = s0 + k + 1;
+                const uint32_t hi = src_sym[si < src_words ? si : src_words - 1];
+                uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh);
+                if (k == SW - 1) v &= tail_mask;
+                d[k] = v;
+                lo = hi;
+            }
+        }
+    } else {
+        // long rows: one wave copies one row, lanes across its words
+        for (uint32_t in_tile = (uint32_t)wave; in_tile < tile_rows; in_tile += kBlock / 64) {
+            const uint64_t sb = (p0 + in_tile) * (uint64_t)src_stride_bits;
+            const int64_t s0 = (int64_t)(sb >> 5);
+            const uint32_t sh = (uint32_t)(sb & 31);
+            uint32_t *d = dst_sym + (uint64_t)dstpos[in_tile] * (uint64_t)SW;
+            for (int k = lane; k < SW; k += 64) {
+                const int64_t si = s0 + k;
+                const uint32_t lo = src_sym[si < src_words ? si : src_words - 1];
+                const uint32_t hi = src_sym[si + 1 < src_words ? si + 1 : src_words - 1];
+                uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh);
+                if (k == SW - 1) v &= tail_mask;
+                d[k] = v;
+            }
+        }
+    }
+}
+
 }  // namespace
 
-hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t n, int F,
+hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n,
                                 uint32_t missing, const uint32_t *src, uint32_t *dst,
                                 const PartJob *jobs, int n_jobs, int total_tiles, uint64_t *masks,
                                 uint32_t *tile_left, uint32_t *n_left_out) {
     if (n_jobs <= 0 || total_tiles <= 0) return hipSuccess;
-    part_flag_kernel<<<total_tiles, kBlock, 0, s>>>(packed, bits, n, F, missing, src, jobs, n_jobs, masks,
+    part_flag_kernel<<<total_tiles, kBlock, 0, s>>>(packed, bits, stride_bits, n, missing, src, jobs, n_jobs, masks,
                                                     tile_left);
     part_scan_kernel<<<n_jobs, kBlock, 0, s>>>(jobs, tile_left, n_left_out);
     part_scatter_kernel<<<total_tiles, kBlock, 0, s>>>(src, dst, jobs, n_jobs, masks, tile_left, n_left_out);
+    return hipGetLastError();
+}
+
+hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
+                                        int64_t n, uint32_t missing, const PartJob *jobs, int n_jobs,
+                                        int total_tiles, uint64_t *masks, uint32_t *tile_left,
+                                        uint32_t *n_left_out) {
+    if (n_jobs <= 0 || total_tiles <= 0) return hipSuccess;
+    part_flag_kernel<<<total_tiles, kBlock, 0, s>>>(src.sym, bits, src.stride_bits, n, missing, nullptr, jobs, n_jobs,
+                                                    masks, tile_left);
+    part_scan_kernel<<<n_jobs, kBlock, 0, s>>>(jobs, tile_left, n_left_out);
+    part_move_kernel<<<total_tiles, kBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw,
+                                                    (int)(dst.stride_bits >> 5), row_bits, (const int2 *)src.gq,
+                                                    (int2 *)dst.gq_rw, src.id, dst.id_rw, jobs, n_jobs, masks,
+                                                    tile_left, n_left_out);
     return hipGetLastError();
 }

@@ -35,8 +35,8 @@ def test_host_only_calls(lib):
         assert g.bits_for(mv) == b
     assert g.packed_words(10_000, 8, 4) * 4 == 40_004
     assert g.packed_words(115_000_000, 13, 8) == (115_000_000 * 13 * 8 + 31) // 32 + 1
-    assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 16, 3) > 1000 * 16
-    assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 16, 99) == 0     # unsupported depth
+    assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 4, 16, 3) > 1000 * 16
+    assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 4, 16, 99) == 0     # unsupported depth
     assert lib.gbt_partition_workspace_bytes(10_000) >= 40_000
     # a null context is refused, not dereferenced
     assert lib.gbt_destroy(None) == g.binding.EINVAL
