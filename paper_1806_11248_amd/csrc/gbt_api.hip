@@ -718,9 +718,11 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
         if (st != GBT_OK) return st;
         const int wnext = wcur == 0 ? 1 : 0;
-        gbt_prof_begin(ctx, GBT_PROF_PARTITION, part_rows * (2.0 * (row_bits / 8.0 + 12.0)));
+        const bool children_need_hist = depth + 1 < max_depth;   // else they are leaves: only their ids matter
+        gbt_prof_begin(ctx, GBT_PROF_PARTITION,
+                       part_rows * (children_need_hist ? 2.0 * (row_bits / 8.0 + 12.0) : bits / 8.0 + 8.0));
         GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym,
-                                                  (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
+                                                  !children_need_hist, (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
                                                   (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
                                                   (uint32_t *)(ws + L.n_left)));
         gbt_prof_end(ctx);
@@ -731,7 +733,6 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         cur = W[wcur];
 
         // ---- children, in creation order
-        const bool children_need_hist = depth + 1 < max_depth;
         hjobs.clear();
         sjobs.clear();
         int64_t built_rows = 0;
@@ -873,8 +874,10 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
         o += gbt_align((size_t)T.n_nodes * 8);
     }
     GBT_HIP(ctx, hipMemcpyAsync(workspace, host.data(), o, hipMemcpyHostToDevice, ctx->stream));
+    int max_nodes = 1;
+    for (int t = 0; t < n_trees; ++t) max_nodes = std::max(max_nodes, trees[t].n_nodes);
     GBT_HIP(ctx, gbt_launch_predict(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees, packed,
-                                    bits, (uint32_t)missing_sym, X, n, F, eta, margin));
+                                    bits, (uint32_t)missing_sym, X, n, F, eta, margin, max_nodes));
     GBT_SYNC(ctx);
     return GBT_OK;
 }

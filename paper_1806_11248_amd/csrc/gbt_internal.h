@@ -149,9 +149,10 @@ struct GbtRows {
     uint32_t *id_rw;
 };
 // Stable partition of the jobs' segments of `src` into `dst` (records move, see kernels_partition.hip).
+// ids_only: move the row ids alone (the segments' children will not be read again).
 hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
-                                        int64_t n, uint32_t missing, const PartJob *jobs, int n_jobs,
-                                        int total_tiles, uint64_t *masks, uint32_t *tile_left,
+                                        int64_t n, uint32_t missing, bool ids_only, const PartJob *jobs,
+                                        int n_jobs, int total_tiles, uint64_t *masks, uint32_t *tile_left,
                                         uint32_t *n_left_out);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
@@ -168,7 +169,7 @@ struct DevTree {   // one tree's arrays inside the predict workspace (offsets in
 };
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
-                              int64_t n, int F, double eta, float *margin);
+                              int64_t n, int F, double eta, float *margin, int max_nodes);
 
 // quantise
 hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,

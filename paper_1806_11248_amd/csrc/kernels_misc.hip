@@ -209,19 +209,89 @@ __global__ void predict_kernel(const char *ws, const DevTree *trees, int n_trees
     }
 }
 
+// Same walk with the tree's nodes staged in LDS (32 bytes per node): the per-level
+// node fetches then cost an LDS read instead of a dependent global load.
+struct LdsNode {
+    int32_t feature, bin, left, right;
+    float thr;
+    int32_t dl;
+    double weight;
+};
+__global__ __launch_bounds__(256) void predict_lds_kernel(const char *ws, const DevTree *trees, int n_trees,
+                                                          const uint32_t *packed, int bits, uint32_t missing,
+                                                          const float *X, int64_t n, int F, double eta,
+                                                          float *margin, int rows_per_block) {
+    extern __shared__ LdsNode nodes[];
+    const uint32_t mask = (1u << bits) - 1u;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+    for (int t = 0; t < n_trees; ++t) {
+        const DevTree T = trees[t];
+        __syncthreads();   // the previous tree's walks are done
+        for (int i = threadIdx.x; i < T.n_nodes; i += 256) {
+            LdsNode nd;
+            nd.feature = ((const int32_t *)(ws + T.feature))[i];
+            nd.bin = ((const int32_t *)(ws + T.bin))[i];
+            nd.left = ((const int32_t *)(ws + T.left))[i];
+            nd.right = ((const int32_t *)(ws + T.right))[i];
+            nd.thr = ((const float *)(ws + T.threshold))[i];
+            nd.dl = ((const int32_t *)(ws + T.default_left))[i];
+            nd.weight = ((const double *)(ws + T.weight))[i];
+            nodes[i] = nd;
+        }
+        __syncthreads();
+        for (int64_t r = r0 + threadIdx.x; r < r1; r += 256) {
+            const uint64_t rowbit = (uint64_t)r * (uint64_t)F * (uint64_t)bits;
+            int node = 0;
+            for (int step = 0; step < T.n_nodes; ++step) {
+                const LdsNode nd = nodes[node];
+                if (nd.feature < 0) break;
+                bool go_left;
+                if (packed) {
+                    const uint64_t bp = rowbit + (uint64_t)nd.feature * (uint64_t)bits;
+                    const uint32_t *w = packed + (bp >> 5);
+                    const uint32_t sh = (uint32_t)(bp & 31);
+                    uint32_t v = w[0] >> sh;
+                    if (sh + (uint32_t)bits > 32u) v |= w[1] << (32u - sh);
+                    const uint32_t s = v & mask;
+                    go_left = (s == missing) ? (nd.dl != 0) : ((int)s <= nd.bin);
+                } else {
+                    const float x = X[r * F + nd.feature];
+                    go_left = (x != x) ? (nd.dl != 0) : (x < nd.thr);
+                }
+                node = go_left ? nd.left : nd.right;
+            }
+            margin[r] = (float)((double)margin[r] + eta * nodes[node].weight);
+        }
+    }
+}
+
 // Final row order and leaf ids: every position of [0, n) lies in exactly one
 // leaf segment; segments are sorted by seg_begin.
-__global__ void leaf_gather_kernel(const uint32_t *buf0, const uint32_t *buf1, const LeafSeg *segs,
-                                   int n_segs, int64_t n, uint32_t *row_idx_out, int32_t *leaf_of_row) {
-    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n;
-         p += (int64_t)gridDim.x * blockDim.x) {
-        int lo = 0, hi = n_segs;   // last segment with seg_begin <= p
+// Each workgroup takes a chunk of positions; the search starts from the segment of the chunk's
+// first position (found once) and only walks forward.
+constexpr int kGatherChunk = 256 * 16;
+__global__ __launch_bounds__(256) void leaf_gather_kernel(const uint32_t *buf0, const uint32_t *buf1,
+                                                          const LeafSeg *segs, int n_segs, int64_t n,
+                                                          uint32_t *row_idx_out, int32_t *leaf_of_row) {
+    const int64_t p0 = (int64_t)blockIdx.x * kGatherChunk;
+    __shared__ int first_seg;
+    if (threadIdx.x == 0) {
+        int lo = 0, hi = n_segs;   // last segment with seg_begin <= p0
         while (hi - lo > 1) {
             int mid = (lo + hi) >> 1;
-            if ((int64_t)segs[mid].seg_begin <= p) lo = mid; else hi = mid;
+            if ((int64_t)segs[mid].seg_begin <= p0) lo = mid; else hi = mid;
         }
-        LeafSeg s = segs[lo];
-        uint32_t r = s.buf == 2 ? (uint32_t)p : (s.buf ? buf1 : buf0)[p];
+        first_seg = lo;
+    }
+    __syncthreads();
+    int cur = first_seg;
+    for (int k = 0; k < kGatherChunk / 256; ++k) {
+        const int64_t p = p0 + (int64_t)k * 256 + threadIdx.x;
+        if (p >= n) break;
+        while (cur + 1 < n_segs && (int64_t)segs[cur + 1].seg_begin <= p) ++cur;
+        const LeafSeg s = segs[cur];
+        const uint32_t r = s.buf == 2 ? (uint32_t)p : (s.buf ? buf1 : buf0)[p];
         row_idx_out[p] = r;
         if (leaf_of_row && (int64_t)r < n) leaf_of_row[r] = (int32_t)s.node;
     }
@@ -302,8 +372,23 @@ hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_ele
 }
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
-                              int64_t n, int F, double eta, float *margin) {
+                              int64_t n, int F, double eta, float *margin, int max_nodes) {
     if (n <= 0) return hipSuccess;
+    const size_t lds = (size_t)max_nodes * sizeof(LdsNode);
+    if (lds <= 96u * 1024u) {
+        static size_t configured = 0;
+        if (lds > configured) {
+            hipError_t e = hipFuncSetAttribute((const void *)predict_lds_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            configured = lds;
+        }
+        const int rows_per_block = 256 * 16;
+        const int64_t grid = (n + rows_per_block - 1) / rows_per_block;
+        predict_lds_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, bits, missing, X, n, F, eta,
+                                                            margin, rows_per_block);
+        return hipGetLastError();
+    }
     predict_kernel<<<grid_for(n, kBlock, 1 << 16), kBlock, 0, s>>>(ws, trees, n_trees, packed, bits,
                                                                     missing, X, n, F, eta, margin);
     return hipGetLastError();
@@ -312,7 +397,7 @@ hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uin
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,
                                   int32_t *leaf_of_row) {
     if (n <= 0 || n_segs <= 0) return hipSuccess;
-    leaf_gather_kernel<<<grid_for(n, kBlock * 4, 16384), kBlock, 0, s>>>(buf0, buf1, segs, n_segs, n,
-                                                                         row_idx_out, leaf_of_row);
+    const int64_t grid = (n + kGatherChunk - 1) / kGatherChunk;
+    leaf_gather_kernel<<<(unsigned)grid, 256, 0, s>>>(buf0, buf1, segs, n_segs, n, row_idx_out, leaf_of_row);
     return hipGetLastError();
 }

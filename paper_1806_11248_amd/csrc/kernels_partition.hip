@@ -43,8 +43,10 @@ __device__ inline int find_job(const PartJob *jobs, int n_jobs, uint32_t tile) {
 
 __device__ inline uint32_t load_symbol(const uint32_t *packed, uint64_t bp, int bits, uint32_t mask) {
     const uint32_t *w = packed + (bp >> 5);
-    uint64_t v = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
-    return (uint32_t)(v >> (bp & 31)) & mask;
+    const uint32_t sh = (uint32_t)(bp & 31);
+    uint32_t v = w[0] >> sh;
+    if (sh + (uint32_t)bits > 32u) v |= w[1] << (32u - sh);   // the element straddles into the next word
+    return v & mask;
 }
 
 // src == NULL: the segment's rows are matrix rows seg_begin .. seg_begin+seg_len-1
@@ -213,7 +215,13 @@ __global__ __launch_bounds__(kBlock) void part_move_kernel(
     const uint32_t tail_bits = (uint32_t)(row_bits - 32 * (SW - 1));   // valid bits of a row's last word, 1..32
     const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
     const uint64_t p0 = (uint64_t)job.seg_begin + base;
-    if (SW <= 16) {
+    if (SW == 4 && src_stride_bits == 128) {
+        // 16-byte rows on both sides (both buffers are 256-byte aligned): one 128-bit load and store per row
+        const uint4 *s4 = (const uint4 *)src_sym;
+        uint4 *d4 = (uint4 *)dst_sym;
+        for (uint32_t in_tile = threadIdx.x; in_tile < tile_rows; in_tile += kBlock)
+            d4[dstpos[in_tile]] = s4[p0 + in_tile];
+    } else if (SW <= 16) {
         // short rows: one lane copies one row
         for (uint32_t in_tile = threadIdx.x; in_tile < tile_rows; in_tile += kBlock) {
             const uint64_t sb = (p0 + in_tile) * (uint64_t)src_stride_bits;
@@ -249,6 +257,52 @@ __global__ __launch_bounds__(kBlock) void part_move_kernel(
     }
 }
 
+// Same ranks as part_move_kernel, but only the ids move (the children are leaves: nobody will
+// read their symbols or gradient pairs again).
+__global__ __launch_bounds__(kBlock) void part_move_ids_kernel(
+    const uint32_t *__restrict__ src_id, uint32_t *__restrict__ dst_id, const PartJob *__restrict__ jobs,
+    int n_jobs, const uint64_t *__restrict__ masks, const uint32_t *__restrict__ tile_left_off,
+    const uint32_t *__restrict__ n_left) {
+    const uint32_t tile = blockIdx.x;
+    const int ji = find_job(jobs, n_jobs, tile);
+    const PartJob job = jobs[ji];
+    const uint32_t base = (tile - job.tile_begin) * kTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ uint64_t words[kWordsPerTile];
+    __shared__ uint32_t lefts_before[kWordsPerTile];
+    if (threadIdx.x < kWordsPerTile) words[threadIdx.x] = masks[(uint64_t)tile * kWordsPerTile + threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0;
+        for (int w = 0; w < kWordsPerTile; ++w) {
+            lefts_before[w] = acc;
+            acc += (uint32_t)__popcll(words[w]);
+        }
+    }
+    __syncthreads();
+    const uint32_t left_base = tile_left_off[tile];
+    const uint32_t right_base = base - left_base;
+    const uint32_t seg_n_left = n_left[ji];
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        const int w = j * (kBlock / 64) + wave;
+        const uint32_t off = base + (uint32_t)w * 64u + (uint32_t)lane;
+        if (off < job.seg_len) {
+            const uint64_t m = words[w];
+            const uint32_t below = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            const uint64_t p = (uint64_t)job.seg_begin + off;
+            uint32_t pos;
+            if ((m >> lane) & 1ull) {
+                pos = left_base + lefts_before[w] + below;
+            } else {
+                const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[w];
+                pos = seg_n_left + right_base + rights_before_word + ((uint32_t)lane - below);
+            }
+            dst_id[(uint64_t)job.seg_begin + pos] = src_id ? src_id[p] : (uint32_t)p;
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n,
@@ -264,13 +318,18 @@ hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits,
 }
 
 hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
-                                        int64_t n, uint32_t missing, const PartJob *jobs, int n_jobs,
-                                        int total_tiles, uint64_t *masks, uint32_t *tile_left,
+                                        int64_t n, uint32_t missing, bool ids_only, const PartJob *jobs,
+                                        int n_jobs, int total_tiles, uint64_t *masks, uint32_t *tile_left,
                                         uint32_t *n_left_out) {
     if (n_jobs <= 0 || total_tiles <= 0) return hipSuccess;
     part_flag_kernel<<<total_tiles, kBlock, 0, s>>>(src.sym, bits, src.stride_bits, n, missing, nullptr, jobs, n_jobs,
                                                     masks, tile_left);
     part_scan_kernel<<<n_jobs, kBlock, 0, s>>>(jobs, tile_left, n_left_out);
+    if (ids_only) {
+        part_move_ids_kernel<<<total_tiles, kBlock, 0, s>>>(src.id, dst.id_rw, jobs, n_jobs, masks, tile_left,
+                                                            n_left_out);
+        return hipGetLastError();
+    }
     part_move_kernel<<<total_tiles, kBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw,
                                                     (int)(dst.stride_bits >> 5), row_bits, (const int2 *)src.gq,
                                                     (int2 *)dst.gq_rw, src.id, dst.id_rw, jobs, n_jobs, masks,
