@@ -1,0 +1,138 @@
+"""GPU parity at the workloads' FULL sizes, in the launch configuration bench.py
+times (-m gpu).  The oracle still checks every row's final position, every
+node's totals and leaf weight, and every split the GPU chose (its fp64 gain);
+the exhaustive best-split search is repeated on a sample of nodes."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from gpu_util import dev, hist_tolerance, host_u32, tree_kw
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_1806_11248_amd as g
+    c = g.Context(0)
+    yield c
+    c.close()
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _sample_nodes(tree, k=24, seed=0):
+    nn = tree["n_nodes"]
+    rng = np.random.default_rng(seed)
+    pick = set(range(min(nn, 7))) | set(int(i) for i in rng.choice(nn, min(k, nn), replace=False))
+    return pick
+
+
+def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True):
+    import paper_1806_11248_amd as g
+    t0 = time.time()
+    d = synth.make(cfg)
+    p = d["params"]
+    X = d["X"]
+    n, F = X.shape
+    B = p["max_bins"]
+    _say(f"C{cfg} full size {n} x {F}: generated in {time.time() - t0:.1f} s")
+
+    # ---- quantise + compress on the GPU, the oracle's on the CPU
+    t0 = time.time()
+    if csr:
+        indptr, indices, values = synth.dense_to_csr(X)
+        cuts, nb, sym, mv, ms = ctx.quantise(csr=(dev(indptr), dev(indices), dev(values)), max_bins=B, n=n, F=F)
+        del indptr, indices, values
+    else:
+        cuts, nb, sym, mv, ms = ctx.quantise(dev(X), max_bins=B)
+    packed, bits = ctx.compress(sym, mv)
+    torch.cuda.synchronize()
+    _say(f"  gpu quantise+compress {time.time() - t0:.2f} s (bits={bits})")
+    t0 = time.time()
+    o_cuts, o_nb = oracle.cuts(X, B)
+    o_sym, o_missing, o_mx = oracle.bin_matrix(X, o_cuts, o_nb)
+    _say(f"  oracle quantise {time.time() - t0:.1f} s")
+    assert np.array_equal(nb.cpu().numpy(), o_nb)
+    assert np.array_equal(cuts.cpu().numpy(), o_cuts)
+    assert (mv, ms) == (o_mx, o_missing) and bits == oracle.bits_for(o_mx)
+    # symbols: bit-exact, compared in slabs to bound host memory
+    step = max(1, (64 << 20) // max(F, 1))
+    for lo in range(0, n, step):
+        assert np.array_equal(sym[lo:lo + step].cpu().numpy(), o_sym[lo:lo + step]), f"symbols differ in rows {lo}.."
+    del sym
+    # packed words: whole rows that start on a word boundary, packed by the oracle
+    period = 32 // np.gcd(32, F * bits)                # rows per word-aligned group
+    words = host_u32(packed)
+    rng = np.random.default_rng(cfg)
+    for r0 in list(rng.integers(0, max(1, n // period - 64), 6) * period) + [0, (n // period - 1) * period]:
+        r0 = int(r0)
+        r1 = min(n, r0 + 37 * period)
+        w0 = r0 * F * bits // 32
+        ref = oracle.pack(o_sym[r0:r1], bits)[:-1]
+        if r1 < n and ((r1 - r0) * F * bits) % 32:
+            ref = ref[:-1]                              # the last word also holds bits of the next row
+        assert np.array_equal(words[w0:w0 + len(ref)], ref)
+    assert words[-1] == 0 and len(words) == oracle.packed_words(n * F, bits)
+    del words
+
+    margin_gpu = torch.zeros(n, dtype=torch.float32, device="cuda")
+    margin_ref = np.zeros(n, np.float32)
+    y_t = dev(d["y"])
+    params = g.make_params(max_depth=p["max_depth"], max_bins=B, lam=p["lam"], gamma=p["gamma"],
+                           min_child_weight=p["min_child_weight"])
+    for r in range(rounds):
+        gp_ref = oracle.gradients(p["objective"], margin_ref, d["y"])
+        gp_t = ctx.gradients(p["objective"], margin_gpu, y_t)
+        gp_gpu = gp_t.cpu().numpy()
+        assert np.allclose(gp_gpu, gp_ref, rtol=1e-5, atol=1e-6)
+        gp_t = dev(gp_ref)                               # the same fp32 pairs feed both sides
+        gq, scale = ctx.gpair_fixed(gp_t)
+        if check_root_hist and r == 0:
+            t0 = time.time()
+            h = ctx.build_hist(packed, bits, n, F, B, ms, gq)
+            hf = ctx.hist_export_f64(h, scale).cpu().numpy()
+            ref, cnt, G, H = oracle.hist(o_sym, B, o_missing, None, gp_ref)
+            assert np.all(np.abs(hf - ref) <= hist_tolerance(ref, cnt, scale))
+            quantum = 0.5 / np.array(scale)
+            big = np.abs(ref) >= np.maximum(cnt, 1)[..., None] * quantum / 1e-5
+            assert np.all(np.abs(hf - ref)[big] <= 1e-5 * np.abs(ref)[big])
+            _say(f"  root histogram checked in {time.time() - t0:.1f} s ({big[cnt > 0].mean():.3f} of bins to plain 1e-5)")
+        del gq
+        t0 = time.time()
+        tree, row_idx, leaf = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_t, params)
+        torch.cuda.synchronize()
+        t_gpu = time.time() - t0
+        t0 = time.time()
+        rep = oracle.replay_tree(tree, o_sym, o_nb, o_missing, gp_ref, **tree_kw(p),
+                                 sum_atol_per_row=0.5 / min(scale), nodes=_sample_nodes(tree, seed=r))
+        _say(f"  round {r}: gpu tree {t_gpu * 1e3:.1f} ms, {tree['n_nodes']} nodes; oracle replay {time.time() - t0:.1f} s, "
+             f"{rep['checked_splits']} exhaustive searches, identical={rep['identical']}, ties={len(rep['ties'])}")
+        assert rep["ok"], rep["errors"][:5]
+        assert np.array_equal(host_u32(row_idx), rep["row_idx"])
+        assert np.array_equal(leaf.cpu().numpy(), rep["leaf_of_row"])
+        del row_idx, leaf
+        ctx.predict([tree], margin_gpu, p["eta"], packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
+        margin_ref = oracle.predict_sym(tree, o_sym, o_missing, p["eta"], margin_ref)
+        assert np.allclose(margin_gpu.cpu().numpy(), margin_ref, rtol=1e-5, atol=1e-6)
+
+
+def test_full_c2_dense_classification(ctx, oracle):
+    _full_case(ctx, oracle, 2, csr=False, rounds=10)
+
+
+def test_full_c3_sparse_regression(ctx, oracle):
+    _full_case(ctx, oracle, 3, csr=True, rounds=2)
+
+
+def test_full_c5_wide(ctx, oracle):
+    _full_case(ctx, oracle, 5, csr=False, rounds=1)
+
+
+def test_full_c4_large_tabular(ctx, oracle):
+    _full_case(ctx, oracle, 4, csr=False, rounds=1)
