@@ -53,6 +53,21 @@ def load_workload(cfg, rows, cache_dir):
     return d
 
 
+def measured_traffic(cfg):
+    """HBM bytes per launch of the histogram kernel as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE on this very command (see the file for the commands); None when no such summary is
+    committed for the workload."""
+    path = os.path.join(ROOT, "profiles", f"hist_kernel_c{cfg}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    out = {}
+    for line in open(path):
+        if line.startswith("@"):
+            k, v = line[1:].split("=", 1)
+            out[k.strip()] = float(v)
+    return out or None
+
+
 def cpu_baseline(d, sample_rows):
     """The oracle's tree (its own quantisation, fp64 histograms, exhaustive
     split search) on the first `sample_rows` rows, timed on the host cores."""
@@ -60,13 +75,14 @@ def cpu_baseline(d, sample_rows):
     import oracle
     p = d["params"]
     X = np.ascontiguousarray(d["X"][:sample_rows])
-    y = d["y"][:sample_rows]
+    y = None if d["y"] is None else d["y"][:sample_rows]
     n, F = X.shape
     t0 = time.time()
     cuts, nb = oracle.cuts(X, p["max_bins"])
     sym, missing, _ = oracle.bin_matrix(X, cuts, nb)
     t_q = time.time() - t0
-    gp = oracle.gradients(p["objective"], np.zeros(n, np.float32), y)
+    gp = (np.stack([d["g"][:sample_rows], d["h"][:sample_rows]], 1) if p["objective"] == "given"
+          else oracle.gradients(p["objective"], np.zeros(n, np.float32), y))
     t0 = time.time()
     oracle.hist(sym, p["max_bins"], missing, None, gp)
     t_hist = time.time() - t0
@@ -92,6 +108,9 @@ def main():
     ap.add_argument("--data-cache", default=None, help="directory to keep the generated inputs in")
     ap.add_argument("--cpu-sample-rows", type=int, default=4_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of the packed matrix (a kernel of known size to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); --gpus must be 1",
@@ -108,18 +127,26 @@ def main():
     X = d["X"]
     n, F = X.shape
     log(f"workload C{a.config}: {n} x {F}, generated in {time.time() - t0:.1f} s")
-    if p["objective"] == "given":
-        raise SystemExit("workload 1 carries its own gradient pairs; bench configs 2..5")
+    given = p["objective"] == "given"   # workload 1 carries its own gradient pairs: a step is the tree alone
 
     ctx = g.Context(0)
     dev = ctx.device
     # ---- one-off preprocessing: quantise + compress (Sec. 2.1, 2.2)
     t0 = time.time()
-    Xd = torch.from_numpy(X).to(dev)
+    if a.config == 3:   # the sparse workload enters as CSR
+        import synth
+        csr = tuple(torch.from_numpy(v).to(dev) for v in synth.dense_to_csr(X))
+        Xd = None
+    else:
+        Xd = torch.from_numpy(X).to(dev)
     torch.cuda.synchronize()
     t_h2d = time.time() - t0
     t0 = time.time()
-    cuts, nb, sym, mv, ms = ctx.quantise(Xd, max_bins=p["max_bins"])
+    if Xd is None:
+        cuts, nb, sym, mv, ms = ctx.quantise(csr=csr, max_bins=p["max_bins"], n=n, F=F)
+        del csr
+    else:
+        cuts, nb, sym, mv, ms = ctx.quantise(Xd, max_bins=p["max_bins"])
     torch.cuda.synchronize()
     t_quant = time.time() - t0
     t0 = time.time()
@@ -130,9 +157,10 @@ def main():
     torch.cuda.empty_cache()
     log(f"H2D {t_h2d:.2f} s, quantise {t_quant * 1e3:.1f} ms, compress {t_comp * 1e3:.1f} ms, bits={bits}")
 
-    y = torch.from_numpy(d["y"]).to(dev)
+    y = None if given else torch.from_numpy(d["y"]).to(dev)
     margin = torch.zeros(n, dtype=torch.float32, device=dev)
-    gp = torch.empty((n, 2), dtype=torch.float32, device=dev)
+    gp = (torch.from_numpy(np.stack([d["g"], d["h"]], 1)).to(dev) if given
+          else torch.empty((n, 2), dtype=torch.float32, device=dev))
     row_idx = torch.empty(n, dtype=torch.int32, device=dev)
     params = g.make_params(max_depth=p["max_depth"], max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
                            min_child_weight=p["min_child_weight"], eta=p["eta"], objective=p["objective"])
@@ -143,7 +171,8 @@ def main():
     def step():
         if single_tree:
             margin.zero_()
-        ctx.gradients(p["objective"], margin, y, out=gp)
+        if not given:
+            ctx.gradients(p["objective"], margin, y, out=gp)
         tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_leaf=False, row_idx_out=row_idx)
         ctx.predict([tree], margin, eta, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
         trees.append(tree)
@@ -151,6 +180,12 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
+    if a.copy_calibration:
+        scratch = torch.empty_like(packed)
+        scratch.copy_(packed)
+        torch.cuda.synchronize()
+        log(f"copy calibration: one device copy of {packed.numel() * 4} bytes")
+        del scratch
     ctx.profile_enable(True)
     ctx.profile_read()
     torch.cuda.synchronize()
@@ -166,7 +201,7 @@ def main():
         ", ".join(f"{k}={v['ms'] / a.steps:.3f}" for k, v in prof.items()))
     log(f"nodes per tree: {[t['n_nodes'] for t in trees[-a.steps:]]}")
 
-    def roof(classes):
+    def roof(classes, kernel):
         ms_ = sum(prof[c]["ms"] for c in classes)
         by = sum(prof[c]["bytes"] for c in classes)
         launches = sum(prof[c]["launches"] for c in classes)
@@ -174,16 +209,23 @@ def main():
             return None
         ach = by / (ms_ * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBPS,
-                "traffic": None, "kernel": "hist_generic_kernel", "launches": launches,
+                "traffic": None, "kernel": kernel, "launches": launches,
                 "avg_launch_ms": ms_ / max(launches, 1), "algorithmic_bytes_per_launch": by / max(launches, 1)}
 
-    roofline = roof(["hist_root", "hist_node"])
-    roofline_root = roof(["hist_root"])
+    hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_generic_kernel"
+    roofline = roof(["hist_root", "hist_node"], hist_kernel)
+    roofline_root = roof(["hist_root"], hist_kernel)
+    roofline_partition = roof(["partition"], "part_flag_kernel + part_scan_kernel + part_move_kernel")
+    traffic = measured_traffic(a.config)
+    if roofline and traffic:
+        roofline["traffic"] = traffic.get("hist_all_launches_avg_bytes")
+        roofline_root["traffic"] = traffic.get("hist_root_launch_bytes")
     root_ms = prof["hist_root"]["ms"] / max(prof["hist_root"]["launches"], 1)
 
     out = {
         "metric": "histogram-tree build throughput: rows*features/s of one boosting step "
-                  "(gradients + one depth-%d tree + margin update)" % p["max_depth"],
+                  "(%sone depth-%d tree%s)" % ("" if given else "gradients + ", p["max_depth"],
+                                              "" if given else " + margin update"),
         "value": n * F / (ms_per_step * 1e-3),
         "unit": "rows*features/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
@@ -198,6 +240,7 @@ def main():
         "hist_root_rows_features_per_s": (n * F / (root_ms * 1e-3)) if root_ms > 0 else None,
         "roofline": roofline,
         "roofline_root": roofline_root,
+        "roofline_partition": roofline_partition,
         "device_ms_per_step": {k: v["ms"] / a.steps for k, v in prof.items()},
         "preprocess_ms": {"quantise": t_quant * 1e3, "compress": t_comp * 1e3, "h2d_raw_matrix": t_h2d * 1e3},
     }
