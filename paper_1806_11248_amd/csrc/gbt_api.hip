@@ -92,6 +92,14 @@ uint32_t pick_rows_per_job(const gbt_ctx *ctx, int64_t total_rows) {
     return (uint32_t)rpj;
 }
 
+// Best of one node's per-chunk split records: largest gain, earliest chunk on ties.
+gbt_split merge_chunks(const gbt_split *rec, int n_chunks) {
+    gbt_split best = rec[0];
+    for (int c = 1; c < n_chunks; ++c)
+        if (rec[c].valid && (!best.valid || rec[c].gain > best.gain)) best = rec[c];
+    return best;
+}
+
 // The first half of the pinned staging is a ring of upload slots: a slot may be
 // overwritten only after the copy (or kernel) that reads it has finished, which
 // a stream synchronisation guarantees; wrapping therefore synchronises first.
@@ -396,11 +404,12 @@ extern "C" int32_t gbt_eval_split(gbt_ctx *ctx, const int64_t *hist, const int32
     st = upload(ctx, &nd, sizeof nd, ws);
     if (st != GBT_OK) return st;
     gbt_split *dsplit = (gbt_split *)(ws + 256);
-    GBT_HIP(ctx, gbt_launch_eval(ctx->stream, hist, (const EvalNode *)ws, 1, nb, F, B, 1.0 / scale[0],
+    const int chunks = gbt_eval_chunks(F, 1, workspace_bytes - 256);
+    GBT_HIP(ctx, gbt_launch_eval(ctx->stream, hist, (const EvalNode *)ws, 1, nb, F, B, chunks, 1.0 / scale[0],
                                  1.0 / scale[1], params->lambda, params->min_child_weight, dsplit));
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), dsplit, sizeof(gbt_split), hipMemcpyDeviceToHost, ctx->stream));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), dsplit, chunks * sizeof(gbt_split), hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
-    memcpy(split_out, rb(ctx), sizeof(gbt_split));
+    *split_out = merge_chunks((const gbt_split *)rb(ctx), chunks);
     return GBT_OK;
 }
 
@@ -531,7 +540,7 @@ GrowLayout grow_layout(int64_t n, int F, int bits, int B, int max_depth) {
     L.n_left = o;     o += gbt_align((size_t)L.level_nodes * 4);
     L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
     L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * sizeof(EvalNode));
-    L.splits = o;     o += gbt_align((size_t)L.level_nodes * sizeof(gbt_split));
+    L.splits = o;     o += gbt_align(GBT_STAGING_BYTES / 2);   // per-(node, feature chunk) records of one level
     L.jobs = o;       o += gbt_align(kUploadBytes);
     L.scratch = o;    o += 4096;
     L.total = o;
@@ -669,17 +678,19 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
         st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
         if (st != GBT_OK) return st;
+        const int chunks = gbt_eval_chunks(F, (int)level.size(), GBT_STAGING_BYTES - kReadbackOff);
         gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)level.size() * (double)hist_len * 8.0);
         GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)level.size(), nb, F, B,
-                                     inv_sg, inv_sh, lambda, params->min_child_weight,
+                                     chunks, inv_sg, inv_sh, lambda, params->min_child_weight,
                                      (gbt_split *)(ws + L.splits)));
         gbt_prof_end(ctx);
-        const size_t sbytes = level.size() * sizeof(gbt_split);
+        const size_t sbytes = level.size() * chunks * sizeof(gbt_split);
         GBT_REQUIRE(ctx, sbytes <= GBT_STAGING_BYTES - kReadbackOff, GBT_EUNSUPPORTED, "level too wide");
         GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
         GBT_SYNC(ctx);
         splits.resize(level.size());
-        memcpy(splits.data(), rb(ctx), sbytes);
+        for (size_t i = 0; i < level.size(); ++i)
+            splits[i] = merge_chunks((const gbt_split *)rb(ctx) + i * chunks, chunks);
 
         // ---- which nodes split; RepartitionInstances for those
         pjobs.clear();

@@ -127,9 +127,11 @@ hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64
 // Largest feature tile whose LDS histogram fits, and the per-job row count to aim for.
 int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B);
 
+// out receives n_nodes * n_chunks records (node-major); gbt_eval_chunks picks n_chunks.
+int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes);
 hipError_t gbt_launch_eval(hipStream_t s, const int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
-                           const int32_t *nb, int F, int B, double inv_sg, double inv_sh, double lambda,
-                           double mcw, gbt_split *out);
+                           const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
+                           double lambda, double mcw, gbt_split *out);
 
 hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n,
                                 uint32_t missing, const uint32_t *src, uint32_t *dst,

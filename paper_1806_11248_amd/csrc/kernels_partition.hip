@@ -160,18 +160,21 @@ __global__ __launch_bounds__(kBlock) void part_scatter_kernel(
 
 // Scatter of whole records.  dst rows are SW words each; src rows start at bit
 // p*src_stride_bits (any alignment).  src_id == NULL: the id of the row at
-// position p is p itself.
+// position p is p itself.  Long rows are cut into slices of `slice_words` words,
+// one workgroup per (tile, slice) (blockIdx.y); slice 0 also moves ids and pairs.
 __global__ __launch_bounds__(kBlock) void part_move_kernel(
     const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words,
     uint32_t *__restrict__ dst_sym, int SW, int row_bits, const int2 *__restrict__ src_gq,
     int2 *__restrict__ dst_gq, const uint32_t *__restrict__ src_id, uint32_t *__restrict__ dst_id,
     const PartJob *__restrict__ jobs, int n_jobs, const uint64_t *__restrict__ masks,
-    const uint32_t *__restrict__ tile_left_off, const uint32_t *__restrict__ n_left) {
+    const uint32_t *__restrict__ tile_left_off, const uint32_t *__restrict__ n_left, int slice_words) {
     const uint32_t tile = blockIdx.x;
     const int ji = find_job(jobs, n_jobs, tile);
     const PartJob job = jobs[ji];
     const uint32_t base = (tile - job.tile_begin) * kTile;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k_begin = (int)blockIdx.y * slice_words;
+    const int k_end = k_begin + slice_words < SW ? k_begin + slice_words : SW;
 
     __shared__ uint64_t words[kWordsPerTile];
     __shared__ uint32_t lefts_before[kWordsPerTile];
@@ -206,9 +209,11 @@ __global__ __launch_bounds__(kBlock) void part_move_kernel(
             }
             const uint32_t q = job.seg_begin + pos;
             dstpos[in_tile] = q;
-            const uint64_t p = (uint64_t)job.seg_begin + base + in_tile;
-            dst_id[q] = src_id ? src_id[p] : (uint32_t)p;
-            dst_gq[q] = src_gq[p];
+            if (blockIdx.y == 0) {
+                const uint64_t p = (uint64_t)job.seg_begin + base + in_tile;
+                dst_id[q] = src_id ? src_id[p] : (uint32_t)p;
+                dst_gq[q] = src_gq[p];
+            }
         }
     }
     __syncthreads();
@@ -221,31 +226,22 @@ __global__ __launch_bounds__(kBlock) void part_move_kernel(
         uint4 *d4 = (uint4 *)dst_sym;
         for (uint32_t in_tile = threadIdx.x; in_tile < tile_rows; in_tile += kBlock)
             d4[dstpos[in_tile]] = s4[p0 + in_tile];
-    } else if (SW <= 16) {
-        // short rows: one lane copies one row
-        for (uint32_t in_tile = threadIdx.x; in_tile < tile_rows; in_tile += kBlock) {
-            const uint64_t sb = (p0 + in_tile) * (uint64_t)src_stride_bits;
-            const int64_t s0 = (int64_t)(sb >> 5);
-            const uint32_t sh = (uint32_t)(sb & 31);
-            uint32_t *d = dst_sym + (uint64_t)dstpos[in_tile] * (uint64_t)SW;
-            uint32_t lo = src_sym[s0 < src_words ? s0 : src_words - 1];
-            for (int k = 0; k < SW; ++k) {
-                const int64_t si = s0 + k + 1;
-                const uint32_t hi = src_sym[si < src_words ? si : src_words - 1];
-                uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh);
-                if (k == SW - 1) v &= tail_mask;
-                d[k] = v;
-                lo = hi;
-            }
-        }
     } else {
-        // long rows: one wave copies one row, lanes across its words
-        for (uint32_t in_tile = (uint32_t)wave; in_tile < tile_rows; in_tile += kBlock / 64) {
+        // a group of lanes (the next power of two >= SW, at most 64) copies one row, one word per
+        // lane and step: the words of a row, and the rows of a run, are written side by side
+        const int nk = k_end - k_begin;
+        int lpr = 1;
+        while (lpr < nk && lpr < 64) lpr <<= 1;
+        const int rows_per_wave = 64 / lpr;
+        const int sub = lane / lpr, k0 = lane % lpr;
+        for (uint32_t row0 = (uint32_t)wave * rows_per_wave; row0 < tile_rows; row0 += (kBlock / 64) * rows_per_wave) {
+            const uint32_t in_tile = row0 + (uint32_t)sub;
+            if (in_tile >= tile_rows) continue;
             const uint64_t sb = (p0 + in_tile) * (uint64_t)src_stride_bits;
             const int64_t s0 = (int64_t)(sb >> 5);
             const uint32_t sh = (uint32_t)(sb & 31);
             uint32_t *d = dst_sym + (uint64_t)dstpos[in_tile] * (uint64_t)SW;
-            for (int k = lane; k < SW; k += 64) {
+            for (int k = k_begin + k0; k < k_end; k += lpr) {
                 const int64_t si = s0 + k;
                 const uint32_t lo = src_sym[si < src_words ? si : src_words - 1];
                 const uint32_t hi = src_sym[si + 1 < src_words ? si + 1 : src_words - 1];
@@ -330,9 +326,11 @@ hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const
                                                             n_left_out);
         return hipGetLastError();
     }
-    part_move_kernel<<<total_tiles, kBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw,
-                                                    (int)(dst.stride_bits >> 5), row_bits, (const int2 *)src.gq,
-                                                    (int2 *)dst.gq_rw, src.id, dst.id_rw, jobs, n_jobs, masks,
-                                                    tile_left, n_left_out);
+    const int SW = (int)(dst.stride_bits >> 5);
+    const int slice_words = SW <= 64 ? SW : 64;   // a wave copies 256 contiguous bytes of a row per step
+    dim3 grid((unsigned)total_tiles, (unsigned)((SW + slice_words - 1) / slice_words));
+    part_move_kernel<<<grid, kBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw, SW, row_bits,
+                                             (const int2 *)src.gq, (int2 *)dst.gq_rw, src.id, dst.id_rw, jobs,
+                                             n_jobs, masks, tile_left, n_left_out, slice_words);
     return hipGetLastError();
 }

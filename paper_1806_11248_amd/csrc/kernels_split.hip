@@ -2,7 +2,9 @@
 // feature and each quantile by performing a scan over the gradient histogram ...
 // a parallel prefix sum").
 //
-// One workgroup per node; each wave takes whole features.  For a feature the
+// One workgroup per (node, feature chunk); each wave takes whole features.  With several
+// chunks per node the caller merges the chunks' records (largest gain, first chunk on ties:
+// chunks are in feature order, so that is the candidate order).  For a feature the
 // wave first reduces the bins to get the node's missing mass for that feature,
 // then runs an inclusive wave-level prefix scan (64 bins per step, carry between
 // steps) over the exact int64 sums and prices every (bin, direction) candidate
@@ -52,8 +54,11 @@ __device__ inline bool better(double ga, uint32_t ka, double gb, uint32_t kb) {
 
 __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     const int64_t *__restrict__ pool, const EvalNode *__restrict__ nodes, const int32_t *__restrict__ nb,
-    int F, int B, double inv_sg, double inv_sh, double lambda, double mcw, gbt_split *__restrict__ out) {
+    int F, int B, int f_per_chunk, double inv_sg, double inv_sh, double lambda, double mcw,
+    gbt_split *__restrict__ out) {
     const EvalNode nd = nodes[blockIdx.x];
+    const int f_begin = blockIdx.y * f_per_chunk;
+    const int f_end = f_begin + f_per_chunk < F ? f_begin + f_per_chunk : F;
     const int64_t *hist = pool + nd.hist_off;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t Gq = nd.Gq, Hq = nd.Hq;
@@ -66,7 +71,7 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     best.GLq = 0;
     best.HLq = 0;
 
-    for (int f = wave; f < F; f += kEvalWaves) {
+    for (int f = f_begin + wave; f < f_end; f += kEvalWaves) {
         int nbf = nb[f];
         if (nbf > B) nbf = B;
         const int64_t *hf = hist + (int64_t)f * B * 2;
@@ -162,16 +167,25 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
             s.GR = (double)(Gq - r.GLq) * inv_sg;
             s.HR = (double)(Hq - r.HLq) * inv_sh;
         }
-        out[blockIdx.x] = s;
+        out[(size_t)blockIdx.x * gridDim.y + blockIdx.y] = s;
     }
 }
 
 }  // namespace
 
+int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes) {
+    int chunks = (F + 63) / 64;   // about 64 features (16 per wave) per workgroup
+    if (chunks > 64) chunks = 64;
+    while (chunks > 1 && (size_t)n_nodes * chunks * sizeof(gbt_split) > record_budget_bytes) --chunks;
+    return chunks < 1 ? 1 : chunks;
+}
+
 hipError_t gbt_launch_eval(hipStream_t s, const int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
-                           const int32_t *nb, int F, int B, double inv_sg, double inv_sh, double lambda,
-                           double mcw, gbt_split *out) {
+                           const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
+                           double lambda, double mcw, gbt_split *out) {
     if (n_nodes <= 0) return hipSuccess;
-    eval_kernel<<<n_nodes, kEvalBlock, 0, s>>>(hist_pool, nodes, nb, F, B, inv_sg, inv_sh, lambda, mcw, out);
+    const int f_per_chunk = (F + n_chunks - 1) / n_chunks;
+    dim3 grid((unsigned)n_nodes, (unsigned)n_chunks);
+    eval_kernel<<<grid, kEvalBlock, 0, s>>>(hist_pool, nodes, nb, F, B, f_per_chunk, inv_sg, inv_sh, lambda, mcw, out);
     return hipGetLastError();
 }
