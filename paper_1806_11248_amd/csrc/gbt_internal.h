@@ -24,6 +24,8 @@ struct gbt_ctx {
     char *pinned;           // host staging for job tables and small read-backs
     size_t pinned_bytes;
     int hist_block;         // threads per histogram workgroup
+    int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
+    int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
     size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
     char err[512];

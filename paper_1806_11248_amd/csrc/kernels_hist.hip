@@ -267,13 +267,105 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
     flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
 }
 
+// ---------------------------------------------------------------------------
+// Compile-time symbol width other than 8 bits.  lane = one row; the row slice is
+// consumed in register windows of E = min(128 / BITS, 32) whole elements: five
+// words are loaded, funnel-shifted (v_alignbit) so that the window starts at bit
+// 0, and every element is then cut out at a compile-time position.  Atomics are
+// issued in groups of up to 16 before their returned words are examined.  A slot
+// without a live feature, a missing symbol or a symbol >= B goes to a spare row
+// of 64 words indexed by the lane (conflict-free) instead of being predicated.
+// ---------------------------------------------------------------------------
+template <int BITS, bool LIST>
+__global__ __launch_bounds__(kHistBlock) void hist_static_kernel(
+    const uint32_t *__restrict__ packed, int64_t n_words, int64_t stride_bits, int64_t n, int B, int Bp,
+    uint32_t missing, const uint32_t *__restrict__ row_idx, const int2 *__restrict__ gq,
+    int64_t *__restrict__ pool, const HistJob *__restrict__ jobs) {
+    constexpr int E = (128 / BITS) < 32 ? (128 / BITS) : 32;   // elements per window
+    constexpr int G = E < 16 ? E : 16;                         // atomics in flight per lane
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    extern __shared__ unsigned long long lds[];
+    const HistJob job = jobs[blockIdx.x];
+    const int ft = (int)job.ft;
+    const int trash = ft * Bp;
+    const int n_acc = trash + 256;
+    unsigned long long *main_ = lds;
+    uint32_t *side = (uint32_t *)(lds + n_acc);
+    for (int i = threadIdx.x; i < n_acc; i += (int)blockDim.x) {
+        main_[i] = 0;
+        side[i] = 0;
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int my_trash = trash + lane;
+    const int nwin = (ft + E - 1) / E;
+    for (uint32_t i = threadIdx.x; i < job.n_rows; i += blockDim.x) {
+        const uint64_t pos_in = (uint64_t)job.row_begin + i;
+        const uint64_t r = LIST ? (uint64_t)row_idx[pos_in] : pos_in;
+        if (r >= (uint64_t)n) continue;
+        const int2 q = gq[r];
+        const unsigned long long addv = pack_pair(q);
+        const uint32_t hq = (uint32_t)q.y;
+        const uint64_t bit0 = r * (uint64_t)stride_bits + (uint64_t)job.f0 * BITS;
+        int c = (lane * nwin) >> 6;   // lanes of a wave start at different windows
+        for (int cc = 0; cc < nwin; ++cc) {
+            const uint64_t wb = bit0 + (uint64_t)c * (E * BITS);
+            const int64_t w0 = (int64_t)(wb >> 5);
+            const uint32_t sh = (uint32_t)(wb & 31);
+            uint32_t w[5], W[4];
+#pragma unroll
+            for (int k = 0; k < 5; ++k) {
+                const int64_t wi = w0 + k;
+                w[k] = packed[wi < n_words ? wi : n_words - 1];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) W[k] = __builtin_amdgcn_alignbit(w[k + 1], w[k], sh);
+            const int tbase = c * E;
+#pragma unroll
+            for (int g0 = 0; g0 < E; g0 += G) {
+                int idx[G];
+                unsigned long long old[G];
+#pragma unroll
+                for (int jj = 0; jj < G; ++jj) {
+                    const int j = g0 + jj;
+                    if (j < E) {
+                        constexpr int dummy = 0;
+                        (void)dummy;
+                        const int pos = j * BITS, wd = pos >> 5, off = pos & 31;
+                        uint32_t sv;
+                        if (off + BITS <= 32)
+                            sv = (W[wd] >> off) & MASK;
+                        else
+                            sv = __builtin_amdgcn_alignbit(W[wd < 3 ? wd + 1 : 3], W[wd], (uint32_t)off) & MASK;
+                        const int t = tbase + j;
+                        const bool ok = (t < ft) & (sv != missing) & (sv < (uint32_t)B);
+                        idx[jj] = ok ? t * Bp + (int)sv : my_trash;
+                        old[jj] = atomicAdd(&main_[idx[jj]], addv);
+                    }
+                }
+#pragma unroll
+                for (int jj = 0; jj < G; ++jj)
+                    if (g0 + jj < E) pk_check(side, idx[jj], old[jj], addv, hq);
+            }
+            ++c;
+            if (c == nwin) c = 0;
+        }
+    }
+    __syncthreads();
+    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
+}
+
 inline int padded_bins(int B) { return B | 1; }   // odd stride: see the note on LDS banks above
 
 }  // namespace
 
 int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B) {
     const size_t per_feature = (size_t)padded_bins(B) * 12;   // 8-byte word + 4-byte side counter per bin
-    const size_t budget = ctx->lds_per_block - 256 * 12;      // the trash row
+    size_t limit = ctx->lds_per_block;
+    if (ctx->hist_lds_kb > 0 && (size_t)ctx->hist_lds_kb * 1024 < limit) limit = (size_t)ctx->hist_lds_kb * 1024;
+    if (limit < per_feature + 256 * 12) limit = ctx->lds_per_block;   // one feature must fit
+    const size_t budget = limit - 256 * 12;                    // the trash row
     int ft = (int)(budget / per_feature);
     if (ft > F) ft = F;
     return ft;   // 0: one feature's bins do not fit in LDS
@@ -316,6 +408,40 @@ hipError_t pick_slots(int max_ft, const B8Args &a) {
     if (max_ft == 13) return launch_b8<LIST, 13, CHK>(a);
     return launch_b8<LIST, 16, CHK>(a);
 }
+template <int BITS, bool LIST>
+hipError_t launch_static(const B8Args &a, int64_t stride_bits) {
+    static size_t configured = 0;
+    if (a.lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)hist_static_kernel<BITS, LIST>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+        if (e != hipSuccess) return e;
+        configured = a.lds;
+    }
+    hist_static_kernel<BITS, LIST><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, stride_bits, a.n, a.B, a.Bp,
+                                                                       a.missing, a.row_idx, a.gq, a.pool, a.jobs);
+    return hipGetLastError();
+}
+template <bool LIST>
+hipError_t pick_static(int bits, const B8Args &a, int64_t stride_bits) {
+    switch (bits) {
+        case 1: return launch_static<1, LIST>(a, stride_bits);
+        case 2: return launch_static<2, LIST>(a, stride_bits);
+        case 3: return launch_static<3, LIST>(a, stride_bits);
+        case 4: return launch_static<4, LIST>(a, stride_bits);
+        case 5: return launch_static<5, LIST>(a, stride_bits);
+        case 6: return launch_static<6, LIST>(a, stride_bits);
+        case 7: return launch_static<7, LIST>(a, stride_bits);
+        case 9: return launch_static<9, LIST>(a, stride_bits);
+        case 10: return launch_static<10, LIST>(a, stride_bits);
+        case 11: return launch_static<11, LIST>(a, stride_bits);
+        case 12: return launch_static<12, LIST>(a, stride_bits);
+        case 13: return launch_static<13, LIST>(a, stride_bits);
+        case 14: return launch_static<14, LIST>(a, stride_bits);
+        case 15: return launch_static<15, LIST>(a, stride_bits);
+        case 16: return launch_static<16, LIST>(a, stride_bits);
+        default: return hipErrorInvalidValue;
+    }
+}
 template <bool LIST>
 hipError_t launch_generic(hipStream_t s, int n_jobs, int block, size_t lds, const uint32_t *packed, int64_t n_words, int bits,
                           int64_t stride_bits, int64_t n, int B, int Bp, uint32_t missing,
@@ -347,6 +473,10 @@ hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64
         const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing, row_idx, g2, hist_pool, jobs};
         if (row_idx) return chk ? pick_slots<true, true>(max_ft, a) : pick_slots<true, false>(max_ft, a);
         return chk ? pick_slots<false, true>(max_ft, a) : pick_slots<false, false>(max_ft, a);
+    }
+    if (!ctx->hist_runtime_bits && bits != 8) {
+        const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, 0, n, B, Bp, missing, row_idx, g2, hist_pool, jobs};
+        return row_idx ? pick_static<true>(bits, a, stride_bits) : pick_static<false>(bits, a, stride_bits);
     }
     if (row_idx)
         return launch_generic<true>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);

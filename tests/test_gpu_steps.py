@@ -126,6 +126,8 @@ HIST_CASES = [
     (20_001, 28, 256, 0.0),      # 8-bit, 112 KB of LDS
     (30_007, 50, 256, 0.8),      # 9-bit with the missing symbol, two feature tiles
     (5_003, 300, 64, 0.0),       # 6-bit, several feature tiles
+    (3_001, 400, 64, 0.0),       # 6-bit, rows of 300 bytes: lanes share a row
+    (2_003, 260, 256, 0.5),      # 9-bit wide rows with the missing symbol
     (4_097, 7, 1000, 0.1),       # 10-bit
     (63, 3, 2, 0.0),             # 1-bit, less than a wave
 ]

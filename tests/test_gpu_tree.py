@@ -73,6 +73,7 @@ CASES = [  # config, rows, kwargs, csr
     (3, 60_000, {}, True),                # 9-bit with missing values, CSR input, depth 8
     (4, 200_000, {}, False),              # 8-bit, 13 features (skewed categorical columns), depth 8
     (5, 6_000, {"F": 300}, False),        # 6-bit, wide, depth 10: many small nodes, feature tiles
+    (5, 4_000, {"F": 500}, False),        # rows of 375 bytes: the row-parallel histogram kernel
 ]
 
 
