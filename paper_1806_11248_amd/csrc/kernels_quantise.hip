@@ -58,42 +58,100 @@ __global__ __launch_bounds__(256) void dense_keys_kernel(const float *__restrict
 }
 
 // ---- 1b. CSR input: count, offset, scatter by column -----------------------
-__global__ void csr_count_kernel(const int32_t *__restrict__ indices, int64_t nnz, int F,
-                                 uint32_t *__restrict__ counts) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz;
-         i += (int64_t)gridDim.x * blockDim.x) {
+// Workgroups take chunks of kCsrChunk stored values and count columns in LDS first, so that
+// HBM sees one atomic per (chunk, column) instead of one per value.  Columns beyond
+// kCsrLdsCols use the direct form.
+constexpr int kCsrChunk = 8192;
+constexpr int kCsrLdsCols = 4096;
+
+__global__ __launch_bounds__(256) void csr_count_kernel(const int32_t *__restrict__ indices, int64_t nnz, int F,
+                                                        uint32_t *__restrict__ counts) {
+    __shared__ uint32_t lc[kCsrLdsCols];
+    const bool use_lds = F <= kCsrLdsCols;
+    if (use_lds) {
+        for (int i = threadIdx.x; i < F; i += 256) lc[i] = 0;
+        __syncthreads();
+    }
+    const int64_t i0 = (int64_t)blockIdx.x * kCsrChunk;
+    const int64_t i1 = i0 + kCsrChunk < nnz ? i0 + kCsrChunk : nnz;
+    for (int64_t i = i0 + threadIdx.x; i < i1; i += 256) {
         const int f = indices[i];
-        if (f >= 0 && f < F) atomicAdd(&counts[f], 1u);
+        if (f < 0 || f >= F) continue;
+        if (use_lds) atomicAdd(&lc[f], 1u); else atomicAdd(&counts[f], 1u);
+    }
+    if (use_lds) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < F; i += 256)
+            if (lc[i]) atomicAdd(&counts[i], lc[i]);
     }
 }
 
-// seg_off[f] = exclusive prefix of counts; blk_off[f] = exclusive prefix of tiles
+__global__ __launch_bounds__(256) void csr_scatter_kernel(const int32_t *__restrict__ indices,
+                                                          const float *__restrict__ values, int64_t nnz, int F,
+                                                          const uint64_t *__restrict__ seg_off,
+                                                          uint32_t *__restrict__ cursor,
+                                                          uint32_t *__restrict__ keys) {
+    __shared__ uint32_t lc[kCsrLdsCols];     // count, then the chunk's first slot, per column
+    const bool use_lds = F <= kCsrLdsCols;
+    const int64_t i0 = (int64_t)blockIdx.x * kCsrChunk;
+    const int64_t i1 = i0 + kCsrChunk < nnz ? i0 + kCsrChunk : nnz;
+    if (!use_lds) {
+        for (int64_t i = i0 + threadIdx.x; i < i1; i += 256) {
+            const int f = indices[i];
+            if (f < 0 || f >= F) continue;
+            const uint32_t slot = atomicAdd(&cursor[f], 1u);   // order inside a segment is irrelevant before the sort
+            keys[seg_off[f] + slot] = float_key(values[i]);
+        }
+        return;
+    }
+    for (int i = threadIdx.x; i < F; i += 256) lc[i] = 0;
+    __syncthreads();
+    // rank of every value among the chunk's values of its column (kCsrChunk / 256 = 32 per thread)
+    uint32_t rank[kCsrChunk / 256];
+#pragma unroll
+    for (int k = 0; k < kCsrChunk / 256; ++k) {
+        const int64_t i = i0 + (int64_t)k * 256 + threadIdx.x;
+        rank[k] = 0;
+        if (i < i1) {
+            const int f = indices[i];
+            if (f >= 0 && f < F) rank[k] = atomicAdd(&lc[f], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < F; i += 256) {
+        const uint32_t c = lc[i];
+        lc[i] = c ? atomicAdd(&cursor[i], c) : 0u;   // the chunk's slots in column i start here
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kCsrChunk / 256; ++k) {
+        const int64_t i = i0 + (int64_t)k * 256 + threadIdx.x;
+        if (i < i1) {
+            const int f = indices[i];
+            if (f >= 0 && f < F) keys[seg_off[f] + lc[f] + rank[k]] = float_key(values[i]);
+        }
+    }
+}
+
+// chk_off[f] = exclusive prefix of the segments' scan chunks (kScanChunk tiles each)
 __global__ void offsets_kernel(const uint32_t *counts, int F, int64_t fixed_len, uint64_t *seg_off,
-                               uint32_t *blk_off) {
+                               uint32_t *blk_off, uint32_t *chk_off, int scan_chunk) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     uint64_t o = 0;
-    uint32_t b = 0;
+    uint32_t b = 0, c = 0;
     for (int f = 0; f < F; ++f) {
         seg_off[f] = o;
         blk_off[f] = b;
+        chk_off[f] = c;
         const uint64_t len = counts ? (uint64_t)counts[f] : (uint64_t)fixed_len;
+        const uint32_t tiles = (uint32_t)((len + kSortTile - 1) / kSortTile);
         o += len;
-        b += (uint32_t)((len + kSortTile - 1) / kSortTile);
+        b += tiles;
+        c += (tiles + (uint32_t)scan_chunk - 1) / (uint32_t)scan_chunk;
     }
     seg_off[F] = o;
     blk_off[F] = b;
-}
-
-__global__ void csr_scatter_kernel(const int32_t *__restrict__ indices, const float *__restrict__ values,
-                                   int64_t nnz, int F, const uint64_t *__restrict__ seg_off,
-                                   uint32_t *__restrict__ cursor, uint32_t *__restrict__ keys) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const int f = indices[i];
-        if (f < 0 || f >= F) continue;
-        const uint32_t slot = atomicAdd(&cursor[f], 1u);   // order inside a segment is irrelevant before the sort
-        keys[seg_off[f] + slot] = float_key(values[i]);
-    }
+    chk_off[F] = c;
 }
 
 // ---- 2. segmented radix sort ----------------------------------------------
@@ -125,30 +183,37 @@ __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const uint32_t *_
     tile_hist[(uint64_t)blk * 256 + threadIdx.x] = h[threadIdx.x];
 }
 
-// One workgroup per segment, thread d owns digit d: tile_hist[blk][d] becomes the
-// position (inside the segment) of the first key of tile blk with digit d.
-__global__ __launch_bounds__(256) void sort_scan_kernel(const uint32_t *__restrict__ blk_off,
-                                                        uint32_t *__restrict__ tile_hist) {
-    const int f = blockIdx.x, d = threadIdx.x;
-    const uint32_t b0 = blk_off[f], b1 = blk_off[f + 1];
+// tile_hist[blk][d] becomes the position (inside the segment) of the first key of tile blk
+// with digit d.  Three launches, thread d owns digit d everywhere:
+//   partial : one workgroup per chunk of kScanChunk tiles adds up the chunk's counts;
+//   chunks  : one workgroup per segment turns the chunk totals into chunk start positions
+//             (exclusive over chunks, then offset by the exclusive scan over the digits);
+//   apply   : one workgroup per chunk walks its tiles from the chunk's start position.
+constexpr int kScanChunk = 128;
+
+__global__ __launch_bounds__(256) void scan_partial_kernel(const uint32_t *__restrict__ blk_off,
+                                                           const uint32_t *__restrict__ chk_off, int F,
+                                                           const uint32_t *__restrict__ tile_hist,
+                                                           uint32_t *__restrict__ chunk_tot) {
+    const uint32_t chunk = blockIdx.x;
+    const int f = find_segment(chk_off, F, chunk), d = threadIdx.x;
+    const uint32_t b0 = blk_off[f] + (chunk - chk_off[f]) * kScanChunk;
+    const uint32_t b1 = b0 + kScanChunk < blk_off[f + 1] ? b0 + kScanChunk : blk_off[f + 1];
     uint32_t run = 0;
-    uint32_t b = b0;
-    for (; b + 8 <= b1; b += 8) {   // eight independent loads in flight per step
-        uint32_t c[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) c[u] = tile_hist[(uint64_t)(b + u) * 256 + d];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            tile_hist[(uint64_t)(b + u) * 256 + d] = run;
-            run += c[u];
-        }
+    for (uint32_t b = b0; b < b1; ++b) run += tile_hist[(uint64_t)b * 256 + d];
+    chunk_tot[(uint64_t)chunk * 256 + d] = run;
+}
+
+__global__ __launch_bounds__(256) void scan_chunks_kernel(const uint32_t *__restrict__ chk_off,
+                                                          uint32_t *__restrict__ chunk_tot) {
+    const int f = blockIdx.x, d = threadIdx.x;
+    const uint32_t c0 = chk_off[f], c1 = chk_off[f + 1];
+    uint32_t run = 0;
+    for (uint32_t c = c0; c < c1; ++c) {
+        const uint32_t v = chunk_tot[(uint64_t)c * 256 + d];
+        chunk_tot[(uint64_t)c * 256 + d] = run;
+        run += v;
     }
-    for (; b < b1; ++b) {
-        const uint32_t c = tile_hist[(uint64_t)b * 256 + d];
-        tile_hist[(uint64_t)b * 256 + d] = run;
-        run += c;
-    }
-    // exclusive scan of the digit totals over the 256 threads
     __shared__ uint32_t tot[256];
     tot[d] = run;
     __syncthreads();
@@ -158,8 +223,24 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(const uint32_t *__restri
         tot[d] += v;
         __syncthreads();
     }
-    const uint32_t base = tot[d] - run;
-    for (b = b0; b < b1; ++b) tile_hist[(uint64_t)b * 256 + d] += base;
+    const uint32_t base = tot[d] - run;   // keys of this segment with a smaller digit
+    for (uint32_t c = c0; c < c1; ++c) chunk_tot[(uint64_t)c * 256 + d] += base;
+}
+
+__global__ __launch_bounds__(256) void scan_apply_kernel(const uint32_t *__restrict__ blk_off,
+                                                         const uint32_t *__restrict__ chk_off, int F,
+                                                         uint32_t *__restrict__ tile_hist,
+                                                         const uint32_t *__restrict__ chunk_tot) {
+    const uint32_t chunk = blockIdx.x;
+    const int f = find_segment(chk_off, F, chunk), d = threadIdx.x;
+    const uint32_t b0 = blk_off[f] + (chunk - chk_off[f]) * kScanChunk;
+    const uint32_t b1 = b0 + kScanChunk < blk_off[f + 1] ? b0 + kScanChunk : blk_off[f + 1];
+    uint32_t run = chunk_tot[(uint64_t)chunk * 256 + d];
+    for (uint32_t b = b0; b < b1; ++b) {
+        const uint32_t c = tile_hist[(uint64_t)b * 256 + d];
+        tile_hist[(uint64_t)b * 256 + d] = run;
+        run += c;
+    }
 }
 
 __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const uint32_t *__restrict__ src,
@@ -343,8 +424,8 @@ __global__ void bin_csr_kernel(const int64_t *__restrict__ indptr, const int32_t
 }
 
 struct QLayout {
-    size_t keys_a, keys_b, tile_hist, seg_off, blk_off, counts, cursor, misc, total;
-    int64_t max_tiles;
+    size_t keys_a, keys_b, tile_hist, chunk_tot, seg_off, blk_off, chk_off, counts, cursor, misc, total;
+    int64_t max_tiles, max_chunks;
 };
 QLayout q_layout(int64_t n, int F, int64_t n_values) {
     (void)n;
@@ -354,8 +435,11 @@ QLayout q_layout(int64_t n, int F, int64_t n_values) {
     L.keys_a = o;    o += gbt_align((size_t)n_values * 4 + 4);
     L.keys_b = o;    o += gbt_align((size_t)n_values * 4 + 4);
     L.tile_hist = o; o += gbt_align((size_t)L.max_tiles * 256 * 4);
+    L.max_chunks = L.max_tiles / 128 + F + 1;
+    L.chunk_tot = o; o += gbt_align((size_t)L.max_chunks * 256 * 4);
     L.seg_off = o;   o += gbt_align((size_t)(F + 1) * 8);
     L.blk_off = o;   o += gbt_align((size_t)(F + 1) * 4);
+    L.chk_off = o;   o += gbt_align((size_t)(F + 1) * 4);
     L.counts = o;    o += gbt_align((size_t)F * 4);
     L.cursor = o;    o += gbt_align((size_t)F * 4);
     L.misc = o;      o += 256;
@@ -395,13 +479,15 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     uint32_t *tile_hist = (uint32_t *)(ws + L.tile_hist);
     uint64_t *seg_off = (uint64_t *)(ws + L.seg_off);
     uint32_t *blk_off = (uint32_t *)(ws + L.blk_off);
+    uint32_t *chk_off = (uint32_t *)(ws + L.chk_off);
+    uint32_t *chunk_tot = (uint32_t *)(ws + L.chunk_tot);
     uint32_t *counts = (uint32_t *)(ws + L.counts), *cursor = (uint32_t *)(ws + L.cursor);
     uint32_t *misc = (uint32_t *)(ws + L.misc);
     const bool dense = X != nullptr;
 
     // 1. key segments
     if (dense) {
-        offsets_kernel<<<1, 1, 0, s>>>(nullptr, F, n, seg_off, blk_off);
+        offsets_kernel<<<1, 1, 0, s>>>(nullptr, F, n, seg_off, blk_off, chk_off, kScanChunk);
         if (n > 0) {
             dim3 grid((unsigned)((n + kTrRows - 1) / kTrRows), (unsigned)((F + kTrCols - 1) / kTrCols));
             dense_keys_kernel<<<grid, 256, 0, s>>>(X, n, F, keys_a);
@@ -409,19 +495,21 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     } else {
         Q_HIP(gbt_launch_fill_u64(s, (uint64_t *)counts, 0, (int64_t)(gbt_align((size_t)F * 4) / 8)));
         Q_HIP(gbt_launch_fill_u64(s, (uint64_t *)cursor, 0, (int64_t)(gbt_align((size_t)F * 4) / 8)));
-        if (n_values > 0) csr_count_kernel<<<grid_for(n_values, 1024, 4096), 256, 0, s>>>(indices, n_values, F, counts);
-        offsets_kernel<<<1, 1, 0, s>>>(counts, F, 0, seg_off, blk_off);
+        const int csr_grid = (int)((n_values + kCsrChunk - 1) / kCsrChunk);
+        if (n_values > 0) csr_count_kernel<<<csr_grid, 256, 0, s>>>(indices, n_values, F, counts);
+        offsets_kernel<<<1, 1, 0, s>>>(counts, F, 0, seg_off, blk_off, chk_off, kScanChunk);
         if (n_values > 0)
-            csr_scatter_kernel<<<grid_for(n_values, 1024, 4096), 256, 0, s>>>(indices, values, n_values, F, seg_off,
-                                                                              cursor, keys_a);
+            csr_scatter_kernel<<<csr_grid, 256, 0, s>>>(indices, values, n_values, F, seg_off, cursor, keys_a);
     }
     Q_HIP(hipGetLastError());
     // number of sort tiles
     Q_HIP(hipMemcpyAsync(ctx->pinned + GBT_STAGING_BYTES / 2, blk_off + F, 4, hipMemcpyDeviceToHost, s));
+    Q_HIP(hipMemcpyAsync(ctx->pinned + GBT_STAGING_BYTES / 2 + 4, chk_off + F, 4, hipMemcpyDeviceToHost, s));
     Q_HIP(hipStreamSynchronize(s));
-    uint32_t n_tiles;
+    uint32_t n_tiles, n_chunks;
     memcpy(&n_tiles, ctx->pinned + GBT_STAGING_BYTES / 2, 4);
-    if ((int64_t)n_tiles > L.max_tiles) {
+    memcpy(&n_chunks, ctx->pinned + GBT_STAGING_BYTES / 2 + 4, 4);
+    if ((int64_t)n_tiles > L.max_tiles || (int64_t)n_chunks > L.max_chunks) {
         *status = gbt_fail(ctx, GBT_EINVAL, "gbt_quantise: inconsistent input (tile count)");
         return hipSuccess;
     }
@@ -431,7 +519,9 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     for (int pass = 0; pass < 4 && n_tiles > 0; ++pass) {
         const int shift = pass * 8;
         sort_hist_kernel<<<n_tiles, kSortBlock, 0, s>>>(src, seg_off, blk_off, F, shift, tile_hist);
-        sort_scan_kernel<<<F, 256, 0, s>>>(blk_off, tile_hist);
+        scan_partial_kernel<<<n_chunks, 256, 0, s>>>(blk_off, chk_off, F, tile_hist, chunk_tot);
+        scan_chunks_kernel<<<F, 256, 0, s>>>(chk_off, chunk_tot);
+        scan_apply_kernel<<<n_chunks, 256, 0, s>>>(blk_off, chk_off, F, tile_hist, chunk_tot);
         sort_scatter_kernel<<<n_tiles, kSortBlock, 0, s>>>(src, dst, seg_off, blk_off, F, shift, tile_hist);
         uint32_t *t = src;
         src = dst;
