@@ -1,0 +1,125 @@
+"""Edge cases and randomised small cases of the GPU path against the oracle (-m gpu)."""
+import numpy as np
+import pytest
+import torch
+from hypothesis import HealthCheck, given, settings, strategies as st
+
+from gpu_util import dev, host_u32, oracle_prep, tree_kw
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_1806_11248_amd as g
+    c = g.Context(0)
+    yield c
+    c.close()
+
+
+def _grow_and_judge(ctx, oracle, X, gp, p):
+    import paper_1806_11248_amd as g
+    n, F = X.shape
+    B = p["max_bins"]
+    o = oracle_prep(oracle, X, B)
+    cuts, nb, sym, mv, ms = ctx.quantise(dev(X), max_bins=B)
+    assert np.array_equal(sym.cpu().numpy(), o["sym"]) and (mv, ms) == (o["max_value"], o["missing"])
+    assert np.array_equal(cuts.cpu().numpy(), o["cuts"]) and np.array_equal(nb.cpu().numpy(), o["nb"])
+    packed, bits = ctx.compress(sym, mv)
+    assert np.array_equal(host_u32(packed), o["words"])
+    params = g.make_params(max_depth=p["max_depth"], max_bins=B, lam=p["lam"], gamma=p["gamma"],
+                           min_child_weight=p["min_child_weight"])
+    gp_t = dev(gp)
+    tree, row_idx, leaf = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_t, params)
+    _, scale = ctx.gpair_fixed(gp_t)
+    rep = oracle.replay_tree(tree, o["sym"], o["nb"], o["missing"], gp, **tree_kw(p),
+                             sum_atol_per_row=0.5 / min(scale))
+    assert rep["ok"], rep["errors"][:5]
+    assert np.array_equal(host_u32(row_idx), rep["row_idx"])
+    assert np.array_equal(leaf.cpu().numpy(), rep["leaf_of_row"])
+    return tree, o, dict(packed=packed, bits=bits, missing=ms)
+
+
+P0 = dict(max_depth=3, max_bins=16, lam=1.0, gamma=0.0, min_child_weight=1.0)
+
+
+def test_single_row_and_single_feature(ctx, oracle):
+    print("n=1", flush=True)
+    tree, _, _ = _grow_and_judge(ctx, oracle, np.array([[0.5]], np.float32), np.array([[1.0, 1.0]], np.float32), P0)
+    assert tree["n_nodes"] == 1
+    print("n=65, F=1", flush=True)
+    rng = np.random.default_rng(0)
+    X = rng.random((65, 1)).astype(np.float32)
+    gp = np.stack([np.where(X[:, 0] > 0.5, 1.0, -1.0), np.ones(65)], 1).astype(np.float32)
+    tree, _, _ = _grow_and_judge(ctx, oracle, X, gp, P0)
+    assert tree["n_nodes"] >= 3
+
+
+def test_identical_rows_and_constant_features(ctx, oracle):
+    print("identical rows", flush=True)
+    X = np.tile(np.array([[1.0, 2.0, 3.0]], np.float32), (1000, 1))
+    rng = np.random.default_rng(1)
+    gp = np.stack([rng.standard_normal(1000), np.ones(1000)], 1).astype(np.float32)
+    tree, _, _ = _grow_and_judge(ctx, oracle, X, gp, P0)
+    assert tree["n_nodes"] == 1                       # one bin per feature: nothing to split on
+    print("all missing but one column", flush=True)
+    X = np.full((3000, 4), np.nan, np.float32)
+    X[:, 2] = rng.random(3000)
+    gp = np.stack([np.where(X[:, 2] > 0.3, 1.0, -1.0), np.ones(3000)], 1).astype(np.float32)
+    tree, _, _ = _grow_and_judge(ctx, oracle, X, gp, P0)
+    assert tree["feature"][0] == 2
+
+
+def test_two_bins_and_many_bins(ctx, oracle):
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((5000, 5)).astype(np.float32)
+    gp = np.stack([rng.standard_normal(5000) + (X[:, 1] > 0), rng.random(5000) + 0.5], 1).astype(np.float32)
+    for B in (2, 3, 1000, 4096):
+        print(f"max_bins={B}", flush=True)
+        p = dict(P0, max_bins=B, max_depth=4)
+        _grow_and_judge(ctx, oracle, X, gp, p)
+
+
+def test_predict_several_trees_in_order(ctx, oracle):
+    rng = np.random.default_rng(3)
+    n, F = 20_000, 6
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    X[rng.random((n, F)) < 0.2] = np.nan
+    y = (rng.random(n) < 0.5).astype(np.float32)
+    p = dict(P0, max_bins=32, max_depth=4)
+    margin = np.zeros(n, np.float32)
+    trees = []
+    for r in range(3):
+        gp = oracle.gradients("logistic", margin, y)
+        tree, o, gdev = _grow_and_judge(ctx, oracle, X, gp, p)
+        trees.append(tree)
+        margin = oracle.predict_sym(tree, o["sym"], o["missing"], 0.3, margin)
+    print("predict 3 trees", flush=True)
+    got = ctx.predict(trees, dev(np.zeros(n, np.float32)), 0.3, packed=gdev["packed"], bits=gdev["bits"],
+                      missing_sym=gdev["missing"], n=n, F=F).cpu().numpy()
+    got_raw = ctx.predict(trees, dev(np.zeros(n, np.float32)), 0.3, X=dev(X)).cpu().numpy()
+    assert np.array_equal(got, margin) and np.array_equal(got_raw, margin)
+
+
+@settings(max_examples=30, deadline=None, suppress_health_check=list(HealthCheck), derandomize=True)
+@given(seed=st.integers(0, 2 ** 31 - 1), n=st.integers(1, 3000), F=st.integers(1, 20),
+       B=st.sampled_from([2, 5, 16, 33, 64, 256]), miss=st.sampled_from([0.0, 0.0, 0.3, 0.9]),
+       depth=st.integers(0, 5), lam=st.sampled_from([0.0, 1.0, 10.0]), gamma=st.sampled_from([0.0, 0.5]),
+       mcw=st.sampled_from([0.0, 1.0, 20.0]), ties=st.booleans())
+def test_random_small_trees(ctx, oracle, seed, n, F, B, miss, depth, lam, gamma, mcw, ties):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    if ties:
+        X = np.round(X * 2) / 2                         # few distinct values, duplicated features
+        if F > 1:
+            X[:, F - 1] = X[:, 0]
+    if miss:
+        X[rng.random((n, F)) < miss] = np.nan
+    g = rng.standard_normal(n) * rng.choice([1e-3, 1.0, 50.0])
+    h = rng.random(n) * rng.choice([1e-2, 1.0]) + 1e-3
+    if ties:
+        g, h = np.sign(g) * 0.5, np.full(n, 0.25)        # exactly representable: exact gain ties
+    gp = np.stack([g, h], 1).astype(np.float32)
+    print(f"random tree seed={seed} n={n} F={F} B={B} miss={miss} depth={depth} lam={lam} gamma={gamma} mcw={mcw} ties={ties}",
+          flush=True)
+    _grow_and_judge(ctx, oracle, X, gp, dict(max_depth=depth, max_bins=B, lam=lam, gamma=gamma, min_child_weight=mcw))
