@@ -859,6 +859,7 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
         bits = 1;
     }
     GBT_REQUIRE(ctx, workspace_bytes >= gbt_predict_workspace_bytes(trees, n_trees), GBT_ENOMEM, "workspace too small");
+    bool compact_ok = true;   // the 8-byte node form of the register-window kernel applies
     // stage the trees: table of offsets, then each tree's arrays
     std::vector<char> host(gbt_predict_workspace_bytes(trees, n_trees), 0);
     DevTree *tab = (DevTree *)host.data();
@@ -868,6 +869,8 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
         GBT_REQUIRE(ctx, T.n_nodes >= 1 && T.n_nodes <= T.capacity, GBT_EINVAL, "tree %d: bad n_nodes", t);
         for (int i = 0; i < T.n_nodes; ++i) {
             if (T.feature[i] < 0) continue;
+            if (T.right[i] != T.left[i] + 1 || T.feature[i] >= (1 << 20) || T.bin[i] < 0 || T.bin[i] >= 4096)
+                compact_ok = false;
             GBT_REQUIRE(ctx, T.feature[i] < F && T.left[i] >= 0 && T.left[i] < T.n_nodes && T.right[i] >= 0 &&
                                  T.right[i] < T.n_nodes,
                         GBT_EINVAL, "tree %d node %d: bad feature or child id", t, i);
@@ -891,7 +894,7 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
     int max_nodes = 1;
     for (int t = 0; t < n_trees; ++t) max_nodes = std::max(max_nodes, trees[t].n_nodes);
     GBT_HIP(ctx, gbt_launch_predict(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees, packed,
-                                    bits, (uint32_t)missing_sym, X, n, F, eta, margin, max_nodes));
+                                    bits, (uint32_t)missing_sym, X, n, F, eta, margin, max_nodes, compact_ok));
     GBT_SYNC(ctx);
     return GBT_OK;
 }

@@ -173,7 +173,8 @@ struct DevTree {   // one tree's arrays inside the predict workspace (offsets in
 };
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
-                              int64_t n, int F, double eta, float *margin, int max_nodes);
+                              int64_t n, int F, double eta, float *margin, int max_nodes, bool compact_ok);
+// compact_ok: every split node has right == left + 1, feature < 2^20 and bin < 4096
 
 // quantise
 hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
