@@ -161,7 +161,6 @@ def main():
     margin = torch.zeros(n, dtype=torch.float32, device=dev)
     gp = (torch.from_numpy(np.stack([d["g"], d["h"]], 1)).to(dev) if given
           else torch.empty((n, 2), dtype=torch.float32, device=dev))
-    row_idx = torch.empty(n, dtype=torch.int32, device=dev)
     params = g.make_params(max_depth=p["max_depth"], max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
                            min_child_weight=p["min_child_weight"], eta=p["eta"], objective=p["objective"])
     single_tree = p["rounds"] == 1   # such a workload is ONE tree from margin 0: every step repeats exactly that
@@ -173,7 +172,7 @@ def main():
             margin.zero_()
         if not given:
             ctx.gradients(p["objective"], margin, y, out=gp)
-        tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_leaf=False, row_idx_out=row_idx)
+        tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=False)
         ctx.predict([tree], margin, eta, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
         trees.append(tree)
 

@@ -248,7 +248,10 @@ GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits,
  *   gpair [dev] float2[n]
  *   tree_out [host]              caller-allocated arrays, see gbt_tree
  *   row_idx_out [dev] uint32[n]  final row order: each node's rows are one
- *                                ascending run, left child's run first
+ *                                ascending run, left child's run first.  May be
+ *                                NULL: then row ids are not carried through the
+ *                                partitions (less memory traffic) and only the
+ *                                tree is produced; leaf_of_row_out must be NULL too
  *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL)
  * Synchronises the stream.
  */

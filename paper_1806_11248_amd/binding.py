@@ -315,11 +315,15 @@ class Context:
 
     # -- Alg. 1 --------------------------------------------------------------
     def grow_tree(self, packed, bits, n, F, missing_sym, nb, cuts, gpair, params: Params, want_leaf=True,
-                  row_idx_out=None, leaf_out=None):
-        """Returns (tree dict of numpy arrays, row_idx int32 tensor [n], leaf_of_row int32 tensor [n])."""
+                  row_idx_out=None, leaf_out=None, want_rows=True):
+        """Returns (tree dict of numpy arrays, row_idx int32 tensor [n], leaf_of_row int32 tensor [n]).
+        want_rows=False: only the tree is produced (row_idx and leaf_of_row are None)."""
         t = new_tree(params.max_depth)
         ts = _tree_struct(t)
-        row_idx = row_idx_out if row_idx_out is not None else self.empty((n,), torch.int32)
+        if not want_rows:
+            want_leaf, row_idx = False, None
+        else:
+            row_idx = row_idx_out if row_idx_out is not None else self.empty((n,), torch.int32)
         leaf = (leaf_out if leaf_out is not None else self.empty((n,), torch.int32)) if want_leaf else None
         ws_bytes = self.lib.gbt_grow_tree_workspace_bytes(n, F, bits, params.max_bins, params.max_depth)
         if ws_bytes == 0:

@@ -170,6 +170,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->hist_lds_kb = 64;   // two resident workgroups per CU hide the row-fetch latency better than one big tile
         if (const char *e1 = getenv("GBT_TUNE_HIST_BLOCK")) { int v = atoi(e1); if (v == 256 || v == 512 || v == 1024) c->hist_block = v; }
         if (const char *e3 = getenv("GBT_TUNE_HIST_RUNTIME_BITS")) c->hist_runtime_bits = atoi(e3) != 0;
+        c->part_fused = 1;
+        if (const char *e6 = getenv("GBT_TUNE_PART_FUSED")) c->part_fused = atoi(e6) != 0;
         if (const char *e5 = getenv("GBT_TUNE_HIST_LDS_KB")) { int v = atoi(e5); if (v >= 8 && v <= 128) c->hist_lds_kb = v; }
         if (const char *e2 = getenv("GBT_TUNE_HIST_JOBS")) { int v = atoi(e2); if (v >= 1 && v <= 64) c->hist_jobs_per_cu = v; }
         size_t lds = prop.sharedMemPerBlock;
@@ -519,7 +521,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
 namespace {
 
 struct GrowLayout {
-    size_t gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, pool, eval_nodes, splits, jobs, scratch, total;
+    size_t gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, splits, jobs, scratch, total;
     int64_t hist_nodes, level_nodes, tiles, w_words;
     int sw;   // 32-bit words per row of the working copies
 };
@@ -541,6 +543,7 @@ GrowLayout grow_layout(int64_t n, int F, int bits, int B, int max_depth) {
     L.masks = o;      o += gbt_align((size_t)L.tiles * (GBT_PART_TILE / 64) * 8);
     L.tile_left = o;  o += gbt_align((size_t)L.tiles * 4);
     L.n_left = o;     o += gbt_align((size_t)L.level_nodes * 4);
+    L.state = o;      o += gbt_align((size_t)L.level_nodes * 8);
     L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
     L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * sizeof(EvalNode));
     L.splits = o;     o += gbt_align(GBT_STAGING_BYTES / 2);   // per-(node, feature chunk) records of one level
@@ -572,7 +575,9 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     if (!ctx) return GBT_EINVAL;
     int32_t st = check_matrix(ctx, packed, bits, n, F);
     if (st != GBT_OK) return st;
-    GBT_REQUIRE(ctx, nb && cuts && gpair && params && tree && row_idx_out && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, nb && cuts && gpair && params && tree && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, row_idx_out || !leaf_of_row_out, GBT_EINVAL, "leaf_of_row_out needs row_idx_out");
+    const bool tracked = row_idx_out != nullptr;   // else row ids are not carried along
     const int B = params->max_bins, max_depth = params->max_depth;
     st = check_bins(ctx, F, B);
     if (st != GBT_OK) return st;
@@ -695,7 +700,14 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         for (size_t i = 0; i < level.size(); ++i)
             splits[i] = merge_chunks((const gbt_split *)rb(ctx) + i * chunks, chunks);
 
-        // ---- which nodes split; RepartitionInstances for those
+        // ---- which nodes split; RepartitionInstances for those.
+        // Children that are split again get their whole records moved: by the one-launch form
+        // when nobody needs the row order and the rows are narrow enough, else by the three-launch
+        // form.  Leaves only need their ids moved, or just the row counts when ids are not tracked.
+        const int wnext = wcur == 0 ? 1 : 0;
+        const bool children_need_hist = depth + 1 < max_depth;
+        const bool fused = children_need_hist && !tracked && ctx->part_fused && gbt_partition_fused_ok(W[wnext]);
+        const uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile() : (uint32_t)GBT_PART_TILE;
         pjobs.clear();
         split_of.clear();
         uint32_t tile_cursor = 0;
@@ -716,7 +728,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             j.bin = (uint32_t)sp.bin;
             j.default_left = (uint32_t)sp.default_left;
             j.tile_begin = tile_cursor;
-            j.n_tiles = (nd.len + GBT_PART_TILE - 1) / GBT_PART_TILE;
+            j.n_tiles = (nd.len + part_tile - 1) / part_tile;
             j.pad = 0;
             tile_cursor += j.n_tiles;
             part_rows += nd.len;
@@ -731,20 +743,33 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         GBT_REQUIRE(ctx, (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
         if (st != GBT_OK) return st;
-        const int wnext = wcur == 0 ? 1 : 0;
-        const bool children_need_hist = depth + 1 < max_depth;   // else they are leaves: only their ids matter
+        const int what = children_need_hist ? GBT_PART_RECORDS : tracked ? GBT_PART_IDS : GBT_PART_COUNT;
+        const double rec_bytes = row_bits / 8.0 + 8.0;
         gbt_prof_begin(ctx, GBT_PROF_PARTITION,
-                       part_rows * (children_need_hist ? 2.0 * (row_bits / 8.0 + 12.0) : bits / 8.0 + 8.0));
-        GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym,
-                                                  !children_need_hist, (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
-                                                  (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
-                                                  (uint32_t *)(ws + L.n_left)));
+                       part_rows * (fused ? 2.0 * rec_bytes
+                                    : what == GBT_PART_RECORDS ? row_bits / 8.0 + 2.0 * (rec_bytes + 4.0)
+                                    : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
+                                                               : row_bits / 8.0));
+        if (fused) {
+            GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,
+                                                    (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
+                                                    (int)tile_cursor, (unsigned long long *)(ws + L.state)));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+        } else {
+            GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym, what,
+                                                      (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
+                                                      (int)tile_cursor, (uint64_t *)(ws + L.masks),
+                                                      (uint32_t *)(ws + L.tile_left), (uint32_t *)(ws + L.n_left)));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
+        }
         gbt_prof_end(ctx);
-        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
         GBT_SYNC(ctx);
+        const int nl_stride = fused ? 2 : 1;   // the one-launch form returns 64-bit cursors, n_left in the low half
+        if (what != GBT_PART_COUNT) {
+            wcur = wnext;
+            cur = W[wcur];
+        }
         const uint32_t *n_left = (const uint32_t *)rb(ctx);
-        wcur = wnext;
-        cur = W[wcur];
 
         // ---- children, in creation order
         hjobs.clear();
@@ -756,7 +781,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         for (size_t k = 0; k < pjobs.size(); ++k) {
             const HNode &nd = level[split_of[k]];
             const gbt_split &sp = splits[split_of[k]];
-            const uint32_t nl = n_left[k];
+            const uint32_t nl = n_left[k * nl_stride];
             GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
             HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq};
             HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq};
@@ -817,6 +842,11 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     }
     // nodes still open when the depth limit (or an empty level) ended the loop are leaves
     for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)wcur, nd.len});
+    if (!tracked) {
+        GBT_SYNC(ctx);
+        tree->n_nodes = n_nodes;
+        return GBT_OK;
+    }
 
     std::sort(leaves.begin(), leaves.end(),
               [](const LeafSeg &a, const LeafSeg &b) {   // an empty segment sorts before the one that starts at the same place

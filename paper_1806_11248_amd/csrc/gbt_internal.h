@@ -25,6 +25,7 @@ struct gbt_ctx {
     size_t pinned_bytes;
     int hist_block;         // threads per histogram workgroup
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
+    int part_fused;         // 1: one-launch record partition where it applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
     size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
@@ -155,9 +156,21 @@ struct GbtRows {
 // Stable partition of the jobs' segments of `src` into `dst` (records move, see kernels_partition.hip).
 // ids_only: move the row ids alone (the segments' children will not be read again).
 hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
-                                        int64_t n, uint32_t missing, bool ids_only, const PartJob *jobs,
+                                        int64_t n, uint32_t missing, int what, const PartJob *jobs,
                                         int n_jobs, int total_tiles, uint64_t *masks, uint32_t *tile_left,
                                         uint32_t *n_left_out);
+// `what` above: move whole records, move only the ids, or only count the left rows of every job
+enum { GBT_PART_RECORDS = 0, GBT_PART_IDS = 1, GBT_PART_COUNT = 2 };
+// The same move of whole records in one launch for a caller that does not need the row order
+// (and no ids): rows narrow enough (gbt_partition_fused_ok), tiles of gbt_partition_fused_tile()
+// rows (PartJob.tile_begin / n_tiles count those).  cursor: one word per job, cleared by the
+// launcher; after the launch its low half is the job's n_left.  Inside a child the rows of one
+// tile keep their order, the tiles' order is arbitrary.
+bool gbt_partition_fused_ok(const GbtRows &dst);
+int gbt_partition_fused_tile();
+hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
+                                      uint32_t missing, const PartJob *jobs, int n_jobs, int total_tiles,
+                                      unsigned long long *cursor);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,

@@ -299,6 +299,165 @@ __global__ __launch_bounds__(kBlock) void part_move_ids_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// One-launch partition of whole records for a caller that does not need the row
+// order kept (the grow loop when row ids are not tracked: histograms are exact
+// integer sums, so the order of a node's rows does not change any result).
+//
+// A tile decides its rows' sides from the rows it has just loaded, then reserves
+// room for both halves with ONE 64-bit atomic add on its segment's cursor (low
+// word: left rows handed out so far, high word: right rows).  Left rows fill the
+// segment from its start, right rows from its end backwards; inside a tile both
+// halves keep their order, tiles land in the order their atomics arrive.  Compared
+// with the three-launch form the matrix is read once instead of twice, no ballots
+// go through HBM and no workgroup waits for another.  The cursor's low word ends
+// as the segment's n_left.
+// ---------------------------------------------------------------------------
+constexpr int kFBlock = 512;
+constexpr int kFTile = kFBlock * kRowsPerThread;   // 4096 rows
+constexpr int kFWords = kFTile / 64;               // 64 ballot words: one per lane of a wave
+static_assert(kFWords == 64, "the ballot words are ranked by one wave");
+
+__device__ inline uint32_t pick_word(const uint4 &v, int k) { return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w; }
+
+// REG: rows are four words in the destination and at most 128 bits in the source; a thread keeps its
+// eight rows in registers between the load and the store.  Otherwise rows are re-read for the copy
+// (by the workgroup that has just read them for the flags) by sub-wave lane groups.
+template <bool REG>
+__global__ __launch_bounds__(kFBlock) void part_fused_kernel(
+    const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words,
+    uint32_t *__restrict__ dst_sym, int SW, int row_bits, int bits, uint32_t missing,
+    const int2 *__restrict__ src_gq, int2 *__restrict__ dst_gq, const PartJob *__restrict__ jobs, int n_jobs,
+    unsigned long long *__restrict__ cursor) {
+    __shared__ uint32_t left_base_s, right_base_s;
+    __shared__ uint64_t words[kFWords];
+    __shared__ uint32_t lefts_before[kFWords];
+    __shared__ uint32_t dstpos[REG ? 1 : kFTile];
+    const uint32_t tile = blockIdx.x;
+    const int ji = find_job(jobs, n_jobs, tile);
+    const PartJob job = jobs[ji];
+    const uint32_t base = (tile - job.tile_begin) * kFTile;
+    const uint32_t tile_rows = job.seg_len - base < (uint32_t)kFTile ? job.seg_len - base : (uint32_t)kFTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t p0 = (uint64_t)job.seg_begin + base;
+    const uint32_t sym_mask = (1u << bits) - 1u;
+    const uint32_t tail_bits = (uint32_t)(row_bits - 32 * (SW - 1));   // valid bits of a row's last word, 1..32
+    const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
+    const uint32_t fbit = job.feature * (uint32_t)bits;   // the split feature's first bit inside a row
+
+    // ---- load, decide
+    uint4 row[REG ? kRowsPerThread : 1];
+    int2 pair[REG ? kRowsPerThread : 1];
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        const int w = j * (kFBlock / 64) + wave;
+        const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+        bool left = false;
+        if (in_tile < tile_rows) {
+            const uint64_t p = p0 + in_tile;
+            uint32_t sy;
+            if (REG) {
+                uint4 v;
+                if (src_stride_bits == 128) {
+                    v = ((const uint4 *)src_sym)[p];
+                } else {
+                    const uint64_t sb = p * (uint64_t)src_stride_bits;
+                    const int64_t s0 = (int64_t)(sb >> 5);
+                    const uint32_t sh = (uint32_t)(sb & 31);
+                    uint32_t x[5];
+#pragma unroll
+                    for (int k = 0; k < 5; ++k) x[k] = src_sym[s0 + k < src_words ? s0 + k : src_words - 1];
+                    v.x = __builtin_amdgcn_alignbit(x[1], x[0], sh);
+                    v.y = __builtin_amdgcn_alignbit(x[2], x[1], sh);
+                    v.z = __builtin_amdgcn_alignbit(x[3], x[2], sh);
+                    v.w = __builtin_amdgcn_alignbit(x[4], x[3], sh) & tail_mask;
+                }
+                row[j] = v;
+                pair[j] = src_gq[p];
+                const int k = (int)(fbit >> 5);
+                const uint32_t lo = pick_word(v, k), hi = k < 3 ? pick_word(v, k + 1) : 0u;
+                sy = __builtin_amdgcn_alignbit(hi, lo, fbit & 31u) & sym_mask;
+            } else {
+                sy = load_symbol(src_sym, p * (uint64_t)src_stride_bits + fbit, bits, sym_mask);
+            }
+            left = (sy == missing) ? (job.default_left != 0) : (sy <= job.bin);
+        }
+        const uint64_t ballot = __ballot(left);
+        if (lane == 0) words[w] = ballot;
+    }
+    __syncthreads();
+
+    // ---- wave 0 ranks the ballot words (one per lane) and reserves the tile's room
+    if (wave == 0) {
+        const uint32_t c = (uint32_t)__popcll(words[lane]);
+        uint32_t x = c;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t y = (uint32_t)__shfl_up((int)x, d);
+            if (lane >= d) x += y;
+        }
+        lefts_before[lane] = x - c;
+        if (lane == 63) {
+            const uint32_t cnt = x;
+            const unsigned long long old =
+                atomicAdd(&cursor[ji], (unsigned long long)cnt | ((unsigned long long)(tile_rows - cnt) << 32));
+            left_base_s = (uint32_t)(old & 0xffffffffull);
+            right_base_s = (uint32_t)(old >> 32);
+        }
+    }
+    __syncthreads();
+    const uint32_t left_base = left_base_s;     // left rows of this segment placed before this tile's
+    const uint32_t right_base = right_base_s;   // right rows likewise
+    const uint32_t seg_last = job.seg_begin + job.seg_len - 1u;
+
+    // ---- write
+#pragma unroll
+    for (int j = 0; j < kRowsPerThread; ++j) {
+        const int w = j * (kFBlock / 64) + wave;
+        const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+        if (in_tile < tile_rows) {
+            const uint64_t m = words[w];
+            const uint32_t below = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            uint32_t q;
+            if ((m >> lane) & 1ull) {
+                q = job.seg_begin + left_base + lefts_before[w] + below;
+            } else {
+                const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[w];
+                q = seg_last - (right_base + rights_before_word + ((uint32_t)lane - below));
+            }
+            if (REG) {
+                ((uint4 *)dst_sym)[q] = row[j];
+                dst_gq[q] = pair[j];
+            } else {
+                dstpos[in_tile] = q;
+                dst_gq[q] = src_gq[p0 + in_tile];
+            }
+        }
+    }
+    if (!REG) {
+        __syncthreads();
+        int lpr = 1;
+        while (lpr < SW && lpr < 64) lpr <<= 1;
+        const int rows_per_wave = 64 / lpr;
+        const int sub = lane / lpr, k0 = lane % lpr;
+        for (uint32_t row0 = (uint32_t)wave * rows_per_wave; row0 < tile_rows; row0 += (kFBlock / 64) * rows_per_wave) {
+            const uint32_t in_tile = row0 + (uint32_t)sub;
+            if (in_tile >= tile_rows) continue;
+            const uint64_t sb = (p0 + in_tile) * (uint64_t)src_stride_bits;
+            const int64_t s0 = (int64_t)(sb >> 5);
+            const uint32_t sh = (uint32_t)(sb & 31);
+            uint32_t *d = dst_sym + (uint64_t)dstpos[in_tile] * (uint64_t)SW;
+            for (int k = k0; k < SW; k += lpr) {
+                const int64_t si = s0 + k;
+                const uint32_t lo = src_sym[si < src_words ? si : src_words - 1];
+                const uint32_t hi = src_sym[si + 1 < src_words ? si + 1 : src_words - 1];
+                uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh);
+                if (k == SW - 1) v &= tail_mask;
+                d[k] = v;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n,
@@ -314,14 +473,15 @@ hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits,
 }
 
 hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
-                                        int64_t n, uint32_t missing, bool ids_only, const PartJob *jobs,
+                                        int64_t n, uint32_t missing, int what, const PartJob *jobs,
                                         int n_jobs, int total_tiles, uint64_t *masks, uint32_t *tile_left,
                                         uint32_t *n_left_out) {
     if (n_jobs <= 0 || total_tiles <= 0) return hipSuccess;
     part_flag_kernel<<<total_tiles, kBlock, 0, s>>>(src.sym, bits, src.stride_bits, n, missing, nullptr, jobs, n_jobs,
                                                     masks, tile_left);
     part_scan_kernel<<<n_jobs, kBlock, 0, s>>>(jobs, tile_left, n_left_out);
-    if (ids_only) {
+    if (what == GBT_PART_COUNT) return hipGetLastError();
+    if (what == GBT_PART_IDS) {
         part_move_ids_kernel<<<total_tiles, kBlock, 0, s>>>(src.id, dst.id_rw, jobs, n_jobs, masks, tile_left,
                                                             n_left_out);
         return hipGetLastError();
@@ -332,5 +492,26 @@ hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const
     part_move_kernel<<<grid, kBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw, SW, row_bits,
                                              (const int2 *)src.gq, (int2 *)dst.gq_rw, src.id, dst.id_rw, jobs,
                                              n_jobs, masks, tile_left, n_left_out, slice_words);
+    return hipGetLastError();
+}
+
+bool gbt_partition_fused_ok(const GbtRows &dst) { return (dst.stride_bits >> 5) <= 64; }
+int gbt_partition_fused_tile() { return kFTile; }
+
+hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
+                                      uint32_t missing, const PartJob *jobs, int n_jobs, int total_tiles,
+                                      unsigned long long *cursor) {
+    if (n_jobs <= 0 || total_tiles <= 0) return hipSuccess;
+    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)cursor, 0, n_jobs);
+    if (e != hipSuccess) return e;
+    const int SW = (int)(dst.stride_bits >> 5);
+    if (SW == 4 && src.stride_bits <= 128)
+        part_fused_kernel<true><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw, SW,
+                                                                row_bits, bits, missing, (const int2 *)src.gq,
+                                                                (int2 *)dst.gq_rw, jobs, n_jobs, cursor);
+    else
+        part_fused_kernel<false><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw,
+                                                                 SW, row_bits, bits, missing, (const int2 *)src.gq,
+                                                                 (int2 *)dst.gq_rw, jobs, n_jobs, cursor);
     return hipGetLastError();
 }

@@ -64,6 +64,13 @@ def grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, nodes=None):
             want = o["cuts"][f, b] if b < p["max_bins"] - 1 else np.inf
             assert tree["threshold"][i] == want
     rep["scale"] = scale
+    # the same tree when row ids are not carried along
+    bare, none_rows, none_leaf = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"],
+                                               gdev["cuts"], gp_t, params, want_rows=False)
+    assert none_rows is None and none_leaf is None and bare["n_nodes"] == nn
+    for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
+              "sumG", "sumH"):
+        assert np.array_equal(bare[k][:nn], tree[k][:nn]), k
     return tree, rep
 
 
@@ -113,6 +120,38 @@ def test_tree_matches_oracle(ctx, oracle, cfg, n, kw, csr):
                         n=n, F=F).cpu().numpy()
     got_x = ctx.predict([tree], dev(m0), 0.3, X=dev(X)).cpu().numpy()
     assert np.array_equal(got_p, ref) and np.array_equal(got_x, ref)
+
+
+@pytest.fixture()
+def ctx_env(monkeypatch):
+    """A context created under tuning variables (they are read when a context is created)."""
+    made = []
+
+    def make(**env):
+        import paper_1806_11248_amd as g
+        for k, v in env.items():
+            monkeypatch.setenv(k, str(v))
+        c = g.Context(0)
+        made.append(c)
+        return c
+    yield make
+    for c in made:
+        c.close()
+
+
+@pytest.mark.parametrize("cfg,n,kw", [(4, 150_000, {}), (3, 40_000, {}), (5, 5_000, {"F": 200})])
+def test_three_launch_partition_path(ctx_env, oracle, cfg, n, kw):
+    """Without row ids the record partition normally takes its one-launch form; switched off, the
+    flag / scan / move form (the one tracked rows and wide rows always take) must grow the same trees."""
+    c = ctx_env(GBT_TUNE_PART_FUSED=0)
+    d = synth.make(cfg, n, **kw)
+    p = d["params"]
+    n, F = d["X"].shape
+    _say(f"three-launch partition C{cfg} n={n} F={F}")
+    o, gdev = gpu_prep(c, oracle, d)
+    gp = (np.stack([d["g"], d["h"]], 1) if p["objective"] == "given"
+          else oracle.gradients(p["objective"], np.zeros(n, np.float32), d["y"]))
+    grow_and_judge(c, oracle, o, gdev, gp, p, n, F)
 
 
 def test_depth_zero_and_gamma(ctx, oracle):
