@@ -30,15 +30,43 @@ __global__ void iota_u32_kernel(uint32_t *p, int64_t count) {
 // max |g| and max |h| as raw float bits (non-negative floats order like their
 // bit patterns; NaN sorts above +inf, so a non-finite input is detected).
 // out2[2] becomes non-zero if any h is negative.
-__global__ void absmax_kernel(const float2 *gp, int64_t n, uint32_t *out2) {
+// A thread takes kStreamBatch 16-byte loads (two pairs each) that are all issued before the
+// first is used, so that enough bytes are in flight to cover the HBM latency.
+constexpr int kStreamBatch = 4;
+// The pointers must be 16-byte aligned; `head` pairs (0 or 1) in front of them are taken singly,
+// which is how a caller's pointer that is only 8-byte aligned is served.
+__global__ __launch_bounds__(kBlock) void absmax_kernel(const float2 *gp, int64_t n, int head, uint32_t *out2) {
     uint32_t mg = 0, mh = 0, neg = 0;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        float2 v = gp[i];
-        uint32_t a = __float_as_uint(v.x) & 0x7fffffffu;
-        uint32_t b = __float_as_uint(v.y) & 0x7fffffffu;
-        mg = a > mg ? a : mg;
-        mh = b > mh ? b : mh;
+    if (head && blockIdx.x == 0 && threadIdx.x == 1) {
+        const float2 v = gp[-1];
+        mg = __float_as_uint(v.x) & 0x7fffffffu;
+        mh = __float_as_uint(v.y) & 0x7fffffffu;
+        neg = v.y < 0.0f ? 1u : 0u;
+    }
+    const float4 *gp4 = (const float4 *)gp;
+    const int64_t n4 = n >> 1;   // whole 16-byte pieces
+    auto take = [&](const float4 &v) {
+        const uint32_t a0 = __float_as_uint(v.x) & 0x7fffffffu, b0 = __float_as_uint(v.y) & 0x7fffffffu;
+        const uint32_t a1 = __float_as_uint(v.z) & 0x7fffffffu, b1 = __float_as_uint(v.w) & 0x7fffffffu;
+        mg = max(mg, max(a0, a1));
+        mh = max(mh, max(b0, b1));
+        neg |= (v.y < 0.0f || v.w < 0.0f) ? 1u : 0u;
+    };
+    // a workgroup takes contiguous chunks of kStreamBatch * kBlock pieces; whole chunks need no conditional load
+    const int64_t chunk = (int64_t)kStreamBatch * kBlock, n_whole = n4 / chunk;
+    for (int64_t c = blockIdx.x; c < n_whole; c += gridDim.x) {
+        float4 v[kStreamBatch];
+#pragma unroll
+        for (int k = 0; k < kStreamBatch; ++k) v[k] = gp4[c * chunk + k * kBlock + threadIdx.x];
+#pragma unroll
+        for (int k = 0; k < kStreamBatch; ++k) take(v[k]);
+    }
+    for (int64_t i = n_whole * chunk + (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kBlock)
+        take(gp4[i]);
+    if ((n & 1) && blockIdx.x == 0 && threadIdx.x == 0) {   // the odd last pair
+        const float2 v = gp[n - 1];
+        mg = max(mg, __float_as_uint(v.x) & 0x7fffffffu);
+        mh = max(mh, __float_as_uint(v.y) & 0x7fffffffu);
         neg |= v.y < 0.0f ? 1u : 0u;
     }
     for (int o = 32; o > 0; o >>= 1) {
@@ -47,12 +75,28 @@ __global__ void absmax_kernel(const float2 *gp, int64_t n, uint32_t *out2) {
         mh = b > mh ? b : mh;
         neg |= __shfl_xor(neg, o);
     }
+    // one set of atomics per workgroup: atomics on one address run one after the other
+    __shared__ uint32_t red[3][kBlock / 64];
     if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = mg;
+        red[1][threadIdx.x >> 6] = mh;
+        red[2][threadIdx.x >> 6] = neg;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kBlock / 64; ++w) {
+            mg = max(mg, red[0][w]);
+            mh = max(mh, red[1][w]);
+            neg |= red[2][w];
+        }
         atomicMax(&out2[0], mg);
         atomicMax(&out2[1], mh);
         if (neg) atomicOr(&out2[2], 1u);
     }
 }
+
+// Adds the workgroup's (g, h) to sums[0..1] with one pair of atomics (every thread must call).
+__device__ inline void block_add_i64x2(int64_t g, int64_t h, int64_t *sums);
 
 __device__ inline int64_t wave_sum_i64(int64_t v) {
     for (int o = 32; o > 0; o >>= 1) {
@@ -63,11 +107,81 @@ __device__ inline int64_t wave_sum_i64(int64_t v) {
     return v;
 }
 
-__global__ void to_fixed_kernel(const float2 *gp, int64_t n, double sg, double sh, int2 *gq, int64_t *sums) {
+// gp and gq must be 16-byte aligned; `head` pairs (0 or 1) in front of BOTH are taken singly.
+__device__ inline void block_add_i64x2(int64_t g, int64_t h, int64_t *sums) {
+    __shared__ int64_t red[2][kBlock / 64];
+    g = wave_sum_i64(g);
+    h = wave_sum_i64(h);
+    if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = g;
+        red[1][threadIdx.x >> 6] = h;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) {
+            g += red[0][w];
+            h += red[1][w];
+        }
+        atomicAdd((unsigned long long *)&sums[0], (unsigned long long)g);
+        atomicAdd((unsigned long long *)&sums[1], (unsigned long long)h);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void to_fixed_kernel(const float2 *gp, int64_t n, int head, double sg, double sh,
+                                                          int2 *gq, int64_t *sums) {
     int64_t g = 0, h = 0;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        float2 v = gp[i];
+    if (head && blockIdx.x == 0 && threadIdx.x == 1) {
+        const float2 v = gp[-1];
+        int2 q;
+        q.x = __double2int_rn((double)v.x * sg);
+        q.y = __double2int_rn((double)v.y * sh);
+        gq[-1] = q;
+        g = q.x;
+        h = q.y;
+    }
+    const float4 *gp4 = (const float4 *)gp;
+    int4 *gq4 = (int4 *)gq;
+    const int64_t n4 = n >> 1;   // whole 16-byte pieces (two pairs)
+    auto take = [&](int64_t at, const float4 &v) {
+        int4 q;
+        q.x = __double2int_rn((double)v.x * sg);
+        q.y = __double2int_rn((double)v.y * sh);
+        q.z = __double2int_rn((double)v.z * sg);
+        q.w = __double2int_rn((double)v.w * sh);
+        gq4[at] = q;
+        g += (int64_t)q.x + q.z;
+        h += (int64_t)q.y + q.w;
+    };
+    const int64_t chunk = (int64_t)kStreamBatch * kBlock, n_whole = n4 / chunk;
+    for (int64_t c = blockIdx.x; c < n_whole; c += gridDim.x) {
+        float4 v[kStreamBatch];
+#pragma unroll
+        for (int k = 0; k < kStreamBatch; ++k) v[k] = gp4[c * chunk + k * kBlock + threadIdx.x];
+#pragma unroll
+        for (int k = 0; k < kStreamBatch; ++k) take(c * chunk + k * kBlock + threadIdx.x, v[k]);
+    }
+    for (int64_t i = n_whole * chunk + (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kBlock)
+        take(i, gp4[i]);
+    if ((n & 1) && blockIdx.x == 0 && threadIdx.x == 0) {   // the odd last pair
+        const float2 v = gp[n - 1];
+        int2 q;
+        q.x = __double2int_rn((double)v.x * sg);
+        q.y = __double2int_rn((double)v.y * sh);
+        gq[n - 1] = q;
+        g += q.x;
+        h += q.y;
+    }
+    if (sums) {
+        block_add_i64x2(g, h, sums);
+    }
+}
+
+// One pair per load: for a source and a destination whose 16-byte alignments differ.
+__global__ __launch_bounds__(kBlock) void to_fixed_pairs_kernel(const float2 *gp, int64_t n, double sg, double sh,
+                                                                int2 *gq, int64_t *sums) {
+    int64_t g = 0, h = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float2 v = gp[i];
         int2 q;
         q.x = __double2int_rn((double)v.x * sg);
         q.y = __double2int_rn((double)v.y * sh);
@@ -76,16 +190,11 @@ __global__ void to_fixed_kernel(const float2 *gp, int64_t n, double sg, double s
         h += q.y;
     }
     if (sums) {
-        g = wave_sum_i64(g);
-        h = wave_sum_i64(h);
-        if ((threadIdx.x & 63) == 0) {
-            atomicAdd((unsigned long long *)&sums[0], (unsigned long long)g);
-            atomicAdd((unsigned long long *)&sums[1], (unsigned long long)h);
-        }
+        block_add_i64x2(g, h, sums);
     }
 }
 
-__global__ void sum_gq_kernel(const int2 *gq, const uint32_t *row_idx, int64_t n_rows, int64_t *out2) {
+__global__ __launch_bounds__(kBlock) void sum_gq_kernel(const int2 *gq, const uint32_t *row_idx, int64_t n_rows, int64_t *out2) {
     int64_t g = 0, h = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_rows;
          i += (int64_t)gridDim.x * blockDim.x) {
@@ -94,12 +203,7 @@ __global__ void sum_gq_kernel(const int2 *gq, const uint32_t *row_idx, int64_t n
         g += q.x;
         h += q.y;
     }
-    g = wave_sum_i64(g);
-    h = wave_sum_i64(h);
-    if ((threadIdx.x & 63) == 0) {
-        atomicAdd((unsigned long long *)&out2[0], (unsigned long long)g);
-        atomicAdd((unsigned long long *)&out2[1], (unsigned long long)h);
-    }
+    block_add_i64x2(g, h, out2);
 }
 
 // Eq. 1 and Eq. 2 (logistic) and the squared-error pair, one instance per
@@ -365,7 +469,9 @@ hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count) {
 hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2) {
     hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)out2, 0, 2);
     if (e != hipSuccess || n <= 0) return e;
-    absmax_kernel<<<grid_for(n, kBlock * 8, 2048), kBlock, 0, s>>>((const float2 *)gpair, n, out2);
+    const int head = (int)(((uintptr_t)gpair >> 3) & 1u);   // pairs before the first 16-byte boundary
+    absmax_kernel<<<grid_for(n, kBlock * 2 * kStreamBatch, 2048), kBlock, 0, s>>>((const float2 *)gpair + head,
+                                                                                  n - head, head, out2);
     return hipGetLastError();
 }
 hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, double sg, double sh,
@@ -375,8 +481,14 @@ hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, dou
         if (e != hipSuccess) return e;
     }
     if (n <= 0) return hipSuccess;
-    to_fixed_kernel<<<grid_for(n, kBlock * 4, 4096), kBlock, 0, s>>>((const float2 *)gpair, n, sg, sh,
-                                                                      (int2 *)gq, sums_out);
+    const int head = (int)(((uintptr_t)gpair >> 3) & 1u);
+    if (head != (int)(((uintptr_t)gq >> 3) & 1u)) {
+        to_fixed_pairs_kernel<<<grid_for(n, kBlock * 4, 2048), kBlock, 0, s>>>((const float2 *)gpair, n, sg, sh,
+                                                                               (int2 *)gq, sums_out);
+        return hipGetLastError();
+    }
+    to_fixed_kernel<<<grid_for(n, kBlock * 2 * kStreamBatch, 2048), kBlock, 0, s>>>(
+        (const float2 *)gpair + head, n - head, head, sg, sh, (int2 *)gq + head, sums_out);
     return hipGetLastError();
 }
 hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,

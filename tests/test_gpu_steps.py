@@ -238,6 +238,30 @@ def test_gpair_fixed_scale_and_errors(ctx):
     assert scale == (1.0, 1.0) and not gq.any()
 
 
+@pytest.mark.parametrize("n", [1, 2, 7, 4096, 100_003, 2_500_001])
+@pytest.mark.parametrize("src_off,dst_off", [(0, 0), (1, 0), (1, 1), (0, 1)])
+def test_gpair_fixed_any_alignment(ctx, n, src_off, dst_off):
+    """Pairs are 8 bytes; the kernels work in 16-byte pieces and must serve pointers of either
+    alignment, on both sides, with odd and even counts."""
+    import ctypes as C
+    from paper_1806_11248_amd.binding import _ptr
+    rng = np.random.default_rng(n * 4 + src_off * 2 + dst_off)
+    gp = np.stack([rng.normal(0, 2, n), rng.uniform(0, 1, n)], 1).astype(np.float32)
+    src = torch.zeros((n + 1, 2), dtype=torch.float32, device="cuda")
+    src[src_off:src_off + n] = torch.from_numpy(gp).cuda()
+    dst = torch.full((n + 2, 2), -7, dtype=torch.int32, device="cuda")
+    scale = (C.c_double * 2)()
+    ws = ctx.workspace("small", 4096)
+    _say(f"gpair_fixed n={n} src+{src_off} dst+{dst_off}")
+    ctx._check(ctx.lib.gbt_gpair_fixed(ctx.h, _ptr(src[src_off:]), n, _ptr(dst[dst_off:]), scale, _ptr(ws), ws.numel()))
+    want = np.rint(gp.astype(np.float64) * np.array([scale[0], scale[1]])).astype(np.int32)
+    got = dst.cpu().numpy()
+    assert np.array_equal(got[dst_off:dst_off + n], want)
+    assert (got[:dst_off] == -7).all() and (got[dst_off + n:] == -7).all()      # nothing written outside
+    sums = ctx.sum_gpair(dst[dst_off:dst_off + n].contiguous())
+    assert sums == (int(want[:, 0].astype(np.int64).sum()), int(want[:, 1].astype(np.int64).sum()))
+
+
 # ---------------------------------------------------------------------- split --
 @pytest.mark.parametrize("n,F,B,miss", [(10_000, 8, 16, 0.0), (30_007, 50, 256, 0.8), (5_003, 300, 64, 0.0),
                                         (700, 5, 256, 0.3)])
