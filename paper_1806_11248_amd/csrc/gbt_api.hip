@@ -905,9 +905,21 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
                                  T.right[i] < T.n_nodes,
                         GBT_EINVAL, "tree %d node %d: bad feature or child id", t, i);
         }
+        // the tree's depth (steps of its longest walk), if every child comes after its parent
+        std::vector<int> depth_of((size_t)T.n_nodes, 0);
+        int tree_depth = 0;
+        for (int i = 0; i < T.n_nodes; ++i) {
+            if (T.feature[i] < 0) continue;
+            if (T.left[i] <= i || T.right[i] <= i) {
+                compact_ok = false;
+                break;
+            }
+            depth_of[T.left[i]] = depth_of[T.right[i]] = depth_of[i] + 1;
+            tree_depth = std::max(tree_depth, depth_of[i] + 1);
+        }
         const size_t a4 = gbt_align((size_t)T.n_nodes * 4);
         tab[t].n_nodes = T.n_nodes;
-        tab[t].pad = 0;
+        tab[t].pad = tree_depth;
         const void *src4[6] = {T.feature, T.bin, T.default_left, T.left, T.right, T.threshold};
         uint64_t *dst4[6] = {&tab[t].feature, &tab[t].bin, &tab[t].default_left, &tab[t].left, &tab[t].right,
                              &tab[t].threshold};

@@ -181,7 +181,7 @@ hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_ele
 
 struct DevTree {   // one tree's arrays inside the predict workspace (offsets in bytes)
     int32_t n_nodes;
-    int32_t pad;
+    int32_t pad;   // the tree's depth (steps of its longest root-to-leaf walk)
     uint64_t feature, bin, default_left, left, right, threshold, weight;
 };
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,

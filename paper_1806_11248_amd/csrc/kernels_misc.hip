@@ -377,48 +377,75 @@ __device__ __forceinline__ uint32_t pick4(const uint32_t (&W)[4], int i) {
     return i == 0 ? W[0] : (i == 1 ? W[1] : (i == 2 ? W[2] : W[3]));
 }
 // Nodes are staged as 8 bytes: x = left child id | default_left << 31 (the right child is
-// left + 1, which the caller has checked), y = feature << 12 | bin, y = ~0 for a leaf.
+// left + 1, which the caller has checked), y = feature << 12 | bin.  A leaf is staged as a
+// node that sends every row to itself (left = own id, default left, bin 0xfff >= any symbol),
+// so every row takes exactly T.pad steps (the tree's depth) and the walks of the kPredRows rows
+// a thread handles at once run side by side instead of one divergent loop after the other.
+constexpr int kPredRows = 4;
 __global__ __launch_bounds__(256) void predict_window_kernel(const char *ws, const DevTree *trees, int n_trees,
                                                              const uint32_t *packed, int64_t n_words, int bits,
                                                              uint32_t missing, int64_t n, int F, double eta,
-                                                             float *margin, int rows_per_block) {
+                                                             float *margin, int rows_per_block, int max_nodes) {
     extern __shared__ uint2 cnodes[];
+    double *lweight = (double *)(cnodes + max_nodes);
     const uint32_t mask = (1u << bits) - 1u;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
     for (int t = 0; t < n_trees; ++t) {
         const DevTree T = trees[t];
-        const double *weight = (const double *)(ws + T.weight);
         __syncthreads();
         for (int i = threadIdx.x; i < T.n_nodes; i += 256) {
             const int32_t f = ((const int32_t *)(ws + T.feature))[i];
             uint2 c;
-            c.x = (uint32_t)((const int32_t *)(ws + T.left))[i] |
-                  (((const int32_t *)(ws + T.default_left))[i] ? 0x80000000u : 0u);
-            c.y = f < 0 ? 0xffffffffu : (((uint32_t)f << 12) | (uint32_t)((const int32_t *)(ws + T.bin))[i]);
+            if (f < 0) {
+                c.x = (uint32_t)i | 0x80000000u;
+                c.y = 0xfffu;
+            } else {
+                c.x = (uint32_t)((const int32_t *)(ws + T.left))[i] |
+                      (((const int32_t *)(ws + T.default_left))[i] ? 0x80000000u : 0u);
+                c.y = ((uint32_t)f << 12) | (uint32_t)((const int32_t *)(ws + T.bin))[i];
+            }
             cnodes[i] = c;
+            lweight[i] = ((const double *)(ws + T.weight))[i];
         }
         __syncthreads();
-        for (int64_t r = r0 + threadIdx.x; r < r1; r += 256) {
-            const uint64_t rowbit = (uint64_t)r * (uint64_t)F * (uint64_t)bits;
-            const int64_t w0 = (int64_t)(rowbit >> 5);
-            const uint32_t sh = (uint32_t)(rowbit & 31);
-            uint32_t w[5], W[4];
+        const int depth = T.pad;
+        for (int64_t rb = r0 + threadIdx.x; rb < r1; rb += 256 * kPredRows) {
+            uint32_t W[kPredRows][4];
+            float m[kPredRows];
 #pragma unroll
-            for (int k = 0; k < 5; ++k) w[k] = packed[w0 + k < n_words ? w0 + k : n_words - 1];
+            for (int q = 0; q < kPredRows; ++q) {
+                // rows past the end repeat the last row (their result is dropped)
+                const int64_t r = rb + 256 * q < r1 ? rb + 256 * q : r1 - 1;
+                const uint64_t rowbit = (uint64_t)r * (uint64_t)F * (uint64_t)bits;
+                const int64_t w0 = (int64_t)(rowbit >> 5);
+                const uint32_t sh = (uint32_t)(rowbit & 31);
+                uint32_t w[5];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) W[k] = __builtin_amdgcn_alignbit(w[k + 1], w[k], sh);
-            uint32_t node = 0;
-            for (int step = 0; step < T.n_nodes; ++step) {
-                const uint2 c = cnodes[node];
-                if (c.y == 0xffffffffu) break;
-                const int pos = (int)(c.y >> 12) * bits, wd = pos >> 5;
-                const uint32_t lo = pick4(W, wd), hi = wd < 3 ? pick4(W, wd + 1) : 0u;
-                const uint32_t s = __builtin_amdgcn_alignbit(hi, lo, (uint32_t)(pos & 31)) & mask;
-                const bool go_left = (s == missing) ? (c.x >> 31) != 0 : (s <= (c.y & 0xfffu));
-                node = (c.x & 0x7fffffffu) + (go_left ? 0u : 1u);
+                for (int k = 0; k < 5; ++k) w[k] = packed[w0 + k < n_words ? w0 + k : n_words - 1];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) W[q][k] = __builtin_amdgcn_alignbit(w[k + 1], w[k], sh);
+                m[q] = margin[r];
             }
-            margin[r] = (float)((double)margin[r] + eta * weight[node]);
+            uint32_t node[kPredRows];
+#pragma unroll
+            for (int q = 0; q < kPredRows; ++q) node[q] = 0;
+            for (int step = 0; step < depth; ++step) {
+#pragma unroll
+                for (int q = 0; q < kPredRows; ++q) {
+                    const uint2 c = cnodes[node[q]];
+                    const int pos = (int)(c.y >> 12) * bits, wd = pos >> 5;
+                    const uint32_t lo = pick4(W[q], wd), hi = wd < 3 ? pick4(W[q], wd + 1) : 0u;
+                    const uint32_t s = __builtin_amdgcn_alignbit(hi, lo, (uint32_t)(pos & 31)) & mask;
+                    const bool go_left = (s == missing) ? (c.x >> 31) != 0 : (s <= (c.y & 0xfffu));
+                    node[q] = (c.x & 0x7fffffffu) + (go_left ? 0u : 1u);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kPredRows; ++q) {
+                const int64_t r = rb + 256 * q;
+                if (r < r1) margin[r] = (float)((double)m[q] + eta * lweight[node[q]]);
+            }
         }
     }
 }
@@ -540,6 +567,7 @@ hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *tree
                               int64_t n, int F, double eta, float *margin, int max_nodes, bool compact_ok) {
     if (n <= 0) return hipSuccess;
     const size_t lds = (size_t)max_nodes * sizeof(LdsNode);
+    static_assert(sizeof(LdsNode) >= 16, "the register-window kernel stages 16 bytes per node");
     if (lds <= 96u * 1024u) {
         static size_t configured = 0;
         if (lds > configured) {
@@ -560,7 +588,7 @@ hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *tree
             }
             const int64_t n_words = (n * (int64_t)F * bits + 31) / 32 + 1;
             predict_window_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, bits, missing,
-                                                                   n, F, eta, margin, rows_per_block);
+                                                                   n, F, eta, margin, rows_per_block, max_nodes);
             return hipGetLastError();
         }
         predict_lds_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, bits, missing, X, n, F, eta,
