@@ -171,6 +171,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (const char *e1 = getenv("GBT_TUNE_HIST_BLOCK")) { int v = atoi(e1); if (v == 256 || v == 512 || v == 1024) c->hist_block = v; }
         if (const char *e3 = getenv("GBT_TUNE_HIST_RUNTIME_BITS")) c->hist_runtime_bits = atoi(e3) != 0;
         c->part_fused = 1;
+        c->part_hist = 1;
+        if (const char *e8 = getenv("GBT_TUNE_PART_HIST")) c->part_hist = atoi(e8) != 0;
         if (const char *e6 = getenv("GBT_TUNE_PART_FUSED")) c->part_fused = atoi(e6) != 0;
         if (const char *e5 = getenv("GBT_TUNE_HIST_LDS_KB")) { int v = atoi(e5); if (v >= 8 && v <= 128) c->hist_lds_kb = v; }
         if (const char *e2 = getenv("GBT_TUNE_HIST_JOBS")) { int v = atoi(e2); if (v >= 1 && v <= 64) c->hist_jobs_per_cu = v; }
@@ -702,15 +704,15 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
 
         // ---- which nodes split; RepartitionInstances for those.
         // Children that are split again get their whole records moved: by the one-launch form
-        // when nobody needs the row order and the rows are narrow enough, else by the three-launch
-        // form.  Leaves only need their ids moved, or just the row counts when ids are not tracked.
+        // when nobody needs the row order and the rows are narrow enough (and then, where the
+        // histogram kernel's 8-bit single-tile case applies, one child's histogram is built in
+        // the same pass), else by the three-launch form.  Leaves only need their ids moved, or
+        // just the row counts when ids are not tracked.
         const int wnext = wcur == 0 ? 1 : 0;
         const bool children_need_hist = depth + 1 < max_depth;
         const bool fused = children_need_hist && !tracked && ctx->part_fused && gbt_partition_fused_ok(W[wnext]);
-        const uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile() : (uint32_t)GBT_PART_TILE;
-        pjobs.clear();
+        const bool with_hist = fused && ctx->part_hist && pl.n_ftiles == 1 && gbt_part_hist_ok(ctx, bits, F, B, W[wnext]);
         split_of.clear();
-        uint32_t tile_cursor = 0;
         double part_rows = 0;
         for (size_t i = 0; i < level.size(); ++i) {
             const gbt_split &sp = splits[i];
@@ -721,6 +723,22 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)wcur, nd.len});
                 continue;
             }
+            part_rows += nd.len;
+            split_of.push_back((int)i);
+        }
+        // rows per partition workgroup: a tile, or (with the histogram) a span of tiles long enough
+        // to be worth merging an LDS histogram into HBM for
+        uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile() : (uint32_t)GBT_PART_TILE;
+        if (with_hist) {
+            const uint32_t t = (uint32_t)gbt_part_hist_tile();
+            const double want = part_rows / ((double)ctx->num_cu * ctx->hist_jobs_per_cu);
+            part_tile = (uint32_t)std::min<double>(std::max<double>(std::ceil(want / t), 4.0), (double)((1u << 21) / t)) * t;
+        }
+        pjobs.clear();
+        uint32_t tile_cursor = 0;
+        for (size_t k = 0; k < split_of.size(); ++k) {
+            const gbt_split &sp = splits[split_of[k]];
+            const HNode &nd = level[split_of[k]];
             PartJob j;
             j.seg_begin = nd.begin;
             j.seg_len = nd.len;
@@ -729,11 +747,13 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             j.default_left = (uint32_t)sp.default_left;
             j.tile_begin = tile_cursor;
             j.n_tiles = (nd.len + part_tile - 1) / part_tile;
-            j.pad = 0;
+            // with the histogram: build the child with the smaller hessian sum (a stand-in for "fewer
+            // rows", which is only known after the partition); children are numbered in job order
+            const bool build_left = sp.HLq <= nd.Hq - sp.HLq;
+            j.pad = build_left ? 1u : 0u;
+            j.hist_off = (uint64_t)(n_nodes + 2 * (int64_t)k + (build_left ? 0 : 1)) * (uint64_t)hist_len;
             tile_cursor += j.n_tiles;
-            part_rows += nd.len;
             pjobs.push_back(j);
-            split_of.push_back((int)i);
         }
         next.clear();
         if (pjobs.empty()) {
@@ -741,8 +761,16 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             break;
         }
         GBT_REQUIRE(ctx, (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
+        GBT_REQUIRE(ctx, pjobs.size() * sizeof(PartJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
         if (st != GBT_OK) return st;
+        if (with_hist) {   // the children's histograms are accumulated into: clear them first
+            const int64_t n_children = 2 * (int64_t)pjobs.size();
+            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
+            GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)n_nodes * hist_len), 0,
+                                             n_children * hist_len));
+            gbt_prof_end(ctx);
+        }
         const int what = children_need_hist ? GBT_PART_RECORDS : tracked ? GBT_PART_IDS : GBT_PART_COUNT;
         const double rec_bytes = row_bits / 8.0 + 8.0;
         gbt_prof_begin(ctx, GBT_PROF_PARTITION,
@@ -750,7 +778,12 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                                     : what == GBT_PART_RECORDS ? row_bits / 8.0 + 2.0 * (rec_bytes + 4.0)
                                     : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
                                                                : row_bits / 8.0));
-        if (fused) {
+        if (with_hist) {
+            GBT_HIP(ctx, gbt_launch_part_hist(ctx, cur, W[wnext], F, B, (uint32_t)missing_sym,
+                                              (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
+                                              part_tile, (unsigned long long *)(ws + L.state), pool));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+        } else if (fused) {
             GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,
                                                     (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
                                                     (int)tile_cursor, (unsigned long long *)(ws + L.state)));
@@ -796,7 +829,9 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             set_node(lc);
             set_node(rc);
             if (children_need_hist) {
-                const bool left_small = lc.len <= rc.len;
+                // the child whose histogram is built from rows: the one the partition pass has already
+                // built, else the one with fewer rows; its sibling comes by subtraction
+                const bool left_small = with_hist ? pjobs[k].pad == 1u : lc.len <= rc.len;
                 const HNode &sm = left_small ? lc : rc, &lg = left_small ? rc : lc;
                 built.push_back(Built{(uint64_t)sm.id * (uint64_t)hist_len, sm.begin, sm.len});
                 built_rows += sm.len;
@@ -809,9 +844,9 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 leaves.push_back(LeafSeg{rc.begin, (uint32_t)rc.id, (uint32_t)wcur, rc.len});
             }
         }
-        if (children_need_hist) {
+        if (children_need_hist && !with_hist) {
             // ---- BuildPartialHistograms for the smaller children (their rows are now one
-            //      contiguous run of the working copy), siblings by subtraction
+            //      contiguous run of the working copy)
             const int32_t n_children = n_nodes - first_child;
             gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
             GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
@@ -831,6 +866,8 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                                              (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
                 gbt_prof_end(ctx);
             }
+        }
+        if (children_need_hist) {   // ---- siblings by subtraction
             GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
             st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
             if (st != GBT_OK) return st;

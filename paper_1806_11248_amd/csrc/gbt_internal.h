@@ -26,6 +26,7 @@ struct gbt_ctx {
     int hist_block;         // threads per histogram workgroup
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
     int part_fused;         // 1: one-launch record partition where it applies
+    int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
     size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
@@ -84,7 +85,8 @@ struct PartJob {
     uint32_t default_left;
     uint32_t tile_begin;   // index of the segment's first tile in the level's tile arrays
     uint32_t n_tiles;
-    uint32_t pad;
+    uint32_t pad;          // partition + histogram pass: the child to build (1 left, 0 right, 2 none)
+    uint64_t hist_off;     // same pass: that child's histogram in the pool (int64 units)
 };
 
 // One "out = parent - child" for the subtraction kernel (int64 units).
@@ -171,6 +173,16 @@ int gbt_partition_fused_tile();
 hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
                                       uint32_t missing, const PartJob *jobs, int n_jobs, int total_tiles,
                                       unsigned long long *cursor);
+// Partition and the histogram of one child of every job in one pass (8-bit symbols, at most 16
+// features, the bins of all features in one LDS tile: gbt_part_hist_ok).  Rows are moved as by
+// gbt_launch_partition_fused (no ids, order inside a child not kept).  PartJob.tile_begin /
+// n_tiles count spans of rows_per_span rows (a multiple of gbt_part_hist_tile()); PartJob.pad /
+// hist_off name the child to build, whose histogram must have been cleared.
+bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B, const GbtRows &dst);
+int gbt_part_hist_tile();
+hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const GbtRows &src, const GbtRows &dst, int F, int B, uint32_t missing,
+                                const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                                unsigned long long *cursor, int64_t *hist_pool);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,

@@ -356,6 +356,236 @@ __global__ __launch_bounds__(kHistBlock) void hist_static_kernel(
     flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
 }
 
+// ---------------------------------------------------------------------------
+// RepartitionInstances and the children's BuildPartialHistograms in ONE pass
+// (8-bit symbols, at most 16 features, row order not needed).
+//
+// Moving a node's records to its children is bound by HBM, the histogram of a
+// child by the LDS atomic unit; run one after the other the two leave each other's
+// resource idle.  Here a workgroup takes a span of one splitting node's rows, tile
+// by tile: every thread loads its rows into registers, decides their side, adds
+// the rows of the side to be built into the workgroup's LDS histogram (exactly as
+// hist_b8_kernel does) while the tile's room in the children is being reserved
+// with one 64-bit atomic on the node's cursor, and then stores the rows at their
+// new place.  The span's histogram is merged into the child's histogram at the end.
+// Left rows fill the node's segment from its start, right rows from its end
+// backwards; tiles land in the order their atomics arrive (see part_fused_kernel
+// for the same scheme without a histogram).
+//
+// PartJob: tile_begin / n_tiles count SPANS of `rows_per_span` rows here; pad is
+// the side to build (1 left, 0 right, 2 none), hist_off that child's histogram.
+// ---------------------------------------------------------------------------
+constexpr int kPHBlock = 512;
+constexpr int kPHRows = 8;                       // rows per thread and tile: what is in flight while the tile loads
+constexpr int kPHTile = kPHBlock * kPHRows;      // 4096
+constexpr int kPHWords = kPHTile / 64;           // 64 ballot words
+static_assert(kPHWords == 64, "the ballot words are ranked by one wave");
+constexpr int kPHGroup = 7;                      // atomics of a row in flight together (registers for their results)
+
+__device__ inline int find_span_job(const PartJob *jobs, int n_jobs, uint32_t span) {
+    int lo = 0, hi = n_jobs;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (jobs[mid].tile_begin <= span) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+template <int NS, bool CHK>
+__global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
+    const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words, bool aligned_src,
+    uint32_t *__restrict__ dst_sym, int ft, int B, int Bp, uint32_t missing, const int2 *__restrict__ src_gq,
+    int2 *__restrict__ dst_gq, const PartJob *__restrict__ jobs, int n_jobs, uint32_t rows_per_span,
+    unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
+    constexpr int SW = (NS + 3) / 4;   // 32-bit words per row
+    extern __shared__ unsigned long long lds[];
+    __shared__ uint64_t words[2][kPHWords];
+    __shared__ uint32_t lefts_before[2][kPHWords];
+    __shared__ uint32_t base_s[2][2];
+    const int ji = find_span_job(jobs, n_jobs, blockIdx.x);
+    const PartJob job = jobs[ji];
+    const uint32_t span_begin = (blockIdx.x - job.tile_begin) * rows_per_span;
+    const uint32_t span_rows = job.seg_len - span_begin < rows_per_span ? job.seg_len - span_begin : rows_per_span;
+    const bool build = job.pad != 2u, build_left = job.pad == 1u;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    const int trash = ft * Bp;
+    const int n_acc = trash + 256;
+    unsigned long long *main_ = lds;
+    uint32_t *side = (uint32_t *)(lds + n_acc);
+    for (int i = threadIdx.x; i < n_acc; i += kPHBlock) {
+        main_[i] = 0;
+        side[i] = 0;
+    }
+    // slot j of this lane handles feature (j + lane) mod ft (see hist_b8_kernel)
+    uint32_t selA[4], selB[4];
+    int pre[NS];
+    {
+        const int l0 = lane % ft;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            selA[k] = 0;
+            selB[k] = 0;
+        }
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            int t = j + l0;
+            t = t >= ft ? t - ft : t;
+            const bool live = j < ft;
+            pre[j] = live ? t * Bp : trash;
+            const uint32_t a = (live && t < 8) ? (uint32_t)t : 0x0Cu;
+            const uint32_t b = (live && t >= 8) ? (uint32_t)(t - 8) : 0x0Cu;
+            selA[j >> 2] |= a << (8 * (j & 3));
+            selB[j >> 2] |= b << (8 * (j & 3));
+        }
+    }
+    const int fword = (int)(job.feature >> 2);              // the split feature's word and shift inside a row
+    const uint32_t fshift = (job.feature & 3u) * 8u;
+    const int row_bits = ft * 8;
+    const uint32_t tail_bits = (uint32_t)(row_bits - 32 * (SW - 1));
+    const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
+    const uint32_t seg_last = job.seg_begin + job.seg_len - 1u;
+    __syncthreads();
+
+    int par = 0;
+    for (uint32_t done = 0; done < span_rows; done += kPHTile, par ^= 1) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)kPHTile ? span_rows - done : (uint32_t)kPHTile;
+        const uint64_t p0 = (uint64_t)job.seg_begin + span_begin + done;
+        uint32_t row[kPHRows][SW];
+        int2 pair[kPHRows];
+        uint32_t takebits = 0;
+        // ---- load, decide
+#pragma unroll
+        for (int j = 0; j < kPHRows; ++j) {
+            const int w = j * (kPHBlock / 64) + wave;
+            const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+            bool left = false;
+            if (in_tile < tile_rows) {
+                const uint64_t p = p0 + in_tile;
+                if (aligned_src) {
+                    const uint32_t *sp = src_sym + p * SW;
+                    if constexpr (SW == 4) {
+                        const uint4 v = *(const uint4 *)sp;
+                        row[j][0] = v.x; row[j][1] = v.y; row[j][2] = v.z; row[j][3] = v.w;
+                    } else if constexpr (SW == 2) {
+                        const uint2 v = *(const uint2 *)sp;
+                        row[j][0] = v.x; row[j][1] = v.y;
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < SW; ++k) row[j][k] = sp[k];
+                    }
+                } else {
+                    const uint64_t sb = p * (uint64_t)src_stride_bits;
+                    const int64_t s0 = (int64_t)(sb >> 5);
+                    const uint32_t sh = (uint32_t)(sb & 31);
+                    uint32_t x[SW + 1];
+#pragma unroll
+                    for (int k = 0; k <= SW; ++k) x[k] = src_sym[s0 + k < src_words ? s0 + k : src_words - 1];
+#pragma unroll
+                    for (int k = 0; k < SW; ++k) row[j][k] = __builtin_amdgcn_alignbit(x[k + 1], x[k], sh);
+                    row[j][SW - 1] &= tail_mask;
+                }
+                pair[j] = src_gq[p];
+                uint32_t fw = row[j][0];
+#pragma unroll
+                for (int k = 1; k < SW; ++k) fw = fword == k ? row[j][k] : fw;
+                const uint32_t sy = (fw >> fshift) & 0xffu;
+                left = (sy == missing) ? (job.default_left != 0) : (sy <= job.bin);
+                takebits |= (build && left == build_left) ? (1u << j) : 0u;
+            }
+            const uint64_t ballot = __ballot(left);
+            if (lane == 0) words[par][w] = ballot;
+        }
+        __syncthreads();
+
+        // ---- wave 0 ranks the ballot words and reserves the tile's room (the answer is awaited after
+        //      the histogram work below)
+        unsigned long long reserved = 0;
+        if (wave == 0) {
+            const uint32_t c = (uint32_t)__popcll(words[par][lane]);   // kPHWords == 64: one word per lane
+            uint32_t x = c;
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t y = (uint32_t)__shfl_up((int)x, d);
+                if (lane >= d) x += y;
+            }
+            lefts_before[par][lane] = x - c;
+            if (lane == 63)
+                reserved = atomicAdd(&cursor[ji], (unsigned long long)x | ((unsigned long long)(tile_rows - x) << 32));
+        }
+
+        // ---- histogram of the rows on the side to be built
+#pragma unroll
+        for (int j = 0; j < kPHRows; ++j) {
+            if ((takebits >> j) & 1u) {
+                const unsigned long long addv = pack_pair(pair[j]);
+                const uint32_t hq = (uint32_t)pair[j].y;
+                uint32_t W[4], V[(NS + 3) / 4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) W[k] = k < SW ? row[j][k < SW ? k : 0] : 0u;   // words past the row are never selected
+#pragma unroll
+                for (int k = 0; k < (NS + 3) / 4; ++k)
+                    V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
+#pragma unroll
+                for (int t0 = 0; t0 < NS; t0 += kPHGroup) {
+                    int idx[kPHGroup];
+                    unsigned long long old[kPHGroup];
+#pragma unroll
+                    for (int tt = 0; tt < kPHGroup; ++tt) {
+                        const int t = t0 + tt;
+                        if (t < NS) {
+                            const uint32_t sv = (V[t >> 2] >> (8 * (t & 3))) & 0xffu;
+                            bool bad = false;
+                            if (CHK) bad = (sv == missing) | (sv >= (uint32_t)B);
+                            idx[tt] = (bad ? trash : pre[t]) + (int)sv;
+                            old[tt] = atomicAdd(&main_[idx[tt]], addv);
+                        }
+                    }
+#pragma unroll
+                    for (int tt = 0; tt < kPHGroup; ++tt)
+                        if (t0 + tt < NS) pk_check(side, idx[tt], old[tt], addv, hq);
+                }
+            }
+        }
+        if (wave == 0 && lane == 63) {
+            base_s[par][0] = (uint32_t)(reserved & 0xffffffffull);
+            base_s[par][1] = (uint32_t)(reserved >> 32);
+        }
+        __syncthreads();
+
+        // ---- store
+        const uint32_t left_base = base_s[par][0], right_base = base_s[par][1];
+#pragma unroll
+        for (int j = 0; j < kPHRows; ++j) {
+            const int w = j * (kPHBlock / 64) + wave;
+            const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+            if (in_tile < tile_rows) {
+                const uint64_t m = words[par][w];
+                const uint32_t below = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                uint32_t q;
+                if ((m >> lane) & 1ull) {
+                    q = job.seg_begin + left_base + lefts_before[par][w] + below;
+                } else {
+                    const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[par][w];
+                    q = seg_last - (right_base + rights_before_word + ((uint32_t)lane - below));
+                }
+                uint32_t *dp = dst_sym + (uint64_t)q * SW;
+                if constexpr (SW == 4) {
+                    *(uint4 *)dp = make_uint4(row[j][0], row[j][1], row[j][2], row[j][3]);
+                } else if constexpr (SW == 2) {
+                    *(uint2 *)dp = make_uint2(row[j][0], row[j][1]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < SW; ++k) dp[k] = row[j][k];
+                }
+                dst_gq[q] = pair[j];
+            }
+        }
+        // words[par] is rewritten two tiles from now, after two more barriers: no third barrier needed
+    }
+    __syncthreads();
+    if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, kPHBlock);
+}
+
 inline int padded_bins(int B) { return B | 1; }   // odd stride: see the note on LDS banks above
 
 }  // namespace
@@ -481,4 +711,72 @@ hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64
     if (row_idx)
         return launch_generic<true>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
     return launch_generic<false>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
+}
+
+// ---- partition + histogram in one pass --------------------------------------
+namespace {
+struct PHArgs {
+    hipStream_t s;
+    int n_spans;
+    size_t lds;
+    const uint32_t *src_sym;
+    int64_t src_stride_bits, src_words;
+    uint32_t *dst_sym;
+    int ft, B, Bp;
+    uint32_t missing;
+    const int2 *src_gq;
+    int2 *dst_gq;
+    const PartJob *jobs;
+    int n_jobs;
+    uint32_t rows_per_span;
+    unsigned long long *cursor;
+    int64_t *pool;
+};
+template <int NS, bool CHK>
+hipError_t launch_ph(const PHArgs &a) {
+    static size_t configured = 0;
+    if (a.lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+        if (e != hipSuccess) return e;
+        configured = a.lds;
+    }
+    // rows of whole words on a 16-byte aligned base (always true of the working copies) load as vectors
+    const bool aligned_src = a.src_stride_bits == 32 * ((NS + 3) / 4) && ((uintptr_t)a.src_sym & 15u) == 0;
+    part_hist_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src_sym, a.src_stride_bits, a.src_words, aligned_src, a.dst_sym,
+                                                                   a.ft, a.B, a.Bp, a.missing, a.src_gq, a.dst_gq,
+                                                                   a.jobs, a.n_jobs, a.rows_per_span, a.cursor, a.pool);
+    return hipGetLastError();
+}
+template <bool CHK>
+hipError_t pick_ph(int ft, const PHArgs &a) {
+    if (ft <= 4) return launch_ph<4, CHK>(a);
+    if (ft <= 8) return launch_ph<8, CHK>(a);
+    if (ft <= 12) return launch_ph<12, CHK>(a);
+    if (ft == 13) return launch_ph<13, CHK>(a);
+    return launch_ph<16, CHK>(a);
+}
+}  // namespace
+
+bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B, const GbtRows &dst) {
+    if (bits != 8 || F > 16 || B > 256) return false;
+    if (dst.stride_bits != 32 * (int64_t)((F + 3) / 4)) return false;
+    const size_t lds = ((size_t)F * padded_bins(B) + 256) * 12;
+    const size_t cap = ctx->hist_lds_kb > 0 ? (size_t)ctx->hist_lds_kb * 1024 : ctx->lds_per_block;
+    return lds <= cap && lds <= ctx->lds_per_block;
+}
+int gbt_part_hist_tile() { return kPHTile; }
+
+hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const GbtRows &src, const GbtRows &dst, int F, int B, uint32_t missing,
+                                const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                                unsigned long long *cursor, int64_t *hist_pool) {
+    if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
+    hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, n_jobs);
+    if (e != hipSuccess) return e;
+    const int Bp = padded_bins(B);
+    const PHArgs a{ctx->stream, n_spans, ((size_t)F * Bp + 256) * 12, src.sym, src.stride_bits, src.n_words, dst.sym_rw,
+                   F, B, Bp, missing, (const int2 *)src.gq, (int2 *)dst.gq_rw, jobs, n_jobs, rows_per_span, cursor,
+                   hist_pool};
+    const bool chk = missing < 256u || B < 256;
+    return chk ? pick_ph<true>(F, a) : pick_ph<false>(F, a);
 }

@@ -167,7 +167,8 @@ __global__ __launch_bounds__(kBlock) void part_move_kernel(
     uint32_t *__restrict__ dst_sym, int SW, int row_bits, const int2 *__restrict__ src_gq,
     int2 *__restrict__ dst_gq, const uint32_t *__restrict__ src_id, uint32_t *__restrict__ dst_id,
     const PartJob *__restrict__ jobs, int n_jobs, const uint64_t *__restrict__ masks,
-    const uint32_t *__restrict__ tile_left_off, const uint32_t *__restrict__ n_left, int slice_words) {
+    const uint32_t *__restrict__ tile_left_off, const uint32_t *__restrict__ n_left, int slice_words,
+    bool vec_rows) {
     const uint32_t tile = blockIdx.x;
     const int ji = find_job(jobs, n_jobs, tile);
     const PartJob job = jobs[ji];
@@ -220,8 +221,8 @@ __global__ __launch_bounds__(kBlock) void part_move_kernel(
     const uint32_t tail_bits = (uint32_t)(row_bits - 32 * (SW - 1));   // valid bits of a row's last word, 1..32
     const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
     const uint64_t p0 = (uint64_t)job.seg_begin + base;
-    if (SW == 4 && src_stride_bits == 128) {
-        // 16-byte rows on both sides (both buffers are 256-byte aligned): one 128-bit load and store per row
+    if (vec_rows) {
+        // 16-byte rows on both sides, both bases 16-byte aligned: one 128-bit load and store per row
         const uint4 *s4 = (const uint4 *)src_sym;
         uint4 *d4 = (uint4 *)dst_sym;
         for (uint32_t in_tile = threadIdx.x; in_tile < tile_rows; in_tile += kBlock)
@@ -325,7 +326,7 @@ __device__ inline uint32_t pick_word(const uint4 &v, int k) { return k == 0 ? v.
 // (by the workgroup that has just read them for the flags) by sub-wave lane groups.
 template <bool REG>
 __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
-    const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words,
+    const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words, bool aligned_src,
     uint32_t *__restrict__ dst_sym, int SW, int row_bits, int bits, uint32_t missing,
     const int2 *__restrict__ src_gq, int2 *__restrict__ dst_gq, const PartJob *__restrict__ jobs, int n_jobs,
     unsigned long long *__restrict__ cursor) {
@@ -358,7 +359,7 @@ __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
             uint32_t sy;
             if (REG) {
                 uint4 v;
-                if (src_stride_bits == 128) {
+                if (aligned_src) {   // 16-byte rows on a 16-byte aligned base
                     v = ((const uint4 *)src_sym)[p];
                 } else {
                     const uint64_t sb = p * (uint64_t)src_stride_bits;
@@ -491,7 +492,8 @@ hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const
     dim3 grid((unsigned)total_tiles, (unsigned)((SW + slice_words - 1) / slice_words));
     part_move_kernel<<<grid, kBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw, SW, row_bits,
                                              (const int2 *)src.gq, (int2 *)dst.gq_rw, src.id, dst.id_rw, jobs,
-                                             n_jobs, masks, tile_left, n_left_out, slice_words);
+                                             n_jobs, masks, tile_left, n_left_out, slice_words,
+                                             SW == 4 && src.stride_bits == 128 && ((uintptr_t)src.sym & 15u) == 0);
     return hipGetLastError();
 }
 
@@ -505,13 +507,16 @@ hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const G
     hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)cursor, 0, n_jobs);
     if (e != hipSuccess) return e;
     const int SW = (int)(dst.stride_bits >> 5);
+    const bool aligned_src = src.stride_bits == 128 && ((uintptr_t)src.sym & 15u) == 0;
     if (SW == 4 && src.stride_bits <= 128)
-        part_fused_kernel<true><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw, SW,
-                                                                row_bits, bits, missing, (const int2 *)src.gq,
-                                                                (int2 *)dst.gq_rw, jobs, n_jobs, cursor);
+        part_fused_kernel<true><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, aligned_src,
+                                                                dst.sym_rw, SW, row_bits, bits, missing,
+                                                                (const int2 *)src.gq, (int2 *)dst.gq_rw, jobs, n_jobs,
+                                                                cursor);
     else
-        part_fused_kernel<false><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw,
-                                                                 SW, row_bits, bits, missing, (const int2 *)src.gq,
-                                                                 (int2 *)dst.gq_rw, jobs, n_jobs, cursor);
+        part_fused_kernel<false><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, false,
+                                                                 dst.sym_rw, SW, row_bits, bits, missing,
+                                                                 (const int2 *)src.gq, (int2 *)dst.gq_rw, jobs, n_jobs,
+                                                                 cursor);
     return hipGetLastError();
 }

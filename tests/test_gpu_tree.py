@@ -154,6 +154,28 @@ def test_three_launch_partition_path(ctx_env, oracle, cfg, n, kw):
     grow_and_judge(c, oracle, o, gdev, gp, p, n, F)
 
 
+@pytest.mark.parametrize("F,B,miss", [(1, 256, 0.0), (3, 256, 0.0), (4, 256, 0.0), (7, 256, 0.0), (8, 200, 0.1),
+                                      (11, 256, 0.0), (12, 128, 0.3), (13, 256, 0.0), (14, 255, 0.05),
+                                      (16, 256, 0.0)])
+def test_byte_symbols_up_to_16_features(ctx, oracle, F, B, miss):
+    """8-bit rows of one to four words: without row ids the partition pass also builds one child's
+    histogram; the trees must equal the tracked ones (separate kernels) and the oracle's."""
+    n = 70_001
+    d = synth.make(4, n)
+    rng = np.random.default_rng(1000 * F + B)
+    X = d["X"][:, rng.integers(0, d["X"].shape[1], F)].copy()
+    X += rng.normal(0, 0.01, X.shape).astype(np.float32)      # columns drawn twice differ a little
+    if miss > 0:
+        X[rng.random(X.shape) < miss] = np.nan
+    p = dict(d["params"], max_bins=B, max_depth=6)
+    dd = dict(X=X, params=p)
+    _say(f"byte symbols F={F} B={B} missing={miss}")
+    o, gdev = gpu_prep(ctx, oracle, dd)
+    assert gdev["bits"] == 8
+    gp = oracle.gradients(p["objective"], np.zeros(n, np.float32), d["y"])
+    grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
+
+
 def test_depth_zero_and_gamma(ctx, oracle):
     d = synth.make(1)
     p = dict(d["params"])
