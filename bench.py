@@ -211,14 +211,24 @@ def main():
                 "traffic": None, "kernel": kernel, "launches": launches,
                 "avg_launch_ms": ms_ / max(launches, 1), "algorithmic_bytes_per_launch": by / max(launches, 1)}
 
-    hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_generic_kernel"
-    roofline = roof(["hist_root", "hist_node"], hist_kernel)
+    # which kernels the classes of the library's profile stand for on this shape
+    path = ctx.grow_tree_path(F, bits, p["max_bins"], track_rows=False)
+    hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_static_kernel"
+    node_kernel = "part_hist_kernel (partition + one child's histogram in one pass)" if path == 2 else hist_kernel
+    part_kernel = ("part_flag_kernel + part_scan_kernel (row counts of the last level)" if path == 2 else
+                   "part_fused_kernel" if path == 1 else "part_flag_kernel + part_scan_kernel + part_move_kernel")
     roofline_root = roof(["hist_root"], hist_kernel)
-    roofline_partition = roof(["partition"], "part_flag_kernel + part_scan_kernel + part_move_kernel")
+    roofline_node = roof(["hist_node"], node_kernel)
+    roofline_partition = roof(["partition"], part_kernel)
     traffic = measured_traffic(a.config)
-    if roofline and traffic:
-        roofline["traffic"] = traffic.get("hist_all_launches_avg_bytes")
-        roofline_root["traffic"] = traffic.get("hist_root_launch_bytes")
+    if traffic:
+        for obj, key in ((roofline_root, "hist_root_launch_bytes"), (roofline_node, "hist_node_launch_avg_bytes"),
+                         (roofline_partition, "partition_launch_avg_bytes")):
+            if obj:
+                obj["traffic"] = traffic.get(key)
+    # the top-level roofline is the kernel class the step spends most of its time in
+    roofline = max((r for r in (roofline_root, roofline_node, roofline_partition) if r),
+                   key=lambda r: r["avg_launch_ms"] * r["launches"], default=None)
     root_ms = prof["hist_root"]["ms"] / max(prof["hist_root"]["launches"], 1)
 
     out = {
@@ -238,8 +248,10 @@ def main():
         "hist_root_ms": root_ms,
         "hist_root_rows_features_per_s": (n * F / (root_ms * 1e-3)) if root_ms > 0 else None,
         "roofline": roofline,
-        "roofline_root": roofline_root,
+        "roofline_hist_root": roofline_root,
+        "roofline_hist_node": roofline_node,
         "roofline_partition": roofline_partition,
+        "grow_tree_path": path,
         "device_ms_per_step": {k: v["ms"] / a.steps for k, v in prof.items()},
         "preprocess_ms": {"quantise": t_quant * 1e3, "compress": t_comp * 1e3, "h2d_raw_matrix": t_h2d * 1e3},
     }

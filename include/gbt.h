@@ -255,6 +255,17 @@ GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits,
  *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL)
  * Synchronises the stream.
  */
+/*
+ * How gbt_grow_tree moves the rows of splitting nodes for this shape (for
+ * profiling and tests; the result of gbt_grow_tree does not depend on it):
+ *   0  three launches per level (flags, offsets, move), row order kept
+ *   1  one launch per level, row order not kept (only when track_rows == 0)
+ *   2  as 1, and the launch also builds one child's histogram of every split
+ *      node (8-bit symbols, at most 16 features)
+ * Negative: a GBT_E* code.
+ */
+GBT_API int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_t max_bins, int32_t track_rows);
+
 GBT_API int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                       int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
                       const gbt_params *params, gbt_tree *tree_out, uint32_t *row_idx_out,

@@ -25,7 +25,7 @@ SYMBOLS = [
     "gbt_quantise_workspace_bytes", "gbt_quantise", "gbt_bits", "gbt_packed_words", "gbt_compress",
     "gbt_gradients", "gbt_gpair_fixed", "gbt_sum_gpair", "gbt_build_hist", "gbt_hist_subtract",
     "gbt_hist_export_f64", "gbt_eval_split", "gbt_partition_workspace_bytes", "gbt_partition",
-    "gbt_grow_tree_workspace_bytes", "gbt_grow_tree", "gbt_predict_workspace_bytes", "gbt_predict",
+    "gbt_grow_tree_workspace_bytes", "gbt_grow_tree_path", "gbt_grow_tree", "gbt_predict_workspace_bytes", "gbt_predict",
     "gbt_profile_enable", "gbt_profile_read",
 ]
 
@@ -92,6 +92,8 @@ def load():
     L.gbt_quantise_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.c_int32]
     L.gbt_partition_workspace_bytes.argtypes = [C.c_int64]
     L.gbt_grow_tree_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    L.gbt_grow_tree_path.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    L.gbt_grow_tree_path.restype = C.c_int32
     L.gbt_predict_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
     vp, i32, i64, u32, f64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_double, C.c_size_t
     L.gbt_quantise.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, sz]
@@ -334,6 +336,13 @@ class Context:
                                            _ptr(ws), ws.numel()))
         t["n_nodes"] = int(ts.n_nodes)
         return t, row_idx, leaf
+
+    def grow_tree_path(self, F, bits, max_bins, track_rows=True):
+        """0: three-launch partition, 1: one-launch partition, 2: partition + histogram in one launch."""
+        r = self.lib.gbt_grow_tree_path(self.h, F, bits, max_bins, 1 if track_rows else 0)
+        if r < 0:
+            self._check(r)
+        return r
 
     # -- Sec. 2.4 ------------------------------------------------------------
     def predict(self, trees, margin, eta: float, *, packed=None, bits=0, missing_sym=0, X=None, n=None, F=None):

@@ -172,6 +172,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (const char *e3 = getenv("GBT_TUNE_HIST_RUNTIME_BITS")) c->hist_runtime_bits = atoi(e3) != 0;
         c->part_fused = 1;
         c->part_hist = 1;
+        c->hist_fix = 1;
+        if (const char *e10 = getenv("GBT_TUNE_HIST_FIX")) c->hist_fix = atoi(e10) != 0;
         if (const char *e8 = getenv("GBT_TUNE_PART_HIST")) c->part_hist = atoi(e8) != 0;
         if (const char *e6 = getenv("GBT_TUNE_PART_FUSED")) c->part_fused = atoi(e6) != 0;
         if (const char *e5 = getenv("GBT_TUNE_HIST_LDS_KB")) { int v = atoi(e5); if (v >= 8 && v <= 128) c->hist_lds_kb = v; }
@@ -307,8 +309,8 @@ extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *m
 }
 
 // ------------------------------------------------------- fixed-point gpair --
-static int32_t gpair_fixed_impl(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq, double *scale,
-                                void *ws, int64_t *sums_dev /* may be NULL */) {
+// The scales alone (one pass for the largest |g| and h; synchronises).
+static int32_t gpair_scale_impl(gbt_ctx *ctx, const float *gpair, int64_t n, double *scale, void *ws) {
     GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
     GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 12, hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
@@ -322,6 +324,13 @@ static int32_t gpair_fixed_impl(gbt_ctx *ctx, const float *gpair, int64_t n, int
     memcpy(&mh, &bits2[1], 4);
     scale[0] = fixed_scale(mg, kGBits);
     scale[1] = fixed_scale(mh, kHBits);
+    return GBT_OK;
+}
+
+static int32_t gpair_fixed_impl(gbt_ctx *ctx, const float *gpair, int64_t n, int32_t *gq, double *scale,
+                                void *ws, int64_t *sums_dev /* may be NULL */) {
+    int32_t st = gpair_scale_impl(ctx, gpair, n, scale, ws);
+    if (st != GBT_OK) return st;
     GBT_HIP(ctx, gbt_launch_to_fixed(ctx->stream, gpair, n, scale[0], scale[1], gq, sums_dev));
     return GBT_OK;
 }
@@ -354,9 +363,16 @@ extern "C" int32_t gbt_sum_gpair(gbt_ctx *ctx, const int32_t *gq, const uint32_t
 // --------------------------------------------------------------- histogram --
 // Enqueues the histogram of one row range split uniformly into jobs that the
 // kernel derives from its block index (no job table).
+struct RootFix {   // the root histogram converts the fp32 pairs itself (gbt_launch_hist_fix)
+    const float *gpair;
+    double sg, sh;
+    int32_t *gq_out;
+    int64_t *sums_dev;
+};
 static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
-                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs /* may be NULL */);
+                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs /* may be NULL */,
+                            const RootFix *fix = nullptr);
 
 extern "C" int32_t gbt_build_hist(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                                   int32_t B, int32_t missing_sym, const uint32_t *row_idx,
@@ -491,7 +507,7 @@ extern "C" int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t b
 // ------------------------------------------------------------ histogram job --
 static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
-                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs) {
+                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs, const RootFix *fix) {
     HistPlan pl;
     GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, &pl), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins (%d bytes) exceed the LDS budget", B, B * 16);
@@ -512,9 +528,14 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
         dev_jobs = (HistJob *)slot;
     }
     gbt_prof_begin(ctx, row_idx ? GBT_PROF_HIST_NODE : GBT_PROF_HIST_ROOT,
-                   (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0)));
-    GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
-                                 (uint32_t)missing_sym, row_idx, gq, hist_out, dev_jobs, (int)jobs.size(), pl.ft));
+                   (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0) + (fix ? 8.0 : 0.0)));
+    if (fix)
+        GBT_HIP(ctx, gbt_launch_hist_fix(ctx, packed, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
+                                         (uint32_t)missing_sym, fix->gpair, fix->sg, fix->sh, fix->gq_out,
+                                         fix->sums_dev, hist_out, dev_jobs, (int)jobs.size(), pl.ft));
+    else
+        GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
+                                     (uint32_t)missing_sym, row_idx, gq, hist_out, dev_jobs, (int)jobs.size(), pl.ft));
     gbt_prof_end(ctx);
     return GBT_OK;
 }
@@ -568,6 +589,30 @@ extern "C" size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bi
     if (n < 0 || F < 1 || bits < 1 || bits > GBT_MAX_BITS || max_bins < 2 || max_depth < 0 || max_depth > kMaxDepth)
         return 0;
     return grow_layout(n, F, bits, max_bins, max_depth).total;
+}
+
+namespace {
+// the working copies' row stride for a shape (rows start on 32-bit word boundaries)
+GbtRows working_rows_shape(int F, int bits) {
+    GbtRows r{};
+    r.stride_bits = 32 * (((int64_t)F * bits + 31) / 32);
+    return r;
+}
+int grow_path(const gbt_ctx *ctx, int F, int bits, int B, bool tracked, int n_ftiles) {
+    const GbtRows w = working_rows_shape(F, bits);
+    if (tracked || !ctx->part_fused || !gbt_partition_fused_ok(w)) return 0;
+    if (ctx->part_hist && n_ftiles == 1 && gbt_part_hist_ok(ctx, bits, F, B, w)) return 2;
+    return 1;
+}
+}  // namespace
+
+extern "C" int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_t max_bins, int32_t track_rows) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, F >= 1 && bits >= 1 && bits <= GBT_MAX_BITS && max_bins >= 2, GBT_EINVAL, "bad shape");
+    HistPlan pl;
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, max_bins, &pl), GBT_EUNSUPPORTED,
+                "max_bins = %d: one feature's bins exceed the LDS budget", max_bins);
+    return grow_path(ctx, F, bits, max_bins, track_rows != 0, pl.n_ftiles);
 }
 
 extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
@@ -635,20 +680,29 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     std::vector<float> hcuts((size_t)F * (B - 1));
     GBT_HIP(ctx, hipMemcpyAsync(hcuts.data(), cuts, hcuts.size() * sizeof(float), hipMemcpyDeviceToHost, s));
 
+    // Fixed-point gradient pairs and the root's totals: the scales need one pass over the pairs;
+    // the conversion is a pass of its own, or part of the root histogram kernel where that can do it.
     double scale[2];
-    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 24.0);
-    st = gpair_fixed_impl(ctx, gpair, n, gq, scale, ws + L.scratch, (int64_t *)(ws + L.scratch + 256));
+    int64_t *sums_dev = (int64_t *)(ws + L.scratch + 256);
+    const bool fix_in_hist = ctx->hist_fix && max_depth > 0 && gbt_hist_fix_ok(bits, row_bits, pl.ft, pl.n_ftiles);
+    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (fix_in_hist ? 8.0 : 24.0));
+    st = gpair_scale_impl(ctx, gpair, n, scale, ws + L.scratch);
+    if (st == GBT_OK && !fix_in_hist) {
+        hipError_t e = gbt_launch_to_fixed(s, gpair, n, scale[0], scale[1], gq, sums_dev);
+        if (e != hipSuccess) st = gbt_fail(ctx, GBT_EHIP, "gbt_launch_to_fixed: %s", hipGetErrorString(e));
+    }
     gbt_prof_end(ctx);
     if (st != GBT_OK) return st;
     const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
     const double lambda = params->lambda;
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.scratch + 256, 16, hipMemcpyDeviceToHost, s));
     if (max_depth > 0) {
+        const RootFix fix{gpair, scale[0], scale[1], gq, sums_dev};
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
-                          (HistJob *)(ws + L.jobs));
+                          (HistJob *)(ws + L.jobs), fix_in_hist ? &fix : nullptr);
         if (st != GBT_OK) return st;
     }
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), sums_dev, 16, hipMemcpyDeviceToHost, s));
     GBT_SYNC(ctx);
     int64_t root_sums[2];
     memcpy(root_sums, rb(ctx), 16);
@@ -667,6 +721,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         tree->n_rows[nd.id] = nd.len;
     };
 
+    const int path = grow_path(ctx, F, bits, B, tracked, pl.n_ftiles);
     std::vector<HNode> level, next;
     std::vector<LeafSeg> leaves;
     HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1]};
@@ -710,8 +765,8 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         // just the row counts when ids are not tracked.
         const int wnext = wcur == 0 ? 1 : 0;
         const bool children_need_hist = depth + 1 < max_depth;
-        const bool fused = children_need_hist && !tracked && ctx->part_fused && gbt_partition_fused_ok(W[wnext]);
-        const bool with_hist = fused && ctx->part_hist && pl.n_ftiles == 1 && gbt_part_hist_ok(ctx, bits, F, B, W[wnext]);
+        const bool fused = children_need_hist && path >= 1;
+        const bool with_hist = children_need_hist && path == 2;
         split_of.clear();
         double part_rows = 0;
         for (size_t i = 0; i < level.size(); ++i) {
@@ -773,7 +828,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         }
         const int what = children_need_hist ? GBT_PART_RECORDS : tracked ? GBT_PART_IDS : GBT_PART_COUNT;
         const double rec_bytes = row_bits / 8.0 + 8.0;
-        gbt_prof_begin(ctx, GBT_PROF_PARTITION,
+        gbt_prof_begin(ctx, with_hist ? GBT_PROF_HIST_NODE : GBT_PROF_PARTITION,
                        part_rows * (fused ? 2.0 * rec_bytes
                                     : what == GBT_PART_RECORDS ? row_bits / 8.0 + 2.0 * (rec_bytes + 4.0)
                                     : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0

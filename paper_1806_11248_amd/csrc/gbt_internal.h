@@ -26,6 +26,7 @@ struct gbt_ctx {
     int hist_block;         // threads per histogram workgroup
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
     int part_fused;         // 1: one-launch record partition where it applies
+    int hist_fix;           // 1: the root histogram kernel also converts the gradient pairs where that applies
     int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
@@ -173,6 +174,13 @@ int gbt_partition_fused_tile();
 hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
                                       uint32_t missing, const PartJob *jobs, int n_jobs, int total_tiles,
                                       unsigned long long *cursor);
+// The root histogram straight from the fp32 gradient pairs (8-bit symbols, one feature tile of at
+// most 16 features, jobs that cover rows [0, n) exactly once: gbt_hist_fix_ok): rounds each pair to
+// fixed point with the given scales, stores it to gq_out and adds the totals into sums_out[2].
+bool gbt_hist_fix_ok(int bits, int64_t stride_bits, int max_ft, int n_ftiles);
+hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t stride_bits, int64_t n_words, int64_t n,
+                               int B, uint32_t missing, const float *gpair, double sg, double sh, int32_t *gq_out,
+                               int64_t *sums_out, int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft);
 // Partition and the histogram of one child of every job in one pass (8-bit symbols, at most 16
 // features, the bins of all features in one LDS tile: gbt_part_hist_ok).  Rows are moved as by
 // gbt_launch_partition_fused (no ids, order inside a child not kept).  PartJob.tile_begin /

@@ -151,6 +151,10 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
 //         otherwise the tile has at most NS <= 16 features (slots past the last
 //         feature fall into the trash row)
 //   CHK : a symbol may be the missing symbol, or >= B (B < 256)
+//   FIX : (the root of a tree: every row is visited by exactly one workgroup) the
+//         gradient pairs are still fp32: the kernel rounds them to fixed point
+//         itself, stores them for the later levels and adds up the root's totals,
+//         which saves the separate conversion pass over all rows
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long long old,
                                          unsigned long long addv, uint32_t hq) {
@@ -170,11 +174,18 @@ __device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long 
     }
 }
 
-template <bool LIST, int NS, bool CHK>
+struct FixArgs {   // FIX only
+    const float2 *gpair;
+    double sg, sh;
+    int2 *gq_out;
+    int64_t *sums;   // [2], cleared by the launcher
+};
+
+template <bool LIST, int NS, bool CHK, bool FIX>
 __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
     const uint32_t *__restrict__ packed, int64_t n_words, int64_t stride_bytes, int64_t n, int B, int Bp,
     uint32_t missing, const uint32_t *__restrict__ row_idx, const int2 *__restrict__ gq,
-    int64_t *__restrict__ pool, const HistJob *__restrict__ jobs) {
+    int64_t *__restrict__ pool, const HistJob *__restrict__ jobs, FixArgs fix) {
     extern __shared__ unsigned long long lds[];
     const HistJob job = jobs[blockIdx.x];
     const int ft = (int)job.ft;
@@ -190,6 +201,8 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
 
     constexpr bool SINGLE = NS != 0;
     constexpr int SLOTS = SINGLE ? NS : 16;
+    static_assert(!FIX || (SINGLE && !LIST), "the conversion needs every row visited once, in matrix order");
+    int64_t sum_g = 0, sum_h = 0;              // FIX: this thread's share of the root's totals
     const int lane = threadIdx.x & 63;
     const int nchunks = (ft + 15) >> 4;        // 16-byte windows per row slice (same for every lane)
     // SINGLE: slot j of this lane handles feature (j + lane) mod ft
@@ -218,7 +231,17 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
         const uint64_t pos_in = (uint64_t)job.row_begin + i;
         const uint64_t r = LIST ? (uint64_t)row_idx[pos_in] : pos_in;
         if (r >= (uint64_t)n) continue;
-        const int2 q = gq[r];
+        int2 q;
+        if (FIX) {
+            const float2 v = fix.gpair[r];
+            q.x = __double2int_rn((double)v.x * fix.sg);
+            q.y = __double2int_rn((double)v.y * fix.sh);
+            fix.gq_out[r] = q;
+            sum_g += q.x;
+            sum_h += q.y;
+        } else {
+            q = gq[r];
+        }
         const unsigned long long addv = pack_pair(q);
         const uint32_t hq = (uint32_t)q.y;
         const uint64_t byte0 = r * (uint64_t)stride_bytes + job.f0;
@@ -265,6 +288,28 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
     }
     __syncthreads();
     flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
+    if (FIX) {   // one pair of global atomics per workgroup
+        __shared__ int64_t red[2][kHistBlock / 64];
+        for (int o = 32; o > 0; o >>= 1) {
+            sum_g += (int64_t)(((uint64_t)(uint32_t)__shfl_xor((int)(sum_g >> 32), o) << 32) |
+                               (uint32_t)__shfl_xor((int)(sum_g & 0xffffffff), o));
+            sum_h += (int64_t)(((uint64_t)(uint32_t)__shfl_xor((int)(sum_h >> 32), o) << 32) |
+                               (uint32_t)__shfl_xor((int)(sum_h & 0xffffffff), o));
+        }
+        if (lane == 0) {
+            red[0][threadIdx.x >> 6] = sum_g;
+            red[1][threadIdx.x >> 6] = sum_h;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < (int)(blockDim.x >> 6); ++w) {
+                sum_g += red[0][w];
+                sum_h += red[1][w];
+            }
+            atomicAdd((unsigned long long *)&fix.sums[0], (unsigned long long)sum_g);
+            atomicAdd((unsigned long long *)&fix.sums[1], (unsigned long long)sum_h);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -614,29 +659,34 @@ struct B8Args {
     const int2 *gq;
     int64_t *pool;
     const HistJob *jobs;
+    FixArgs fix;
 };
-template <bool LIST, int NS, bool CHK>
+template <bool LIST, int NS, bool CHK, bool FIX>
 hipError_t launch_b8(const B8Args &a) {
     static size_t configured = 0;
     if (a.lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)hist_b8_kernel<LIST, NS, CHK>,
+        hipError_t e = hipFuncSetAttribute((const void *)hist_b8_kernel<LIST, NS, CHK, FIX>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
         configured = a.lds;
     }
-    hist_b8_kernel<LIST, NS, CHK><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bytes, a.n, a.B,
-                                                                         a.Bp, a.missing, a.row_idx, a.gq, a.pool,
-                                                                         a.jobs);
+    hist_b8_kernel<LIST, NS, CHK, FIX><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bytes, a.n,
+                                                                              a.B, a.Bp, a.missing, a.row_idx, a.gq,
+                                                                              a.pool, a.jobs, a.fix);
     return hipGetLastError();
+}
+template <bool LIST, bool CHK, bool FIX>
+hipError_t pick_slots_single(int max_ft, const B8Args &a) {
+    if (max_ft <= 4) return launch_b8<LIST, 4, CHK, FIX>(a);
+    if (max_ft <= 8) return launch_b8<LIST, 8, CHK, FIX>(a);
+    if (max_ft <= 12) return launch_b8<LIST, 12, CHK, FIX>(a);
+    if (max_ft == 13) return launch_b8<LIST, 13, CHK, FIX>(a);
+    return launch_b8<LIST, 16, CHK, FIX>(a);
 }
 template <bool LIST, bool CHK>
 hipError_t pick_slots(int max_ft, const B8Args &a) {
-    if (max_ft > 16) return launch_b8<LIST, 0, CHK>(a);
-    if (max_ft <= 4) return launch_b8<LIST, 4, CHK>(a);
-    if (max_ft <= 8) return launch_b8<LIST, 8, CHK>(a);
-    if (max_ft <= 12) return launch_b8<LIST, 12, CHK>(a);
-    if (max_ft == 13) return launch_b8<LIST, 13, CHK>(a);
-    return launch_b8<LIST, 16, CHK>(a);
+    if (max_ft > 16) return launch_b8<LIST, 0, CHK, false>(a);
+    return pick_slots_single<LIST, CHK, false>(max_ft, a);
 }
 template <int BITS, bool LIST>
 hipError_t launch_static(const B8Args &a, int64_t stride_bits) {
@@ -700,17 +750,35 @@ hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64
     hipStream_t s = ctx->stream;
     if (bits == 8 && (stride_bits & 7) == 0) {
         const bool chk = missing < 256u || B < 256;
-        const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing, row_idx, g2, hist_pool, jobs};
+        const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing, row_idx, g2, hist_pool, jobs, FixArgs{}};
         if (row_idx) return chk ? pick_slots<true, true>(max_ft, a) : pick_slots<true, false>(max_ft, a);
         return chk ? pick_slots<false, true>(max_ft, a) : pick_slots<false, false>(max_ft, a);
     }
     if (!ctx->hist_runtime_bits && bits != 8) {
-        const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, 0, n, B, Bp, missing, row_idx, g2, hist_pool, jobs};
+        const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, 0, n, B, Bp, missing, row_idx, g2, hist_pool, jobs, FixArgs{}};
         return row_idx ? pick_static<true>(bits, a, stride_bits) : pick_static<false>(bits, a, stride_bits);
     }
     if (row_idx)
         return launch_generic<true>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
     return launch_generic<false>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
+}
+
+bool gbt_hist_fix_ok(int bits, int64_t stride_bits, int max_ft, int n_ftiles) {
+    return bits == 8 && (stride_bits & 7) == 0 && n_ftiles == 1 && max_ft <= 16;
+}
+
+hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t stride_bits, int64_t n_words, int64_t n,
+                               int B, uint32_t missing, const float *gpair, double sg, double sh, int32_t *gq_out,
+                               int64_t *sums_out, int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft) {
+    hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)sums_out, 0, 2);
+    if (e != hipSuccess || n_jobs <= 0) return e;
+    const int Bp = padded_bins(B);
+    const size_t lds = ((size_t)max_ft * Bp + 256) * 12;
+    const B8Args a{ctx->stream, n_jobs, ctx->hist_block, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing,
+                   nullptr, nullptr, hist_pool, jobs,
+                   FixArgs{(const float2 *)gpair, sg, sh, (int2 *)gq_out, sums_out}};
+    const bool chk = missing < 256u || B < 256;
+    return chk ? pick_slots_single<false, true, true>(max_ft, a) : pick_slots_single<false, false, true>(max_ft, a);
 }
 
 // ---- partition + histogram in one pass --------------------------------------

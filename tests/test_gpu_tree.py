@@ -143,7 +143,7 @@ def ctx_env(monkeypatch):
 def test_three_launch_partition_path(ctx_env, oracle, cfg, n, kw):
     """Without row ids the record partition normally takes its one-launch form; switched off, the
     flag / scan / move form (the one tracked rows and wide rows always take) must grow the same trees."""
-    c = ctx_env(GBT_TUNE_PART_FUSED=0)
+    c = ctx_env(GBT_TUNE_PART_FUSED=0, GBT_TUNE_HIST_FIX=0)   # and the separate fixed-point conversion pass
     d = synth.make(cfg, n, **kw)
     p = d["params"]
     n, F = d["X"].shape
