@@ -450,6 +450,83 @@ __global__ __launch_bounds__(256) void predict_window_kernel(const char *ws, con
     }
 }
 
+// The same walk for 8-bit symbols (rows of at most 16 bytes, any byte alignment): a node is staged
+// as a v_perm selector that cuts its feature's byte out of one half of the row, so a step is two
+// permutes and a handful of compares.
+//   y = 0x0C0C0C00 | (feature & 7)                       (selector: byte -> bits 0..7, zeros above)
+//   x = left child id (20 bits) | bin << 20 | (feature >= 8) << 28 | default_left << 29
+// A leaf is staged as (own id, bin 255, feature 0, default left): every row stays on it.
+// MISS: the matrix has a missing symbol (it is < 256).
+template <bool MISS>
+__global__ __launch_bounds__(256) void predict_b8_kernel(const char *ws, const DevTree *trees, int n_trees,
+                                                         const uint32_t *packed, int64_t n_words, uint32_t missing,
+                                                         int64_t n, int F, double eta, float *margin,
+                                                         int rows_per_block, int max_nodes) {
+    extern __shared__ uint2 cnodes[];
+    double *lweight = (double *)(cnodes + max_nodes);
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+    for (int t = 0; t < n_trees; ++t) {
+        const DevTree T = trees[t];
+        __syncthreads();
+        for (int i = threadIdx.x; i < T.n_nodes; i += 256) {
+            const int32_t f = ((const int32_t *)(ws + T.feature))[i];
+            uint2 c;
+            if (f < 0) {
+                c.x = (uint32_t)i | (255u << 20) | (1u << 29);
+                c.y = 0x0C0C0C00u;
+            } else {
+                const int32_t bin = ((const int32_t *)(ws + T.bin))[i];   // a bin >= 255 admits every symbol
+                c.x = (uint32_t)((const int32_t *)(ws + T.left))[i] |
+                      ((uint32_t)(bin < 255 ? bin : 255) << 20) | ((uint32_t)((f >> 3) & 1) << 28) |
+                      (((const int32_t *)(ws + T.default_left))[i] ? (1u << 29) : 0u);
+                c.y = 0x0C0C0C00u | (uint32_t)(f & 7);
+            }
+            cnodes[i] = c;
+            lweight[i] = ((const double *)(ws + T.weight))[i];
+        }
+        __syncthreads();
+        const int depth = T.pad;
+        for (int64_t rb = r0 + threadIdx.x; rb < r1; rb += 256 * kPredRows) {
+            uint32_t W[kPredRows][4];
+            float m[kPredRows];
+#pragma unroll
+            for (int q = 0; q < kPredRows; ++q) {
+                const int64_t r = rb + 256 * q < r1 ? rb + 256 * q : r1 - 1;   // past the end: the last row again
+                const uint64_t byte0 = (uint64_t)r * (uint64_t)F;
+                const int64_t w0 = (int64_t)(byte0 >> 2);
+                const uint32_t a = (uint32_t)(byte0 & 3);
+                uint32_t w[5];
+#pragma unroll
+                for (int k = 0; k < 5; ++k) w[k] = packed[w0 + k < n_words ? w0 + k : n_words - 1];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) W[q][k] = __builtin_amdgcn_alignbyte(w[k + 1], w[k], a);
+                m[q] = margin[r];
+            }
+            uint32_t node[kPredRows];
+#pragma unroll
+            for (int q = 0; q < kPredRows; ++q) node[q] = 0;
+            for (int step = 0; step < depth; ++step) {
+#pragma unroll
+                for (int q = 0; q < kPredRows; ++q) {
+                    const uint2 c = cnodes[node[q]];
+                    const uint32_t lo = __builtin_amdgcn_perm(W[q][1], W[q][0], c.y);
+                    const uint32_t hi = __builtin_amdgcn_perm(W[q][3], W[q][2], c.y);
+                    const uint32_t sy = (c.x & (1u << 28)) ? hi : lo;
+                    bool go_left = sy <= ((c.x >> 20) & 0xffu);
+                    if (MISS) go_left = (sy == missing) ? (c.x & (1u << 29)) != 0 : go_left;
+                    node[q] = (c.x & 0xfffffu) + (go_left ? 0u : 1u);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kPredRows; ++q) {
+                const int64_t r = rb + 256 * q;
+                if (r < r1) margin[r] = (float)((double)m[q] + eta * lweight[node[q]]);
+            }
+        }
+    }
+}
+
 // Final row order and leaf ids: every position of [0, n) lies in exactly one
 // leaf segment; segments are sorted by seg_begin.
 // Each workgroup takes a chunk of positions; the search starts from the segment of the chunk's
@@ -587,6 +664,25 @@ hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *tree
                 configured_w = lds;
             }
             const int64_t n_words = (n * (int64_t)F * bits + 31) / 32 + 1;
+            if (bits == 8 && F <= 16 && max_nodes <= (1 << 20)) {   // node ids fit the 20-bit field
+                static size_t configured_b = 0;
+                if (lds > configured_b) {
+                    hipError_t e = hipFuncSetAttribute((const void *)predict_b8_kernel<true>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                    if (e == hipSuccess)
+                        e = hipFuncSetAttribute((const void *)predict_b8_kernel<false>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                    if (e != hipSuccess) return e;
+                    configured_b = lds;
+                }
+                if (missing < 256u)
+                    predict_b8_kernel<true><<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, missing,
+                                                                            n, F, eta, margin, rows_per_block, max_nodes);
+                else
+                    predict_b8_kernel<false><<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, missing,
+                                                                             n, F, eta, margin, rows_per_block, max_nodes);
+                return hipGetLastError();
+            }
             predict_window_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, bits, missing,
                                                                    n, F, eta, margin, rows_per_block, max_nodes);
             return hipGetLastError();
