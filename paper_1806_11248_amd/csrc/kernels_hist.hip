@@ -496,6 +496,8 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     for (uint32_t done = 0; done < span_rows; done += kPHTile, par ^= 1) {
         const uint32_t tile_rows = span_rows - done < (uint32_t)kPHTile ? span_rows - done : (uint32_t)kPHTile;
         const uint64_t p0 = (uint64_t)job.seg_begin + span_begin + done;
+        // every word an unaligned row load of this tile can touch lies inside the source buffer
+        const bool tile_inside = (int64_t)(((p0 + tile_rows) * (uint64_t)src_stride_bits) >> 5) + SW + 1 <= src_words;
         uint32_t row[kPHRows][SW];
         int2 pair[kPHRows];
         uint32_t takebits = 0;
@@ -524,8 +526,13 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
                     const int64_t s0 = (int64_t)(sb >> 5);
                     const uint32_t sh = (uint32_t)(sb & 31);
                     uint32_t x[SW + 1];
+                    if (tile_inside) {
 #pragma unroll
-                    for (int k = 0; k <= SW; ++k) x[k] = src_sym[s0 + k < src_words ? s0 + k : src_words - 1];
+                        for (int k = 0; k <= SW; ++k) x[k] = src_sym[s0 + k];
+                    } else {   // the matrix ends inside this tile's last window: read the last word instead
+#pragma unroll
+                        for (int k = 0; k <= SW; ++k) x[k] = src_sym[s0 + k < src_words ? s0 + k : src_words - 1];
+                    }
 #pragma unroll
                     for (int k = 0; k < SW; ++k) row[j][k] = __builtin_amdgcn_alignbit(x[k + 1], x[k], sh);
                     row[j][SW - 1] &= tail_mask;
