@@ -528,7 +528,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
         dev_jobs = (HistJob *)slot;
     }
     gbt_prof_begin(ctx, row_idx ? GBT_PROF_HIST_NODE : GBT_PROF_HIST_ROOT,
-                   (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0) + (fix ? 8.0 : 0.0)));
+                   (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0)));
     if (fix)
         GBT_HIP(ctx, gbt_launch_hist_fix(ctx, packed, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
                                          (uint32_t)missing_sym, fix->gpair, fix->sg, fix->sh, fix->gq_out,

@@ -117,6 +117,18 @@ def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True):
         assert np.array_equal(host_u32(row_idx), rep["row_idx"])
         assert np.array_equal(leaf.cpu().numpy(), rep["leaf_of_row"])
         del row_idx, leaf
+        # the launch configuration the benchmark times: no row order asked for (one-launch partition,
+        # with one child's histogram in the same pass where the shape allows) -- the same tree
+        t0 = time.time()
+        bare, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_t, params, want_rows=False)
+        torch.cuda.synchronize()
+        nn = tree["n_nodes"]
+        _say(f"  round {r}: same tree without row ids in {(time.time() - t0) * 1e3:.1f} ms "
+             f"(path {ctx.grow_tree_path(F, bits, B, track_rows=False)})")
+        assert bare["n_nodes"] == nn
+        for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
+                  "sumG", "sumH"):
+            assert np.array_equal(bare[k][:nn], tree[k][:nn]), k
         ctx.predict([tree], margin_gpu, p["eta"], packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
         margin_ref = oracle.predict_sym(tree, o_sym, o_missing, p["eta"], margin_ref)
         assert np.allclose(margin_gpu.cpu().numpy(), margin_ref, rtol=1e-5, atol=1e-6)
