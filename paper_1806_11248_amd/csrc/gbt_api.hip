@@ -555,7 +555,9 @@ GrowLayout grow_layout(int64_t n, int F, int bits, int B, int max_depth) {
     L.level_nodes = (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0);   // most nodes evaluated in one level
     L.tiles = n / GBT_PART_TILE + L.level_nodes + 1;
     L.sw = (int)(((int64_t)F * bits + 31) / 32);
-    L.w_words = n * L.sw + 4;
+    // the partition + histogram pass keeps symbols and gradient pair in one record per row
+    const int rw = (bits == 8 && F <= 16) ? gbt_part_hist_record_words(F) : 0;
+    L.w_words = n * std::max(L.sw, rw) + 4;
     size_t o = 0;
     L.gq = o;         o += gbt_align((size_t)n * 8);
     for (int k = 0; k < 2; ++k) {
@@ -601,7 +603,7 @@ GbtRows working_rows_shape(int F, int bits) {
 int grow_path(const gbt_ctx *ctx, int F, int bits, int B, bool tracked, int n_ftiles) {
     const GbtRows w = working_rows_shape(F, bits);
     if (tracked || !ctx->part_fused || !gbt_partition_fused_ok(w)) return 0;
-    if (ctx->part_hist && n_ftiles == 1 && gbt_part_hist_ok(ctx, bits, F, B, w)) return 2;
+    if (ctx->part_hist && n_ftiles == 1 && gbt_part_hist_ok(ctx, bits, F, B)) return 2;
     return 1;
 }
 }  // namespace
@@ -654,6 +656,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     // The rows in their current order.  Level 0 reads the caller's packed matrix; every
     // partition then moves whole records (symbols, gradient pair, id) into the other of two
     // word-aligned working copies, so that each node's rows stay contiguous.
+    const int path = grow_path(ctx, F, bits, B, tracked, pl.n_ftiles);
     GbtRows W[2];
     for (int k = 0; k < 2; ++k) {
         W[k].sym_rw = (uint32_t *)(ws + L.wsym[k]);
@@ -664,6 +667,11 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         W[k].id = W[k].id_rw;
         W[k].stride_bits = 32 * (int64_t)L.sw;
         W[k].n_words = L.w_words;
+        if (path == 2) {   // records: the pair travels inside the row (only symbols are read from outside)
+            W[k].stride_bits = 32 * (int64_t)gbt_part_hist_record_words(F);
+            W[k].gq = nullptr;
+            W[k].gq_rw = nullptr;
+        }
     }
     GbtRows cur;
     cur.sym = packed;
@@ -721,7 +729,6 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         tree->n_rows[nd.id] = nd.len;
     };
 
-    const int path = grow_path(ctx, F, bits, B, tracked, pl.n_ftiles);
     std::vector<HNode> level, next;
     std::vector<LeafSeg> leaves;
     HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1]};
@@ -834,9 +841,12 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                                     : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
                                                                : row_bits / 8.0));
         if (with_hist) {
-            GBT_HIP(ctx, gbt_launch_part_hist(ctx, cur, W[wnext], F, B, (uint32_t)missing_sym,
-                                              (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
-                                              part_tile, (unsigned long long *)(ws + L.state), pool));
+            // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
+            GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
+                                              wcur == 2 ? nullptr : W[wcur].sym, W[wnext].sym_rw, F, B,
+                                              (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
+                                              (int)pjobs.size(), (int)tile_cursor, part_tile,
+                                              (unsigned long long *)(ws + L.state), pool));
             GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
         } else if (fused) {
             GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,

@@ -182,13 +182,17 @@ hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t str
                                int B, uint32_t missing, const float *gpair, double sg, double sh, int32_t *gq_out,
                                int64_t *sums_out, int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft);
 // Partition and the histogram of one child of every job in one pass (8-bit symbols, at most 16
-// features, the bins of all features in one LDS tile: gbt_part_hist_ok).  Rows are moved as by
-// gbt_launch_partition_fused (no ids, order inside a child not kept).  PartJob.tile_begin /
-// n_tiles count spans of rows_per_span rows (a multiple of gbt_part_hist_tile()); PartJob.pad /
-// hist_off name the child to build, whose histogram must have been cleared.
-bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B, const GbtRows &dst);
+// features, the bins of all features in one LDS tile: gbt_part_hist_ok).  No ids, order inside a
+// child not kept.  Rows travel as records of gbt_part_hist_record_words(F) words (symbols, padding,
+// the fixed-point pair in the last 7 bytes); src_records == NULL: the source is the packed matrix
+// (rows of F bytes) with the pairs in gq.  PartJob.tile_begin / n_tiles count spans of rows_per_span
+// rows (a multiple of gbt_part_hist_tile()); PartJob.pad / hist_off name the child to build, whose
+// histogram must have been cleared.
+bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B);
 int gbt_part_hist_tile();
-hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const GbtRows &src, const GbtRows &dst, int F, int B, uint32_t missing,
+int gbt_part_hist_record_words(int F);
+hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
+                                const uint32_t *src_records, uint32_t *dst_records, int F, int B, uint32_t missing,
                                 const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
                                 unsigned long long *cursor, int64_t *hist_pool);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.

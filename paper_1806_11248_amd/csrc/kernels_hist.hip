@@ -417,6 +417,15 @@ __global__ __launch_bounds__(kHistBlock) void hist_static_kernel(
 // backwards; tiles land in the order their atomics arrive (see part_fused_kernel
 // for the same scheme without a histogram).
 //
+// Records.  The pass is bound by the bytes it moves, so a row travels as ONE record
+// of RW = ceil((NS + 7) / 4) words: the symbols from byte 0, zero padding, and in the
+// last 7 bytes the fixed-point pair as a 56-bit little-endian number
+// [ h : 24 bits | g : 28 bits, two's complement ] (|g| <= 2^26, 0 <= h <= 2^22).
+// 13 features: 20 bytes instead of a 16-byte padded row plus an 8-byte pair.  The
+// pair always sits in bytes 1..3 of word RW-2 and in word RW-1.
+// FIRST: the source is the caller's packed matrix (rows of `ft` bytes at any byte
+// alignment) with the pairs in their own array; otherwise records.
+//
 // PartJob: tile_begin / n_tiles count SPANS of `rows_per_span` rows here; pad is
 // the side to build (1 left, 0 right, 2 none), hist_off that child's histogram.
 // ---------------------------------------------------------------------------
@@ -426,6 +435,7 @@ constexpr int kPHTile = kPHBlock * kPHRows;      // 4096
 constexpr int kPHWords = kPHTile / 64;           // 64 ballot words
 static_assert(kPHWords == 64, "the ballot words are ranked by one wave");
 constexpr int kPHGroup = 7;                      // atomics of a row in flight together (registers for their results)
+constexpr int record_words(int ns) { return (ns + 7 + 3) / 4; }
 
 __device__ inline int find_span_job(const PartJob *jobs, int n_jobs, uint32_t span) {
     int lo = 0, hi = n_jobs;
@@ -436,13 +446,13 @@ __device__ inline int find_span_job(const PartJob *jobs, int n_jobs, uint32_t sp
     return lo;
 }
 
-template <int NS, bool CHK>
+template <int NS, bool CHK, bool FIRST>
 __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
-    const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words, bool aligned_src,
-    uint32_t *__restrict__ dst_sym, int ft, int B, int Bp, uint32_t missing, const int2 *__restrict__ src_gq,
-    int2 *__restrict__ dst_gq, const PartJob *__restrict__ jobs, int n_jobs, uint32_t rows_per_span,
-    unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
-    constexpr int SW = (NS + 3) / 4;   // 32-bit words per row
+    const uint32_t *__restrict__ src, int64_t src_stride_bytes, int64_t src_words, const int2 *__restrict__ src_gq,
+    uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs,
+    int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
+    constexpr int SW = (NS + 3) / 4;        // words that hold symbols
+    constexpr int RW = record_words(NS);    // words of a record
     extern __shared__ unsigned long long lds[];
     __shared__ uint64_t words[2][kPHWords];
     __shared__ uint32_t lefts_before[2][kPHWords];
@@ -486,8 +496,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     }
     const int fword = (int)(job.feature >> 2);              // the split feature's word and shift inside a row
     const uint32_t fshift = (job.feature & 3u) * 8u;
-    const int row_bits = ft * 8;
-    const uint32_t tail_bits = (uint32_t)(row_bits - 32 * (SW - 1));
+    const uint32_t tail_bits = (uint32_t)(ft * 8 - 32 * (SW - 1));   // valid bits of the last symbol word, 1..32
     const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
     const uint32_t seg_last = job.seg_begin + job.seg_len - 1u;
     __syncthreads();
@@ -496,10 +505,9 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     for (uint32_t done = 0; done < span_rows; done += kPHTile, par ^= 1) {
         const uint32_t tile_rows = span_rows - done < (uint32_t)kPHTile ? span_rows - done : (uint32_t)kPHTile;
         const uint64_t p0 = (uint64_t)job.seg_begin + span_begin + done;
-        // every word an unaligned row load of this tile can touch lies inside the source buffer
-        const bool tile_inside = (int64_t)(((p0 + tile_rows) * (uint64_t)src_stride_bits) >> 5) + SW + 1 <= src_words;
-        uint32_t row[kPHRows][SW];
-        int2 pair[kPHRows];
+        // FIRST: every word an unaligned row load of this tile can touch lies inside the source buffer
+        const bool tile_inside = (int64_t)(((p0 + tile_rows) * (uint64_t)src_stride_bytes) >> 2) + SW + 1 <= src_words;
+        uint32_t row[kPHRows][RW];
         uint32_t takebits = 0;
         // ---- load, decide
 #pragma unroll
@@ -509,35 +517,31 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
             bool left = false;
             if (in_tile < tile_rows) {
                 const uint64_t p = p0 + in_tile;
-                if (aligned_src) {
-                    const uint32_t *sp = src_sym + p * SW;
-                    if constexpr (SW == 4) {
-                        const uint4 v = *(const uint4 *)sp;
-                        row[j][0] = v.x; row[j][1] = v.y; row[j][2] = v.z; row[j][3] = v.w;
-                    } else if constexpr (SW == 2) {
-                        const uint2 v = *(const uint2 *)sp;
-                        row[j][0] = v.x; row[j][1] = v.y;
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < SW; ++k) row[j][k] = sp[k];
-                    }
-                } else {
-                    const uint64_t sb = p * (uint64_t)src_stride_bits;
-                    const int64_t s0 = (int64_t)(sb >> 5);
-                    const uint32_t sh = (uint32_t)(sb & 31);
+                if (FIRST) {
+                    const uint64_t sb = p * (uint64_t)src_stride_bytes;
+                    const int64_t s0 = (int64_t)(sb >> 2);
+                    const uint32_t sh = (uint32_t)(sb & 3);
                     uint32_t x[SW + 1];
                     if (tile_inside) {
 #pragma unroll
-                        for (int k = 0; k <= SW; ++k) x[k] = src_sym[s0 + k];
+                        for (int k = 0; k <= SW; ++k) x[k] = src[s0 + k];
                     } else {   // the matrix ends inside this tile's last window: read the last word instead
 #pragma unroll
-                        for (int k = 0; k <= SW; ++k) x[k] = src_sym[s0 + k < src_words ? s0 + k : src_words - 1];
+                        for (int k = 0; k <= SW; ++k) x[k] = src[s0 + k < src_words ? s0 + k : src_words - 1];
                     }
 #pragma unroll
-                    for (int k = 0; k < SW; ++k) row[j][k] = __builtin_amdgcn_alignbit(x[k + 1], x[k], sh);
+                    for (int k = 0; k < RW; ++k) row[j][k] = k < SW ? __builtin_amdgcn_alignbyte(x[k < SW ? k + 1 : 0], x[k < SW ? k : 0], sh) : 0u;
                     row[j][SW - 1] &= tail_mask;
+                    const int2 q = src_gq[p];
+                    const unsigned long long v56 = ((unsigned long long)(uint32_t)q.x & 0x0fffffffull) |
+                                                   ((unsigned long long)(uint32_t)q.y << 28);
+                    row[j][RW - 2] |= (uint32_t)(v56 << 8);          // bytes 1..3
+                    row[j][RW - 1] = (uint32_t)(v56 >> 24);
+                } else {
+                    const uint32_t *rp = src + p * RW;
+#pragma unroll
+                    for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
                 }
-                pair[j] = src_gq[p];
                 uint32_t fw = row[j][0];
 #pragma unroll
                 for (int k = 1; k < SW; ++k) fw = fword == k ? row[j][k] : fw;
@@ -569,11 +573,17 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
 #pragma unroll
         for (int j = 0; j < kPHRows; ++j) {
             if ((takebits >> j) & 1u) {
-                const unsigned long long addv = pack_pair(pair[j]);
-                const uint32_t hq = (uint32_t)pair[j].y;
+                // the pair: bytes 1..3 of word RW-2 and word RW-1
+                const uint32_t qlo = (row[j][RW - 2] >> 8) | (row[j][RW - 1] << 24);   // bits 0..31 of the 56
+                const uint32_t qhi = row[j][RW - 1] >> 8;                              // bits 32..55
+                int2 q;
+                q.x = (int32_t)(qlo << 4) >> 4;                                        // 28 bits, sign-extended
+                q.y = (int32_t)((qlo >> 28) | (qhi << 4));                             // 24 bits
+                const unsigned long long addv = pack_pair(q);
+                const uint32_t hq = (uint32_t)q.y;
                 uint32_t W[4], V[(NS + 3) / 4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) W[k] = k < SW ? row[j][k < SW ? k : 0] : 0u;   // words past the row are never selected
+                for (int k = 0; k < 4; ++k) W[k] = k < SW ? row[j][k < SW ? k : 0] : 0u;   // words past the symbols are never selected
 #pragma unroll
                 for (int k = 0; k < (NS + 3) / 4; ++k)
                     V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
@@ -620,16 +630,9 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
                     const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[par][w];
                     q = seg_last - (right_base + rights_before_word + ((uint32_t)lane - below));
                 }
-                uint32_t *dp = dst_sym + (uint64_t)q * SW;
-                if constexpr (SW == 4) {
-                    *(uint4 *)dp = make_uint4(row[j][0], row[j][1], row[j][2], row[j][3]);
-                } else if constexpr (SW == 2) {
-                    *(uint2 *)dp = make_uint2(row[j][0], row[j][1]);
-                } else {
+                uint32_t *dp = dst + (uint64_t)q * RW;
 #pragma unroll
-                    for (int k = 0; k < SW; ++k) dp[k] = row[j][k];
-                }
-                dst_gq[q] = pair[j];
+                for (int k = 0; k < RW; ++k) dp[k] = row[j][k];
             }
         }
         // words[par] is rewritten two tiles from now, after two more barriers: no third barrier needed
@@ -794,64 +797,65 @@ struct PHArgs {
     hipStream_t s;
     int n_spans;
     size_t lds;
-    const uint32_t *src_sym;
-    int64_t src_stride_bits, src_words;
-    uint32_t *dst_sym;
+    const uint32_t *src;
+    int64_t src_stride_bytes, src_words;
+    const int2 *src_gq;
+    uint32_t *dst;
     int ft, B, Bp;
     uint32_t missing;
-    const int2 *src_gq;
-    int2 *dst_gq;
     const PartJob *jobs;
     int n_jobs;
     uint32_t rows_per_span;
     unsigned long long *cursor;
     int64_t *pool;
 };
-template <int NS, bool CHK>
+template <int NS, bool CHK, bool FIRST>
 hipError_t launch_ph(const PHArgs &a) {
     static size_t configured = 0;
     if (a.lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>,
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK, FIRST>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
         configured = a.lds;
     }
-    // rows of whole words on a 16-byte aligned base (always true of the working copies) load as vectors
-    const bool aligned_src = a.src_stride_bits == 32 * ((NS + 3) / 4) && ((uintptr_t)a.src_sym & 15u) == 0;
-    part_hist_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src_sym, a.src_stride_bits, a.src_words, aligned_src, a.dst_sym,
-                                                                   a.ft, a.B, a.Bp, a.missing, a.src_gq, a.dst_gq,
-                                                                   a.jobs, a.n_jobs, a.rows_per_span, a.cursor, a.pool);
+    part_hist_kernel<NS, CHK, FIRST><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
+                                                                          a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs,
+                                                                          a.n_jobs, a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
 }
-template <bool CHK>
+template <bool CHK, bool FIRST>
 hipError_t pick_ph(int ft, const PHArgs &a) {
-    if (ft <= 4) return launch_ph<4, CHK>(a);
-    if (ft <= 8) return launch_ph<8, CHK>(a);
-    if (ft <= 12) return launch_ph<12, CHK>(a);
-    if (ft == 13) return launch_ph<13, CHK>(a);
-    return launch_ph<16, CHK>(a);
+    if (ft <= 4) return launch_ph<4, CHK, FIRST>(a);
+    if (ft <= 8) return launch_ph<8, CHK, FIRST>(a);
+    if (ft <= 12) return launch_ph<12, CHK, FIRST>(a);
+    if (ft == 13) return launch_ph<13, CHK, FIRST>(a);
+    return launch_ph<16, CHK, FIRST>(a);
 }
+int slots_for(int ft) { return ft <= 4 ? 4 : ft <= 8 ? 8 : ft <= 12 ? 12 : ft == 13 ? 13 : 16; }
 }  // namespace
 
-bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B, const GbtRows &dst) {
+bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B) {
     if (bits != 8 || F > 16 || B > 256) return false;
-    if (dst.stride_bits != 32 * (int64_t)((F + 3) / 4)) return false;
     const size_t lds = ((size_t)F * padded_bins(B) + 256) * 12;
     const size_t cap = ctx->hist_lds_kb > 0 ? (size_t)ctx->hist_lds_kb * 1024 : ctx->lds_per_block;
     return lds <= cap && lds <= ctx->lds_per_block;
 }
 int gbt_part_hist_tile() { return kPHTile; }
+int gbt_part_hist_record_words(int F) { return record_words(slots_for(F)); }
 
-hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const GbtRows &src, const GbtRows &dst, int F, int B, uint32_t missing,
+hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
+                                const uint32_t *src_records, uint32_t *dst_records, int F, int B, uint32_t missing,
                                 const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
                                 unsigned long long *cursor, int64_t *hist_pool) {
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
     hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, n_jobs);
     if (e != hipSuccess) return e;
     const int Bp = padded_bins(B);
-    const PHArgs a{ctx->stream, n_spans, ((size_t)F * Bp + 256) * 12, src.sym, src.stride_bits, src.n_words, dst.sym_rw,
-                   F, B, Bp, missing, (const int2 *)src.gq, (int2 *)dst.gq_rw, jobs, n_jobs, rows_per_span, cursor,
+    const bool first = src_records == nullptr;
+    const PHArgs a{ctx->stream, n_spans, ((size_t)F * Bp + 256) * 12, first ? packed : src_records, first ? (int64_t)F : 0,
+                   packed_words, (const int2 *)gq, dst_records, F, B, Bp, missing, jobs, n_jobs, rows_per_span, cursor,
                    hist_pool};
     const bool chk = missing < 256u || B < 256;
-    return chk ? pick_ph<true>(F, a) : pick_ph<false>(F, a);
+    if (first) return chk ? pick_ph<true, true>(F, a) : pick_ph<false, true>(F, a);
+    return chk ? pick_ph<true, false>(F, a) : pick_ph<false, false>(F, a);
 }
