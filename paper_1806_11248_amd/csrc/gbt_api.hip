@@ -743,26 +743,41 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     std::vector<gbt_split> splits;
     std::vector<int> split_of;   // index into `level` of every splitting node
 
-    for (int depth = 0; depth < max_depth && !level.empty(); ++depth) {
-        // ---- EvaluateSplit for every open node of the level
-        enodes.resize(level.size());
-        for (size_t i = 0; i < level.size(); ++i)
-            enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
-        st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
-        if (st != GBT_OK) return st;
-        const int chunks = gbt_eval_chunks(F, (int)level.size(), GBT_STAGING_BYTES - kReadbackOff);
-        gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)level.size() * (double)hist_len * 8.0);
-        GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)level.size(), nb, F, B,
-                                     chunks, inv_sg, inv_sh, lambda, params->min_child_weight,
+    // Split records come back in the read-back half of the staging behind the partition's row counts.
+    constexpr size_t kSplitRb = 512u << 10;
+    int chunks = 1;
+    bool pre_eval = false;   // the level's split records are already in the read-back buffer
+    auto enqueue_eval = [&](const std::vector<EvalNode> &en, int *n_chunks) -> int32_t {
+        int32_t st2 = upload(ctx, en.data(), en.size() * sizeof(EvalNode), ws + L.eval_nodes);
+        if (st2 != GBT_OK) return st2;
+        const size_t budget = GBT_STAGING_BYTES - kReadbackOff - kSplitRb;
+        *n_chunks = gbt_eval_chunks(F, (int)en.size(), budget);
+        gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)en.size() * (double)hist_len * 8.0);
+        GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)en.size(), nb, F, B,
+                                     *n_chunks, inv_sg, inv_sh, lambda, params->min_child_weight,
                                      (gbt_split *)(ws + L.splits)));
         gbt_prof_end(ctx);
-        const size_t sbytes = level.size() * chunks * sizeof(gbt_split);
-        GBT_REQUIRE(ctx, sbytes <= GBT_STAGING_BYTES - kReadbackOff, GBT_EUNSUPPORTED, "level too wide");
-        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
-        GBT_SYNC(ctx);
+        const size_t sbytes = en.size() * (size_t)*n_chunks * sizeof(gbt_split);
+        GBT_REQUIRE(ctx, sbytes <= budget, GBT_EUNSUPPORTED, "level too wide");
+        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx) + kSplitRb, ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
+        return GBT_OK;
+    };
+
+    for (int depth = 0; depth < max_depth && !level.empty(); ++depth) {
+        // ---- EvaluateSplit for every open node of the level (already enqueued, and waited for, by
+        //      the level before when that ran the partition + histogram pass)
+        if (!pre_eval) {
+            enodes.resize(level.size());
+            for (size_t i = 0; i < level.size(); ++i)
+                enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
+            st = enqueue_eval(enodes, &chunks);
+            if (st != GBT_OK) return st;
+            GBT_SYNC(ctx);
+        }
+        pre_eval = false;
         splits.resize(level.size());
         for (size_t i = 0; i < level.size(); ++i)
-            splits[i] = merge_chunks((const gbt_split *)rb(ctx) + i * chunks, chunks);
+            splits[i] = merge_chunks((const gbt_split *)(rb(ctx) + kSplitRb) + i * chunks, chunks);
 
         // ---- which nodes split; RepartitionInstances for those.
         // Children that are split again get their whole records moved: by the one-launch form
@@ -848,19 +863,45 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                                               (int)pjobs.size(), (int)tile_cursor, part_tile,
                                               (unsigned long long *)(ws + L.state), pool));
             GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+            gbt_prof_end(ctx);
+            // Everything the children's evaluation needs is known before the rows are counted (ids,
+            // sums, which child was built): enqueue the subtraction and the evaluation behind the
+            // pass, so that the host waits once per level instead of twice.
+            sjobs.clear();
+            enodes.clear();
+            for (size_t k = 0; k < pjobs.size(); ++k) {
+                const HNode &nd = level[split_of[k]];
+                const gbt_split &sp = splits[split_of[k]];
+                const int64_t lid = n_nodes + 2 * (int64_t)k, rid = lid + 1;
+                const int64_t built = pjobs[k].pad == 1u ? lid : rid, other = pjobs[k].pad == 1u ? rid : lid;
+                sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)built * (uint64_t)hist_len,
+                                       (uint64_t)other * (uint64_t)hist_len});
+                enodes.push_back(EvalNode{(uint64_t)lid * (uint64_t)hist_len, sp.GLq, sp.HLq});
+                enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq});
+            }
+            GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
+            st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
+            if (st != GBT_OK) return st;
+            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
+            GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
+            gbt_prof_end(ctx);
+            st = enqueue_eval(enodes, &chunks);
+            if (st != GBT_OK) return st;
+            pre_eval = true;
         } else if (fused) {
             GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,
                                                     (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
                                                     (int)tile_cursor, (unsigned long long *)(ws + L.state)));
             GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+            gbt_prof_end(ctx);
         } else {
             GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym, what,
                                                       (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
                                                       (int)tile_cursor, (uint64_t *)(ws + L.masks),
                                                       (uint32_t *)(ws + L.tile_left), (uint32_t *)(ws + L.n_left)));
             GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
+            gbt_prof_end(ctx);
         }
-        gbt_prof_end(ctx);
         GBT_SYNC(ctx);
         const int nl_stride = fused ? 2 : 1;   // the one-launch form returns 64-bit cursors, n_left in the low half
         if (what != GBT_PART_COUNT) {
@@ -932,7 +973,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 gbt_prof_end(ctx);
             }
         }
-        if (children_need_hist) {   // ---- siblings by subtraction
+        if (children_need_hist && !with_hist) {   // ---- siblings by subtraction (with_hist: already enqueued)
             GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
             st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
             if (st != GBT_OK) return st;
