@@ -58,11 +58,24 @@ double fixed_scale(float vmax, int top) {
 struct HistPlan {
     int ft_max, n_ftiles, ft;
 };
-bool plan_tiles(const gbt_ctx *ctx, int F, int B, HistPlan *p) {
+// The kernels consume a row slice in register windows of E whole elements and issue an atomic for
+// every slot of a window, used or not.  More tiles than the LDS budget demands cost a pass over the
+// gradient pairs each, so they are taken only when they save at least a fifth of the slots.
+bool plan_tiles(const gbt_ctx *ctx, int F, int B, int bits, HistPlan *p) {
     p->ft_max = gbt_hist_feature_tile(ctx, F, B);
     if (p->ft_max < 1) return false;
-    p->n_ftiles = (F + p->ft_max - 1) / p->ft_max;
-    p->ft = (F + p->n_ftiles - 1) / p->n_ftiles;
+    const int E = bits == 8 ? 16 : std::min(128 / std::max(bits, 1), 32);
+    const int nt_min = (F + p->ft_max - 1) / p->ft_max;
+    int64_t best_slots = -1;
+    for (int nt = nt_min; nt <= nt_min + 8 && nt <= F; ++nt) {
+        const int ft = (F + nt - 1) / nt;
+        const int64_t slots = (int64_t)nt * ((ft + E - 1) / E) * E;
+        if (best_slots < 0 || slots * 5 <= best_slots * 4) {
+            best_slots = slots;
+            p->n_ftiles = nt;
+            p->ft = ft;
+        }
+    }
     return true;
 }
 
@@ -509,7 +522,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
                             const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs, const RootFix *fix) {
     HistPlan pl;
-    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, &pl), GBT_EUNSUPPORTED,
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins (%d bytes) exceed the LDS budget", B, B * 16);
     GBT_HIP(ctx, gbt_launch_fill_u64(ctx->stream, (uint64_t *)hist_out, 0, (int64_t)F * B * 2));
     if (n_rows == 0) return GBT_OK;
@@ -612,7 +625,7 @@ extern "C" int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int
     if (!ctx) return GBT_EINVAL;
     GBT_REQUIRE(ctx, F >= 1 && bits >= 1 && bits <= GBT_MAX_BITS && max_bins >= 2, GBT_EINVAL, "bad shape");
     HistPlan pl;
-    GBT_REQUIRE(ctx, plan_tiles(ctx, F, max_bins, &pl), GBT_EUNSUPPORTED,
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, max_bins, bits, &pl), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins exceed the LDS budget", max_bins);
     return grow_path(ctx, F, bits, max_bins, track_rows != 0, pl.n_ftiles);
 }
@@ -643,7 +656,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     const GrowLayout L = grow_layout(n, F, bits, B, max_depth);
     GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
     HistPlan pl;
-    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, &pl), GBT_EUNSUPPORTED,
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins exceed the LDS budget", B);
 
     char *ws = (char *)workspace;
