@@ -211,6 +211,18 @@ def new_tree(max_depth: int) -> dict:
         n_rows=np.zeros(cap, np.int64), depth=np.zeros(cap, np.int32))
 
 
+def new_tree_leaves(max_leaves: int) -> dict:
+    """A tree with room for max_leaves leaves (2*max_leaves - 1 nodes)."""
+    t = new_tree(0)
+    cap = 2 * max_leaves - 1
+    for k, v in list(t.items()):
+        if isinstance(v, np.ndarray):
+            t[k] = np.resize(v, cap)
+            t[k][:] = v[0]
+    t["capacity"] = cap
+    return t
+
+
 def _threshold(cuts_, nb, f, b):
     # rows with symbol <= b are those with x < cuts[f][b]; the feature's last
     # bin has no cut to its right (only missing rows can be on the other side)
@@ -255,6 +267,60 @@ def grow_tree(sym, nb, cuts_, missing_sym, gpair, *, max_depth, max_bins, lam=1.
         t["left"][node], t["right"][node], t["gain"][node] = li, ri, sp["gain"]
         queue.append((li, lo, lo + nl, depth + 1))
         queue.append((ri, lo + nl, hi, depth + 1))
+    return t, rows, leaf_of_row
+
+
+def grow_tree_lossguide(sym, nb, cuts_, missing_sym, gpair, *, max_leaves, max_depth, max_bins, lam=1.0,
+                        gamma=0.0, min_child_weight=1.0):
+    """Alg. 1 with the loss-guided policy of Sec. 2.3: instead of the node closest to the
+    root, the open leaf whose best split has the LARGEST gain is expanded next (the smaller
+    node id on equal gains), until the tree has max_leaves leaves or no leaf is open.  A
+    leaf is open iff it has a valid candidate with gain > max(gamma, GAIN_FLOOR) and its
+    depth is below max_depth.  Children get the next two ids at the moment of the
+    expansion.  Returns (tree, row_idx, leaf_of_row) like grow_tree."""
+    n, F = sym.shape
+    B = max_bins
+    t = new_tree_leaves(max_leaves)
+    rows = np.arange(n, dtype=np.uint32)
+    leaf_of_row = np.zeros(n, np.int32)
+    seg = {}      # node -> (lo, hi)
+    open_ = {}    # node -> its best split
+
+    def settle(node, lo, hi, depth):
+        r = rows[lo:hi]
+        h_, cnt, G, H = hist(sym, B, missing_sym, r, gpair)
+        t["sumG"][node], t["sumH"][node], t["n_rows"][node] = G, H, hi - lo
+        t["weight"][node] = -G / (H + lam)
+        t["depth"][node] = depth
+        seg[node] = (lo, hi)
+        if depth < max_depth:
+            sp = eval_split(h_, cnt, nb, G, H, hi - lo, lam, min_child_weight)
+            if bool(sp["valid"]) and sp["gain"] > gamma and sp["gain"] > GAIN_FLOOR:
+                open_[node] = sp
+
+    t["n_nodes"] = 1
+    settle(0, 0, n, 0)
+    n_leaves = 1
+    while n_leaves < max_leaves and open_:
+        node = min(open_, key=lambda k: (-open_[k]["gain"], k))
+        sp = open_.pop(node)
+        lo, hi = seg[node]
+        f, b, dl = sp["feature"], sp["bin"], sp["default_left"]
+        out, nl = partition(sym, rows[lo:hi], f, b, dl, missing_sym)
+        rows[lo:hi] = out
+        li, ri = t["n_nodes"], t["n_nodes"] + 1
+        t["n_nodes"] += 2
+        t["feature"][node], t["bin"][node], t["default_left"][node] = f, b, dl
+        t["threshold"][node] = _threshold(cuts_, nb, f, b)
+        t["left"][node], t["right"][node], t["gain"][node] = li, ri, sp["gain"]
+        d = int(t["depth"][node]) + 1
+        settle(li, lo, lo + nl, d)
+        settle(ri, lo + nl, hi, d)
+        n_leaves += 1
+    for node in range(t["n_nodes"]):
+        if t["feature"][node] < 0:
+            lo, hi = seg[node]
+            leaf_of_row[rows[lo:hi]] = node
     return t, rows, leaf_of_row
 
 
@@ -393,6 +459,109 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
                     err(f"node {node}: leaf although best gain {best['gain']!r} > {thr}")
     if seen != int(other["n_nodes"]):
         err(f"reached {seen} nodes, tree says {int(other['n_nodes'])}")
+    rep["row_idx"] = rows
+    rep["leaf_of_row"] = leaf_of_row
+    return rep
+
+
+def replay_tree_lossguide(other, sym, nb, missing_sym, gpair, *, max_leaves, max_depth, max_bins, lam=1.0,
+                          gamma=0.0, min_child_weight=1.0, tie_rtol=1e-6, sum_rtol=1e-5, sum_atol_per_row=0.0):
+    """Judge a loss-guided tree grown elsewhere.  The k-th expansion of ``other`` is the node
+    whose children are 2k+1 and 2k+2.  Replays the expansions in that order on the oracle's
+    own row lists and checks, besides everything ``replay_tree`` checks per node, the policy:
+    the expanded node was an open leaf whose chosen split's fp64 gain is within ``tie_rtol``
+    (relative) of the largest best gain over the leaves open at that moment, and growth
+    stopped only at max_leaves leaves or with no open leaf left (ties at the threshold aside)."""
+    n, F = sym.shape
+    B = max_bins
+    rows = np.arange(n, dtype=np.uint32)
+    leaf_of_row = np.zeros(n, np.int32)
+    rep = dict(ok=True, identical=True, n_nodes=int(other["n_nodes"]), ties=[], errors=[], checked_splits=0)
+    thr = max(gamma, GAIN_FLOOR)
+
+    def err(msg):
+        rep["ok"] = False
+        rep["errors"].append(msg)
+
+    seg, info = {}, {}   # node -> (lo, hi, depth); node -> (hist, cnt, G, H, best)
+
+    def settle(node, lo, hi, depth):
+        r = rows[lo:hi]
+        if int(other["n_rows"][node]) != hi - lo:
+            err(f"node {node}: n_rows {int(other['n_rows'][node])} != {hi - lo}")
+        h_, cnt, G, H = hist(sym, B, missing_sym, r, gpair)
+        atol = sum_atol_per_row * (hi - lo)
+        for nm, ref, got in (("sumG", G, other["sumG"][node]), ("sumH", H, other["sumH"][node])):
+            if abs(got - ref) > sum_rtol * abs(ref) + atol + 1e-300:
+                err(f"node {node}: {nm} {got!r} vs {ref!r}")
+        w = -G / (H + lam)
+        if abs(other["weight"][node] - w) > sum_rtol * abs(w) + 2.0 * atol / (H + lam) + 1e-300:
+            err(f"node {node}: weight {other['weight'][node]!r} vs {w!r}")
+        rep["checked_splits"] += 1
+        best = eval_split(h_, cnt, nb, G, H, hi - lo, lam, min_child_weight) \
+            if depth < max_depth else dict(valid=0, gain=-np.inf, feature=-1, bin=0, default_left=0)
+        seg[node] = (lo, hi, depth)
+        info[node] = (h_, G, H, best)
+
+    def open_gain(node):
+        best = info[node][3]
+        return best["gain"] if bool(best["valid"]) and best["gain"] > thr else -np.inf
+
+    nn = int(other["n_nodes"])
+    if nn % 2 != 1 or nn > 2 * max_leaves - 1:
+        err(f"n_nodes {nn} is not an odd number <= {2 * max_leaves - 1}")
+        return rep
+    parent_of = {}
+    for node in range(nn):
+        if other["feature"][node] >= 0:
+            parent_of[int(other["left"][node])] = node
+    settle(0, 0, n, 0)
+    leaves = {0}
+    for k in range((nn - 1) // 2):
+        li, ri = 2 * k + 1, 2 * k + 2
+        node = parent_of.get(li)
+        if node is None or int(other["right"][node]) != ri or node not in leaves:
+            err(f"expansion {k}: children {li},{ri} do not hang under one current leaf")
+            return rep
+        lo, hi, depth = seg[node]
+        h_, G, H, best = info[node]
+        f, b, dl = int(other["feature"][node]), int(other["bin"][node]), int(other["default_left"][node])
+        if not (0 <= f < F and 0 <= b < nb[f]) or depth >= max_depth:
+            err(f"node {node}: split ({f},{b}) out of range or too deep")
+            return rep
+        g_other, _ = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight)
+        if not np.isfinite(g_other):
+            err(f"node {node}: chosen split ({f},{b},{dl}) is not a valid candidate")
+            return rep
+        if (f, b, dl) != (best["feature"], best["bin"], best["default_left"]):
+            rep["identical"] = False
+            rep["ties"].append((node, (f, b, dl), (best["feature"], best["bin"], best["default_left"]),
+                                g_other, best["gain"]))
+            if not abs(g_other - best["gain"]) <= tie_rtol * abs(best["gain"]):
+                err(f"node {node}: split ({f},{b},{dl}) gain {g_other!r} vs best gain {best['gain']!r}")
+        top = max(open_gain(x) for x in leaves)
+        if not g_other >= top - tie_rtol * abs(top):
+            err(f"expansion {k}: node {node} (gain {g_other!r}) expanded while a leaf with gain {top!r} was open")
+        elif node != min(leaves, key=lambda x: (-open_gain(x), x)):
+            rep["identical"] = False
+        if not g_other > thr - tie_rtol * max(abs(thr), abs(g_other)):
+            err(f"node {node}: split although its gain {g_other!r} is below {thr}")
+        out, nl = partition(sym, rows[lo:hi], f, b, dl, missing_sym)
+        rows[lo:hi] = out
+        leaves.remove(node)
+        settle(li, lo, lo + nl, depth + 1)
+        settle(ri, lo + nl, hi, depth + 1)
+        leaves |= {li, ri}
+    if len(leaves) < max_leaves:
+        top = max(open_gain(x) for x in leaves)
+        if np.isfinite(top) and not abs(top - thr) <= tie_rtol * max(abs(thr), abs(top)):
+            rep["identical"] = False
+            err(f"stopped at {len(leaves)} leaves although a leaf with gain {top!r} was open")
+    for node in leaves:
+        if other["feature"][node] >= 0:
+            err(f"node {node} is marked as split but has no children among the {nn} nodes")
+        lo, hi, _ = seg[node]
+        leaf_of_row[rows[lo:hi]] = node
     rep["row_idx"] = rows
     rep["leaf_of_row"] = leaf_of_row
     return rep
