@@ -271,6 +271,25 @@ GBT_API int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits
                       const gbt_params *params, gbt_tree *tree_out, uint32_t *row_idx_out,
                       int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
 
+/*
+ * Alg. 1 with the loss-guided policy of Sec. 2.3 ("highest gain first"): the open
+ * leaf whose best split has the largest gain is expanded next (the smaller node id
+ * on equal gains) until the tree has max_leaves leaves or no leaf is open.  A leaf is
+ * open iff it has a valid candidate with gain > max(gamma, GBT_GAIN_FLOOR) and its
+ * depth is below params->max_depth (any value >= 0 here).  Children get the next
+ * two node ids at the moment of the expansion, so the k-th expansion creates nodes
+ * 2k+1 and 2k+2.  Arguments, outputs, the NULL row_idx_out form and error behaviour
+ * as for gbt_grow_tree; tree_out needs capacity >= 2*max_leaves - 1.
+ * One node is split per step (partition, one child's histogram, subtraction,
+ * evaluation of both children) with the kernels of the depth-wise loop.
+ */
+GBT_API size_t gbt_grow_tree_lossguide_workspace_bytes(int64_t n, int32_t F, int32_t bits, int32_t max_bins,
+                                                       int32_t max_leaves);
+GBT_API int32_t gbt_grow_tree_lossguide(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                      int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
+                      const gbt_params *params, int32_t max_leaves, gbt_tree *tree_out, uint32_t *row_idx_out,
+                      int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
+
 /* ---- Sec. 2.4 prediction ------------------------------------------------ */
 
 GBT_API size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_trees);

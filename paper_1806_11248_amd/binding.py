@@ -25,7 +25,8 @@ SYMBOLS = [
     "gbt_quantise_workspace_bytes", "gbt_quantise", "gbt_bits", "gbt_packed_words", "gbt_compress",
     "gbt_gradients", "gbt_gpair_fixed", "gbt_sum_gpair", "gbt_build_hist", "gbt_hist_subtract",
     "gbt_hist_export_f64", "gbt_eval_split", "gbt_partition_workspace_bytes", "gbt_partition",
-    "gbt_grow_tree_workspace_bytes", "gbt_grow_tree_path", "gbt_grow_tree", "gbt_predict_workspace_bytes", "gbt_predict",
+    "gbt_grow_tree_workspace_bytes", "gbt_grow_tree_path", "gbt_grow_tree",
+    "gbt_grow_tree_lossguide_workspace_bytes", "gbt_grow_tree_lossguide", "gbt_predict_workspace_bytes", "gbt_predict",
     "gbt_profile_enable", "gbt_profile_read",
 ]
 
@@ -92,6 +93,8 @@ def load():
     L.gbt_quantise_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.c_int32]
     L.gbt_partition_workspace_bytes.argtypes = [C.c_int64]
     L.gbt_grow_tree_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    L.gbt_grow_tree_lossguide_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    L.gbt_grow_tree_lossguide_workspace_bytes.restype = C.c_size_t
     L.gbt_grow_tree_path.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     L.gbt_grow_tree_path.restype = C.c_int32
     L.gbt_predict_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
@@ -107,6 +110,7 @@ def load():
     L.gbt_eval_split.argtypes = [vp, vp, vp, i32, i32, i64, i64, vp, vp, vp, vp, sz]
     L.gbt_partition.argtypes = [vp, vp, i32, i64, i32, vp, i64, i64, i32, i32, i32, i32, vp, sz, vp]
     L.gbt_grow_tree.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
+    L.gbt_grow_tree_lossguide.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz]
     L.gbt_predict.argtypes = [vp, vp, i32, vp, i32, i32, vp, i64, i32, f64, vp, vp, sz]
     L.gbt_profile_enable.argtypes = [vp, i32]
     L.gbt_profile_read.argtypes = [vp, vp]
@@ -130,6 +134,15 @@ def make_params(*, max_depth, max_bins, lam=1.0, gamma=0.0, min_child_weight=1.0
 
 def new_tree(max_depth: int) -> dict:
     cap = 2 ** (max_depth + 1) - 1
+    t = {nm: np.zeros(cap, dt) for nm, dt in _TREE_FIELDS}
+    t["capacity"] = cap
+    t["n_nodes"] = 0
+    return t
+
+
+def new_tree_leaves(max_leaves: int) -> dict:
+    """Arrays for a tree of at most max_leaves leaves (2*max_leaves - 1 nodes)."""
+    cap = max(1, 2 * max_leaves - 1)   # a bad budget is the library's to refuse
     t = {nm: np.zeros(cap, dt) for nm, dt in _TREE_FIELDS}
     t["capacity"] = cap
     t["n_nodes"] = 0
@@ -334,6 +347,23 @@ class Context:
         self._check(self.lib.gbt_grow_tree(self.h, _ptr(packed), bits, n, F, missing_sym, _ptr(nb), _ptr(cuts),
                                            _ptr(gpair), C.byref(params), C.byref(ts), _ptr(row_idx), _ptr(leaf),
                                            _ptr(ws), ws.numel()))
+        t["n_nodes"] = int(ts.n_nodes)
+        return t, row_idx, leaf
+
+    def grow_tree_lossguide(self, packed, bits, n, F, missing_sym, nb, cuts, gpair, params: Params, max_leaves,
+                            want_leaf=True, want_rows=True):
+        """Loss-guided growth (Sec. 2.3); returns what grow_tree returns."""
+        t = new_tree_leaves(max_leaves)
+        ts = _tree_struct(t)
+        row_idx = self.empty((n,), torch.int32) if want_rows else None
+        leaf = self.empty((n,), torch.int32) if (want_rows and want_leaf) else None
+        ws_bytes = self.lib.gbt_grow_tree_lossguide_workspace_bytes(n, F, bits, params.max_bins, max_leaves)
+        if ws_bytes == 0:
+            raise GbtError(EINVAL, "gbt_grow_tree_lossguide_workspace_bytes rejected the shape")
+        ws = self.workspace("grow", ws_bytes)
+        self._check(self.lib.gbt_grow_tree_lossguide(self.h, _ptr(packed), bits, n, F, missing_sym, _ptr(nb),
+                                                     _ptr(cuts), _ptr(gpair), C.byref(params), max_leaves,
+                                                     C.byref(ts), _ptr(row_idx), _ptr(leaf), _ptr(ws), ws.numel()))
         t["n_nodes"] = int(ts.n_nodes)
         return t, row_idx, leaf
 

@@ -562,10 +562,16 @@ struct GrowLayout {
     int sw;   // 32-bit words per row of the working copies
 };
 
+// hist_nodes: nodes that may own a histogram (ids below it); level_nodes: most nodes split in one round
+GrowLayout grow_layout_nodes(int64_t n, int F, int bits, int B, int64_t hist_nodes, int64_t level_nodes);
 GrowLayout grow_layout(int64_t n, int F, int bits, int B, int max_depth) {
+    return grow_layout_nodes(n, F, bits, B, max_depth == 0 ? 1 : (((int64_t)1 << max_depth) - 1),
+                             (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0));
+}
+GrowLayout grow_layout_nodes(int64_t n, int F, int bits, int B, int64_t hist_nodes, int64_t level_nodes) {
     GrowLayout L;
-    L.hist_nodes = max_depth == 0 ? 1 : (((int64_t)1 << max_depth) - 1);
-    L.level_nodes = (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0);   // most nodes evaluated in one level
+    L.hist_nodes = hist_nodes;
+    L.level_nodes = level_nodes;
     L.tiles = n / GBT_PART_TILE + L.level_nodes + 1;
     L.sw = (int)(((int64_t)F * bits + 31) / 32);
     // the partition + histogram pass keeps symbols and gradient pair in one record per row
@@ -580,10 +586,10 @@ GrowLayout grow_layout(int64_t n, int F, int bits, int B, int max_depth) {
     }
     L.masks = o;      o += gbt_align((size_t)L.tiles * (GBT_PART_TILE / 64) * 8);
     L.tile_left = o;  o += gbt_align((size_t)L.tiles * 4);
-    L.n_left = o;     o += gbt_align((size_t)L.level_nodes * 4);
+    L.n_left = o;     o += gbt_align((size_t)L.level_nodes * 4 + 4);
     L.state = o;      o += gbt_align((size_t)L.level_nodes * 8);
     L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
-    L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * sizeof(EvalNode));
+    L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * 2 * sizeof(EvalNode));
     L.splits = o;     o += gbt_align(GBT_STAGING_BYTES / 2);   // per-(node, feature chunk) records of one level
     L.jobs = o;       o += gbt_align(kUploadBytes);
     L.scratch = o;    o += 4096;
@@ -595,7 +601,11 @@ struct HNode {
     int32_t id;
     uint32_t begin, len;
     int64_t Gq, Hq;
+    int32_t depth;
+    int32_t buf;   // where the node's rows are: 0/1 = working copy, 2 = the caller's matrix (the root)
 };
+enum { GBT_POLICY_DEPTHWISE = 0, GBT_POLICY_LOSSGUIDE = 1 };
+constexpr int32_t kMaxLeaves = 1 << 20;
 
 }  // namespace
 
@@ -630,10 +640,13 @@ extern "C" int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int
     return grow_path(ctx, F, bits, max_bins, track_rows != 0, pl.n_ftiles);
 }
 
-extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
-                                 int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
-                                 const gbt_params *params, gbt_tree *tree, uint32_t *row_idx_out,
-                                 int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes) {
+// Alg. 1 under either policy of Sec. 2.3.  Growth proceeds in rounds: the nodes created by the round
+// before are evaluated; depth-wise then splits every one of them that may split, loss-guided only
+// the open leaf with the largest gain (smaller id on equal gains), however long ago it was created.
+static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                         int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
+                         const gbt_params *params, int policy, int32_t max_leaves, gbt_tree *tree,
+                         uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes) {
     if (!ctx) return GBT_EINVAL;
     int32_t st = check_matrix(ctx, packed, bits, n, F);
     if (st != GBT_OK) return st;
@@ -643,17 +656,20 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     const int B = params->max_bins, max_depth = params->max_depth;
     st = check_bins(ctx, F, B);
     if (st != GBT_OK) return st;
+    const bool lossguide = policy == GBT_POLICY_LOSSGUIDE;
     GBT_REQUIRE(ctx, max_depth >= 0, GBT_EINVAL, "max_depth < 0");
-    GBT_REQUIRE(ctx, max_depth <= kMaxDepth, GBT_EUNSUPPORTED, "max_depth %d > %d", max_depth, kMaxDepth);
+    GBT_REQUIRE(ctx, lossguide || max_depth <= kMaxDepth, GBT_EUNSUPPORTED, "max_depth %d > %d", max_depth, kMaxDepth);
+    GBT_REQUIRE(ctx, !lossguide || (max_leaves >= 1 && max_leaves <= kMaxLeaves), lossguide && max_leaves >= 1 ? GBT_EUNSUPPORTED : GBT_EINVAL,
+                "max_leaves %d outside 1..%d", max_leaves, kMaxLeaves);
     GBT_REQUIRE(ctx, n >= 1, GBT_EINVAL, "n < 1");
     GBT_REQUIRE(ctx, missing_sym >= 0, GBT_EINVAL, "missing_sym < 0");
     GBT_REQUIRE(ctx, params->lambda >= 0.0, GBT_EINVAL, "lambda < 0");
-    const int64_t cap = ((int64_t)1 << (max_depth + 1)) - 1;
+    const int64_t cap = lossguide ? 2 * (int64_t)max_leaves - 1 : ((int64_t)1 << (max_depth + 1)) - 1;
     GBT_REQUIRE(ctx, tree->capacity >= cap, GBT_EINVAL, "tree capacity %d < %lld", tree->capacity, (long long)cap);
     GBT_REQUIRE(ctx, tree->feature && tree->bin && tree->default_left && tree->left && tree->right &&
                          tree->threshold && tree->weight && tree->gain && tree->sumG && tree->sumH && tree->n_rows,
                 GBT_EINVAL, "tree arrays must be allocated");
-    const GrowLayout L = grow_layout(n, F, bits, B, max_depth);
+    const GrowLayout L = lossguide ? grow_layout_nodes(n, F, bits, B, cap, 1) : grow_layout(n, F, bits, B, max_depth);
     GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
     HistPlan pl;
     GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
@@ -686,16 +702,15 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             W[k].gq_rw = nullptr;
         }
     }
-    GbtRows cur;
-    cur.sym = packed;
-    cur.stride_bits = row_bits;
-    cur.n_words = gbt_packed_words(n, F, bits);
-    cur.gq = gq;
-    cur.id = nullptr;
-    cur.sym_rw = nullptr;
-    cur.gq_rw = nullptr;
-    cur.id_rw = nullptr;
-    int wcur = 2;   // which id buffer describes the current order: 0/1 = W[k], 2 = identity
+    GbtRows matrix;   // the caller's matrix seen as "buffer 2": rows in matrix order, ids = positions
+    matrix.sym = packed;
+    matrix.stride_bits = row_bits;
+    matrix.n_words = gbt_packed_words(n, F, bits);
+    matrix.gq = gq;
+    matrix.id = nullptr;
+    matrix.sym_rw = nullptr;
+    matrix.gq_rw = nullptr;
+    matrix.id_rw = nullptr;
 
     // thresholds come from the cut table
     std::vector<float> hcuts((size_t)F * (B - 1));
@@ -705,7 +720,8 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     // the conversion is a pass of its own, or part of the root histogram kernel where that can do it.
     double scale[2];
     int64_t *sums_dev = (int64_t *)(ws + L.scratch + 256);
-    const bool fix_in_hist = ctx->hist_fix && max_depth > 0 && gbt_hist_fix_ok(bits, row_bits, pl.ft, pl.n_ftiles);
+    const bool root_may_split = max_depth > 0 && (!lossguide || max_leaves > 1);
+    const bool fix_in_hist = ctx->hist_fix && root_may_split && gbt_hist_fix_ok(bits, row_bits, pl.ft, pl.n_ftiles);
     gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (fix_in_hist ? 8.0 : 24.0));
     st = gpair_scale_impl(ctx, gpair, n, scale, ws + L.scratch);
     if (st == GBT_OK && !fix_in_hist) {
@@ -717,7 +733,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
     const double lambda = params->lambda;
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
-    if (max_depth > 0) {
+    if (root_may_split) {
         const RootFix fix{gpair, scale[0], scale[1], gq, sums_dev};
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
                           (HistJob *)(ws + L.jobs), fix_in_hist ? &fix : nullptr);
@@ -742,19 +758,26 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         tree->n_rows[nd.id] = nd.len;
     };
 
-    std::vector<HNode> level, next;
+    std::vector<HNode> level, next;   // the nodes created by the last round: to be evaluated
     std::vector<LeafSeg> leaves;
-    HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1]};
+    HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1], 0, 2};
     set_node(root);
-    level.push_back(root);
-    int32_t n_nodes = 1;
+    if (root_may_split)
+        level.push_back(root);
+    else
+        leaves.push_back(LeafSeg{0, 0, 2, (uint32_t)n});
+    int32_t n_nodes = 1, n_leaves = 1;
+    // loss-guided: the leaves that may still be split, with their best splits
+    struct OpenLeaf { HNode nd; gbt_split sp; };
+    std::vector<OpenLeaf> open_leaves;
+    std::vector<HNode> sel_nodes;      // the nodes this round splits ...
+    std::vector<gbt_split> sel_splits; // ... and how
 
     std::vector<EvalNode> enodes;
     std::vector<PartJob> pjobs;
     std::vector<HistJob> hjobs;
     std::vector<SubJob> sjobs;
     std::vector<gbt_split> splits;
-    std::vector<int> split_of;   // index into `level` of every splitting node
 
     // Split records come back in the read-back half of the staging behind the partition's row counts.
     constexpr size_t kSplitRb = 512u << 10;
@@ -776,10 +799,10 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         return GBT_OK;
     };
 
-    for (int depth = 0; depth < max_depth && !level.empty(); ++depth) {
+    while (!level.empty() || !open_leaves.empty()) {
         // ---- EvaluateSplit for every open node of the level (already enqueued, and waited for, by
         //      the level before when that ran the partition + histogram pass)
-        if (!pre_eval) {
+        if (!pre_eval && !level.empty()) {
             enodes.resize(level.size());
             for (size_t i = 0; i < level.size(); ++i)
                 enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
@@ -798,24 +821,45 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         // histogram kernel's 8-bit single-tile case applies, one child's histogram is built in
         // the same pass), else by the three-launch form.  Leaves only need their ids moved, or
         // just the row counts when ids are not tracked.
-        const int wnext = wcur == 0 ? 1 : 0;
-        const bool children_need_hist = depth + 1 < max_depth;
-        const bool fused = children_need_hist && path >= 1;
-        const bool with_hist = children_need_hist && path == 2;
-        split_of.clear();
-        double part_rows = 0;
+        sel_nodes.clear();
+        sel_splits.clear();
         for (size_t i = 0; i < level.size(); ++i) {
             const gbt_split &sp = splits[i];
             const HNode &nd = level[i];
             const bool ok = sp.valid && sp.gain > min_gain && sp.feature >= 0 && sp.feature < F &&
                             sp.bin >= 0 && sp.bin < B && nd.len > 0;
             if (!ok) {
-                leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)wcur, nd.len});
-                continue;
+                leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)nd.buf, nd.len});
+            } else if (lossguide) {
+                open_leaves.push_back(OpenLeaf{nd, sp});
+            } else {
+                sel_nodes.push_back(nd);
+                sel_splits.push_back(sp);
             }
-            part_rows += nd.len;
-            split_of.push_back((int)i);
         }
+        level.clear();
+        if (lossguide && n_leaves < max_leaves && !open_leaves.empty()) {
+            size_t best = 0;
+            for (size_t i = 1; i < open_leaves.size(); ++i)
+                if (open_leaves[i].sp.gain > open_leaves[best].sp.gain ||
+                    (open_leaves[i].sp.gain == open_leaves[best].sp.gain && open_leaves[i].nd.id < open_leaves[best].nd.id))
+                    best = i;
+            sel_nodes.push_back(open_leaves[best].nd);
+            sel_splits.push_back(open_leaves[best].sp);
+            open_leaves.erase(open_leaves.begin() + (std::ptrdiff_t)best);
+        }
+        if (sel_nodes.empty()) break;   // nothing splits any more: what is still open stays a leaf
+        // all nodes of a round lie in the same buffer (a whole level, or a single node)
+        const int wcur = sel_nodes[0].buf;
+        const GbtRows &cur = wcur == 2 ? matrix : W[wcur];
+        const int wnext = wcur == 0 ? 1 : 0;
+        const int child_depth = sel_nodes[0].depth + 1;
+        const bool children_need_hist =
+            child_depth < max_depth && (!lossguide || n_leaves + 1 < max_leaves);
+        const bool fused = children_need_hist && path >= 1;
+        const bool with_hist = children_need_hist && path == 2;
+        double part_rows = 0;
+        for (const HNode &nd : sel_nodes) part_rows += nd.len;
         // rows per partition workgroup: a tile, or (with the histogram) a span of tiles long enough
         // to be worth merging an LDS histogram into HBM for
         uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile() : (uint32_t)GBT_PART_TILE;
@@ -826,9 +870,9 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         }
         pjobs.clear();
         uint32_t tile_cursor = 0;
-        for (size_t k = 0; k < split_of.size(); ++k) {
-            const gbt_split &sp = splits[split_of[k]];
-            const HNode &nd = level[split_of[k]];
+        for (size_t k = 0; k < sel_nodes.size(); ++k) {
+            const gbt_split &sp = sel_splits[k];
+            const HNode &nd = sel_nodes[k];
             PartJob j;
             j.seg_begin = nd.begin;
             j.seg_len = nd.len;
@@ -846,10 +890,6 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             pjobs.push_back(j);
         }
         next.clear();
-        if (pjobs.empty()) {
-            level.clear();
-            break;
-        }
         GBT_REQUIRE(ctx, (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
         GBT_REQUIRE(ctx, pjobs.size() * sizeof(PartJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
@@ -883,8 +923,8 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
             sjobs.clear();
             enodes.clear();
             for (size_t k = 0; k < pjobs.size(); ++k) {
-                const HNode &nd = level[split_of[k]];
-                const gbt_split &sp = splits[split_of[k]];
+                const HNode &nd = sel_nodes[k];
+                const gbt_split &sp = sel_splits[k];
                 const int64_t lid = n_nodes + 2 * (int64_t)k, rid = lid + 1;
                 const int64_t built = pjobs[k].pad == 1u ? lid : rid, other = pjobs[k].pad == 1u ? rid : lid;
                 sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)built * (uint64_t)hist_len,
@@ -917,10 +957,7 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         }
         GBT_SYNC(ctx);
         const int nl_stride = fused ? 2 : 1;   // the one-launch form returns 64-bit cursors, n_left in the low half
-        if (what != GBT_PART_COUNT) {
-            wcur = wnext;
-            cur = W[wcur];
-        }
+        const int child_buf = what != GBT_PART_COUNT ? wnext : wcur;   // a count moves nothing
         const uint32_t *n_left = (const uint32_t *)rb(ctx);
 
         // ---- children, in creation order
@@ -931,13 +968,14 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         std::vector<Built> built;
         const int32_t first_child = n_nodes;
         for (size_t k = 0; k < pjobs.size(); ++k) {
-            const HNode &nd = level[split_of[k]];
-            const gbt_split &sp = splits[split_of[k]];
+            const HNode &nd = sel_nodes[k];
+            const gbt_split &sp = sel_splits[k];
             const uint32_t nl = n_left[k * nl_stride];
             GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
-            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq};
-            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq};
+            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, child_depth, child_buf};
+            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, child_depth, child_buf};
             n_nodes += 2;
+            n_leaves += 1;
             tree->feature[nd.id] = sp.feature;
             tree->bin[nd.id] = sp.bin;
             tree->default_left[nd.id] = sp.default_left;
@@ -959,8 +997,8 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 next.push_back(lc);
                 next.push_back(rc);
             } else {
-                leaves.push_back(LeafSeg{lc.begin, (uint32_t)lc.id, (uint32_t)wcur, lc.len});
-                leaves.push_back(LeafSeg{rc.begin, (uint32_t)rc.id, (uint32_t)wcur, rc.len});
+                leaves.push_back(LeafSeg{lc.begin, (uint32_t)lc.id, (uint32_t)child_buf, lc.len});
+                leaves.push_back(LeafSeg{rc.begin, (uint32_t)rc.id, (uint32_t)child_buf, rc.len});
             }
         }
         if (children_need_hist && !with_hist) {
@@ -980,8 +1018,8 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                 if (st != GBT_OK) return st;
                 gbt_prof_begin(ctx, GBT_PROF_HIST_NODE,
                                j0 == 0 ? (double)built_rows * ((double)row_bits / 8.0 + 8.0) : 0.0);
-                GBT_HIP(ctx, gbt_launch_hist(ctx, cur.sym, bits, cur.stride_bits, cur.n_words, n, B,
-                                             (uint32_t)missing_sym, nullptr, cur.gq, pool,
+                GBT_HIP(ctx, gbt_launch_hist(ctx, W[wnext].sym, bits, W[wnext].stride_bits, W[wnext].n_words, n, B,
+                                             (uint32_t)missing_sym, nullptr, W[wnext].gq, pool,
                                              (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
                 gbt_prof_end(ctx);
             }
@@ -996,8 +1034,10 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
         }
         level.swap(next);
     }
-    // nodes still open when the depth limit (or an empty level) ended the loop are leaves
-    for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)wcur, nd.len});
+    // whatever is still waiting when nothing splits any more is a leaf
+    for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)nd.buf, nd.len});
+    for (const OpenLeaf &ol : open_leaves)
+        leaves.push_back(LeafSeg{ol.nd.begin, (uint32_t)ol.nd.id, (uint32_t)ol.nd.buf, ol.nd.len});
     if (!tracked) {
         GBT_SYNC(ctx);
         tree->n_nodes = n_nodes;
@@ -1017,6 +1057,30 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     GBT_SYNC(ctx);
     tree->n_nodes = n_nodes;
     return GBT_OK;
+}
+
+extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                 int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
+                                 const gbt_params *params, gbt_tree *tree, uint32_t *row_idx_out,
+                                 int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes) {
+    return grow_impl(ctx, packed, bits, n, F, missing_sym, nb, cuts, gpair, params, GBT_POLICY_DEPTHWISE, 0, tree,
+                     row_idx_out, leaf_of_row_out, workspace, workspace_bytes);
+}
+
+extern "C" size_t gbt_grow_tree_lossguide_workspace_bytes(int64_t n, int32_t F, int32_t bits, int32_t max_bins,
+                                                          int32_t max_leaves) {
+    if (n < 0 || F < 1 || bits < 1 || bits > GBT_MAX_BITS || max_bins < 2 || max_leaves < 1 || max_leaves > kMaxLeaves)
+        return 0;
+    return grow_layout_nodes(n, F, bits, max_bins, 2 * (int64_t)max_leaves - 1, 1).total;
+}
+
+extern "C" int32_t gbt_grow_tree_lossguide(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                           int32_t missing_sym, const int32_t *nb, const float *cuts,
+                                           const float *gpair, const gbt_params *params, int32_t max_leaves,
+                                           gbt_tree *tree, uint32_t *row_idx_out, int32_t *leaf_of_row_out,
+                                           void *workspace, size_t workspace_bytes) {
+    return grow_impl(ctx, packed, bits, n, F, missing_sym, nb, cuts, gpair, params, GBT_POLICY_LOSSGUIDE, max_leaves,
+                     tree, row_idx_out, leaf_of_row_out, workspace, workspace_bytes);
 }
 
 // ----------------------------------------------------------------- predict --
