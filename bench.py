@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--data-cache", default=None, help="directory to keep the generated inputs in")
     ap.add_argument("--cpu-sample-rows", type=int, default=4_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--policy", choices=["depthwise", "lossguide"], default="depthwise",
+                    help="node expansion order (Sec. 2.3); lossguide grows --max-leaves leaves, no depth cap")
+    ap.add_argument("--max-leaves", type=int, default=0, help="lossguide: leaf budget (default 2^max_depth)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of the packed matrix (a kernel of known size to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -163,6 +166,10 @@ def main():
           else torch.empty((n, 2), dtype=torch.float32, device=dev))
     params = g.make_params(max_depth=p["max_depth"], max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
                            min_child_weight=p["min_child_weight"], eta=p["eta"], objective=p["objective"])
+    lossguide = a.policy == "lossguide"
+    max_leaves = a.max_leaves or 2 ** p["max_depth"]
+    lg_params = g.make_params(max_depth=64, max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
+                              min_child_weight=p["min_child_weight"], eta=p["eta"], objective=p["objective"])
     single_tree = p["rounds"] == 1   # such a workload is ONE tree from margin 0: every step repeats exactly that
     eta = p["eta"]
     trees = []
@@ -172,7 +179,11 @@ def main():
             margin.zero_()
         if not given:
             ctx.gradients(p["objective"], margin, y, out=gp)
-        tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=False)
+        if lossguide:
+            tree, _, _ = ctx.grow_tree_lossguide(packed, bits, n, F, ms, nb, cuts, gp, lg_params, max_leaves,
+                                                 want_rows=False)
+        else:
+            tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=False)
         ctx.predict([tree], margin, eta, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
         trees.append(tree)
 
@@ -233,8 +244,9 @@ def main():
 
     out = {
         "metric": "histogram-tree build throughput: rows*features/s of one boosting step "
-                  "(%sone depth-%d tree%s)" % ("" if given else "gradients + ", p["max_depth"],
-                                              "" if given else " + margin update"),
+                  "(%sone %s tree%s)" % ("" if given else "gradients + ",
+                                         ("loss-guided %d-leaf" % max_leaves) if lossguide else ("depth-%d" % p["max_depth"]),
+                                         "" if given else " + margin update"),
         "value": n * F / (ms_per_step * 1e-3),
         "unit": "rows*features/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
@@ -243,7 +255,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"C{a.config}: {n} rows x {F} features, {p['max_bins']} bins, {bits}-bit packing, "
                                f"depth {p['max_depth']}, lambda {p['lam']}, {p['objective']} objective",
-                   "rows": n, "features": F, "bits": bits, "max_depth": p["max_depth"]},
+                   "rows": n, "features": F, "bits": bits, "max_depth": p["max_depth"],
+                   "policy": a.policy, **({"max_leaves": max_leaves} if lossguide else {})},
         "seconds_per_tree": ms_per_step * 1e-3,
         "hist_root_ms": root_ms,
         "hist_root_rows_features_per_s": (n * F / (root_ms * 1e-3)) if root_ms > 0 else None,
