@@ -235,12 +235,25 @@ GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits,
                                              int32_t max_depth);
 
 /*
+ * How gbt_grow_tree moves the rows of splitting nodes for this shape (for
+ * profiling and tests; the result of gbt_grow_tree does not depend on it):
+ *   0  three launches per level (flags, offsets, move), row order kept
+ *   1  one launch per level, row order not kept (only when track_rows == 0)
+ *   2  as 1, and the launch also builds one child's histogram of every split
+ *      node (8-bit symbols, at most 16 features)
+ * Negative: a GBT_E* code.
+ */
+GBT_API int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_t max_bins, int32_t track_rows);
+
+/*
  * Grows one tree depth-wise (Alg. 1 with the "closest to the root first"
  * policy): root histogram; per level evaluate the open nodes, partition the
  * rows of those that split (whole records -- symbols, gradient pair, row id --
  * move inside the workspace so that each node's rows stay contiguous), build
- * the histogram of each split's smaller child (fewer rows, tie -> left) and get
- * the larger one by subtraction.  A node is
+ * the histogram of one child of each split from its rows (the one with fewer
+ * rows, tie -> left; where partition and histogram run as one pass, the one
+ * with the smaller hessian sum) and get the other one by subtraction; sums are
+ * exact integers, so the choice changes no value.  A node is
  * split iff it has a valid candidate with gain > max(gamma, GBT_GAIN_FLOOR) and
  * depth < max_depth.  Leaf weight = -G/(H+lambda).
  *   packed, bits, n, F, missing_sym : packed matrix [dev]
@@ -255,17 +268,6 @@ GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits,
  *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL)
  * Synchronises the stream.
  */
-/*
- * How gbt_grow_tree moves the rows of splitting nodes for this shape (for
- * profiling and tests; the result of gbt_grow_tree does not depend on it):
- *   0  three launches per level (flags, offsets, move), row order kept
- *   1  one launch per level, row order not kept (only when track_rows == 0)
- *   2  as 1, and the launch also builds one child's histogram of every split
- *      node (8-bit symbols, at most 16 features)
- * Negative: a GBT_E* code.
- */
-GBT_API int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_t max_bins, int32_t track_rows);
-
 GBT_API int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                       int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
                       const gbt_params *params, gbt_tree *tree_out, uint32_t *row_idx_out,
