@@ -181,9 +181,9 @@ def main():
             ctx.gradients(p["objective"], margin, y, out=gp)
         if lossguide:
             tree, _, _ = ctx.grow_tree_lossguide(packed, bits, n, F, ms, nb, cuts, gp, lg_params, max_leaves,
-                                                 want_rows=False)
+                                                 want_rows=False, want_leaf=False)
         else:
-            tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=False)
+            tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=False, want_leaf=False)
         ctx.predict([tree], margin, eta, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
         trees.append(tree)
 

@@ -263,9 +263,11 @@ GBT_API int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_
  *   row_idx_out [dev] uint32[n]  final row order: each node's rows are one
  *                                ascending run, left child's run first.  May be
  *                                NULL: then row ids are not carried through the
- *                                partitions (less memory traffic) and only the
- *                                tree is produced; leaf_of_row_out must be NULL too
- *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL)
+ *                                partitions (less memory traffic, the faster
+ *                                partition forms)
+ *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL).  Without
+ *                                row_idx_out it comes from one walk of the
+ *                                finished tree over the packed matrix
  * Synchronises the stream.
  */
 GBT_API int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,

@@ -332,11 +332,12 @@ class Context:
     def grow_tree(self, packed, bits, n, F, missing_sym, nb, cuts, gpair, params: Params, want_leaf=True,
                   row_idx_out=None, leaf_out=None, want_rows=True):
         """Returns (tree dict of numpy arrays, row_idx int32 tensor [n], leaf_of_row int32 tensor [n]).
-        want_rows=False: only the tree is produced (row_idx and leaf_of_row are None)."""
+        want_rows=False: the final row order is not produced (row_idx is None), which lets the library
+        take its faster partition paths; leaf_of_row is still available (want_leaf)."""
         t = new_tree(params.max_depth)
         ts = _tree_struct(t)
         if not want_rows:
-            want_leaf, row_idx = False, None
+            row_idx = None
         else:
             row_idx = row_idx_out if row_idx_out is not None else self.empty((n,), torch.int32)
         leaf = (leaf_out if leaf_out is not None else self.empty((n,), torch.int32)) if want_leaf else None
@@ -356,7 +357,7 @@ class Context:
         t = new_tree_leaves(max_leaves)
         ts = _tree_struct(t)
         row_idx = self.empty((n,), torch.int32) if want_rows else None
-        leaf = self.empty((n,), torch.int32) if (want_rows and want_leaf) else None
+        leaf = self.empty((n,), torch.int32) if want_leaf else None
         ws_bytes = self.lib.gbt_grow_tree_lossguide_workspace_bytes(n, F, bits, params.max_bins, max_leaves)
         if ws_bytes == 0:
             raise GbtError(EINVAL, "gbt_grow_tree_lossguide_workspace_bytes rejected the shape")

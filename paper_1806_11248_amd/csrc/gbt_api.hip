@@ -557,7 +557,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
 namespace {
 
 struct GrowLayout {
-    size_t gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, splits, jobs, scratch, total;
+    size_t tree_stage, tree_stage_bytes, gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, splits, jobs, scratch, total;
     int64_t hist_nodes, level_nodes, tiles, w_words;
     int sw;   // 32-bit words per row of the working copies
 };
@@ -593,6 +593,11 @@ GrowLayout grow_layout_nodes(int64_t n, int F, int bits, int B, int64_t hist_nod
     L.splits = o;     o += gbt_align(GBT_STAGING_BYTES / 2);   // per-(node, feature chunk) records of one level
     L.jobs = o;       o += gbt_align(kUploadBytes);
     L.scratch = o;    o += 4096;
+    // room to stage the finished tree for a walk (as gbt_predict_workspace_bytes counts it); a tree has
+    // at most 2 * hist_nodes + 1 nodes under either policy
+    const size_t cap_nodes = (size_t)(2 * hist_nodes + 1);
+    L.tree_stage_bytes = gbt_align(64) + gbt_align(cap_nodes * 4) * 6 + gbt_align(cap_nodes * 8) + 256;
+    L.tree_stage = o; o += gbt_align(L.tree_stage_bytes);
     L.total = o;
     return L;
 }
@@ -640,6 +645,10 @@ extern "C" int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int
     return grow_path(ctx, F, bits, max_bins, track_rows != 0, pl.n_ftiles);
 }
 
+static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
+                            int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
+                            float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes);
+
 // Alg. 1 under either policy of Sec. 2.3.  Growth proceeds in rounds: the nodes created by the round
 // before are evaluated; depth-wise then splits every one of them that may split, loss-guided only
 // the open leaf with the largest gain (smaller id on equal gains), however long ago it was created.
@@ -651,7 +660,6 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     int32_t st = check_matrix(ctx, packed, bits, n, F);
     if (st != GBT_OK) return st;
     GBT_REQUIRE(ctx, nb && cuts && gpair && params && tree && workspace, GBT_EINVAL, "NULL argument");
-    GBT_REQUIRE(ctx, row_idx_out || !leaf_of_row_out, GBT_EINVAL, "leaf_of_row_out needs row_idx_out");
     const bool tracked = row_idx_out != nullptr;   // else row ids are not carried along
     const int B = params->max_bins, max_depth = params->max_depth;
     st = check_bins(ctx, F, B);
@@ -1039,8 +1047,16 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     for (const OpenLeaf &ol : open_leaves)
         leaves.push_back(LeafSeg{ol.nd.begin, (uint32_t)ol.nd.id, (uint32_t)ol.nd.buf, ol.nd.len});
     if (!tracked) {
-        GBT_SYNC(ctx);
         tree->n_nodes = n_nodes;
+        if (leaf_of_row_out) {
+            // the rows were not followed: one walk of the finished tree over the matrix names each row's leaf
+            gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (row_bits / 8.0 + 4.0));
+            st = predict_impl(ctx, tree, 1, packed, bits, missing_sym, nullptr, n, F, 0.0, nullptr, leaf_of_row_out,
+                              ws + L.tree_stage, L.tree_stage_bytes);
+            gbt_prof_end(ctx);
+            if (st != GBT_OK) return st;
+        }
+        GBT_SYNC(ctx);
         return GBT_OK;
     }
 
@@ -1095,11 +1111,12 @@ extern "C" size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_t
     return o + 256;
 }
 
-extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
-                               int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
-                               float *margin, void *workspace, size_t workspace_bytes) {
-    if (!ctx) return GBT_EINVAL;
-    GBT_REQUIRE(ctx, trees && margin && workspace, GBT_EINVAL, "NULL argument");
+// Stages the trees in `workspace` and walks them: margin += eta * leaf weight per tree, or (leaf_out,
+// one tree) the id of each row's leaf.  Does not synchronise.
+static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
+                            int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
+                            float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes) {
+    GBT_REQUIRE(ctx, trees && (margin || leaf_out) && workspace, GBT_EINVAL, "NULL argument");
     GBT_REQUIRE(ctx, (packed != nullptr) != (X != nullptr), GBT_EINVAL, "give exactly one of packed and X");
     GBT_REQUIRE(ctx, n >= 0 && F >= 1 && n_trees >= 0, GBT_EINVAL, "bad shape");
     if (packed) {
@@ -1156,7 +1173,19 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
     int max_nodes = 1;
     for (int t = 0; t < n_trees; ++t) max_nodes = std::max(max_nodes, trees[t].n_nodes);
     GBT_HIP(ctx, gbt_launch_predict(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees, packed,
-                                    bits, (uint32_t)missing_sym, X, n, F, eta, margin, max_nodes, compact_ok));
+                                    bits, (uint32_t)missing_sym, X, n, F, eta, margin, leaf_out, max_nodes,
+                                    compact_ok));
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
+                               int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
+                               float *margin, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, margin != nullptr, GBT_EINVAL, "NULL argument");
+    int32_t st = predict_impl(ctx, trees, n_trees, packed, bits, missing_sym, X, n, F, eta, margin, nullptr, workspace,
+                              workspace_bytes);
+    if (st != GBT_OK) return st;
     GBT_SYNC(ctx);
     return GBT_OK;
 }

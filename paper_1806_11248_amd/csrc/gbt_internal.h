@@ -210,7 +210,8 @@ struct DevTree {   // one tree's arrays inside the predict workspace (offsets in
 };
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
-                              int64_t n, int F, double eta, float *margin, int max_nodes, bool compact_ok);
+                              int64_t n, int F, double eta, float *margin, int32_t *leaf_out, int max_nodes,
+                              bool compact_ok);   // leaf_out != NULL: store each row's leaf id instead of updating margin
 // compact_ok: every split node has right == left + 1, feature < 2^20 and bin < 4096
 
 // quantise

@@ -277,11 +277,11 @@ __device__ inline uint32_t load_symbol(const uint32_t *packed, uint64_t elem, in
 // Sec. 2.4: one instance per thread, trees in order, walking from the root.
 __global__ void predict_kernel(const char *ws, const DevTree *trees, int n_trees,
                                const uint32_t *packed, int bits, uint32_t missing, const float *X,
-                               int64_t n, int F, double eta, float *margin) {
+                               int64_t n, int F, double eta, float *margin, int32_t *leaf_out) {
     const uint32_t mask = (1u << bits) - 1u;
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n;
          r += (int64_t)gridDim.x * blockDim.x) {
-        double m = margin[r];
+        double m = margin ? margin[r] : 0.0;
         for (int t = 0; t < n_trees; ++t) {
             DevTree T = trees[t];
             const int32_t *feature = (const int32_t *)(ws + T.feature);
@@ -308,8 +308,9 @@ __global__ void predict_kernel(const char *ws, const DevTree *trees, int n_trees
                 node = go_left ? left[node] : right[node];
             }
             m = (double)(float)(m + eta * weight[node]);
+            if (leaf_out) leaf_out[r] = node;   // leaf mode: the caller passes one tree
         }
-        margin[r] = (float)m;
+        if (margin) margin[r] = (float)m;
     }
 }
 
@@ -324,7 +325,7 @@ struct LdsNode {
 __global__ __launch_bounds__(256) void predict_lds_kernel(const char *ws, const DevTree *trees, int n_trees,
                                                           const uint32_t *packed, int bits, uint32_t missing,
                                                           const float *X, int64_t n, int F, double eta,
-                                                          float *margin, int rows_per_block) {
+                                                          float *margin, int rows_per_block, int32_t *leaf_out) {
     extern __shared__ LdsNode nodes[];
     const uint32_t mask = (1u << bits) - 1u;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
@@ -365,7 +366,8 @@ __global__ __launch_bounds__(256) void predict_lds_kernel(const char *ws, const 
                 }
                 node = go_left ? nd.left : nd.right;
             }
-            margin[r] = (float)((double)margin[r] + eta * nodes[node].weight);
+            if (leaf_out) leaf_out[r] = node;
+            else margin[r] = (float)((double)margin[r] + eta * nodes[node].weight);
         }
     }
 }
@@ -385,7 +387,8 @@ constexpr int kPredRows = 4;
 __global__ __launch_bounds__(256) void predict_window_kernel(const char *ws, const DevTree *trees, int n_trees,
                                                              const uint32_t *packed, int64_t n_words, int bits,
                                                              uint32_t missing, int64_t n, int F, double eta,
-                                                             float *margin, int rows_per_block, int max_nodes) {
+                                                             float *margin, int rows_per_block, int max_nodes,
+                                                             int32_t *leaf_out) {
     extern __shared__ uint2 cnodes[];
     double *lweight = (double *)(cnodes + max_nodes);
     const uint32_t mask = (1u << bits) - 1u;
@@ -425,7 +428,7 @@ __global__ __launch_bounds__(256) void predict_window_kernel(const char *ws, con
                 for (int k = 0; k < 5; ++k) w[k] = packed[w0 + k < n_words ? w0 + k : n_words - 1];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) W[q][k] = __builtin_amdgcn_alignbit(w[k + 1], w[k], sh);
-                m[q] = margin[r];
+                m[q] = leaf_out ? 0.f : margin[r];
             }
             uint32_t node[kPredRows];
 #pragma unroll
@@ -444,7 +447,10 @@ __global__ __launch_bounds__(256) void predict_window_kernel(const char *ws, con
 #pragma unroll
             for (int q = 0; q < kPredRows; ++q) {
                 const int64_t r = rb + 256 * q;
-                if (r < r1) margin[r] = (float)((double)m[q] + eta * lweight[node[q]]);
+                if (r < r1) {
+                    if (leaf_out) leaf_out[r] = (int32_t)node[q];
+                    else margin[r] = (float)((double)m[q] + eta * lweight[node[q]]);
+                }
             }
         }
     }
@@ -461,7 +467,7 @@ template <bool MISS>
 __global__ __launch_bounds__(256) void predict_b8_kernel(const char *ws, const DevTree *trees, int n_trees,
                                                          const uint32_t *packed, int64_t n_words, uint32_t missing,
                                                          int64_t n, int F, double eta, float *margin,
-                                                         int rows_per_block, int max_nodes) {
+                                                         int rows_per_block, int max_nodes, int32_t *leaf_out) {
     extern __shared__ uint2 cnodes[];
     double *lweight = (double *)(cnodes + max_nodes);
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
@@ -501,7 +507,7 @@ __global__ __launch_bounds__(256) void predict_b8_kernel(const char *ws, const D
                 for (int k = 0; k < 5; ++k) w[k] = packed[w0 + k < n_words ? w0 + k : n_words - 1];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) W[q][k] = __builtin_amdgcn_alignbyte(w[k + 1], w[k], a);
-                m[q] = margin[r];
+                m[q] = leaf_out ? 0.f : margin[r];
             }
             uint32_t node[kPredRows];
 #pragma unroll
@@ -521,7 +527,10 @@ __global__ __launch_bounds__(256) void predict_b8_kernel(const char *ws, const D
 #pragma unroll
             for (int q = 0; q < kPredRows; ++q) {
                 const int64_t r = rb + 256 * q;
-                if (r < r1) margin[r] = (float)((double)m[q] + eta * lweight[node[q]]);
+                if (r < r1) {
+                    if (leaf_out) leaf_out[r] = (int32_t)node[q];
+                    else margin[r] = (float)((double)m[q] + eta * lweight[node[q]]);
+                }
             }
         }
     }
@@ -641,7 +650,8 @@ hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_ele
 }
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
-                              int64_t n, int F, double eta, float *margin, int max_nodes, bool compact_ok) {
+                              int64_t n, int F, double eta, float *margin, int32_t *leaf_out, int max_nodes,
+                              bool compact_ok) {
     if (n <= 0) return hipSuccess;
     const size_t lds = (size_t)max_nodes * sizeof(LdsNode);
     static_assert(sizeof(LdsNode) >= 16, "the register-window kernel stages 16 bytes per node");
@@ -677,22 +687,22 @@ hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *tree
                 }
                 if (missing < 256u)
                     predict_b8_kernel<true><<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, missing,
-                                                                            n, F, eta, margin, rows_per_block, max_nodes);
+                                                                            n, F, eta, margin, rows_per_block, max_nodes, leaf_out);
                 else
                     predict_b8_kernel<false><<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, missing,
-                                                                             n, F, eta, margin, rows_per_block, max_nodes);
+                                                                             n, F, eta, margin, rows_per_block, max_nodes, leaf_out);
                 return hipGetLastError();
             }
             predict_window_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, bits, missing,
-                                                                   n, F, eta, margin, rows_per_block, max_nodes);
+                                                                   n, F, eta, margin, rows_per_block, max_nodes, leaf_out);
             return hipGetLastError();
         }
         predict_lds_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, bits, missing, X, n, F, eta,
-                                                            margin, rows_per_block);
+                                                            margin, rows_per_block, leaf_out);
         return hipGetLastError();
     }
     predict_kernel<<<grid_for(n, kBlock, 1 << 16), kBlock, 0, s>>>(ws, trees, n_trees, packed, bits,
-                                                                    missing, X, n, F, eta, margin);
+                                                                    missing, X, n, F, eta, margin, leaf_out);
     return hipGetLastError();
 }
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,

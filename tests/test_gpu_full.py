@@ -120,9 +120,11 @@ def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True):
         # the launch configuration the benchmark times: no row order asked for (one-launch partition,
         # with one child's histogram in the same pass where the shape allows) -- the same tree
         t0 = time.time()
-        bare, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_t, params, want_rows=False)
+        bare, _, leaf2 = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_t, params, want_rows=False)
         torch.cuda.synchronize()
         nn = tree["n_nodes"]
+        assert np.array_equal(leaf2.cpu().numpy(), rep["leaf_of_row"])
+        del leaf2
         _say(f"  round {r}: same tree without row ids in {(time.time() - t0) * 1e3:.1f} ms "
              f"(path {ctx.grow_tree_path(F, bits, B, track_rows=False)})")
         assert bare["n_nodes"] == nn

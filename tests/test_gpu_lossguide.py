@@ -40,7 +40,8 @@ def _judge(ctx, oracle, o, gdev, gp, p, n, F, max_leaves):
     # the same tree when row ids are not carried along (one-launch partition paths)
     bare, r2, l2 = ctx.grow_tree_lossguide(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"],
                                            gdev["cuts"], gp_t, params, max_leaves, want_rows=False)
-    assert r2 is None and l2 is None and bare["n_nodes"] == nn
+    assert r2 is None and bare["n_nodes"] == nn
+    assert np.array_equal(l2.cpu().numpy(), rep["leaf_of_row"])
     for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
               "sumG", "sumH"):
         assert np.array_equal(bare[k][:nn], tree[k][:nn]), k

@@ -65,9 +65,13 @@ def grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, nodes=None):
             assert tree["threshold"][i] == want
     rep["scale"] = scale
     # the same tree when row ids are not carried along
-    bare, none_rows, none_leaf = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"],
-                                               gdev["cuts"], gp_t, params, want_rows=False)
-    assert none_rows is None and none_leaf is None and bare["n_nodes"] == nn
+    bare, none_rows, leaf2 = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"],
+                                           gdev["cuts"], gp_t, params, want_rows=False)
+    assert none_rows is None and bare["n_nodes"] == nn
+    assert np.array_equal(leaf2.cpu().numpy(), rep["leaf_of_row"])    # leaf ids from a walk of the finished tree
+    only_tree = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"], gdev["cuts"], gp_t,
+                              params, want_rows=False, want_leaf=False)
+    assert only_tree[1] is None and only_tree[2] is None and only_tree[0]["n_nodes"] == nn
     for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
               "sumG", "sumH"):
         assert np.array_equal(bare[k][:nn], tree[k][:nn]), k
