@@ -251,7 +251,9 @@ def main():
         "unit": "rows*features/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int64 fixed-point sums of fp32 gradient pairs; fp64 gain",
+        "dtype": "int64",
+        "dtype_note": "histogram sums are exact 64-bit integers of fixed-point (26/22-bit) roundings of the fp32 "
+                      "gradient pairs; split gains fp64",
         "data": "synthetic",
         "config": {"workload": f"C{a.config}: {n} rows x {F} features, {p['max_bins']} bins, {bits}-bit packing, "
                                f"depth {p['max_depth']}, lambda {p['lam']}, {p['objective']} objective",
