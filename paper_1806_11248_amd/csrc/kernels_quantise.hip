@@ -370,23 +370,44 @@ __device__ inline uint32_t bin_of(const float *c, int ncut, float x) {
     return (uint32_t)lo;
 }
 
-__global__ void bin_dense_kernel(const float *__restrict__ X, int64_t n_elems, int F, int B,
-                                 const float *__restrict__ cuts, const int32_t *__restrict__ nb,
-                                 uint32_t missing, uint16_t *__restrict__ sym, uint32_t *__restrict__ max_out) {
+// LDS_CUTS: the cut table (F * (B-1) floats) and nb are staged in LDS first, so the bisection's
+// dependent reads stay on the CU (the table is 13 KB for 13 x 256 bins).  The feature of an element
+// is carried along instead of a 64-bit modulo per element.
+template <bool LDS_CUTS>
+__global__ __launch_bounds__(256) void bin_dense_kernel(const float *__restrict__ X, int64_t n_elems, int F, int B,
+                                                        const float *__restrict__ cuts, const int32_t *__restrict__ nb,
+                                                        uint32_t missing, uint16_t *__restrict__ sym,
+                                                        uint32_t *__restrict__ max_out) {
+    extern __shared__ float lcuts[];
+    int32_t *lnb = (int32_t *)(lcuts + (LDS_CUTS ? F * (B - 1) : 0));
+    if (LDS_CUTS) {
+        for (int i = threadIdx.x; i < F * (B - 1); i += 256) lcuts[i] = cuts[i];
+        for (int i = threadIdx.x; i < F; i += 256) lnb[i] = nb[i];
+        __syncthreads();
+    }
+    const float *ct = LDS_CUTS ? lcuts : cuts;
+    const int32_t *nbt = LDS_CUTS ? lnb : nb;
     uint32_t mx = 0;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_elems;
-         e += (int64_t)gridDim.x * blockDim.x) {
-        const int f = (int)(e % F);
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int step_f = (int)(stride % F);
+    int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int f = (int)(e % F);
+    for (; e < n_elems; e += stride) {
         const float x = X[e];
-        const uint32_t s = (x != x) ? missing : bin_of(cuts + (int64_t)f * (B - 1), nb[f] - 1, x);
+        const uint32_t s = (x != x) ? missing : bin_of(ct + f * (B - 1), nbt[f] - 1, x);
         sym[e] = (uint16_t)s;
         mx = s > mx ? s : mx;
+        f += step_f;
+        f = f >= F ? f - F : f;
     }
     for (int o = 32; o > 0; o >>= 1) {
         const uint32_t t = (uint32_t)__shfl_xor((int)mx, o);
         mx = t > mx ? t : mx;
     }
-    if ((threadIdx.x & 63) == 0) atomicMax(max_out, mx);
+    __shared__ uint32_t wmax[4];
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicMax(max_out, max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3])));
 }
 
 __global__ void fill_u16_kernel(uint16_t *p, uint16_t v, int64_t count) {
@@ -546,8 +567,20 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     Q_HIP(gbt_launch_fill_u64(s, (uint64_t *)misc, 0, 1));
     if (n > 0) {
         if (dense) {
-            bin_dense_kernel<<<grid_for(n * (int64_t)F, 1024, 16384), 256, 0, s>>>(X, n * (int64_t)F, F, B, cuts, nb,
-                                                                                    (uint32_t)miss, sym, misc);
+            const size_t cut_bytes = ((size_t)F * (B - 1) + (size_t)F) * 4;
+            if (cut_bytes <= 60u * 1024u) {
+                static size_t configured = 0;
+                if (cut_bytes > configured) {
+                    Q_HIP(hipFuncSetAttribute((const void *)bin_dense_kernel<true>,
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)cut_bytes));
+                    configured = cut_bytes;
+                }
+                bin_dense_kernel<true><<<grid_for(n * (int64_t)F, 4096, 8192), 256, cut_bytes, s>>>(
+                    X, n * (int64_t)F, F, B, cuts, nb, (uint32_t)miss, sym, misc);
+            } else {
+                bin_dense_kernel<false><<<grid_for(n * (int64_t)F, 1024, 16384), 256, 0, s>>>(
+                    X, n * (int64_t)F, F, B, cuts, nb, (uint32_t)miss, sym, misc);
+            }
         } else {
             fill_u16_kernel<<<grid_for(n * (int64_t)F, 2048, 16384), 256, 0, s>>>(sym, (uint16_t)miss,
                                                                                    n * (int64_t)F);
