@@ -57,6 +57,25 @@ __global__ __launch_bounds__(256) void dense_keys_kernel(const float *__restrict
     }
 }
 
+// Few features (F <= 64): a tile of 256 whole rows is one contiguous piece of X; it is read linearly
+// (every lane busy, whole lines), kept in LDS with an odd row stride, and written out column by column.
+constexpr int kTrNarrowRows = 256;
+__global__ __launch_bounds__(256) void dense_keys_narrow_kernel(const float *__restrict__ X, int64_t n, int F,
+                                                                uint32_t *__restrict__ keys) {
+    extern __shared__ uint32_t ntile[];   // [kTrNarrowRows][F | 1]
+    const int stride = F | 1;
+    const int64_t r0 = (int64_t)blockIdx.x * kTrNarrowRows;
+    const int rows = n - r0 < kTrNarrowRows ? (int)(n - r0) : kTrNarrowRows;
+    const float *src = X + r0 * F;
+    for (int i = threadIdx.x; i < rows * F; i += 256) {
+        const int r = i / F, f = i - r * F;
+        ntile[r * stride + f] = float_key(src[i]);
+    }
+    __syncthreads();
+    for (int f = 0; f < F; ++f)
+        if ((int)threadIdx.x < rows) keys[(int64_t)f * n + r0 + threadIdx.x] = ntile[threadIdx.x * stride + f];
+}
+
 // ---- 1b. CSR input: count, offset, scatter by column -----------------------
 // Workgroups take chunks of kCsrChunk stored values and count columns in LDS first, so that
 // HBM sees one atomic per (chunk, column) instead of one per value.  Columns beyond
@@ -155,6 +174,19 @@ __global__ void offsets_kernel(const uint32_t *counts, int F, int64_t fixed_len,
 }
 
 // ---- 2. segmented radix sort ----------------------------------------------
+// One count per key into a 256-bin LDS histogram.  Sorted or low-cardinality data gives a whole wave
+// the same digit, which as 64 atomics on one address would take 64 turns: that case is one add.
+__device__ inline void count_digit(uint32_t *h, uint32_t d, bool live) {
+    const uint64_t act = __ballot(live);
+    if (act == 0) return;
+    const uint32_t lead = (uint32_t)__builtin_amdgcn_readlane((int)d, (int)__builtin_ctzll(act));
+    if (__ballot(live && d == lead) == act) {
+        if ((threadIdx.x & 63) == (uint32_t)__builtin_ctzll(act)) atomicAdd(&h[lead], (uint32_t)__popcll(act));
+    } else if (live) {
+        atomicAdd(&h[d], 1u);
+    }
+}
+
 __device__ inline int find_segment(const uint32_t *blk_off, int F, uint32_t blk) {
     int lo = 0, hi = F;   // last f with blk_off[f] <= blk and a non-empty tile range
     while (hi - lo > 1) {
@@ -175,9 +207,18 @@ __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const uint32_t *_
     const int f = find_segment(blk_off, F, blk);
     const uint64_t base = seg_off[f], len = seg_off[f + 1] - base;
     const uint64_t t0 = (uint64_t)(blk - blk_off[f]) * kSortTile;
-    for (int i = threadIdx.x; i < kSortTile; i += kSortBlock) {
-        const uint64_t p = t0 + i;
-        if (p < len) atomicAdd(&h[(keys[base + p] >> shift) & 255u], 1u);
+    if (t0 + kSortTile <= len) {   // a whole tile: all loads are issued before the first count
+        uint32_t k[kSortTile / kSortBlock];
+#pragma unroll
+        for (int j = 0; j < kSortTile / kSortBlock; ++j) k[j] = keys[base + t0 + (uint64_t)j * kSortBlock + threadIdx.x];
+#pragma unroll
+        for (int j = 0; j < kSortTile / kSortBlock; ++j) count_digit(h, (k[j] >> shift) & 255u, true);
+    } else {
+        for (int i0 = 0; i0 < kSortTile; i0 += kSortBlock) {   // uniform trip count: count_digit uses ballots
+            const uint64_t p = t0 + i0 + threadIdx.x;
+            const bool live = p < len;
+            count_digit(h, live ? (keys[base + p] >> shift) & 255u : 0u, live);
+        }
     }
     __syncthreads();
     tile_hist[(uint64_t)blk * 256 + threadIdx.x] = h[threadIdx.x];
@@ -243,17 +284,26 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(const uint32_t *__restr
     }
 }
 
+// Stable scatter of one tile.  The tile's keys are first put in digit order inside LDS (ranks from
+// per-wave digit counts and, inside a round of 64 keys, from ballots), then copied out: consecutive
+// threads hold consecutive keys of a digit's run, so the run goes to HBM as whole lines instead of
+// 64 separate 4-byte stores per wave instruction.
 __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const uint32_t *__restrict__ src,
                                                                   uint32_t *__restrict__ dst,
                                                                   const uint64_t *__restrict__ seg_off,
                                                                   const uint32_t *__restrict__ blk_off, int F,
                                                                   int shift,
                                                                   const uint32_t *__restrict__ tile_hist) {
-    __shared__ uint32_t cnt[kSortBlock / 64][256];   // per wave: running count per digit
+    __shared__ uint32_t cnt[kSortBlock / 64][256];   // per wave: running local position per digit
+    __shared__ uint32_t local_start[256];            // first local position of each digit's run
+    __shared__ uint32_t run_base[256];               // position in the segment of each digit's run
+    __shared__ uint32_t stage[kSortTile];
+    static_assert(kSortBlock == 256, "one thread per digit below");
     const uint32_t blk = blockIdx.x;
     const int f = find_segment(blk_off, F, blk);
     const uint64_t base = seg_off[f], len = seg_off[f + 1] - base;
     const uint64_t t0 = (uint64_t)(blk - blk_off[f]) * kSortTile;
+    const uint32_t tile_keys = len - t0 < (uint64_t)kSortTile ? (uint32_t)(len - t0) : (uint32_t)kSortTile;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int i = threadIdx.x; i < (kSortBlock / 64) * 256; i += kSortBlock) (&cnt[0][0])[i] = 0;
     __syncthreads();
@@ -268,11 +318,27 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const uint32_t
         if (p < len) atomicAdd(&cnt[wave][(key[r] >> shift) & 255u], 1u);
     }
     __syncthreads();
-    // cnt[w][d] -> number of digit-d keys in the waves before w (exclusive over waves),
-    // plus the tile's position for digit d
+    // thread d: the tile's digit-d keys are [local_start[d], local_start[d] + total) inside the tile,
+    // wave w's share of them starts at cnt[w][d]
     {
-        const int d = threadIdx.x;   // 256 threads, one digit each
-        uint32_t run = tile_hist[(uint64_t)blk * 256 + d];
+        const int d = threadIdx.x;
+        uint32_t total = 0;
+        for (int w = 0; w < kSortBlock / 64; ++w) total += cnt[w][d];
+        // exclusive scan of the totals over the 256 digits
+        uint32_t x = total;
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t y = (uint32_t)__shfl_up((int)x, o);
+            if (lane >= o) x += y;
+        }
+        __shared__ uint32_t wave_tot[kSortBlock / 64];
+        if (lane == 63) wave_tot[wave] = x;
+        __syncthreads();
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        const uint32_t start = before + x - total;
+        local_start[d] = start;
+        run_base[d] = tile_hist[(uint64_t)blk * 256 + d];
+        uint32_t run = start;
         for (int w = 0; w < kSortBlock / 64; ++w) {
             const uint32_t c = cnt[w][d];
             cnt[w][d] = run;
@@ -298,7 +364,13 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const uint32_t
         __builtin_amdgcn_wave_barrier();
         if (live && below == 0) wc[dgt] = first + (uint32_t)__popcll(peers);   // ... before the leader bumps it
         __builtin_amdgcn_wave_barrier();
-        if (live) dst[base + first + below] = key[r];
+        if (live) stage[first + below] = key[r];   // first + below < tile_keys
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < tile_keys; i += kSortBlock) {
+        const uint32_t k = stage[i];
+        const uint32_t d = (k >> shift) & 255u;
+        dst[base + run_base[d] + (i - local_start[d])] = k;
     }
 }
 
@@ -509,7 +581,17 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     // 1. key segments
     if (dense) {
         offsets_kernel<<<1, 1, 0, s>>>(nullptr, F, n, seg_off, blk_off, chk_off, kScanChunk);
-        if (n > 0) {
+        if (n > 0 && F <= 64) {
+            const size_t lds = (size_t)kTrNarrowRows * (F | 1) * 4;   // at most 65 KB
+            static size_t configured = 0;
+            if (lds > configured) {
+                Q_HIP(hipFuncSetAttribute((const void *)dense_keys_narrow_kernel,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+                configured = lds;
+            }
+            dense_keys_narrow_kernel<<<(unsigned)((n + kTrNarrowRows - 1) / kTrNarrowRows), 256, lds, s>>>(X, n, F,
+                                                                                                           keys_a);
+        } else if (n > 0) {
             dim3 grid((unsigned)((n + kTrRows - 1) / kTrRows), (unsigned)((F + kTrCols - 1) / kTrCols));
             dense_keys_kernel<<<grid, 256, 0, s>>>(X, n, F, keys_a);
         }
