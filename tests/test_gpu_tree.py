@@ -180,6 +180,25 @@ def test_byte_symbols_up_to_16_features(ctx, oracle, F, B, miss):
     grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
 
 
+@pytest.mark.parametrize("F,B,miss", [(16, 200, 0.05), (6, 256, 0.0)])
+def test_byte_symbols_many_tiles(ctx, oracle, F, B, miss):
+    """The partition + histogram pass over millions of rows: spans of several tiles, cursors handed
+    out to hundreds of workgroups, the slot classes other than the 13-feature one."""
+    n = 2_500_003
+    d = synth.make(4, n)
+    rng = np.random.default_rng(77 + F)
+    X = d["X"][:, rng.integers(0, d["X"].shape[1], F)].copy()
+    X += rng.normal(0, 0.01, X.shape).astype(np.float32)
+    if miss > 0:
+        X[rng.random(X.shape) < miss] = np.nan
+    p = dict(d["params"], max_bins=B, max_depth=5)
+    _say(f"byte symbols, many tiles: n={n} F={F} B={B} missing={miss}")
+    o, gdev = gpu_prep(ctx, oracle, dict(X=X, params=p))
+    assert gdev["bits"] == 8 and ctx.grow_tree_path(F, 8, B, track_rows=False) == 2
+    gp = oracle.gradients(p["objective"], np.zeros(n, np.float32), d["y"])
+    grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, nodes={0, 1, 2, 5, 12, 20, 31, 40})
+
+
 def test_depth_zero_and_gamma(ctx, oracle):
     d = synth.make(1)
     p = dict(d["params"])
