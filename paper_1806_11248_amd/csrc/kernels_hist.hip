@@ -144,9 +144,10 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
 // Wider tiles are walked window by window, lanes starting at different windows.
 //
 // All atomics of a window are issued before the first returned word is examined,
-// so their latencies overlap.  A missing symbol, or a symbol >= B, is sent to a
-// spare "trash" row of 256 words behind the histogram instead of being
-// predicated.
+// so their latencies overlap.  A missing symbol, a symbol >= B or a slot past the
+// tile's last feature is sent to a spare "trash" row behind the histogram instead
+// of being predicated: word `lane` of it, so that no two lanes of an instruction
+// meet on one address (same-address atomics take turns).
 //   NS  : unrolled slots per window.  0: wide tile (16 slots, no permutation);
 //         otherwise the tile has at most NS <= 16 features (slots past the last
 //         feature fall into the trash row)
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
             int t = j + l0;
             t = t >= ft ? t - ft : t;          // (j + lane) mod ft for j < ft
             const bool live = j < ft;
-            pre[j] = live ? t * Bp : trash;
+            pre[j] = live ? t * Bp : trash + lane;   // a slot past the last feature: this lane's own trash word
             const uint32_t a = (live && t < 8) ? (uint32_t)t : 0x0Cu;           // 0x0C selects a zero byte
             const uint32_t b = (live && t >= 8) ? (uint32_t)(t - 8) : 0x0Cu;
             selA[j >> 2] |= a << (8 * (j & 3));
@@ -274,10 +275,11 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
 #pragma unroll
             for (int j = 0; j < SLOTS; ++j) {
                 const uint32_t s = (V[j >> 2] >> (8 * (j & 3))) & 0xffu;
-                const int base = SINGLE ? pre[j] : (j < nv ? (16 * c + j) * Bp : trash);
-                bool bad = false;
-                if (CHK) bad = (s == missing) | (s >= (uint32_t)B);
-                idx[j] = (bad ? trash : base) + (int)s;
+                const bool dead = !SINGLE && j >= nv;   // wide tile: a slot past the tile's last feature
+                const int base = SINGLE ? pre[j] : (16 * c + j) * Bp;
+                bool bad = dead;
+                if (CHK) bad |= (s == missing) | (s >= (uint32_t)B);
+                idx[j] = bad ? trash + lane : base + (int)s;   // trash: one word per lane, no two lanes collide
                 old[j] = atomicAdd(&main_[idx[j]], addv);
             }
 #pragma unroll
@@ -487,7 +489,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
             int t = j + l0;
             t = t >= ft ? t - ft : t;
             const bool live = j < ft;
-            pre[j] = live ? t * Bp : trash;
+            pre[j] = live ? t * Bp : trash + lane;   // a slot past the last feature: this lane's own trash word
             const uint32_t a = (live && t < 8) ? (uint32_t)t : 0x0Cu;
             const uint32_t b = (live && t >= 8) ? (uint32_t)(t - 8) : 0x0Cu;
             selA[j >> 2] |= a << (8 * (j & 3));
@@ -598,7 +600,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
                             const uint32_t sv = (V[t >> 2] >> (8 * (t & 3))) & 0xffu;
                             bool bad = false;
                             if (CHK) bad = (sv == missing) | (sv >= (uint32_t)B);
-                            idx[tt] = (bad ? trash : pre[t]) + (int)sv;
+                            idx[tt] = bad ? trash + lane : pre[t] + (int)sv;
                             old[tt] = atomicAdd(&main_[idx[tt]], addv);
                         }
                     }
