@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
 }  // namespace
 
 int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes) {
-    int chunks = (F + 63) / 64;   // about 64 features (16 per wave) per workgroup
+    int chunks = (F + 3) / 4;     // one feature per wave while that keeps the number of records small
     if (chunks > 64) chunks = 64;
     while (chunks > 1 && (size_t)n_nodes * chunks * sizeof(gbt_split) > record_budget_bytes) --chunks;
     return chunks < 1 ? 1 : chunks;
