@@ -870,7 +870,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         for (const HNode &nd : sel_nodes) part_rows += nd.len;
         // rows per partition workgroup: a tile, or (with the histogram) a span of tiles long enough
         // to be worth merging an LDS histogram into HBM for
-        uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile() : (uint32_t)GBT_PART_TILE;
+        uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile(W[wnext]) : (uint32_t)GBT_PART_TILE;
         if (with_hist) {
             const uint32_t t = (uint32_t)gbt_part_hist_tile();
             const double want = part_rows / ((double)ctx->num_cu * ctx->hist_jobs_per_cu);
@@ -898,7 +898,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             pjobs.push_back(j);
         }
         next.clear();
-        GBT_REQUIRE(ctx, (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
+        // the three-launch form keeps ballots and counts per tile in the workspace
+        GBT_REQUIRE(ctx, fused || (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
         GBT_REQUIRE(ctx, pjobs.size() * sizeof(PartJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
         if (st != GBT_OK) return st;

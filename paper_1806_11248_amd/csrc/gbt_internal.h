@@ -165,12 +165,12 @@ hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const
 // `what` above: move whole records, move only the ids, or only count the left rows of every job
 enum { GBT_PART_RECORDS = 0, GBT_PART_IDS = 1, GBT_PART_COUNT = 2 };
 // The same move of whole records in one launch for a caller that does not need the row order
-// (and no ids): rows narrow enough (gbt_partition_fused_ok), tiles of gbt_partition_fused_tile()
+// (and no ids): rows narrow enough (gbt_partition_fused_ok), tiles of gbt_partition_fused_tile(dst)
 // rows (PartJob.tile_begin / n_tiles count those).  cursor: one word per job, cleared by the
 // launcher; after the launch its low half is the job's n_left.  Inside a child the rows of one
 // tile keep their order, the tiles' order is arbitrary.
 bool gbt_partition_fused_ok(const GbtRows &dst);
-int gbt_partition_fused_tile();
+int gbt_partition_fused_tile(const GbtRows &dst);
 hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
                                       uint32_t missing, const PartJob *jobs, int n_jobs, int total_tiles,
                                       unsigned long long *cursor);

@@ -321,10 +321,8 @@ static_assert(kFWords == 64, "the ballot words are ranked by one wave");
 
 __device__ inline uint32_t pick_word(const uint4 &v, int k) { return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w; }
 
-// REG: rows are four words in the destination and at most 128 bits in the source; a thread keeps its
-// eight rows in registers between the load and the store.  Otherwise rows are re-read for the copy
-// (by the workgroup that has just read them for the flags) by sub-wave lane groups.
-template <bool REG>
+// Rows of four words in the destination and at most 128 bits in the source: a thread keeps its eight
+// rows in registers between the load and the store.  (Other widths: part_staged_kernel below.)
 __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
     const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words, bool aligned_src,
     uint32_t *__restrict__ dst_sym, int SW, int row_bits, int bits, uint32_t missing,
@@ -333,7 +331,6 @@ __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
     __shared__ uint32_t left_base_s, right_base_s;
     __shared__ uint64_t words[kFWords];
     __shared__ uint32_t lefts_before[kFWords];
-    __shared__ uint32_t dstpos[REG ? 1 : kFTile];
     const uint32_t tile = blockIdx.x;
     const int ji = find_job(jobs, n_jobs, tile);
     const PartJob job = jobs[ji];
@@ -347,8 +344,8 @@ __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
     const uint32_t fbit = job.feature * (uint32_t)bits;   // the split feature's first bit inside a row
 
     // ---- load, decide
-    uint4 row[REG ? kRowsPerThread : 1];
-    int2 pair[REG ? kRowsPerThread : 1];
+    uint4 row[kRowsPerThread];
+    int2 pair[kRowsPerThread];
 #pragma unroll
     for (int j = 0; j < kRowsPerThread; ++j) {
         const int w = j * (kFBlock / 64) + wave;
@@ -357,7 +354,7 @@ __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
         if (in_tile < tile_rows) {
             const uint64_t p = p0 + in_tile;
             uint32_t sy;
-            if (REG) {
+            {
                 uint4 v;
                 if (aligned_src) {   // 16-byte rows on a 16-byte aligned base
                     v = ((const uint4 *)src_sym)[p];
@@ -378,8 +375,6 @@ __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
                 const int k = (int)(fbit >> 5);
                 const uint32_t lo = pick_word(v, k), hi = k < 3 ? pick_word(v, k + 1) : 0u;
                 sy = __builtin_amdgcn_alignbit(hi, lo, fbit & 31u) & sym_mask;
-            } else {
-                sy = load_symbol(src_sym, p * (uint64_t)src_stride_bits + fbit, bits, sym_mask);
             }
             left = (sy == missing) ? (job.default_left != 0) : (sy <= job.bin);
         }
@@ -425,36 +420,116 @@ __global__ __launch_bounds__(kFBlock) void part_fused_kernel(
                 const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[w];
                 q = seg_last - (right_base + rights_before_word + ((uint32_t)lane - below));
             }
-            if (REG) {
-                ((uint4 *)dst_sym)[q] = row[j];
-                dst_gq[q] = pair[j];
-            } else {
-                dstpos[in_tile] = q;
-                dst_gq[q] = src_gq[p0 + in_tile];
-            }
+            ((uint4 *)dst_sym)[q] = row[j];
+            dst_gq[q] = pair[j];
         }
     }
-    if (!REG) {
-        __syncthreads();
-        int lpr = 1;
-        while (lpr < SW && lpr < 64) lpr <<= 1;
-        const int rows_per_wave = 64 / lpr;
-        const int sub = lane / lpr, k0 = lane % lpr;
-        for (uint32_t row0 = (uint32_t)wave * rows_per_wave; row0 < tile_rows; row0 += (kFBlock / 64) * rows_per_wave) {
-            const uint32_t in_tile = row0 + (uint32_t)sub;
-            if (in_tile >= tile_rows) continue;
-            const uint64_t sb = (p0 + in_tile) * (uint64_t)src_stride_bits;
-            const int64_t s0 = (int64_t)(sb >> 5);
-            const uint32_t sh = (uint32_t)(sb & 31);
-            uint32_t *d = dst_sym + (uint64_t)dstpos[in_tile] * (uint64_t)SW;
-            for (int k = k0; k < SW; k += lpr) {
-                const int64_t si = s0 + k;
-                const uint32_t lo = src_sym[si < src_words ? si : src_words - 1];
-                const uint32_t hi = src_sym[si + 1 < src_words ? si + 1 : src_words - 1];
-                uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh);
-                if (k == SW - 1) v &= tail_mask;
-                d[k] = v;
+}
+
+// The same one-launch partition for rows of any width up to 64 words: the tile's rows are one
+// contiguous piece of the source bit stream, which is read linearly into LDS (every lane busy, whole
+// lines, each byte fetched once); the split symbols are then cut out of LDS, and every row is copied
+// from LDS to its new place by a group of lanes, one word per lane.  The tile holds as many rows as
+// fit kStageBytes (at most kFTile).
+constexpr int kStageBytes = 48 * 1024;
+__host__ __device__ inline int staged_tile_rows(int64_t dst_stride_bits) {
+    int64_t r = (int64_t)kStageBytes * 8 / dst_stride_bits;   // the source stride is never larger
+    r = r / 64 * 64;
+    return (int)(r > kFTile ? kFTile : (r < 64 ? 64 : r));
+}
+
+__global__ __launch_bounds__(kFBlock) void part_staged_kernel(
+    const uint32_t *__restrict__ src_sym, int64_t src_stride_bits, int64_t src_words,
+    uint32_t *__restrict__ dst_sym, int SW, int row_bits, int bits, uint32_t missing,
+    const int2 *__restrict__ src_gq, int2 *__restrict__ dst_gq, const PartJob *__restrict__ jobs, int n_jobs,
+    int tile_cap, unsigned long long *__restrict__ cursor) {
+    extern __shared__ uint32_t stage[];                 // the tile's words, then one destination per row
+    __shared__ uint32_t left_base_s, right_base_s;
+    __shared__ uint64_t words[kFWords];
+    __shared__ uint32_t lefts_before[kFWords];
+    const uint32_t tile = blockIdx.x;
+    const int ji = find_job(jobs, n_jobs, tile);
+    const PartJob job = jobs[ji];
+    const uint32_t base = (tile - job.tile_begin) * (uint32_t)tile_cap;
+    const uint32_t tile_rows = job.seg_len - base < (uint32_t)tile_cap ? job.seg_len - base : (uint32_t)tile_cap;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t p0 = (uint64_t)job.seg_begin + base;
+    const uint64_t bit0 = p0 * (uint64_t)src_stride_bits;      // first bit of the tile in the source
+    const int64_t w_lo = (int64_t)(bit0 >> 5);
+    const uint32_t sh0 = (uint32_t)(bit0 & 31);
+    const uint32_t n_stage = (uint32_t)((sh0 + (uint64_t)tile_rows * (uint64_t)src_stride_bits + 31) >> 5) + 1u;
+    uint32_t *dstpos = stage + (((uint64_t)tile_cap * (uint64_t)src_stride_bits + 31) >> 5) + 2;
+    for (uint32_t i = threadIdx.x; i < n_stage; i += kFBlock)
+        stage[i] = src_sym[w_lo + i < src_words ? w_lo + i : src_words - 1];
+    __syncthreads();
+
+    const uint32_t sym_mask = (1u << bits) - 1u;
+    const uint32_t fbit = job.feature * (uint32_t)bits;
+    const int n_words_tile = (tile_cap + 63) / 64;             // ballot words in use, <= kFWords
+    for (int w = wave; w < n_words_tile; w += kFBlock / 64) {
+        const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+        bool left = false;
+        if (in_tile < tile_rows) {
+            const uint64_t b = sh0 + (uint64_t)in_tile * (uint64_t)src_stride_bits + fbit;   // inside the staged words
+            const uint32_t lo = stage[b >> 5], hi = stage[(b >> 5) + 1];
+            const uint32_t sy = __builtin_amdgcn_alignbit(hi, lo, (uint32_t)(b & 31)) & sym_mask;
+            left = (sy == missing) ? (job.default_left != 0) : (sy <= job.bin);
+        }
+        const uint64_t ballot = __ballot(left);
+        if (lane == 0) words[w] = ballot;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t c = lane < n_words_tile ? (uint32_t)__popcll(words[lane]) : 0u;
+        uint32_t x = c;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t y = (uint32_t)__shfl_up((int)x, d);
+            if (lane >= d) x += y;
+        }
+        if (lane < n_words_tile) lefts_before[lane] = x - c;
+        if (lane == 63) {
+            const unsigned long long old =
+                atomicAdd(&cursor[ji], (unsigned long long)x | ((unsigned long long)(tile_rows - x) << 32));
+            left_base_s = (uint32_t)(old & 0xffffffffull);
+            right_base_s = (uint32_t)(old >> 32);
+        }
+    }
+    __syncthreads();
+    const uint32_t left_base = left_base_s, right_base = right_base_s;
+    const uint32_t seg_last = job.seg_begin + job.seg_len - 1u;
+    for (int w = wave; w < n_words_tile; w += kFBlock / 64) {
+        const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+        if (in_tile < tile_rows) {
+            const uint64_t m = words[w];
+            const uint32_t below = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            uint32_t q;
+            if ((m >> lane) & 1ull) {
+                q = job.seg_begin + left_base + lefts_before[w] + below;
+            } else {
+                const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[w];
+                q = seg_last - (right_base + rights_before_word + ((uint32_t)lane - below));
             }
+            dstpos[in_tile] = q;
+            dst_gq[q] = src_gq[p0 + in_tile];
+        }
+    }
+    __syncthreads();
+    const uint32_t tail_bits = (uint32_t)(row_bits - 32 * (SW - 1));
+    const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
+    int lpr = 1;   // lanes per row: the next power of two >= SW, at most 64
+    while (lpr < SW && lpr < 64) lpr <<= 1;
+    const int rows_per_wave = 64 / lpr;
+    const int sub = lane / lpr, k0 = lane % lpr;
+    for (uint32_t row0 = (uint32_t)wave * rows_per_wave; row0 < tile_rows; row0 += (kFBlock / 64) * rows_per_wave) {
+        const uint32_t in_tile = row0 + (uint32_t)sub;
+        if (in_tile >= tile_rows) continue;
+        const uint64_t b = sh0 + (uint64_t)in_tile * (uint64_t)src_stride_bits;
+        const uint32_t s0 = (uint32_t)(b >> 5), sh = (uint32_t)(b & 31);
+        uint32_t *d = dst_sym + (uint64_t)dstpos[in_tile] * (uint64_t)SW;
+        for (int k = k0; k < SW; k += lpr) {
+            uint32_t v = __builtin_amdgcn_alignbit(stage[s0 + k + 1], stage[s0 + k], sh);   // s0 + k + 1 < n_stage
+            if (k == SW - 1) v &= tail_mask;
+            d[k] = v;
         }
     }
 }
@@ -498,7 +573,9 @@ hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const
 }
 
 bool gbt_partition_fused_ok(const GbtRows &dst) { return (dst.stride_bits >> 5) <= 64; }
-int gbt_partition_fused_tile() { return kFTile; }
+int gbt_partition_fused_tile(const GbtRows &dst) {
+    return (dst.stride_bits >> 5) == 4 ? kFTile : staged_tile_rows(dst.stride_bits);
+}
 
 hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const GbtRows &dst, int bits, int row_bits,
                                       uint32_t missing, const PartJob *jobs, int n_jobs, int total_tiles,
@@ -509,14 +586,23 @@ hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const G
     const int SW = (int)(dst.stride_bits >> 5);
     const bool aligned_src = src.stride_bits == 128 && ((uintptr_t)src.sym & 15u) == 0;
     if (SW == 4 && src.stride_bits <= 128)
-        part_fused_kernel<true><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, aligned_src,
+        part_fused_kernel<<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, aligned_src,
                                                                 dst.sym_rw, SW, row_bits, bits, missing,
                                                                 (const int2 *)src.gq, (int2 *)dst.gq_rw, jobs, n_jobs,
                                                                 cursor);
-    else
-        part_fused_kernel<false><<<total_tiles, kFBlock, 0, s>>>(src.sym, src.stride_bits, src.n_words, false,
-                                                                 dst.sym_rw, SW, row_bits, bits, missing,
-                                                                 (const int2 *)src.gq, (int2 *)dst.gq_rw, jobs, n_jobs,
-                                                                 cursor);
+    else {
+        const int cap = staged_tile_rows(dst.stride_bits);
+        const size_t lds = ((((size_t)cap * (size_t)src.stride_bits + 31) >> 5) + 2 + (size_t)cap) * 4;
+        static size_t configured = 0;
+        if (lds > configured) {
+            e = hipFuncSetAttribute((const void *)part_staged_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds);
+            if (e != hipSuccess) return e;
+            configured = lds;
+        }
+        part_staged_kernel<<<total_tiles, kFBlock, lds, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw, SW,
+                                                             row_bits, bits, missing, (const int2 *)src.gq,
+                                                             (int2 *)dst.gq_rw, jobs, n_jobs, cap, cursor);
+    }
     return hipGetLastError();
 }
