@@ -108,6 +108,8 @@ def main():
     ap.add_argument("--data-cache", default=None, help="directory to keep the generated inputs in")
     ap.add_argument("--cpu-sample-rows", type=int, default=4_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-outputs-leg", action="store_true",
+                    help="skip the extra timing of the steps with row order and leaf ids asked for")
     ap.add_argument("--policy", choices=["depthwise", "lossguide"], default="depthwise",
                     help="node expansion order (Sec. 2.3); lossguide grows --max-leaves leaves, no depth cap")
     ap.add_argument("--max-leaves", type=int, default=0, help="lossguide: leaf budget (default 2^max_depth)")
@@ -174,16 +176,18 @@ def main():
     eta = p["eta"]
     trees = []
 
-    def step():
+    def step(outputs=False):
+        # outputs: also the final row order and each row's leaf (nothing in the boosting loop reads them)
         if single_tree:
             margin.zero_()
         if not given:
             ctx.gradients(p["objective"], margin, y, out=gp)
         if lossguide:
             tree, _, _ = ctx.grow_tree_lossguide(packed, bits, n, F, ms, nb, cuts, gp, lg_params, max_leaves,
-                                                 want_rows=False, want_leaf=False)
+                                                 want_rows=outputs, want_leaf=outputs)
         else:
-            tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=False, want_leaf=False)
+            tree, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=outputs,
+                                       want_leaf=outputs)
         ctx.predict([tree], margin, eta, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
         trees.append(tree)
 
@@ -207,6 +211,24 @@ def main():
     prof = ctx.profile_read()
     ctx.profile_enable(False)
     ms_per_step = dt * 1e3 / a.steps
+    # the same steps when the caller also asks for the row order and the leaf of every row
+    if single_tree:
+        margin_keep = None
+    else:
+        margin_keep = margin.clone()
+    n_trees_timed = len(trees)
+    ms_per_step_outputs = None
+    if not a.no_outputs_leg:
+        step(outputs=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            step(outputs=True)
+        torch.cuda.synchronize()
+        ms_per_step_outputs = (time.perf_counter() - t0) * 1e3 / a.steps
+    del trees[n_trees_timed:]
+    if margin_keep is not None:
+        margin.copy_(margin_keep)
     log("per-class device ms per step: " +
         ", ".join(f"{k}={v['ms'] / a.steps:.3f}" for k, v in prof.items()))
     log(f"nodes per tree: {[t['n_nodes'] for t in trees[-a.steps:]]}")
@@ -260,6 +282,9 @@ def main():
                    "rows": n, "features": F, "bits": bits, "max_depth": p["max_depth"],
                    "policy": a.policy, **({"max_leaves": max_leaves} if lossguide else {})},
         "seconds_per_tree": ms_per_step * 1e-3,
+        "with_row_order_and_leaf_ids": (None if ms_per_step_outputs is None else
+                                        {"ms_per_step": ms_per_step_outputs,
+                                         "value": n * F / (ms_per_step_outputs * 1e-3)}),
         "hist_root_ms": root_ms,
         "hist_root_rows_features_per_s": (n * F / (root_ms * 1e-3)) if root_ms > 0 else None,
         "roofline": roofline,

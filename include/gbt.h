@@ -237,10 +237,16 @@ GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits,
 /*
  * How gbt_grow_tree moves the rows of splitting nodes for this shape (for
  * profiling and tests; the result of gbt_grow_tree does not depend on it):
- *   0  three launches per level (flags, offsets, move), row order kept
- *   1  one launch per level, row order not kept (only when track_rows == 0)
+ *   0  three launches per level (flags, offsets, move); row ids travel with the
+ *      rows and every node's rows keep their order
+ *   1  one launch per level, order inside a node not kept, no ids (rows of at
+ *      most 64 words)
  *   2  as 1, and the launch also builds one child's histogram of every split
  *      node (8-bit symbols, at most 16 features)
+ * track_rows: whether the caller passes row_idx_out.  It does not change the
+ * answer unless the library was told (GBT_TUNE_ORDER_ROWS=0 in the environment
+ * when the context was created) to produce row_idx_out by carrying the ids,
+ * which needs form 0.
  * Negative: a GBT_E* code.
  */
 GBT_API int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_t max_bins, int32_t track_rows);
@@ -260,14 +266,16 @@ GBT_API int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_
  *   nb [dev] int32[F]; cuts [dev] float[F][max_bins-1] (for thresholds)
  *   gpair [dev] float2[n]
  *   tree_out [host]              caller-allocated arrays, see gbt_tree
- *   row_idx_out [dev] uint32[n]  final row order: each node's rows are one
- *                                ascending run, left child's run first.  May be
- *                                NULL: then row ids are not carried through the
- *                                partitions (less memory traffic, the faster
- *                                partition forms)
- *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL).  Without
- *                                row_idx_out it comes from one walk of the
- *                                finished tree over the packed matrix
+ *   row_idx_out [dev] uint32[n]  final row order (may be NULL): what the stable
+ *                                partitions of Alg. 1 leave of the list 0..n-1;
+ *                                each node's rows are one ascending run, the
+ *                                left child's run first.  Where the rows move
+ *                                without ids (forms 1 and 2 above) the list is
+ *                                made at the end: the rows sorted stably by
+ *                                their leaf's place in left-to-right order
+ *   leaf_of_row_out [dev] int32[n] leaf id per row (may be NULL).  In forms 1
+ *                                and 2 it comes from one walk of the finished
+ *                                tree over the packed matrix
  * Synchronises the stream.
  */
 GBT_API int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,

@@ -186,6 +186,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->part_fused = 1;
         c->part_hist = 1;
         c->hist_fix = 1;
+        c->order_rows = 1;
+        if (const char *e11 = getenv("GBT_TUNE_ORDER_ROWS")) c->order_rows = atoi(e11) != 0;
         if (const char *e10 = getenv("GBT_TUNE_HIST_FIX")) c->hist_fix = atoi(e10) != 0;
         if (const char *e8 = getenv("GBT_TUNE_PART_HIST")) c->part_hist = atoi(e8) != 0;
         if (const char *e6 = getenv("GBT_TUNE_PART_FUSED")) c->part_fused = atoi(e6) != 0;
@@ -557,7 +559,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
 namespace {
 
 struct GrowLayout {
-    size_t tree_stage, tree_stage_bytes, gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, splits, jobs, scratch, total;
+    size_t tree_stage, tree_stage_bytes, gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, splits, jobs, scratch, order, rank_tbl, total;
     int64_t hist_nodes, level_nodes, tiles, w_words;
     int sw;   // 32-bit words per row of the working copies
 };
@@ -598,6 +600,9 @@ GrowLayout grow_layout_nodes(int64_t n, int F, int bits, int B, int64_t hist_nod
     const size_t cap_nodes = (size_t)(2 * hist_nodes + 1);
     L.tree_stage_bytes = gbt_align(64) + gbt_align(cap_nodes * 4) * 6 + gbt_align(cap_nodes * 8) + 256;
     L.tree_stage = o; o += gbt_align(L.tree_stage_bytes);
+    // row ids in leaf order after a growth that did not follow the rows
+    L.order = o;      o += gbt_order_ws(n);
+    L.rank_tbl = o;   o += gbt_align(cap_nodes * 4);
     L.total = o;
     return L;
 }
@@ -630,7 +635,7 @@ GbtRows working_rows_shape(int F, int bits) {
 }
 int grow_path(const gbt_ctx *ctx, int F, int bits, int B, bool tracked, int n_ftiles) {
     const GbtRows w = working_rows_shape(F, bits);
-    if (tracked || !ctx->part_fused || !gbt_partition_fused_ok(w)) return 0;
+    if ((tracked && !ctx->order_rows) || !ctx->part_fused || !gbt_partition_fused_ok(w)) return 0;
     if (ctx->part_hist && n_ftiles == 1 && gbt_part_hist_ok(ctx, bits, F, B)) return 2;
     return 1;
 }
@@ -828,7 +833,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         // when nobody needs the row order and the rows are narrow enough (and then, where the
         // histogram kernel's 8-bit single-tile case applies, one child's histogram is built in
         // the same pass), else by the three-launch form.  Leaves only need their ids moved, or
-        // just the row counts when ids are not tracked.
+        // just the row counts when no ids travel with the rows.
         sel_nodes.clear();
         sel_splits.clear();
         for (size_t i = 0; i < level.size(); ++i) {
@@ -910,7 +915,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                              n_children * hist_len));
             gbt_prof_end(ctx);
         }
-        const int what = children_need_hist ? GBT_PART_RECORDS : tracked ? GBT_PART_IDS : GBT_PART_COUNT;
+        const int what = children_need_hist ? GBT_PART_RECORDS : (tracked && path == 0) ? GBT_PART_IDS : GBT_PART_COUNT;
         const double rec_bytes = row_bits / 8.0 + 8.0;
         gbt_prof_begin(ctx, with_hist ? GBT_PROF_HIST_NODE : GBT_PROF_PARTITION,
                        part_rows * (fused ? 2.0 * rec_bytes
@@ -1047,15 +1052,44 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)nd.buf, nd.len});
     for (const OpenLeaf &ol : open_leaves)
         leaves.push_back(LeafSeg{ol.nd.begin, (uint32_t)ol.nd.id, (uint32_t)ol.nd.buf, ol.nd.len});
-    if (!tracked) {
+    if (!tracked || path != 0) {
         tree->n_nodes = n_nodes;
-        if (leaf_of_row_out) {
-            // the rows were not followed: one walk of the finished tree over the matrix names each row's leaf
+        // the rows were not followed: one walk of the finished tree over the matrix names each row's leaf
+        int32_t *leaf_ids = leaf_of_row_out ? leaf_of_row_out : (int32_t *)W[0].id_rw;
+        if (leaf_of_row_out || tracked) {
             gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (row_bits / 8.0 + 4.0));
-            st = predict_impl(ctx, tree, 1, packed, bits, missing_sym, nullptr, n, F, 0.0, nullptr, leaf_of_row_out,
+            st = predict_impl(ctx, tree, 1, packed, bits, missing_sym, nullptr, n, F, 0.0, nullptr, leaf_ids,
                               ws + L.tree_stage, L.tree_stage_bytes);
             gbt_prof_end(ctx);
             if (st != GBT_OK) return st;
+        }
+        if (tracked) {
+            // ... and the stable partitions' final id list is the rows sorted by their leaf's place in
+            // the tree's left-to-right order, ids ascending inside a leaf
+            std::vector<uint32_t> rank((size_t)n_nodes, 0u);
+            std::vector<int32_t> stack{0};
+            uint32_t n_ranks = 0;
+            while (!stack.empty()) {
+                const int32_t id = stack.back();
+                stack.pop_back();
+                if (tree->feature[id] < 0) {
+                    rank[(size_t)id] = n_ranks++;
+                } else {
+                    stack.push_back(tree->right[id]);
+                    stack.push_back(tree->left[id]);
+                }
+            }
+            const size_t per_upload = kUploadBytes / 4;
+            for (size_t i0 = 0; i0 < rank.size(); i0 += per_upload) {
+                st = upload(ctx, rank.data() + i0, std::min(per_upload, rank.size() - i0) * 4, ws + L.rank_tbl + i0 * 4);
+                if (st != GBT_OK) return st;
+            }
+            uint32_t *key_tmp[2] = {W[1].id_rw, (uint32_t *)(ws + L.wgq[0]) + n};
+            uint32_t *val_tmp[2] = {(uint32_t *)(ws + L.wgq[0]), (uint32_t *)(ws + L.wgq[1])};
+            gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
+            GBT_HIP(ctx, gbt_launch_order_rows(s, leaf_ids, (const uint32_t *)(ws + L.rank_tbl), (uint32_t)n_nodes,
+                                               n_ranks, n, key_tmp, val_tmp, ws + L.order, row_idx_out));
+            gbt_prof_end(ctx);
         }
         GBT_SYNC(ctx);
         return GBT_OK;

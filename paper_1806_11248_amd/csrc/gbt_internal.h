@@ -26,6 +26,7 @@ struct gbt_ctx {
     int hist_block;         // threads per histogram workgroup
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
     int part_fused;         // 1: one-launch record partition where it applies
+    int order_rows;         // 1: a caller's row order is made from the finished tree, so that it does not restrict the partition form
     int hist_fix;           // 1: the root histogram kernel also converts the gradient pairs where that applies
     int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
@@ -199,6 +200,14 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,
                                   int32_t *leaf_of_row);
+
+// Row ids in leaf order from each row's leaf: a stable sort of the positions 0..n-1 by
+// rank_tbl[leaf[row]] (n_nodes table entries, ranks below n_ranks).  key_tmp / val_tmp: two buffers of
+// n words each, touched only when n_ranks > 256; ws: gbt_order_ws(n) bytes.
+size_t gbt_order_ws(int64_t n);
+hipError_t gbt_launch_order_rows(hipStream_t s, const int32_t *leaf, const uint32_t *rank_tbl, uint32_t n_nodes,
+                                 uint32_t n_ranks, int64_t n, uint32_t *key_tmp[2], uint32_t *val_tmp[2], char *ws,
+                                 uint32_t *row_idx_out);
 
 hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_elems, int bits,
                                uint32_t *packed, int64_t n_words);
