@@ -149,6 +149,32 @@ GBT_API int64_t gbt_packed_words(int64_t n, int32_t F, int32_t bits);
 GBT_API int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, uint32_t max_value,
                      uint32_t *packed_out, int32_t *bits_out);
 
+/* ---- sparse rows: Sec. 1 (sparse input), Sec. 2.2 (compressed storage) ---- */
+
+/*
+ * A second storage form of the quantised matrix for mostly-empty data: row r
+ * keeps only its present elements (sym != missing_sym), each as the 16-bit
+ * global bin id  gid = f * max_bins + sym  (needs F * max_bins <= 65536, else
+ * GBT_EUNSUPPORTED), ascending, in ent[rowptr[r] .. rowptr[r+1]).  2*gid is the
+ * element's place in a [F][max_bins][2] histogram.  Two calls, because the
+ * caller allocates the entry stream:
+ *   gbt_compress_sparse_count  sym [dev] uint16[n][F] -> rowptr_out [dev]
+ *                              uint32[n+1], *nnz_out [host] = rowptr[n].
+ *                              Synchronises the stream.
+ *   gbt_compress_sparse        fills ent_out [dev, 4-byte aligned]; it must hold
+ *                              gbt_sparse_capacity(nnz) entries: the kernels read
+ *                              the stream as whole words, up to 16 entries past
+ *                              the end.  Asynchronous.
+ */
+GBT_API int64_t gbt_sparse_capacity(int64_t nnz);
+GBT_API size_t gbt_compress_sparse_workspace_bytes(int64_t n);
+GBT_API int32_t gbt_compress_sparse_count(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F,
+                      int32_t missing_sym, uint32_t *rowptr_out, int64_t *nnz_out, void *workspace,
+                      size_t workspace_bytes);
+GBT_API int32_t gbt_compress_sparse(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, int32_t max_bins,
+                      int32_t missing_sym, const uint32_t *rowptr, int64_t nnz, uint16_t *ent_out,
+                      int64_t ent_capacity);
+
 /* ---- Sec. 2.5 gradient evaluation (Eq. 1, Eq. 2) ------------------------ */
 
 /* gpair_out[i] = (g, h) of margin[i], label[i]: logistic g = s - y, h = s(1-s)
@@ -187,6 +213,14 @@ GBT_API int32_t gbt_sum_gpair(gbt_ctx *ctx, const int32_t *gq, const uint32_t *r
 GBT_API int32_t gbt_build_hist(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                        int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_node_rows,
                        const int32_t *gq, int64_t *hist_out);
+
+/* gbt_build_hist over sparse rows (gbt_compress_sparse): the node's rows are the
+ * contiguous range [row_begin, row_begin + n_node_rows) of the n rows; absent
+ * elements are missing and accumulate nowhere.  hist_out [dev] int64[F][B][2],
+ * overwritten.  Asynchronous. */
+GBT_API int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                       int32_t F, int32_t B, int64_t row_begin, int64_t n_node_rows, const int32_t *gq,
+                       int64_t *hist_out);
 
 /* out = parent - child, elementwise over `count` int64 values [dev] (the
  * sibling-subtraction trick: the larger child's histogram).  Asynchronous. */
@@ -302,6 +336,22 @@ GBT_API int32_t gbt_grow_tree_lossguide(gbt_ctx *ctx, const uint32_t *packed, in
                       const gbt_params *params, int32_t max_leaves, gbt_tree *tree_out, uint32_t *row_idx_out,
                       int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
 
+/*
+ * gbt_grow_tree (depth-wise) over sparse rows (gbt_compress_sparse): the same
+ * tree as on the packed matrix of the same symbols -- an absent element is a
+ * missing value.  Rows move without ids through one-launch unordered
+ * partitions; leaf_of_row_out comes from a walk of the finished tree,
+ * row_idx_out from a stable sort of the rows by leaf (both may be NULL).
+ * nnz = rowptr[n].  Other arguments, outputs and errors as for gbt_grow_tree.
+ * Synchronises the stream.
+ */
+GBT_API size_t gbt_grow_tree_sparse_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
+                                                    int32_t max_depth);
+GBT_API int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                      int64_t nnz, int32_t F, const int32_t *nb, const float *cuts, const float *gpair,
+                      const gbt_params *params, gbt_tree *tree_out, uint32_t *row_idx_out,
+                      int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
+
 /* ---- Sec. 2.4 prediction ------------------------------------------------ */
 
 GBT_API size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_trees);
@@ -318,6 +368,13 @@ GBT_API size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_tree
 GBT_API int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                     int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F,
                     double eta, float *margin_inout, void *workspace, size_t workspace_bytes);
+
+/* gbt_predict over sparse rows: left iff the row's symbol of the node's feature
+ * is <= bin, an absent element -> default child.  A tree must fit LDS (32 bytes
+ * per node).  workspace as for gbt_predict.  Synchronises the stream. */
+GBT_API int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *rowptr,
+                      const uint16_t *ent, int64_t n, int32_t F, int32_t max_bins, double eta, float *margin,
+                      void *workspace, size_t workspace_bytes);
 
 /* ---- measurement -------------------------------------------------------- */
 

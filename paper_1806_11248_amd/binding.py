@@ -28,6 +28,8 @@ SYMBOLS = [
     "gbt_grow_tree_workspace_bytes", "gbt_grow_tree_path", "gbt_grow_tree",
     "gbt_grow_tree_lossguide_workspace_bytes", "gbt_grow_tree_lossguide", "gbt_predict_workspace_bytes", "gbt_predict",
     "gbt_profile_enable", "gbt_profile_read",
+    "gbt_sparse_capacity", "gbt_compress_sparse_workspace_bytes", "gbt_compress_sparse_count", "gbt_compress_sparse",
+    "gbt_build_hist_sparse", "gbt_grow_tree_sparse_workspace_bytes", "gbt_grow_tree_sparse", "gbt_predict_sparse",
 ]
 
 PROF_CLASSES = ["hist_root", "hist_node", "partition", "eval", "subtract", "other"]
@@ -112,6 +114,17 @@ def load():
     L.gbt_grow_tree.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
     L.gbt_grow_tree_lossguide.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz]
     L.gbt_predict.argtypes = [vp, vp, i32, vp, i32, i32, vp, i64, i32, f64, vp, vp, sz]
+    L.gbt_sparse_capacity.argtypes = [i64]
+    L.gbt_sparse_capacity.restype = i64
+    L.gbt_compress_sparse_workspace_bytes.argtypes = [i64]
+    L.gbt_compress_sparse_workspace_bytes.restype = sz
+    L.gbt_compress_sparse_count.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, sz]
+    L.gbt_compress_sparse.argtypes = [vp, vp, i64, i32, i32, i32, vp, i64, vp, i64]
+    L.gbt_build_hist_sparse.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, vp, vp]
+    L.gbt_grow_tree_sparse_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
+    L.gbt_grow_tree_sparse_workspace_bytes.restype = sz
+    L.gbt_grow_tree_sparse.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
+    L.gbt_predict_sparse.argtypes = [vp, vp, i32, vp, vp, i64, i32, i32, f64, vp, vp, sz]
     L.gbt_profile_enable.argtypes = [vp, i32]
     L.gbt_profile_read.argtypes = [vp, vp]
     _lib = L
@@ -257,6 +270,22 @@ class Context:
         self._check(self.lib.gbt_compress(self.h, _ptr(sym), n, F, max_value, _ptr(packed), C.byref(b)))
         return packed, b.value
 
+    def compress_sparse(self, sym, max_bins: int, missing_sym: int):
+        """Sparse rows of sym[n][F]: (rowptr uint32[n+1] as int32 tensor, ent uint16[capacity], nnz)."""
+        _need(sym, torch.uint16, "sym")
+        n, F = sym.shape
+        rowptr = self.empty((n + 1,), torch.int32)
+        ws_bytes = self.lib.gbt_compress_sparse_workspace_bytes(n)
+        ws = self.workspace("small", max(ws_bytes, 4096))
+        nnz = C.c_int64()
+        self._check(self.lib.gbt_compress_sparse_count(self.h, _ptr(sym), n, F, missing_sym, _ptr(rowptr),
+                                                       C.byref(nnz), _ptr(ws), ws.numel()))
+        cap = int(self.lib.gbt_sparse_capacity(nnz.value))
+        ent = self.empty((cap,), torch.uint16)
+        self._check(self.lib.gbt_compress_sparse(self.h, _ptr(sym), n, F, max_bins, missing_sym, _ptr(rowptr),
+                                                 nnz.value, _ptr(ent), cap))
+        return rowptr, ent, nnz.value
+
     # -- Sec. 2.5 ------------------------------------------------------------
     def gradients(self, objective: str, margin, label, out=None):
         _need(margin, torch.float32, "margin"); _need(label, torch.float32, "label")
@@ -294,6 +323,12 @@ class Context:
         n_rows = 0 if row_idx is None else row_idx.numel()
         self._check(self.lib.gbt_build_hist(self.h, _ptr(packed), bits, n, F, B, missing_sym,
                                             self._rows_ptr(row_idx), n_rows, _ptr(gq), _ptr(hist)))
+        return hist
+
+    def build_hist_sparse(self, rowptr, ent, n, F, B, gq, row_begin=0, n_rows=None, out=None):
+        hist = out if out is not None else self.empty((F, B, 2), torch.int64)
+        self._check(self.lib.gbt_build_hist_sparse(self.h, _ptr(rowptr), _ptr(ent), n, F, B, row_begin,
+                                                   n if n_rows is None else n_rows, _ptr(gq), _ptr(hist)))
         return hist
 
     def hist_subtract(self, parent, child):
@@ -351,6 +386,23 @@ class Context:
         t["n_nodes"] = int(ts.n_nodes)
         return t, row_idx, leaf
 
+    def grow_tree_sparse(self, rowptr, ent, n, nnz, F, nb, cuts, gpair, params: Params, want_leaf=True,
+                         want_rows=True):
+        """grow_tree over sparse rows (compress_sparse); returns what grow_tree returns."""
+        t = new_tree(params.max_depth)
+        ts = _tree_struct(t)
+        row_idx = self.empty((n,), torch.int32) if want_rows else None
+        leaf = self.empty((n,), torch.int32) if want_leaf else None
+        ws_bytes = self.lib.gbt_grow_tree_sparse_workspace_bytes(n, nnz, F, params.max_bins, params.max_depth)
+        if ws_bytes == 0:
+            raise GbtError(EINVAL, "gbt_grow_tree_sparse_workspace_bytes rejected the shape")
+        ws = self.workspace("grow", ws_bytes)
+        self._check(self.lib.gbt_grow_tree_sparse(self.h, _ptr(rowptr), _ptr(ent), n, nnz, F, _ptr(nb), _ptr(cuts),
+                                                  _ptr(gpair), C.byref(params), C.byref(ts), _ptr(row_idx),
+                                                  _ptr(leaf), _ptr(ws), ws.numel()))
+        t["n_nodes"] = int(ts.n_nodes)
+        return t, row_idx, leaf
+
     def grow_tree_lossguide(self, packed, bits, n, F, missing_sym, nb, cuts, gpair, params: Params, max_leaves,
                             want_leaf=True, want_rows=True):
         """Loss-guided growth (Sec. 2.3); returns what grow_tree returns."""
@@ -376,6 +428,14 @@ class Context:
         return r
 
     # -- Sec. 2.4 ------------------------------------------------------------
+    def predict_sparse(self, trees, margin, eta: float, rowptr, ent, n, F, max_bins):
+        arr = (Tree * len(trees))(*[_tree_struct(t) for t in trees])
+        ws_bytes = self.lib.gbt_predict_workspace_bytes(arr, len(trees))
+        ws = self.workspace("predict", ws_bytes)
+        self._check(self.lib.gbt_predict_sparse(self.h, arr, len(trees), _ptr(rowptr), _ptr(ent), n, F, max_bins, eta,
+                                                _ptr(margin), _ptr(ws), ws.numel()))
+        return margin
+
     def predict(self, trees, margin, eta: float, *, packed=None, bits=0, missing_sym=0, X=None, n=None, F=None):
         arr = (Tree * len(trees))(*[_tree_struct(t) for t in trees])
         if X is not None:

@@ -186,6 +186,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->part_fused = 1;
         c->part_hist = 1;
         c->hist_fix = 1;
+        c->sparse_jobs_per_cu = 6;
+        if (const char *e12 = getenv("GBT_TUNE_SPARSE_JOBS")) { int v = atoi(e12); if (v >= 1 && v <= 64) c->sparse_jobs_per_cu = v; }
         c->order_rows = 1;
         if (const char *e11 = getenv("GBT_TUNE_ORDER_ROWS")) c->order_rows = atoi(e11) != 0;
         if (const char *e10 = getenv("GBT_TUNE_HIST_FIX")) c->hist_fix = atoi(e10) != 0;
@@ -650,9 +652,15 @@ extern "C" int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int
     return grow_path(ctx, F, bits, max_bins, track_rows != 0, pl.n_ftiles);
 }
 
+struct SparseRowsArg {   // rows in the sparse form instead of packed / X
+    const uint32_t *rowptr;
+    const uint16_t *ent;
+    int32_t B;
+};
 static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                             int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
-                            float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes);
+                            float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes,
+                            const SparseRowsArg *sparse = nullptr);
 
 // Alg. 1 under either policy of Sec. 2.3.  Growth proceeds in rounds: the nodes created by the round
 // before are evaluated; depth-wise then splits every one of them that may split, loss-guided only
@@ -1150,11 +1158,14 @@ extern "C" size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_t
 // one tree) the id of each row's leaf.  Does not synchronise.
 static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                             int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
-                            float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes) {
+                            float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes,
+                            const SparseRowsArg *sparse) {
     GBT_REQUIRE(ctx, trees && (margin || leaf_out) && workspace, GBT_EINVAL, "NULL argument");
-    GBT_REQUIRE(ctx, (packed != nullptr) != (X != nullptr), GBT_EINVAL, "give exactly one of packed and X");
+    GBT_REQUIRE(ctx, sparse || (packed != nullptr) != (X != nullptr), GBT_EINVAL, "give exactly one of packed and X");
     GBT_REQUIRE(ctx, n >= 0 && F >= 1 && n_trees >= 0, GBT_EINVAL, "bad shape");
-    if (packed) {
+    if (sparse) {
+        bits = 1;
+    } else if (packed) {
         int32_t st = check_matrix(ctx, packed, bits, n, F);
         if (st != GBT_OK) return st;
     } else {
@@ -1207,6 +1218,13 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
     GBT_HIP(ctx, hipMemcpyAsync(workspace, host.data(), o, hipMemcpyHostToDevice, ctx->stream));
     int max_nodes = 1;
     for (int t = 0; t < n_trees; ++t) max_nodes = std::max(max_nodes, trees[t].n_nodes);
+    if (sparse) {
+        GBT_REQUIRE(ctx, (size_t)max_nodes * 32 <= ctx->lds_per_block, GBT_EUNSUPPORTED,
+                    "a tree of %d nodes does not fit the LDS of the sparse-row walk", max_nodes);
+        GBT_HIP(ctx, gbt_launch_sparse_walk(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees,
+                                            sparse->rowptr, sparse->ent, n, sparse->B, eta, margin, leaf_out, max_nodes));
+        return GBT_OK;
+    }
     GBT_HIP(ctx, gbt_launch_predict(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees, packed,
                                     bits, (uint32_t)missing_sym, X, n, F, eta, margin, leaf_out, max_nodes,
                                     compact_ok));
@@ -1220,6 +1238,453 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
     GBT_REQUIRE(ctx, margin != nullptr, GBT_EINVAL, "NULL argument");
     int32_t st = predict_impl(ctx, trees, n_trees, packed, bits, missing_sym, X, n, F, eta, margin, nullptr, workspace,
                               workspace_bytes);
+    if (st != GBT_OK) return st;
+    GBT_SYNC(ctx);
+    return GBT_OK;
+}
+
+// ------------------------------------------------------------- sparse rows --
+namespace {
+constexpr int64_t kSparseSlack = 16;   // entries past the last one that word-wise readers may touch
+
+int32_t check_sparse_shape(gbt_ctx *ctx, int64_t n, int32_t F, int32_t B) {
+    GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) - 1, GBT_EINVAL, "n = %lld out of range", (long long)n);
+    GBT_REQUIRE(ctx, F >= 1 && B >= 2, GBT_EINVAL, "bad shape");
+    GBT_REQUIRE(ctx, (int64_t)F * B <= 65536, GBT_EUNSUPPORTED,
+                "F * max_bins = %lld global bin ids do not fit 16 bits", (long long)F * B);
+    return GBT_OK;
+}
+
+// Rows per workgroup: every workgroup merges its whole id tile into HBM at the end, so a launch aims
+// at few, long jobs (a handful per compute unit over all tiles) rather than at many short ones.
+uint32_t sparse_rows_per_job(const gbt_ctx *ctx, int64_t total_rows, int64_t bins, int glen) {
+    const int64_t tiles = (bins + glen - 1) / glen;
+    int64_t per_tile = std::max<int64_t>(1, (int64_t)ctx->num_cu * ctx->sparse_jobs_per_cu / tiles);
+    int64_t rpj = (total_rows + per_tile - 1) / per_tile;
+    if (rpj < 2048) rpj = 2048;
+    if (rpj > ((int64_t)1 << 24)) rpj = (int64_t)1 << 24;
+    return (uint32_t)rpj;
+}
+
+// jobs over rows [begin, begin + len) for every id tile of a node
+void add_sparse_hist_jobs(std::vector<HistJob> &jobs, uint64_t hist_off, uint32_t begin, uint32_t len, int64_t bins,
+                          int glen, uint32_t rows_per_job) {
+    for (uint32_t r0 = 0; r0 < len; r0 += rows_per_job) {
+        const uint32_t nr = std::min(rows_per_job, len - r0);
+        for (int64_t g0 = 0; g0 < bins; g0 += glen) {
+            HistJob j;
+            j.hist_off = hist_off;
+            j.row_begin = begin + r0;
+            j.n_rows = nr;
+            j.f0 = (uint32_t)g0;
+            j.ft = (uint32_t)std::min<int64_t>(glen, bins - g0);
+            j.pad0 = j.pad1 = 0;
+            jobs.push_back(j);
+        }
+    }
+}
+}  // namespace
+
+extern "C" int64_t gbt_sparse_capacity(int64_t nnz) {
+    if (nnz < 0) return 0;
+    return ((nnz + 1) & ~(int64_t)1) + kSparseSlack;
+}
+
+extern "C" size_t gbt_compress_sparse_workspace_bytes(int64_t n) {
+    if (n < 0) return 0;
+    return gbt_align((size_t)gbt_sparse_scan_tiles(n) * 8) + 256;
+}
+
+extern "C" int32_t gbt_compress_sparse_count(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F,
+                                             int32_t missing_sym, uint32_t *rowptr_out, int64_t *nnz_out,
+                                             void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, sym && rowptr_out && nnz_out && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) - 1 && F >= 1, GBT_EINVAL, "bad shape");
+    GBT_REQUIRE(ctx, missing_sym >= 0 && missing_sym <= 65535, GBT_EINVAL, "missing_sym out of range");
+    GBT_REQUIRE(ctx, workspace_bytes >= gbt_compress_sparse_workspace_bytes(n), GBT_ENOMEM, "workspace too small");
+    char *ws = (char *)workspace;
+    uint64_t *total = (uint64_t *)ws;
+    uint64_t *tile_ws = (uint64_t *)(ws + 256);
+    GBT_HIP(ctx, gbt_launch_sparse_rowptr(ctx->stream, sym, n, F, (uint32_t)missing_sym, rowptr_out, tile_ws, total));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), total, 8, hipMemcpyDeviceToHost, ctx->stream));
+    GBT_SYNC(ctx);
+    uint64_t nnz;
+    memcpy(&nnz, rb(ctx), 8);
+    GBT_REQUIRE(ctx, nnz < ((uint64_t)1 << 32) - 64, GBT_EUNSUPPORTED, "%llu present elements exceed 32-bit row pointers",
+                (unsigned long long)nnz);
+    *nnz_out = (int64_t)nnz;
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_compress_sparse(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, int32_t max_bins,
+                                       int32_t missing_sym, const uint32_t *rowptr, int64_t nnz, uint16_t *ent_out,
+                                       int64_t ent_capacity) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, sym && rowptr && ent_out, GBT_EINVAL, "NULL argument");
+    int32_t st = check_sparse_shape(ctx, n, F, max_bins);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, missing_sym >= 0 && missing_sym <= 65535, GBT_EINVAL, "missing_sym out of range");
+    GBT_REQUIRE(ctx, nnz >= 0 && ent_capacity >= gbt_sparse_capacity(nnz), GBT_ENOMEM,
+                "ent_out holds %lld entries, %lld needed", (long long)ent_capacity, (long long)gbt_sparse_capacity(nnz));
+    GBT_REQUIRE(ctx, ((uintptr_t)ent_out & 3) == 0, GBT_EINVAL, "ent_out must be 4-byte aligned");
+    GBT_HIP(ctx, gbt_launch_sparse_fill(ctx->stream, sym, n, F, max_bins, (uint32_t)missing_sym, rowptr, ent_out, nnz,
+                                        gbt_sparse_capacity(nnz)));
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                                         int32_t F, int32_t B, int64_t row_begin, int64_t n_node_rows,
+                                         const int32_t *gq, int64_t *hist_out) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, rowptr && ent && gq && hist_out, GBT_EINVAL, "NULL argument");
+    int32_t st = check_sparse_shape(ctx, n, F, B);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, ((uintptr_t)ent & 3) == 0, GBT_EINVAL, "ent must be 4-byte aligned");
+    GBT_REQUIRE(ctx, row_begin >= 0 && n_node_rows >= 0 && row_begin + n_node_rows <= n, GBT_EINVAL,
+                "rows [%lld, +%lld) outside the matrix", (long long)row_begin, (long long)n_node_rows);
+    const int64_t bins = (int64_t)F * B;
+    GBT_HIP(ctx, gbt_launch_fill_u64(ctx->stream, (uint64_t *)hist_out, 0, bins * 2));
+    if (n_node_rows == 0) return GBT_OK;
+    const int glen = gbt_sparse_hist_tile(ctx, bins);
+    std::vector<HistJob> jobs;
+    add_sparse_hist_jobs(jobs, 0, (uint32_t)row_begin, (uint32_t)n_node_rows, bins, glen,
+                         sparse_rows_per_job(ctx, n_node_rows, bins, glen));
+    char *slot;
+    st = stage(ctx, jobs.data(), jobs.size() * sizeof(HistJob), &slot);
+    if (st != GBT_OK) return st;
+    gbt_prof_begin(ctx, row_begin == 0 && n_node_rows == n ? GBT_PROF_HIST_ROOT : GBT_PROF_HIST_NODE, 0.0);
+    GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, rowptr, ent, gq, hist_out, (const HistJob *)slot, (int)jobs.size(), glen));
+    gbt_prof_end(ctx);
+    return GBT_OK;
+}
+
+namespace {
+struct SparseGrowLayout {
+    size_t gq, rowptr[2], ent[2], wgq[2], state, pool, eval_nodes, splits, jobs, scratch, tree_stage, tree_stage_bytes,
+        order, rank_tbl, total;
+    int64_t hist_nodes, level_nodes;
+};
+SparseGrowLayout sparse_grow_layout(int64_t n, int64_t nnz, int F, int B, int max_depth) {
+    SparseGrowLayout L;
+    L.hist_nodes = max_depth == 0 ? 1 : (((int64_t)1 << max_depth) - 1);
+    L.level_nodes = (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0);
+    size_t o = 0;
+    L.gq = o; o += gbt_align((size_t)n * 8);
+    for (int k = 0; k < 2; ++k) {
+        L.rowptr[k] = o; o += gbt_align((size_t)(n + 1) * 4);
+        L.ent[k] = o;    o += gbt_align((size_t)gbt_sparse_capacity(nnz) * 2);
+        L.wgq[k] = o;    o += gbt_align((size_t)n * 8);
+    }
+    L.state = o;      o += gbt_align((size_t)L.level_nodes * 16);
+    L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
+    L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * 2 * sizeof(EvalNode));
+    L.splits = o;     o += gbt_align(GBT_STAGING_BYTES / 2);
+    L.jobs = o;       o += gbt_align(kUploadBytes);
+    L.scratch = o;    o += 4096;
+    const size_t cap_nodes = (size_t)(2 * L.hist_nodes + 1);
+    L.tree_stage_bytes = gbt_align(64) + gbt_align(cap_nodes * 4) * 6 + gbt_align(cap_nodes * 8) + 256;
+    L.tree_stage = o; o += gbt_align(L.tree_stage_bytes);
+    L.order = o;      o += gbt_order_ws(n);
+    L.rank_tbl = o;   o += gbt_align(cap_nodes * 4);
+    L.total = o;
+    return L;
+}
+}  // namespace
+
+extern "C" size_t gbt_grow_tree_sparse_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
+                                                       int32_t max_depth) {
+    if (n < 0 || nnz < 0 || F < 1 || max_bins < 2 || (int64_t)F * max_bins > 65536 || max_depth < 0 ||
+        max_depth > kMaxDepth)
+        return 0;
+    return sparse_grow_layout(n, nnz, F, max_bins, max_depth).total;
+}
+
+// Alg. 1, depth-wise, over sparse rows: the loop of gbt_grow_tree with the sparse-row kernels.  Rows
+// move without ids through one-launch unordered partitions; leaf ids come from a walk of the finished
+// tree, the row order from a stable sort by leaf rank.
+extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                                        int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
+                                        const float *gpair, const gbt_params *params, gbt_tree *tree,
+                                        uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace,
+                                        size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, rowptr && ent && nb && cuts && gpair && params && tree && workspace, GBT_EINVAL, "NULL argument");
+    const int B = params->max_bins, max_depth = params->max_depth;
+    int32_t st = check_sparse_shape(ctx, n, F, B);
+    if (st != GBT_OK) return st;
+    st = check_bins(ctx, F, B);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, ((uintptr_t)ent & 3) == 0, GBT_EINVAL, "ent must be 4-byte aligned");
+    GBT_REQUIRE(ctx, n >= 1 && nnz >= 0 && nnz < ((int64_t)1 << 32) - 64, GBT_EINVAL, "bad n or nnz");
+    GBT_REQUIRE(ctx, max_depth >= 0, GBT_EINVAL, "max_depth < 0");
+    GBT_REQUIRE(ctx, max_depth <= kMaxDepth, GBT_EUNSUPPORTED, "max_depth %d > %d", max_depth, kMaxDepth);
+    GBT_REQUIRE(ctx, params->lambda >= 0.0, GBT_EINVAL, "lambda < 0");
+    const int64_t cap = ((int64_t)1 << (max_depth + 1)) - 1;
+    GBT_REQUIRE(ctx, tree->capacity >= cap, GBT_EINVAL, "tree capacity %d < %lld", tree->capacity, (long long)cap);
+    GBT_REQUIRE(ctx, tree->feature && tree->bin && tree->default_left && tree->left && tree->right &&
+                         tree->threshold && tree->weight && tree->gain && tree->sumG && tree->sumH && tree->n_rows,
+                GBT_EINVAL, "tree arrays must be allocated");
+    const SparseGrowLayout L = sparse_grow_layout(n, nnz, F, B, max_depth);
+    GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
+
+    char *ws = (char *)workspace;
+    hipStream_t s = ctx->stream;
+    int32_t *gq = (int32_t *)(ws + L.gq);
+    int64_t *pool = (int64_t *)(ws + L.pool);
+    const int64_t bins = (int64_t)F * B, hist_len = bins * 2;
+    const int glen = gbt_sparse_hist_tile(ctx, bins);
+    struct Rows { const uint32_t *rowptr; const uint16_t *ent; const int32_t *gq; };
+    const Rows canon{rowptr, ent, gq};
+    uint32_t *w_rowptr[2] = {(uint32_t *)(ws + L.rowptr[0]), (uint32_t *)(ws + L.rowptr[1])};
+    uint16_t *w_ent[2] = {(uint16_t *)(ws + L.ent[0]), (uint16_t *)(ws + L.ent[1])};
+    int32_t *w_gq[2] = {(int32_t *)(ws + L.wgq[0]), (int32_t *)(ws + L.wgq[1])};
+    auto rows_of = [&](int buf) { return buf == 2 ? canon : Rows{w_rowptr[buf], w_ent[buf], w_gq[buf]}; };
+    std::vector<float> hcuts((size_t)F * (B - 1));
+    GBT_HIP(ctx, hipMemcpyAsync(hcuts.data(), cuts, hcuts.size() * sizeof(float), hipMemcpyDeviceToHost, s));
+
+    double scale[2];
+    int64_t *sums_dev = (int64_t *)(ws + L.scratch + 256);
+    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 24.0);
+    st = gpair_scale_impl(ctx, gpair, n, scale, ws + L.scratch);
+    if (st == GBT_OK) {
+        hipError_t e = gbt_launch_to_fixed(s, gpair, n, scale[0], scale[1], gq, sums_dev);
+        if (e != hipSuccess) st = gbt_fail(ctx, GBT_EHIP, "gbt_launch_to_fixed: %s", hipGetErrorString(e));
+    }
+    gbt_prof_end(ctx);
+    if (st != GBT_OK) return st;
+    const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
+    const double lambda = params->lambda;
+    const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
+    const double row_bytes = 12.0 + 2.0 * (double)nnz / (double)n;   // row pointer, pair, the average row's entries
+
+    std::vector<HistJob> hjobs;
+    auto launch_hist = [&](const Rows &R, int cls, double bytes) -> int32_t {
+        const size_t per_launch = kUploadBytes / sizeof(HistJob);
+        for (size_t j0 = 0; j0 < hjobs.size(); j0 += per_launch) {
+            const size_t nj = std::min(per_launch, hjobs.size() - j0);
+            int32_t st2 = upload(ctx, hjobs.data() + j0, nj * sizeof(HistJob), ws + L.jobs);
+            if (st2 != GBT_OK) return st2;
+            gbt_prof_begin(ctx, cls, j0 == 0 ? bytes : 0.0);
+            GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, R.rowptr, R.ent, R.gq, pool, (const HistJob *)(ws + L.jobs), (int)nj,
+                                                glen));
+            gbt_prof_end(ctx);
+        }
+        return GBT_OK;
+    };
+
+    if (max_depth > 0) {
+        GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)pool, 0, hist_len));
+        hjobs.clear();
+        add_sparse_hist_jobs(hjobs, 0, 0, (uint32_t)n, bins, glen, sparse_rows_per_job(ctx, n, bins, glen));
+        st = launch_hist(canon, GBT_PROF_HIST_ROOT, (double)n * row_bytes);
+        if (st != GBT_OK) return st;
+    }
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), sums_dev, 16, hipMemcpyDeviceToHost, s));
+    GBT_SYNC(ctx);
+    int64_t root_sums[2];
+    memcpy(root_sums, rb(ctx), 16);
+
+    auto set_node = [&](const HNode &nd) {
+        const double G = (double)nd.Gq * inv_sg, H = (double)nd.Hq * inv_sh;
+        tree->feature[nd.id] = -1;
+        tree->bin[nd.id] = 0;
+        tree->default_left[nd.id] = 0;
+        tree->left[nd.id] = tree->right[nd.id] = -1;
+        tree->threshold[nd.id] = INFINITY;
+        tree->gain[nd.id] = 0.0;
+        tree->sumG[nd.id] = G;
+        tree->sumH[nd.id] = H;
+        tree->weight[nd.id] = -G / (H + lambda);
+        tree->n_rows[nd.id] = nd.len;
+    };
+    std::vector<HNode> level, next, sel_nodes;
+    std::vector<gbt_split> splits, sel_splits;
+    std::vector<EvalNode> enodes;
+    std::vector<PartJob> pjobs;
+    std::vector<SubJob> sjobs;
+    HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1], 0, 2};
+    set_node(root);
+    if (max_depth > 0) level.push_back(root);
+    int32_t n_nodes = 1;
+    constexpr size_t kSplitRb = 512u << 10;
+
+    while (!level.empty()) {
+        // ---- EvaluateSplit for the level's nodes
+        enodes.resize(level.size());
+        for (size_t i = 0; i < level.size(); ++i)
+            enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
+        st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
+        if (st != GBT_OK) return st;
+        const size_t budget = GBT_STAGING_BYTES - kReadbackOff - kSplitRb;
+        const int chunks = gbt_eval_chunks(F, (int)enodes.size(), budget);
+        const size_t sbytes = enodes.size() * (size_t)chunks * sizeof(gbt_split);
+        GBT_REQUIRE(ctx, sbytes <= budget, GBT_EUNSUPPORTED, "level too wide");
+        gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)enodes.size() * (double)hist_len * 8.0);
+        GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)enodes.size(), nb, F, B, chunks,
+                                     inv_sg, inv_sh, lambda, params->min_child_weight, (gbt_split *)(ws + L.splits)));
+        gbt_prof_end(ctx);
+        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx) + kSplitRb, ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
+        GBT_SYNC(ctx);
+        sel_nodes.clear();
+        sel_splits.clear();
+        for (size_t i = 0; i < level.size(); ++i) {
+            const gbt_split sp = merge_chunks((const gbt_split *)(rb(ctx) + kSplitRb) + i * chunks, chunks);
+            const HNode &nd = level[i];
+            if (sp.valid && sp.gain > min_gain && sp.feature >= 0 && sp.feature < F && sp.bin >= 0 && sp.bin < B &&
+                nd.len > 0) {
+                sel_nodes.push_back(nd);
+                sel_splits.push_back(sp);
+            }
+        }
+        level.clear();
+        if (sel_nodes.empty()) break;
+
+        // ---- RepartitionInstances: the whole level in one launch
+        const int wcur = sel_nodes[0].buf, wnext = wcur == 0 ? 1 : 0;
+        const Rows cur = rows_of(wcur);
+        const int child_depth = sel_nodes[0].depth + 1;
+        const bool children_need_hist = child_depth < max_depth;
+        const uint32_t tile = (uint32_t)gbt_sparse_part_tile();
+        pjobs.clear();
+        uint32_t tile_cursor = 0;
+        double part_rows = 0;
+        for (size_t k = 0; k < sel_nodes.size(); ++k) {
+            PartJob j;
+            j.seg_begin = sel_nodes[k].begin;
+            j.seg_len = sel_nodes[k].len;
+            j.feature = (uint32_t)sel_splits[k].feature;
+            j.bin = (uint32_t)sel_splits[k].bin;
+            j.default_left = (uint32_t)sel_splits[k].default_left;
+            j.tile_begin = tile_cursor;
+            j.n_tiles = (j.seg_len + tile - 1) / tile;
+            j.pad = 2;
+            j.hist_off = 0;
+            tile_cursor += j.n_tiles;
+            part_rows += j.seg_len;
+            pjobs.push_back(j);
+        }
+        GBT_REQUIRE(ctx, pjobs.size() * sizeof(PartJob) <= kUploadBytes && pjobs.size() * 16 <= kSplitRb, GBT_EUNSUPPORTED,
+                    "level too wide");
+        st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
+        if (st != GBT_OK) return st;
+        gbt_prof_begin(ctx, GBT_PROF_PARTITION, part_rows * (children_need_hist ? 2.0 * row_bytes : row_bytes - 8.0));
+        GBT_HIP(ctx, gbt_launch_sparse_partition(s, cur.rowptr, cur.ent, cur.gq, w_rowptr[wnext], w_ent[wnext], w_gq[wnext],
+                                                 B, children_need_hist, (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
+                                                 (int)tile_cursor, (unsigned long long *)(ws + L.state)));
+        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 16, hipMemcpyDeviceToHost, s));
+        gbt_prof_end(ctx);
+        GBT_SYNC(ctx);
+        const uint32_t *cur_words = (const uint32_t *)rb(ctx);   // four words per job; the first: left rows
+
+        // ---- children, in creation order; the child with fewer rows is built from rows
+        hjobs.clear();
+        sjobs.clear();
+        next.clear();
+        int64_t built_rows = 0;
+        const int32_t first_child = n_nodes;
+        const int child_buf = children_need_hist ? wnext : wcur;
+        struct Built { uint64_t off; uint32_t begin, len; };
+        std::vector<Built> built;
+        for (size_t k = 0; k < pjobs.size(); ++k) {
+            const HNode &nd = sel_nodes[k];
+            const gbt_split &sp = sel_splits[k];
+            const uint32_t nl = cur_words[4 * k];
+            GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
+            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, child_depth, child_buf};
+            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, child_depth, child_buf};
+            n_nodes += 2;
+            tree->feature[nd.id] = sp.feature;
+            tree->bin[nd.id] = sp.bin;
+            tree->default_left[nd.id] = sp.default_left;
+            tree->left[nd.id] = lc.id;
+            tree->right[nd.id] = rc.id;
+            tree->gain[nd.id] = sp.gain;
+            tree->threshold[nd.id] = sp.bin < B - 1 ? hcuts[(size_t)sp.feature * (B - 1) + sp.bin] : INFINITY;
+            set_node(lc);
+            set_node(rc);
+            if (children_need_hist) {
+                const bool left_small = lc.len <= rc.len;
+                const HNode &sm = left_small ? lc : rc, &lg = left_small ? rc : lc;
+                built.push_back(Built{(uint64_t)sm.id * (uint64_t)hist_len, sm.begin, sm.len});
+                built_rows += sm.len;
+                sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)sm.id * (uint64_t)hist_len,
+                                       (uint64_t)lg.id * (uint64_t)hist_len});
+                next.push_back(lc);
+                next.push_back(rc);
+            }
+        }
+        if (children_need_hist) {
+            const int32_t n_children = n_nodes - first_child;
+            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
+            GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
+                                             (int64_t)n_children * hist_len));
+            gbt_prof_end(ctx);
+            const uint32_t rpj = sparse_rows_per_job(ctx, built_rows, bins, glen);
+            for (const Built &b : built) add_sparse_hist_jobs(hjobs, b.off, b.begin, b.len, bins, glen, rpj);
+            st = launch_hist(rows_of(wnext), GBT_PROF_HIST_NODE, (double)built_rows * row_bytes);
+            if (st != GBT_OK) return st;
+            GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
+            st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
+            if (st != GBT_OK) return st;
+            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
+            GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
+            gbt_prof_end(ctx);
+        }
+        level.swap(next);
+    }
+    tree->n_nodes = n_nodes;
+
+    // ---- each row's leaf by a walk of the finished tree; the row order by a stable sort on leaf rank
+    int32_t *leaf_ids = leaf_of_row_out ? leaf_of_row_out : (int32_t *)w_rowptr[0];
+    if (leaf_of_row_out || row_idx_out) {
+        const SparseRowsArg sr{rowptr, ent, B};
+        gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (row_bytes - 8.0 + 4.0));
+        st = predict_impl(ctx, tree, 1, nullptr, 1, 0, nullptr, n, F, 0.0, nullptr, leaf_ids, ws + L.tree_stage,
+                          L.tree_stage_bytes, &sr);
+        gbt_prof_end(ctx);
+        if (st != GBT_OK) return st;
+    }
+    if (row_idx_out) {
+        std::vector<uint32_t> rank((size_t)n_nodes, 0u);
+        std::vector<int32_t> stack{0};
+        uint32_t n_ranks = 0;
+        while (!stack.empty()) {
+            const int32_t id = stack.back();
+            stack.pop_back();
+            if (tree->feature[id] < 0) {
+                rank[(size_t)id] = n_ranks++;
+            } else {
+                stack.push_back(tree->right[id]);
+                stack.push_back(tree->left[id]);
+            }
+        }
+        const size_t per_upload = kUploadBytes / 4;
+        for (size_t i0 = 0; i0 < rank.size(); i0 += per_upload) {
+            st = upload(ctx, rank.data() + i0, std::min(per_upload, rank.size() - i0) * 4, ws + L.rank_tbl + i0 * 4);
+            if (st != GBT_OK) return st;
+        }
+        uint32_t *key_tmp[2] = {w_rowptr[1], (uint32_t *)w_gq[0] + n};
+        uint32_t *val_tmp[2] = {(uint32_t *)w_gq[0], (uint32_t *)w_gq[1]};
+        gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
+        GBT_HIP(ctx, gbt_launch_order_rows(s, leaf_ids, (const uint32_t *)(ws + L.rank_tbl), (uint32_t)n_nodes, n_ranks, n,
+                                           key_tmp, val_tmp, ws + L.order, row_idx_out));
+        gbt_prof_end(ctx);
+    }
+    GBT_SYNC(ctx);
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *rowptr,
+                                      const uint16_t *ent, int64_t n, int32_t F, int32_t max_bins, double eta,
+                                      float *margin, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, rowptr && ent && margin, GBT_EINVAL, "NULL argument");
+    int32_t st = check_sparse_shape(ctx, n, F, max_bins);
+    if (st != GBT_OK) return st;
+    const SparseRowsArg sr{rowptr, ent, max_bins};
+    st = predict_impl(ctx, trees, n_trees, nullptr, 1, 0, nullptr, n, F, eta, margin, nullptr, workspace, workspace_bytes,
+                      &sr);
     if (st != GBT_OK) return st;
     GBT_SYNC(ctx);
     return GBT_OK;

@@ -1,0 +1,488 @@
+// Sparse-native row layout (Sec. 1: sparse input is supported; Sec. 2.2: the quantised matrix is
+// stored compressed).  A row keeps only its present elements, each as a 16-bit global bin id
+//     gid = feature * B + symbol            (B = max_bins, F * B <= 65536),
+// ascending inside the row; rowptr[r] .. rowptr[r+1] delimit row r in the entry stream.  A missing
+// element costs nothing instead of one symbol, so a matrix that is 80% empty moves about a third
+// of the bytes of its dense packing, and the histogram kernel issues atomics for present elements
+// only.  gid * 2 is also the element's place in the node's [F][B][2] histogram.
+//
+// The entry stream is read as aligned 32-bit words, eight words per row and step, so the buffer
+// must extend 16 entries past the last one (gbt_sparse_capacity).
+#include "gbt_internal.h"
+
+namespace {
+
+constexpr int kHShift = 30;                        // [ g : 34 bits signed | h : 30 bits ] as in the dense kernels
+constexpr uint32_t kHMask = (1u << kHShift) - 1u;
+
+__device__ __forceinline__ unsigned long long sp_pack_pair(int2 q) {
+    return ((unsigned long long)(long long)q.x << kHShift) + (unsigned long long)(uint32_t)q.y;
+}
+
+// The rare events that the packed add cannot hold -- a carry out of the h field (it lands in the g
+// field as +1), a wrap of the g field -- are seen by the lane whose add caused them in the returned
+// word.  It corrects the node's histogram in HBM right away (integer adds commute with the merge of
+// the LDS words), so the LDS histogram needs no side counters: 8 bytes per bin.
+__device__ __forceinline__ void sp_check(int64_t *out2, uint32_t idx, unsigned long long old,
+                                         unsigned long long addv, uint32_t hq) {
+    uint32_t olo = (uint32_t)old, ohi = (uint32_t)(old >> 32);
+    const bool danger = ((olo & 0x3FC00000u) == 0x3FC00000u) | ((ohi + 0x82000000u) < 0x04000000u);
+    if (danger) {
+        asm volatile("" : "+v"(olo), "+v"(ohi));
+        const uint32_t carry = ((olo & kHMask) + hq) >> kHShift;
+        const uint32_t alo = (uint32_t)addv, ahi = (uint32_t)(addv >> 32);
+        const uint32_t nlo = olo + alo;
+        const uint32_t nhi = ohi + ahi + (nlo < olo ? 1u : 0u);
+        const int32_t ovf = (int32_t)((ohi ^ nhi) & (ahi ^ nhi));
+        const int64_t wraps = ovf < 0 ? ((int32_t)nhi < 0 ? 1 : -1) : 0;
+        if (carry != 0 || wraps != 0) {
+            const int64_t dg = wraps * ((int64_t)1 << (64 - kHShift)) - (int64_t)carry;
+            atomicAdd((unsigned long long *)(out2 + 2 * (int64_t)idx), (unsigned long long)dg);
+            if (carry) atomicAdd((unsigned long long *)(out2 + 2 * (int64_t)idx + 1), (unsigned long long)carry << kHShift);
+        }
+    }
+}
+
+// ---- layout conversion -----------------------------------------------------
+constexpr int kScanTile = 4096;   // counts per workgroup of the scan kernels (256 threads x 16)
+
+// len[r] = present elements of row r (sym != missing); len[n] = 0
+__global__ __launch_bounds__(256) void sparse_count_kernel(const uint16_t *__restrict__ sym, int64_t n, int F,
+                                                           uint32_t missing, uint32_t *__restrict__ len) {
+    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r <= n; r += (int64_t)gridDim.x * 256) {
+        uint32_t c = 0;
+        if (r < n) {
+            const uint16_t *row = sym + r * F;
+            for (int f = 0; f < F; ++f) c += row[f] != missing;
+        }
+        len[r] = c;
+    }
+}
+
+// exclusive scan of v[0..m) in place, three launches; total (64-bit) to *total_out
+__global__ __launch_bounds__(256) void scan_tile_sums_kernel(const uint32_t *__restrict__ v, int64_t m,
+                                                             uint64_t *__restrict__ tile_sum) {
+    __shared__ uint64_t red[4];
+    const int64_t t0 = (int64_t)blockIdx.x * kScanTile;
+    uint64_t s = 0;
+    for (int k = 0; k < kScanTile / 256; ++k) {
+        const int64_t i = t0 + (int64_t)k * 256 + threadIdx.x;
+        if (i < m) s += v[i];
+    }
+    for (int o = 32; o > 0; o >>= 1)
+        s += ((uint64_t)(uint32_t)__shfl_xor((int)(s >> 32), o) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)s, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void scan_tile_offsets_kernel(uint64_t *__restrict__ tile_sum, int64_t n_tiles,
+                                                                uint64_t *__restrict__ total_out) {
+    __shared__ uint64_t buf[256];
+    uint64_t carry = 0;
+    for (int64_t b0 = 0; b0 < n_tiles; b0 += 256) {
+        const int64_t i = b0 + threadIdx.x;
+        const uint64_t x = i < n_tiles ? tile_sum[i] : 0;
+        buf[threadIdx.x] = x;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {
+            const uint64_t y = (int)threadIdx.x >= o ? buf[threadIdx.x - o] : 0;
+            __syncthreads();
+            buf[threadIdx.x] += y;
+            __syncthreads();
+        }
+        if (i < n_tiles) tile_sum[i] = carry + buf[threadIdx.x] - x;
+        carry += buf[255];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total_out = carry;
+}
+
+__global__ __launch_bounds__(256) void scan_apply_u32_kernel(uint32_t *__restrict__ v, int64_t m,
+                                                             const uint64_t *__restrict__ tile_off) {
+    // thread t owns 16 consecutive counts of the tile
+    __shared__ uint32_t part[256];
+    const int64_t i0 = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * 16;
+    uint32_t x[16], s = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        x[k] = i0 + k < m ? v[i0 + k] : 0;
+        s += x[k];
+    }
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+        const uint32_t y = (int)threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+        __syncthreads();
+        part[threadIdx.x] += y;
+        __syncthreads();
+    }
+    uint32_t run = (uint32_t)tile_off[blockIdx.x] + part[threadIdx.x] - s;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        if (i0 + k < m) v[i0 + k] = run;
+        run += x[k];
+    }
+}
+
+__global__ __launch_bounds__(256) void sparse_fill_kernel(const uint16_t *__restrict__ sym, int64_t n, int F, int B,
+                                                          uint32_t missing, const uint32_t *__restrict__ rowptr,
+                                                          uint16_t *__restrict__ ent) {
+    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < n; r += (int64_t)gridDim.x * 256) {
+        const uint16_t *row = sym + r * F;
+        uint32_t o = rowptr[r];
+        for (int f = 0; f < F; ++f) {
+            const uint32_t s = row[f];
+            if (s != missing) ent[o++] = (uint16_t)((uint32_t)f * (uint32_t)B + s);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_u16_tail_kernel(uint16_t *p, int count) {
+    if ((int)threadIdx.x < count) p[threadIdx.x] = 0;
+}
+
+// ---- BuildPartialHistograms over sparse rows --------------------------------
+// One workgroup: rows [row_begin, row_begin + n_rows), global bin ids [f0, f0 + ft) (HistJob's
+// fields, reused), a private LDS histogram of that id range.  lane = one row: its entries are
+// fetched 16 at a time as eight aligned words (all loads of a step in flight together) and cut out
+// of registers; an entry outside the job's id range or outside the row is skipped, a step that no
+// lane of the wave needs is skipped by the whole wave.
+constexpr int kSpBlock = 512;
+struct __attribute__((packed, aligned(4))) Words4 {   // four words at a 4-byte aligned address
+    uint32_t x, y, z, w;
+};
+
+__global__ __launch_bounds__(kSpBlock) void sparse_hist_kernel(const uint32_t *__restrict__ rowptr,
+                                                               const uint32_t *__restrict__ ent_words,
+                                                               const int2 *__restrict__ gq,
+                                                               int64_t *__restrict__ pool,
+                                                               const HistJob *__restrict__ jobs) {
+    extern __shared__ unsigned long long lds[];
+    const HistJob job = jobs[blockIdx.x];
+    const uint32_t g0 = job.f0, glen = job.ft;
+    int64_t *out = pool + job.hist_off + 2 * (int64_t)g0;
+    for (uint32_t i = threadIdx.x; i < glen; i += kSpBlock) lds[i] = 0;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < job.n_rows; i += kSpBlock) {
+        const uint64_t r = (uint64_t)job.row_begin + i;
+        const uint32_t s = rowptr[r], e = rowptr[r + 1];
+        const int2 q = gq[r];
+        const unsigned long long addv = sp_pack_pair(q);
+        const uint32_t hq = (uint32_t)q.y;
+        const uint32_t a = s & 1u, end = a + (e - s);     // the row is halfwords [a, end) from word s >> 1 on
+        const uint32_t *wp = ent_words + (s >> 1);
+        for (uint32_t k0 = 0; k0 < end; k0 += 16) {
+            const Words4 lo = *(const Words4 *)(wp + (k0 >> 1));
+            const Words4 hi = *(const Words4 *)(wp + (k0 >> 1) + 4);
+            const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            uint32_t rel[16];
+            unsigned long long old[16];
+            uint32_t live = 0;
+            // all atomics of the step are issued before the first returned word is looked at
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const uint32_t gid = (w[k >> 1] >> (16 * (k & 1))) & 0xffffu;
+                const uint32_t pos = k0 + (uint32_t)k;
+                rel[k] = gid - g0;
+                const bool in = pos >= a && pos < end && rel[k] < glen;
+                if (in) {
+                    live |= 1u << k;
+                    old[k] = atomicAdd(&lds[rel[k]], addv);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (live & (1u << k)) sp_check(out, rel[k], old[k], addv, hq);
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < glen; i += kSpBlock) {
+        const unsigned long long w = lds[i];
+        if (w == 0) continue;
+        const int64_t g = (int64_t)w >> kHShift;
+        const int64_t h = (int64_t)(w & kHMask);
+        if (g != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i), (unsigned long long)g);
+        if (h != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i + 1), (unsigned long long)h);
+    }
+}
+
+// ---- RepartitionInstances over sparse rows ----------------------------------
+// One launch per level, order inside a child not kept.  A tile of kSpTile rows finds each row's
+// side (the row's entry of the split feature is looked up among its ascending ids; a row without
+// one is missing and takes the default side), ranks rows and entries per side inside the tile and
+// reserves room in both children with two 64-bit atomics on the node's cursors
+// [ entries : high word | rows : low word ], one for each side.  Left rows and their entries fill
+// the node's row range and entry range from the front, right rows from the back, so both children
+// stay contiguous in rows AND in entries, and rowptr[r + 1] - rowptr[r] stays a row's length.
+// move == 0: only the left rows are counted (the last level).
+constexpr int kSpTile = 2048;
+constexpr int kSpRowsPerThread = kSpTile / kSpBlock;   // 4
+constexpr int kSpGroups = kSpRowsPerThread * (kSpBlock / 64);   // (k, wave) groups of 64 rows: 32
+
+__device__ inline int find_part_job(const PartJob *jobs, int n_jobs, uint32_t tile) {
+    int lo = 0, hi = n_jobs;   // last job with tile_begin <= tile
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (jobs[mid].tile_begin <= tile) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// the row's entry with an id in [lo, lo + B), or 0xffffffff
+__device__ inline uint32_t find_feature_entry(const uint16_t *__restrict__ ent, uint32_t s, uint32_t e, uint32_t lo,
+                                              uint32_t B) {
+    // first entry >= lo by bisection (ids ascend inside a row)
+    uint32_t a = s, b = e;
+    while (a < b) {
+        const uint32_t mid = a + ((b - a) >> 1);
+        if ((uint32_t)ent[mid] < lo) a = mid + 1; else b = mid;
+    }
+    if (a < e) {
+        const uint32_t g = ent[a];
+        if (g - lo < B) return g;
+    }
+    return 0xffffffffu;
+}
+
+__global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *__restrict__ src_rowptr,
+                                                               const uint16_t *__restrict__ src_ent,
+                                                               const int2 *__restrict__ src_gq,
+                                                               uint32_t *__restrict__ dst_rowptr,
+                                                               uint16_t *__restrict__ dst_ent,
+                                                               int2 *__restrict__ dst_gq, uint32_t B, int move,
+                                                               const PartJob *__restrict__ jobs, int n_jobs,
+                                                               unsigned long long *__restrict__ cursor) {
+    __shared__ uint32_t grp_rows[2][kSpGroups];   // [side][group]: rows, then their exclusive offsets
+    __shared__ uint32_t grp_ent[2][kSpGroups];
+    __shared__ unsigned long long base[2];        // what the cursors returned
+    __shared__ uint32_t tot[4];                   // rows L, rows R, entries L, entries R of the tile
+    const int j = find_part_job(jobs, n_jobs, blockIdx.x);
+    const PartJob job = jobs[j];
+    const uint32_t t_local = blockIdx.x - job.tile_begin;
+    const uint32_t seg_end = job.seg_begin + job.seg_len;
+    const uint32_t r0 = job.seg_begin + t_local * (uint32_t)kSpTile;
+    const uint32_t lo = job.feature * B, thr = lo + job.bin;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    uint32_t rs[kSpRowsPerThread], rlen[kSpRowsPerThread], within_rows[kSpRowsPerThread], within_ent[kSpRowsPerThread];
+    bool live[kSpRowsPerThread], left[kSpRowsPerThread];
+#pragma unroll
+    for (int k = 0; k < kSpRowsPerThread; ++k) {
+        const uint32_t r = r0 + (uint32_t)k * kSpBlock + threadIdx.x;
+        live[k] = r < seg_end;
+        rs[k] = 0;
+        rlen[k] = 0;
+        left[k] = false;
+        if (live[k]) {
+            rs[k] = src_rowptr[r];
+            rlen[k] = src_rowptr[r + 1] - rs[k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kSpRowsPerThread; ++k) {
+        if (live[k]) {
+            const uint32_t g = find_feature_entry(src_ent, rs[k], rs[k] + rlen[k], lo, B);
+            left[k] = g == 0xffffffffu ? job.default_left != 0 : g <= thr;
+        }
+    }
+    // ranks inside each group of 64 rows: rows by ballot, entries by a 64-bit scan holding both sides
+#pragma unroll
+    for (int k = 0; k < kSpRowsPerThread; ++k) {
+        const uint64_t bl = __ballot(live[k] && left[k]), br = __ballot(live[k] && !left[k]);
+        const uint64_t below = (1ull << lane) - 1ull;
+        within_rows[k] = (uint32_t)__popcll((left[k] ? bl : br) & below);
+        unsigned long long x = !live[k] ? 0ull : left[k] ? (unsigned long long)rlen[k] : ((unsigned long long)rlen[k] << 32);
+        unsigned long long incl = x;
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t ylo = (uint32_t)__shfl_up((int)(uint32_t)incl, o);
+            const uint32_t yhi = (uint32_t)__shfl_up((int)(uint32_t)(incl >> 32), o);
+            if (lane >= o) incl += ((unsigned long long)yhi << 32) | ylo;
+        }
+        const unsigned long long excl = incl - x;
+        within_ent[k] = left[k] ? (uint32_t)excl : (uint32_t)(excl >> 32);
+        if (lane == 63) {
+            const int grp = k * (kSpBlock / 64) + wave;
+            grp_rows[0][grp] = (uint32_t)__popcll(bl);
+            grp_rows[1][grp] = (uint32_t)__popcll(br);
+            grp_ent[0][grp] = (uint32_t)incl;
+            grp_ent[1][grp] = (uint32_t)(incl >> 32);
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {   // exclusive offsets over the groups; lanes 0..31 rows, 32..63 entries; both sides
+        static_assert(kSpGroups == 32, "one half wave per table");
+        const int grp = lane & 31;
+        for (int side = 0; side < 2; ++side) {
+            uint32_t *tab = lane < 32 ? grp_rows[side] : grp_ent[side];
+            const uint32_t v = tab[grp];
+            uint32_t incl = v;
+            for (int o = 1; o < 32; o <<= 1) {
+                const uint32_t y = (uint32_t)__shfl_up((int)incl, o);
+                if (grp >= o) incl += y;
+            }
+            tab[grp] = incl - v;
+            if (grp == 31) tot[(lane < 32 ? 0 : 2) + side] = incl;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        base[0] = atomicAdd(&cursor[2 * j], ((unsigned long long)tot[2] << 32) | tot[0]);
+        if (move) base[1] = atomicAdd(&cursor[2 * j + 1], ((unsigned long long)tot[3] << 32) | tot[1]);
+    }
+    if (!move) return;
+    __syncthreads();
+    const uint32_t ent_begin = src_rowptr[job.seg_begin], ent_end = src_rowptr[seg_end];
+    const uint32_t row_l = job.seg_begin + (uint32_t)base[0], ent_l = ent_begin + (uint32_t)(base[0] >> 32);
+    const uint32_t row_r = seg_end - (uint32_t)base[1] - tot[1], ent_r = ent_end - (uint32_t)(base[1] >> 32) - tot[3];
+    if (t_local == 0 && threadIdx.x == 0) dst_rowptr[seg_end] = ent_end;   // the segment's closing row pointer
+#pragma unroll
+    for (int k = 0; k < kSpRowsPerThread; ++k) {
+        if (!live[k]) continue;
+        const uint32_t r = r0 + (uint32_t)k * kSpBlock + threadIdx.x;
+        const int grp = k * (kSpBlock / 64) + wave;
+        const int side = left[k] ? 0 : 1;
+        const uint32_t drow = (left[k] ? row_l : row_r) + grp_rows[side][grp] + within_rows[k];
+        const uint32_t dent = (left[k] ? ent_l : ent_r) + grp_ent[side][grp] + within_ent[k];
+        dst_rowptr[drow] = dent;
+        dst_gq[drow] = src_gq[r];
+        for (uint32_t q = 0; q < rlen[k]; ++q) dst_ent[dent + q] = src_ent[rs[k] + q];
+    }
+}
+
+// ---- Sec. 2.4 prediction over sparse rows -----------------------------------
+// One row per thread, trees in order, nodes staged in LDS as in the dense kernels; the row's entry of
+// a node's feature is found by bisection over the row's ascending ids.
+struct SpNode {
+    int32_t feature, bin, left, right;
+    int32_t dl, pad;
+    double weight;
+};
+__global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const DevTree *trees, int n_trees,
+                                                          const uint32_t *__restrict__ rowptr,
+                                                          const uint16_t *__restrict__ ent, int64_t n, uint32_t B,
+                                                          double eta, float *margin, int32_t *leaf_out,
+                                                          int rows_per_block) {
+    extern __shared__ SpNode sp_nodes[];
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+    for (int t = 0; t < n_trees; ++t) {
+        const DevTree T = trees[t];
+        __syncthreads();
+        for (int i = threadIdx.x; i < T.n_nodes; i += 256) {
+            SpNode nd;
+            nd.feature = ((const int32_t *)(ws + T.feature))[i];
+            nd.bin = ((const int32_t *)(ws + T.bin))[i];
+            nd.left = ((const int32_t *)(ws + T.left))[i];
+            nd.right = ((const int32_t *)(ws + T.right))[i];
+            nd.dl = ((const int32_t *)(ws + T.default_left))[i];
+            nd.pad = 0;
+            nd.weight = ((const double *)(ws + T.weight))[i];
+            sp_nodes[i] = nd;
+        }
+        __syncthreads();
+        for (int64_t r = r0 + threadIdx.x; r < r1; r += 256) {
+            const uint32_t s = rowptr[r], e = rowptr[r + 1];
+            int node = 0;
+            for (int step = 0; step < T.n_nodes; ++step) {
+                const SpNode nd = sp_nodes[node];
+                if (nd.feature < 0) break;
+                const uint32_t lo = (uint32_t)nd.feature * B;
+                const uint32_t g = find_feature_entry(ent, s, e, lo, B);
+                const bool go_left = g == 0xffffffffu ? nd.dl != 0 : g <= lo + (uint32_t)nd.bin;
+                node = go_left ? nd.left : nd.right;
+            }
+            if (leaf_out) leaf_out[r] = node;
+            else margin[r] = (float)((double)margin[r] + eta * sp_nodes[node].weight);
+        }
+    }
+}
+
+int grid_rows(int64_t n) {
+    int64_t g = (n + 255) / 256;
+    if (g < 1) g = 1;
+    if (g > 65536) g = 65536;
+    return (int)g;
+}
+
+}  // namespace
+
+int64_t gbt_sparse_scan_tiles(int64_t n) { return (n + 1 + kScanTile - 1) / kScanTile; }
+
+// rowptr[0..n] = exclusive scan of the rows' present counts; *total_dev (device) = number of entries
+hipError_t gbt_launch_sparse_rowptr(hipStream_t s, const uint16_t *sym, int64_t n, int F, uint32_t missing,
+                                    uint32_t *rowptr, uint64_t *tile_ws, uint64_t *total_dev) {
+    const int64_t m = n + 1, tiles = gbt_sparse_scan_tiles(n);
+    sparse_count_kernel<<<grid_rows(m), 256, 0, s>>>(sym, n, F, missing, rowptr);
+    scan_tile_sums_kernel<<<(unsigned)tiles, 256, 0, s>>>(rowptr, m, tile_ws);
+    scan_tile_offsets_kernel<<<1, 256, 0, s>>>(tile_ws, tiles, total_dev);
+    scan_apply_u32_kernel<<<(unsigned)tiles, 256, 0, s>>>(rowptr, m, tile_ws);
+    return hipGetLastError();
+}
+
+hipError_t gbt_launch_sparse_fill(hipStream_t s, const uint16_t *sym, int64_t n, int F, int B, uint32_t missing,
+                                  const uint32_t *rowptr, uint16_t *ent, int64_t nnz, int64_t capacity) {
+    if (n > 0) sparse_fill_kernel<<<grid_rows(n), 256, 0, s>>>(sym, n, F, B, missing, rowptr, ent);
+    const int64_t tail = capacity - nnz;   // the slack that word-wise readers may touch: defined values
+    if (tail > 0) fill_u16_tail_kernel<<<1, 256, 0, s>>>(ent + nnz, (int)(tail < 256 ? tail : 256));
+    return hipGetLastError();
+}
+
+// ids per LDS tile for a total of `bins` global bin ids (8 bytes of LDS per id)
+int gbt_sparse_hist_tile(const gbt_ctx *ctx, int64_t bins) {
+    size_t limit = ctx->lds_per_block;
+    if (ctx->hist_lds_kb > 0 && (size_t)ctx->hist_lds_kb * 1024 < limit) limit = (size_t)ctx->hist_lds_kb * 1024;
+    const int64_t cap = (int64_t)(limit / 8);
+    const int64_t tiles = (bins + cap - 1) / cap;
+    return (int)((bins + tiles - 1) / tiles);
+}
+
+hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, const int32_t *gq,
+                                  int64_t *pool, const HistJob *jobs, int n_jobs, int max_glen) {
+    if (n_jobs <= 0) return hipSuccess;
+    const size_t lds = (size_t)max_glen * 8;
+    static size_t configured = 0;
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)sparse_hist_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        configured = lds;
+    }
+    sparse_hist_kernel<<<n_jobs, kSpBlock, lds, ctx->stream>>>(rowptr, (const uint32_t *)ent, (const int2 *)gq, pool,
+                                                               jobs);
+    return hipGetLastError();
+}
+
+int gbt_sparse_part_tile() { return kSpTile; }
+
+hipError_t gbt_launch_sparse_partition(hipStream_t s, const uint32_t *src_rowptr, const uint16_t *src_ent,
+                                       const int32_t *src_gq, uint32_t *dst_rowptr, uint16_t *dst_ent,
+                                       int32_t *dst_gq, int B, bool move, const PartJob *jobs, int n_jobs,
+                                       int n_tiles, unsigned long long *cursor) {
+    if (n_jobs <= 0 || n_tiles <= 0) return hipSuccess;
+    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)cursor, 0, 2 * (int64_t)n_jobs);
+    if (e != hipSuccess) return e;
+    sparse_part_kernel<<<n_tiles, kSpBlock, 0, s>>>(src_rowptr, src_ent, (const int2 *)src_gq, dst_rowptr, dst_ent,
+                                                    (int2 *)dst_gq, (uint32_t)B, move ? 1 : 0, jobs, n_jobs, cursor);
+    return hipGetLastError();
+}
+
+// the trees staged as for gbt_launch_predict; nodes of one tree must fit LDS (32 bytes each)
+hipError_t gbt_launch_sparse_walk(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
+                                  const uint32_t *rowptr, const uint16_t *ent, int64_t n, int B, double eta,
+                                  float *margin, int32_t *leaf_out, int max_nodes) {
+    if (n <= 0 || n_trees <= 0) return hipSuccess;
+    const size_t lds = (size_t)max_nodes * sizeof(SpNode);
+    static size_t configured = 0;
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)sparse_walk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        configured = lds;
+    }
+    const int rows_per_block = 2048;
+    const int64_t grid = (n + rows_per_block - 1) / rows_per_block;
+    sparse_walk_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, rowptr, ent, n, (uint32_t)B, eta, margin,
+                                                        leaf_out, rows_per_block);
+    return hipGetLastError();
+}
