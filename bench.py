@@ -113,6 +113,8 @@ def main():
     ap.add_argument("--policy", choices=["depthwise", "lossguide"], default="depthwise",
                     help="node expansion order (Sec. 2.3); lossguide grows --max-leaves leaves, no depth cap")
     ap.add_argument("--max-leaves", type=int, default=0, help="lossguide: leaf budget (default 2^max_depth)")
+    ap.add_argument("--layout", choices=["dense", "sparse"], default="dense",
+                    help="sparse: rows keep only their present elements (16-bit global bin ids); depth-wise only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of the packed matrix (a kernel of known size to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -158,6 +160,16 @@ def main():
     packed, bits = ctx.compress(sym, mv)
     torch.cuda.synchronize()
     t_comp = time.time() - t0
+    sparse = a.layout == "sparse"
+    t_sparse = None
+    if sparse:
+        if a.policy != "depthwise":
+            sys.exit("bench.py: --layout sparse grows depth-wise only")
+        t0 = time.time()
+        rowptr, ent, nnz = ctx.compress_sparse(sym, p["max_bins"], ms)
+        torch.cuda.synchronize()
+        t_sparse = time.time() - t0
+        log(f"sparse rows: {nnz} present elements ({nnz / (n * F):.1%}), {t_sparse * 1e3:.1f} ms")
     del Xd, sym
     torch.cuda.empty_cache()
     log(f"H2D {t_h2d:.2f} s, quantise {t_quant * 1e3:.1f} ms, compress {t_comp * 1e3:.1f} ms, bits={bits}")
@@ -182,6 +194,12 @@ def main():
             margin.zero_()
         if not given:
             ctx.gradients(p["objective"], margin, y, out=gp)
+        if sparse:
+            tree, _, _ = ctx.grow_tree_sparse(rowptr, ent, n, nnz, F, nb, cuts, gp, params, want_rows=outputs,
+                                              want_leaf=outputs)
+            ctx.predict_sparse([tree], margin, eta, rowptr, ent, n, F, p["max_bins"])
+            trees.append(tree)
+            return
         if lossguide:
             tree, _, _ = ctx.grow_tree_lossguide(packed, bits, n, F, ms, nb, cuts, gp, lg_params, max_leaves,
                                                  want_rows=outputs, want_leaf=outputs)
@@ -249,11 +267,15 @@ def main():
     hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_static_kernel"
     node_kernel = "part_hist_kernel (partition + one child's histogram in one pass)" if path == 2 else hist_kernel
     part_kernel = ("part_flag_kernel + part_scan_kernel (row counts of the last level)" if path == 2 else
-                   "part_fused_kernel" if path == 1 else "part_flag_kernel + part_scan_kernel + part_move_kernel")
+                   ("part_fused_kernel" if (F * bits + 31) // 32 == 4 else "part_staged_kernel") if path == 1 else
+                   "part_flag_kernel + part_scan_kernel + part_move_kernel")
+    if sparse:
+        hist_kernel = node_kernel = "sparse_hist_kernel"
+        part_kernel = "sparse_part_kernel"
     roofline_root = roof(["hist_root"], hist_kernel)
     roofline_node = roof(["hist_node"], node_kernel)
     roofline_partition = roof(["partition"], part_kernel)
-    traffic = measured_traffic(a.config)
+    traffic = None if sparse else measured_traffic(a.config)
     if traffic:
         for obj, key in ((roofline_root, "hist_root_launch_bytes"), (roofline_node, "hist_node_launch_avg_bytes"),
                          (roofline_partition, "partition_launch_avg_bytes")):
@@ -280,7 +302,8 @@ def main():
         "config": {"workload": f"C{a.config}: {n} rows x {F} features, {p['max_bins']} bins, {bits}-bit packing, "
                                f"depth {p['max_depth']}, lambda {p['lam']}, {p['objective']} objective",
                    "rows": n, "features": F, "bits": bits, "max_depth": p["max_depth"],
-                   "policy": a.policy, **({"max_leaves": max_leaves} if lossguide else {})},
+                   "policy": a.policy, **({"max_leaves": max_leaves} if lossguide else {}),
+                   "layout": a.layout, **({"present_elements": nnz} if sparse else {})},
         "seconds_per_tree": ms_per_step * 1e-3,
         "with_row_order_and_leaf_ids": (None if ms_per_step_outputs is None else
                                         {"ms_per_step": ms_per_step_outputs,
@@ -293,7 +316,8 @@ def main():
         "roofline_partition": roofline_partition,
         "grow_tree_path": path,
         "device_ms_per_step": {k: v["ms"] / a.steps for k, v in prof.items()},
-        "preprocess_ms": {"quantise": t_quant * 1e3, "compress": t_comp * 1e3, "h2d_raw_matrix": t_h2d * 1e3},
+        "preprocess_ms": {"quantise": t_quant * 1e3, "compress": t_comp * 1e3, "h2d_raw_matrix": t_h2d * 1e3,
+                          **({"compress_sparse": t_sparse * 1e3} if sparse else {})},
     }
     if not a.no_cpu_baseline:
         t0 = time.time()

@@ -163,7 +163,7 @@ GBT_API int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32
  *                              Synchronises the stream.
  *   gbt_compress_sparse        fills ent_out [dev, 4-byte aligned]; it must hold
  *                              gbt_sparse_capacity(nnz) entries: the kernels read
- *                              the stream as whole words, up to 16 entries past
+ *                              the stream as whole words, up to 32 entries past
  *                              the end.  Asynchronous.
  */
 GBT_API int64_t gbt_sparse_capacity(int64_t nnz);

@@ -186,8 +186,9 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->part_fused = 1;
         c->part_hist = 1;
         c->hist_fix = 1;
-        c->sparse_jobs_per_cu = 6;
+        c->sparse_jobs_per_cu = 1;
         if (const char *e12 = getenv("GBT_TUNE_SPARSE_JOBS")) { int v = atoi(e12); if (v >= 1 && v <= 64) c->sparse_jobs_per_cu = v; }
+        if (const char *e13 = getenv("GBT_TUNE_SPARSE_TILED")) c->sparse_tiled = atoi(e13) != 0;
         c->order_rows = 1;
         if (const char *e11 = getenv("GBT_TUNE_ORDER_ROWS")) c->order_rows = atoi(e11) != 0;
         if (const char *e10 = getenv("GBT_TUNE_HIST_FIX")) c->hist_fix = atoi(e10) != 0;
@@ -1219,7 +1220,7 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
     int max_nodes = 1;
     for (int t = 0; t < n_trees; ++t) max_nodes = std::max(max_nodes, trees[t].n_nodes);
     if (sparse) {
-        GBT_REQUIRE(ctx, (size_t)max_nodes * 32 <= ctx->lds_per_block, GBT_EUNSUPPORTED,
+        GBT_REQUIRE(ctx, (size_t)max_nodes * 32 + 16384 <= ctx->lds_per_block, GBT_EUNSUPPORTED,
                     "a tree of %d nodes does not fit the LDS of the sparse-row walk", max_nodes);
         GBT_HIP(ctx, gbt_launch_sparse_walk(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees,
                                             sparse->rowptr, sparse->ent, n, sparse->B, eta, margin, leaf_out, max_nodes));
@@ -1245,7 +1246,7 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
 
 // ------------------------------------------------------------- sparse rows --
 namespace {
-constexpr int64_t kSparseSlack = 16;   // entries past the last one that word-wise readers may touch
+constexpr int64_t kSparseSlack = 32;   // entries past the last one that word-wise readers may touch
 
 int32_t check_sparse_shape(gbt_ctx *ctx, int64_t n, int32_t F, int32_t B) {
     GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) - 1, GBT_EINVAL, "n = %lld out of range", (long long)n);
@@ -1255,11 +1256,13 @@ int32_t check_sparse_shape(gbt_ctx *ctx, int64_t n, int32_t F, int32_t B) {
     return GBT_OK;
 }
 
-// Rows per workgroup: every workgroup merges its whole id tile into HBM at the end, so a launch aims
-// at few, long jobs (a handful per compute unit over all tiles) rather than at many short ones.
+// Rows per workgroup: every workgroup merges its whole id tile into HBM at the end with 64-bit global
+// atomics (about 10^11 of them per second, all compute units together), so a launch aims at few, long
+// jobs: the rows are cut into about one piece per compute unit, whatever the number of id tiles.
 uint32_t sparse_rows_per_job(const gbt_ctx *ctx, int64_t total_rows, int64_t bins, int glen) {
-    const int64_t tiles = (bins + glen - 1) / glen;
-    int64_t per_tile = std::max<int64_t>(1, (int64_t)ctx->num_cu * ctx->sparse_jobs_per_cu / tiles);
+    (void)bins;
+    (void)glen;
+    int64_t per_tile = std::max<int64_t>(1, (int64_t)ctx->num_cu * ctx->sparse_jobs_per_cu);
     int64_t rpj = (total_rows + per_tile - 1) / per_tile;
     if (rpj < 2048) rpj = 2048;
     if (rpj > ((int64_t)1 << 24)) rpj = (int64_t)1 << 24;
@@ -1354,7 +1357,8 @@ extern "C" int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, c
     st = stage(ctx, jobs.data(), jobs.size() * sizeof(HistJob), &slot);
     if (st != GBT_OK) return st;
     gbt_prof_begin(ctx, row_begin == 0 && n_node_rows == n ? GBT_PROF_HIST_ROOT : GBT_PROF_HIST_NODE, 0.0);
-    GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, rowptr, ent, gq, hist_out, (const HistJob *)slot, (int)jobs.size(), glen));
+    GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, rowptr, ent, gq, hist_out, (const HistJob *)slot, (int)jobs.size(), glen,
+                                        glen < bins));
     gbt_prof_end(ctx);
     return GBT_OK;
 }
@@ -1467,7 +1471,7 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
             if (st2 != GBT_OK) return st2;
             gbt_prof_begin(ctx, cls, j0 == 0 ? bytes : 0.0);
             GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, R.rowptr, R.ent, R.gq, pool, (const HistJob *)(ws + L.jobs), (int)nj,
-                                                glen));
+                                                glen, glen < bins));
             gbt_prof_end(ctx);
         }
         return GBT_OK;

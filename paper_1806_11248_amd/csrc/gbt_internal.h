@@ -31,7 +31,8 @@ struct gbt_ctx {
     int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
-    int sparse_jobs_per_cu; // the same for the sparse-row histogram kernel, over all id tiles
+    int sparse_jobs_per_cu; // row pieces per compute unit and launch of the sparse-row histogram kernel
+    int sparse_tiled;       // 1: keep the sparse-row LDS histogram under hist_lds_kb even where all ids would fit
     size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
     char err[512];
     bool profiling;
@@ -219,7 +220,7 @@ hipError_t gbt_launch_sparse_fill(hipStream_t s, const uint16_t *sym, int64_t n,
 int gbt_sparse_hist_tile(const gbt_ctx *ctx, int64_t bins);
 // HistJob.f0 / ft: the job's range of global bin ids
 hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, const int32_t *gq,
-                                  int64_t *pool, const HistJob *jobs, int n_jobs, int max_glen);
+                                  int64_t *pool, const HistJob *jobs, int n_jobs, int max_glen, bool tiled);
 
 // Unordered partition of sparse rows, one launch per level (PartJob as for the dense forms; tiles of
 // gbt_sparse_part_tile() rows).  cursor: two 64-bit words per job, cleared here; afterwards the low

@@ -6,8 +6,8 @@
 // of the bytes of its dense packing, and the histogram kernel issues atomics for present elements
 // only.  gid * 2 is also the element's place in the node's [F][B][2] histogram.
 //
-// The entry stream is read as aligned 32-bit words, eight words per row and step, so the buffer
-// must extend 16 entries past the last one (gbt_sparse_capacity).
+// The entry stream is read as aligned 32-bit words, nine words per row and step, so the buffer
+// must extend 32 entries past the last one (gbt_sparse_capacity).
 #include "gbt_internal.h"
 
 namespace {
@@ -153,39 +153,49 @@ struct __attribute__((packed, aligned(4))) Words4 {   // four words at a 4-byte 
     uint32_t x, y, z, w;
 };
 
-__global__ __launch_bounds__(kSpBlock) void sparse_hist_kernel(const uint32_t *__restrict__ rowptr,
-                                                               const uint32_t *__restrict__ ent_words,
-                                                               const int2 *__restrict__ gq,
-                                                               int64_t *__restrict__ pool,
-                                                               const HistJob *__restrict__ jobs) {
+// BLOCK: 512, or 1024 for an id range whose LDS histogram leaves room for one workgroup per compute
+// unit only.  TILED: the job covers part of the ids, entries outside it are skipped.
+template <int BLOCK, bool TILED>
+__global__ __launch_bounds__(BLOCK) void sparse_hist_kernel(const uint32_t *__restrict__ rowptr,
+                                                            const uint32_t *__restrict__ ent_words,
+                                                            const int2 *__restrict__ gq,
+                                                            int64_t *__restrict__ pool,
+                                                            const HistJob *__restrict__ jobs) {
     extern __shared__ unsigned long long lds[];
     const HistJob job = jobs[blockIdx.x];
     const uint32_t g0 = job.f0, glen = job.ft;
     int64_t *out = pool + job.hist_off + 2 * (int64_t)g0;
-    for (uint32_t i = threadIdx.x; i < glen; i += kSpBlock) lds[i] = 0;
+    for (uint32_t i = threadIdx.x; i < glen; i += BLOCK) lds[i] = 0;
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < job.n_rows; i += kSpBlock) {
+    for (uint32_t i = threadIdx.x; i < job.n_rows; i += BLOCK) {
         const uint64_t r = (uint64_t)job.row_begin + i;
-        const uint32_t s = rowptr[r], e = rowptr[r + 1];
+        const uint32_t s = rowptr[r], len = rowptr[r + 1] - s;
         const int2 q = gq[r];
         const unsigned long long addv = sp_pack_pair(q);
         const uint32_t hq = (uint32_t)q.y;
-        const uint32_t a = s & 1u, end = a + (e - s);     // the row is halfwords [a, end) from word s >> 1 on
+        const uint32_t sh = (s & 1u) * 16u;               // the row starts in the upper half of its first word
         const uint32_t *wp = ent_words + (s >> 1);
-        for (uint32_t k0 = 0; k0 < end; k0 += 16) {
+        for (uint32_t k0 = 0; k0 < len; k0 += 16) {
+            // nine words hold the step's 16 entries whatever the row's alignment; shifted so that
+            // entry k0 + k sits at halfword k
             const Words4 lo = *(const Words4 *)(wp + (k0 >> 1));
             const Words4 hi = *(const Words4 *)(wp + (k0 >> 1) + 4);
-            const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            const uint32_t w8 = wp[(k0 >> 1) + 8];
+            const uint32_t w[9] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w, w8};
+            uint32_t W[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) W[k] = __builtin_amdgcn_alignbit(w[k + 1], w[k], sh);
+            const uint32_t rem = len - k0;
             uint32_t rel[16];
             unsigned long long old[16];
             uint32_t live = 0;
             // all atomics of the step are issued before the first returned word is looked at
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                const uint32_t gid = (w[k >> 1] >> (16 * (k & 1))) & 0xffffu;
-                const uint32_t pos = k0 + (uint32_t)k;
+                const uint32_t gid = (k & 1) ? (W[k >> 1] >> 16) : (W[k >> 1] & 0xffffu);
                 rel[k] = gid - g0;
-                const bool in = pos >= a && pos < end && rel[k] < glen;
+                bool in = (uint32_t)k < rem;
+                if (TILED) in = in && rel[k] < glen;
                 if (in) {
                     live |= 1u << k;
                     old[k] = atomicAdd(&lds[rel[k]], addv);
@@ -197,7 +207,7 @@ __global__ __launch_bounds__(kSpBlock) void sparse_hist_kernel(const uint32_t *_
         }
     }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < glen; i += kSpBlock) {
+    for (uint32_t i = threadIdx.x; i < glen; i += BLOCK) {
         const unsigned long long w = lds[i];
         if (w == 0) continue;
         const int64_t g = (int64_t)w >> kHShift;
@@ -216,9 +226,9 @@ __global__ __launch_bounds__(kSpBlock) void sparse_hist_kernel(const uint32_t *_
 // the node's row range and entry range from the front, right rows from the back, so both children
 // stay contiguous in rows AND in entries, and rowptr[r + 1] - rowptr[r] stays a row's length.
 // move == 0: only the left rows are counted (the last level).
-constexpr int kSpTile = 2048;
-constexpr int kSpRowsPerThread = kSpTile / kSpBlock;   // 4
-constexpr int kSpGroups = kSpRowsPerThread * (kSpBlock / 64);   // (k, wave) groups of 64 rows: 32
+constexpr int kSpTile = 1024;
+constexpr int kSpRowsPerThread = kSpTile / kSpBlock;   // 2
+constexpr int kSpGroups = kSpRowsPerThread * (kSpBlock / 64);   // (k, wave) groups of 64 rows: 16
 
 __device__ inline int find_part_job(const PartJob *jobs, int n_jobs, uint32_t tile) {
     int lo = 0, hi = n_jobs;   // last job with tile_begin <= tile
@@ -229,11 +239,10 @@ __device__ inline int find_part_job(const PartJob *jobs, int n_jobs, uint32_t ti
     return lo;
 }
 
-// the row's entry with an id in [lo, lo + B), or 0xffffffff
-__device__ inline uint32_t find_feature_entry(const uint16_t *__restrict__ ent, uint32_t s, uint32_t e, uint32_t lo,
-                                              uint32_t B) {
-    // first entry >= lo by bisection (ids ascend inside a row)
-    uint32_t a = s, b = e;
+// the entry with an id in [lo, lo + B) among the ascending ids ent[s .. e), or 0xffffffff
+template <typename P>
+__device__ __forceinline__ uint32_t find_feature_entry(P ent, uint32_t s, uint32_t e, uint32_t lo, uint32_t B) {
+    uint32_t a = s, b = e;   // first entry >= lo by bisection
     while (a < b) {
         const uint32_t mid = a + ((b - a) >> 1);
         if ((uint32_t)ent[mid] < lo) a = mid + 1; else b = mid;
@@ -245,6 +254,14 @@ __device__ inline uint32_t find_feature_entry(const uint16_t *__restrict__ ent, 
     return 0xffffffffu;
 }
 
+// The entries of a tile's rows are one contiguous piece of the stream: it is fetched once, linearly,
+// into LDS (kSpStage entries; a tile with more falls back to reading and writing the stream row by
+// row), and the feature look-ups read it there.  The tile's left rows land in one contiguous piece of
+// the destination stream and its right rows in another: both are put together inside LDS (a second
+// window, halfword-aligned like the destination) and leave as whole 32-bit words -- sub-word stores
+// retire about one lane per clock and compute unit, whatever their addresses.
+constexpr int kSpStage = 12288;
+
 __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *__restrict__ src_rowptr,
                                                                const uint16_t *__restrict__ src_ent,
                                                                const int2 *__restrict__ src_gq,
@@ -253,36 +270,55 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
                                                                int2 *__restrict__ dst_gq, uint32_t B, int move,
                                                                const PartJob *__restrict__ jobs, int n_jobs,
                                                                unsigned long long *__restrict__ cursor) {
+    __shared__ uint32_t stage_w[kSpStage / 2];
+    __shared__ uint32_t out_w[kSpStage / 2 + 4];
     __shared__ uint32_t grp_rows[2][kSpGroups];   // [side][group]: rows, then their exclusive offsets
     __shared__ uint32_t grp_ent[2][kSpGroups];
     __shared__ unsigned long long base[2];        // what the cursors returned
     __shared__ uint32_t tot[4];                   // rows L, rows R, entries L, entries R of the tile
+    const uint16_t *stage = (const uint16_t *)stage_w;
     const int j = find_part_job(jobs, n_jobs, blockIdx.x);
     const PartJob job = jobs[j];
     const uint32_t t_local = blockIdx.x - job.tile_begin;
     const uint32_t seg_end = job.seg_begin + job.seg_len;
     const uint32_t r0 = job.seg_begin + t_local * (uint32_t)kSpTile;
+    const uint32_t r1 = r0 + (uint32_t)kSpTile < seg_end ? r0 + (uint32_t)kSpTile : seg_end;
     const uint32_t lo = job.feature * B, thr = lo + job.bin;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
+    // the tile's piece of the stream, from the word that holds its first entry
+    const uint32_t e0 = src_rowptr[r0], e1 = src_rowptr[r1];
+    const uint32_t w0 = e0 >> 1, n_words = ((e1 + 1) >> 1) - w0;
+    const bool staged = n_words <= (uint32_t)(kSpStage / 2);
+    if (staged) {
+        const uint32_t *src_w = (const uint32_t *)src_ent + w0;
+        for (uint32_t w = threadIdx.x; w < n_words; w += kSpBlock) stage_w[w] = src_w[w];
+    }
+    const uint32_t sbase = w0 * 2;   // stream index of stage[0]
+
     uint32_t rs[kSpRowsPerThread], rlen[kSpRowsPerThread], within_rows[kSpRowsPerThread], within_ent[kSpRowsPerThread];
     bool live[kSpRowsPerThread], left[kSpRowsPerThread];
+    int2 pair[kSpRowsPerThread];
 #pragma unroll
     for (int k = 0; k < kSpRowsPerThread; ++k) {
         const uint32_t r = r0 + (uint32_t)k * kSpBlock + threadIdx.x;
-        live[k] = r < seg_end;
+        live[k] = r < r1;
         rs[k] = 0;
         rlen[k] = 0;
         left[k] = false;
+        pair[k] = make_int2(0, 0);
         if (live[k]) {
             rs[k] = src_rowptr[r];
             rlen[k] = src_rowptr[r + 1] - rs[k];
+            if (move) pair[k] = src_gq[r];
         }
     }
+    __syncthreads();
 #pragma unroll
     for (int k = 0; k < kSpRowsPerThread; ++k) {
         if (live[k]) {
-            const uint32_t g = find_feature_entry(src_ent, rs[k], rs[k] + rlen[k], lo, B);
+            const uint32_t g = staged ? find_feature_entry(stage, rs[k] - sbase, rs[k] - sbase + rlen[k], lo, B)
+                                      : find_feature_entry(src_ent, rs[k], rs[k] + rlen[k], lo, B);
             left[k] = g == 0xffffffffu ? job.default_left != 0 : g <= thr;
         }
     }
@@ -310,19 +346,20 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
         }
     }
     __syncthreads();
-    if (wave == 0) {   // exclusive offsets over the groups; lanes 0..31 rows, 32..63 entries; both sides
-        static_assert(kSpGroups == 32, "one half wave per table");
-        const int grp = lane & 31;
+    if (wave == 0 && lane < 2 * kSpGroups) {   // exclusive offsets over the groups: first G lanes rows, next G entries
+        static_assert(kSpGroups <= 32 && (kSpGroups & (kSpGroups - 1)) == 0, "two tables inside one wave");
+        const int grp = lane & (kSpGroups - 1);
+        const bool rows_tab = lane < kSpGroups;
         for (int side = 0; side < 2; ++side) {
-            uint32_t *tab = lane < 32 ? grp_rows[side] : grp_ent[side];
+            uint32_t *tab = rows_tab ? grp_rows[side] : grp_ent[side];
             const uint32_t v = tab[grp];
             uint32_t incl = v;
-            for (int o = 1; o < 32; o <<= 1) {
+            for (int o = 1; o < kSpGroups; o <<= 1) {
                 const uint32_t y = (uint32_t)__shfl_up((int)incl, o);
                 if (grp >= o) incl += y;
             }
             tab[grp] = incl - v;
-            if (grp == 31) tot[(lane < 32 ? 0 : 2) + side] = incl;
+            if (grp == kSpGroups - 1) tot[(rows_tab ? 0 : 2) + side] = incl;
         }
     }
     __syncthreads();
@@ -336,17 +373,40 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
     const uint32_t row_l = job.seg_begin + (uint32_t)base[0], ent_l = ent_begin + (uint32_t)(base[0] >> 32);
     const uint32_t row_r = seg_end - (uint32_t)base[1] - tot[1], ent_r = ent_end - (uint32_t)(base[1] >> 32) - tot[3];
     if (t_local == 0 && threadIdx.x == 0) dst_rowptr[seg_end] = ent_end;   // the segment's closing row pointer
+    // where the two pieces sit in the output window: at the parity of their place in the stream
+    const uint32_t lds_l = ent_l & 1u;
+    const uint32_t lds_r = ((lds_l + tot[2] + 1u) & ~1u) + (ent_r & 1u);
+    uint16_t *out16 = (uint16_t *)out_w;
 #pragma unroll
     for (int k = 0; k < kSpRowsPerThread; ++k) {
         if (!live[k]) continue;
-        const uint32_t r = r0 + (uint32_t)k * kSpBlock + threadIdx.x;
         const int grp = k * (kSpBlock / 64) + wave;
         const int side = left[k] ? 0 : 1;
+        const uint32_t in_piece = grp_ent[side][grp] + within_ent[k];   // the row's place inside its side's piece
         const uint32_t drow = (left[k] ? row_l : row_r) + grp_rows[side][grp] + within_rows[k];
-        const uint32_t dent = (left[k] ? ent_l : ent_r) + grp_ent[side][grp] + within_ent[k];
+        const uint32_t dent = (left[k] ? ent_l : ent_r) + in_piece;
         dst_rowptr[drow] = dent;
-        dst_gq[drow] = src_gq[r];
-        for (uint32_t q = 0; q < rlen[k]; ++q) dst_ent[dent + q] = src_ent[rs[k] + q];
+        dst_gq[drow] = pair[k];
+        if (staged) {
+            const uint16_t *from = stage + (rs[k] - sbase);
+            uint16_t *to = out16 + (left[k] ? lds_l : lds_r) + in_piece;
+            for (uint32_t q = 0; q < rlen[k]; ++q) to[q] = from[q];
+        } else {
+            for (uint32_t q = 0; q < rlen[k]; ++q) dst_ent[dent + q] = src_ent[rs[k] + q];
+        }
+    }
+    if (!staged) return;
+    __syncthreads();
+    for (int side = 0; side < 2; ++side) {
+        const uint32_t gs = side == 0 ? ent_l : ent_r, ge = gs + tot[2 + side];   // the piece in the stream
+        const uint32_t ls = side == 0 ? lds_l : lds_r;                             // and in the window
+        if (gs == ge) continue;
+        const uint32_t wfirst = (gs + 1) >> 1, wend = ge >> 1;                     // whole words [wfirst, wend)
+        const uint32_t lw = (ls + (gs & 1u)) >> 1;                                 // window word of stream word wfirst
+        uint32_t *dst_words = (uint32_t *)dst_ent;
+        for (uint32_t w = threadIdx.x; wfirst + w < wend; w += kSpBlock) dst_words[wfirst + w] = out_w[lw + w];
+        if (threadIdx.x == 0 && (gs & 1u)) dst_ent[gs] = out16[ls];
+        if (threadIdx.x == 64 && (ge & 1u) && (ge - 1 >= gs)) dst_ent[ge - 1] = out16[ls + (ge - 1 - gs)];
     }
 }
 
@@ -358,12 +418,19 @@ struct SpNode {
     int32_t dl, pad;
     double weight;
 };
+// A wave's 64 consecutive rows own one contiguous piece of the entry stream: the wave fetches it
+// linearly into its own LDS window (kWalkWords words; a longer piece is read from the stream
+// directly) and every level's look-up bisects there.
+constexpr int kWalkWords = 1024;
 __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const DevTree *trees, int n_trees,
                                                           const uint32_t *__restrict__ rowptr,
                                                           const uint16_t *__restrict__ ent, int64_t n, uint32_t B,
                                                           double eta, float *margin, int32_t *leaf_out,
-                                                          int rows_per_block) {
+                                                          int rows_per_block, int max_nodes) {
     extern __shared__ SpNode sp_nodes[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t *st = (uint32_t *)(sp_nodes + max_nodes) + wave * kWalkWords;
+    const uint16_t *st16 = (const uint16_t *)st;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
     for (int t = 0; t < n_trees; ++t) {
@@ -381,19 +448,38 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
             sp_nodes[i] = nd;
         }
         __syncthreads();
-        for (int64_t r = r0 + threadIdx.x; r < r1; r += 256) {
-            const uint32_t s = rowptr[r], e = rowptr[r + 1];
-            int node = 0;
-            for (int step = 0; step < T.n_nodes; ++step) {
-                const SpNode nd = sp_nodes[node];
-                if (nd.feature < 0) break;
-                const uint32_t lo = (uint32_t)nd.feature * B;
-                const uint32_t g = find_feature_entry(ent, s, e, lo, B);
-                const bool go_left = g == 0xffffffffu ? nd.dl != 0 : g <= lo + (uint32_t)nd.bin;
-                node = go_left ? nd.left : nd.right;
+        for (int64_t rw = r0 + wave * 64; rw < r1; rw += 256) {   // rw: the wave's first row
+            const int64_t r = rw + lane;
+            const bool live = r < r1;
+            const uint32_t s = live ? rowptr[r] : 0u, e = live ? rowptr[r + 1] : 0u;
+            const int last = 63 - (int)__builtin_clzll(__ballot(live));   // lane 0 is live
+            const uint32_t ws0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s);
+            const uint32_t we = (uint32_t)__builtin_amdgcn_readlane((int)e, last);
+            const uint32_t word0 = ws0 >> 1, n_words = ((we + 1) >> 1) - word0;
+            const bool fits = n_words <= (uint32_t)kWalkWords;
+            if (fits) {
+                const uint32_t *src_w = (const uint32_t *)ent + word0;
+                for (uint32_t w = lane; w < n_words; w += 64) st[w] = src_w[w];
             }
-            if (leaf_out) leaf_out[r] = node;
-            else margin[r] = (float)((double)margin[r] + eta * sp_nodes[node].weight);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (live) {
+                const uint32_t sb = word0 * 2;
+                int node = 0;
+                for (int step = 0; step < T.n_nodes; ++step) {
+                    const SpNode nd = sp_nodes[node];
+                    if (nd.feature < 0) break;
+                    const uint32_t lo = (uint32_t)nd.feature * B;
+                    const uint32_t g = fits ? find_feature_entry(st16, s - sb, e - sb, lo, B)
+                                            : find_feature_entry(ent, s, e, lo, B);
+                    const bool go_left = g == 0xffffffffu ? nd.dl != 0 : g <= lo + (uint32_t)nd.bin;
+                    node = go_left ? nd.left : nd.right;
+                }
+                if (leaf_out) leaf_out[r] = node;
+                else margin[r] = (float)((double)margin[r] + eta * sp_nodes[node].weight);
+            }
+            __builtin_amdgcn_wave_barrier();   // the window is refilled only after every lane has left it
         }
     }
 }
@@ -428,8 +514,11 @@ hipError_t gbt_launch_sparse_fill(hipStream_t s, const uint16_t *sym, int64_t n,
     return hipGetLastError();
 }
 
-// ids per LDS tile for a total of `bins` global bin ids (8 bytes of LDS per id)
+// ids per LDS tile for a total of `bins` global bin ids (8 bytes of LDS per id): all of them when they
+// fit one workgroup's LDS at all (one pass over a row's entries then serves every id), else equal
+// parts under the cap that lets several workgroups share a compute unit
 int gbt_sparse_hist_tile(const gbt_ctx *ctx, int64_t bins) {
+    if ((size_t)bins * 8 <= ctx->lds_per_block && !ctx->sparse_tiled) return (int)bins;
     size_t limit = ctx->lds_per_block;
     if (ctx->hist_lds_kb > 0 && (size_t)ctx->hist_lds_kb * 1024 < limit) limit = (size_t)ctx->hist_lds_kb * 1024;
     const int64_t cap = (int64_t)(limit / 8);
@@ -437,19 +526,27 @@ int gbt_sparse_hist_tile(const gbt_ctx *ctx, int64_t bins) {
     return (int)((bins + tiles - 1) / tiles);
 }
 
+// tiled: the jobs cover parts of the id range [0, bins)
 hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, const int32_t *gq,
-                                  int64_t *pool, const HistJob *jobs, int n_jobs, int max_glen) {
+                                  int64_t *pool, const HistJob *jobs, int n_jobs, int max_glen, bool tiled) {
     if (n_jobs <= 0) return hipSuccess;
     const size_t lds = (size_t)max_glen * 8;
-    static size_t configured = 0;
-    if (lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)sparse_hist_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
+    const bool big = lds > 64u * 1024u;   // one workgroup per compute unit: make it a large one
+    const void *fn = big ? (tiled ? (const void *)sparse_hist_kernel<1024, true> : (const void *)sparse_hist_kernel<1024, false>)
+                         : (tiled ? (const void *)sparse_hist_kernel<512, true> : (const void *)sparse_hist_kernel<512, false>);
+    static size_t configured[4] = {0, 0, 0, 0};
+    const int slot = (big ? 2 : 0) + (tiled ? 1 : 0);
+    if (lds > configured[slot]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = lds;
+        configured[slot] = lds;
     }
-    sparse_hist_kernel<<<n_jobs, kSpBlock, lds, ctx->stream>>>(rowptr, (const uint32_t *)ent, (const int2 *)gq, pool,
-                                                               jobs);
+    const uint32_t *words = (const uint32_t *)ent;
+    const int2 *gq2 = (const int2 *)gq;
+    if (big && tiled) sparse_hist_kernel<1024, true><<<n_jobs, 1024, lds, ctx->stream>>>(rowptr, words, gq2, pool, jobs);
+    else if (big) sparse_hist_kernel<1024, false><<<n_jobs, 1024, lds, ctx->stream>>>(rowptr, words, gq2, pool, jobs);
+    else if (tiled) sparse_hist_kernel<512, true><<<n_jobs, 512, lds, ctx->stream>>>(rowptr, words, gq2, pool, jobs);
+    else sparse_hist_kernel<512, false><<<n_jobs, 512, lds, ctx->stream>>>(rowptr, words, gq2, pool, jobs);
     return hipGetLastError();
 }
 
@@ -472,7 +569,7 @@ hipError_t gbt_launch_sparse_walk(hipStream_t s, const char *ws, const DevTree *
                                   const uint32_t *rowptr, const uint16_t *ent, int64_t n, int B, double eta,
                                   float *margin, int32_t *leaf_out, int max_nodes) {
     if (n <= 0 || n_trees <= 0) return hipSuccess;
-    const size_t lds = (size_t)max_nodes * sizeof(SpNode);
+    const size_t lds = (size_t)max_nodes * sizeof(SpNode) + 4 * kWalkWords * 4;
     static size_t configured = 0;
     if (lds > configured) {
         hipError_t e = hipFuncSetAttribute((const void *)sparse_walk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -483,6 +580,6 @@ hipError_t gbt_launch_sparse_walk(hipStream_t s, const char *ws, const DevTree *
     const int rows_per_block = 2048;
     const int64_t grid = (n + rows_per_block - 1) / rows_per_block;
     sparse_walk_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, rowptr, ent, n, (uint32_t)B, eta, margin,
-                                                        leaf_out, rows_per_block);
+                                                        leaf_out, rows_per_block, max_nodes);
     return hipGetLastError();
 }

@@ -33,7 +33,7 @@ def _sample_nodes(tree, k=24, seed=0):
     return pick
 
 
-def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True):
+def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True, sparse_rows=False):
     import paper_1806_11248_amd as g
     t0 = time.time()
     d = synth.make(cfg)
@@ -65,6 +65,9 @@ def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True):
     step = max(1, (64 << 20) // max(F, 1))
     for lo in range(0, n, step):
         assert np.array_equal(sym[lo:lo + step].cpu().numpy(), o_sym[lo:lo + step]), f"symbols differ in rows {lo}.."
+    if sparse_rows:   # the same matrix in the sparse-row form
+        sp_rowptr, sp_ent, sp_nnz = ctx.compress_sparse(sym, B, ms)
+        assert sp_nnz == int((o_sym != o_missing).sum())
     del sym
     # packed words: whole rows that start on a word boundary, packed by the oracle
     period = 32 // np.gcd(32, F * bits)                # rows per word-aligned group
@@ -131,7 +134,24 @@ def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True):
         for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
                   "sumG", "sumH"):
             assert np.array_equal(bare[k][:nn], tree[k][:nn]), k
+        if sparse_rows:   # the sparse-row kernels: the same tree, row order and leaves, the same margins
+            t0 = time.time()
+            st, s_rows, s_leaf = ctx.grow_tree_sparse(sp_rowptr, sp_ent, n, sp_nnz, F, nb, cuts, gp_t, params)
+            torch.cuda.synchronize()
+            _say(f"  round {r}: same tree over sparse rows in {(time.time() - t0) * 1e3:.1f} ms")
+            assert st["n_nodes"] == nn
+            for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
+                      "sumG", "sumH"):
+                assert np.array_equal(st[k][:nn], tree[k][:nn]), k
+            assert np.array_equal(host_u32(s_rows), rep["row_idx"])
+            assert np.array_equal(s_leaf.cpu().numpy(), rep["leaf_of_row"])
+            del s_rows, s_leaf
+            m2 = margin_gpu.clone()
+            ctx.predict_sparse([tree], m2, p["eta"], sp_rowptr, sp_ent, n, F, B)
         ctx.predict([tree], margin_gpu, p["eta"], packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
+        if sparse_rows:
+            assert torch.equal(m2, margin_gpu)
+            del m2
         margin_ref = oracle.predict_sym(tree, o_sym, o_missing, p["eta"], margin_ref)
         assert np.allclose(margin_gpu.cpu().numpy(), margin_ref, rtol=1e-5, atol=1e-6)
 
@@ -181,7 +201,7 @@ def test_full_c2_dense_classification(ctx, oracle):
 
 
 def test_full_c3_sparse_regression(ctx, oracle):
-    _full_case(ctx, oracle, 3, csr=True, rounds=2)
+    _full_case(ctx, oracle, 3, csr=True, rounds=2, sparse_rows=True)
 
 
 def test_full_c5_wide(ctx, oracle):
