@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--max-leaves", type=int, default=0, help="lossguide: leaf budget (default 2^max_depth)")
     ap.add_argument("--layout", choices=["dense", "sparse"], default="dense",
                     help="sparse: rows keep only their present elements (16-bit global bin ids); depth-wise only")
+    ap.add_argument("--predict-trees", type=int, default=0,
+                    help="also boost this many rounds (untimed) and time gbt_predict with all those trees at once "
+                         "on the raw float matrix (Sec. 2.4); reported as predict_many_trees")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of the packed matrix (a kernel of known size to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -319,6 +322,34 @@ def main():
         "preprocess_ms": {"quantise": t_quant * 1e3, "compress": t_comp * 1e3, "h2d_raw_matrix": t_h2d * 1e3,
                           **({"compress_sparse": t_sparse * 1e3} if sparse else {})},
     }
+    if a.predict_trees > 0 and not given:
+        # Sec. 2.4 with many trees: boost (untimed), then one gbt_predict call over the raw floats
+        Xraw = torch.from_numpy(X).to(dev)
+        bm = torch.zeros(n, dtype=torch.float32, device=dev)
+        many = []
+        for _ in range(a.predict_trees):
+            ctx.gradients(p["objective"], bm, y, out=gp)
+            t_, _, _ = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp, params, want_rows=False, want_leaf=False)
+            ctx.predict([t_], bm, eta, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
+            many.append(t_)
+        pm = torch.zeros(n, dtype=torch.float32, device=dev)
+        ctx.predict(many, pm, eta, X=Xraw)
+        same = bool(torch.equal(pm, bm))     # the margins the boosting loop built tree by tree
+        ctx.profile_enable(True)
+        ctx.profile_read()
+        reps = 5
+        for _ in range(reps):
+            ctx.predict(many, pm, eta, X=Xraw)
+        torch.cuda.synchronize()
+        pp = ctx.profile_read()["other"]
+        ctx.profile_enable(False)
+        k_ms = pp["ms"] / max(pp["launches"], 1)
+        out["predict_many_trees"] = {
+            "trees": len(many), "rows": n, "features": F, "input": "raw fp32 matrix, one pass",
+            "kernel_ms": k_ms, "row_trees_per_s": n * len(many) / (k_ms * 1e-3),
+            "hbm_GBps": (n * (F * 4 + 8)) / (k_ms * 1e-3) / 1e9,
+            "equals_boosting_margins": same}
+        del Xraw
     if not a.no_cpu_baseline:
         t0 = time.time()
         out["cpu_baseline"] = cpu_baseline(d, min(a.cpu_sample_rows, n))

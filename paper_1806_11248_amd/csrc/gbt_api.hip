@@ -661,7 +661,7 @@ struct SparseRowsArg {   // rows in the sparse form instead of packed / X
 static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                             int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
                             float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes,
-                            const SparseRowsArg *sparse = nullptr);
+                            const SparseRowsArg *sparse = nullptr, bool own_span = false);
 
 // Alg. 1 under either policy of Sec. 2.3.  Growth proceeds in rounds: the nodes created by the round
 // before are evaluated; depth-wise then splits every one of them that may split, loss-guided only
@@ -1148,11 +1148,38 @@ namespace {
 size_t tree_bytes(int32_t n_nodes) { return gbt_align((size_t)n_nodes * 4) * 6 + gbt_align((size_t)n_nodes * 8); }
 }
 
-extern "C" size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_trees) {
-    if (!trees || n_trees < 0) return 0;
+namespace {
+// the plain staging (table of DevTree, then every tree's arrays) ...
+size_t predict_plain_bytes(const gbt_tree *trees, int32_t n_trees) {
     size_t o = gbt_align((size_t)n_trees * sizeof(DevTree));
     for (int t = 0; t < n_trees; ++t) o += tree_bytes(trees[t].n_nodes);
     return o + 256;
+}
+// ... and behind it the form of the many-trees kernel: 8-byte nodes, weights, three small tables
+struct BatchLayout {
+    size_t nodes, wts, tree_off, tree_depth, group_end, total;
+};
+BatchLayout batch_layout(size_t base, int64_t total_nodes, int32_t n_trees) {
+    BatchLayout L;
+    size_t o = base;
+    L.nodes = o;      o += gbt_align((size_t)total_nodes * 8);
+    L.wts = o;        o += gbt_align((size_t)total_nodes * 8);
+    L.tree_off = o;   o += gbt_align((size_t)(n_trees + 1) * 4);
+    L.tree_depth = o; o += gbt_align((size_t)(n_trees + 1) * 4);
+    L.group_end = o;  o += gbt_align((size_t)(n_trees + 1) * 4);
+    L.total = o;
+    return L;
+}
+int64_t total_nodes_of(const gbt_tree *trees, int32_t n_trees) {
+    int64_t s = 0;
+    for (int t = 0; t < n_trees; ++t) s += std::max(trees[t].n_nodes, 0);
+    return s;
+}
+}  // namespace
+
+extern "C" size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_trees) {
+    if (!trees || n_trees < 0) return 0;
+    return batch_layout(predict_plain_bytes(trees, n_trees), total_nodes_of(trees, n_trees), n_trees).total;
 }
 
 // Stages the trees in `workspace` and walks them: margin += eta * leaf weight per tree, or (leaf_out,
@@ -1160,7 +1187,8 @@ extern "C" size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_t
 static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                             int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
                             float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes,
-                            const SparseRowsArg *sparse) {
+                            const SparseRowsArg *sparse, bool own_span) {
+    // own_span: the walk is a profile span of its own (class "other"); callers inside a span pass false
     GBT_REQUIRE(ctx, trees && (margin || leaf_out) && workspace, GBT_EINVAL, "NULL argument");
     GBT_REQUIRE(ctx, sparse || (packed != nullptr) != (X != nullptr), GBT_EINVAL, "give exactly one of packed and X");
     GBT_REQUIRE(ctx, n >= 0 && F >= 1 && n_trees >= 0, GBT_EINVAL, "bad shape");
@@ -1172,10 +1200,15 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
     } else {
         bits = 1;
     }
-    GBT_REQUIRE(ctx, workspace_bytes >= gbt_predict_workspace_bytes(trees, n_trees), GBT_ENOMEM, "workspace too small");
+    const bool may_batch = X && margin && !leaf_out && n_trees >= 2;   // then the workspace also holds the batched form
+    GBT_REQUIRE(ctx, workspace_bytes >= (may_batch ? gbt_predict_workspace_bytes(trees, n_trees)
+                                                   : predict_plain_bytes(trees, n_trees)),
+                GBT_ENOMEM, "workspace too small");
     bool compact_ok = true;   // the 8-byte node form of the register-window kernel applies
     // stage the trees: table of offsets, then each tree's arrays
-    std::vector<char> host(gbt_predict_workspace_bytes(trees, n_trees), 0);
+    std::vector<char> host(predict_plain_bytes(trees, n_trees), 0);
+    std::vector<int> depths((size_t)n_trees, 0);
+    bool ordered = true;      // every child comes after its parent, in every tree
     DevTree *tab = (DevTree *)host.data();
     size_t o = gbt_align((size_t)n_trees * sizeof(DevTree));
     for (int t = 0; t < n_trees; ++t) {
@@ -1196,6 +1229,7 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
             if (T.feature[i] < 0) continue;
             if (T.left[i] <= i || T.right[i] <= i) {
                 compact_ok = false;
+                ordered = false;
                 break;
             }
             depth_of[T.left[i]] = depth_of[T.right[i]] = depth_of[i] + 1;
@@ -1204,6 +1238,7 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
         const size_t a4 = gbt_align((size_t)T.n_nodes * 4);
         tab[t].n_nodes = T.n_nodes;
         tab[t].pad = tree_depth;
+        depths[(size_t)t] = tree_depth;
         const void *src4[6] = {T.feature, T.bin, T.default_left, T.left, T.right, T.threshold};
         uint64_t *dst4[6] = {&tab[t].feature, &tab[t].bin, &tab[t].default_left, &tab[t].left, &tab[t].right,
                              &tab[t].threshold};
@@ -1219,16 +1254,84 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
     GBT_HIP(ctx, hipMemcpyAsync(workspace, host.data(), o, hipMemcpyHostToDevice, ctx->stream));
     int max_nodes = 1;
     for (int t = 0; t < n_trees; ++t) max_nodes = std::max(max_nodes, trees[t].n_nodes);
+    // Several trees on raw floats: one pass over the rows with the trees taken through LDS in groups
+    // (needs right == left + 1 and children after parents, which grown trees have).
+    if (may_batch && compact_ok && ordered && F <= gbt_predict_batch_max_features() && max_nodes <= 32767) {
+        const size_t tile = (((size_t)256 * (size_t)(F | 1) * 4) + 15) & ~(size_t)15;
+        int cap_nodes = std::max(2048, max_nodes);
+        if (tile + (size_t)cap_nodes * 16 > ctx->lds_per_block) cap_nodes = max_nodes;
+        if (tile + (size_t)cap_nodes * 16 <= ctx->lds_per_block) {
+            const int64_t total_nodes = total_nodes_of(trees, n_trees);
+            const BatchLayout BL = batch_layout(predict_plain_bytes(trees, n_trees), total_nodes, n_trees);
+            std::vector<gbt_batch_node> bn((size_t)total_nodes);
+            std::vector<double> bw((size_t)total_nodes);
+            std::vector<int32_t> off((size_t)n_trees + 1), grp;
+            int64_t run = 0;
+            int in_group = 0;
+            for (int t = 0; t < n_trees; ++t) {
+                const gbt_tree &T = trees[t];
+                if (in_group + T.n_nodes > cap_nodes) {   // the group is full: it ends before this tree
+                    grp.push_back(t);
+                    in_group = 0;
+                }
+                in_group += T.n_nodes;
+                off[(size_t)t] = (int32_t)run;
+                for (int i = 0; i < T.n_nodes; ++i) {
+                    gbt_batch_node q;
+                    if (T.feature[i] < 0) {
+                        q.thr = INFINITY;
+                        q.meta = (uint32_t)i | (1u << 15);
+                    } else {
+                        q.thr = T.threshold[i];
+                        q.meta = (uint32_t)T.left[i] | ((T.default_left[i] ? 1u : 0u) << 15) | (1u << 16) |
+                                 ((uint32_t)T.feature[i] << 17);
+                    }
+                    bn[(size_t)(run + i)] = q;
+                    bw[(size_t)(run + i)] = T.weight[i];
+                }
+                run += T.n_nodes;
+            }
+            off[(size_t)n_trees] = (int32_t)run;
+            grp.push_back(n_trees);
+            char *wsb = (char *)workspace;
+            const size_t per_upload = kUploadBytes;
+            auto put = [&](const void *src, size_t bytes, size_t at) -> int32_t {
+                for (size_t o2 = 0; o2 < bytes; o2 += per_upload) {
+                    int32_t st2 = upload(ctx, (const char *)src + o2, std::min(per_upload, bytes - o2), wsb + at + o2);
+                    if (st2 != GBT_OK) return st2;
+                }
+                return GBT_OK;
+            };
+            int32_t st = put(bn.data(), bn.size() * 8, BL.nodes);
+            if (st == GBT_OK) st = put(bw.data(), bw.size() * 8, BL.wts);
+            if (st == GBT_OK) st = put(off.data(), off.size() * 4, BL.tree_off);
+            if (st == GBT_OK) st = put(depths.data(), depths.size() * 4, BL.tree_depth);
+            if (st == GBT_OK) st = put(grp.data(), grp.size() * 4, BL.group_end);
+            if (st != GBT_OK) return st;
+            if (own_span) gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * ((double)F * 4.0 + 8.0));
+            GBT_HIP(ctx, gbt_launch_predict_raw_batched(ctx->stream, (const gbt_batch_node *)(wsb + BL.nodes),
+                                                        (const double *)(wsb + BL.wts), (const int32_t *)(wsb + BL.tree_off),
+                                                        (const int32_t *)(wsb + BL.tree_depth),
+                                                        (const int32_t *)(wsb + BL.group_end), (int)grp.size(), cap_nodes,
+                                                        X, n, F, eta, margin));
+            if (own_span) gbt_prof_end(ctx);
+            return GBT_OK;
+        }
+    }
     if (sparse) {
         GBT_REQUIRE(ctx, (size_t)max_nodes * 32 + 16384 <= ctx->lds_per_block, GBT_EUNSUPPORTED,
                     "a tree of %d nodes does not fit the LDS of the sparse-row walk", max_nodes);
+        if (own_span) gbt_prof_begin(ctx, GBT_PROF_OTHER, 0.0);
         GBT_HIP(ctx, gbt_launch_sparse_walk(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees,
                                             sparse->rowptr, sparse->ent, n, sparse->B, eta, margin, leaf_out, max_nodes));
+        if (own_span) gbt_prof_end(ctx);
         return GBT_OK;
     }
+    if (own_span) gbt_prof_begin(ctx, GBT_PROF_OTHER, 0.0);
     GBT_HIP(ctx, gbt_launch_predict(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees, packed,
                                     bits, (uint32_t)missing_sym, X, n, F, eta, margin, leaf_out, max_nodes,
                                     compact_ok));
+    if (own_span) gbt_prof_end(ctx);
     return GBT_OK;
 }
 
@@ -1238,7 +1341,7 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
     if (!ctx) return GBT_EINVAL;
     GBT_REQUIRE(ctx, margin != nullptr, GBT_EINVAL, "NULL argument");
     int32_t st = predict_impl(ctx, trees, n_trees, packed, bits, missing_sym, X, n, F, eta, margin, nullptr, workspace,
-                              workspace_bytes);
+                              workspace_bytes, nullptr, true);
     if (st != GBT_OK) return st;
     GBT_SYNC(ctx);
     return GBT_OK;
@@ -1688,7 +1791,7 @@ extern "C" int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32
     if (st != GBT_OK) return st;
     const SparseRowsArg sr{rowptr, ent, max_bins};
     st = predict_impl(ctx, trees, n_trees, nullptr, 1, 0, nullptr, n, F, eta, margin, nullptr, workspace, workspace_bytes,
-                      &sr);
+                      &sr, true);
     if (st != GBT_OK) return st;
     GBT_SYNC(ctx);
     return GBT_OK;

@@ -249,6 +249,21 @@ hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *tree
                               bool compact_ok);   // leaf_out != NULL: store each row's leaf id instead of updating margin
 // compact_ok: every split node has right == left + 1, feature < 2^20 and bin < 4096
 
+// Many trees on raw floats in one pass over the rows (kernels_misc.hip).  A node is 8 bytes:
+// meta = left child's id inside its tree (15 bits) | default_left << 15 | step << 16 | feature << 17,
+// next = left + (go left ? 0 : step); a leaf has step 0 and left = its own id.  tree_off[t] = first
+// node of tree t in nodes / wts (tree_off[n_trees] = total); group_end[g] = one past the last tree of
+// group g; no group has more than cap_nodes nodes.
+struct gbt_batch_node {
+    float thr;
+    uint32_t meta;
+};
+int gbt_predict_batch_max_features();
+hipError_t gbt_launch_predict_raw_batched(hipStream_t s, const gbt_batch_node *nodes, const double *wts,
+                                          const int32_t *tree_off, const int32_t *tree_depth,
+                                          const int32_t *group_end, int n_groups, int cap_nodes, const float *X,
+                                          int64_t n, int F, double eta, float *margin);
+
 // quantise
 hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
                             const float *values, int64_t n, int F, int64_t n_values, int B, float *cuts,

@@ -648,6 +648,137 @@ hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_ele
                                                                             n_words);
     return hipGetLastError();
 }
+// ---------------------------------------------------------------------------
+// Sec. 2.4 for many trees on raw floats: the rows are read from HBM once.  A workgroup stages a
+// tile of 256 rows in LDS (odd row stride), then takes the trees in groups that fit LDS beside it
+// (8-byte nodes + 8-byte weights, converted on the host): one row per thread, four trees of a group
+// walked side by side (independent chains hide the LDS latency), every walk a fixed number of steps
+// (the tree's depth) because a leaf is staged as a node that leads to itself.  The margin stays in a
+// register and is rounded to fp32 after every tree, in tree order, like the one-tree kernels.
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int kBatchRows = 256;
+constexpr int kBatchTrees = 4;
+
+__global__ __launch_bounds__(kBatchRows) void predict_raw_batched_kernel(
+    const gbt_batch_node *__restrict__ nodes_g, const double *__restrict__ wts_g,
+    const int32_t *__restrict__ tree_off, const int32_t *__restrict__ tree_depth,
+    const int32_t *__restrict__ group_end, int n_groups, const float *__restrict__ X, int64_t n, int F, int XS,
+    double eta, float *__restrict__ margin, int cap_nodes) {
+    extern __shared__ char smem[];
+    float *xs = (float *)smem;
+    gbt_batch_node *nd = (gbt_batch_node *)(smem + (((size_t)kBatchRows * XS * 4 + 15) & ~(size_t)15));
+    double *wt = (double *)(nd + cap_nodes);
+    const int64_t r0 = (int64_t)blockIdx.x * kBatchRows;
+    const int rows = n - r0 < kBatchRows ? (int)(n - r0) : kBatchRows;
+    {   // the tile is one contiguous piece of X: element tid + 256 k is loaded by thread tid in step k,
+        // eight loads in flight per thread; (row, feature) of an element advance without divisions
+        const int total = rows * F;
+        const float *src = X + r0 * F;
+        const int dq = kBatchRows / F, dr = kBatchRows % F;
+        int row = (int)threadIdx.x / F, f = (int)threadIdx.x % F;
+        for (int i0 = threadIdx.x; i0 < total; i0 += 8 * kBatchRows) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = i0 + k * kBatchRows < total ? src[i0 + k * kBatchRows] : 0.0f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (i0 + k * kBatchRows < total) xs[row * XS + f] = v[k];
+                row += dq;
+                f += dr;
+                if (f >= F) {
+                    f -= F;
+                    ++row;
+                }
+            }
+        }
+    }
+    const bool live = (int)threadIdx.x < rows;
+    float m = live ? margin[r0 + threadIdx.x] : 0.0f;
+    const float *xrow = xs + (live ? (int)threadIdx.x : 0) * XS;
+    int t_begin = 0;
+    for (int g = 0; g < n_groups; ++g) {
+        const int t_end = group_end[g];
+        const int n0 = tree_off[t_begin], n1 = tree_off[t_end];
+        __syncthreads();   // the row tile is complete; the previous group's walks are done
+        for (int i0 = threadIdx.x; i0 < n1 - n0; i0 += 4 * kBatchRows) {   // eight loads in flight per thread
+            gbt_batch_node a[4];
+            double w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = i0 + k * kBatchRows;
+                const int ic = i < n1 - n0 ? i : n1 - n0 - 1;
+                a[k] = nodes_g[n0 + ic];
+                w[k] = wts_g[n0 + ic];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = i0 + k * kBatchRows;
+                if (i < n1 - n0) {
+                    nd[i] = a[k];
+                    wt[i] = w[k];
+                }
+            }
+        }
+        __syncthreads();
+        for (int t = t_begin; t < t_end; t += kBatchTrees) {
+            int base[kBatchTrees], id[kBatchTrees], depth = 0;
+#pragma unroll
+            for (int k = 0; k < kBatchTrees; ++k) {
+                const int tk = t + k < t_end ? t + k : t_end - 1;   // past the group: the last tree again, unused
+                base[k] = tree_off[tk] - n0;
+                id[k] = 0;
+                const int dk = tree_depth[tk];
+                depth = dk > depth ? dk : depth;
+            }
+            for (int d = 0; d < depth; ++d) {
+                // the four walks' LDS reads are issued together: first the nodes, then the values
+                uint2 q[kBatchTrees];
+                float x[kBatchTrees];
+#pragma unroll
+                for (int k = 0; k < kBatchTrees; ++k) q[k] = *(const uint2 *)&nd[base[k] + id[k]];   // x: thr, y: meta
+#pragma unroll
+                for (int k = 0; k < kBatchTrees; ++k) x[k] = xrow[q[k].y >> 17];
+#pragma unroll
+                for (int k = 0; k < kBatchTrees; ++k) {
+                    const uint32_t lt = x[k] < __uint_as_float(q[k].x) ? 1u : 0u;      // false for NaN
+                    const uint32_t nan = x[k] != x[k] ? 1u : 0u;
+                    const uint32_t go_left = (nan & (q[k].y >> 15)) | lt;
+                    id[k] = (int)((q[k].y & 0x7fffu) + ((go_left ^ 1u) & (q[k].y >> 16) & 1u));
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kBatchTrees; ++k)
+                if (t + k < t_end) m = (float)((double)m + eta * wt[base[k] + id[k]]);
+        }
+        t_begin = t_end;
+    }
+    if (live) margin[r0 + threadIdx.x] = m;
+}
+}  // namespace
+
+int gbt_predict_batch_max_features() { return 95; }   // 256 rows x 96 words = 96 KB of LDS for the row tile
+
+hipError_t gbt_launch_predict_raw_batched(hipStream_t s, const gbt_batch_node *nodes, const double *wts,
+                                          const int32_t *tree_off, const int32_t *tree_depth,
+                                          const int32_t *group_end, int n_groups, int cap_nodes, const float *X,
+                                          int64_t n, int F, double eta, float *margin) {
+    if (n <= 0 || n_groups <= 0) return hipSuccess;
+    const int XS = F | 1;
+    const size_t lds = (((size_t)kBatchRows * XS * 4 + 15) & ~(size_t)15) + (size_t)cap_nodes * 16;
+    static size_t configured = 0;
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)predict_raw_batched_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = lds;
+    }
+    const int64_t grid = (n + kBatchRows - 1) / kBatchRows;
+    predict_raw_batched_kernel<<<(unsigned)grid, kBatchRows, lds, s>>>(nodes, wts, tree_off, tree_depth, group_end,
+                                                                      n_groups, X, n, F, XS, eta, margin, cap_nodes);
+    return hipGetLastError();
+}
+
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
                               int64_t n, int F, double eta, float *margin, int32_t *leaf_out, int max_nodes,
