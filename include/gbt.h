@@ -277,6 +277,9 @@ GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits,
  *      most 64 words)
  *   2  as 1, and the launch also builds one child's histogram of every split
  *      node (8-bit symbols, at most 16 features)
+ *   3  rows wider than 64 words are never moved: the nodes' row-id lists are
+ *      partitioned (stable, three launches) and the histogram kernel gathers
+ *      the rows by id from the packed matrix
  * track_rows: whether the caller passes row_idx_out.  It does not change the
  * answer unless the library was told (GBT_TUNE_ORDER_ROWS=0 in the environment
  * when the context was created) to produce row_idx_out by carrying the ids,

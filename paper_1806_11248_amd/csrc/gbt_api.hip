@@ -189,6 +189,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->sparse_jobs_per_cu = 1;
         if (const char *e12 = getenv("GBT_TUNE_SPARSE_JOBS")) { int v = atoi(e12); if (v >= 1 && v <= 64) c->sparse_jobs_per_cu = v; }
         if (const char *e13 = getenv("GBT_TUNE_SPARSE_TILED")) c->sparse_tiled = atoi(e13) != 0;
+        c->part_ids = 1;
+        if (const char *e14 = getenv("GBT_TUNE_PART_IDS")) c->part_ids = atoi(e14) != 0;
         c->order_rows = 1;
         if (const char *e11 = getenv("GBT_TUNE_ORDER_ROWS")) c->order_rows = atoi(e11) != 0;
         if (const char *e10 = getenv("GBT_TUNE_HIST_FIX")) c->hist_fix = atoi(e10) != 0;
@@ -638,7 +640,9 @@ GbtRows working_rows_shape(int F, int bits) {
 }
 int grow_path(const gbt_ctx *ctx, int F, int bits, int B, bool tracked, int n_ftiles) {
     const GbtRows w = working_rows_shape(F, bits);
-    if ((tracked && !ctx->order_rows) || !ctx->part_fused || !gbt_partition_fused_ok(w)) return 0;
+    // rows too wide to be worth moving: they stay where they are and only their ids are partitioned
+    if (!gbt_partition_fused_ok(w)) return ctx->part_ids ? 3 : 0;
+    if ((tracked && !ctx->order_rows) || !ctx->part_fused) return 0;
     if (ctx->part_hist && n_ftiles == 1 && gbt_part_hist_ok(ctx, bits, F, B)) return 2;
     return 1;
 }
@@ -755,6 +759,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
     const double lambda = params->lambda;
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
+    if (path == 3 && root_may_split)   // the root's id list, read by the first partition
+        GBT_HIP(ctx, gbt_launch_iota_u32(s, W[1].id_rw, n));
     if (root_may_split) {
         const RootFix fix{gpair, scale[0], scale[1], gq, sums_dev};
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
@@ -878,7 +884,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         const int child_depth = sel_nodes[0].depth + 1;
         const bool children_need_hist =
             child_depth < max_depth && (!lossguide || n_leaves + 1 < max_leaves);
-        const bool fused = children_need_hist && path >= 1;
+        const bool unordered = path == 1 || path == 2;
+        const bool fused = children_need_hist && unordered;
         const bool with_hist = children_need_hist && path == 2;
         double part_rows = 0;
         for (const HNode &nd : sel_nodes) part_rows += nd.len;
@@ -924,10 +931,14 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                              n_children * hist_len));
             gbt_prof_end(ctx);
         }
-        const int what = children_need_hist ? GBT_PART_RECORDS : (tracked && path == 0) ? GBT_PART_IDS : GBT_PART_COUNT;
+        const int what = path == 3            ? GBT_PART_IDS
+                         : children_need_hist ? GBT_PART_RECORDS
+                         : (tracked && path == 0) ? GBT_PART_IDS
+                                                  : GBT_PART_COUNT;
         const double rec_bytes = row_bits / 8.0 + 8.0;
         gbt_prof_begin(ctx, with_hist ? GBT_PROF_HIST_NODE : GBT_PROF_PARTITION,
-                       part_rows * (fused ? 2.0 * rec_bytes
+                       part_rows * (path == 3 ? 8.0 + 32.0   // ids read and written, one sector of symbols per row
+                                    : fused   ? 2.0 * rec_bytes
                                     : what == GBT_PART_RECORDS ? row_bits / 8.0 + 2.0 * (rec_bytes + 4.0)
                                     : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
                                                                : row_bits / 8.0));
@@ -969,6 +980,15 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                                     (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
                                                     (int)tile_cursor, (unsigned long long *)(ws + L.state)));
             GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+            gbt_prof_end(ctx);
+        } else if (path == 3) {
+            // stable partition of the nodes' id lists; the symbols are gathered from the caller's matrix
+            GBT_HIP(ctx, gbt_launch_partition(s, packed, bits, row_bits, n, (uint32_t)missing_sym,
+                                              wcur == 2 ? W[1].id : W[wcur].id, W[wnext].id_rw,
+                                              (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
+                                              (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
+                                              (uint32_t *)(ws + L.n_left)));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
             gbt_prof_end(ctx);
         } else {
             GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym, what,
@@ -1041,9 +1061,14 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 if (st != GBT_OK) return st;
                 gbt_prof_begin(ctx, GBT_PROF_HIST_NODE,
                                j0 == 0 ? (double)built_rows * ((double)row_bits / 8.0 + 8.0) : 0.0);
-                GBT_HIP(ctx, gbt_launch_hist(ctx, W[wnext].sym, bits, W[wnext].stride_bits, W[wnext].n_words, n, B,
-                                             (uint32_t)missing_sym, nullptr, W[wnext].gq, pool,
-                                             (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
+                if (path == 3)   // the rows by id from the caller's matrix, the pairs by id
+                    GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, row_bits, gbt_packed_words(n, F, bits), n, B,
+                                                 (uint32_t)missing_sym, W[wnext].id, gq, pool,
+                                                 (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
+                else
+                    GBT_HIP(ctx, gbt_launch_hist(ctx, W[wnext].sym, bits, W[wnext].stride_bits, W[wnext].n_words, n, B,
+                                                 (uint32_t)missing_sym, nullptr, W[wnext].gq, pool,
+                                                 (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
                 gbt_prof_end(ctx);
             }
         }
@@ -1061,7 +1086,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)nd.buf, nd.len});
     for (const OpenLeaf &ol : open_leaves)
         leaves.push_back(LeafSeg{ol.nd.begin, (uint32_t)ol.nd.id, (uint32_t)ol.nd.buf, ol.nd.len});
-    if (!tracked || path != 0) {
+    if (!tracked || path == 1 || path == 2) {
         tree->n_nodes = n_nodes;
         // the rows were not followed: one walk of the finished tree over the matrix names each row's leaf
         int32_t *leaf_ids = leaf_of_row_out ? leaf_of_row_out : (int32_t *)W[0].id_rw;

@@ -26,6 +26,7 @@ struct gbt_ctx {
     int hist_block;         // threads per histogram workgroup
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
     int part_fused;         // 1: one-launch record partition where it applies
+    int part_ids;           // 1: rows wider than 64 words are not moved: id lists are partitioned and the histogram kernel gathers
     int order_rows;         // 1: a caller's row order is made from the finished tree, so that it does not restrict the partition form
     int hist_fix;           // 1: the root histogram kernel also converts the gradient pairs where that applies
     int part_hist;          // 1: and the children's histograms in the same pass where that applies

@@ -233,13 +233,11 @@ __global__ __launch_bounds__(kOrdBlock) void order_scatter_kernel(const int32_t 
     }
 }
 
-__global__ __launch_bounds__(256) void iota_u32_kernel(uint32_t *p, int64_t n) {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = (uint32_t)i;
-}
 
 }  // namespace
 
 int gbt_order_tile() { return kOrdTile; }
+
 
 size_t gbt_order_ws(int64_t n) {
     const int64_t tiles = (n + kOrdTile - 1) / kOrdTile, chunks = (tiles + kOrdChunk - 1) / kOrdChunk;
@@ -250,12 +248,7 @@ hipError_t gbt_launch_order_rows(hipStream_t s, const int32_t *leaf, const uint3
                                  uint32_t n_ranks, int64_t n, uint32_t *key_tmp[2], uint32_t *val_tmp[2], char *ws,
                                  uint32_t *row_idx_out) {
     if (n <= 0) return hipSuccess;
-    if (n_ranks <= 1) {   // one leaf: the ids in order
-        int64_t g = (n + 2047) / 2048;
-        if (g > 8192) g = 8192;
-        iota_u32_kernel<<<(unsigned)g, 256, 0, s>>>(row_idx_out, n);
-        return hipGetLastError();
-    }
+    if (n_ranks <= 1) return gbt_launch_iota_u32(s, row_idx_out, n);   // one leaf: the ids in order
     int rank_bits = 1;
     while (rank_bits < 32 && (1ull << rank_bits) < (unsigned long long)n_ranks) ++rank_bits;
     const int passes = (rank_bits + 7) / 8;

@@ -96,6 +96,8 @@ def test_tree_matches_oracle(ctx, oracle, cfg, n, kw, csr):
     n, F = X.shape
     _say(f"tree C{cfg} n={n} F={F} depth={p['max_depth']}")
     o, gdev = gpu_prep(ctx, oracle, d, use_csr=csr)
+    wide = F * gdev["bits"] > 64 * 32      # such rows are not moved: id lists are partitioned instead
+    assert (ctx.grow_tree_path(F, gdev["bits"], p["max_bins"], track_rows=True) == 3) == wide
     if p["objective"] == "given":
         gp = np.stack([d["g"], d["h"]], 1)
     else:
@@ -143,16 +145,17 @@ def ctx_env(monkeypatch):
         c.close()
 
 
-@pytest.mark.parametrize("cfg,n,kw", [(4, 150_000, {}), (3, 40_000, {}), (5, 5_000, {"F": 200})])
+@pytest.mark.parametrize("cfg,n,kw", [(4, 150_000, {}), (3, 40_000, {}), (5, 5_000, {"F": 200}), (5, 4_000, {"F": 500})])
 def test_three_launch_partition_path(ctx_env, oracle, cfg, n, kw):
-    """Without row ids the record partition normally takes its one-launch form; switched off, the
-    flag / scan / move form (the one tracked rows and wide rows always take) must grow the same trees."""
-    c = ctx_env(GBT_TUNE_PART_FUSED=0, GBT_TUNE_HIST_FIX=0)   # and the separate fixed-point conversion pass
+    """The record partition normally takes its one-launch form (rows wider than 64 words: only ids
+    move); switched off, the flag / scan / move form that carries whole records must grow the same trees."""
+    c = ctx_env(GBT_TUNE_PART_FUSED=0, GBT_TUNE_PART_IDS=0, GBT_TUNE_HIST_FIX=0)   # and the separate fixed-point conversion pass
     d = synth.make(cfg, n, **kw)
     p = d["params"]
     n, F = d["X"].shape
     _say(f"three-launch partition C{cfg} n={n} F={F}")
     o, gdev = gpu_prep(c, oracle, d)
+    assert c.grow_tree_path(F, gdev["bits"], p["max_bins"], track_rows=True) == 0
     gp = (np.stack([d["g"], d["h"]], 1) if p["objective"] == "given"
           else oracle.gradients(p["objective"], np.zeros(n, np.float32), d["y"]))
     grow_and_judge(c, oracle, o, gdev, gp, p, n, F)
