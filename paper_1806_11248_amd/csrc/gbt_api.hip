@@ -189,6 +189,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->sparse_jobs_per_cu = 1;
         if (const char *e12 = getenv("GBT_TUNE_SPARSE_JOBS")) { int v = atoi(e12); if (v >= 1 && v <= 64) c->sparse_jobs_per_cu = v; }
         if (const char *e13 = getenv("GBT_TUNE_SPARSE_TILED")) c->sparse_tiled = atoi(e13) != 0;
+        c->part_nomove = 1;
+        if (const char *e15 = getenv("GBT_TUNE_PART_NOMOVE")) c->part_nomove = atoi(e15) != 0;
         c->part_ids = 1;
         if (const char *e14 = getenv("GBT_TUNE_PART_IDS")) c->part_ids = atoi(e14) != 0;
         c->order_rows = 1;
@@ -618,6 +620,14 @@ struct HNode {
     int64_t Gq, Hq;
     int32_t depth;
     int32_t buf;   // where the node's rows are: 0/1 = working copy, 2 = the caller's matrix (the root)
+    // >= 0: the rows were not moved at the parent's split: they lie interleaved with the sibling's in the
+    // parent's segment; 2 * (index of the parent's record in the table of such splits) + (1 for the right child)
+    int32_t virt = -1;
+};
+struct UnmovedSplit {   // a split whose rows stayed in place
+    uint32_t begin, len;   // the parent's segment
+    int32_t buf;
+    uint32_t feature, bin, default_left;
 };
 enum { GBT_POLICY_DEPTHWISE = 0, GBT_POLICY_LOSSGUIDE = 1 };
 constexpr int32_t kMaxLeaves = 1 << 20;
@@ -798,6 +808,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     // loss-guided: the leaves that may still be split, with their best splits
     struct OpenLeaf { HNode nd; gbt_split sp; };
     std::vector<OpenLeaf> open_leaves;
+    std::vector<UnmovedSplit> unmoved;
+    std::vector<CountJob> cjobs;
+    std::vector<uint32_t> nl_of;       // left rows of each node this round splits
     std::vector<HNode> sel_nodes;      // the nodes this round splits ...
     std::vector<gbt_split> sel_splits; // ... and how
 
@@ -887,6 +900,11 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         const bool unordered = path == 1 || path == 2;
         const bool fused = children_need_hist && unordered;
         const bool with_hist = children_need_hist && path == 2;
+        // Depth-wise, the last level that needs histograms: its children's children are leaves, of which only
+        // the row counts are wanted.  The pass then builds the histograms and counts without moving a row,
+        // and the counts one level down come from a two-level count over the parents' segments.
+        const bool nomove = with_hist && !lossguide && child_depth == max_depth - 1 && ctx->part_nomove;
+        const bool two_level = !children_need_hist && sel_nodes[0].virt >= 0;
         double part_rows = 0;
         for (const HNode &nd : sel_nodes) part_rows += nd.len;
         // rows per partition workgroup: a tile, or (with the histogram) a span of tiles long enough
@@ -919,89 +937,140 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             pjobs.push_back(j);
         }
         next.clear();
-        // the three-launch form keeps ballots and counts per tile in the workspace
-        GBT_REQUIRE(ctx, fused || (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
-        GBT_REQUIRE(ctx, pjobs.size() * sizeof(PartJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
-        st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
-        if (st != GBT_OK) return st;
-        if (with_hist) {   // the children's histograms are accumulated into: clear them first
-            const int64_t n_children = 2 * (int64_t)pjobs.size();
-            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
-            GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)n_nodes * hist_len), 0,
-                                             n_children * hist_len));
-            gbt_prof_end(ctx);
-        }
+        nl_of.assign(sel_nodes.size(), 0u);
         const int what = path == 3            ? GBT_PART_IDS
                          : children_need_hist ? GBT_PART_RECORDS
                          : (tracked && path == 0) ? GBT_PART_IDS
                                                   : GBT_PART_COUNT;
-        const double rec_bytes = row_bits / 8.0 + 8.0;
-        gbt_prof_begin(ctx, with_hist ? GBT_PROF_HIST_NODE : GBT_PROF_PARTITION,
-                       part_rows * (path == 3 ? 8.0 + 32.0   // ids read and written, one sector of symbols per row
-                                    : fused   ? 2.0 * rec_bytes
-                                    : what == GBT_PART_RECORDS ? row_bits / 8.0 + 2.0 * (rec_bytes + 4.0)
-                                    : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
-                                                               : row_bits / 8.0));
-        if (with_hist) {
-            // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
-            GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
-                                              wcur == 2 ? nullptr : W[wcur].sym, W[wnext].sym_rw, F, B,
-                                              (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
-                                              (int)pjobs.size(), (int)tile_cursor, part_tile,
-                                              (unsigned long long *)(ws + L.state), pool));
-            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
-            gbt_prof_end(ctx);
-            // Everything the children's evaluation needs is known before the rows are counted (ids,
-            // sums, which child was built): enqueue the subtraction and the evaluation behind the
-            // pass, so that the host waits once per level instead of twice.
-            sjobs.clear();
-            enodes.clear();
-            for (size_t k = 0; k < pjobs.size(); ++k) {
-                const HNode &nd = sel_nodes[k];
-                const gbt_split &sp = sel_splits[k];
-                const int64_t lid = n_nodes + 2 * (int64_t)k, rid = lid + 1;
-                const int64_t built = pjobs[k].pad == 1u ? lid : rid, other = pjobs[k].pad == 1u ? rid : lid;
-                sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)built * (uint64_t)hist_len,
-                                       (uint64_t)other * (uint64_t)hist_len});
-                enodes.push_back(EvalNode{(uint64_t)lid * (uint64_t)hist_len, sp.GLq, sp.HLq});
-                enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq});
+        if (two_level) {
+            // one job per parent segment that has a child to count for (siblings are adjacent in sel_nodes)
+            cjobs.clear();
+            std::vector<int> job_of(sel_nodes.size());
+            uint32_t ctiles = 0;
+            const uint32_t ct = (uint32_t)gbt_count2_tile();
+            for (size_t k = 0; k < sel_nodes.size(); ++k) {
+                const int pi = sel_nodes[k].virt >> 1, side = sel_nodes[k].virt & 1;
+                const UnmovedSplit &u = unmoved[(size_t)pi];
+                if (cjobs.empty() || job_of[k - 1] < 0 || (sel_nodes[k - 1].virt >> 1) != pi) {
+                    CountJob cj{};
+                    cj.seg_begin = u.begin;
+                    cj.seg_len = u.len;
+                    cj.tile_begin = ctiles;
+                    cj.n_tiles = (u.len + ct - 1) / ct;
+                    cj.feature[0] = u.feature;
+                    cj.bin[0] = u.bin;
+                    cj.default_left[0] = u.default_left;
+                    ctiles += cj.n_tiles;
+                    cjobs.push_back(cj);
+                }
+                CountJob &cj = cjobs.back();
+                cj.feature[1 + side] = (uint32_t)sel_splits[k].feature;
+                cj.bin[1 + side] = (uint32_t)sel_splits[k].bin;
+                cj.default_left[1 + side] = (uint32_t)sel_splits[k].default_left;
+                cj.has[side] = 1;
+                job_of[k] = (int)cjobs.size() - 1;
             }
-            GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
-            st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
+            GBT_REQUIRE(ctx, cjobs.size() * sizeof(CountJob) <= kUploadBytes && cjobs.size() * 8 <= (size_t)L.level_nodes * 8,
+                        GBT_EUNSUPPORTED, "level too wide");
+            st = upload(ctx, cjobs.data(), cjobs.size() * sizeof(CountJob), ws + L.jobs);
             if (st != GBT_OK) return st;
-            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
-            GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
+            const UnmovedSplit &u0 = unmoved[(size_t)(sel_nodes[0].virt >> 1)];
+            const bool from_matrix = u0.buf == 2;
+            const uint8_t *rows8 = from_matrix ? (const uint8_t *)packed : (const uint8_t *)W[u0.buf].sym;
+            const int64_t stride8 = from_matrix ? (int64_t)F : 4 * (int64_t)gbt_part_hist_record_words(F);
+            double crow = 0;
+            for (const CountJob &cj : cjobs) crow += cj.seg_len;
+            gbt_prof_begin(ctx, GBT_PROF_PARTITION, crow * (double)stride8);
+            GBT_HIP(ctx, gbt_launch_count2(s, rows8, stride8, (uint32_t)missing_sym, (const CountJob *)(ws + L.jobs),
+                                           (int)cjobs.size(), (int)ctiles, (uint32_t *)(ws + L.state)));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, cjobs.size() * 8, hipMemcpyDeviceToHost, s));
             gbt_prof_end(ctx);
-            st = enqueue_eval(enodes, &chunks);
-            if (st != GBT_OK) return st;
-            pre_eval = true;
-        } else if (fused) {
-            GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,
-                                                    (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
-                                                    (int)tile_cursor, (unsigned long long *)(ws + L.state)));
-            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
-            gbt_prof_end(ctx);
-        } else if (path == 3) {
-            // stable partition of the nodes' id lists; the symbols are gathered from the caller's matrix
-            GBT_HIP(ctx, gbt_launch_partition(s, packed, bits, row_bits, n, (uint32_t)missing_sym,
-                                              wcur == 2 ? W[1].id : W[wcur].id, W[wnext].id_rw,
-                                              (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
-                                              (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
-                                              (uint32_t *)(ws + L.n_left)));
-            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
-            gbt_prof_end(ctx);
+            GBT_SYNC(ctx);
+            const uint32_t *cnt = (const uint32_t *)rb(ctx);
+            for (size_t k = 0; k < sel_nodes.size(); ++k) nl_of[k] = cnt[2 * job_of[k] + (sel_nodes[k].virt & 1)];
         } else {
-            GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym, what,
-                                                      (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
-                                                      (int)tile_cursor, (uint64_t *)(ws + L.masks),
-                                                      (uint32_t *)(ws + L.tile_left), (uint32_t *)(ws + L.n_left)));
-            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
-            gbt_prof_end(ctx);
+            // the three-launch form keeps ballots and counts per tile in the workspace
+            GBT_REQUIRE(ctx, fused || (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
+            GBT_REQUIRE(ctx, pjobs.size() * sizeof(PartJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
+            st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
+            if (st != GBT_OK) return st;
+            if (with_hist) {   // the children's histograms are accumulated into: clear them first
+                const int64_t n_children = 2 * (int64_t)pjobs.size();
+                gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
+                GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)n_nodes * hist_len), 0,
+                                                 n_children * hist_len));
+                gbt_prof_end(ctx);
+            }
+            const double rec_bytes = row_bits / 8.0 + 8.0;
+            gbt_prof_begin(ctx, with_hist ? GBT_PROF_HIST_NODE : GBT_PROF_PARTITION,
+                           part_rows * (path == 3 ? 8.0 + 32.0   // ids read and written, one sector of symbols per row
+                                        : nomove  ? rec_bytes
+                                    : fused   ? 2.0 * rec_bytes
+                                        : what == GBT_PART_RECORDS ? row_bits / 8.0 + 2.0 * (rec_bytes + 4.0)
+                                        : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
+                                                                   : row_bits / 8.0));
+            if (with_hist) {
+                // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
+                GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
+                                                  wcur == 2 ? nullptr : W[wcur].sym, nomove ? nullptr : W[wnext].sym_rw, F, B,
+                                                  (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
+                                                  (int)pjobs.size(), (int)tile_cursor, part_tile,
+                                                  (unsigned long long *)(ws + L.state), pool));
+                GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+                gbt_prof_end(ctx);
+                // Everything the children's evaluation needs is known before the rows are counted (ids,
+                // sums, which child was built): enqueue the subtraction and the evaluation behind the
+                // pass, so that the host waits once per level instead of twice.
+                sjobs.clear();
+                enodes.clear();
+                for (size_t k = 0; k < pjobs.size(); ++k) {
+                    const HNode &nd = sel_nodes[k];
+                    const gbt_split &sp = sel_splits[k];
+                    const int64_t lid = n_nodes + 2 * (int64_t)k, rid = lid + 1;
+                    const int64_t built = pjobs[k].pad == 1u ? lid : rid, other = pjobs[k].pad == 1u ? rid : lid;
+                    sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)built * (uint64_t)hist_len,
+                                           (uint64_t)other * (uint64_t)hist_len});
+                    enodes.push_back(EvalNode{(uint64_t)lid * (uint64_t)hist_len, sp.GLq, sp.HLq});
+                    enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq});
+                }
+                GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
+                st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
+                if (st != GBT_OK) return st;
+                gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
+                GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
+                gbt_prof_end(ctx);
+                st = enqueue_eval(enodes, &chunks);
+                if (st != GBT_OK) return st;
+                pre_eval = true;
+            } else if (fused) {
+                GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,
+                                                        (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
+                                                        (int)tile_cursor, (unsigned long long *)(ws + L.state)));
+                GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+                gbt_prof_end(ctx);
+            } else if (path == 3) {
+                // stable partition of the nodes' id lists; the symbols are gathered from the caller's matrix
+                GBT_HIP(ctx, gbt_launch_partition(s, packed, bits, row_bits, n, (uint32_t)missing_sym,
+                                                  wcur == 2 ? W[1].id : W[wcur].id, W[wnext].id_rw,
+                                                  (const PartJob *)(ws + L.jobs), (int)pjobs.size(), (int)tile_cursor,
+                                                  (uint64_t *)(ws + L.masks), (uint32_t *)(ws + L.tile_left),
+                                                  (uint32_t *)(ws + L.n_left)));
+                GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
+                gbt_prof_end(ctx);
+            } else {
+                GBT_HIP(ctx, gbt_launch_partition_records(s, cur, W[wnext], bits, row_bits, n, (uint32_t)missing_sym, what,
+                                                          (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
+                                                          (int)tile_cursor, (uint64_t *)(ws + L.masks),
+                                                          (uint32_t *)(ws + L.tile_left), (uint32_t *)(ws + L.n_left)));
+                GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.n_left, pjobs.size() * 4, hipMemcpyDeviceToHost, s));
+                gbt_prof_end(ctx);
+            }
+            GBT_SYNC(ctx);
+            const int nl_stride = fused ? 2 : 1;   // the one-launch form returns 64-bit cursors, n_left in the low half
+            const uint32_t *n_left = (const uint32_t *)rb(ctx);
+            for (size_t k = 0; k < pjobs.size(); ++k) nl_of[k] = n_left[k * nl_stride];
         }
-        GBT_SYNC(ctx);
-        const int nl_stride = fused ? 2 : 1;   // the one-launch form returns 64-bit cursors, n_left in the low half
-        const int child_buf = what != GBT_PART_COUNT ? wnext : wcur;   // a count moves nothing
-        const uint32_t *n_left = (const uint32_t *)rb(ctx);
+        const int child_buf = (nomove || two_level || what == GBT_PART_COUNT) ? wcur : wnext;   // a count moves nothing
 
         // ---- children, in creation order
         hjobs.clear();
@@ -1013,10 +1082,16 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         for (size_t k = 0; k < pjobs.size(); ++k) {
             const HNode &nd = sel_nodes[k];
             const gbt_split &sp = sel_splits[k];
-            const uint32_t nl = n_left[k * nl_stride];
+            const uint32_t nl = nl_of[k];
             GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
             HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, child_depth, child_buf};
             HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, child_depth, child_buf};
+            if (nomove) {
+                lc.virt = 2 * (int32_t)unmoved.size();
+                rc.virt = lc.virt + 1;
+                unmoved.push_back(UnmovedSplit{nd.begin, nd.len, wcur, (uint32_t)sp.feature, (uint32_t)sp.bin,
+                                               (uint32_t)sp.default_left});
+            }
             n_nodes += 2;
             n_leaves += 1;
             tree->feature[nd.id] = sp.feature;

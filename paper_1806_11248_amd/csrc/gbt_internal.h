@@ -26,6 +26,7 @@ struct gbt_ctx {
     int hist_block;         // threads per histogram workgroup
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
     int part_fused;         // 1: one-launch record partition where it applies
+    int part_nomove;        // 1: the last histogram level of a depth-wise tree is built without moving rows (partition + histogram pass)
     int part_ids;           // 1: rows wider than 64 words are not moved: id lists are partitioned and the histogram kernel gathers
     int order_rows;         // 1: a caller's row order is made from the finished tree, so that it does not restrict the partition form
     int hist_fix;           // 1: the root histogram kernel also converts the gradient pairs where that applies
@@ -92,6 +93,17 @@ struct PartJob {
     uint32_t n_tiles;
     uint32_t pad;          // partition + histogram pass: the child to build (1 left, 0 right, 2 none)
     uint64_t hist_off;     // same pass: that child's histogram in the pool (int64 units)
+};
+
+// One parent segment for the two-level row count: the rows still lie in the parent's order, its split
+// (index 0) tells each row's child, and the children's splits (1: left child, 2: right child; has[] = 0
+// for a child that is not split) tell the row's side there.
+struct CountJob {
+    uint32_t seg_begin, seg_len;
+    uint32_t tile_begin, n_tiles;
+    uint32_t feature[3], bin[3], default_left[3];
+    uint32_t has[2];
+    uint32_t pad;
 };
 
 // One "out = parent - child" for the subtraction kernel (int64 units).
@@ -192,7 +204,14 @@ hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t str
 // (rows of F bytes) with the pairs in gq.  PartJob.tile_begin / n_tiles count spans of rows_per_span
 // rows (a multiple of gbt_part_hist_tile()); PartJob.pad / hist_off name the child to build, whose
 // histogram must have been cleared.
+// dst_records == NULL: nothing is moved (the children's rows stay interleaved in the parent's segment);
+// the histogram is built and the low word of each cursor counts the left rows.
 bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B);
+// Rows of 8-bit symbols, row p at byte p * stride_bytes of `rows`: counts[2 * j + c] = rows of job j's
+// child c that go left at that child's split.  counts is cleared here.
+int gbt_count2_tile();
+hipError_t gbt_launch_count2(hipStream_t s, const uint8_t *rows, int64_t stride_bytes, uint32_t missing,
+                             const CountJob *jobs, int n_jobs, int n_tiles, uint32_t *counts);
 int gbt_part_hist_tile();
 int gbt_part_hist_record_words(int F);
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,

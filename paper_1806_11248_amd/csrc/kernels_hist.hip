@@ -503,6 +503,8 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     const uint32_t seg_last = job.seg_begin + job.seg_len - 1u;
     __syncthreads();
 
+    const bool nomove = dst == nullptr;   // the rows stay where they are: no ranks, no room to reserve, no barriers
+    uint32_t my_lefts = 0;                // nomove, lane 0 of every wave: left rows seen
     int par = 0;
     for (uint32_t done = 0; done < span_rows; done += kPHTile, par ^= 1) {
         const uint32_t tile_rows = span_rows - done < (uint32_t)kPHTile ? span_rows - done : (uint32_t)kPHTile;
@@ -552,14 +554,15 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
                 takebits |= (build && left == build_left) ? (1u << j) : 0u;
             }
             const uint64_t ballot = __ballot(left);
-            if (lane == 0) words[par][w] = ballot;
+            if (nomove) my_lefts += (uint32_t)__popcll(ballot);
+            else if (lane == 0) words[par][w] = ballot;
         }
-        __syncthreads();
+        if (!nomove) __syncthreads();
 
         // ---- wave 0 ranks the ballot words and reserves the tile's room (the answer is awaited after
         //      the histogram work below)
         unsigned long long reserved = 0;
-        if (wave == 0) {
+        if (wave == 0 && !nomove) {
             const uint32_t c = (uint32_t)__popcll(words[par][lane]);   // kPHWords == 64: one word per lane
             uint32_t x = c;
             for (int d = 1; d < 64; d <<= 1) {
@@ -610,6 +613,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
                 }
             }
         }
+        if (nomove) continue;
         if (wave == 0 && lane == 63) {
             base_s[par][0] = (uint32_t)(reserved & 0xffffffffull);
             base_s[par][1] = (uint32_t)(reserved >> 32);
@@ -639,6 +643,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
         }
         // words[par] is rewritten two tiles from now, after two more barriers: no third barrier needed
     }
+    if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[ji], (unsigned long long)my_lefts);
     __syncthreads();
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, kPHBlock);
 }

@@ -572,6 +572,69 @@ hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Row counts two levels down, for the children of nodes whose rows were not moved at their own
+// split (the last level that needs histograms: its children's histograms come out of the pass that
+// would have moved the rows, and below them only row counts are wanted).  One byte per level and row
+// is needed; the rows come in by whole sectors.
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int kC2Block = 512, kC2Rows = 8, kC2Tile = kC2Block * kC2Rows;
+
+__global__ __launch_bounds__(kC2Block) void count2_kernel(const uint8_t *__restrict__ rows, int64_t stride_bytes,
+                                                          uint32_t missing, const CountJob *__restrict__ jobs,
+                                                          int n_jobs, uint32_t *__restrict__ counts) {
+    __shared__ uint32_t acc[2];
+    int lo = 0, hi = n_jobs;   // last job with tile_begin <= this tile
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (jobs[mid].tile_begin <= blockIdx.x) lo = mid; else hi = mid;
+    }
+    const CountJob job = jobs[lo];
+    if (threadIdx.x < 2) acc[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t t0 = (blockIdx.x - job.tile_begin) * (uint32_t)kC2Tile;
+    uint32_t s0[kC2Rows], s1[kC2Rows], s2[kC2Rows];
+#pragma unroll
+    for (int j = 0; j < kC2Rows; ++j) {   // every load of the tile is issued before the first is used
+        const uint32_t i = t0 + (uint32_t)j * kC2Block + threadIdx.x;
+        const uint32_t ic = i < job.seg_len ? i : job.seg_len - 1;
+        const uint8_t *rp = rows + ((uint64_t)job.seg_begin + ic) * (uint64_t)stride_bytes;
+        s0[j] = rp[job.feature[0]];
+        s1[j] = rp[job.feature[1]];
+        s2[j] = rp[job.feature[2]];
+    }
+    uint32_t c0 = 0, c1 = 0;
+#pragma unroll
+    for (int j = 0; j < kC2Rows; ++j) {
+        const uint32_t i = t0 + (uint32_t)j * kC2Block + threadIdx.x;
+        const bool live = i < job.seg_len;
+        const bool left0 = s0[j] == missing ? job.default_left[0] != 0 : s0[j] <= job.bin[0];
+        const uint32_t sc = left0 ? s1[j] : s2[j];
+        const int c = left0 ? 1 : 2;
+        const bool leftc = sc == missing ? job.default_left[c] != 0 : sc <= job.bin[c];
+        c0 += (uint32_t)__popcll(__ballot(live && left0 && leftc));
+        c1 += (uint32_t)__popcll(__ballot(live && !left0 && leftc));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        if (c0) atomicAdd(&acc[0], c0);
+        if (c1) atomicAdd(&acc[1], c1);
+    }
+    __syncthreads();
+    if (threadIdx.x < 2 && acc[threadIdx.x] && job.has[threadIdx.x]) atomicAdd(&counts[2 * lo + threadIdx.x], acc[threadIdx.x]);
+}
+}  // namespace
+
+int gbt_count2_tile() { return kC2Tile; }
+hipError_t gbt_launch_count2(hipStream_t s, const uint8_t *rows, int64_t stride_bytes, uint32_t missing,
+                             const CountJob *jobs, int n_jobs, int n_tiles, uint32_t *counts) {
+    if (n_jobs <= 0) return hipSuccess;
+    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)counts, 0, n_jobs);   // two 32-bit counts per job
+    if (e != hipSuccess || n_tiles <= 0) return e;
+    count2_kernel<<<n_tiles, kC2Block, 0, s>>>(rows, stride_bytes, missing, jobs, n_jobs, counts);
+    return hipGetLastError();
+}
+
 bool gbt_partition_fused_ok(const GbtRows &dst) { return (dst.stride_bits >> 5) <= 64; }
 int gbt_partition_fused_tile(const GbtRows &dst) {
     return (dst.stride_bits >> 5) == 4 ? kFTile : staged_tile_rows(dst.stride_bits);

@@ -237,3 +237,27 @@ def test_boosting_rounds_in_lock_step(ctx, oracle):
                         missing_sym=gdev["missing"], n=n, F=F)
             margin_ref = oracle.predict_sym(tree, o["sym"], o["missing"], p["eta"], margin_ref)
             assert np.allclose(margin_gpu.cpu().numpy(), margin_ref, rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("depth", [1, 2, 3, 6])
+def test_last_levels_without_moving_rows(ctx, ctx_env, oracle, depth):
+    """Byte symbols, at most 16 features: the level above the last split level builds its children's
+    histograms without moving rows and the leaves' row counts come from a two-level count (depth 2:
+    straight from the packed matrix).  Same trees as with the rows moved at every level."""
+    d = synth.make(4, 120_000)
+    p = dict(d["params"], max_depth=depth)
+    n, F = d["X"].shape
+    _say(f"no-move last levels, depth {depth}")
+    o, gdev = gpu_prep(ctx, oracle, d)
+    gp = oracle.gradients(p["objective"], np.zeros(n, np.float32), d["y"])
+    tree, rep = grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
+    import paper_1806_11248_amd as g
+    params = g.make_params(max_depth=depth, max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
+                           min_child_weight=p["min_child_weight"])
+    moved, _, _ = ctx_env(GBT_TUNE_PART_NOMOVE=0).grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"],
+                                                          gdev["nb"], gdev["cuts"], dev(gp), params, want_rows=False,
+                                                          want_leaf=False)
+    nn = tree["n_nodes"]
+    assert moved["n_nodes"] == nn
+    for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "weight", "gain"):
+        assert np.array_equal(moved[k][:nn], tree[k][:nn]), k
