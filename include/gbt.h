@@ -373,8 +373,8 @@ GBT_API int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
                     double eta, float *margin_inout, void *workspace, size_t workspace_bytes);
 
 /* gbt_predict over sparse rows: left iff the row's symbol of the node's feature
- * is <= bin, an absent element -> default child.  A tree must fit LDS (32 bytes
- * per node).  workspace as for gbt_predict.  Synchronises the stream. */
+ * is <= bin, an absent element -> default child.  workspace as for gbt_predict.
+ * Synchronises the stream. */
 GBT_API int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *rowptr,
                       const uint16_t *ent, int64_t n, int32_t F, int32_t max_bins, double eta, float *margin,
                       void *workspace, size_t workspace_bytes);

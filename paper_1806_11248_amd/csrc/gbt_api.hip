@@ -1419,8 +1419,6 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
         }
     }
     if (sparse) {
-        GBT_REQUIRE(ctx, (size_t)max_nodes * 32 + 16384 <= ctx->lds_per_block, GBT_EUNSUPPORTED,
-                    "a tree of %d nodes does not fit the LDS of the sparse-row walk", max_nodes);
         if (own_span) gbt_prof_begin(ctx, GBT_PROF_OTHER, 0.0);
         GBT_HIP(ctx, gbt_launch_sparse_walk(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees,
                                             sparse->rowptr, sparse->ent, n, sparse->B, eta, margin, leaf_out, max_nodes));

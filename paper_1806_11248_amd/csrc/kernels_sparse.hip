@@ -427,6 +427,8 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
                                                           const uint16_t *__restrict__ ent, int64_t n, uint32_t B,
                                                           double eta, float *margin, int32_t *leaf_out,
                                                           int rows_per_block, int max_nodes) {
+    // max_nodes == 0: the trees are too large for LDS, their nodes are read from the staged arrays
+    const bool lds_nodes = max_nodes > 0;
     extern __shared__ SpNode sp_nodes[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t *st = (uint32_t *)(sp_nodes + max_nodes) + wave * kWalkWords;
@@ -436,7 +438,7 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
     for (int t = 0; t < n_trees; ++t) {
         const DevTree T = trees[t];
         __syncthreads();
-        for (int i = threadIdx.x; i < T.n_nodes; i += 256) {
+        for (int i = threadIdx.x; lds_nodes && i < T.n_nodes; i += 256) {
             SpNode nd;
             nd.feature = ((const int32_t *)(ws + T.feature))[i];
             nd.bin = ((const int32_t *)(ws + T.bin))[i];
@@ -468,7 +470,16 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
                 const uint32_t sb = word0 * 2;
                 int node = 0;
                 for (int step = 0; step < T.n_nodes; ++step) {
-                    const SpNode nd = sp_nodes[node];
+                    SpNode nd;
+                    if (lds_nodes) {
+                        nd = sp_nodes[node];
+                    } else {
+                        nd.feature = ((const int32_t *)(ws + T.feature))[node];
+                        nd.bin = ((const int32_t *)(ws + T.bin))[node];
+                        nd.left = ((const int32_t *)(ws + T.left))[node];
+                        nd.right = ((const int32_t *)(ws + T.right))[node];
+                        nd.dl = ((const int32_t *)(ws + T.default_left))[node];
+                    }
                     if (nd.feature < 0) break;
                     const uint32_t lo = (uint32_t)nd.feature * B;
                     const uint32_t g = fits ? find_feature_entry(st16, s - sb, e - sb, lo, B)
@@ -477,7 +488,8 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
                     node = go_left ? nd.left : nd.right;
                 }
                 if (leaf_out) leaf_out[r] = node;
-                else margin[r] = (float)((double)margin[r] + eta * sp_nodes[node].weight);
+                else margin[r] = (float)((double)margin[r] +
+                                         eta * (lds_nodes ? sp_nodes[node].weight : ((const double *)(ws + T.weight))[node]));
             }
             __builtin_amdgcn_wave_barrier();   // the window is refilled only after every lane has left it
         }
@@ -564,11 +576,12 @@ hipError_t gbt_launch_sparse_partition(hipStream_t s, const uint32_t *src_rowptr
     return hipGetLastError();
 }
 
-// the trees staged as for gbt_launch_predict; nodes of one tree must fit LDS (32 bytes each)
+// the trees staged as for gbt_launch_predict; a tree's nodes go through LDS (32 bytes each) when they fit
 hipError_t gbt_launch_sparse_walk(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                                   const uint32_t *rowptr, const uint16_t *ent, int64_t n, int B, double eta,
                                   float *margin, int32_t *leaf_out, int max_nodes) {
     if (n <= 0 || n_trees <= 0) return hipSuccess;
+    if ((size_t)max_nodes * sizeof(SpNode) + 4 * kWalkWords * 4 > 120u * 1024u) max_nodes = 0;   // nodes stay in HBM / L2
     const size_t lds = (size_t)max_nodes * sizeof(SpNode) + 4 * kWalkWords * 4;
     static size_t configured = 0;
     if (lds > configured) {

@@ -112,6 +112,7 @@ def test_sparse_hist_extreme_pile_up(ctx, oracle):
 TREE_CASES = [  # config, rows, kwargs, max_depth override
     (3, 60_000, {}, None),                # the sparse workload: 50 features, 80% missing, depth 8
     (3, 9_000, {}, 11),                   # deep: more than 256 leaves, tiny nodes, many leaves above the last level
+    (2, 40_000, {}, 13),                  # a tree too large for the walk's LDS: nodes are read from memory
     (4, 100_000, {}, 6),                  # nothing missing: 13 entries in every row
     (2, 30_000, {}, None),                # 28 features, dense
 ]
