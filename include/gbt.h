@@ -329,8 +329,13 @@ GBT_API int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits
  * two node ids at the moment of the expansion, so the k-th expansion creates nodes
  * 2k+1 and 2k+2.  Arguments, outputs, the NULL row_idx_out form and error behaviour
  * as for gbt_grow_tree; tree_out needs capacity >= 2*max_leaves - 1.
- * One node is split per step (partition, one child's histogram, subtraction,
- * evaluation of both children) with the kernels of the depth-wise loop.
+ * The kernels are those of the depth-wise loop.  Work is issued in rounds: the
+ * leaf whose turn it is and a few more open leaves in gain order are expanded
+ * together (a leaf's best split does not depend on when it is found), and the
+ * tree follows the sequential rule over what is known, numbering children when
+ * their parent's turn comes; expansions the budget never reaches are discarded.
+ * The workspace holds histograms for those extra nodes (max_leaves/4, at least
+ * 32 and at most 4096 expansions).
  */
 GBT_API size_t gbt_grow_tree_lossguide_workspace_bytes(int64_t n, int32_t F, int32_t bits, int32_t max_bins,
                                                        int32_t max_leaves);

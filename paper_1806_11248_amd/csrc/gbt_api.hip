@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <new>
+#include <set>
 #include <vector>
 
 // ---------------------------------------------------------------- plumbing --
@@ -189,6 +190,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->sparse_jobs_per_cu = 1;
         if (const char *e12 = getenv("GBT_TUNE_SPARSE_JOBS")) { int v = atoi(e12); if (v >= 1 && v <= 64) c->sparse_jobs_per_cu = v; }
         if (const char *e13 = getenv("GBT_TUNE_SPARSE_TILED")) c->sparse_tiled = atoi(e13) != 0;
+        c->lossguide_batch = 16;
+        if (const char *e16 = getenv("GBT_TUNE_LOSSGUIDE_BATCH")) { int v = atoi(e16); if (v >= 1 && v <= 64) c->lossguide_batch = v; }
         c->part_nomove = 1;
         if (const char *e15 = getenv("GBT_TUNE_PART_NOMOVE")) c->part_nomove = atoi(e15) != 0;
         c->part_ids = 1;
@@ -631,6 +634,13 @@ struct UnmovedSplit {   // a split whose rows stayed in place
 };
 enum { GBT_POLICY_DEPTHWISE = 0, GBT_POLICY_LOSSGUIDE = 1 };
 constexpr int32_t kMaxLeaves = 1 << 20;
+// Loss-guided growth expands a few open leaves per round ahead of their turn (see grow_impl): nodes
+// created that way need histogram slots even if the leaf budget ends before they are reached.
+constexpr int kLossguideBatchMax = 32;
+int64_t lossguide_phys_nodes(int32_t max_leaves) {
+    const int64_t slack = std::min<int64_t>(std::max<int64_t>(max_leaves / 4, 32), 4096);   // expansions that may go unused
+    return 2 * (int64_t)max_leaves - 1 + 2 * slack;
+}
 
 }  // namespace
 
@@ -705,7 +715,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     GBT_REQUIRE(ctx, tree->feature && tree->bin && tree->default_left && tree->left && tree->right &&
                          tree->threshold && tree->weight && tree->gain && tree->sumG && tree->sumH && tree->n_rows,
                 GBT_EINVAL, "tree arrays must be allocated");
-    const GrowLayout L = lossguide ? grow_layout_nodes(n, F, bits, B, cap, 1) : grow_layout(n, F, bits, B, max_depth);
+    const int64_t cap_phys = lossguide ? lossguide_phys_nodes(max_leaves) : cap;
+    const GrowLayout L = lossguide ? grow_layout_nodes(n, F, bits, B, cap_phys, kLossguideBatchMax)
+                                   : grow_layout(n, F, bits, B, max_depth);
     GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
     HistPlan pl;
     GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
@@ -782,19 +794,20 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     int64_t root_sums[2];
     memcpy(root_sums, rb(ctx), 16);
 
-    auto set_node = [&](const HNode &nd) {
+    auto set_node_at = [&](int32_t at, const HNode &nd) {
         const double G = (double)nd.Gq * inv_sg, H = (double)nd.Hq * inv_sh;
-        tree->feature[nd.id] = -1;
-        tree->bin[nd.id] = 0;
-        tree->default_left[nd.id] = 0;
-        tree->left[nd.id] = tree->right[nd.id] = -1;
-        tree->threshold[nd.id] = INFINITY;
-        tree->gain[nd.id] = 0.0;
-        tree->sumG[nd.id] = G;
-        tree->sumH[nd.id] = H;
-        tree->weight[nd.id] = -G / (H + lambda);
-        tree->n_rows[nd.id] = nd.len;
+        tree->feature[at] = -1;
+        tree->bin[at] = 0;
+        tree->default_left[at] = 0;
+        tree->left[at] = tree->right[at] = -1;
+        tree->threshold[at] = INFINITY;
+        tree->gain[at] = 0.0;
+        tree->sumG[at] = G;
+        tree->sumH[at] = H;
+        tree->weight[at] = -G / (H + lambda);
+        tree->n_rows[at] = nd.len;
     };
+    auto set_node = [&](const HNode &nd) { set_node_at(nd.id, nd); };
 
     std::vector<HNode> level, next;   // the nodes created by the last round: to be evaluated
     std::vector<LeafSeg> leaves;
@@ -805,9 +818,33 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     else
         leaves.push_back(LeafSeg{0, 0, 2, (uint32_t)n});
     int32_t n_nodes = 1, n_leaves = 1;
-    // loss-guided: the leaves that may still be split, with their best splits
-    struct OpenLeaf { HNode nd; gbt_split sp; };
-    std::vector<OpenLeaf> open_leaves;
+    // Loss-guided growth.  The tree is defined by a strictly sequential rule (expand the open leaf with
+    // the largest gain, then look again), but a step per expansion leaves the chip idle between small
+    // launches.  So growth runs in two layers.  PHYSICAL nodes are created in rounds: the leaf whose turn it
+    // is plus a few more open leaves in gain order (they are likely to have their turn soon; a leaf's best
+    // split does not depend on when it is found).  A physical node's id is its slot in the histogram pool.
+    // The LOGICAL tree -- the caller's -- follows the sequential rule over what is known: it pops the best
+    // open leaf as long as that leaf has been expanded physically, numbering children at that moment, and
+    // asks for a round when it has not.  Expansions the budget never reaches are simply not part of the
+    // tree; leaf ids and row order come from the finished logical tree (walk + sort), never from where
+    // the rows physically ended up.
+    struct Phys {
+        HNode nd;
+        gbt_split sp;
+        int32_t lc, rc;        // physical children, -1: not expanded
+        int32_t logical;       // id in the caller's tree, -1: not (yet) part of it
+        bool open;             // has a split that may be taken
+    };
+    std::vector<Phys> phys;             // by physical id
+    struct OpenKey {   // order of turns: larger gain first, smaller logical id on equal gains
+        double gain;
+        int32_t logical, pid;
+        bool operator<(const OpenKey &o) const { return gain > o.gain || (gain == o.gain && logical < o.logical); }
+    };
+    std::set<OpenKey> sim_open;         // the logical tree's open leaves
+    int32_t n_logical = 1;
+    if (lossguide) phys.push_back(Phys{root, gbt_split{}, -1, -1, 0, false});
+    const int batch_max = std::max(1, std::min(ctx->lossguide_batch, kLossguideBatchMax));
     std::vector<UnmovedSplit> unmoved;
     std::vector<CountJob> cjobs;
     std::vector<uint32_t> nl_of;       // left rows of each node this round splits
@@ -840,7 +877,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         return GBT_OK;
     };
 
-    while (!level.empty() || !open_leaves.empty()) {
+    while (!level.empty() || !sim_open.empty()) {
         // ---- EvaluateSplit for every open node of the level (already enqueued, and waited for, by
         //      the level before when that ran the partition + histogram pass)
         if (!pre_eval && !level.empty()) {
@@ -869,32 +906,71 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             const HNode &nd = level[i];
             const bool ok = sp.valid && sp.gain > min_gain && sp.feature >= 0 && sp.feature < F &&
                             sp.bin >= 0 && sp.bin < B && nd.len > 0;
-            if (!ok) {
+            if (lossguide) {
+                Phys &ph = phys[(size_t)nd.id];
+                ph.sp = sp;
+                ph.open = ok;
+                if (ok && ph.logical >= 0) sim_open.insert(OpenKey{sp.gain, ph.logical, nd.id});   // the root
+            } else if (!ok) {
                 leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)nd.buf, nd.len});
-            } else if (lossguide) {
-                open_leaves.push_back(OpenLeaf{nd, sp});
             } else {
                 sel_nodes.push_back(nd);
                 sel_splits.push_back(sp);
             }
         }
         level.clear();
-        if (lossguide && n_leaves < max_leaves && !open_leaves.empty()) {
-            size_t best = 0;
-            for (size_t i = 1; i < open_leaves.size(); ++i)
-                if (open_leaves[i].sp.gain > open_leaves[best].sp.gain ||
-                    (open_leaves[i].sp.gain == open_leaves[best].sp.gain && open_leaves[i].nd.id < open_leaves[best].nd.id))
-                    best = i;
-            sel_nodes.push_back(open_leaves[best].nd);
-            sel_splits.push_back(open_leaves[best].sp);
-            open_leaves.erase(open_leaves.begin() + (std::ptrdiff_t)best);
+        if (lossguide) {
+            // the logical tree advances as far as the physical expansions reach
+            while (n_leaves < max_leaves && !sim_open.empty()) {
+                const int32_t pid = sim_open.begin()->pid;
+                Phys &ph = phys[(size_t)pid];
+                if (ph.lc < 0) break;   // its turn, but not expanded yet: a round is needed
+                sim_open.erase(sim_open.begin());
+                const int32_t at = ph.logical, lcl = n_logical, rcl = n_logical + 1;
+                GBT_REQUIRE(ctx, rcl < tree->capacity, GBT_EHIP, "internal: logical tree overflow");
+                n_logical += 2;
+                n_leaves += 1;
+                tree->feature[at] = ph.sp.feature;
+                tree->bin[at] = ph.sp.bin;
+                tree->default_left[at] = ph.sp.default_left;
+                tree->left[at] = lcl;
+                tree->right[at] = rcl;
+                tree->gain[at] = ph.sp.gain;
+                tree->threshold[at] =
+                    ph.sp.bin < B - 1 ? hcuts[(size_t)ph.sp.feature * (B - 1) + ph.sp.bin] : INFINITY;
+                for (int side = 0; side < 2; ++side) {
+                    const int32_t cid = side == 0 ? ph.lc : ph.rc;
+                    Phys &ch = phys[(size_t)cid];
+                    ch.logical = side == 0 ? lcl : rcl;
+                    set_node_at(ch.logical, ch.nd);
+                    if (ch.open) sim_open.insert(OpenKey{ch.sp.gain, ch.logical, cid});
+                }
+            }
+            if (n_leaves < max_leaves && !sim_open.empty()) {
+                // the leaf whose turn it is, and the next ones in gain order that live in the same working
+                // copy and agree with it on whether their children can still split; every expansion takes two
+                // physical slots, of which enough stay reserved for the expansions the budget still allows
+                const int64_t room = (cap_phys - n_nodes) / 2, budget = (int64_t)max_leaves - n_leaves;
+                const int64_t k_max = std::max<int64_t>(1, std::min<int64_t>({(int64_t)batch_max, budget, room - budget + 1}));
+                const HNode first = phys[(size_t)sim_open.begin()->pid].nd;
+                int looked = 0;
+                for (const OpenKey &key : sim_open) {
+                    if (++looked > 8 * kLossguideBatchMax) break;   // far down the order a leaf's turn is unlikely to come
+                    const Phys &ph = phys[(size_t)key.pid];
+                    if (ph.lc >= 0) continue;   // expanded ahead of its turn already
+                    if (ph.nd.buf != first.buf || (ph.nd.depth + 1 < max_depth) != (first.depth + 1 < max_depth)) continue;
+                    sel_nodes.push_back(ph.nd);
+                    sel_splits.push_back(ph.sp);
+                    if ((int64_t)sel_nodes.size() >= k_max) break;
+                }
+            }
         }
         if (sel_nodes.empty()) break;   // nothing splits any more: what is still open stays a leaf
         // all nodes of a round lie in the same buffer (a whole level, or a single node)
         const int wcur = sel_nodes[0].buf;
         const GbtRows &cur = wcur == 2 ? matrix : W[wcur];
         const int wnext = wcur == 0 ? 1 : 0;
-        const int child_depth = sel_nodes[0].depth + 1;
+        const int child_depth = sel_nodes[0].depth + 1;   // loss-guided: of the first node; the others agree on "< max_depth"
         const bool children_need_hist =
             child_depth < max_depth && (!lossguide || n_leaves + 1 < max_leaves);
         const bool unordered = path == 1 || path == 2;
@@ -1084,8 +1160,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             const gbt_split &sp = sel_splits[k];
             const uint32_t nl = nl_of[k];
             GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
-            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, child_depth, child_buf};
-            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, child_depth, child_buf};
+            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, nd.depth + 1, child_buf};
+            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, nd.depth + 1, child_buf};
             if (nomove) {
                 lc.virt = 2 * (int32_t)unmoved.size();
                 rc.virt = lc.virt + 1;
@@ -1093,16 +1169,24 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                                (uint32_t)sp.default_left});
             }
             n_nodes += 2;
-            n_leaves += 1;
-            tree->feature[nd.id] = sp.feature;
-            tree->bin[nd.id] = sp.bin;
-            tree->default_left[nd.id] = sp.default_left;
-            tree->left[nd.id] = lc.id;
-            tree->right[nd.id] = rc.id;
-            tree->gain[nd.id] = sp.gain;
-            tree->threshold[nd.id] = sp.bin < B - 1 ? hcuts[(size_t)sp.feature * (B - 1) + sp.bin] : INFINITY;
-            set_node(lc);
-            set_node(rc);
+            if (lossguide) {   // physical children; the caller's tree learns of them when their parent is popped
+                GBT_REQUIRE(ctx, n_nodes <= cap_phys, GBT_EHIP, "internal: physical node overflow");
+                phys[(size_t)nd.id].lc = lc.id;
+                phys[(size_t)nd.id].rc = rc.id;
+                phys.push_back(Phys{lc, gbt_split{}, -1, -1, -1, false});
+                phys.push_back(Phys{rc, gbt_split{}, -1, -1, -1, false});
+            } else {
+                n_leaves += 1;
+                tree->feature[nd.id] = sp.feature;
+                tree->bin[nd.id] = sp.bin;
+                tree->default_left[nd.id] = sp.default_left;
+                tree->left[nd.id] = lc.id;
+                tree->right[nd.id] = rc.id;
+                tree->gain[nd.id] = sp.gain;
+                tree->threshold[nd.id] = sp.bin < B - 1 ? hcuts[(size_t)sp.feature * (B - 1) + sp.bin] : INFINITY;
+                set_node(lc);
+                set_node(rc);
+            }
             if (children_need_hist) {
                 // the child whose histogram is built from rows: the one the partition pass has already
                 // built, else the one with fewer rows; its sibling comes by subtraction
@@ -1159,10 +1243,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     }
     // whatever is still waiting when nothing splits any more is a leaf
     for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)nd.buf, nd.len});
-    for (const OpenLeaf &ol : open_leaves)
-        leaves.push_back(LeafSeg{ol.nd.begin, (uint32_t)ol.nd.id, (uint32_t)ol.nd.buf, ol.nd.len});
-    if (!tracked || path == 1 || path == 2) {
-        tree->n_nodes = n_nodes;
+    const int32_t n_tree = lossguide ? n_logical : n_nodes;   // nodes of the caller's tree
+    if (!tracked || path == 1 || path == 2 || lossguide) {
+        tree->n_nodes = n_tree;
         // the rows were not followed: one walk of the finished tree over the matrix names each row's leaf
         int32_t *leaf_ids = leaf_of_row_out ? leaf_of_row_out : (int32_t *)W[0].id_rw;
         if (leaf_of_row_out || tracked) {
@@ -1175,7 +1258,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         if (tracked) {
             // ... and the stable partitions' final id list is the rows sorted by their leaf's place in
             // the tree's left-to-right order, ids ascending inside a leaf
-            std::vector<uint32_t> rank((size_t)n_nodes, 0u);
+            std::vector<uint32_t> rank((size_t)n_tree, 0u);
             std::vector<int32_t> stack{0};
             uint32_t n_ranks = 0;
             while (!stack.empty()) {
@@ -1196,7 +1279,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             uint32_t *key_tmp[2] = {W[1].id_rw, (uint32_t *)(ws + L.wgq[0]) + n};
             uint32_t *val_tmp[2] = {(uint32_t *)(ws + L.wgq[0]), (uint32_t *)(ws + L.wgq[1])};
             gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
-            GBT_HIP(ctx, gbt_launch_order_rows(s, leaf_ids, (const uint32_t *)(ws + L.rank_tbl), (uint32_t)n_nodes,
+            GBT_HIP(ctx, gbt_launch_order_rows(s, leaf_ids, (const uint32_t *)(ws + L.rank_tbl), (uint32_t)n_tree,
                                                n_ranks, n, key_tmp, val_tmp, ws + L.order, row_idx_out));
             gbt_prof_end(ctx);
         }
@@ -1231,7 +1314,7 @@ extern "C" size_t gbt_grow_tree_lossguide_workspace_bytes(int64_t n, int32_t F, 
                                                           int32_t max_leaves) {
     if (n < 0 || F < 1 || bits < 1 || bits > GBT_MAX_BITS || max_bins < 2 || max_leaves < 1 || max_leaves > kMaxLeaves)
         return 0;
-    return grow_layout_nodes(n, F, bits, max_bins, 2 * (int64_t)max_leaves - 1, 1).total;
+    return grow_layout_nodes(n, F, bits, max_bins, lossguide_phys_nodes(max_leaves), kLossguideBatchMax).total;
 }
 
 extern "C" int32_t gbt_grow_tree_lossguide(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
@@ -1690,19 +1773,20 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
     int64_t root_sums[2];
     memcpy(root_sums, rb(ctx), 16);
 
-    auto set_node = [&](const HNode &nd) {
+    auto set_node_at = [&](int32_t at, const HNode &nd) {
         const double G = (double)nd.Gq * inv_sg, H = (double)nd.Hq * inv_sh;
-        tree->feature[nd.id] = -1;
-        tree->bin[nd.id] = 0;
-        tree->default_left[nd.id] = 0;
-        tree->left[nd.id] = tree->right[nd.id] = -1;
-        tree->threshold[nd.id] = INFINITY;
-        tree->gain[nd.id] = 0.0;
-        tree->sumG[nd.id] = G;
-        tree->sumH[nd.id] = H;
-        tree->weight[nd.id] = -G / (H + lambda);
-        tree->n_rows[nd.id] = nd.len;
+        tree->feature[at] = -1;
+        tree->bin[at] = 0;
+        tree->default_left[at] = 0;
+        tree->left[at] = tree->right[at] = -1;
+        tree->threshold[at] = INFINITY;
+        tree->gain[at] = 0.0;
+        tree->sumG[at] = G;
+        tree->sumH[at] = H;
+        tree->weight[at] = -G / (H + lambda);
+        tree->n_rows[at] = nd.len;
     };
+    auto set_node = [&](const HNode &nd) { set_node_at(nd.id, nd); };
     std::vector<HNode> level, next, sel_nodes;
     std::vector<gbt_split> splits, sel_splits;
     std::vector<EvalNode> enodes;

@@ -26,6 +26,7 @@ struct gbt_ctx {
     int hist_block;         // threads per histogram workgroup
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
     int part_fused;         // 1: one-launch record partition where it applies
+    int lossguide_batch;    // open leaves a round of loss-guided growth expands at once (1: only the one whose turn it is)
     int part_nomove;        // 1: the last histogram level of a depth-wise tree is built without moving rows (partition + histogram pass)
     int part_ids;           // 1: rows wider than 64 words are not moved: id lists are partitioned and the histogram kernel gathers
     int order_rows;         // 1: a caller's row order is made from the finished tree, so that it does not restrict the partition form

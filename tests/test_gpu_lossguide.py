@@ -109,3 +109,32 @@ def test_lossguide_argument_errors(ctx):
     rc = ctx.lib.gbt_grow_tree_lossguide(ctx.h, _ptr(packed), bits, n, F, ms, _ptr(nb), _ptr(cuts), _ptr(gp),
                                          C.byref(params), 8, C.byref(_tree_struct(t)), None, None, _ptr(ws), ws.numel())
     assert rc == g.binding.EINVAL
+
+
+def test_rounds_of_several_leaves_keep_the_sequential_rule(oracle, monkeypatch):
+    """Several open leaves are expanded per round ahead of their turn; with one expansion per round the
+    library follows the rule step by step.  Both must give the same tree, node numbers included, also
+    when the depth cap stops some of a round's leaves and when the budget ends inside a round."""
+    import paper_1806_11248_amd as g
+    d = synth.make(4, 150_000)
+    n, F = d["X"].shape
+    ctxs = []
+    for batch in (1, 16, 32):
+        monkeypatch.setenv("GBT_TUNE_LOSSGUIDE_BATCH", str(batch))
+        ctxs.append(g.Context(0))
+    o, gdev = gpu_prep(ctxs[1], oracle, d)
+    gp = dev(oracle.gradients("logistic", np.zeros(n, np.float32), d["y"]))
+    for max_leaves, depth in ((37, 64), (100, 5), (3, 64), (200, 9)):
+        params = g.make_params(max_depth=depth, max_bins=d["params"]["max_bins"])
+        print(f"lossguide batches, {max_leaves} leaves, depth cap {depth}", flush=True)
+        got = [c.grow_tree_lossguide(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"], gdev["cuts"], gp,
+                                     params, max_leaves) for c in ctxs]
+        nn = got[0][0]["n_nodes"]
+        for t, rows, leaf in got[1:]:
+            assert t["n_nodes"] == nn
+            for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
+                      "sumG", "sumH"):
+                assert np.array_equal(t[k][:nn], got[0][0][k][:nn]), k
+            assert torch.equal(rows, got[0][1]) and torch.equal(leaf, got[0][2])
+    for c in ctxs:
+        c.close()
