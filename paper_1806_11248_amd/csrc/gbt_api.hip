@@ -448,12 +448,13 @@ extern "C" int32_t gbt_eval_split(gbt_ctx *ctx, const int64_t *hist, const int32
     nd.hist_off = 0;
     nd.Gq = Gq;
     nd.Hq = Hq;
+    nd.parent_off = nd.built_off = GBT_NO_HIST;
     char *ws = (char *)workspace;
     st = upload(ctx, &nd, sizeof nd, ws);
     if (st != GBT_OK) return st;
     gbt_split *dsplit = (gbt_split *)(ws + 256);
     const int chunks = gbt_eval_chunks(F, 1, workspace_bytes - 256);
-    GBT_HIP(ctx, gbt_launch_eval(ctx->stream, hist, (const EvalNode *)ws, 1, nb, F, B, chunks, 1.0 / scale[0],
+    GBT_HIP(ctx, gbt_launch_eval(ctx->stream, const_cast<int64_t *>(hist), (const EvalNode *)ws, 1, nb, F, B, chunks, 1.0 / scale[0],
                                  1.0 / scale[1], params->lambda, params->min_child_weight, dsplit));
     GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), dsplit, chunks * sizeof(gbt_split), hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
@@ -626,6 +627,8 @@ struct HNode {
     // >= 0: the rows were not moved at the parent's split: they lie interleaved with the sibling's in the
     // parent's segment; 2 * (index of the parent's record in the table of such splits) + (1 for the right child)
     int32_t virt = -1;
+    // >= 0: the node's histogram is still to be made as parent - built (pool slots) when it is evaluated
+    int32_t sub_parent = -1, sub_built = -1;
 };
 struct UnmovedSplit {   // a split whose rows stayed in place
     uint32_t begin, len;   // the parent's segment
@@ -854,7 +857,6 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     std::vector<EvalNode> enodes;
     std::vector<PartJob> pjobs;
     std::vector<HistJob> hjobs;
-    std::vector<SubJob> sjobs;
     std::vector<gbt_split> splits;
 
     // Split records come back in the read-back half of the staging behind the partition's row counts.
@@ -883,7 +885,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         if (!pre_eval && !level.empty()) {
             enodes.resize(level.size());
             for (size_t i = 0; i < level.size(); ++i)
-                enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
+                enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq,
+                                     level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_parent * (uint64_t)hist_len : GBT_NO_HIST,
+                                     level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_built * (uint64_t)hist_len : GBT_NO_HIST};
             st = enqueue_eval(enodes, &chunks);
             if (st != GBT_OK) return st;
             GBT_SYNC(ctx);
@@ -1095,26 +1099,22 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
                 gbt_prof_end(ctx);
                 // Everything the children's evaluation needs is known before the rows are counted (ids,
-                // sums, which child was built): enqueue the subtraction and the evaluation behind the
-                // pass, so that the host waits once per level instead of twice.
-                sjobs.clear();
+                // sums, which child was built): enqueue the evaluation (which makes the other child's
+                // histogram by subtraction on the way) behind the pass, so that the host waits once per
+                // level instead of twice.
                 enodes.clear();
                 for (size_t k = 0; k < pjobs.size(); ++k) {
                     const HNode &nd = sel_nodes[k];
                     const gbt_split &sp = sel_splits[k];
                     const int64_t lid = n_nodes + 2 * (int64_t)k, rid = lid + 1;
-                    const int64_t built = pjobs[k].pad == 1u ? lid : rid, other = pjobs[k].pad == 1u ? rid : lid;
-                    sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)built * (uint64_t)hist_len,
-                                           (uint64_t)other * (uint64_t)hist_len});
-                    enodes.push_back(EvalNode{(uint64_t)lid * (uint64_t)hist_len, sp.GLq, sp.HLq});
-                    enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq});
+                    const bool left_built = pjobs[k].pad == 1u;
+                    const uint64_t par = (uint64_t)nd.id * (uint64_t)hist_len;
+                    const uint64_t blt = (uint64_t)(left_built ? lid : rid) * (uint64_t)hist_len;
+                    enodes.push_back(EvalNode{(uint64_t)lid * (uint64_t)hist_len, sp.GLq, sp.HLq,
+                                              left_built ? GBT_NO_HIST : par, left_built ? GBT_NO_HIST : blt});
+                    enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq,
+                                              left_built ? par : GBT_NO_HIST, left_built ? blt : GBT_NO_HIST});
                 }
-                GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
-                st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
-                if (st != GBT_OK) return st;
-                gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
-                GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
-                gbt_prof_end(ctx);
                 st = enqueue_eval(enodes, &chunks);
                 if (st != GBT_OK) return st;
                 pre_eval = true;
@@ -1150,7 +1150,6 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
 
         // ---- children, in creation order
         hjobs.clear();
-        sjobs.clear();
         int64_t built_rows = 0;
         struct Built { uint64_t off; uint32_t begin, len; };
         std::vector<Built> built;
@@ -1191,11 +1190,12 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 // the child whose histogram is built from rows: the one the partition pass has already
                 // built, else the one with fewer rows; its sibling comes by subtraction
                 const bool left_small = with_hist ? pjobs[k].pad == 1u : lc.len <= rc.len;
-                const HNode &sm = left_small ? lc : rc, &lg = left_small ? rc : lc;
+                const HNode &sm = left_small ? lc : rc;
                 built.push_back(Built{(uint64_t)sm.id * (uint64_t)hist_len, sm.begin, sm.len});
                 built_rows += sm.len;
-                sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)sm.id * (uint64_t)hist_len,
-                                       (uint64_t)lg.id * (uint64_t)hist_len});
+                HNode &other = left_small ? rc : lc;   // its histogram: parent - built, made when it is evaluated
+                other.sub_parent = nd.id;
+                other.sub_built = sm.id;
                 next.push_back(lc);
                 next.push_back(rc);
             } else {
@@ -1230,14 +1230,6 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                                  (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
                 gbt_prof_end(ctx);
             }
-        }
-        if (children_need_hist && !with_hist) {   // ---- siblings by subtraction (with_hist: already enqueued)
-            GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
-            st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
-            if (st != GBT_OK) return st;
-            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
-            GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
-            gbt_prof_end(ctx);
         }
         level.swap(next);
     }
@@ -1791,7 +1783,6 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
     std::vector<gbt_split> splits, sel_splits;
     std::vector<EvalNode> enodes;
     std::vector<PartJob> pjobs;
-    std::vector<SubJob> sjobs;
     HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1], 0, 2};
     set_node(root);
     if (max_depth > 0) level.push_back(root);
@@ -1802,7 +1793,9 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         // ---- EvaluateSplit for the level's nodes
         enodes.resize(level.size());
         for (size_t i = 0; i < level.size(); ++i)
-            enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq};
+            enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq,
+                                 level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_parent * (uint64_t)hist_len : GBT_NO_HIST,
+                                 level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_built * (uint64_t)hist_len : GBT_NO_HIST};
         st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
         if (st != GBT_OK) return st;
         const size_t budget = GBT_STAGING_BYTES - kReadbackOff - kSplitRb;
@@ -1868,7 +1861,6 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
 
         // ---- children, in creation order; the child with fewer rows is built from rows
         hjobs.clear();
-        sjobs.clear();
         next.clear();
         int64_t built_rows = 0;
         const int32_t first_child = n_nodes;
@@ -1894,11 +1886,12 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
             set_node(rc);
             if (children_need_hist) {
                 const bool left_small = lc.len <= rc.len;
-                const HNode &sm = left_small ? lc : rc, &lg = left_small ? rc : lc;
+                const HNode &sm = left_small ? lc : rc;
                 built.push_back(Built{(uint64_t)sm.id * (uint64_t)hist_len, sm.begin, sm.len});
                 built_rows += sm.len;
-                sjobs.push_back(SubJob{(uint64_t)nd.id * (uint64_t)hist_len, (uint64_t)sm.id * (uint64_t)hist_len,
-                                       (uint64_t)lg.id * (uint64_t)hist_len});
+                HNode &other = left_small ? rc : lc;   // its histogram: parent - built, made when it is evaluated
+                other.sub_parent = nd.id;
+                other.sub_built = sm.id;
                 next.push_back(lc);
                 next.push_back(rc);
             }
@@ -1913,12 +1906,6 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
             for (const Built &b : built) add_sparse_hist_jobs(hjobs, b.off, b.begin, b.len, bins, glen, rpj);
             st = launch_hist(rows_of(wnext), GBT_PROF_HIST_NODE, (double)built_rows * row_bytes);
             if (st != GBT_OK) return st;
-            GBT_REQUIRE(ctx, sjobs.size() * sizeof(SubJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
-            st = upload(ctx, sjobs.data(), sjobs.size() * sizeof(SubJob), ws + L.jobs);
-            if (st != GBT_OK) return st;
-            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)sjobs.size() * (double)hist_len * 24.0);
-            GBT_HIP(ctx, gbt_launch_subtract(s, pool, (const SubJob *)(ws + L.jobs), (int)sjobs.size(), hist_len));
-            gbt_prof_end(ctx);
         }
         level.swap(next);
     }

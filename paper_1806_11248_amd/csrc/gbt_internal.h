@@ -83,7 +83,12 @@ struct HistJob {
 struct EvalNode {
     uint64_t hist_off;
     int64_t Gq, Hq;
+    // sibling subtraction folded into the evaluation: when parent_off != GBT_NO_HIST the node's histogram
+    // does not exist yet; the kernel makes it as parent - built (int64 units, like hist_off), stores it
+    // at hist_off and evaluates it in the same pass
+    uint64_t parent_off, built_off;
 };
+#define GBT_NO_HIST (~0ull)
 
 // One segment for the partition kernels.
 struct PartJob {
@@ -107,10 +112,6 @@ struct CountJob {
     uint32_t pad;
 };
 
-// One "out = parent - child" for the subtraction kernel (int64 units).
-struct SubJob {
-    uint64_t parent_off, child_off, out_off;
-};
 
 // One leaf segment for the final gather.
 struct LeafSeg {
@@ -134,8 +135,6 @@ hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *r
                              int64_t *out2 /* zeroed by the launcher */);
 hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margin, const float *label,
                                 int64_t n, float *gpair);
-hipError_t gbt_launch_subtract(hipStream_t s, int64_t *pool, const SubJob *jobs, int n_jobs,
-                               int64_t count);
 hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const int64_t *child,
                                    int64_t *out, int64_t count);
 hipError_t gbt_launch_export(hipStream_t s, const int64_t *hist, int64_t count, double inv_sg,
@@ -152,7 +151,7 @@ int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B);
 
 // out receives n_nodes * n_chunks records (node-major); gbt_eval_chunks picks n_chunks.
 int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes);
-hipError_t gbt_launch_eval(hipStream_t s, const int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
+hipError_t gbt_launch_eval(hipStream_t s, int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
                            const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
                            double lambda, double mcw, gbt_split *out);
 

@@ -226,14 +226,6 @@ __global__ void gradients_kernel(int objective, const float *margin, const float
     }
 }
 
-__global__ void subtract_jobs_kernel(int64_t *pool, const SubJob *jobs, int64_t count) {
-    SubJob j = jobs[blockIdx.y];
-    const int64_t *p = pool + j.parent_off, *c = pool + j.child_off;
-    int64_t *o = pool + j.out_off;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
-         i += (int64_t)gridDim.x * blockDim.x)
-        o[i] = p[i] - c[i];
-}
 
 __global__ void subtract_one_kernel(const int64_t *p, const int64_t *c, int64_t *o, int64_t count) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
@@ -617,16 +609,6 @@ hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margi
     if (n <= 0) return hipSuccess;
     gradients_kernel<<<grid_for(n, kBlock * 2, 8192), kBlock, 0, s>>>(objective, margin, label, n,
                                                                       (float2 *)gpair);
-    return hipGetLastError();
-}
-hipError_t gbt_launch_subtract(hipStream_t s, int64_t *pool, const SubJob *jobs, int n_jobs,
-                               int64_t count) {
-    if (n_jobs <= 0 || count <= 0) return hipSuccess;
-    for (int j0 = 0; j0 < n_jobs; j0 += 65535) {   // grid.y limit
-        int nj = n_jobs - j0 < 65535 ? n_jobs - j0 : 65535;
-        dim3 grid(grid_for(count, kBlock * 4, 256), nj);
-        subtract_jobs_kernel<<<grid, kBlock, 0, s>>>(pool, jobs + j0, count);
-    }
     return hipGetLastError();
 }
 hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const int64_t *child,

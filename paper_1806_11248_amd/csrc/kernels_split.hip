@@ -53,13 +53,16 @@ __device__ inline bool better(double ga, uint32_t ka, double gb, uint32_t kb) {
 }
 
 __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
-    const int64_t *__restrict__ pool, const EvalNode *__restrict__ nodes, const int32_t *__restrict__ nb,
+    int64_t *__restrict__ pool, const EvalNode *__restrict__ nodes, const int32_t *__restrict__ nb,
     int F, int B, int f_per_chunk, double inv_sg, double inv_sh, double lambda, double mcw,
     gbt_split *__restrict__ out) {
     const EvalNode nd = nodes[blockIdx.x];
     const int f_begin = blockIdx.y * f_per_chunk;
     const int f_end = f_begin + f_per_chunk < F ? f_begin + f_per_chunk : F;
-    const int64_t *hist = pool + nd.hist_off;
+    int64_t *hist = pool + nd.hist_off;
+    // the larger sibling: its histogram is made here, as parent - built (exact: integers), and kept
+    const bool subtract = nd.parent_off != GBT_NO_HIST;
+    const int64_t *hpar = pool + (subtract ? nd.parent_off : 0), *hblt = pool + (subtract ? nd.built_off : 0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t Gq = nd.Gq, Hq = nd.Hq;
     const double G = (double)Gq * inv_sg, H = (double)Hq * inv_sh;
@@ -74,12 +77,23 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     for (int f = f_begin + wave; f < f_end; f += kEvalWaves) {
         int nbf = nb[f];
         if (nbf > B) nbf = B;
-        const int64_t *hf = hist + (int64_t)f * B * 2;
+        int64_t *hf = hist + (int64_t)f * B * 2;
         // pass 1: the feature's present mass -> the node's missing mass
         int64_t sg = 0, sh = 0;
-        for (int b = lane; b < nbf; b += 64) {
-            sg += hf[2 * b];
-            sh += hf[2 * b + 1];
+        if (subtract) {   // (the lane that stores bin b is the lane that reads it again in pass 2)
+            const int64_t *pf = hpar + (int64_t)f * B * 2, *bf = hblt + (int64_t)f * B * 2;
+            for (int b = lane; b < nbf; b += 64) {
+                const int64_t g = pf[2 * b] - bf[2 * b], h = pf[2 * b + 1] - bf[2 * b + 1];
+                hf[2 * b] = g;
+                hf[2 * b + 1] = h;
+                sg += g;
+                sh += h;
+            }
+        } else {
+            for (int b = lane; b < nbf; b += 64) {
+                sg += hf[2 * b];
+                sh += hf[2 * b + 1];
+            }
         }
         for (int o = 32; o > 0; o >>= 1) {
             sg += shfl_xor_i64(sg, o);
@@ -180,7 +194,7 @@ int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes) {
     return chunks < 1 ? 1 : chunks;
 }
 
-hipError_t gbt_launch_eval(hipStream_t s, const int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
+hipError_t gbt_launch_eval(hipStream_t s, int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
                            const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
                            double lambda, double mcw, gbt_split *out) {
     if (n_nodes <= 0) return hipSuccess;
