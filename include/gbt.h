@@ -388,11 +388,11 @@ GBT_API int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t 
 
 /* Kernel classes timed by the optional profiler. */
 #define GBT_PROF_HIST_ROOT 0 /* histogram of all rows (no row-id list) */
-#define GBT_PROF_HIST_NODE 1 /* histogram of listed rows (levels >= 1) */
-#define GBT_PROF_PARTITION 2 /* flag + scan + scatter */
-#define GBT_PROF_EVAL 3      /* split evaluation */
-#define GBT_PROF_SUBTRACT 4  /* histogram zero-fill and sibling subtraction */
-#define GBT_PROF_OTHER 5     /* fixed-point conversion, totals, row-id init, leaf gather */
+#define GBT_PROF_HIST_NODE 1 /* histograms of levels >= 1 (the partition + histogram pass where that runs) */
+#define GBT_PROF_PARTITION 2 /* moving or counting rows without a histogram */
+#define GBT_PROF_EVAL 3      /* split evaluation, sibling subtraction included */
+#define GBT_PROF_CLEAR 4     /* zero-fill of the children's histograms */
+#define GBT_PROF_OTHER 5     /* scale search, fixed-point conversion, tree walks (leaf ids, prediction), row order */
 #define GBT_PROF_CLASSES 6
 
 typedef struct gbt_profile {

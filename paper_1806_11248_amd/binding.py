@@ -32,7 +32,7 @@ SYMBOLS = [
     "gbt_build_hist_sparse", "gbt_grow_tree_sparse_workspace_bytes", "gbt_grow_tree_sparse", "gbt_predict_sparse",
 ]
 
-PROF_CLASSES = ["hist_root", "hist_node", "partition", "eval", "subtract", "other"]
+PROF_CLASSES = ["hist_root", "hist_node", "partition", "eval", "clear", "other"]
 
 
 class GbtError(RuntimeError):

@@ -1076,7 +1076,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             if (st != GBT_OK) return st;
             if (with_hist) {   // the children's histograms are accumulated into: clear them first
                 const int64_t n_children = 2 * (int64_t)pjobs.size();
-                gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
+                gbt_prof_begin(ctx, GBT_PROF_CLEAR, (double)n_children * (double)hist_len * 8.0);
                 GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)n_nodes * hist_len), 0,
                                                  n_children * hist_len));
                 gbt_prof_end(ctx);
@@ -1207,7 +1207,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             // ---- BuildPartialHistograms for the smaller children (their rows are now one
             //      contiguous run of the working copy)
             const int32_t n_children = n_nodes - first_child;
-            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
+            gbt_prof_begin(ctx, GBT_PROF_CLEAR, (double)n_children * (double)hist_len * 8.0);
             GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
                                              (int64_t)n_children * hist_len));
             gbt_prof_end(ctx);
@@ -1898,7 +1898,7 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         }
         if (children_need_hist) {
             const int32_t n_children = n_nodes - first_child;
-            gbt_prof_begin(ctx, GBT_PROF_SUBTRACT, (double)n_children * (double)hist_len * 8.0);
+            gbt_prof_begin(ctx, GBT_PROF_CLEAR, (double)n_children * (double)hist_len * 8.0);
             GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
                                              (int64_t)n_children * hist_len));
             gbt_prof_end(ctx);

@@ -123,3 +123,54 @@ def test_random_small_trees(ctx, oracle, seed, n, F, B, miss, depth, lam, gamma,
     print(f"random tree seed={seed} n={n} F={F} B={B} miss={miss} depth={depth} lam={lam} gamma={gamma} mcw={mcw} ties={ties}",
           flush=True)
     _grow_and_judge(ctx, oracle, X, gp, dict(max_depth=depth, max_bins=B, lam=lam, gamma=gamma, min_child_weight=mcw))
+
+
+@settings(max_examples=25, deadline=None, suppress_health_check=list(HealthCheck), derandomize=True)
+@given(seed=st.integers(0, 2 ** 31 - 1), n=st.integers(1, 6000), F=st.integers(1, 40),
+       B=st.sampled_from([2, 7, 32, 256, 1000]), miss=st.sampled_from([0.0, 0.5, 0.9, 1.0]),
+       depth=st.integers(0, 9), max_leaves=st.integers(1, 60), ties=st.booleans())
+def test_random_sparse_rows_and_lossguide(ctx, oracle, seed, n, F, B, miss, depth, max_leaves, ties):
+    """Random small shapes through the other two growth entry points: the sparse-row form must give
+    the packed form's tree, row order and leaves bit for bit (the packed form is judged above), and
+    loss-guided growth in rounds must pass the oracle's replay of the sequential rule."""
+    import paper_1806_11248_amd as g
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    if ties:
+        X = np.round(X * 2) / 2
+    if miss:
+        X[rng.random((n, F)) < miss] = np.nan
+    gv = rng.standard_normal(n) * rng.choice([1e-2, 1.0, 20.0])
+    hv = rng.random(n) + 1e-3
+    if ties:
+        gv, hv = np.sign(gv) * 0.5, np.full(n, 0.25)
+    gp = np.stack([gv, hv], 1).astype(np.float32)
+    print(f"random sparse/lossguide seed={seed} n={n} F={F} B={B} miss={miss} depth={depth} leaves={max_leaves} ties={ties}",
+          flush=True)
+    p = dict(max_depth=depth, max_bins=B, lam=1.0, gamma=0.0, min_child_weight=1.0)
+    o = oracle_prep(oracle, X, B)
+    cuts, nb, sym, mv, ms = ctx.quantise(dev(X), max_bins=B)
+    packed, bits = ctx.compress(sym, mv)
+    params = g.make_params(max_depth=depth, max_bins=B, lam=1.0, gamma=0.0, min_child_weight=1.0)
+    gp_t = dev(gp)
+    tree, row_idx, leaf = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_t, params)
+    nn = tree["n_nodes"]
+    if F * B <= 65536:
+        rowptr, ent, nnz = ctx.compress_sparse(sym, B, ms)
+        assert nnz == int((o["sym"] != o["missing"]).sum())
+        st_, srows, sleaf = ctx.grow_tree_sparse(rowptr, ent, n, nnz, F, nb, cuts, gp_t, params)
+        assert st_["n_nodes"] == nn
+        for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
+                  "sumG", "sumH"):
+            assert np.array_equal(st_[k][:nn], tree[k][:nn]), k
+        assert torch.equal(srows, row_idx) and torch.equal(sleaf, leaf)
+        m = ctx.predict_sparse([tree], dev(np.zeros(n, np.float32)), 0.5, rowptr, ent, n, F, B)
+        m2 = ctx.predict([tree], dev(np.zeros(n, np.float32)), 0.5, packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
+        assert torch.equal(m, m2)
+    lg, lrows, lleaf = ctx.grow_tree_lossguide(packed, bits, n, F, ms, nb, cuts, gp_t, params, max_leaves)
+    _, scale = ctx.gpair_fixed(gp_t)
+    rep = oracle.replay_tree_lossguide(lg, o["sym"], o["nb"], o["missing"], gp, max_leaves=max_leaves, **tree_kw(p),
+                                       sum_atol_per_row=0.5 / min(scale))
+    assert rep["ok"], rep["errors"][:5]
+    assert np.array_equal(host_u32(lrows), rep["row_idx"])
+    assert np.array_equal(lleaf.cpu().numpy(), rep["leaf_of_row"])
