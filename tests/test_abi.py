@@ -38,6 +38,14 @@ def test_host_only_calls(lib):
     assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 4, 16, 3) > 1000 * 16
     assert lib.gbt_grow_tree_workspace_bytes(1000, 8, 4, 16, 99) == 0     # unsupported depth
     assert lib.gbt_partition_workspace_bytes(10_000) >= 40_000
+    # sparse rows: an even number of entries plus the slack that word-wise readers may touch
+    assert lib.gbt_sparse_capacity(0) == 32 and lib.gbt_sparse_capacity(5) == 38 and lib.gbt_sparse_capacity(-1) == 0
+    assert lib.gbt_grow_tree_sparse_workspace_bytes(1000, 5000, 50, 256, 8) > 2 * 5000 * 2
+    assert lib.gbt_grow_tree_sparse_workspace_bytes(1000, 5000, 300, 256, 8) == 0   # 76,800 global bin ids
+    # loss-guided growth keeps histograms for the nodes it expands ahead of their turn
+    assert (lib.gbt_grow_tree_lossguide_workspace_bytes(1000, 8, 4, 16, 64)
+            > lib.gbt_grow_tree_workspace_bytes(1000, 8, 4, 16, 6))
+    assert lib.gbt_grow_tree_lossguide_workspace_bytes(1000, 8, 4, 16, 0) == 0
     # a null context is refused, not dereferenced
     assert lib.gbt_destroy(None) == g.binding.EINVAL
     assert lib.gbt_gradients(None, 0, None, None, 0, None) == g.binding.EINVAL
