@@ -174,3 +174,34 @@ def test_random_sparse_rows_and_lossguide(ctx, oracle, seed, n, F, B, miss, dept
     assert rep["ok"], rep["errors"][:5]
     assert np.array_equal(host_u32(lrows), rep["row_idx"])
     assert np.array_equal(lleaf.cpu().numpy(), rep["leaf_of_row"])
+
+
+@settings(max_examples=15, deadline=None, suppress_health_check=list(HealthCheck), derandomize=True)
+@given(seed=st.integers(0, 2 ** 31 - 1), n=st.integers(5_000, 250_000), F=st.integers(1, 40),
+       B=st.sampled_from([16, 64, 255, 256]), miss=st.sampled_from([0.0, 0.0, 0.2]), depth=st.integers(1, 9),
+       skew=st.booleans())
+def test_random_medium_trees(ctx, oracle, seed, n, F, B, miss, depth, skew):
+    """Shapes of a few tiles to a few dozen tiles through whichever growth path their width selects
+    (fused partition + histogram up to 16 byte-wide features, one-launch partition, id lists), with and
+    without the final row order, against the oracle's replay."""
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    if skew:   # low-cardinality columns with one dominant value, like categorical data
+        k = max(1, F // 2)
+        X[:, :k] = np.floor(np.abs(X[:, :k]) * 1.5)
+    if miss:
+        X[rng.random((n, F)) < miss] = np.nan
+    y = (X[:, 0] > 0).astype(np.float64) + 0.3 * rng.standard_normal(n)
+    gp = np.stack([rng.standard_normal(n) * 0.1 - np.nan_to_num(y), rng.random(n) * 0.5 + 0.5], 1).astype(np.float32)
+    print(f"random medium tree seed={seed} n={n} F={F} B={B} miss={miss} depth={depth} skew={skew}", flush=True)
+    import paper_1806_11248_amd as g
+    p = dict(max_depth=depth, max_bins=B, lam=1.0, gamma=0.0, min_child_weight=1.0)
+    tree, o, gdev = _grow_and_judge(ctx, oracle, X, gp, p)
+    params = g.make_params(max_depth=depth, max_bins=B, lam=1.0, gamma=0.0, min_child_weight=1.0)
+    cuts, nb, sym, mv, ms = ctx.quantise(dev(X), max_bins=B)
+    bare, _, _ = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, ms, nb, cuts, dev(gp), params, want_rows=False,
+                               want_leaf=False)
+    nn = tree["n_nodes"]
+    assert bare["n_nodes"] == nn
+    for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "weight", "gain"):
+        assert np.array_equal(bare[k][:nn], tree[k][:nn]), k
