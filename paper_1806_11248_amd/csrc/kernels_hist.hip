@@ -425,8 +425,9 @@ __global__ __launch_bounds__(kHistBlock) void hist_static_kernel(
 // [ h : 24 bits | g : 28 bits, two's complement ] (|g| <= 2^26, 0 <= h <= 2^22).
 // 13 features: 20 bytes instead of a 16-byte padded row plus an 8-byte pair.  The
 // pair always sits in bytes 1..3 of word RW-2 and in word RW-1.
-// FIRST: the source is the caller's packed matrix (rows of `ft` bytes at any byte
-// alignment) with the pairs in their own array; otherwise records.
+// part_hist_first_kernel (level 0): the source is the caller's packed matrix (rows of
+// `ft` bytes at any byte alignment) with the pairs in their own array;
+// part_hist_kernel (every later level): records.
 //
 // PartJob: tile_begin / n_tiles count SPANS of `rows_per_span` rows here; pad is
 // the side to build (1 left, 0 right, 2 none), hist_off that child's histogram.
@@ -434,6 +435,8 @@ __global__ __launch_bounds__(kHistBlock) void hist_static_kernel(
 constexpr int kPHBlock = 512;
 constexpr int kPHRows = 8;                       // rows per thread and tile: what is in flight while the tile loads
 constexpr int kPHTile = kPHBlock * kPHRows;      // 4096
+constexpr int kPFRows = 4;                       // records kernel: rows per thread and tile, twice (current and next tile)
+static_assert(kPHTile % (kPHBlock * kPFRows) == 0, "spans are whole tiles of either kernel");
 constexpr int kPHWords = kPHTile / 64;           // 64 ballot words
 static_assert(kPHWords == 64, "the ballot words are ranked by one wave");
 constexpr int kPHGroup = 7;                      // atomics of a row in flight together (registers for their results)
@@ -448,8 +451,63 @@ __device__ inline int find_span_job(const PartJob *jobs, int n_jobs, uint32_t sp
     return lo;
 }
 
-template <int NS, bool CHK, bool FIRST>
-__global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
+// Adds one record's pair to the LDS histogram at the bins of its NS symbol slots (slot j of a lane
+// is feature (j + lane) mod ft; pre[] / selA / selB are the lane's slot tables).  The atomics go out
+// in groups; a group's returned words are tested together for an event (a carry out of the h field,
+// a wrap of the g field): the smallest distance of any of them from one decides whether the
+// per-word bookkeeping runs at all.
+template <int NS, bool CHK, int RW>
+__device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned long long *main_, uint32_t *side,
+                                           const int (&pre)[NS], const uint32_t (&selA)[4], const uint32_t (&selB)[4],
+                                           int trash, int lane, uint32_t missing, int B) {
+    constexpr int SW = (NS + 3) / 4;
+    // the pair: bytes 1..3 of word RW-2 and word RW-1
+    const uint32_t qlo = (row[RW - 2] >> 8) | (row[RW - 1] << 24);   // bits 0..31 of the 56
+    const uint32_t qhi = row[RW - 1] >> 8;                           // bits 32..55
+    int2 q;
+    q.x = (int32_t)(qlo << 4) >> 4;                                  // 28 bits, sign-extended
+    q.y = (int32_t)((qlo >> 28) | (qhi << 4));                       // 24 bits
+    const unsigned long long addv = pack_pair(q);
+    const uint32_t hq = (uint32_t)q.y;
+    uint32_t W[4], V[(NS + 3) / 4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) W[k] = k < SW ? row[k < SW ? k : 0] : 0u;   // words past the symbols are never selected
+#pragma unroll
+    for (int k = 0; k < (NS + 3) / 4; ++k)
+        V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
+#pragma unroll
+    for (int t0 = 0; t0 < NS; t0 += kPHGroup) {
+        int idx[kPHGroup];
+        unsigned long long old[kPHGroup];
+#pragma unroll
+        for (int tt = 0; tt < kPHGroup; ++tt) {
+            const int t = t0 + tt;
+            if (t < NS) {
+                const uint32_t sv = (V[t >> 2] >> (8 * (t & 3))) & 0xffu;
+                bool bad = false;
+                if (CHK) bad = (sv == missing) | (sv >= (uint32_t)B);
+                idx[tt] = bad ? trash + lane : pre[t] + (int)sv;
+                old[tt] = atomicAdd(&main_[idx[tt]], addv);
+            }
+        }
+        uint32_t near_carry = 0xffffffffu, near_wrap = 0xffffffffu;   // see pk_check for the two conditions
+#pragma unroll
+        for (int tt = 0; tt < kPHGroup; ++tt)
+            if (t0 + tt < NS) {
+                const uint32_t olo = (uint32_t)old[tt], ohi = (uint32_t)(old[tt] >> 32);
+                near_carry = min(near_carry, ~olo & 0x3FC00000u);
+                near_wrap = min(near_wrap, ohi + 0x82000000u);
+            }
+        if (near_carry == 0u || near_wrap < 0x04000000u) {
+#pragma unroll
+            for (int tt = 0; tt < kPHGroup; ++tt)
+                if (t0 + tt < NS) pk_check(side, idx[tt], old[tt], addv, hq);
+        }
+    }
+}
+
+template <int NS, bool CHK>
+__global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
     const uint32_t *__restrict__ src, int64_t src_stride_bytes, int64_t src_words, const int2 *__restrict__ src_gq,
     uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs,
     int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
@@ -509,7 +567,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     for (uint32_t done = 0; done < span_rows; done += kPHTile, par ^= 1) {
         const uint32_t tile_rows = span_rows - done < (uint32_t)kPHTile ? span_rows - done : (uint32_t)kPHTile;
         const uint64_t p0 = (uint64_t)job.seg_begin + span_begin + done;
-        // FIRST: every word an unaligned row load of this tile can touch lies inside the source buffer
+        // every word an unaligned row load of this tile can touch lies inside the source buffer
         const bool tile_inside = (int64_t)(((p0 + tile_rows) * (uint64_t)src_stride_bytes) >> 2) + SW + 1 <= src_words;
         uint32_t row[kPHRows][RW];
         uint32_t takebits = 0;
@@ -521,7 +579,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
             bool left = false;
             if (in_tile < tile_rows) {
                 const uint64_t p = p0 + in_tile;
-                if (FIRST) {
+                {
                     const uint64_t sb = p * (uint64_t)src_stride_bytes;
                     const int64_t s0 = (int64_t)(sb >> 2);
                     const uint32_t sh = (uint32_t)(sb & 3);
@@ -541,10 +599,6 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
                                                    ((unsigned long long)(uint32_t)q.y << 28);
                     row[j][RW - 2] |= (uint32_t)(v56 << 8);          // bytes 1..3
                     row[j][RW - 1] = (uint32_t)(v56 >> 24);
-                } else {
-                    const uint32_t *rp = src + p * RW;
-#pragma unroll
-                    for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
                 }
                 uint32_t fw = row[j][0];
 #pragma unroll
@@ -577,41 +631,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
         // ---- histogram of the rows on the side to be built
 #pragma unroll
         for (int j = 0; j < kPHRows; ++j) {
-            if ((takebits >> j) & 1u) {
-                // the pair: bytes 1..3 of word RW-2 and word RW-1
-                const uint32_t qlo = (row[j][RW - 2] >> 8) | (row[j][RW - 1] << 24);   // bits 0..31 of the 56
-                const uint32_t qhi = row[j][RW - 1] >> 8;                              // bits 32..55
-                int2 q;
-                q.x = (int32_t)(qlo << 4) >> 4;                                        // 28 bits, sign-extended
-                q.y = (int32_t)((qlo >> 28) | (qhi << 4));                             // 24 bits
-                const unsigned long long addv = pack_pair(q);
-                const uint32_t hq = (uint32_t)q.y;
-                uint32_t W[4], V[(NS + 3) / 4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) W[k] = k < SW ? row[j][k < SW ? k : 0] : 0u;   // words past the symbols are never selected
-#pragma unroll
-                for (int k = 0; k < (NS + 3) / 4; ++k)
-                    V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
-#pragma unroll
-                for (int t0 = 0; t0 < NS; t0 += kPHGroup) {
-                    int idx[kPHGroup];
-                    unsigned long long old[kPHGroup];
-#pragma unroll
-                    for (int tt = 0; tt < kPHGroup; ++tt) {
-                        const int t = t0 + tt;
-                        if (t < NS) {
-                            const uint32_t sv = (V[t >> 2] >> (8 * (t & 3))) & 0xffu;
-                            bool bad = false;
-                            if (CHK) bad = (sv == missing) | (sv >= (uint32_t)B);
-                            idx[tt] = bad ? trash + lane : pre[t] + (int)sv;
-                            old[tt] = atomicAdd(&main_[idx[tt]], addv);
-                        }
-                    }
-#pragma unroll
-                    for (int tt = 0; tt < kPHGroup; ++tt)
-                        if (t0 + tt < NS) pk_check(side, idx[tt], old[tt], addv, hq);
-                }
-            }
+            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
         }
         if (nomove) continue;
         if (wave == 0 && lane == 63) {
@@ -646,6 +666,163 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[ji], (unsigned long long)my_lefts);
     __syncthreads();
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, kPHBlock);
+}
+
+// Levels below the first: the source is records.  A thread holds two sets of kPFRows records, one
+// being ranked, added to the histogram and stored, the other (the next tile) on its way from HBM
+// meanwhile, so that the loads never start from an empty pipe behind a tile's barriers.
+template <int NS, bool CHK>
+__global__ __launch_bounds__(kPHBlock) void part_hist_kernel(
+    const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing,
+    const PartJob *__restrict__ jobs, int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor,
+    int64_t *__restrict__ pool) {
+    constexpr int SW = (NS + 3) / 4;
+    constexpr int RW = record_words(NS);
+    constexpr int BLK = kPHBlock, ROWS = kPFRows;
+    constexpr int TILE = BLK * ROWS;
+    constexpr int NW = TILE / 64;          // ballot words of a tile
+    constexpr int WAVES = BLK / 64;
+    static_assert(NW <= 64 && TILE % 64 == 0, "the ballot words are ranked by one wave");
+    extern __shared__ unsigned long long lds[];
+    __shared__ uint64_t words[2][NW];
+    __shared__ uint32_t lefts_before[2][NW];
+    __shared__ uint32_t base_s[2][2];
+    const int ji = find_span_job(jobs, n_jobs, blockIdx.x);
+    const PartJob job = jobs[ji];
+    const uint32_t span_begin = (blockIdx.x - job.tile_begin) * rows_per_span;
+    const uint32_t span_rows = job.seg_len - span_begin < rows_per_span ? job.seg_len - span_begin : rows_per_span;
+    const bool build = job.pad != 2u, build_left = job.pad == 1u;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    const int trash = ft * Bp;
+    const int n_acc = trash + 256;
+    unsigned long long *main_ = lds;
+    uint32_t *side = (uint32_t *)(lds + n_acc);
+    for (int i = threadIdx.x; i < n_acc; i += BLK) {
+        main_[i] = 0;
+        side[i] = 0;
+    }
+    uint32_t selA[4], selB[4];
+    int pre[NS];
+    {
+        const int l0 = lane % ft;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            selA[k] = 0;
+            selB[k] = 0;
+        }
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            int t = j + l0;
+            t = t >= ft ? t - ft : t;
+            const bool live = j < ft;
+            pre[j] = live ? t * Bp : trash + lane;
+            const uint32_t a = (live && t < 8) ? (uint32_t)t : 0x0Cu;
+            const uint32_t b = (live && t >= 8) ? (uint32_t)(t - 8) : 0x0Cu;
+            selA[j >> 2] |= a << (8 * (j & 3));
+            selB[j >> 2] |= b << (8 * (j & 3));
+        }
+    }
+    // byte `feature` of a record, picked without indexing the register array by a run-time value
+    const uint32_t fselA = 0x0C0C0C00u | (job.feature < 8u ? job.feature : 0x0Cu);
+    const uint32_t fselB = 0x0C0C0C00u | (job.feature >= 8u ? job.feature - 8u : 0x0Cu);
+    const uint32_t seg_last = job.seg_begin + job.seg_len - 1u;
+    const bool nomove = dst == nullptr;
+    uint32_t my_lefts = 0;
+    const uint64_t span_first = (uint64_t)job.seg_begin + span_begin;
+    __syncthreads();
+
+    auto load_tile = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
+            if (in_tile < tile_rows) {
+                const uint32_t *rp = src + (span_first + done + in_tile) * RW;
+#pragma unroll
+                for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+            }
+        }
+    };
+    auto process = [&](uint32_t (&row)[ROWS][RW], uint32_t done, int par) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+        uint32_t takebits = 0;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const int w = j * WAVES + wave;
+            const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+            bool left = false;
+            if (in_tile < tile_rows) {
+                const uint32_t sy = __builtin_amdgcn_perm(SW > 1 ? row[j][SW > 1 ? 1 : 0] : 0u, row[j][0], fselA) |
+                                    __builtin_amdgcn_perm(SW > 3 ? row[j][SW > 3 ? 3 : 0] : 0u,
+                                                          SW > 2 ? row[j][SW > 2 ? 2 : 0] : 0u, fselB);
+                left = (sy == missing) ? (job.default_left != 0) : (sy <= job.bin);
+                takebits |= (build && left == build_left) ? (1u << j) : 0u;
+            }
+            const uint64_t ballot = __ballot(left);
+            if (nomove) my_lefts += (uint32_t)__popcll(ballot);
+            else if (lane == 0) words[par][w] = ballot;
+        }
+        if (!nomove) __syncthreads();
+        unsigned long long reserved = 0;
+        if (wave == 0 && !nomove) {
+            const uint32_t c = lane < NW ? (uint32_t)__popcll(words[par][lane < NW ? lane : 0]) : 0u;
+            uint32_t x = c;
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t y = (uint32_t)__shfl_up((int)x, d);
+                if (lane >= d) x += y;
+            }
+            if (lane < NW) lefts_before[par][lane] = x - c;
+            if (lane == 63)
+                reserved = atomicAdd(&cursor[ji], (unsigned long long)x | ((unsigned long long)(tile_rows - x) << 32));
+        }
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
+        }
+        if (nomove) return;
+        if (wave == 0 && lane == 63) {
+            base_s[par][0] = (uint32_t)(reserved & 0xffffffffull);
+            base_s[par][1] = (uint32_t)(reserved >> 32);
+        }
+        __syncthreads();
+        const uint32_t left_base = base_s[par][0], right_base = base_s[par][1];
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const int w = j * WAVES + wave;
+            const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+            if (in_tile < tile_rows) {
+                const uint64_t m = words[par][w];
+                const uint32_t below = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                uint32_t q;
+                if ((m >> lane) & 1ull) {
+                    q = job.seg_begin + left_base + lefts_before[par][w] + below;
+                } else {
+                    const uint32_t rights_before_word = (uint32_t)w * 64u - lefts_before[par][w];
+                    q = seg_last - (right_base + rights_before_word + ((uint32_t)lane - below));
+                }
+                uint32_t *dp = dst + (uint64_t)q * RW;
+#pragma unroll
+                for (int k = 0; k < RW; ++k) dp[k] = row[j][k];
+            }
+        }
+        // words[par] is rewritten two tiles from now, after two more barriers
+    };
+
+    uint32_t rowA[ROWS][RW], rowB[ROWS][RW];
+    load_tile(rowA, 0);
+    for (uint32_t done = 0; done < span_rows;) {
+        if (done + TILE < span_rows) load_tile(rowB, done + TILE);
+        process(rowA, done, 0);
+        done += TILE;
+        if (done >= span_rows) break;
+        if (done + TILE < span_rows) load_tile(rowA, done + TILE);
+        process(rowB, done, 1);
+        done += TILE;
+    }
+    if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[ji], (unsigned long long)my_lefts);
+    __syncthreads();
+    if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
 }
 
 inline int padded_bins(int B) { return B | 1; }   // odd stride: see the note on LDS banks above
@@ -816,27 +993,47 @@ struct PHArgs {
     unsigned long long *cursor;
     int64_t *pool;
 };
-template <int NS, bool CHK, bool FIRST>
-hipError_t launch_ph(const PHArgs &a) {
+template <int NS, bool CHK>
+hipError_t launch_ph_first(const PHArgs &a) {
     static size_t configured = 0;
     if (a.lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK, FIRST>,
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_first_kernel<NS, CHK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
         configured = a.lds;
     }
-    part_hist_kernel<NS, CHK, FIRST><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
-                                                                          a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs,
-                                                                          a.n_jobs, a.rows_per_span, a.cursor, a.pool);
+    part_hist_first_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
+                                                                         a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
+                                                                         a.rows_per_span, a.cursor, a.pool);
+    return hipGetLastError();
+}
+template <int NS, bool CHK>
+hipError_t launch_ph(const PHArgs &a) {
+    static size_t configured = 0;
+    if (a.lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+        if (e != hipSuccess) return e;
+        configured = a.lds;
+    }
+    part_hist_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
+                                                                   a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
 }
 template <bool CHK, bool FIRST>
 hipError_t pick_ph(int ft, const PHArgs &a) {
-    if (ft <= 4) return launch_ph<4, CHK, FIRST>(a);
-    if (ft <= 8) return launch_ph<8, CHK, FIRST>(a);
-    if (ft <= 12) return launch_ph<12, CHK, FIRST>(a);
-    if (ft == 13) return launch_ph<13, CHK, FIRST>(a);
-    return launch_ph<16, CHK, FIRST>(a);
+    if (FIRST) {
+        if (ft <= 4) return launch_ph_first<4, CHK>(a);
+        if (ft <= 8) return launch_ph_first<8, CHK>(a);
+        if (ft <= 12) return launch_ph_first<12, CHK>(a);
+        if (ft == 13) return launch_ph_first<13, CHK>(a);
+        return launch_ph_first<16, CHK>(a);
+    }
+    if (ft <= 4) return launch_ph<4, CHK>(a);
+    if (ft <= 8) return launch_ph<8, CHK>(a);
+    if (ft <= 12) return launch_ph<12, CHK>(a);
+    if (ft == 13) return launch_ph<13, CHK>(a);
+    return launch_ph<16, CHK>(a);
 }
 int slots_for(int ft) { return ft <= 4 ? 4 : ft <= 8 ? 8 : ft <= 12 ? 12 : ft == 13 ? 13 : 16; }
 }  // namespace
