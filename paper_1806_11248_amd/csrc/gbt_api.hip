@@ -151,6 +151,24 @@ int32_t upload(gbt_ctx *ctx, const void *host, size_t bytes, void *dev) {
     return GBT_OK;
 }
 
+// Two tables with one copy: `b` lands behind `a` at the next aligned offset, which is returned.
+int32_t upload2(gbt_ctx *ctx, const void *a, size_t a_bytes, const void *b, size_t b_bytes, void *dev, size_t *b_off) {
+    const size_t off = gbt_align(a_bytes ? a_bytes : 1);
+    GBT_REQUIRE(ctx, off + b_bytes <= kUploadBytes, GBT_EUNSUPPORTED, "job tables of %zu bytes exceed staging", off + b_bytes);
+    const size_t need = gbt_align(off + (b_bytes ? b_bytes : 1));
+    if (ctx->up_off + need > kUploadBytes) {
+        int32_t st = sync(ctx);
+        if (st != GBT_OK) return st;
+    }
+    char *slot = up(ctx) + ctx->up_off;
+    memcpy(slot, a, a_bytes);
+    memcpy(slot + off, b, b_bytes);
+    ctx->up_off += need;
+    GBT_HIP(ctx, hipMemcpyAsync(dev, slot, off + b_bytes, hipMemcpyHostToDevice, ctx->stream));
+    *b_off = off;
+    return GBT_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ context --
@@ -570,7 +588,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
 namespace {
 
 struct GrowLayout {
-    size_t tree_stage, tree_stage_bytes, gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, splits, jobs, scratch, order, rank_tbl, total;
+    size_t tree_stage, tree_stage_bytes, gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, jobs, scratch, order, rank_tbl, total;
     int64_t hist_nodes, level_nodes, tiles, w_words;
     int sw;   // 32-bit words per row of the working copies
 };
@@ -603,7 +621,6 @@ GrowLayout grow_layout_nodes(int64_t n, int F, int bits, int B, int64_t hist_nod
     L.state = o;      o += gbt_align((size_t)L.level_nodes * 8);
     L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
     L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * 2 * sizeof(EvalNode));
-    L.splits = o;     o += gbt_align(GBT_STAGING_BYTES / 2);   // per-(node, feature chunk) records of one level
     L.jobs = o;       o += gbt_align(kUploadBytes);
     L.scratch = o;    o += 4096;
     // room to stage the finished tree for a walk (as gbt_predict_workspace_bytes counts it); a tree has
@@ -863,21 +880,27 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     constexpr size_t kSplitRb = 512u << 10;
     int chunks = 1;
     bool pre_eval = false;   // the level's split records are already in the read-back buffer
-    auto enqueue_eval = [&](const std::vector<EvalNode> &en, int *n_chunks) -> int32_t {
-        int32_t st2 = upload(ctx, en.data(), en.size() * sizeof(EvalNode), ws + L.eval_nodes);
-        if (st2 != GBT_OK) return st2;
+    // The kernel writes the records straight into the pinned read-back buffer (the device can address it):
+    // no copy launch between the evaluation and the host's wait.  dev_nodes: the node table is on the
+    // device already; tail: words the same launch hands back (see gbt_launch_eval).
+    auto enqueue_eval = [&](const std::vector<EvalNode> &en, int *n_chunks, const EvalNode *dev_nodes = nullptr,
+                            EvalTail tail = EvalTail{nullptr, nullptr, 0, 0}) -> int32_t {
+        if (dev_nodes == nullptr) {
+            int32_t st2 = upload(ctx, en.data(), en.size() * sizeof(EvalNode), ws + L.eval_nodes);
+            if (st2 != GBT_OK) return st2;
+            dev_nodes = (const EvalNode *)(ws + L.eval_nodes);
+        }
         const size_t budget = GBT_STAGING_BYTES - kReadbackOff - kSplitRb;
         *n_chunks = gbt_eval_chunks(F, (int)en.size(), budget);
-        gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)en.size() * (double)hist_len * 8.0);
-        GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)en.size(), nb, F, B,
-                                     *n_chunks, inv_sg, inv_sh, lambda, params->min_child_weight,
-                                     (gbt_split *)(ws + L.splits)));
-        gbt_prof_end(ctx);
         const size_t sbytes = en.size() * (size_t)*n_chunks * sizeof(gbt_split);
         GBT_REQUIRE(ctx, sbytes <= budget, GBT_EUNSUPPORTED, "level too wide");
-        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx) + kSplitRb, ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
+        gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)en.size() * (double)hist_len * 8.0);
+        GBT_HIP(ctx, gbt_launch_eval(s, pool, dev_nodes, (int)en.size(), nb, F, B, *n_chunks, inv_sg, inv_sh, lambda,
+                                     params->min_child_weight, (gbt_split *)(rb(ctx) + kSplitRb), tail));
+        gbt_prof_end(ctx);
         return GBT_OK;
     };
+    bool cursors_zero = false;   // the partition + histogram pass's cursors (L.state) were cleared by the evaluation behind the last pass
 
     while (!level.empty() || !sim_open.empty()) {
         // ---- EvaluateSplit for every open node of the level (already enqueued, and waited for, by
@@ -1064,6 +1087,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             GBT_HIP(ctx, gbt_launch_count2(s, rows8, stride8, (uint32_t)missing_sym, (const CountJob *)(ws + L.jobs),
                                            (int)cjobs.size(), (int)ctiles, (uint32_t *)(ws + L.state)));
             GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, cjobs.size() * 8, hipMemcpyDeviceToHost, s));
+            cursors_zero = false;
             gbt_prof_end(ctx);
             GBT_SYNC(ctx);
             const uint32_t *cnt = (const uint32_t *)rb(ctx);
@@ -1072,7 +1096,35 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             // the three-launch form keeps ballots and counts per tile in the workspace
             GBT_REQUIRE(ctx, fused || (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
             GBT_REQUIRE(ctx, pjobs.size() * sizeof(PartJob) <= kUploadBytes, GBT_EUNSUPPORTED, "level too wide");
-            st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
+            const EvalNode *children_dev = nullptr;   // with_hist: the children's evaluation table, uploaded with the jobs
+            if (with_hist) {
+                // Everything the children's evaluation needs is known before the rows are counted (ids,
+                // sums, which child was built): it is enqueued behind the pass (and makes the other child's
+                // histogram by subtraction on the way), so that the host waits once per level, not twice.
+                enodes.clear();
+                for (size_t k = 0; k < pjobs.size(); ++k) {
+                    const HNode &nd = sel_nodes[k];
+                    const gbt_split &sp = sel_splits[k];
+                    const int64_t lid = n_nodes + 2 * (int64_t)k, rid = lid + 1;
+                    const bool left_built = pjobs[k].pad == 1u;
+                    const uint64_t par = (uint64_t)nd.id * (uint64_t)hist_len;
+                    const uint64_t blt = (uint64_t)(left_built ? lid : rid) * (uint64_t)hist_len;
+                    enodes.push_back(EvalNode{(uint64_t)lid * (uint64_t)hist_len, sp.GLq, sp.HLq,
+                                              left_built ? GBT_NO_HIST : par, left_built ? GBT_NO_HIST : blt});
+                    enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq,
+                                              left_built ? par : GBT_NO_HIST, left_built ? blt : GBT_NO_HIST});
+                }
+                const size_t pj_bytes = pjobs.size() * sizeof(PartJob), en_bytes = enodes.size() * sizeof(EvalNode);
+                if (gbt_align(pj_bytes) + en_bytes <= kUploadBytes) {   // both tables with one copy
+                    size_t en_off = 0;
+                    st = upload2(ctx, pjobs.data(), pj_bytes, enodes.data(), en_bytes, ws + L.jobs, &en_off);
+                    children_dev = (const EvalNode *)(ws + L.jobs + en_off);
+                } else {
+                    st = upload(ctx, pjobs.data(), pj_bytes, ws + L.jobs);
+                }
+            } else {
+                st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
+            }
             if (st != GBT_OK) return st;
             if (with_hist) {   // the children's histograms are accumulated into: clear them first
                 const int64_t n_children = 2 * (int64_t)pjobs.size();
@@ -1090,38 +1142,30 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                         : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
                                                                    : row_bits / 8.0));
             if (with_hist) {
+                GBT_REQUIRE(ctx, pjobs.size() * 8 <= kSplitRb, GBT_EUNSUPPORTED, "level too wide");
+                if (!cursors_zero) {   // every cursor a level can have; from then on the evaluation launch keeps them clear
+                    GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(ws + L.state), 0, L.level_nodes));
+                    cursors_zero = true;
+                }
                 // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
                 GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
                                                   wcur == 2 ? nullptr : W[wcur].sym, nomove ? nullptr : W[wnext].sym_rw, F, B,
                                                   (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
                                                   (int)pjobs.size(), (int)tile_cursor, part_tile,
-                                                  (unsigned long long *)(ws + L.state), pool));
-                GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
+                                                  (unsigned long long *)(ws + L.state), pool, true));
                 gbt_prof_end(ctx);
-                // Everything the children's evaluation needs is known before the rows are counted (ids,
-                // sums, which child was built): enqueue the evaluation (which makes the other child's
-                // histogram by subtraction on the way) behind the pass, so that the host waits once per
-                // level instead of twice.
-                enodes.clear();
-                for (size_t k = 0; k < pjobs.size(); ++k) {
-                    const HNode &nd = sel_nodes[k];
-                    const gbt_split &sp = sel_splits[k];
-                    const int64_t lid = n_nodes + 2 * (int64_t)k, rid = lid + 1;
-                    const bool left_built = pjobs[k].pad == 1u;
-                    const uint64_t par = (uint64_t)nd.id * (uint64_t)hist_len;
-                    const uint64_t blt = (uint64_t)(left_built ? lid : rid) * (uint64_t)hist_len;
-                    enodes.push_back(EvalNode{(uint64_t)lid * (uint64_t)hist_len, sp.GLq, sp.HLq,
-                                              left_built ? GBT_NO_HIST : par, left_built ? GBT_NO_HIST : blt});
-                    enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq,
-                                              left_built ? par : GBT_NO_HIST, left_built ? blt : GBT_NO_HIST});
-                }
-                st = enqueue_eval(enodes, &chunks);
+                // the evaluation launch also hands the cursors (the left counts) to the host and clears them
+                // for the next pass: no copy and no fill launch of their own
+                st = enqueue_eval(enodes, &chunks, children_dev,
+                                  EvalTail{(unsigned long long *)(ws + L.state), (unsigned long long *)rb(ctx),
+                                           (int)pjobs.size(), 1});
                 if (st != GBT_OK) return st;
                 pre_eval = true;
             } else if (fused) {
                 GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,
                                                         (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
                                                         (int)tile_cursor, (unsigned long long *)(ws + L.state)));
+                cursors_zero = false;
                 GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 8, hipMemcpyDeviceToHost, s));
                 gbt_prof_end(ctx);
             } else if (path == 3) {
@@ -1641,7 +1685,7 @@ extern "C" int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, c
 
 namespace {
 struct SparseGrowLayout {
-    size_t gq, rowptr[2], ent[2], wgq[2], state, pool, eval_nodes, splits, jobs, scratch, tree_stage, tree_stage_bytes,
+    size_t gq, rowptr[2], ent[2], wgq[2], state, pool, eval_nodes, jobs, scratch, tree_stage, tree_stage_bytes,
         order, rank_tbl, total;
     int64_t hist_nodes, level_nodes;
 };
@@ -1659,7 +1703,6 @@ SparseGrowLayout sparse_grow_layout(int64_t n, int64_t nnz, int F, int B, int ma
     L.state = o;      o += gbt_align((size_t)L.level_nodes * 16);
     L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
     L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * 2 * sizeof(EvalNode));
-    L.splits = o;     o += gbt_align(GBT_STAGING_BYTES / 2);
     L.jobs = o;       o += gbt_align(kUploadBytes);
     L.scratch = o;    o += 4096;
     const size_t cap_nodes = (size_t)(2 * L.hist_nodes + 1);
@@ -1803,10 +1846,10 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         const size_t sbytes = enodes.size() * (size_t)chunks * sizeof(gbt_split);
         GBT_REQUIRE(ctx, sbytes <= budget, GBT_EUNSUPPORTED, "level too wide");
         gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)enodes.size() * (double)hist_len * 8.0);
+        // (the records go straight into the pinned read-back buffer: no copy launch before the wait)
         GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)enodes.size(), nb, F, B, chunks,
-                                     inv_sg, inv_sh, lambda, params->min_child_weight, (gbt_split *)(ws + L.splits)));
+                                     inv_sg, inv_sh, lambda, params->min_child_weight, (gbt_split *)(rb(ctx) + kSplitRb)));
         gbt_prof_end(ctx);
-        GBT_HIP(ctx, hipMemcpyAsync(rb(ctx) + kSplitRb, ws + L.splits, sbytes, hipMemcpyDeviceToHost, s));
         GBT_SYNC(ctx);
         sel_nodes.clear();
         sel_splits.clear();

@@ -151,9 +151,17 @@ int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B);
 
 // out receives n_nodes * n_chunks records (node-major); gbt_eval_chunks picks n_chunks.
 int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes);
+// `out` may be host memory the device can address (the pinned staging): the records are then where the
+// host reads them when the launch has finished, without a copy.  tail: n 64-bit words copied from src to
+// dst (again possibly such host memory) by the same launch, and src cleared behind the copy if `clear`
+// (the row cursors of the partition that ran before, returned and made ready for the next one).
+struct EvalTail {
+    unsigned long long *src, *dst;
+    int n, clear;
+};
 hipError_t gbt_launch_eval(hipStream_t s, int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
                            const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
-                           double lambda, double mcw, gbt_split *out);
+                           double lambda, double mcw, gbt_split *out, EvalTail tail = EvalTail{nullptr, nullptr, 0, 0});
 
 hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n,
                                 uint32_t missing, const uint32_t *src, uint32_t *dst,
@@ -206,6 +214,7 @@ hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t str
 // histogram must have been cleared.
 // dst_records == NULL: nothing is moved (the children's rows stay interleaved in the parent's segment);
 // the histogram is built and the low word of each cursor counts the left rows.
+// The cursors (one 64-bit word per job) are cleared here unless the caller says they are zero already.
 bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B);
 // Rows of 8-bit symbols, row p at byte p * stride_bytes of `rows`: counts[2 * j + c] = rows of job j's
 // child c that go left at that child's split.  counts is cleared here.
@@ -217,7 +226,7 @@ int gbt_part_hist_record_words(int F);
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
                                 const uint32_t *src_records, uint32_t *dst_records, int F, int B, uint32_t missing,
                                 const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
-                                unsigned long long *cursor, int64_t *hist_pool);
+                                unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,

@@ -1060,10 +1060,12 @@ int gbt_part_hist_record_words(int F) { return record_words(slots_for(F)); }
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
                                 const uint32_t *src_records, uint32_t *dst_records, int F, int B, uint32_t missing,
                                 const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
-                                unsigned long long *cursor, int64_t *hist_pool) {
+                                unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero) {
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
-    hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, n_jobs);
-    if (e != hipSuccess) return e;
+    if (!cursors_are_zero) {
+        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, n_jobs);
+        if (e != hipSuccess) return e;
+    }
     const int Bp = padded_bins(B);
     const bool first = src_records == nullptr;
     const PHArgs a{ctx->stream, n_spans, ((size_t)F * Bp + 256) * 12, first ? packed : src_records, first ? (int64_t)F : 0,

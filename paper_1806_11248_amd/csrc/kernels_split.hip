@@ -55,7 +55,13 @@ __device__ inline bool better(double ga, uint32_t ka, double gb, uint32_t kb) {
 __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     int64_t *__restrict__ pool, const EvalNode *__restrict__ nodes, const int32_t *__restrict__ nb,
     int F, int B, int f_per_chunk, double inv_sg, double inv_sh, double lambda, double mcw,
-    gbt_split *__restrict__ out) {
+    gbt_split *__restrict__ out, EvalTail tail) {
+    if (blockIdx.x == 0 && blockIdx.y == 0) {   // the words handed back with the records (see gbt_launch_eval)
+        for (int i = threadIdx.x; i < tail.n; i += kEvalBlock) {
+            tail.dst[i] = tail.src[i];
+            if (tail.clear) tail.src[i] = 0ull;
+        }
+    }
     const EvalNode nd = nodes[blockIdx.x];
     const int f_begin = blockIdx.y * f_per_chunk;
     const int f_end = f_begin + f_per_chunk < F ? f_begin + f_per_chunk : F;
@@ -196,10 +202,10 @@ int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes) {
 
 hipError_t gbt_launch_eval(hipStream_t s, int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
                            const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
-                           double lambda, double mcw, gbt_split *out) {
-    if (n_nodes <= 0) return hipSuccess;
+                           double lambda, double mcw, gbt_split *out, EvalTail tail) {
+    if (n_nodes <= 0) return hipSuccess;   // (the callers have no tail without nodes)
     const int f_per_chunk = (F + n_chunks - 1) / n_chunks;
     dim3 grid((unsigned)n_nodes, (unsigned)n_chunks);
-    eval_kernel<<<grid, kEvalBlock, 0, s>>>(hist_pool, nodes, nb, F, B, f_per_chunk, inv_sg, inv_sh, lambda, mcw, out);
+    eval_kernel<<<grid, kEvalBlock, 0, s>>>(hist_pool, nodes, nb, F, B, f_per_chunk, inv_sg, inv_sh, lambda, mcw, out, tail);
     return hipGetLastError();
 }
