@@ -884,7 +884,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     // no copy launch between the evaluation and the host's wait.  dev_nodes: the node table is on the
     // device already; tail: words the same launch hands back (see gbt_launch_eval).
     auto enqueue_eval = [&](const std::vector<EvalNode> &en, int *n_chunks, const EvalNode *dev_nodes = nullptr,
-                            EvalTail tail = EvalTail{nullptr, nullptr, 0, 0}) -> int32_t {
+                            EvalTail tail = EvalTail{nullptr, nullptr, 0, 0, -1, 0}) -> int32_t {
         if (dev_nodes == nullptr) {
             int32_t st2 = upload(ctx, en.data(), en.size() * sizeof(EvalNode), ws + L.eval_nodes);
             if (st2 != GBT_OK) return st2;
@@ -900,6 +900,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         gbt_prof_end(ctx);
         return GBT_OK;
     };
+    int64_t pool_zero_end = 0;   // pool slots [n_nodes, pool_zero_end) were zeroed by the last evaluation launch
     bool cursors_zero = false;   // the partition + histogram pass's cursors (L.state) were cleared by the evaluation behind the last pass
 
     while (!level.empty() || !sim_open.empty()) {
@@ -1126,7 +1127,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
             }
             if (st != GBT_OK) return st;
-            if (with_hist) {   // the children's histograms are accumulated into: clear them first
+            if (with_hist && (int64_t)n_nodes + 2 * (int64_t)pjobs.size() > pool_zero_end) {
+                // the children's histograms are accumulated into: clear them first (unless the evaluation
+                // launch of the level before has done so, as it does for every child its nodes can have)
                 const int64_t n_children = 2 * (int64_t)pjobs.size();
                 gbt_prof_begin(ctx, GBT_PROF_CLEAR, (double)n_children * (double)hist_len * 8.0);
                 GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)n_nodes * hist_len), 0,
@@ -1156,10 +1159,15 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 gbt_prof_end(ctx);
                 // the evaluation launch also hands the cursors (the left counts) to the host and clears them
                 // for the next pass: no copy and no fill launch of their own
+                // ... and zeroes the histograms of the children's children where those will be built
+                const int64_t after = (int64_t)n_nodes + 2 * (int64_t)pjobs.size();
+                const bool more = child_depth + 1 < max_depth;
+                const int64_t zero_end = more ? std::min<int64_t>(after + 2 * (int64_t)enodes.size(), L.hist_nodes) : 0;
                 st = enqueue_eval(enodes, &chunks, children_dev,
                                   EvalTail{(unsigned long long *)(ws + L.state), (unsigned long long *)rb(ctx),
-                                           (int)pjobs.size(), 1});
+                                           (int)pjobs.size(), 1, more ? after : -1, zero_end});
                 if (st != GBT_OK) return st;
+                pool_zero_end = zero_end;
                 pre_eval = true;
             } else if (fused) {
                 GBT_HIP(ctx, gbt_launch_partition_fused(s, cur, W[wnext], bits, row_bits, (uint32_t)missing_sym,

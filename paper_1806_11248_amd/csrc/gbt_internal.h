@@ -155,13 +155,17 @@ int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes);
 // host reads them when the launch has finished, without a copy.  tail: n 64-bit words copied from src to
 // dst (again possibly such host memory) by the same launch, and src cleared behind the copy if `clear`
 // (the row cursors of the partition that ran before, returned and made ready for the next one).
+// clear_slot >= 0: the launch also zeroes the histograms that the evaluated nodes' children would
+// accumulate into if their parents split: pool slots clear_slot + 2 i and clear_slot + 2 i + 1 for node
+// i, as far as they lie below clear_slot_end (a slot is F * B * 2 values).
 struct EvalTail {
     unsigned long long *src, *dst;
     int n, clear;
+    int64_t clear_slot, clear_slot_end;
 };
 hipError_t gbt_launch_eval(hipStream_t s, int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
                            const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
-                           double lambda, double mcw, gbt_split *out, EvalTail tail = EvalTail{nullptr, nullptr, 0, 0});
+                           double lambda, double mcw, gbt_split *out, EvalTail tail = EvalTail{nullptr, nullptr, 0, 0, -1, 0});
 
 hipError_t gbt_launch_partition(hipStream_t s, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n,
                                 uint32_t missing, const uint32_t *src, uint32_t *dst,

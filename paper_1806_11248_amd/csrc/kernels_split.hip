@@ -65,6 +65,15 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     const EvalNode nd = nodes[blockIdx.x];
     const int f_begin = blockIdx.y * f_per_chunk;
     const int f_end = f_begin + f_per_chunk < F ? f_begin + f_per_chunk : F;
+    if (tail.clear_slot >= 0 && f_begin < f_end) {   // this chunk's features of the two histograms below node blockIdx.x
+        const int64_t per = (int64_t)F * B * 2, span = (int64_t)(f_end - f_begin) * B * 2;
+        for (int c = 0; c < 2; ++c) {
+            const int64_t slot = tail.clear_slot + 2 * (int64_t)blockIdx.x + c;
+            if (slot >= tail.clear_slot_end) break;
+            int64_t *z = pool + slot * per + (int64_t)f_begin * B * 2;
+            for (int64_t i = threadIdx.x; i < span; i += kEvalBlock) z[i] = 0;
+        }
+    }
     int64_t *hist = pool + nd.hist_off;
     // the larger sibling: its histogram is made here, as parent - built (exact: integers), and kept
     const bool subtract = nd.parent_off != GBT_NO_HIST;
