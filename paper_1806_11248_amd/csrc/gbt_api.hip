@@ -780,9 +780,14 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     matrix.gq_rw = nullptr;
     matrix.id_rw = nullptr;
 
-    // thresholds come from the cut table
+    // thresholds come from the cut table: it travels through the part of the pinned read-back buffer that
+    // the split records use later, and is picked up behind the first wait below (a copy into pageable
+    // memory would be a wait of its own); a table too large for that is copied directly
     std::vector<float> hcuts((size_t)F * (B - 1));
-    GBT_HIP(ctx, hipMemcpyAsync(hcuts.data(), cuts, hcuts.size() * sizeof(float), hipMemcpyDeviceToHost, s));
+    constexpr size_t kCutsRb = 512u << 10;   // (= where the split records go, see kSplitRb)
+    const bool cuts_via_pinned = hcuts.size() * sizeof(float) <= GBT_STAGING_BYTES - kReadbackOff - kCutsRb;
+    GBT_HIP(ctx, hipMemcpyAsync(cuts_via_pinned ? (void *)(rb(ctx) + kCutsRb) : (void *)hcuts.data(), cuts,
+                                hcuts.size() * sizeof(float), hipMemcpyDeviceToHost, s));
 
     // Fixed-point gradient pairs and the root's totals: the scales need one pass over the pairs;
     // the conversion is a pass of its own, or part of the root histogram kernel where that can do it.
@@ -813,6 +818,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     GBT_SYNC(ctx);
     int64_t root_sums[2];
     memcpy(root_sums, rb(ctx), 16);
+    if (cuts_via_pinned) memcpy(hcuts.data(), rb(ctx) + kCutsRb, hcuts.size() * sizeof(float));
 
     auto set_node_at = [&](int32_t at, const HNode &nd) {
         const double G = (double)nd.Gq * inv_sg, H = (double)nd.Hq * inv_sh;
