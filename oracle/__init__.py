@@ -381,7 +381,7 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
 
     ``nodes``: optional set of node ids whose split is searched exhaustively
     (the partition and the totals are always checked for every node).
-    Returns a report dict; ``report['ok']`` is the verdict.
+    Returns a report dict; ``report['ok']`` is the outcome.
     """
     n, F = sym.shape
     B = max_bins
