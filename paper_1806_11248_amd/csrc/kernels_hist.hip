@@ -14,9 +14,10 @@
 // as long as two events are counted: a carry out of the h field (it lands in the
 // g field as +1) and a wrap of the g field.  The atomic returns the old word;
 // the lane whose add caused an event records it in a small side counter
-// [ wraps : int16 | carries : uint16 ] of the same bin.  Events are rare (at
-// least 256 adds between carries, 128 same-sign extreme adds between wraps), a
-// two-compare test on the returned word skips the bookkeeping otherwise.
+// [ wraps : int16 | carries : uint16 ] of the same bin.  A bin sees an event only
+// every few hundred adds (at least 256 adds between carries, 128 same-sign extreme
+// adds between wraps), and a two-compare test on the returned word, exact for the
+// carry and tight for the wrap, skips the bookkeeping otherwise.
 //
 // The bin axis of the LDS histogram is padded to an odd stride so that equal bin
 // indices of different features (e.g. the most frequent category of several
@@ -157,12 +158,29 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
 //         itself, stores them for the later levels and adds up the root's totals,
 //         which saves the separate conversion pass over all rows
 // ---------------------------------------------------------------------------
+// The two quick tests on a returned word, as tight as the row's own pair allows (events are not
+// rare enough for loose ones: a heavy bin sees a carry every few hundred adds, and with 64 lanes
+// and 13 features some lane is near one most of the time):
+//   carry  iff  h field + hq >= 2^30        iff  (~low word & 2^30-1) < hq          (exact)
+//   wrap   only if the g field lies within |g| + 1 of the end it is moving towards.  In units of
+//          four (the high word is the g field >> 2, signed): its distance from that end is
+//          high ^ kind, kind = 0x7FFFFFFF going up, 0x80000000 going down, and the test is
+//          distance < reach, reach = |g| / 4 rounded up, plus one for the carry that may come along.
+// (everything is derived from the pair's own word where it is used, so that no register is held for it)
+__device__ __forceinline__ uint32_t pk_near_carry(unsigned long long old) { return ~(uint32_t)old & kHMask; }
+__device__ __forceinline__ uint32_t pk_near_wrap(unsigned long long old, unsigned long long addv) {
+    const uint32_t down = (uint32_t)((int32_t)(addv >> 32) >> 31);   // 0 going up, all ones going down
+    return (uint32_t)(old >> 32) ^ down ^ 0x7FFFFFFFu;
+}
+__device__ __forceinline__ uint32_t pk_reach(unsigned long long addv) {
+    const uint32_t ahi = (uint32_t)(addv >> 32);   // floor(g / 4), signed
+    return (ahi ^ (uint32_t)((int32_t)ahi >> 31)) + 2u;
+}
+
 __device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long long old,
                                          unsigned long long addv, uint32_t hq) {
     uint32_t olo = (uint32_t)old, ohi = (uint32_t)(old >> 32);
-    // carry possible only if h-field bits 22..29 are all ones; wrap possible only if the
-    // g field is within 2^27 of +-2^33 (top seven bits of the word are 0111111 or 1000000)
-    const bool danger = ((olo & 0x3FC00000u) == 0x3FC00000u) | ((ohi + 0x82000000u) < 0x04000000u);
+    const bool danger = (pk_near_carry(old) < hq) | (pk_near_wrap(old, addv) < pk_reach(addv));
     if (danger) {
         asm volatile("" : "+v"(olo), "+v"(ohi));   // keep the rare bookkeeping inside the branch
         const uint32_t carry = ((olo & kHMask) + hq) >> kHShift;
@@ -184,11 +202,10 @@ __device__ __forceinline__ void pk_check_group(uint32_t *side, const int (&idx)[
 #pragma unroll
     for (int j = 0; j < G; ++j)
         if (j < live) {
-            const uint32_t olo = (uint32_t)old[j], ohi = (uint32_t)(old[j] >> 32);
-            near_carry = min(near_carry, ~olo & 0x3FC00000u);
-            near_wrap = min(near_wrap, ohi + 0x82000000u);
+            near_carry = min(near_carry, pk_near_carry(old[j]));
+            near_wrap = min(near_wrap, pk_near_wrap(old[j], addv));
         }
-    if (near_carry == 0u || near_wrap < 0x04000000u) {
+    if (near_carry < hq || near_wrap < pk_reach(addv)) {
 #pragma unroll
         for (int j = 0; j < G; ++j)
             if (j < live) pk_check(side, idx[j], old[j], addv, hq);
@@ -478,7 +495,7 @@ __device__ inline int find_span_job(const PartJob *jobs, int n_jobs, uint32_t sp
 // in groups; a group's returned words are tested together for an event (a carry out of the h field,
 // a wrap of the g field): the smallest distance of any of them from one decides whether the
 // per-word bookkeeping runs at all.
-template <int NS, bool CHK, int RW>
+template <int NS, bool CHK, int RW, int GROUP = kPHGroup>
 __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned long long *main_, uint32_t *side,
                                            const int (&pre)[NS], const uint32_t (&selA)[4], const uint32_t (&selB)[4],
                                            int trash, int lane, uint32_t missing, int B) {
@@ -498,11 +515,11 @@ __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned l
     for (int k = 0; k < (NS + 3) / 4; ++k)
         V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
 #pragma unroll
-    for (int t0 = 0; t0 < NS; t0 += kPHGroup) {
-        int idx[kPHGroup];
-        unsigned long long old[kPHGroup];
+    for (int t0 = 0; t0 < NS; t0 += GROUP) {
+        int idx[GROUP];
+        unsigned long long old[GROUP];
 #pragma unroll
-        for (int tt = 0; tt < kPHGroup; ++tt) {
+        for (int tt = 0; tt < GROUP; ++tt) {
             const int t = t0 + tt;
             if (t < NS) {
                 const uint32_t sv = (V[t >> 2] >> (8 * (t & 3))) & 0xffu;
@@ -512,7 +529,7 @@ __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned l
                 old[tt] = atomicAdd(&main_[idx[tt]], addv);
             }
         }
-        pk_check_group<kPHGroup>(side, idx, old, NS - t0, addv, hq);
+        pk_check_group<GROUP>(side, idx, old, NS - t0, addv, hq);
     }
 }
 
@@ -641,7 +658,8 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
         // ---- histogram of the rows on the side to be built
 #pragma unroll
         for (int j = 0; j < kPHRows; ++j) {
-            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
+            // (groups of 5 atomics here: with 8 rows of raw words per thread, 7 results in flight spill registers)
+            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW, 5>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
         }
         if (nomove) continue;
         if (wave == 0 && lane == 63) {
@@ -682,7 +700,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
 // being ranked, added to the histogram and stored, the other (the next tile) on its way from HBM
 // meanwhile, so that the loads never start from an empty pipe behind a tile's barriers.
 template <int NS, bool CHK>
-__global__ __launch_bounds__(kPHBlock) void part_hist_kernel(
+__global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing,
     const PartJob *__restrict__ jobs, int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor,
     int64_t *__restrict__ pool) {

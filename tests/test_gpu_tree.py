@@ -183,6 +183,44 @@ def test_byte_symbols_up_to_16_features(ctx, oracle, F, B, miss):
     grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
 
 
+@pytest.mark.parametrize("F", [13, 16, 5])
+def test_pass_with_carries_and_wraps_everywhere(ctx, ctx_env, oracle, F):
+    """Extreme same-sign pairs piled into few bins: in the partition + histogram pass the packed LDS
+    words carry and wrap every few hundred adds.  The tree must equal, to the last bit of every sum,
+    the one grown through the separate histogram kernels on row lists."""
+    import paper_1806_11248_amd as g
+    n, B = 1_200_007, 256
+    rng = np.random.default_rng(40 + F)
+    sym = np.zeros((n, F), np.uint16)
+    sym[:, 0] = rng.integers(0, 3, n)                       # three heavy bins
+    sym[:, 1] = (np.arange(n) // 7) % B
+    for f in range(2, F):
+        sym[:, f] = rng.integers(0, 1 + f, n) * (B // (1 + f))
+    run = (np.arange(n) // 50_000) % 2 == 0                 # long runs of one sign, then the other
+    gmag = np.where(rng.random(n) < 0.5, 1.999, 1.3).astype(np.float32)
+    gp = np.stack([np.where(run, gmag, -gmag), np.where(rng.random(n) < 0.7, 1.999, 0.9)], 1).astype(np.float32)
+    gp[:, 0] += (sym[:, 0] == 1) * np.float32(0.5)          # something to split on
+    nb = np.full(F, B, np.int32)
+    cuts = np.tile(np.arange(1, B, dtype=np.float32), (F, 1))
+    packed = dev(oracle.pack(sym, 8).view(np.int32))
+    params = g.make_params(max_depth=4, max_bins=B)
+    _say(f"carries and wraps in the pass, F={F}")
+    assert ctx.grow_tree_path(F, 8, B, track_rows=False) == 2
+    tree, _, leaf = ctx.grow_tree(packed, 8, n, F, B, dev(nb), dev(cuts), dev(gp), params, want_rows=False)
+    other = ctx_env(GBT_TUNE_PART_HIST=0, GBT_TUNE_PART_FUSED=0, GBT_TUNE_ORDER_ROWS=0)
+    assert other.grow_tree_path(F, 8, B, track_rows=True) == 0
+    ref, _, leaf_ref = other.grow_tree(packed, 8, n, F, B, dev(nb), dev(cuts), dev(gp), params)
+    nn = tree["n_nodes"]
+    assert nn > 3 and ref["n_nodes"] == nn
+    for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "weight", "gain", "sumG", "sumH"):
+        assert np.array_equal(ref[k][:nn], tree[k][:nn]), k
+    assert torch.equal(leaf, leaf_ref)
+    # and the root's sums against plain fp64 arithmetic on the fixed-point pairs
+    gq, scale = ctx.gpair_fixed(dev(gp))
+    q = gq.cpu().numpy().astype(np.int64)
+    assert tree["sumG"][0] == q[:, 0].sum() / scale[0] and tree["sumH"][0] == q[:, 1].sum() / scale[1]
+
+
 @pytest.mark.parametrize("F,B,miss", [(16, 200, 0.05), (6, 256, 0.0)])
 def test_byte_symbols_many_tiles(ctx, oracle, F, B, miss):
     """The partition + histogram pass over millions of rows: spans of several tiles, cursors handed
