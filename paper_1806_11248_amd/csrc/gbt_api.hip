@@ -210,8 +210,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (const char *e13 = getenv("GBT_TUNE_SPARSE_TILED")) c->sparse_tiled = atoi(e13) != 0;
         c->lossguide_batch = 16;
         if (const char *e16 = getenv("GBT_TUNE_LOSSGUIDE_BATCH")) { int v = atoi(e16); if (v >= 1 && v <= 64) c->lossguide_batch = v; }
-        c->part_nomove = 1;
-        if (const char *e15 = getenv("GBT_TUNE_PART_NOMOVE")) c->part_nomove = atoi(e15) != 0;
+        c->part_nomove = 2;
+        if (const char *e15 = getenv("GBT_TUNE_PART_NOMOVE")) { int v = atoi(e15); if (v >= 0 && v <= 2) c->part_nomove = v; }
         c->part_ids = 1;
         if (const char *e14 = getenv("GBT_TUNE_PART_IDS")) c->part_ids = atoi(e14) != 0;
         c->order_rows = 1;
@@ -641,16 +641,23 @@ struct HNode {
     int64_t Gq, Hq;
     int32_t depth;
     int32_t buf;   // where the node's rows are: 0/1 = working copy, 2 = the caller's matrix (the root)
-    // >= 0: the rows were not moved at the parent's split: they lie interleaved with the sibling's in the
-    // parent's segment; 2 * (index of the parent's record in the table of such splits) + (1 for the right child)
-    int32_t virt = -1;
+    // virt >= 0: the node's rows were not moved when it was made: they lie interleaved with other nodes' rows
+    // in segment `virt` of the table of such segments, where the node has heap position vpos below the
+    // segment's own split (1, 2: its children; 3..6: its grandchildren)
+    int32_t virt = -1, vpos = 0;
     // >= 0: the node's histogram is still to be made as parent - built (pool slots) when it is evaluated
     int32_t sub_parent = -1, sub_built = -1;
 };
-struct UnmovedSplit {   // a split whose rows stayed in place
-    uint32_t begin, len;   // the parent's segment
+struct UnmovedSeg {   // a segment whose rows stay in place below its own split, and the splits made there since
+    uint32_t begin, len;
     int32_t buf;
-    uint32_t feature, bin, default_left;
+    uint32_t feature[7], bin[7], default_left[7], has[7];   // heap order, as in CountJob
+    void set(int p, const gbt_split &sp) {
+        feature[p] = (uint32_t)sp.feature;
+        bin[p] = (uint32_t)sp.bin;
+        default_left[p] = (uint32_t)sp.default_left;
+        has[p] = 1;
+    }
 };
 enum { GBT_POLICY_DEPTHWISE = 0, GBT_POLICY_LOSSGUIDE = 1 };
 constexpr int32_t kMaxLeaves = 1 << 20;
@@ -871,8 +878,12 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     int32_t n_logical = 1;
     if (lossguide) phys.push_back(Phys{root, gbt_split{}, -1, -1, 0, false});
     const int batch_max = std::max(1, std::min(ctx->lossguide_batch, kLossguideBatchMax));
-    std::vector<UnmovedSplit> unmoved;
+    std::vector<UnmovedSeg> unmoved;
     std::vector<CountJob> cjobs;
+    std::vector<Hist2Job> h2jobs;
+    std::vector<int> job_of;           // sel node -> its segment's job (count and two-histogram passes)
+    uint32_t h2_spans = 0;
+    int64_t h2_rows = 0;
     std::vector<uint32_t> nl_of;       // left rows of each node this round splits
     std::vector<HNode> sel_nodes;      // the nodes this round splits ...
     std::vector<gbt_split> sel_splits; // ... and how
@@ -1013,16 +1024,26 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         // Depth-wise, the last level that needs histograms: its children's children are leaves, of which only
         // the row counts are wanted.  The pass then builds the histograms and counts without moving a row,
         // and the counts one level down come from a two-level count over the parents' segments.
-        const bool nomove = with_hist && !lossguide && child_depth == max_depth - 1 && ctx->part_nomove;
-        const bool two_level = !children_need_hist && sel_nodes[0].virt >= 0;
+        // One level earlier the same again where that level's rows are records that can serve a second pass with
+        // TWO histograms per workgroup (one for each of a segment's two children): the nodes of depth
+        // max_depth - 3 are then the last whose rows were moved into place, and the leaves are counted over
+        // three levels of splits.
+        const bool in_place = sel_nodes[0].virt >= 0;   // this level's nodes were not moved when they were made
+        const bool nomove = with_hist && !lossguide && !in_place && ctx->part_nomove &&
+                            (child_depth == max_depth - 1 ||
+                             (ctx->part_nomove >= 2 && child_depth == max_depth - 2 && wcur != 2 && gbt_hist2_ok(ctx, F, B)));
+        const bool nomove2 = with_hist && in_place;     // (their heap positions are 1 and 2)
+        const bool two_level = !children_need_hist && in_place;
+        const int count_levels = two_level && sel_nodes[0].vpos >= 3 ? 2 : 1;
         double part_rows = 0;
         for (const HNode &nd : sel_nodes) part_rows += nd.len;
         // rows per partition workgroup: a tile, or (with the histogram) a span of tiles long enough
         // to be worth merging an LDS histogram into HBM for
         uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile(W[wnext]) : (uint32_t)GBT_PART_TILE;
         if (with_hist) {
+            // (the two-histogram pass merges two histograms per span and has one workgroup per CU: half the spans)
             const uint32_t t = (uint32_t)gbt_part_hist_tile();
-            const double want = part_rows / ((double)ctx->num_cu * ctx->hist_jobs_per_cu);
+            const double want = part_rows / ((double)ctx->num_cu * (in_place ? std::max(1, ctx->hist_jobs_per_cu / 2) : ctx->hist_jobs_per_cu));
             part_tile = (uint32_t)std::min<double>(std::max<double>(std::ceil(want / t), 4.0), (double)((1u << 21) / t)) * t;
         }
         pjobs.clear();
@@ -1052,39 +1073,45 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                          : children_need_hist ? GBT_PART_RECORDS
                          : (tracked && path == 0) ? GBT_PART_IDS
                                                   : GBT_PART_COUNT;
+        // the segments this level's nodes live in, one job each (nodes of a segment are adjacent in sel_nodes)
+        job_of.assign(sel_nodes.size(), -1);
+        if (in_place) {
+            int n_seg_jobs = 0;
+            for (size_t k = 0; k < sel_nodes.size(); ++k) {
+                if (k == 0 || sel_nodes[k - 1].virt != sel_nodes[k].virt) ++n_seg_jobs;
+                job_of[k] = n_seg_jobs - 1;
+                unmoved[(size_t)sel_nodes[k].virt].set(sel_nodes[k].vpos, sel_splits[k]);
+            }
+        }
         if (two_level) {
-            // one job per parent segment that has a child to count for (siblings are adjacent in sel_nodes)
             cjobs.clear();
-            std::vector<int> job_of(sel_nodes.size());
             uint32_t ctiles = 0;
             const uint32_t ct = (uint32_t)gbt_count2_tile();
             for (size_t k = 0; k < sel_nodes.size(); ++k) {
-                const int pi = sel_nodes[k].virt >> 1, side = sel_nodes[k].virt & 1;
-                const UnmovedSplit &u = unmoved[(size_t)pi];
-                if (cjobs.empty() || job_of[k - 1] < 0 || (sel_nodes[k - 1].virt >> 1) != pi) {
-                    CountJob cj{};
-                    cj.seg_begin = u.begin;
-                    cj.seg_len = u.len;
-                    cj.tile_begin = ctiles;
-                    cj.n_tiles = (u.len + ct - 1) / ct;
-                    cj.feature[0] = u.feature;
-                    cj.bin[0] = u.bin;
-                    cj.default_left[0] = u.default_left;
-                    ctiles += cj.n_tiles;
-                    cjobs.push_back(cj);
-                }
-                CountJob &cj = cjobs.back();
-                cj.feature[1 + side] = (uint32_t)sel_splits[k].feature;
-                cj.bin[1 + side] = (uint32_t)sel_splits[k].bin;
-                cj.default_left[1 + side] = (uint32_t)sel_splits[k].default_left;
-                cj.has[side] = 1;
-                job_of[k] = (int)cjobs.size() - 1;
+                if (k > 0 && job_of[k] == job_of[k - 1]) continue;
+                const UnmovedSeg &u = unmoved[(size_t)sel_nodes[k].virt];
+                CountJob cj{};
+                cj.seg_begin = u.begin;
+                cj.seg_len = u.len;
+                cj.tile_begin = ctiles;
+                cj.n_tiles = (u.len + ct - 1) / ct;
+                ctiles += cj.n_tiles;
+                cjobs.push_back(cj);
             }
-            GBT_REQUIRE(ctx, cjobs.size() * sizeof(CountJob) <= kUploadBytes && cjobs.size() * 8 <= (size_t)L.level_nodes * 8,
+            for (size_t k = 0; k < sel_nodes.size(); ++k) {   // (after every split of the level has been noted in its segment)
+                const UnmovedSeg &u = unmoved[(size_t)sel_nodes[k].virt];
+                CountJob &cj = cjobs[(size_t)job_of[k]];
+                memcpy(cj.feature, u.feature, sizeof cj.feature);
+                memcpy(cj.bin, u.bin, sizeof cj.bin);
+                memcpy(cj.default_left, u.default_left, sizeof cj.default_left);
+                memcpy(cj.has, u.has, sizeof cj.has);
+            }
+            const size_t cnt_bytes = cjobs.size() * (count_levels == 2 ? 16 : 8);
+            GBT_REQUIRE(ctx, cjobs.size() * sizeof(CountJob) <= kUploadBytes && cnt_bytes <= (size_t)L.level_nodes * 8,
                         GBT_EUNSUPPORTED, "level too wide");
             st = upload(ctx, cjobs.data(), cjobs.size() * sizeof(CountJob), ws + L.jobs);
             if (st != GBT_OK) return st;
-            const UnmovedSplit &u0 = unmoved[(size_t)(sel_nodes[0].virt >> 1)];
+            const UnmovedSeg &u0 = unmoved[(size_t)sel_nodes[0].virt];
             const bool from_matrix = u0.buf == 2;
             const uint8_t *rows8 = from_matrix ? (const uint8_t *)packed : (const uint8_t *)W[u0.buf].sym;
             const int64_t stride8 = from_matrix ? (int64_t)F : 4 * (int64_t)gbt_part_hist_record_words(F);
@@ -1092,13 +1119,16 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             for (const CountJob &cj : cjobs) crow += cj.seg_len;
             gbt_prof_begin(ctx, GBT_PROF_PARTITION, crow * (double)stride8);
             GBT_HIP(ctx, gbt_launch_count2(s, rows8, stride8, (uint32_t)missing_sym, (const CountJob *)(ws + L.jobs),
-                                           (int)cjobs.size(), (int)ctiles, (uint32_t *)(ws + L.state)));
-            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, cjobs.size() * 8, hipMemcpyDeviceToHost, s));
+                                           (int)cjobs.size(), (int)ctiles, (uint32_t *)(ws + L.state), count_levels,
+                                           !from_matrix));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, cnt_bytes, hipMemcpyDeviceToHost, s));
             cursors_zero = false;
             gbt_prof_end(ctx);
             GBT_SYNC(ctx);
             const uint32_t *cnt = (const uint32_t *)rb(ctx);
-            for (size_t k = 0; k < sel_nodes.size(); ++k) nl_of[k] = cnt[2 * job_of[k] + (sel_nodes[k].virt & 1)];
+            for (size_t k = 0; k < sel_nodes.size(); ++k)
+                nl_of[k] = count_levels == 2 ? cnt[4 * job_of[k] + (sel_nodes[k].vpos - 3)]
+                                             : cnt[2 * job_of[k] + (sel_nodes[k].vpos - 1)];
         } else {
             // the three-launch form keeps ballots and counts per tile in the workspace
             GBT_REQUIRE(ctx, fused || (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
@@ -1121,13 +1151,47 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                     enodes.push_back(EvalNode{(uint64_t)rid * (uint64_t)hist_len, nd.Gq - sp.GLq, nd.Hq - sp.HLq,
                                               left_built ? par : GBT_NO_HIST, left_built ? blt : GBT_NO_HIST});
                 }
-                const size_t pj_bytes = pjobs.size() * sizeof(PartJob), en_bytes = enodes.size() * sizeof(EvalNode);
+                const void *jobs_host = pjobs.data();
+                size_t pj_bytes = pjobs.size() * sizeof(PartJob);
+                if (nomove2) {   // one job per segment: its own split, and what its (one or two) splitting children do
+                    h2jobs.clear();
+                    h2_spans = 0;
+                    h2_rows = 0;
+                    for (size_t k = 0; k < sel_nodes.size(); ++k) {
+                        const UnmovedSeg &u = unmoved[(size_t)sel_nodes[k].virt];
+                        if (k == 0 || job_of[k] != job_of[k - 1]) {
+                            Hist2Job hj{};
+                            hj.seg_begin = u.begin;
+                            hj.seg_len = u.len;
+                            hj.tile_begin = h2_spans;
+                            hj.n_tiles = (u.len + part_tile - 1) / part_tile;
+                            hj.feature[0] = u.feature[0];
+                            hj.bin[0] = u.bin[0];
+                            hj.default_left[0] = u.default_left[0];
+                            hj.build[0] = hj.build[1] = 2u;
+                            h2_spans += hj.n_tiles;
+                            h2_rows += u.len;
+                            h2jobs.push_back(hj);
+                        }
+                        Hist2Job &hj = h2jobs.back();
+                        const int c = sel_nodes[k].vpos - 1;
+                        hj.feature[1 + c] = (uint32_t)sel_splits[k].feature;
+                        hj.bin[1 + c] = (uint32_t)sel_splits[k].bin;
+                        hj.default_left[1 + c] = (uint32_t)sel_splits[k].default_left;
+                        hj.has[c] = 1;
+                        hj.build[c] = pjobs[k].pad;
+                        hj.hist_off[c] = pjobs[k].hist_off;
+                    }
+                    jobs_host = h2jobs.data();
+                    pj_bytes = h2jobs.size() * sizeof(Hist2Job);
+                }
+                const size_t en_bytes = enodes.size() * sizeof(EvalNode);
                 if (gbt_align(pj_bytes) + en_bytes <= kUploadBytes) {   // both tables with one copy
                     size_t en_off = 0;
-                    st = upload2(ctx, pjobs.data(), pj_bytes, enodes.data(), en_bytes, ws + L.jobs, &en_off);
+                    st = upload2(ctx, jobs_host, pj_bytes, enodes.data(), en_bytes, ws + L.jobs, &en_off);
                     children_dev = (const EvalNode *)(ws + L.jobs + en_off);
                 } else {
-                    st = upload(ctx, pjobs.data(), pj_bytes, ws + L.jobs);
+                    st = upload(ctx, jobs_host, pj_bytes, ws + L.jobs);
                 }
             } else {
                 st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
@@ -1144,6 +1208,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             }
             const double rec_bytes = row_bits / 8.0 + 8.0;
             gbt_prof_begin(ctx, with_hist ? GBT_PROF_HIST_NODE : GBT_PROF_PARTITION,
+                           nomove2 ? (double)h2_rows * rec_bytes :
                            part_rows * (path == 3 ? 8.0 + 32.0   // ids read and written, one sector of symbols per row
                                         : nomove  ? rec_bytes
                                     : fused   ? 2.0 * rec_bytes
@@ -1156,12 +1221,16 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                     GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(ws + L.state), 0, L.level_nodes));
                     cursors_zero = true;
                 }
-                // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
-                GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
-                                                  wcur == 2 ? nullptr : W[wcur].sym, nomove ? nullptr : W[wnext].sym_rw, F, B,
-                                                  (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
-                                                  (int)pjobs.size(), (int)tile_cursor, part_tile,
+                if (nomove2)   // the segments' records once more, two histograms per workgroup
+                    GBT_HIP(ctx, gbt_launch_hist2(ctx, W[wcur].sym, F, B, (uint32_t)missing_sym, (const Hist2Job *)(ws + L.jobs),
+                                                  (int)h2jobs.size(), (int)h2_spans, part_tile,
                                                   (unsigned long long *)(ws + L.state), pool, true));
+                else   // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
+                    GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
+                                                      wcur == 2 ? nullptr : W[wcur].sym, nomove ? nullptr : W[wnext].sym_rw, F, B,
+                                                      (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
+                                                      (int)pjobs.size(), (int)tile_cursor, part_tile,
+                                                      (unsigned long long *)(ws + L.state), pool, true));
                 gbt_prof_end(ctx);
                 // the evaluation launch also hands the cursors (the left counts) to the host and clears them
                 // for the next pass: no copy and no fill launch of their own
@@ -1171,7 +1240,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 const int64_t zero_end = more ? std::min<int64_t>(after + 2 * (int64_t)enodes.size(), L.hist_nodes) : 0;
                 st = enqueue_eval(enodes, &chunks, children_dev,
                                   EvalTail{(unsigned long long *)(ws + L.state), (unsigned long long *)rb(ctx),
-                                           (int)pjobs.size(), 1, more ? after : -1, zero_end});
+                                           nomove2 ? 2 * (int)h2jobs.size() : (int)pjobs.size(), 1, more ? after : -1, zero_end});
                 if (st != GBT_OK) return st;
                 pool_zero_end = zero_end;
                 pre_eval = true;
@@ -1202,9 +1271,10 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             GBT_SYNC(ctx);
             const int nl_stride = fused ? 2 : 1;   // the one-launch form returns 64-bit cursors, n_left in the low half
             const uint32_t *n_left = (const uint32_t *)rb(ctx);
-            for (size_t k = 0; k < pjobs.size(); ++k) nl_of[k] = n_left[k * nl_stride];
+            for (size_t k = 0; k < pjobs.size(); ++k)   // (two-histogram pass: cursor 2 * job + child, 64 bits each)
+                nl_of[k] = nomove2 ? n_left[2 * (2 * job_of[k] + (sel_nodes[k].vpos - 1))] : n_left[k * nl_stride];
         }
-        const int child_buf = (nomove || two_level || what == GBT_PART_COUNT) ? wcur : wnext;   // a count moves nothing
+        const int child_buf = (nomove || nomove2 || two_level || what == GBT_PART_COUNT) ? wcur : wnext;   // a count moves nothing
 
         // ---- children, in creation order
         hjobs.clear();
@@ -1219,11 +1289,20 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
             HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, nd.depth + 1, child_buf};
             HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, nd.depth + 1, child_buf};
-            if (nomove) {
-                lc.virt = 2 * (int32_t)unmoved.size();
-                rc.virt = lc.virt + 1;
-                unmoved.push_back(UnmovedSplit{nd.begin, nd.len, wcur, (uint32_t)sp.feature, (uint32_t)sp.bin,
-                                               (uint32_t)sp.default_left});
+            if (nomove) {   // a new segment of rows that stay in place: the children are its heap positions 1 and 2
+                UnmovedSeg u{};
+                u.begin = nd.begin;
+                u.len = nd.len;
+                u.buf = wcur;
+                u.set(0, sp);
+                lc.virt = rc.virt = (int32_t)unmoved.size();
+                lc.vpos = 1;
+                rc.vpos = 2;
+                unmoved.push_back(u);
+            } else if (nomove2) {   // one level further down in the same segment
+                lc.virt = rc.virt = nd.virt;
+                lc.vpos = 2 * nd.vpos + 1;
+                rc.vpos = 2 * nd.vpos + 2;
             }
             n_nodes += 2;
             if (lossguide) {   // physical children; the caller's tree learns of them when their parent is popped

@@ -27,7 +27,7 @@ struct gbt_ctx {
     int hist_runtime_bits;  // 1: unpack with run-time shifts even where a compile-time kernel exists
     int part_fused;         // 1: one-launch record partition where it applies
     int lossguide_batch;    // open leaves a round of loss-guided growth expands at once (1: only the one whose turn it is)
-    int part_nomove;        // 1: the last histogram level of a depth-wise tree is built without moving rows (partition + histogram pass)
+    int part_nomove;        // partition + histogram path, depth-wise: 1: the last histogram level is built without moving rows; 2: the last two
     int part_ids;           // 1: rows wider than 64 words are not moved: id lists are partitioned and the histogram kernel gathers
     int order_rows;         // 1: a caller's row order is made from the finished tree, so that it does not restrict the partition form
     int hist_fix;           // 1: the root histogram kernel also converts the gradient pairs where that applies
@@ -107,9 +107,24 @@ struct PartJob {
 struct CountJob {
     uint32_t seg_begin, seg_len;
     uint32_t tile_begin, n_tiles;
-    uint32_t feature[3], bin[3], default_left[3];
-    uint32_t has[2];
+    // the splits below the segment in heap order: 0 the segment's own, 1 and 2 its left / right child's,
+    // 3..6 the grandchildren's (left to right); has[p]: node p splits (0 always does)
+    uint32_t feature[7], bin[7], default_left[7];
+    uint32_t has[7];
     uint32_t pad;
+};
+
+// One segment for the histogram pass over rows that were not moved at the segment's own split: the
+// split tells each row's child (0 left, 1 right), the child's split (if it has one) the row's side there.
+// Of each splitting child's two children one histogram is built (build[c]: 1 the left, 0 the right)
+// into hist_off[c]; cursor word 2 * job + c counts the child's left rows.
+struct Hist2Job {
+    uint32_t seg_begin, seg_len;
+    uint32_t tile_begin, n_tiles;   // in spans of rows_per_span rows
+    uint32_t feature[3], bin[3], default_left[3];
+    uint32_t has[2], build[2];
+    uint32_t pad;
+    uint64_t hist_off[2];
 };
 
 
@@ -220,11 +235,21 @@ hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t str
 // the histogram is built and the low word of each cursor counts the left rows.
 // The cursors (one 64-bit word per job) are cleared here unless the caller says they are zero already.
 bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B);
-// Rows of 8-bit symbols, row p at byte p * stride_bytes of `rows`: counts[2 * j + c] = rows of job j's
-// child c that go left at that child's split.  counts is cleared here.
+// Rows of 8-bit symbols, row p at byte p * stride_bytes of `rows`.  levels = 1: counts[2 * j + c] = rows
+// of job j's child c that go left at that child's split; levels = 2: counts[4 * j + t] the same for
+// grandchild t (heap position 3 + t).  Rows that reach a node without a split on their way are not
+// counted.  counts is cleared here.
 int gbt_count2_tile();
 hipError_t gbt_launch_count2(hipStream_t s, const uint8_t *rows, int64_t stride_bytes, uint32_t missing,
-                             const CountJob *jobs, int n_jobs, int n_tiles, uint32_t *counts);
+                             const CountJob *jobs, int n_jobs, int n_tiles, uint32_t *counts, int levels = 1,
+                             bool records_ok = false);   // records_ok: rows are records of the partition + histogram pass
+// The histogram pass over record segments that stay in place for a second level (Hist2Job); 8-bit symbols,
+// at most 16 features, two LDS histograms per workgroup (gbt_hist2_ok).  cursor: 2 words per job, cleared
+// here unless the caller says they are zero; the built children's histograms must have been cleared.
+bool gbt_hist2_ok(const gbt_ctx *ctx, int F, int B);
+hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B, uint32_t missing,
+                            const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                            unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false);
 int gbt_part_hist_tile();
 int gbt_part_hist_record_words(int F);
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,

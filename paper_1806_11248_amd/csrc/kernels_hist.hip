@@ -853,6 +853,135 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
 }
 
+// Rows that were not moved at their segment's split and are not moved now: every row belongs to one
+// of the segment's two children, whose split (if it has one) sends it left or right; of each splitting
+// child's two children one histogram is built.  A workgroup keeps BOTH histograms in LDS and takes a
+// span of the segment tile by tile, the next tile's records on their way while the current one is
+// added; no ranks, no stores, no barriers inside the span.  Left rows of the children are counted in
+// the cursor words 2 * job and 2 * job + 1.
+constexpr int kH2Block = 1024;
+template <int NS, bool CHK>
+__global__ __launch_bounds__(kH2Block) void hist2_kernel(
+    const uint32_t *__restrict__ src, int ft, int B, int Bp, uint32_t missing, const Hist2Job *__restrict__ jobs,
+    int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
+    constexpr int SW = (NS + 3) / 4;
+    constexpr int RW = record_words(NS);
+    constexpr int ROWS = kPFRows, TILE = kH2Block * ROWS, WAVES = kH2Block / 64;
+    extern __shared__ unsigned long long lds[];
+    int lo = 0, hi = n_jobs;   // last job with tile_begin <= this span
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (jobs[mid].tile_begin <= blockIdx.x) lo = mid; else hi = mid;
+    }
+    const int ji = lo;
+    const Hist2Job job = jobs[ji];
+    const uint32_t span_begin = (blockIdx.x - job.tile_begin) * rows_per_span;
+    const uint32_t span_rows = job.seg_len - span_begin < rows_per_span ? job.seg_len - span_begin : rows_per_span;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    const int trash = ft * Bp;
+    const int n_acc = trash + 256;
+    // histogram c: words [c * n_acc, (c + 1) * n_acc) of the accumulators, then of the side counters
+    unsigned long long *main0 = lds;
+    uint32_t *side0 = (uint32_t *)(lds + 2 * n_acc);
+    for (int i = threadIdx.x; i < 2 * n_acc; i += kH2Block) {
+        main0[i] = 0;
+        side0[i] = 0;
+    }
+    uint32_t selA[4], selB[4];
+    int pre[NS];
+    {
+        const int l0 = lane % ft;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            selA[k] = 0;
+            selB[k] = 0;
+        }
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            int t = j + l0;
+            t = t >= ft ? t - ft : t;
+            const bool live = j < ft;
+            pre[j] = live ? t * Bp : trash + lane;
+            const uint32_t a = (live && t < 8) ? (uint32_t)t : 0x0Cu;
+            const uint32_t b = (live && t >= 8) ? (uint32_t)(t - 8) : 0x0Cu;
+            selA[j >> 2] |= a << (8 * (j & 3));
+            selB[j >> 2] |= b << (8 * (j & 3));
+        }
+    }
+    // byte `feature` of a record for the three splits (see part_hist_kernel)
+    uint32_t fselA[3], fselB[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        fselA[k] = 0x0C0C0C00u | (job.feature[k] < 8u ? job.feature[k] : 0x0Cu);
+        fselB[k] = 0x0C0C0C00u | (job.feature[k] >= 8u ? job.feature[k] - 8u : 0x0Cu);
+    }
+    uint32_t my_lefts[2] = {0, 0};
+    const uint64_t span_first = (uint64_t)job.seg_begin + span_begin;
+    __syncthreads();
+
+    auto byte_of = [&](const uint32_t (&row)[RW], uint32_t sa, uint32_t sb) __attribute__((always_inline)) {
+        return __builtin_amdgcn_perm(SW > 1 ? row[SW > 1 ? 1 : 0] : 0u, row[0], sa) |
+               __builtin_amdgcn_perm(SW > 3 ? row[SW > 3 ? 3 : 0] : 0u, SW > 2 ? row[SW > 2 ? 2 : 0] : 0u, sb);
+    };
+    auto load_tile = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
+            if (in_tile < tile_rows) {
+                const uint32_t *rp = src + (span_first + done + in_tile) * RW;
+#pragma unroll
+                for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+            }
+        }
+    };
+    auto process = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
+            bool left1 = false, counted = false;
+            int c = 0;
+            if (in_tile < tile_rows) {
+                const uint32_t s0 = byte_of(row[j], fselA[0], fselB[0]);
+                const bool left0 = (s0 == missing) ? (job.default_left[0] != 0) : (s0 <= job.bin[0]);
+                c = left0 ? 0 : 1;
+                const uint32_t s1 = byte_of(row[j], left0 ? fselA[1] : fselA[2], left0 ? fselB[1] : fselB[2]);
+                const uint32_t bin1 = left0 ? job.bin[1] : job.bin[2];
+                const uint32_t dl1 = left0 ? job.default_left[1] : job.default_left[2];
+                left1 = (s1 == missing) ? (dl1 != 0) : (s1 <= bin1);
+                counted = (left0 ? job.has[0] : job.has[1]) != 0;
+            }
+            const uint64_t b0 = __ballot(counted && c == 0 && left1), b1 = __ballot(counted && c == 1 && left1);
+            my_lefts[0] += (uint32_t)__popcll(b0);
+            my_lefts[1] += (uint32_t)__popcll(b1);
+            const bool take = counted && (left1 == ((c == 0 ? job.build[0] : job.build[1]) == 1u));
+            if (take)
+                ph_add_row<NS, CHK, RW>(row[j], main0 + c * n_acc, side0 + c * n_acc, pre, selA, selB, trash, lane, missing, B);
+        }
+    };
+
+    uint32_t rowA[ROWS][RW], rowB[ROWS][RW];
+    load_tile(rowA, 0);
+    for (uint32_t done = 0; done < span_rows;) {
+        if (done + TILE < span_rows) load_tile(rowB, done + TILE);
+        process(rowA, done);
+        done += TILE;
+        if (done >= span_rows) break;
+        if (done + TILE < span_rows) load_tile(rowA, done + TILE);
+        process(rowB, done);
+        done += TILE;
+    }
+    if (lane == 0) {
+        if (my_lefts[0]) atomicAdd(&cursor[2 * ji], (unsigned long long)my_lefts[0]);
+        if (my_lefts[1]) atomicAdd(&cursor[2 * ji + 1], (unsigned long long)my_lefts[1]);
+    }
+    __syncthreads();
+    if (job.has[0]) flush_tile(main0, side0, ft, B, Bp, pool + job.hist_off[0], kH2Block);
+    if (job.has[1]) flush_tile(main0 + n_acc, side0 + n_acc, ft, B, Bp, pool + job.hist_off[1], kH2Block);
+}
+
 inline int padded_bins(int B) { return B | 1; }   // odd stride: see the note on LDS banks above
 
 }  // namespace
@@ -1073,6 +1202,53 @@ bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B) {
     return lds <= cap && lds <= ctx->lds_per_block;
 }
 int gbt_part_hist_tile() { return kPHTile; }
+
+bool gbt_hist2_ok(const gbt_ctx *ctx, int F, int B) {
+    if (F > 16 || B > 256) return false;
+    return 2 * ((size_t)F * padded_bins(B) + 256) * 12 <= ctx->lds_per_block;
+}
+namespace {
+template <int NS, bool CHK>
+hipError_t launch_hist2(gbt_ctx *ctx, size_t lds, const uint32_t *records, int ft, int B, int Bp, uint32_t missing,
+                        const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                        unsigned long long *cursor, int64_t *pool) {
+    static size_t configured = 0;
+    if (lds > configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)hist2_kernel<NS, CHK>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+        configured = lds;
+    }
+    hist2_kernel<NS, CHK><<<n_spans, kH2Block, lds, ctx->stream>>>(records, ft, B, Bp, missing, jobs, n_jobs, rows_per_span,
+                                                                   cursor, pool);
+    return hipGetLastError();
+}
+template <bool CHK>
+hipError_t pick_hist2(int ft, gbt_ctx *ctx, size_t lds, const uint32_t *records, int B, int Bp, uint32_t missing,
+                      const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span, unsigned long long *cursor,
+                      int64_t *pool) {
+    if (ft <= 4) return launch_hist2<4, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
+    if (ft <= 8) return launch_hist2<8, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
+    if (ft <= 12) return launch_hist2<12, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
+    if (ft == 13) return launch_hist2<13, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
+    return launch_hist2<16, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
+}
+}  // namespace
+
+hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B, uint32_t missing,
+                            const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                            unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero) {
+    if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
+    if (!cursors_are_zero) {
+        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 2 * (int64_t)n_jobs);
+        if (e != hipSuccess) return e;
+    }
+    const int Bp = padded_bins(B);
+    const size_t lds = 2 * ((size_t)F * Bp + 256) * 12;
+    const bool chk = missing < 256u || B < 256;
+    return chk ? pick_hist2<true>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool)
+               : pick_hist2<false>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool);
+}
 int gbt_part_hist_record_words(int F) { return record_words(slots_for(F)); }
 
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,

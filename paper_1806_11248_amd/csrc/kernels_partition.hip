@@ -581,57 +581,110 @@ hipError_t gbt_launch_partition_records(hipStream_t s, const GbtRows &src, const
 namespace {
 constexpr int kC2Block = 512, kC2Rows = 8, kC2Tile = kC2Block * kC2Rows;
 
+// LEVELS splits lie between the segment and the nodes whose left rows are counted: a row is taken down
+// from the segment's own split and counted at the node it reaches if that node splits.
+// RECORDS: the rows are records of whole words whose first 16 bytes hold every symbol: they are loaded
+// once (all of a thread's rows before the first is used) and a split's byte is cut out with v_perm;
+// otherwise (rows of the packed matrix, any byte stride) one dependent byte load per level.
+template <int LEVELS, bool RECORDS>
 __global__ __launch_bounds__(kC2Block) void count2_kernel(const uint8_t *__restrict__ rows, int64_t stride_bytes,
                                                           uint32_t missing, const CountJob *__restrict__ jobs,
                                                           int n_jobs, uint32_t *__restrict__ counts) {
-    __shared__ uint32_t acc[2];
+    constexpr int NT = 1 << LEVELS;          // target nodes per job
+    constexpr int FIRST_T = NT - 1;          // heap position of the first target
+    __shared__ uint32_t acc[NT];
+    __shared__ CountJob sjob;
     int lo = 0, hi = n_jobs;   // last job with tile_begin <= this tile
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (jobs[mid].tile_begin <= blockIdx.x) lo = mid; else hi = mid;
     }
-    const CountJob job = jobs[lo];
-    if (threadIdx.x < 2) acc[threadIdx.x] = 0;
+    if (threadIdx.x < (int)(sizeof(CountJob) / 4)) ((uint32_t *)&sjob)[threadIdx.x] = ((const uint32_t *)&jobs[lo])[threadIdx.x];
+    if (threadIdx.x < NT) acc[threadIdx.x] = 0;
     __syncthreads();
+    const CountJob &job = sjob;
     const uint32_t t0 = (blockIdx.x - job.tile_begin) * (uint32_t)kC2Tile;
-    uint32_t s0[kC2Rows], s1[kC2Rows], s2[kC2Rows];
+    const uint8_t *rp[kC2Rows];
+    uint4 rec[RECORDS ? kC2Rows : 1];
+    uint32_t pos[kC2Rows];     // heap position of the node the row has reached; 0xff: out of the count
+    uint32_t sy[kC2Rows];
+    auto symbol = [&](int j, uint32_t f) __attribute__((always_inline)) -> uint32_t {
+        if (RECORDS) {
+            const uint32_t sa = 0x0C0C0C00u | (f < 8u ? f : 0x0Cu), sb = 0x0C0C0C00u | (f >= 8u ? f - 8u : 0x0Cu);
+            return __builtin_amdgcn_perm(rec[RECORDS ? j : 0].y, rec[RECORDS ? j : 0].x, sa) |
+                   __builtin_amdgcn_perm(rec[RECORDS ? j : 0].w, rec[RECORDS ? j : 0].z, sb);
+        }
+        return rp[j][f];
+    };
 #pragma unroll
-    for (int j = 0; j < kC2Rows; ++j) {   // every load of the tile is issued before the first is used
+    for (int j = 0; j < kC2Rows; ++j) {   // every load of the tile (of a level) is issued before the first is used
         const uint32_t i = t0 + (uint32_t)j * kC2Block + threadIdx.x;
         const uint32_t ic = i < job.seg_len ? i : job.seg_len - 1;
-        const uint8_t *rp = rows + ((uint64_t)job.seg_begin + ic) * (uint64_t)stride_bytes;
-        s0[j] = rp[job.feature[0]];
-        s1[j] = rp[job.feature[1]];
-        s2[j] = rp[job.feature[2]];
+        rp[j] = rows + ((uint64_t)job.seg_begin + ic) * (uint64_t)stride_bytes;
+        pos[j] = i < job.seg_len ? 0u : 0xffu;
+        if (RECORDS) {
+            const uint32_t *w = (const uint32_t *)rp[j];
+            rec[RECORDS ? j : 0] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
     }
-    uint32_t c0 = 0, c1 = 0;
 #pragma unroll
-    for (int j = 0; j < kC2Rows; ++j) {
-        const uint32_t i = t0 + (uint32_t)j * kC2Block + threadIdx.x;
-        const bool live = i < job.seg_len;
-        const bool left0 = s0[j] == missing ? job.default_left[0] != 0 : s0[j] <= job.bin[0];
-        const uint32_t sc = left0 ? s1[j] : s2[j];
-        const int c = left0 ? 1 : 2;
-        const bool leftc = sc == missing ? job.default_left[c] != 0 : sc <= job.bin[c];
-        c0 += (uint32_t)__popcll(__ballot(live && left0 && leftc));
-        c1 += (uint32_t)__popcll(__ballot(live && !left0 && leftc));
+    for (int j = 0; j < kC2Rows; ++j) sy[j] = symbol(j, job.feature[0]);
+    unsigned long long mine = 0;   // 16 bits per target: rows of this thread counted there
+#pragma unroll
+    for (int l = 0; l <= LEVELS; ++l) {
+#pragma unroll
+        for (int j = 0; j < kC2Rows; ++j) {
+            if (pos[j] != 0xffu) {
+                const uint32_t p = pos[j];
+                const bool left = sy[j] == missing ? job.default_left[p] != 0 : sy[j] <= job.bin[p];
+                if (l == LEVELS) {
+                    if (left) mine += 1ull << (16 * (p - FIRST_T));
+                } else {
+                    const uint32_t q = 2u * p + (left ? 1u : 2u);
+                    pos[j] = job.has[q] ? q : 0xffu;
+                }
+            }
+        }
+        if (l < LEVELS) {
+#pragma unroll
+            for (int j = 0; j < kC2Rows; ++j) sy[j] = pos[j] != 0xffu ? symbol(j, job.feature[pos[j]]) : 0u;
+        }
     }
+    for (int o = 32; o > 0; o >>= 1) {   // a field holds at most 64 * kC2Rows
+        const uint32_t a = (uint32_t)__shfl_xor((int)(uint32_t)mine, o), b = (uint32_t)__shfl_xor((int)(uint32_t)(mine >> 32), o);
+        mine += ((unsigned long long)b << 32) | a;
+    }
+    static_assert(64 * kC2Rows < 65536, "16-bit fields");
     if ((threadIdx.x & 63) == 0) {
-        if (c0) atomicAdd(&acc[0], c0);
-        if (c1) atomicAdd(&acc[1], c1);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const uint32_t c = (uint32_t)(mine >> (16 * t)) & 0xffffu;
+            if (c) atomicAdd(&acc[t], c);
+        }
     }
     __syncthreads();
-    if (threadIdx.x < 2 && acc[threadIdx.x] && job.has[threadIdx.x]) atomicAdd(&counts[2 * lo + threadIdx.x], acc[threadIdx.x]);
+    if (threadIdx.x < NT && acc[threadIdx.x]) atomicAdd(&counts[NT * lo + threadIdx.x], acc[threadIdx.x]);
 }
 }  // namespace
 
 int gbt_count2_tile() { return kC2Tile; }
 hipError_t gbt_launch_count2(hipStream_t s, const uint8_t *rows, int64_t stride_bytes, uint32_t missing,
-                             const CountJob *jobs, int n_jobs, int n_tiles, uint32_t *counts) {
+                             const CountJob *jobs, int n_jobs, int n_tiles, uint32_t *counts, int levels, bool records_ok) {
     if (n_jobs <= 0) return hipSuccess;
-    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)counts, 0, n_jobs);   // two 32-bit counts per job
+    if (levels != 1 && levels != 2) return hipErrorInvalidValue;
+    hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)counts, 0, (int64_t)n_jobs * levels);   // 2 or 4 32-bit counts per job
     if (e != hipSuccess || n_tiles <= 0) return e;
-    count2_kernel<<<n_tiles, kC2Block, 0, s>>>(rows, stride_bytes, missing, jobs, n_jobs, counts);
+    // records: whole words per row, 4-byte aligned, at least 16 readable bytes from every row's start (the
+    // working copies end in spare words), every feature index below 16
+    const bool records = (stride_bytes & 3) == 0 && ((uintptr_t)rows & 3u) == 0 && records_ok;
+    if (levels == 1 && records)
+        count2_kernel<1, true><<<n_tiles, kC2Block, 0, s>>>(rows, stride_bytes, missing, jobs, n_jobs, counts);
+    else if (levels == 1)
+        count2_kernel<1, false><<<n_tiles, kC2Block, 0, s>>>(rows, stride_bytes, missing, jobs, n_jobs, counts);
+    else if (records)
+        count2_kernel<2, true><<<n_tiles, kC2Block, 0, s>>>(rows, stride_bytes, missing, jobs, n_jobs, counts);
+    else
+        count2_kernel<2, false><<<n_tiles, kC2Block, 0, s>>>(rows, stride_bytes, missing, jobs, n_jobs, counts);
     return hipGetLastError();
 }
 

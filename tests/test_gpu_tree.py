@@ -277,25 +277,35 @@ def test_boosting_rounds_in_lock_step(ctx, oracle):
             assert np.allclose(margin_gpu.cpu().numpy(), margin_ref, rtol=1e-5, atol=1e-6)
 
 
-@pytest.mark.parametrize("depth", [1, 2, 3, 6])
-def test_last_levels_without_moving_rows(ctx, ctx_env, oracle, depth):
-    """Byte symbols, at most 16 features: the level above the last split level builds its children's
-    histograms without moving rows and the leaves' row counts come from a two-level count (depth 2:
-    straight from the packed matrix).  Same trees as with the rows moved at every level."""
-    d = synth.make(4, 120_000)
+@pytest.mark.parametrize("depth,F,miss", [(1, 13, 0.0), (2, 13, 0.0), (3, 13, 0.0), (4, 13, 0.0), (5, 13, 0.0),
+                                          (6, 13, 0.0), (8, 13, 0.0), (7, 16, 0.1), (6, 3, 0.0), (9, 8, 0.3)])
+def test_last_levels_without_moving_rows(ctx, ctx_env, oracle, depth, F, miss):
+    """Byte symbols, at most 16 features: the last two levels that need histograms are built without
+    moving rows (the second of them with two histograms per workgroup over the first one's segments)
+    and the leaves' row counts come from a count over up to three levels of splits (depth 2:
+    straight from the packed matrix).  Same trees as with one such level, and as with the rows moved
+    at every level."""
+    n = 120_000
+    d = synth.make(4, n)
+    rng = np.random.default_rng(100 * depth + F)
+    X = d["X"] if F == 13 and miss == 0.0 else d["X"][:, rng.integers(0, d["X"].shape[1], F)].copy()
+    if miss > 0:
+        X = X + rng.normal(0, 0.01, X.shape).astype(np.float32)
+        X[rng.random(X.shape) < miss] = np.nan
     p = dict(d["params"], max_depth=depth)
-    n, F = d["X"].shape
-    _say(f"no-move last levels, depth {depth}")
-    o, gdev = gpu_prep(ctx, oracle, d)
+    n, F = X.shape
+    _say(f"no-move last levels, depth {depth} F={F} missing={miss}")
+    o, gdev = gpu_prep(ctx, oracle, dict(X=X, params=p))
     gp = oracle.gradients(p["objective"], np.zeros(n, np.float32), d["y"])
     tree, rep = grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
     import paper_1806_11248_amd as g
     params = g.make_params(max_depth=depth, max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
                            min_child_weight=p["min_child_weight"])
-    moved, _, _ = ctx_env(GBT_TUNE_PART_NOMOVE=0).grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"],
-                                                          gdev["nb"], gdev["cuts"], dev(gp), params, want_rows=False,
-                                                          want_leaf=False)
     nn = tree["n_nodes"]
-    assert moved["n_nodes"] == nn
-    for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "weight", "gain"):
-        assert np.array_equal(moved[k][:nn], tree[k][:nn]), k
+    for levels in (0, 1):
+        other, _, _ = ctx_env(GBT_TUNE_PART_NOMOVE=levels).grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"],
+                                                                    gdev["nb"], gdev["cuts"], dev(gp), params,
+                                                                    want_rows=False, want_leaf=False)
+        assert other["n_nodes"] == nn
+        for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "weight", "gain", "sumG", "sumH"):
+            assert np.array_equal(other[k][:nn], tree[k][:nn]), (levels, k)
