@@ -268,7 +268,7 @@ def main():
     # which kernels the classes of the library's profile stand for on this shape
     path = ctx.grow_tree_path(F, bits, p["max_bins"], track_rows=False)
     hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_static_kernel"
-    node_kernel = "part_hist_kernel (partition + one child's histogram in one pass)" if path == 2 else hist_kernel
+    node_kernel = "part_hist_first_kernel / part_hist_kernel / hist2_kernel (partition + one child's histogram in one pass; the last two of the seven launches move nothing)" if path == 2 else hist_kernel
     part_kernel = ("count2_kernel (row counts of the leaves)" if path == 2 and not lossguide else
                    "part_flag_kernel + part_scan_kernel (row counts of the last level)" if path == 2 else
                    ("part_fused_kernel" if (F * bits + 31) // 32 == 4 else "part_staged_kernel") if path == 1 else
