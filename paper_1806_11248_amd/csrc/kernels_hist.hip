@@ -27,6 +27,23 @@
 namespace {
 
 constexpr int kHistBlock = 1024;
+// Four consecutive words with ONE load instruction at 4-byte alignment (rows of packed symbols start at any byte).
+typedef uint32_t gbt_u32x4 __attribute__((ext_vector_type(4), aligned(4)));
+template <int N>
+__device__ __forceinline__ void load_words(uint32_t (&x)[N], const uint32_t *p) {
+    static_assert(N >= 1 && N <= 5, "a 16-byte window and the word behind it");
+    if (N >= 4) {
+        const gbt_u32x4 v = *(const gbt_u32x4 *)p;
+        x[0] = v.x;
+        x[1] = v.y;
+        x[2] = v.z;
+        x[3] = v.w;
+        if (N == 5) x[N - 1] = p[4];
+    } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x[k] = p[k];
+    }
+}
 constexpr int kHShift = 30;                        // width of the h field
 constexpr uint32_t kHMask = (1u << kHShift) - 1u;
 
@@ -288,7 +305,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
         int c = SINGLE ? 0 : (lane * nchunks) >> 6;
         for (int cc = 0; cc < (SINGLE ? 1 : nchunks); ++cc) {
             // words past the end of the buffer hold no bit of this row: read the last word instead
-            uint32_t w[5];
+            uint32_t w[5];   // (five single-word loads: one 16-byte load and a branch for the buffer's end measured slower here)
 #pragma unroll
             for (int k = 0; k < 5; ++k) {
                 const int64_t wi = w0 + 4 * c + k;
@@ -612,8 +629,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
                     const uint32_t sh = (uint32_t)(sb & 3);
                     uint32_t x[SW + 1];
                     if (tile_inside) {
-#pragma unroll
-                        for (int k = 0; k <= SW; ++k) x[k] = src[s0 + k];
+                        load_words(x, src + s0);
                     } else {   // the matrix ends inside this tile's last window: read the last word instead
 #pragma unroll
                         for (int k = 0; k <= SW; ++k) x[k] = src[s0 + k < src_words ? s0 + k : src_words - 1];
