@@ -322,6 +322,27 @@ hipError_t gbt_launch_predict_raw_batched(hipStream_t s, const gbt_batch_node *n
                                           const int32_t *group_end, int n_groups, int cap_nodes, const float *X,
                                           int64_t n, int F, double eta, float *margin);
 
+// Four consecutive words with ONE load instruction at 4-byte alignment (rows of packed symbols start at any byte).
+typedef uint32_t gbt_u32x4 __attribute__((ext_vector_type(4), aligned(4)));
+template <int N>
+__device__ __forceinline__ void load_words(uint32_t (&x)[N], const uint32_t *p) {
+    static_assert(N >= 1 && N <= 5, "a 16-byte window and the word behind it");
+    if (N >= 4) {
+        const gbt_u32x4 v = *(const gbt_u32x4 *)p;
+        x[0] = v.x;
+        x[1] = v.y;
+        x[2] = v.z;
+        x[3] = v.w;
+        if (N == 5) x[N - 1] = p[4];
+    } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) x[k] = p[k];
+    }
+}
+constexpr int kHShift = 30;                        // width of the h field
+constexpr uint32_t kHMask = (1u << kHShift) - 1u;
+
+
 // quantise
 hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
                             const float *values, int64_t n, int F, int64_t n_values, int B, float *cuts,

@@ -27,26 +27,6 @@
 namespace {
 
 constexpr int kHistBlock = 1024;
-// Four consecutive words with ONE load instruction at 4-byte alignment (rows of packed symbols start at any byte).
-typedef uint32_t gbt_u32x4 __attribute__((ext_vector_type(4), aligned(4)));
-template <int N>
-__device__ __forceinline__ void load_words(uint32_t (&x)[N], const uint32_t *p) {
-    static_assert(N >= 1 && N <= 5, "a 16-byte window and the word behind it");
-    if (N >= 4) {
-        const gbt_u32x4 v = *(const gbt_u32x4 *)p;
-        x[0] = v.x;
-        x[1] = v.y;
-        x[2] = v.z;
-        x[3] = v.w;
-        if (N == 5) x[N - 1] = p[4];
-    } else {
-#pragma unroll
-        for (int k = 0; k < N; ++k) x[k] = p[k];
-    }
-}
-constexpr int kHShift = 30;                        // width of the h field
-constexpr uint32_t kHMask = (1u << kHShift) - 1u;
-
 __device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long long old,
                                          unsigned long long addv, uint32_t hq);
 

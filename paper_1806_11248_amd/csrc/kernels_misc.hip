@@ -495,8 +495,12 @@ __global__ __launch_bounds__(256) void predict_b8_kernel(const char *ws, const D
                 const int64_t w0 = (int64_t)(byte0 >> 2);
                 const uint32_t a = (uint32_t)(byte0 & 3);
                 uint32_t w[5];
+                if (w0 + 4 < n_words) {   // (all but the last rows of the matrix) one 16-byte load and one word
+                    load_words(w, packed + w0);
+                } else {
 #pragma unroll
-                for (int k = 0; k < 5; ++k) w[k] = packed[w0 + k < n_words ? w0 + k : n_words - 1];
+                    for (int k = 0; k < 5; ++k) w[k] = packed[w0 + k < n_words ? w0 + k : n_words - 1];
+                }
 #pragma unroll
                 for (int k = 0; k < 4; ++k) W[q][k] = __builtin_amdgcn_alignbyte(w[k + 1], w[k], a);
                 m[q] = leaf_out ? 0.f : margin[r];
