@@ -34,6 +34,12 @@ def test_gradients(ctx, oracle, objective):
     assert np.allclose(gp, ref, rtol=1e-6, atol=1e-7)
     assert (gp != ref).mean() < 1e-3      # both sides evaluate in fp64 and round once
     assert ctx.gradients(objective, dev(m[:0]), dev(y[:0])).shape == (0, 2)
+    # arrays that do not start on a 16-byte boundary, and lengths around the four instances a thread takes at once
+    mt, yt = dev(m), dev(y)
+    for off, k in ((1, 1), (1, 6), (2, 4099), (3, 1001), (0, 3), (0, 7)):
+        out = torch.empty((k + 1, 2), dtype=torch.float32, device="cuda")[1:] if off & 1 else None
+        got = ctx.gradients(objective, mt[off:off + k], yt[off:off + k], out=out).cpu().numpy()
+        assert np.array_equal(got, gp[off:off + k]), (off, k)
 
 
 # ------------------------------------------------------------------- quantise --
