@@ -268,7 +268,10 @@ def main():
     # which kernels the classes of the library's profile stand for on this shape
     path = ctx.grow_tree_path(F, bits, p["max_bins"], track_rows=False)
     hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_static_kernel"
-    node_kernel = "part_hist_first_kernel / part_hist_kernel / hist2_kernel (partition + one child's histogram in one pass; the last two of the seven launches move nothing)" if path == 2 else hist_kernel
+    # (path 2: the pass has three kernels, each a profile class of its own; this is the one that reads and
+    # writes records, every level but the first and the last: its launches are the ones rocprofv3 lists
+    # under this name, the no-move launch of the second-to-last level included)
+    node_kernel = "part_hist_kernel (partition + one child's histogram in one pass)" if path == 2 else hist_kernel
     part_kernel = ("count2_kernel (row counts of the leaves)" if path == 2 and not lossguide else
                    "part_flag_kernel + part_scan_kernel (row counts of the last level)" if path == 2 else
                    ("part_fused_kernel" if (F * bits + 31) // 32 == 4 else "part_staged_kernel") if path == 1 else
@@ -279,6 +282,8 @@ def main():
         part_kernel = "sparse_part_kernel"
     roofline_root = roof(["hist_root"], hist_kernel)
     roofline_node = roof(["hist_node"], node_kernel)
+    roofline_first = roof(["hist_first"], "part_hist_first_kernel (the same pass at level 0, from the packed matrix)")
+    roofline_inplace = roof(["hist_inplace"], "hist2_kernel (the pass at the last level: rows in place, two histograms per workgroup)")
     roofline_partition = roof(["partition"], part_kernel)
     traffic = None if sparse else measured_traffic(a.config)
     if traffic:
@@ -318,6 +323,8 @@ def main():
         "roofline": roofline,
         "roofline_hist_root": roofline_root,
         "roofline_hist_node": roofline_node,
+        "roofline_hist_first_level": roofline_first,
+        "roofline_hist_in_place": roofline_inplace,
         "roofline_partition": roofline_partition,
         "grow_tree_path": path,
         "device_ms_per_step": {k: v["ms"] / a.steps for k, v in prof.items()},

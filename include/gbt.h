@@ -393,7 +393,11 @@ GBT_API int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t 
 #define GBT_PROF_EVAL 3      /* split evaluation, sibling subtraction included */
 #define GBT_PROF_CLEAR 4     /* zero-fill of the children's histograms */
 #define GBT_PROF_OTHER 5     /* scale search, fixed-point conversion, tree walks (leaf ids, prediction), row order */
-#define GBT_PROF_CLASSES 6
+/* The partition + histogram pass has three kernels; GBT_PROF_HIST_NODE holds the one that reads and writes
+ * records (every level but the first, the second-to-last no-move level included), these two the others: */
+#define GBT_PROF_HIST_FIRST 6   /* its first level, whose source is the caller's packed matrix */
+#define GBT_PROF_HIST_INPLACE 7 /* its last level where two levels stay in place (two histograms per workgroup) */
+#define GBT_PROF_CLASSES 8
 
 typedef struct gbt_profile {
     double ms[GBT_PROF_CLASSES];        /* device time between HIP events around the launches */

@@ -32,7 +32,7 @@ SYMBOLS = [
     "gbt_build_hist_sparse", "gbt_grow_tree_sparse_workspace_bytes", "gbt_grow_tree_sparse", "gbt_predict_sparse",
 ]
 
-PROF_CLASSES = ["hist_root", "hist_node", "partition", "eval", "clear", "other"]
+PROF_CLASSES = ["hist_root", "hist_node", "partition", "eval", "clear", "other", "hist_first", "hist_inplace"]
 
 
 class GbtError(RuntimeError):
@@ -54,7 +54,7 @@ class Split(C.Structure):
 
 
 class Profile(C.Structure):
-    _fields_ = [("ms", C.c_double * 6), ("bytes", C.c_double * 6), ("launches", C.c_int64 * 6)]
+    _fields_ = [("ms", C.c_double * 8), ("bytes", C.c_double * 8), ("launches", C.c_int64 * 8)]
 
 
 class Tree(C.Structure):

@@ -1207,7 +1207,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 gbt_prof_end(ctx);
             }
             const double rec_bytes = row_bits / 8.0 + 8.0;
-            gbt_prof_begin(ctx, with_hist ? GBT_PROF_HIST_NODE : GBT_PROF_PARTITION,
+            gbt_prof_begin(ctx, nomove2 ? GBT_PROF_HIST_INPLACE : with_hist ? (wcur == 2 ? GBT_PROF_HIST_FIRST : GBT_PROF_HIST_NODE)
+                                                                            : GBT_PROF_PARTITION,
                            nomove2 ? (double)h2_rows * rec_bytes :
                            part_rows * (path == 3 ? 8.0 + 32.0   // ids read and written, one sector of symbols per row
                                         : nomove  ? rec_bytes
