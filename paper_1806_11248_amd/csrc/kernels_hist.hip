@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
         int c = SINGLE ? 0 : (lane * nchunks) >> 6;
         for (int cc = 0; cc < (SINGLE ? 1 : nchunks); ++cc) {
             // words past the end of the buffer hold no bit of this row: read the last word instead
-            uint32_t w[5];   // (five single-word loads: one 16-byte load and a branch for the buffer's end measured slower here)
+            uint32_t w[5];   // (five single-word loads: one 16-byte load, with or without a test for the buffer's end, measured slower in this kernel)
 #pragma unroll
             for (int k = 0; k < 5; ++k) {
                 const int64_t wi = w0 + 4 * c + k;
