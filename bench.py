@@ -43,11 +43,15 @@ def load_workload(cfg, rows, cache_dir):
         fx = os.path.join(cache_dir, f"c{cfg}_{rows}_X.npy")
         fy = os.path.join(cache_dir, f"c{cfg}_{rows}_y.npy")
         if os.path.exists(fx) and os.path.exists(fy):
-            d = synth.make(cfg, 1)
-            d["X"], d["y"] = np.load(fx), np.load(fy)
-            return d
+            try:
+                d = synth.make(cfg, 1)
+                d["X"], d["y"] = np.load(fx), np.load(fy)
+                if d["X"].ndim == 2 and d["y"].shape == (d["X"].shape[0],):
+                    return d
+            except (ValueError, OSError):
+                pass   # not a cache this version wrote: make the workload again
     d = synth.make(cfg, rows)
-    if cache_dir:
+    if cache_dir and d.get("y") is not None:   # (a workload with given gradient pairs has more than X and y: not cached)
         np.save(fx, d["X"])
         np.save(fy, d["y"])
     return d
