@@ -57,3 +57,4 @@ def test_struct_layouts_match_header():
     assert C.sizeof(g.binding.Split) == 72
     assert C.sizeof(g.binding.Params) == 48
     assert C.sizeof(g.binding.Tree) == 8 + 11 * 8
+    assert C.sizeof(g.binding.Profile) == 3 * 8 * len(g.binding.PROF_CLASSES) == 3 * 8 * 8   # GBT_PROF_CLASSES
