@@ -41,6 +41,8 @@ def test_cuts_against_numpy_sort(oracle, seed):
     X[:, 1] = np.round(X[:, 1] * 2)                     # heavy ties, > B? no: few distinct
     X[:, 2] = np.where(rng.random(n) < 0.7, 0.0, X[:, 2])   # one huge tie at the minimum side
     X[:, 2] = np.abs(X[:, 2])
+    X[:, 3] = np.where(rng.random(n) < 0.5, 0.125, X[:, 3])   # many distinct values, half the rows on one of
+                                                             # them: several quantile ranks land on it
     X[rng.random((n, F)) < 0.1] = np.nan
     X[:, 4] = np.nan                                     # nothing present
     cuts, nb = oracle.cuts(X, B)
@@ -54,7 +56,10 @@ def test_cuts_against_numpy_sort(oracle, seed):
         if len(u) <= B:
             want = u[1:]
         else:
-            cand = np.unique(v[(np.arange(1, B) * m) // B])
+            cand = v[(np.arange(1, B) * m) // B]
+            if f == 3:
+                assert np.count_nonzero(cand == np.float32(0.125)) > 3
+            cand = np.unique(cand)
             want = cand[cand != v[0]]
         assert nb[f] == len(want) + 1 <= B
         assert np.array_equal(cuts[f][: len(want)], want)

@@ -230,6 +230,9 @@ def test_split_tie_break_and_min_child_weight(oracle):
     # min_child_weight larger than either side's hessian mass: no valid candidate
     sp = oracle.eval_split(h, cnt, nb, G, H, 4, 1.0, 2.5)
     assert not sp["valid"]
+    # and pricing that candidate by name says the same: a gain at weight 2 (each side holds exactly 2), none at 2.5
+    assert np.isclose(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.0)[0], 4 / 3 + 4 / 3)
+    assert np.isnan(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.5)[0])
     # a single-bin feature with nothing missing can never split
     sym1 = np.zeros((5, 1), np.uint16)
     gp1 = np.stack([np.arange(5) - 2.0, np.ones(5)], 1).astype(np.float32)

@@ -164,3 +164,24 @@ def test_replay_accepts_own_tree_and_rejects_planted_mistakes(oracle, c1):
     # row counts
     bad = copy.deepcopy(t); bad["n_rows"][2] += 1
     assert not oracle.replay_tree(bad, sym, nb, missing, gp, **kw)["ok"]
+    # a tree that is consistent throughout (counts, totals, weights, partitions) but was grown blind to
+    # the feature the root should split on: only the comparison of the gains can tell
+    nb_blind = nb.copy(); nb_blind[int(t["feature"][0])] = 1
+    blind, _, _ = oracle.grow_tree(sym, nb_blind, cuts, missing, gp, **kw)
+    assert blind["feature"][0] != t["feature"][0]
+    rep = oracle.replay_tree(blind, sym, nb, missing, gp, **kw)
+    assert not rep["ok"] and any("vs best" in e for e in rep["errors"])
+    # the same tree judged under stricter rules than it was grown with: every rule has to speak up
+    split = np.flatnonzero(t["feature"][: t["n_nodes"]] >= 0)
+    weakest = split[np.argmin(t["gain"][split])]
+    rep = oracle.replay_tree(t, sym, nb, missing, gp, **dict(kw, gamma=float(t["gain"][weakest]) * 1.01))
+    assert not rep["ok"] and any(e.startswith(f"node {weakest}: split although") for e in rep["errors"])
+    rep = oracle.replay_tree(t, sym, nb, missing, gp, **dict(kw, max_depth=kw["max_depth"] - 1))
+    assert not rep["ok"] and any("split at depth" in e for e in rep["errors"])
+    lightest = min(float(min(t["sumH"][t["left"][k]], t["sumH"][t["right"][k]])) for k in split)
+    rep = oracle.replay_tree(t, sym, nb, missing, gp, **dict(kw, min_child_weight=lightest * 1.01))
+    assert not rep["ok"] and any("is not a valid candidate" in e for e in rep["errors"])
+    # a consistent tree that stopped one level early: only "this leaf had a split due" can tell
+    shallow, _, _ = oracle.grow_tree(sym, nb, cuts, missing, gp, **dict(kw, max_depth=kw["max_depth"] - 1))
+    rep = oracle.replay_tree(shallow, sym, nb, missing, gp, **kw)
+    assert not rep["ok"] and rep["errors"] and all("leaf although" in e for e in rep["errors"])
