@@ -122,7 +122,8 @@ GBT_API size_t gbt_quantise_workspace_bytes(int64_t n, int32_t F, int64_t n_valu
  * Per-feature quantile cuts and binning.  Input is EITHER dense row-major
  * X[n][F] [dev] with NaN = missing (indptr = indices = values = NULL) OR CSR
  * (X = NULL; indptr int64[n+1], indices int32[nnz] column ids, values
- * float[nnz], all [dev]; absent entries are missing).
+ * float[nnz], all [dev]; absent entries are missing; with nnz = indptr[n] = 0
+ * indices and values may be NULL).
  *   cuts_out  [dev] float[F][max_bins-1], strictly increasing, +inf padded.
  *             With m present values v[0..m) sorted and d distinct ones:
  *             d <= max_bins: every distinct value but the smallest is a cut;
@@ -239,7 +240,10 @@ GBT_API int32_t gbt_hist_export_f64(gbt_ctx *ctx, const int64_t *hist, int32_t F
  * fp64.  The node's missing mass for feature f is (Gq, Hq) - sum_b hist[f][b];
  * it is tried on the right and, when non-zero, on the left.  Candidates are
  * ordered (feature, bin, right-before-left); a later one wins only with a
- * strictly larger gain.  A candidate needs HL, HR >= min_child_weight.
+ * strictly larger gain.  A candidate needs HL, HR >= min_child_weight.  (Rows
+ * are not counted here: a side without rows has mass exactly (0, 0), so such
+ * a candidate can only come back with a gain <= 0, below what any grower of
+ * this library accepts.)
  *   hist [dev], nb [dev] int32[F], Gq/Hq node totals (gbt_sum_gpair),
  *   scale [host] double[2], split_out [host].  workspace [dev] >= 4096 bytes.
  * Synchronises the stream.

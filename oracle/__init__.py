@@ -146,6 +146,36 @@ def gradients(objective: str, margin: np.ndarray, label: np.ndarray) -> np.ndarr
     return out
 
 
+# --------------------------------------------------- the GPU library's grid --
+G_TOP, H_TOP = 26, 22
+
+
+def fixed_point(gpair: np.ndarray):
+    """NOT from the paper: the precision the GPU library declares for its sums, restated here so that a
+    decision which depends on rounding (is this child heavy enough? which of two close gains is larger?)
+    can be taken by both sides in ONE precision.  The library rounds every g to an integer multiple of
+    1/scale_g and every h to one of 1/scale_h, ties to even, with power-of-two scales: for a largest
+    magnitude m * 2^e (0.5 <= m < 1) the scale is 2^(26 - e) for g and 2^(22 - e) for h, 1 when all are zero.
+    Returns (q int32 [n][2], (scale_g, scale_h))."""
+    gp = _c(gpair, np.float32).astype(np.float64)
+    scale = []
+    for col, top in ((0, G_TOP), (1, H_TOP)):
+        vmax = float(np.abs(gp[:, col]).max()) if len(gp) else 0.0
+        scale.append(2.0 ** (top - np.frexp(vmax)[1]) if vmax > 0.0 else 1.0)
+    q = np.rint(gp * np.array(scale)).astype(np.int32)
+    return q, (scale[0], scale[1])
+
+
+def on_grid(gpair: np.ndarray) -> np.ndarray:
+    """The pairs moved onto that grid, as fp32 (exact: an fp32 value scaled by a power of two and rounded
+    to an integer still fits 24 bits).  Sums of these in fp64 are exact, so a tree judged on them is judged
+    in the GPU library's own precision."""
+    q, scale = fixed_point(gpair)
+    out = (q.astype(np.float64) / np.array(scale)).astype(np.float32)
+    assert np.array_equal(out.astype(np.float64) * np.array(scale), q)
+    return out
+
+
 # ----------------------------------------------------------------- histogram --
 def hist(sym: np.ndarray, B: int, missing_sym: int, rows, gpair: np.ndarray):
     """Histogram of one node.  rows: uint32 row ids, or None for all rows.
@@ -366,6 +396,13 @@ def boost(sym, nb, cuts_, missing_sym, label, *, objective, rounds, eta, base_ma
 
 
 # -------------------------------------------------------------------- replay --
+def _weight_atol(w, denom, atol):
+    """How far the leaf weight w = -G / denom (denom = H + lambda) can move when G and H each move by at
+    most atol:  |-(G+dG)/(denom+dH) - w| = |dG + w*dH| / |denom + dH| <= (1 + |w|) * atol / (denom - atol).
+    (No bound when atol reaches denom: then the other side's H + lambda may be anywhere near zero.)"""
+    return (1.0 + abs(w)) * atol / (denom - atol) if denom > atol else np.inf
+
+
 def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=1.0, gamma=0.0,
                 min_child_weight=1.0, tie_rtol=1e-6, sum_rtol=1e-5, sum_atol_per_row=0.0,
                 nodes=None):
@@ -416,7 +453,7 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
             if abs(got - ref) > sum_rtol * abs(ref) + atol + 1e-300:
                 err(f"node {node}: {nm} {got!r} vs {ref!r}")
         w = -G / (H + lam)
-        w_tol = sum_rtol * abs(w) + 2.0 * atol / (H + lam)
+        w_tol = sum_rtol * abs(w) + _weight_atol(w, H + lam, atol)
         if abs(other["weight"][node] - w) > w_tol + 1e-300:
             err(f"node {node}: weight {other['weight'][node]!r} vs {w!r}")
         thr = max(gamma, GAIN_FLOOR)
@@ -495,7 +532,7 @@ def replay_tree_lossguide(other, sym, nb, missing_sym, gpair, *, max_leaves, max
             if abs(got - ref) > sum_rtol * abs(ref) + atol + 1e-300:
                 err(f"node {node}: {nm} {got!r} vs {ref!r}")
         w = -G / (H + lam)
-        if abs(other["weight"][node] - w) > sum_rtol * abs(w) + 2.0 * atol / (H + lam) + 1e-300:
+        if abs(other["weight"][node] - w) > sum_rtol * abs(w) + _weight_atol(w, H + lam, atol) + 1e-300:
             err(f"node {node}: weight {other['weight'][node]!r} vs {w!r}")
         rep["checked_splits"] += 1
         best = eval_split(h_, cnt, nb, G, H, hi - lo, lam, min_child_weight) \

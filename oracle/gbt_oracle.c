@@ -28,7 +28,10 @@
  *   - cuts are data values: exact order statistics v[floor(k*m/B)], k=1..B-1,
  *     of the m present values (or every distinct value when there are <= B);
  *   - gain = GL^2/(HL+lambda) + GR^2/(HR+lambda) - G^2/(H+lambda), a candidate
- *     is valid iff HL >= min_child_weight and HR >= min_child_weight;
+ *     is valid iff both sides hold at least one row (counted, not inferred from
+ *     the sums: with lambda = 0 and min_child_weight = 0 the term of a side
+ *     without rows is 0/0, and rounding noise in G - GL must not turn it into
+ *     a winner) and HL >= min_child_weight and HR >= min_child_weight;
  *   - the missing rows' mass is tried on the right, then on the left (only if
  *     the node really has missing rows in that feature);
  *   - best = first candidate, in (feature, bin, right-before-left) order,
@@ -308,11 +311,14 @@ void gbto_eval_split(const double *hist, const int64_t *cnt, const int32_t *nb, 
         int has_missing = present < n_rows;
         double Gm = G - sg, Hm = H - sh;
         double pg = 0.0, ph = 0.0;
+        int64_t pc = 0;
         for (int32_t b = 0; b < nb[f]; ++b) {
             pg += hf[2 * b];
             ph += hf[2 * b + 1];
+            pc += cf[b];
             for (int32_t dir = 0; dir <= has_missing; ++dir) {
-                if (b == nb[f] - 1 && (dir == 1 || !has_missing)) continue; /* right side empty */
+                int64_t n_left = pc + (dir == 1 ? n_rows - present : 0);
+                if (n_left == 0 || n_left == n_rows) continue; /* a side without rows is no split */
                 double GL = pg, HL = ph;
                 if (dir == 1) { GL += Gm; HL += Hm; }
                 double GR = G - GL, HR = H - HL;

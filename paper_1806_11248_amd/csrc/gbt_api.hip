@@ -2116,7 +2116,6 @@ extern "C" int32_t gbt_quantise(gbt_ctx *ctx, const float *X, const int64_t *ind
     if (!ctx) return GBT_EINVAL;
     const bool dense = X != nullptr;
     GBT_REQUIRE(ctx, dense != (indptr != nullptr), GBT_EINVAL, "give exactly one of X and (indptr, indices, values)");
-    GBT_REQUIRE(ctx, dense || (indices && values), GBT_EINVAL, "CSR input needs indices and values");
     GBT_REQUIRE(ctx, cuts_out && nb_out && sym_out && max_value_out && missing_sym_out && workspace, GBT_EINVAL,
                 "NULL argument");
     GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) && F >= 1 && F <= (1 << 20), GBT_EINVAL, "bad shape");
@@ -2129,6 +2128,8 @@ extern "C" int32_t gbt_quantise(gbt_ctx *ctx, const float *X, const int64_t *ind
         memcpy(&n_values, rb(ctx), 8);
         GBT_REQUIRE(ctx, n_values >= 0 && n_values <= n * (int64_t)F, GBT_EINVAL, "indptr[n] = %lld out of range",
                     (long long)n_values);
+        // (a matrix with nothing stored has nothing to point at: every value is missing)
+        GBT_REQUIRE(ctx, n_values == 0 || (indices && values), GBT_EINVAL, "CSR input needs indices and values");
     }
     GBT_REQUIRE(ctx, workspace_bytes >= gbt_quantise_ws(n, F, n_values, max_bins), GBT_ENOMEM,
                 "workspace %zu < %zu bytes", workspace_bytes, gbt_quantise_ws(n, F, n_values, max_bins));

@@ -35,3 +35,16 @@ def hist_tolerance(oracle_hist, cnt, scale, rtol=1e-5):
     tol[..., 0] += cnt * (0.5 / scale[0])
     tol[..., 1] += cnt * (0.5 / scale[1])
     return tol + 1e-300
+
+
+def judge_on_grid(oracle, judge, tree, o, gp, scale, **kw):
+    """The tree judged in the GPU library's own precision: on the pairs moved onto its fixed-point grid every
+    fp64 sum of the oracle is exact, so totals and weights must agree to rounding of the last operation and
+    every decision (valid child? larger gain? above gamma?) must come out the same: the oracle's exhaustive
+    best split at every node, no ties to excuse."""
+    q, scale_o = oracle.fixed_point(gp)
+    assert tuple(scale) == scale_o
+    rep = judge(tree, o["sym"], o["nb"], o["missing"], oracle.on_grid(gp), **kw, sum_rtol=1e-13, tie_rtol=1e-13,
+                sum_atol_per_row=0.0)
+    assert rep["ok"] and rep["identical"] and not rep["ties"], (rep["errors"][:5], rep["ties"][:3])
+    return rep

@@ -4,7 +4,7 @@ import pytest
 import torch
 from hypothesis import HealthCheck, given, settings, strategies as st
 
-from gpu_util import dev, host_u32, oracle_prep, tree_kw
+from gpu_util import dev, host_u32, judge_on_grid, oracle_prep, tree_kw
 
 pytestmark = pytest.mark.gpu
 
@@ -32,6 +32,7 @@ def _grow_and_judge(ctx, oracle, X, gp, p):
     gp_t = dev(gp)
     tree, row_idx, leaf = ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_t, params)
     _, scale = ctx.gpair_fixed(gp_t)
+    judge_on_grid(oracle, oracle.replay_tree, tree, o, gp, scale, **tree_kw(p))
     rep = oracle.replay_tree(tree, o["sym"], o["nb"], o["missing"], gp, **tree_kw(p),
                              sum_atol_per_row=0.5 / min(scale))
     assert rep["ok"], rep["errors"][:5]
@@ -169,6 +170,7 @@ def test_random_sparse_rows_and_lossguide(ctx, oracle, seed, n, F, B, miss, dept
         assert torch.equal(m, m2)
     lg, lrows, lleaf = ctx.grow_tree_lossguide(packed, bits, n, F, ms, nb, cuts, gp_t, params, max_leaves)
     _, scale = ctx.gpair_fixed(gp_t)
+    judge_on_grid(oracle, oracle.replay_tree_lossguide, lg, o, gp, scale, max_leaves=max_leaves, **tree_kw(p))
     rep = oracle.replay_tree_lossguide(lg, o["sym"], o["nb"], o["missing"], gp, max_leaves=max_leaves, **tree_kw(p),
                                        sum_atol_per_row=0.5 / min(scale))
     assert rep["ok"], rep["errors"][:5]

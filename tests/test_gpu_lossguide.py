@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, host_u32, tree_kw
+from gpu_util import dev, host_u32, judge_on_grid, tree_kw
 from test_gpu_tree import gpu_prep
 
 pytestmark = pytest.mark.gpu
@@ -23,7 +23,7 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _judge(ctx, oracle, o, gdev, gp, p, n, F, max_leaves):
+def _judge(ctx, oracle, o, gdev, gp, p, n, F, max_leaves, grid_only=False):
     import paper_1806_11248_amd as g
     params = g.make_params(max_depth=p["max_depth"], max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
                            min_child_weight=p["min_child_weight"])
@@ -31,9 +31,11 @@ def _judge(ctx, oracle, o, gdev, gp, p, n, F, max_leaves):
     tree, row_idx, leaf = ctx.grow_tree_lossguide(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"],
                                                   gdev["cuts"], gp_t, params, max_leaves)
     _, scale = ctx.gpair_fixed(gp_t)
-    rep = oracle.replay_tree_lossguide(tree, o["sym"], o["nb"], o["missing"], gp, max_leaves=max_leaves,
-                                       **tree_kw(p), sum_atol_per_row=0.5 / min(scale))
-    assert rep["ok"], rep["errors"][:5]
+    rep = judge_on_grid(oracle, oracle.replay_tree_lossguide, tree, o, gp, scale, max_leaves=max_leaves, **tree_kw(p))
+    if not grid_only:
+        rep = oracle.replay_tree_lossguide(tree, o["sym"], o["nb"], o["missing"], gp, max_leaves=max_leaves,
+                                           **tree_kw(p), sum_atol_per_row=0.5 / min(scale))
+        assert rep["ok"], rep["errors"][:5]
     assert np.array_equal(host_u32(row_idx), rep["row_idx"])           # partitions: bit-exact
     assert np.array_equal(leaf.cpu().numpy(), rep["leaf_of_row"])
     nn = tree["n_nodes"]
@@ -48,7 +50,7 @@ def _judge(ctx, oracle, o, gdev, gp, p, n, F, max_leaves):
     # an independently grown oracle tree is the same unless a legal tie intervened
     t_ref, rows_ref, leaf_ref = oracle.grow_tree_lossguide(o["sym"], o["nb"], o["cuts"], o["missing"], gp,
                                                            max_leaves=max_leaves, **tree_kw(p))
-    if rep["identical"]:
+    if rep["identical"] and not grid_only:
         assert t_ref["n_nodes"] == nn
         for k in ("feature", "bin", "default_left", "left", "right", "n_rows"):
             assert np.array_equal(tree[k][:nn], t_ref[k][:nn]), k

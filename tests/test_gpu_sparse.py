@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, hist_tolerance, host_u32, tree_kw
+from gpu_util import dev, hist_tolerance, host_u32, judge_on_grid, tree_kw
 
 pytestmark = pytest.mark.gpu
 
@@ -140,6 +140,7 @@ def test_sparse_tree_matches_oracle(ctx, oracle, cfg, n, kw, depth):
                            min_child_weight=p["min_child_weight"])
     tree, row_idx, leaf = ctx.grow_tree_sparse(rowptr, ent, n, nnz, F, gdev["nb"], gdev["cuts"], gp_t, params)
     _, scale = ctx.gpair_fixed(gp_t)
+    judge_on_grid(oracle, oracle.replay_tree, tree, o, gp, scale, **tree_kw(p))
     rep = oracle.replay_tree(tree, o["sym"], o["nb"], o["missing"], gp, **tree_kw(p),
                              sum_atol_per_row=0.5 / min(scale))
     assert rep["ok"], rep["errors"][:5]

@@ -85,6 +85,19 @@ def test_quantise_csr_matches_dense_oracle(ctx, oracle):
     assert np.array_equal(sym.cpu().numpy(), o["sym"])
 
 
+def test_quantise_csr_with_nothing_stored(ctx, oracle):
+    # every value missing: the index and value arrays are empty (no address to give), all symbols are the missing one
+    n, F = 37, 5
+    X = np.full((n, F), np.nan, np.float32)
+    indptr, indices, values = synth.dense_to_csr(X)
+    assert len(values) == 0
+    cuts, nb, sym, mv, ms = ctx.quantise(csr=(dev(indptr), dev(indices), dev(values)), max_bins=16, n=n, F=F)
+    o = oracle_prep(oracle, X, 16)
+    assert np.array_equal(nb.cpu().numpy(), o["nb"]) and np.array_equal(cuts.cpu().numpy(), o["cuts"])
+    assert (mv, ms) == (o["max_value"], o["missing"]) == (1, 1)
+    assert np.array_equal(sym.cpu().numpy(), o["sym"])
+
+
 # ------------------------------------------------------------------- compress --
 @pytest.mark.parametrize("bits", list(range(1, 17)))
 def test_compress(ctx, oracle, bits):
@@ -226,12 +239,20 @@ def test_sibling_subtraction_is_exact(ctx, oracle):
     assert torch.equal(ctx.hist_subtract(hp, hr), hl)
 
 
-def test_gpair_fixed_scale_and_errors(ctx):
+def test_gpair_fixed_scale_and_errors(ctx, oracle):
     import paper_1806_11248_amd as g
     gp = np.array([[0.75, 0.25], [-3.0, 0.0], [1e-3, 1.0]], np.float32)
     gq, scale = ctx.gpair_fixed(dev(gp))
     assert scale == (2.0 ** 24, 2.0 ** 21)            # 3.0 < 2^2, 1.0 < 2^1: |g|*scale <= 2^26, h*scale <= 2^22
     assert np.array_equal(gq.cpu().numpy(), np.rint(gp.astype(np.float64) * np.array(scale)).astype(np.int32))
+    # the oracle's restatement of the grid, on ties, tiny and huge magnitudes
+    rng = np.random.default_rng(9)
+    for sg, sh in ((1.0, 1.0), (3e-7, 2e5), (9e6, 1e-4)):
+        gp2 = np.stack([rng.standard_normal(70_001) * sg, rng.uniform(0, 1, 70_001) * sh], 1).astype(np.float32)
+        gp2[5] = [2.5 * 2.0 ** -25 * sg, 3.5 * 2.0 ** -21 * sh]
+        gq, scale = ctx.gpair_fixed(dev(gp2))
+        q, scale_o = oracle.fixed_point(gp2)
+        assert scale == scale_o and np.array_equal(gq.cpu().numpy(), q)
     bad = gp.copy(); bad[1, 0] = np.inf
     with pytest.raises(g.GbtError) as e:
         ctx.gpair_fixed(dev(bad))

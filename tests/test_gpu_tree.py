@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, host_u32, oracle_prep, tree_kw
+from gpu_util import dev, host_u32, judge_on_grid, oracle_prep, tree_kw
 
 pytestmark = pytest.mark.gpu
 
@@ -44,7 +44,7 @@ def gpu_prep(ctx, oracle, d, use_csr=False):
     return o, dict(cuts=cuts, nb=nb, packed=packed, bits=bits, missing=ms)
 
 
-def grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, nodes=None):
+def grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, nodes=None, grid_only=False):
     import paper_1806_11248_amd as g
     params = g.make_params(max_depth=p["max_depth"], max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
                            min_child_weight=p["min_child_weight"])
@@ -52,9 +52,11 @@ def grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, nodes=None):
     tree, row_idx, leaf = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"],
                                         gdev["cuts"], gp_t, params)
     _, scale = ctx.gpair_fixed(gp_t)
-    rep = oracle.replay_tree(tree, o["sym"], o["nb"], o["missing"], gp, **tree_kw(p),
-                             sum_atol_per_row=0.5 / min(scale), nodes=nodes)
-    assert rep["ok"], rep["errors"][:5]
+    rep = judge_on_grid(oracle, oracle.replay_tree, tree, o, gp, scale, **tree_kw(p), nodes=nodes)
+    if not grid_only:   # and against the unrounded pairs, within the stated bound of one rounding per row
+        rep = oracle.replay_tree(tree, o["sym"], o["nb"], o["missing"], gp, **tree_kw(p),
+                                 sum_atol_per_row=0.5 / min(scale), nodes=nodes)
+        assert rep["ok"], rep["errors"][:5]
     assert np.array_equal(host_u32(row_idx), rep["row_idx"])           # partitions: bit-exact
     assert np.array_equal(leaf.cpu().numpy(), rep["leaf_of_row"])
     nn = tree["n_nodes"]
@@ -251,6 +253,25 @@ def test_depth_zero_and_gamma(ctx, oracle):
         _say(f"degenerate tree {change}")
         tree, rep = grow_and_judge(ctx, oracle, o, gdev, gp, q, n, F)
         assert tree["n_nodes"] == 1 and tree["feature"][0] == -1
+
+
+@pytest.mark.parametrize("cfg,n,kw", [(4, 60_000, {}), (5, 7_000, {"F": 40})])
+def test_a_few_huge_pairs_set_the_fixed_point_scale(ctx, oracle, cfg, n, kw):
+    # One row in a thousand carries pairs a thousand times the rest and half the hessians are zero: the largest pair
+    # fixes the quantum, the ordinary rows keep about 16 of their bits, and leaves with |weight| far above 1
+    # appear.  Sums stay within half a quantum per row; the weights within what that bound implies.
+    d = synth.make(cfg, n, **kw)
+    p = dict(d["params"], max_depth=6, lam=1.0, gamma=0.0, min_child_weight=3.3)
+    n, F = d["X"].shape
+    rng = np.random.default_rng(n)
+    gp = np.stack([rng.standard_normal(n) * 400.0, np.where(rng.random(n) < 0.5, 0.0, rng.uniform(0, 1, n) * 2.5)], 1)
+    gp[rng.integers(0, n, n // 1000)] *= 1000.0
+    gp = gp.astype(np.float32)
+    o, gdev = gpu_prep(ctx, oracle, d)
+    _say(f"huge pairs: config {cfg}, {n} x {F}")
+    tree, rep = grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
+    nn = tree["n_nodes"]
+    assert nn > 15 and np.abs(tree["weight"][:nn]).max() > 50.0
 
 
 def test_boosting_rounds_in_lock_step(ctx, oracle):

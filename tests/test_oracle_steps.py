@@ -115,7 +115,7 @@ def _brute_force_best(sym, nb, missing, gp, lam, mcw):
         for b in range(nb[f]):
             for d in ((0, 1) if has_missing else (0,)):
                 left = ((s <= b) & (s != missing)) | ((s == missing) & (d == 1))
-                if b == nb[f] - 1 and (d == 1 or not has_missing):
+                if not left.any() or left.all():
                     continue
                 GL, HL = g[left].sum(), h[left].sum()
                 GR, HR = g[~left].sum(), h[~left].sum()
@@ -152,6 +152,30 @@ def test_split_against_brute_force(oracle, seed):
     g2, sides = oracle.candidate_gain(h, *where, G, H, lam, mcw)
     assert np.isclose(g2, gain, rtol=1e-10, atol=1e-12)
     assert np.allclose(sides, [sp["GL"], sp["HL"], sp["GR"], sp["HR"]], rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_split_never_leaves_a_side_without_rows(oracle, seed):
+    # lambda = 0 and min_child_weight = 0, the node's rows all in the low bins, large gradients: priced from
+    # G - GL, a right side without rows is rounding noise squared over zero.  No such candidate may win, and the
+    # winner is the brute-force one (which sums each side from its rows).
+    rng = np.random.default_rng(seed)
+    n, F, B = 4000, 3, 16
+    nb = np.array([16, 12, 9], np.int32)
+    sym = np.stack([rng.integers(2, 6, n), rng.integers(0, 5, n), rng.integers(3, 4, n)], 1).astype(np.uint16)
+    missing = 16
+    if seed % 2:
+        sym[rng.random((n, F)) < 0.2] = missing
+    gp = np.stack([rng.standard_normal(n) * 10.0 ** rng.uniform(-8, 8, n), np.ones(n)], 1).astype(np.float32)
+    h, cnt, G, H = oracle.hist(sym, B, missing, None, gp)
+    if seed % 2 == 0:   # the trap is really set: nothing is missing, some right side without rows has G - GL != 0
+        assert any(G - np.cumsum(h[f, :, 0])[b] != 0.0 for f in range(F) for b in range(int(sym[:, f].max()), nb[f] - 1))
+    sp = oracle.eval_split(h, cnt, nb, G, H, n, 0.0, 0.0)
+    gain, where = _brute_force_best(sym, nb, missing, gp, 0.0, 0.0)
+    assert sp["valid"] and np.isfinite(sp["gain"]) and (sp["feature"], sp["bin"], sp["default_left"]) == where
+    assert np.isclose(sp["gain"], gain, rtol=1e-9)
+    out, nl = oracle.partition(sym, np.arange(n, dtype=np.uint32), sp["feature"], sp["bin"], sp["default_left"], missing)
+    assert 0 < nl < n
 
 
 def test_split_two_cluster_closed_form(oracle):
@@ -238,6 +262,35 @@ def test_split_tie_break_and_min_child_weight(oracle):
     gp1 = np.stack([np.arange(5) - 2.0, np.ones(5)], 1).astype(np.float32)
     h, cnt, G, H = oracle.hist(sym1, 2, 1, None, gp1)
     assert not oracle.eval_split(h, cnt, np.array([1], np.int32), G, H, 5, 1.0, 0.0)["valid"]
+
+
+# ------------------------------------------------------------- the GPU's grid --
+def test_fixed_point_grid(oracle):
+    # the scale: the power of two that puts the largest magnitude into [2^25, 2^26) (g) or [2^21, 2^22) (h)
+    gp = np.array([[0.75, 0.25], [-3.0, 0.0], [1e-3, 1.0]], np.float32)
+    q, scale = oracle.fixed_point(gp)
+    assert scale == (2.0 ** 24, 2.0 ** 21)
+    assert q.tolist() == [[3 * 2 ** 22, 2 ** 19], [-3 * 2 ** 24, 0], [16777, 2 ** 21]]   # 1e-3 * 2^24 = 16777.216
+    assert oracle.fixed_point(np.array([[0.99, 0.49]], np.float32))[1] == (2.0 ** 26, 2.0 ** 23)
+    assert oracle.fixed_point(np.zeros((4, 2), np.float32))[1] == (1.0, 1.0)
+    assert oracle.fixed_point(np.zeros((0, 2), np.float32))[1] == (1.0, 1.0)
+    # ties go to the even integer: 2.5 and 3.5 quanta (the 1.0 fixes the quantum at 2^-25)
+    q, scale = oracle.fixed_point(np.array([[1.0, 1.0], [2.5 * 2.0 ** -25, 3.5 * 2.0 ** -21]], np.float32))
+    assert scale == (2.0 ** 25, 2.0 ** 21) and q[1].tolist() == [2, 4]
+    rng = np.random.default_rng(4)
+    for sg, sh in ((1.0, 1.0), (1e-6, 3e4), (7e5, 1e-3)):
+        gp = np.stack([rng.standard_normal(5000) * sg, rng.uniform(0, 1, 5000) * sh], 1).astype(np.float32)
+        q, scale = oracle.fixed_point(gp)
+        for c, top in ((0, 26), (1, 22)):
+            m = np.abs(q[:, c].astype(np.int64)).max()
+            assert 2 ** (top - 1) <= m <= 2 ** top and np.log2(scale[c]) == np.round(np.log2(scale[c]))
+        assert np.all(np.abs(q / np.array(scale) - gp.astype(np.float64)) <= 0.5 / np.array(scale))   # one rounding
+        og = oracle.on_grid(gp)
+        assert og.dtype == np.float32 and np.array_equal(og.astype(np.float64) * np.array(scale), q)
+        q2, scale2 = oracle.fixed_point(og)                                # already on the grid: nothing moves
+        assert scale2 == scale and np.array_equal(q2, q)
+        # sums of on-grid values are exact in fp64 whatever the order
+        assert og[:, 0].astype(np.float64).sum() == og[::-1, 0].astype(np.float64).sum() == q[:, 0].astype(np.int64).sum() / scale[0]
 
 
 # ----------------------------------------------------------------- partition --

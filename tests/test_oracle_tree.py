@@ -142,6 +142,19 @@ def test_sparse_workload_learns_default_directions(oracle):
     assert np.array_equal(l1, leaf) and np.array_equal(l2, leaf)
 
 
+def test_judges_weight_tolerance_is_the_worst_corner(oracle):
+    # G and H each off by at most a: the leaf weight -G/(H+lambda) moves furthest at one of the four corners
+    # (the map is monotone in each argument while H+lambda stays positive), and the bound equals that corner
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        G, H, lam = rng.standard_normal() * 10.0 ** rng.uniform(-2, 4), 10.0 ** rng.uniform(-3, 3), float(rng.choice([0.0, 1.0]))
+        a = (H + lam) * 10.0 ** rng.uniform(-8, -0.1)
+        w = -G / (H + lam)
+        worst = max(abs(-(G + dg) / (H + lam + dh) - w) for dg in (-a, a) for dh in (-a, a))
+        assert np.isclose(oracle._weight_atol(w, H + lam, a), worst, rtol=1e-9)
+    assert oracle._weight_atol(-3.0, 2.0, 0.0) == 0.0 and oracle._weight_atol(-3.0, 2.0, 2.0) == np.inf
+
+
 def test_replay_accepts_own_tree_and_rejects_planted_mistakes(oracle, c1):
     d, cuts, nb, sym, missing, gp, t, rows, leaf = c1
     kw = _kw(d["params"])

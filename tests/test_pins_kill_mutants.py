@@ -51,6 +51,9 @@ MUTANTS = [
     ("lambda dropped from the parent term", C, 1, "double c = G * G / (H + lambda);", "double c = G * G / H;"),
     ("left term not squared", C, 1, "double a = GL * GL / (HL + lambda);", "double a = GL / (HL + lambda);"),
     ("right term over the left hessian", C, 1, "double b = GR * GR / (HR + lambda);", "double b = GR * GR / (HL + lambda);"),
+    ("a side without rows may win", C, 1, "if (n_left == 0 || n_left == n_rows) continue;",
+     "if (b == nb[f] - 1 && (dir == 1 || !has_missing)) continue;"),
+    ("rows of the missing side not counted", C, 1, "int64_t n_left = pc + (dir == 1 ? n_rows - present : 0);", "int64_t n_left = pc;"),
     ("later candidate wins ties", C, 1, "if (gain > best.gain) {", "if (gain >= best.gain) {"),
     ("missing mass on the wrong side", C, 1, "if (dir == 1) { GL += Gm; HL += Hm; }", "if (dir == 0) { GL += Gm; HL += Hm; }"),
     ("missing mass with the wrong sign", C, 2, "double Gm = G - sg, Hm = H - sh;", "double Gm = sg - G, Hm = sh - H;"),
@@ -95,6 +98,8 @@ MUTANTS = [
     ("judge: accepts any gain", PY, 1, "close = abs(g_other - best[\"gain\"]) <= tie_rtol * abs(best[\"gain\"])", "close = True"),
     ("judge: row counts not compared", PY, 1, 'if int(other["n_rows"][node]) != hi - lo:', "if False:"),
     ("judge: leaf weights not compared", PY, 1, 'if abs(other["weight"][node] - w) > w_tol + 1e-300:', "if False:"),
+    ("judge: weight tolerance without the hessian's share", PY, 1, "return (1.0 + abs(w)) * atol / (denom - atol) if denom > atol else np.inf",
+     "return atol / (denom - atol) if denom > atol else np.inf"),
     ("judge: totals not compared", PY, 1, "if abs(got - ref) > sum_rtol * abs(ref) + atol + 1e-300:", "if False:"),
     ("judge: a split below the threshold is accepted", PY, 1,
      'err(f"node {node}: split although the best gain {best[\'gain\']!r} is below {thr}")', "pass"),
