@@ -1,12 +1,13 @@
 """GPU parity on RANDOM small workloads (-m gpu): shapes, bin counts, missing rates, gradient-pair
 distributions and parameters drawn per seed, far outside what the named configurations cover (1 to 250 000
-rows, 1 to 70 features, 2 to 1024 bins, up to 90% missing, pairs spanning eight decades with zero hessians
+rows, 1 to 400 features, 2 to 4096 bins, up to 90% missing, pairs spanning eight decades with zero hessians
 and outliers, lambda = 0, min_child_weight = 0, depth 0 to 9).  Everything is judged in the GPU library's own
 precision (pairs moved onto its fixed-point grid, where the oracle's sums are exact): histograms and gains
 equal to the last bit, the oracle's exhaustive best split at every node, partitions and predictions bit-exact.
 
 A fixed set of seeds runs by default.  GBT_TEST_SWEEP_SECONDS=<s> adds fresh seeds for that long (seeds start
-at GBT_TEST_SWEEP_SEED, default 1000000), printing each case before it runs.
+at GBT_TEST_SWEEP_SEED, default 1000000), printing each case before it runs (give pytest -s to see them as
+they come).
 """
 import os
 import time
@@ -50,8 +51,9 @@ def random_workload(seed):
     n = int(rng.choice([1, 2, 63, 64, 65, 500, 2047, 2049, 7000, 30000, 90000, 250000]))
     if n > 10:
         n = max(1, n + int(rng.integers(-3, 4)))
-    F = int(rng.choice([1, 2, 3, 5, 8, 12, 13, 16, 17, 28, 40, 70]))
-    B = int(rng.choice([2, 3, 4, 16, 17, 64, 100, 255, 256, 257, 512, 1024]))
+    F = int(rng.choice([1, 2, 3, 5, 8, 12, 13, 16, 17, 28, 40, 70, 150, 400]))
+    B = int(rng.choice([2, 3, 4, 16, 17, 64, 100, 255, 256, 257, 512, 1024, 4096]))
+    n = min(n, 4_000_000 // F)          # (keeps the oracle's sorts short; rows wider than 64 words stay in)
     miss = float(rng.choice([0.0, 0.0, 0.02, 0.3, 0.9]))
     X = np.stack([column(rng, n, int(rng.integers(0, 6))) for _ in range(F)], 1).astype(np.float32)
     if miss > 0:
