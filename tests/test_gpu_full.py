@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import synth
-from gpu_util import dev, hist_tolerance, host_u32, tree_kw
+from gpu_util import dev, hist_tolerance, host_u32, judge_on_grid, tree_kw
 
 pytestmark = pytest.mark.gpu
 
@@ -120,6 +120,11 @@ def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True, sparse_rows=
         assert np.array_equal(host_u32(row_idx), rep["row_idx"])
         assert np.array_equal(leaf.cpu().numpy(), rep["leaf_of_row"])
         del row_idx, leaf
+        if r == 0:   # and in the library's own precision: exact totals, the exhaustive best split at each sampled node
+            t0 = time.time()
+            judge_on_grid(oracle, oracle.replay_tree, tree, dict(sym=o_sym, nb=o_nb, missing=o_missing), gp_ref, scale,
+                          **tree_kw(p), nodes=_sample_nodes(tree, seed=r))
+            _say(f"  judged on the fixed-point grid in {time.time() - t0:.1f} s")
         # the launch configuration the benchmark times: no row order asked for (one-launch partition,
         # with one child's histogram in the same pass where the shape allows) -- the same tree
         t0 = time.time()
