@@ -78,7 +78,7 @@ typedef struct gbt_split {
     int32_t bin;          /* rows with symbol <= bin go left */
     int32_t default_left; /* 1: rows with the missing symbol go left */
     int32_t valid;
-    double gain;          /* GL^2/(HL+l) + GR^2/(HR+l) - G^2/(H+l) */
+    double gain;          /* GL^2/(HL+l) + GR^2/(HR+l) - G^2/(H+l); a term with denominator 0 counts 0 */
     double GL, HL, GR, HR;
     int64_t GLq, HLq;     /* left sums in fixed point (exact) */
 } gbt_split;
@@ -95,7 +95,7 @@ typedef struct gbt_tree {
     int32_t *left, *right; /* child ids, -1 for a leaf */
     float *threshold;      /* raw-value form of the split: left iff x < threshold
                               (= cuts[feature][bin]; +inf when bin is the last bin) */
-    double *weight;        /* -G/(H+lambda) of every node */
+    double *weight;        /* -G/(H+lambda) of every node; 0 where H+lambda = 0 */
     double *gain;          /* gain of the node's split, 0 for a leaf */
     double *sumG, *sumH;
     int64_t *n_rows;
@@ -302,7 +302,7 @@ GBT_API int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int32_
  * with the smaller hessian sum) and get the other one by subtraction; sums are
  * exact integers, so the choice changes no value.  A node is
  * split iff it has a valid candidate with gain > max(gamma, GBT_GAIN_FLOOR) and
- * depth < max_depth.  Leaf weight = -G/(H+lambda).
+ * depth < max_depth.  Leaf weight = -G/(H+lambda), 0 where H+lambda = 0.
  *   packed, bits, n, F, missing_sym : packed matrix [dev]
  *   nb [dev] int32[F]; cuts [dev] float[F][max_bins-1] (for thresholds)
  *   gpair [dev] float2[n]

@@ -253,6 +253,12 @@ def new_tree_leaves(max_leaves: int) -> dict:
     return t
 
 
+def leaf_weight(G, H, lam):
+    """w = -G / (H + lambda), the minimiser of G*w + (H + lambda)*w^2/2.  Without curvature (H + lambda = 0, only
+    possible with lambda = 0 and no hessian mass) there is no minimiser; the reading taken is "no step": 0."""
+    return -G / (H + lam) if H + lam > 0.0 else 0.0
+
+
 def _threshold(cuts_, nb, f, b):
     # rows with symbol <= b are those with x < cuts[f][b]; the feature's last
     # bin has no cut to its right (only missing rows can be on the other side)
@@ -278,7 +284,7 @@ def grow_tree(sym, nb, cuts_, missing_sym, gpair, *, max_depth, max_bins, lam=1.
         r = rows[lo:hi]
         h_, cnt, G, H = hist(sym, B, missing_sym, r, gpair)
         t["sumG"][node], t["sumH"][node], t["n_rows"][node] = G, H, hi - lo
-        t["weight"][node] = -G / (H + lam)
+        t["weight"][node] = leaf_weight(G, H, lam)
         t["depth"][node] = depth
         do_split = False
         if depth < max_depth:
@@ -320,7 +326,7 @@ def grow_tree_lossguide(sym, nb, cuts_, missing_sym, gpair, *, max_leaves, max_d
         r = rows[lo:hi]
         h_, cnt, G, H = hist(sym, B, missing_sym, r, gpair)
         t["sumG"][node], t["sumH"][node], t["n_rows"][node] = G, H, hi - lo
-        t["weight"][node] = -G / (H + lam)
+        t["weight"][node] = leaf_weight(G, H, lam)
         t["depth"][node] = depth
         seg[node] = (lo, hi)
         if depth < max_depth:
@@ -400,6 +406,8 @@ def _weight_atol(w, denom, atol):
     """How far the leaf weight w = -G / denom (denom = H + lambda) can move when G and H each move by at
     most atol:  |-(G+dG)/(denom+dH) - w| = |dG + w*dH| / |denom + dH| <= (1 + |w|) * atol / (denom - atol).
     (No bound when atol reaches denom: then the other side's H + lambda may be anywhere near zero.)"""
+    if atol == 0.0:
+        return 0.0
     return (1.0 + abs(w)) * atol / (denom - atol) if denom > atol else np.inf
 
 
@@ -452,7 +460,7 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
         for nm, ref, got in (("sumG", G, other["sumG"][node]), ("sumH", H, other["sumH"][node])):
             if abs(got - ref) > sum_rtol * abs(ref) + atol + 1e-300:
                 err(f"node {node}: {nm} {got!r} vs {ref!r}")
-        w = -G / (H + lam)
+        w = leaf_weight(G, H, lam)
         w_tol = sum_rtol * abs(w) + _weight_atol(w, H + lam, atol)
         if abs(other["weight"][node] - w) > w_tol + 1e-300:
             err(f"node {node}: weight {other['weight'][node]!r} vs {w!r}")
@@ -531,7 +539,7 @@ def replay_tree_lossguide(other, sym, nb, missing_sym, gpair, *, max_leaves, max
         for nm, ref, got in (("sumG", G, other["sumG"][node]), ("sumH", H, other["sumH"][node])):
             if abs(got - ref) > sum_rtol * abs(ref) + atol + 1e-300:
                 err(f"node {node}: {nm} {got!r} vs {ref!r}")
-        w = -G / (H + lam)
+        w = leaf_weight(G, H, lam)
         if abs(other["weight"][node] - w) > sum_rtol * abs(w) + _weight_atol(w, H + lam, atol) + 1e-300:
             err(f"node {node}: weight {other['weight'][node]!r} vs {w!r}")
         rep["checked_splits"] += 1

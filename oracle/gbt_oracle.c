@@ -27,7 +27,8 @@
  *     a split (f, b) sends left the rows whose symbol is <= b;
  *   - cuts are data values: exact order statistics v[floor(k*m/B)], k=1..B-1,
  *     of the m present values (or every distinct value when there are <= B);
- *   - gain = GL^2/(HL+lambda) + GR^2/(HR+lambda) - G^2/(H+lambda), a candidate
+ *   - gain = GL^2/(HL+lambda) + GR^2/(HR+lambda) - G^2/(H+lambda), where a term
+ *     whose denominator is 0 (lambda = 0, no hessian mass) counts 0; a candidate
  *     is valid iff both sides hold at least one row (counted, not inferred from
  *     the sums: with lambda = 0 and min_child_weight = 0 the term of a side
  *     without rows is 0/0, and rounding noise in G - GL must not turn it into
@@ -256,12 +257,20 @@ typedef struct {
     double gain, GL, HL, GR, HR;
 } gbto_split;
 
+/* What the best step w = -G/(H+lambda) of a set of rows gains (twice over): G^2/(H+lambda).  Without
+ * curvature, H + lambda = 0, there is no best step: the weight is defined as 0 and so, to match, is this. */
+static double term(double G, double H, double lambda)
+{
+    double d = H + lambda;
+    return d > 0.0 ? G * G / d : 0.0;
+}
+
 static double split_gain(double GL, double HL, double GR, double HR, double G, double H,
                          double lambda)
 {
-    double a = GL * GL / (HL + lambda);
-    double b = GR * GR / (HR + lambda);
-    double c = G * G / (H + lambda);
+    double a = term(GL, HL, lambda);
+    double b = term(GR, HR, lambda);
+    double c = term(G, H, lambda);
     return (a + b) - c;
 }
 

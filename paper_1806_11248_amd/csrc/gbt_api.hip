@@ -837,7 +837,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         tree->gain[at] = 0.0;
         tree->sumG[at] = G;
         tree->sumH[at] = H;
-        tree->weight[at] = -G / (H + lambda);
+        tree->weight[at] = H + lambda > 0.0 ? -G / (H + lambda) : 0.0;   // no curvature, no step
         tree->n_rows[at] = nd.len;
     };
     auto set_node = [&](const HNode &nd) { set_node_at(nd.id, nd); };
@@ -1912,7 +1912,7 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         tree->gain[at] = 0.0;
         tree->sumG[at] = G;
         tree->sumH[at] = H;
-        tree->weight[at] = -G / (H + lambda);
+        tree->weight[at] = H + lambda > 0.0 ? -G / (H + lambda) : 0.0;   // no curvature, no step
         tree->n_rows[at] = nd.len;
     };
     auto set_node = [&](const HNode &nd) { set_node_at(nd.id, nd); };

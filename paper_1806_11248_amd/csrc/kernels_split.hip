@@ -52,6 +52,10 @@ __device__ inline bool better(double ga, uint32_t ka, double gb, uint32_t kb) {
     return ga > gb || (ga == gb && ka < kb);
 }
 
+// G^2/(H + lambda): what the best step of a set of rows gains.  Without curvature (denominator 0: lambda = 0 and
+// no hessian mass) there is no best step; the leaf weight is then defined as 0 and, to match, so is the gain.
+__device__ __forceinline__ double gain_term(double G, double denom) { return denom > 0.0 ? G * G / denom : 0.0; }
+
 __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     int64_t *__restrict__ pool, const EvalNode *__restrict__ nodes, const int32_t *__restrict__ nb,
     int F, int B, int f_per_chunk, double inv_sg, double inv_sh, double lambda, double mcw,
@@ -81,7 +85,7 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t Gq = nd.Gq, Hq = nd.Hq;
     const double G = (double)Gq * inv_sg, H = (double)Hq * inv_sh;
-    const double parent = G * G / (H + lambda);
+    const double parent = gain_term(G, H + lambda);
 
     Best best;
     best.gain = -INFINITY;
@@ -140,8 +144,8 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
                     const double GL = (double)GLq * inv_sg, HL = (double)HLq * inv_sh;
                     const double GR = (double)(Gq - GLq) * inv_sg, HR = (double)(Hq - HLq) * inv_sh;
                     if (!(HL >= mcw) || !(HR >= mcw)) continue;
-                    const double a = GL * GL / (HL + lambda);
-                    const double c = GR * GR / (HR + lambda);
+                    const double a = gain_term(GL, HL + lambda);
+                    const double c = gain_term(GR, HR + lambda);
                     const double gain = (a + c) - parent;
                     if (gain > best.gain) {
                         best.gain = gain;

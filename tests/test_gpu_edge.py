@@ -56,6 +56,24 @@ def test_single_row_and_single_feature(ctx, oracle):
     assert tree["n_nodes"] >= 3
 
 
+def test_no_hessian_mass_under_lambda_zero(ctx, oracle):
+    # lambda = 0 and every hessian 0: no candidate has a finite gain and the root's weight is defined as 0
+    print("no curvature at all", flush=True)
+    rng = np.random.default_rng(3)
+    X = rng.random((500, 3)).astype(np.float32)
+    gp = np.stack([rng.standard_normal(500), np.zeros(500)], 1).astype(np.float32)
+    p = dict(P0, lam=0.0, min_child_weight=0.0)
+    tree, _, _ = _grow_and_judge(ctx, oracle, X, gp, p)
+    assert tree["n_nodes"] == 1 and tree["weight"][0] == 0.0 and tree["sumH"][0] == 0.0
+    m = ctx.predict([tree], dev(np.ones(500, np.float32)), 0.5, X=dev(X), n=500, F=3).cpu().numpy()
+    assert np.array_equal(m, np.ones(500, np.float32))
+    # some rows with curvature, some without: whatever is grown, both sides agree on it and no weight is NaN
+    print("half the rows without curvature", flush=True)
+    gp[::2, 1] = 1.0
+    tree, _, _ = _grow_and_judge(ctx, oracle, X, gp, p)
+    assert not np.isnan(tree["weight"][: tree["n_nodes"]]).any()
+
+
 def test_identical_rows_and_constant_features(ctx, oracle):
     print("identical rows", flush=True)
     X = np.tile(np.array([[1.0, 2.0, 3.0]], np.float32), (1000, 1))

@@ -72,8 +72,8 @@ def random_workload(seed):
     gp = gp.astype(np.float32)
     lam = float(rng.choice([0.0, 1.0, 10.0]))
     mcw = float(rng.choice([0.0, 1.0, 5.0])) * (sh if mode == 0 else 1.0)
-    if mode == 3:
-        lam, mcw = 1.0, 1.7321 * sh
+    if mode == 3:     # (no child weight a sum could equal; lambda = 0 with rows that have no curvature is in)
+        lam, mcw = float(rng.choice([0.0, 1.0])), float(rng.choice([0.0, 1.7321])) * sh
     p = dict(max_depth=int(rng.integers(0, 10)), max_bins=B, lam=lam, gamma=float(rng.choice([0.0, 0.0, 1e-3, 1.0])),
              min_child_weight=mcw)
     desc = dict(seed=seed, n=n, F=F, B=B, miss=miss, mode=mode, sg=float(f"{sg:.3g}"), sh=float(f"{sh:.3g}"),

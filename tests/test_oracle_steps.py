@@ -121,8 +121,8 @@ def _brute_force_best(sym, nb, missing, gp, lam, mcw):
                 GR, HR = g[~left].sum(), h[~left].sum()
                 if HL < mcw or HR < mcw:
                     continue
-                with np.errstate(all="ignore"):
-                    gain = GL * GL / (HL + lam) + GR * GR / (HR + lam) - G * G / (H + lam)
+                term = lambda g_, h_: g_ * g_ / (h_ + lam) if h_ + lam > 0 else 0.0   # no curvature: no step, no gain
+                gain = term(GL, HL) + term(GR, HR) - term(G, H)
                 if gain > best[0] + 1e-12 * max(1.0, abs(gain)):
                     best = (gain, (f, b, d))
     return best
@@ -176,6 +176,10 @@ def test_split_never_leaves_a_side_without_rows(oracle, seed):
     assert np.isclose(sp["gain"], gain, rtol=1e-9)
     out, nl = oracle.partition(sym, np.arange(n, dtype=np.uint32), sp["feature"], sp["bin"], sp["default_left"], missing)
     assert 0 < nl < n
+    # all rows in one bin of five, nothing missing, no weight asked of a child: still nothing to split on
+    one = np.full((50, 1), 2, np.uint16)
+    h1, cnt1, G1, H1 = oracle.hist(one, 8, 8, None, gp[:50])
+    assert not oracle.eval_split(h1, cnt1, np.array([5], np.int32), G1, H1, 50, 1.0, 0.0)["valid"]
 
 
 def test_split_two_cluster_closed_form(oracle):
@@ -257,6 +261,13 @@ def test_split_tie_break_and_min_child_weight(oracle):
     # and pricing that candidate by name says the same: a gain at weight 2 (each side holds exactly 2), none at 2.5
     assert np.isclose(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.0)[0], 4 / 3 + 4 / 3)
     assert np.isnan(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.5)[0])
+    # a side without curvature under lambda = 0 counts nothing (not +inf): 2^2/2 + 0 - 8^2/2
+    symz = np.array([[0], [0], [1], [1]], np.uint16)
+    gpz = np.array([[1, 1], [1, 1], [-5, 0], [-5, 0]], np.float32)
+    hz, cntz, Gz, Hz = oracle.hist(symz, 2, 2, None, gpz)
+    spz = oracle.eval_split(hz, cntz, np.array([2], np.int32), Gz, Hz, 4, 0.0, 0.0)
+    assert spz["valid"] and (spz["feature"], spz["bin"]) == (0, 0) and spz["gain"] == 2.0 + 0.0 - 32.0
+    assert oracle.candidate_gain(hz, 0, 0, 0, Gz, Hz, 0.0, 0.0)[0] == -30.0
     # a single-bin feature with nothing missing can never split
     sym1 = np.zeros((5, 1), np.uint16)
     gp1 = np.stack([np.arange(5) - 2.0, np.ones(5)], 1).astype(np.float32)

@@ -153,6 +153,28 @@ def test_judges_weight_tolerance_is_the_worst_corner(oracle):
         worst = max(abs(-(G + dg) / (H + lam + dh) - w) for dg in (-a, a) for dh in (-a, a))
         assert np.isclose(oracle._weight_atol(w, H + lam, a), worst, rtol=1e-9)
     assert oracle._weight_atol(-3.0, 2.0, 0.0) == 0.0 and oracle._weight_atol(-3.0, 2.0, 2.0) == np.inf
+    assert oracle._weight_atol(0.0, 0.0, 0.0) == 0.0
+
+
+def test_leaf_weight_minimises_the_quadratic_and_is_zero_without_curvature(oracle):
+    # w = argmin G*w + (H + lambda)*w^2/2: no nearby w does better; and the defined value where no minimiser exists
+    rng = np.random.default_rng(12)
+    for _ in range(100):
+        G, H, lam = float(rng.standard_normal() * 50), float(rng.uniform(0, 9)), float(rng.choice([0.0, 1.0, 4.0]))
+        if H + lam == 0.0:
+            continue
+        w = oracle.leaf_weight(G, H, lam)
+        loss = lambda x: G * x + (H + lam) * x * x / 2
+        assert loss(w) <= min(loss(w * (1 + 1e-4) + 1e-6), loss(w * (1 - 1e-4) - 1e-6))
+        assert np.isclose(loss(w), -G * G / (H + lam) / 2)          # the gain formula's term, halved
+    assert oracle.leaf_weight(3.0, 0.0, 0.0) == 0.0 and oracle.leaf_weight(0.0, 0.0, 0.0) == 0.0
+    # a node without any hessian mass under lambda = 0: one leaf, weight 0, and nothing divides by zero
+    sym = np.array([[0], [1], [1], [2]], np.uint16)
+    gp = np.array([[1, 0], [-2, 0], [0.5, 0], [3, 0]], np.float32)
+    cuts = np.array([[1.0, 2.0]], np.float32)
+    t, rows, leaf = oracle.grow_tree(sym, np.array([3], np.int32), cuts, 3, gp, max_depth=3, max_bins=3, lam=0.0,
+                                     gamma=0.0, min_child_weight=0.0)
+    assert t["n_nodes"] == 1 and t["weight"][0] == 0.0 and t["sumG"][0] == 2.5 and not leaf.any()
 
 
 def test_replay_accepts_own_tree_and_rejects_planted_mistakes(oracle, c1):

@@ -48,9 +48,10 @@ MUTANTS = [
     ("symbols read with the wrong stride", C, 1, "uint32_t s = sym[r * F + f];", "uint32_t s = sym[f * F + r % F];"),
     # Alg. 1 / Sec. 2.3: split evaluation
     ("parent term added", C, 1, "return (a + b) - c;", "return (a + b) + c;"),
-    ("lambda dropped from the parent term", C, 1, "double c = G * G / (H + lambda);", "double c = G * G / H;"),
-    ("left term not squared", C, 1, "double a = GL * GL / (HL + lambda);", "double a = GL / (HL + lambda);"),
-    ("right term over the left hessian", C, 1, "double b = GR * GR / (HR + lambda);", "double b = GR * GR / (HL + lambda);"),
+    ("lambda dropped from the parent term", C, 1, "double c = term(G, H, lambda);", "double c = term(G, H, 0.0);"),
+    ("terms not squared", C, 1, "return d > 0.0 ? G * G / d : 0.0;", "return d > 0.0 ? G / d : 0.0;"),
+    ("a side without curvature prices as infinite", C, 1, "return d > 0.0 ? G * G / d : 0.0;", "return G * G / d;"),
+    ("right term over the left hessian", C, 1, "double b = term(GR, HR, lambda);", "double b = term(GR, HL, lambda);"),
     ("a side without rows may win", C, 1, "if (n_left == 0 || n_left == n_rows) continue;",
      "if (b == nb[f] - 1 && (dir == 1 || !has_missing)) continue;"),
     ("rows of the missing side not counted", C, 1, "int64_t n_left = pc + (dir == 1 ? n_rows - present : 0);", "int64_t n_left = pc;"),
@@ -80,8 +81,10 @@ MUTANTS = [
     ("prediction: missing value takes the other side", C, 1, "(s == missing_sym) ? default_left[node]", "(s == missing_sym) ? !default_left[node]"),
     ("prediction on floats: NaN takes the other side", C, 1, "isnan(x) ? default_left[node]", "isnan(x) ? !default_left[node]"),
     # the tree drivers
-    ("leaf weight sign", PY, 1, 't["weight"][node] = -G / (H + lam)', 't["weight"][node] = G / (H + lam)'),
-    ("leaf weight without lambda", PY, 1, 't["weight"][node] = -G / (H + lam)', 't["weight"][node] = -G / H'),
+    ("leaf weight sign", PY, 1, "return -G / (H + lam) if H + lam > 0.0 else 0.0", "return G / (H + lam) if H + lam > 0.0 else 0.0"),
+    ("leaf weight without lambda", PY, 1, "return -G / (H + lam) if H + lam > 0.0 else 0.0", "return -G / H if H > 0.0 else 0.0"),
+    ("leaf weight without curvature is not 0", PY, 1, "return -G / (H + lam) if H + lam > 0.0 else 0.0",
+     "return -G / (H + lam) if H + lam > 0.0 else -np.sign(G) * np.inf"),
     ("children recorded the other way round", PY, 1, 't["left"][node], t["right"][node], t["gain"][node] = li, ri, sp["gain"]',
      't["left"][node], t["right"][node], t["gain"][node] = ri, li, sp["gain"]'),
     ("threshold is the cut below", PY, 1, "return np.float32(cuts_[f, b]) if b < nb[f] - 1", "return np.float32(cuts_[f, b - 1]) if b < nb[f] - 1"),
@@ -92,14 +95,14 @@ MUTANTS = [
     ("loss-guided: smallest gain first", PY, 1, 'key=lambda k: (-open_[k]["gain"], k)', 'key=lambda k: (open_[k]["gain"], k)'),
     ("loss-guided: larger id first on equal gains", PY, 1, 'key=lambda k: (-open_[k]["gain"], k)', 'key=lambda k: (-open_[k]["gain"], -k)'),
     ("loss-guided: one leaf too many", PY, 1, "while n_leaves < max_leaves and open_:", "while n_leaves <= max_leaves and open_:"),
-    ("loss-guided: leaf weight sign", PY, 2, 't["weight"][node] = -G / (H + lam)', 't["weight"][node] = G / (H + lam)'),
+    ("loss-guided: leaf weight sign", PY, 2, 't["weight"][node] = leaf_weight(G, H, lam)', 't["weight"][node] = -leaf_weight(G, H, lam)'),
     ("boosting: margin not carried over", PY, 1, "margin = predict_sym(t, sym, missing_sym, eta, margin)",
      "margin = predict_sym(t, sym, missing_sym, eta, np.full(n, base_margin, np.float32))"),
     ("judge: accepts any gain", PY, 1, "close = abs(g_other - best[\"gain\"]) <= tie_rtol * abs(best[\"gain\"])", "close = True"),
     ("judge: row counts not compared", PY, 1, 'if int(other["n_rows"][node]) != hi - lo:', "if False:"),
     ("judge: leaf weights not compared", PY, 1, 'if abs(other["weight"][node] - w) > w_tol + 1e-300:', "if False:"),
-    ("judge: weight tolerance without the hessian's share", PY, 1, "return (1.0 + abs(w)) * atol / (denom - atol) if denom > atol else np.inf",
-     "return atol / (denom - atol) if denom > atol else np.inf"),
+    ("judge: weight tolerance without the hessian's share", PY, 1, "    return (1.0 + abs(w)) * atol / (denom - atol) if denom > atol else np.inf",
+     "    return atol / (denom - atol) if denom > atol else np.inf"),
     ("judge: totals not compared", PY, 1, "if abs(got - ref) > sum_rtol * abs(ref) + atol + 1e-300:", "if False:"),
     ("judge: a split below the threshold is accepted", PY, 1,
      'err(f"node {node}: split although the best gain {best[\'gain\']!r} is below {thr}")', "pass"),
