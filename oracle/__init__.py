@@ -17,8 +17,15 @@ drivers that are easier to read in Python than in C:
   lists it re-derives, node by node, the exhaustive best split and the fp64
   gain of the split the other side chose.
 
+Two more things live here because the judging needs them, not because the paper
+states them: ``fixed_point`` / ``on_grid`` restate the grid the GPU library
+declares for its sums, so that decisions rounding could tip are compared in one
+precision; ``leaf_weight`` holds the reading for a node without curvature.
+
 Pins (tests/test_oracle_*.py): closed forms, numpy/scipy/scikit-learn library
 routines, brute-force enumeration on tiny inputs, conservation invariants.
+tests/test_pins_kill_mutants.py plants single mistakes into copies of this
+directory and demands that a pin fails for each.
 Whole-workload trees have no printed example in the paper, so they are pinned
 only through those per-step pins plus the invariants at full size.
 """
