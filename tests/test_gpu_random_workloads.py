@@ -21,7 +21,23 @@ from test_gpu_tree import gpu_prep, grow_and_judge
 
 pytestmark = pytest.mark.gpu
 
-NOMOVE = [None, "0", "1"]      # GBT_TUNE_PART_NOMOVE: the last levels with and without moving rows
+# Contexts are created under one of these settings in turn: every path the growers can take (the default
+# choices, rows moved at every level or not at the last one or two, the three-launch partition, histograms
+# apart from the partition, pairs rounded in a pass of their own, row ids carried along, one loss-guided
+# expansion per round, run-time bit widths, other workgroup shapes)
+VARIANTS = [
+    {},
+    {"GBT_TUNE_PART_NOMOVE": "0"},
+    {"GBT_TUNE_PART_NOMOVE": "1"},
+    {"GBT_TUNE_PART_FUSED": "0"},
+    {"GBT_TUNE_PART_HIST": "0"},
+    {"GBT_TUNE_HIST_FIX": "0"},
+    {"GBT_TUNE_ORDER_ROWS": "0"},
+    {"GBT_TUNE_LOSSGUIDE_BATCH": "1"},
+    {"GBT_TUNE_HIST_RUNTIME_BITS": "1"},
+    {"GBT_TUNE_HIST_BLOCK": "256", "GBT_TUNE_HIST_LDS_KB": "16", "GBT_TUNE_HIST_JOBS": "3"},
+    {"GBT_TUNE_PART_IDS": "0"},
+]
 
 
 def _say(msg):
@@ -84,13 +100,14 @@ def random_workload(seed):
 def check_growers(oracle, monkeypatch, seed):
     import paper_1806_11248_amd as g
     d, gp, p, n, F, desc = random_workload(seed)
-    nomove = NOMOVE[seed % 3]
-    if nomove is None:
-        monkeypatch.delenv("GBT_TUNE_PART_NOMOVE", raising=False)
-    else:
-        monkeypatch.setenv("GBT_TUNE_PART_NOMOVE", nomove)
+    variant = VARIANTS[seed % len(VARIANTS)]
+    for v in VARIANTS:
+        for k in v:
+            monkeypatch.delenv(k, raising=False)
+    for k, v in variant.items():
+        monkeypatch.setenv(k, v)
     lossguide = seed % 4 == 3
-    _say(f"random workload {desc} nomove={nomove} lossguide={lossguide}")
+    _say(f"random workload {desc} {variant} lossguide={lossguide}")
     ctx = g.Context(0)
     try:
         o, gdev = gpu_prep(ctx, oracle, d, use_csr=(seed % 5 == 0))
@@ -174,7 +191,7 @@ def ctx():
     c.close()
 
 
-@pytest.mark.parametrize("seed", range(1000, 1048))
+@pytest.mark.parametrize("seed", range(1000, 1066))
 def test_random_workload_growers(oracle, monkeypatch, seed):
     check_growers(oracle, monkeypatch, seed)
 
