@@ -183,12 +183,31 @@ def check_steps_sparse_predict(ctx, oracle, seed):
     assert np.array_equal(refr, ref) and np.array_equal(got, ref)
 
 
+# the sparse-row histogram with all global bin ids in LDS at once (default where they fit) or in tiles, and
+# with other job counts
+SPARSE_VARIANTS = [{}, {"GBT_TUNE_SPARSE_TILED": "1"}, {"GBT_TUNE_SPARSE_TILED": "1", "GBT_TUNE_SPARSE_JOBS": "4",
+                                                        "GBT_TUNE_HIST_LDS_KB": "16"}]
+
+
 @pytest.fixture(scope="module")
-def ctx():
+def ctxs():
+    """One context per entry of SPARSE_VARIANTS (the variables are read when a context is created)."""
     import paper_1806_11248_amd as g
-    c = g.Context(0)
-    yield c
-    c.close()
+    made = []
+    for variant in SPARSE_VARIANTS:
+        saved = {k: os.environ.get(k) for k in variant}
+        os.environ.update(variant)
+        try:
+            made.append(g.Context(0))
+        finally:
+            for k, v in saved.items():
+                if v is None:
+                    os.environ.pop(k, None)
+                else:
+                    os.environ[k] = v
+    yield made
+    for c in made:
+        c.close()
 
 
 @pytest.mark.parametrize("seed", range(1000, 1066))
@@ -197,11 +216,11 @@ def test_random_workload_growers(oracle, monkeypatch, seed):
 
 
 @pytest.mark.parametrize("seed", range(100000, 100032))
-def test_random_workload_steps_sparse_predict(ctx, oracle, seed):
-    check_steps_sparse_predict(ctx, oracle, seed)
+def test_random_workload_steps_sparse_predict(ctxs, oracle, seed):
+    check_steps_sparse_predict(ctxs[seed % len(ctxs)], oracle, seed)
 
 
-def test_random_workload_sweep(ctx, oracle, monkeypatch):
+def test_random_workload_sweep(ctxs, oracle, monkeypatch):
     budget = float(os.environ.get("GBT_TEST_SWEEP_SECONDS", "0"))
     if budget <= 0:
         pytest.skip("set GBT_TEST_SWEEP_SECONDS to sweep fresh seeds")
@@ -209,6 +228,6 @@ def test_random_workload_sweep(ctx, oracle, monkeypatch):
     t0, k = time.time(), 0
     while time.time() - t0 < budget:
         check_growers(oracle, monkeypatch, seed + k)
-        check_steps_sparse_predict(ctx, oracle, seed + k)
+        check_steps_sparse_predict(ctxs[(seed + k) % len(ctxs)], oracle, seed + k)
         k += 1
     _say(f"swept {k} seeds from {seed}")
