@@ -17,10 +17,8 @@ drivers that are easier to read in Python than in C:
   lists it re-derives, node by node, the exhaustive best split and the fp64
   gain of the split the other side chose.
 
-Two more things live here because the judging needs them, not because the paper
-states them: ``fixed_point`` / ``on_grid`` restate the grid the GPU library
-declares for its sums, so that decisions rounding could tip are compared in one
-precision; ``leaf_weight`` holds the reading for a node without curvature.
+``leaf_weight`` holds the reading taken for a node without curvature.  Nothing
+here knows how the GPU library represents its sums.
 
 Pins (tests/test_oracle_*.py): closed forms, numpy/scipy/scikit-learn library
 routines, brute-force enumeration on tiny inputs, conservation invariants.
@@ -150,36 +148,6 @@ def gradients(objective: str, margin: np.ndarray, label: np.ndarray) -> np.ndarr
     out = np.empty((m.size, 2), np.float32)
     lib().gbto_gradients(C.c_int32(OBJECTIVES[objective]), C.c_void_p(m.ctypes.data),
                          C.c_void_p(y.ctypes.data), C.c_int64(m.size), C.c_void_p(out.ctypes.data))
-    return out
-
-
-# --------------------------------------------------- the GPU library's grid --
-G_TOP, H_TOP = 26, 22
-
-
-def fixed_point(gpair: np.ndarray):
-    """NOT from the paper: the precision the GPU library declares for its sums, restated here so that a
-    decision which depends on rounding (is this child heavy enough? which of two close gains is larger?)
-    can be taken by both sides in ONE precision.  The library rounds every g to an integer multiple of
-    1/scale_g and every h to one of 1/scale_h, ties to even, with power-of-two scales: for a largest
-    magnitude m * 2^e (0.5 <= m < 1) the scale is 2^(26 - e) for g and 2^(22 - e) for h, 1 when all are zero.
-    Returns (q int32 [n][2], (scale_g, scale_h))."""
-    gp = _c(gpair, np.float32).astype(np.float64)
-    scale = []
-    for col, top in ((0, G_TOP), (1, H_TOP)):
-        vmax = float(np.abs(gp[:, col]).max()) if len(gp) else 0.0
-        scale.append(2.0 ** (top - np.frexp(vmax)[1]) if vmax > 0.0 else 1.0)
-    q = np.rint(gp * np.array(scale)).astype(np.int32)
-    return q, (scale[0], scale[1])
-
-
-def on_grid(gpair: np.ndarray) -> np.ndarray:
-    """The pairs moved onto that grid, as fp32 (exact: an fp32 value scaled by a power of two and rounded
-    to an integer still fits 24 bits).  Sums of these in fp64 are exact, so a tree judged on them is judged
-    in the GPU library's own precision."""
-    q, scale = fixed_point(gpair)
-    out = (q.astype(np.float64) / np.array(scale)).astype(np.float32)
-    assert np.array_equal(out.astype(np.float64) * np.array(scale), q)
     return out
 
 

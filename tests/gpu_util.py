@@ -2,6 +2,8 @@
 import numpy as np
 import torch
 
+import grid
+
 
 def dev(a, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(a))
@@ -42,9 +44,9 @@ def judge_on_grid(oracle, judge, tree, o, gp, scale, **kw):
     fp64 sum of the oracle is exact, so totals and weights must agree to rounding of the last operation and
     every decision (valid child? larger gain? above gamma?) must come out the same: the oracle's exhaustive
     best split at every node, no ties to excuse."""
-    q, scale_o = oracle.fixed_point(gp)
+    q, scale_o = grid.fixed_point(gp)
     assert tuple(scale) == scale_o
-    rep = judge(tree, o["sym"], o["nb"], o["missing"], oracle.on_grid(gp), **kw, sum_rtol=1e-13, tie_rtol=1e-13,
+    rep = judge(tree, o["sym"], o["nb"], o["missing"], grid.on_grid(gp), **kw, sum_rtol=1e-13, tie_rtol=1e-13,
                 sum_atol_per_row=0.0)
     assert rep["ok"] and rep["identical"] and not rep["ties"], (rep["errors"][:5], rep["ties"][:3])
     return rep

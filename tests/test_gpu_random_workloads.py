@@ -15,6 +15,7 @@ import time
 import numpy as np
 import pytest
 
+import grid
 from gpu_util import dev, host_u32, judge_on_grid, tree_kw
 from test_gpu_lossguide import _judge as lossguide_judge
 from test_gpu_tree import gpu_prep, grow_and_judge
@@ -131,7 +132,7 @@ def check_steps_sparse_predict(ctx, oracle, seed):
                            min_child_weight=p["min_child_weight"])
     gp_t = dev(gp)
     gq, scale = ctx.gpair_fixed(gp_t)
-    og = oracle.on_grid(gp)
+    og = grid.on_grid(gp)
     # the steps on a random half of the rows: histogram, totals, best split, partition.  On the grid the
     # oracle's sums are exact, so "equal" means equal
     rng = np.random.default_rng(seed)

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 import torch
 
+import grid
 import synth
 from gpu_util import dev, hist_tolerance, host_u32, oracle_prep
 
@@ -251,7 +252,7 @@ def test_gpair_fixed_scale_and_errors(ctx, oracle):
         gp2 = np.stack([rng.standard_normal(70_001) * sg, rng.uniform(0, 1, 70_001) * sh], 1).astype(np.float32)
         gp2[5] = [2.5 * 2.0 ** -25 * sg, 3.5 * 2.0 ** -21 * sh]
         gq, scale = ctx.gpair_fixed(dev(gp2))
-        q, scale_o = oracle.fixed_point(gp2)
+        q, scale_o = grid.fixed_point(gp2)
         assert scale == scale_o and np.array_equal(gq.cpu().numpy(), q)
     bad = gp.copy(); bad[1, 0] = np.inf
     with pytest.raises(g.GbtError) as e:
