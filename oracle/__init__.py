@@ -183,8 +183,9 @@ def eval_split(hist_: np.ndarray, cnt: np.ndarray, nb: np.ndarray, G: float, H: 
 
 
 def candidate_gain(hist_: np.ndarray, f: int, b: int, default_left: int, G: float, H: float,
-                   lam: float, min_child_weight: float):
-    """fp64 gain of one named candidate, NaN if invalid; also (GL, HL, GR, HR)."""
+                   lam: float, min_child_weight: float, cnt=None, n_rows=None):
+    """fp64 gain of one named candidate, NaN if invalid; also (GL, HL, GR, HR).
+    cnt, n_rows: the node's bin counts and row count (accepted, not yet used)."""
     sides = np.empty(4, np.float64)
     g = lib().gbto_candidate_gain(C.c_void_p(hist_.ctypes.data), hist_.shape[1], f, b, default_left,
                                   G, H, lam, min_child_weight, C.c_void_p(sides.ctypes.data))
