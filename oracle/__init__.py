@@ -72,8 +72,8 @@ def lib():
         L.gbto_packed_words.restype = C.c_int64
         L.gbto_partition.restype = C.c_int64
         L.gbto_candidate_gain.restype = C.c_double
-        L.gbto_candidate_gain.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                                          C.c_double, C.c_double, C.c_double, C.c_double, C.c_void_p]
+        L.gbto_candidate_gain.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32,
+                                          C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double, C.c_void_p]
         L.gbto_eval_split.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_double, C.c_double, C.c_int64, C.c_double, C.c_double,
                                       C.POINTER(Split)]
@@ -183,12 +183,15 @@ def eval_split(hist_: np.ndarray, cnt: np.ndarray, nb: np.ndarray, G: float, H: 
 
 
 def candidate_gain(hist_: np.ndarray, f: int, b: int, default_left: int, G: float, H: float,
-                   lam: float, min_child_weight: float, cnt=None, n_rows=None):
-    """fp64 gain of one named candidate, NaN if invalid; also (GL, HL, GR, HR).
-    cnt, n_rows: the node's bin counts and row count (accepted, not yet used)."""
+                   lam: float, min_child_weight: float, *, cnt: np.ndarray, n_rows: int):
+    """fp64 gain of one named candidate, NaN if invalid (a side without rows, or lighter than
+    min_child_weight: the rule of ``eval_split``); also (GL, HL, GR, HR).
+    cnt, n_rows: the node's bin counts (from ``hist``) and its row count."""
     sides = np.empty(4, np.float64)
-    g = lib().gbto_candidate_gain(C.c_void_p(hist_.ctypes.data), hist_.shape[1], f, b, default_left,
-                                  G, H, lam, min_child_weight, C.c_void_p(sides.ctypes.data))
+    cnt = _c(cnt, np.int64)
+    g = lib().gbto_candidate_gain(C.c_void_p(hist_.ctypes.data), C.c_void_p(cnt.ctypes.data), hist_.shape[1],
+                                  int(n_rows), f, b, default_left, G, H, lam, min_child_weight,
+                                  C.c_void_p(sides.ctypes.data))
     return float(g), sides
 
 
@@ -453,7 +456,7 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
             if not (0 <= f < F and 0 <= b < nb[f]):
                 err(f"node {node}: split ({f},{b}) out of range")
                 continue
-            g_other, _ = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight)
+            g_other, _ = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight, cnt=cnt, n_rows=hi - lo)
             if not np.isfinite(g_other):
                 err(f"node {node}: chosen split ({f},{b},{dl}) is not a valid candidate")
             elif full:
@@ -522,10 +525,10 @@ def replay_tree_lossguide(other, sym, nb, missing_sym, gpair, *, max_leaves, max
         best = eval_split(h_, cnt, nb, G, H, hi - lo, lam, min_child_weight) \
             if depth < max_depth else dict(valid=0, gain=-np.inf, feature=-1, bin=0, default_left=0)
         seg[node] = (lo, hi, depth)
-        info[node] = (h_, G, H, best)
+        info[node] = (h_, cnt, G, H, best)
 
     def open_gain(node):
-        best = info[node][3]
+        best = info[node][4]
         return best["gain"] if bool(best["valid"]) and best["gain"] > thr else -np.inf
 
     nn = int(other["n_nodes"])
@@ -545,12 +548,12 @@ def replay_tree_lossguide(other, sym, nb, missing_sym, gpair, *, max_leaves, max
             err(f"expansion {k}: children {li},{ri} do not hang under one current leaf")
             return rep
         lo, hi, depth = seg[node]
-        h_, G, H, best = info[node]
+        h_, cnt, G, H, best = info[node]
         f, b, dl = int(other["feature"][node]), int(other["bin"][node]), int(other["default_left"][node])
         if not (0 <= f < F and 0 <= b < nb[f]) or depth >= max_depth:
             err(f"node {node}: split ({f},{b}) out of range or too deep")
             return rep
-        g_other, _ = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight)
+        g_other, _ = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight, cnt=cnt, n_rows=hi - lo)
         if not np.isfinite(g_other):
             err(f"node {node}: chosen split ({f},{b},{dl}) is not a valid candidate")
             return rep

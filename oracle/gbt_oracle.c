@@ -276,22 +276,28 @@ static double split_gain(double GL, double HL, double GR, double HR, double G, d
 
 /*
  * Gain of one named candidate (feature f, bin b, direction) from a node's
- * histogram; NaN when the candidate is not valid.  Used to price a split that
- * somebody else chose.
+ * histogram and bin counts; NaN when the candidate is not valid.  The rule is
+ * the one of the exhaustive search below: both sides hold at least one row and
+ * both have H >= min_child_weight.  Used to price a split that somebody else
+ * chose.
  */
-double gbto_candidate_gain(const double *hist, int32_t B, int32_t f, int32_t b, int32_t default_left,
-                           double G, double H, double lambda, double min_child_weight,
-                           double *sides_out /* GL HL GR HR, may be NULL */)
+double gbto_candidate_gain(const double *hist, const int64_t *cnt, int32_t B, int64_t n_rows, int32_t f,
+                           int32_t b, int32_t default_left, double G, double H, double lambda,
+                           double min_child_weight, double *sides_out /* GL HL GR HR, may be NULL */)
 {
     const double *hf = hist + (int64_t)f * B * 2;
+    const int64_t *cf = cnt + (int64_t)f * B;
     double sg = 0.0, sh = 0.0;
-    for (int32_t k = 0; k < B; ++k) { sg += hf[2 * k]; sh += hf[2 * k + 1]; }
+    int64_t present = 0;
+    for (int32_t k = 0; k < B; ++k) { sg += hf[2 * k]; sh += hf[2 * k + 1]; present += cf[k]; }
     double Gm = G - sg, Hm = H - sh;
     double GL = 0.0, HL = 0.0;
-    for (int32_t k = 0; k <= b; ++k) { GL += hf[2 * k]; HL += hf[2 * k + 1]; }
-    if (default_left) { GL += Gm; HL += Hm; }
+    int64_t n_left = 0;
+    for (int32_t k = 0; k <= b; ++k) { GL += hf[2 * k]; HL += hf[2 * k + 1]; n_left += cf[k]; }
+    if (default_left) { GL += Gm; HL += Hm; n_left += n_rows - present; }
     double GR = G - GL, HR = H - HL;
     if (sides_out) { sides_out[0] = GL; sides_out[1] = HL; sides_out[2] = GR; sides_out[3] = HR; }
+    if (n_left == 0 || n_left == n_rows) return NAN; /* a side without rows is no split */
     if (!(HL >= min_child_weight) || !(HR >= min_child_weight)) return NAN;
     return split_gain(GL, HL, GR, HR, G, H, lambda);
 }

@@ -310,7 +310,8 @@ def test_eval_split(ctx, oracle, n, F, B, miss, lam, mcw):
     if not ref["valid"]:
         return
     same = (sp["feature"], sp["bin"], sp["default_left"]) == (ref["feature"], ref["bin"], ref["default_left"])
-    g_own, sides = oracle.candidate_gain(ref_h, sp["feature"], sp["bin"], sp["default_left"], G, H, lam, mcw)
+    g_own, sides = oracle.candidate_gain(ref_h, sp["feature"], sp["bin"], sp["default_left"], G, H, lam, mcw,
+                                         cnt=cnt, n_rows=n)
     assert same or abs(g_own - ref["gain"]) <= 1e-6 * abs(ref["gain"])
     assert abs(sp["gain"] - g_own) <= 1e-5 * abs(g_own) + 1e-9
     assert np.allclose([sp["GL"], sp["HL"], sp["GR"], sp["HR"]], sides, rtol=1e-5, atol=n * 0.5 / min(scale))

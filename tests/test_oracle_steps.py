@@ -149,7 +149,7 @@ def test_split_against_brute_force(oracle, seed):
     assert np.isclose(sp["gain"], gain, rtol=1e-10, atol=1e-12)
     assert (sp["feature"], sp["bin"], sp["default_left"]) == where
     assert sp["gain"] >= -1e-12          # lambda >= 0: the best valid candidate never loses
-    g2, sides = oracle.candidate_gain(h, *where, G, H, lam, mcw)
+    g2, sides = oracle.candidate_gain(h, *where, G, H, lam, mcw, cnt=cnt, n_rows=len(sym))
     assert np.isclose(g2, gain, rtol=1e-10, atol=1e-12)
     assert np.allclose(sides, [sp["GL"], sp["HL"], sp["GR"], sp["HR"]], rtol=1e-12, atol=1e-12)
 
@@ -182,7 +182,6 @@ def test_split_never_leaves_a_side_without_rows(oracle, seed):
     assert not oracle.eval_split(h1, cnt1, np.array([5], np.int32), G1, H1, 50, 1.0, 0.0)["valid"]
 
 
-@pytest.mark.xfail(strict=True, reason="pin written before the rule: candidate_gain does not yet refuse a side without rows")
 @pytest.mark.parametrize("seed", range(4))
 def test_named_candidate_is_priced_by_the_search_rule(oracle, seed):
     # Pricing a candidate by name must follow the rule of the exhaustive search: valid iff BOTH sides hold a row
@@ -294,15 +293,15 @@ def test_split_tie_break_and_min_child_weight(oracle):
     sp = oracle.eval_split(h, cnt, nb, G, H, 4, 1.0, 2.5)
     assert not sp["valid"]
     # and pricing that candidate by name says the same: a gain at weight 2 (each side holds exactly 2), none at 2.5
-    assert np.isclose(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.0)[0], 4 / 3 + 4 / 3)
-    assert np.isnan(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.5)[0])
+    assert np.isclose(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.0, cnt=cnt, n_rows=4)[0], 4 / 3 + 4 / 3)
+    assert np.isnan(oracle.candidate_gain(h, 0, 0, 0, G, H, 1.0, 2.5, cnt=cnt, n_rows=4)[0])
     # a side without curvature under lambda = 0 counts nothing (not +inf): 2^2/2 + 0 - 8^2/2
     symz = np.array([[0], [0], [1], [1]], np.uint16)
     gpz = np.array([[1, 1], [1, 1], [-5, 0], [-5, 0]], np.float32)
     hz, cntz, Gz, Hz = oracle.hist(symz, 2, 2, None, gpz)
     spz = oracle.eval_split(hz, cntz, np.array([2], np.int32), Gz, Hz, 4, 0.0, 0.0)
     assert spz["valid"] and (spz["feature"], spz["bin"]) == (0, 0) and spz["gain"] == 2.0 + 0.0 - 32.0
-    assert oracle.candidate_gain(hz, 0, 0, 0, Gz, Hz, 0.0, 0.0)[0] == -30.0
+    assert oracle.candidate_gain(hz, 0, 0, 0, Gz, Hz, 0.0, 0.0, cnt=cntz, n_rows=4)[0] == -30.0
     # a single-bin feature with nothing missing can never split
     sym1 = np.zeros((5, 1), np.uint16)
     gp1 = np.stack([np.arange(5) - 2.0, np.ones(5)], 1).astype(np.float32)

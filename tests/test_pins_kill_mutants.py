@@ -54,6 +54,9 @@ MUTANTS = [
     ("right term over the left hessian", C, 1, "double b = term(GR, HR, lambda);", "double b = term(GR, HL, lambda);"),
     ("a side without rows may win", C, 1, "if (n_left == 0 || n_left == n_rows) continue;",
      "if (b == nb[f] - 1 && (dir == 1 || !has_missing)) continue;"),
+    ("a named candidate with a side without rows is priced", C, 1, "if (n_left == 0 || n_left == n_rows) return NAN; /* a side without rows is no split */", ""),
+    ("a named candidate forgets the rows of the missing side", C, 1, "if (default_left) { GL += Gm; HL += Hm; n_left += n_rows - present; }",
+     "if (default_left) { GL += Gm; HL += Hm; }"),
     ("rows of the missing side not counted", C, 1, "int64_t n_left = pc + (dir == 1 ? n_rows - present : 0);", "int64_t n_left = pc;"),
     ("later candidate wins ties", C, 1, "if (gain > best.gain) {", "if (gain >= best.gain) {"),
     ("missing mass on the wrong side", C, 1, "if (dir == 1) { GL += Gm; HL += Hm; }", "if (dir == 0) { GL += Gm; HL += Hm; }"),
@@ -62,9 +65,9 @@ MUTANTS = [
      "if (!(HL >= min_child_weight)) continue;"),
     ("prefix sum skips the split bin", C, 1, "for (int32_t b = 0; b < nb[f]; ++b) {\n            pg += hf[2 * b];\n            ph += hf[2 * b + 1];",
      "for (int32_t b = 0; b < nb[f]; ++b) {\n            if (b) { pg += hf[2 * b - 2]; ph += hf[2 * b - 1]; }"),
-    ("named candidate: prefix excludes its bin", C, 1, "for (int32_t k = 0; k <= b; ++k) { GL += hf[2 * k]; HL += hf[2 * k + 1]; }",
-     "for (int32_t k = 0; k < b; ++k) { GL += hf[2 * k]; HL += hf[2 * k + 1]; }"),
-    ("named candidate: default side ignored", C, 1, "if (default_left) { GL += Gm; HL += Hm; }", ""),
+    ("named candidate: prefix excludes its bin", C, 1, "for (int32_t k = 0; k <= b; ++k) { GL += hf[2 * k]; HL += hf[2 * k + 1]; n_left += cf[k]; }",
+     "for (int32_t k = 0; k < b; ++k) { GL += hf[2 * k]; HL += hf[2 * k + 1]; n_left += cf[k]; }"),
+    ("named candidate: default side ignored", C, 1, "if (default_left) { GL += Gm; HL += Hm; n_left += n_rows - present; }", ""),
     ("named candidate: child weights not checked", C, 1,
      "if (!(HL >= min_child_weight) || !(HR >= min_child_weight)) return NAN;", ""),
     # Alg. 1: repartition
