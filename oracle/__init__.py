@@ -390,6 +390,20 @@ def _weight_atol(w, denom, atol):
     return (1.0 + abs(w)) * atol / (denom - atol) if denom > atol else np.inf
 
 
+def _gain_atol(sides, G, H, lam, rtol, atol):
+    """How far a reported gain may lie from the oracle's gain of the same candidate when every sum behind it
+    (GL, HL, GR, HR, G, H) carries a relative error of rtol and an absolute one of atol.  A term T = S^2 / D
+    with D = Hs + lambda moves by at most (2|w| + w^2) * dS for w = S / D, and by 3 * rtol * T; the gain is
+    two terms minus a third, so the three allowances add up."""
+    tol = 0.0
+    for S, Hs in ((sides[0], sides[1]), (sides[2], sides[3]), (G, H)):
+        D = Hs + lam
+        if D > 0.0:
+            w = abs(S) / D
+            tol += 3.0 * rtol * S * S / D + (2.0 * w + w * w) * atol
+    return tol
+
+
 def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=1.0, gamma=0.0,
                 min_child_weight=1.0, tie_rtol=1e-6, sum_rtol=1e-5, sum_atol_per_row=0.0,
                 nodes=None):
@@ -398,9 +412,11 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
     Walks ``other`` from the root with the oracle's OWN row lists.  For every
     node it checks the row count exactly, the (G, H) totals and the leaf weight
     to ``sum_rtol`` (plus ``sum_atol_per_row`` * rows, the other side's stated
-    per-row quantisation bound), and the split decision: identical to the
-    oracle's exhaustive best, or its fp64 gain within ``tie_rtol`` (relative) of
-    the best one.  Children are then formed with the OTHER side's split, so one
+    per-row quantisation bound), the gain the other side reports for its split
+    (against the oracle's fp64 gain of that same candidate, within what those
+    allowances on the sums can move it), and the split decision: identical to
+    the oracle's exhaustive best, or its fp64 gain within ``tie_rtol``
+    (relative) of the best one.  Children are then formed with the OTHER side's split, so one
     legal tie does not make the rest incomparable.
 
     ``nodes``: optional set of node ids whose split is searched exhaustively
@@ -430,7 +446,7 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
         full = nodes is None or node in nodes
         if int(other["n_rows"][node]) != hi - lo:
             err(f"node {node}: n_rows {int(other['n_rows'][node])} != {hi - lo}")
-        if full or is_split:
+        if is_split or (full and depth < max_depth):
             h_, cnt, G, H = hist(sym, B, missing_sym, r, gpair)
         else:
             gp = np.asarray(gpair, np.float32)[r].astype(np.float64)
@@ -456,10 +472,12 @@ def replay_tree(other, sym, nb, missing_sym, gpair, *, max_depth, max_bins, lam=
             if not (0 <= f < F and 0 <= b < nb[f]):
                 err(f"node {node}: split ({f},{b}) out of range")
                 continue
-            g_other, _ = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight, cnt=cnt, n_rows=hi - lo)
+            g_other, sides = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight, cnt=cnt, n_rows=hi - lo)
             if not np.isfinite(g_other):
                 err(f"node {node}: chosen split ({f},{b},{dl}) is not a valid candidate")
-            elif full:
+            elif abs(other["gain"][node] - g_other) > _gain_atol(sides, G, H, lam, sum_rtol, atol) + 1e-300:
+                err(f"node {node}: reported gain {other['gain'][node]!r} vs {g_other!r} for its own split")
+            if np.isfinite(g_other) and full:
                 same = (f, b, dl) == (best["feature"], best["bin"], best["default_left"])
                 if not same:
                     rep["identical"] = False
@@ -553,10 +571,12 @@ def replay_tree_lossguide(other, sym, nb, missing_sym, gpair, *, max_leaves, max
         if not (0 <= f < F and 0 <= b < nb[f]) or depth >= max_depth:
             err(f"node {node}: split ({f},{b}) out of range or too deep")
             return rep
-        g_other, _ = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight, cnt=cnt, n_rows=hi - lo)
+        g_other, sides = candidate_gain(h_, f, b, dl, G, H, lam, min_child_weight, cnt=cnt, n_rows=hi - lo)
         if not np.isfinite(g_other):
             err(f"node {node}: chosen split ({f},{b},{dl}) is not a valid candidate")
             return rep
+        if abs(other["gain"][node] - g_other) > _gain_atol(sides, G, H, lam, sum_rtol, sum_atol_per_row * (hi - lo)) + 1e-300:
+            err(f"node {node}: reported gain {other['gain'][node]!r} vs {g_other!r} for its own split")
         if (f, b, dl) != (best["feature"], best["bin"], best["default_left"]):
             rep["identical"] = False
             rep["ties"].append((node, (f, b, dl), (best["feature"], best["bin"], best["default_left"]),

@@ -136,6 +136,11 @@ def test_replay_judge_accepts_and_rejects(oracle):
     short, _, _ = oracle.grow_tree_lossguide(sym, nb, cuts, missing, gp, **dict(kw, max_leaves=6))
     rep = oracle.replay_tree_lossguide(short, sym, nb, missing, gp, **kw)
     assert not rep["ok"] and any("stopped at" in e for e in rep["errors"])
+    # a reported gain that is not the gain of the reported split
+    t2 = copy.deepcopy(t)
+    t2["gain"][1] *= 1.001
+    rep = oracle.replay_tree_lossguide(t2, sym, nb, missing, gp, **kw)
+    assert not rep["ok"] and all("reported gain" in e for e in rep["errors"])
     # a wrong bin, a wrong total, a wrong row count: each caught
     for field, delta, what in (("bin", 1, "gain"), ("sumG", 1.0, "sumG"), ("n_rows", 1, "n_rows")):
         t2 = copy.deepcopy(t)

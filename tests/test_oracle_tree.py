@@ -199,6 +199,10 @@ def test_replay_accepts_own_tree_and_rejects_planted_mistakes(oracle, c1):
     # row counts
     bad = copy.deepcopy(t); bad["n_rows"][2] += 1
     assert not oracle.replay_tree(bad, sym, nb, missing, gp, **kw)["ok"]
+    # a reported gain that is not the gain of the reported split (1e-4 off; the allowance is 3e-5 of the terms)
+    bad = copy.deepcopy(t); bad["gain"][2] += 1e-4 * (t["sumG"][2] ** 2 / (t["sumH"][2] + kw["lam"]) + bad["gain"][2])
+    rep = oracle.replay_tree(bad, sym, nb, missing, gp, **kw)
+    assert not rep["ok"] and all("reported gain" in e for e in rep["errors"])
     # a tree that is consistent throughout (counts, totals, weights, partitions) but was grown blind to
     # the feature the root should split on: only the comparison of the gains can tell
     nb_blind = nb.copy(); nb_blind[int(t["feature"][0])] = 1

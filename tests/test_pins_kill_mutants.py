@@ -102,6 +102,9 @@ MUTANTS = [
     ("boosting: margin not carried over", PY, 1, "margin = predict_sym(t, sym, missing_sym, eta, margin)",
      "margin = predict_sym(t, sym, missing_sym, eta, np.full(n, base_margin, np.float32))"),
     ("judge: accepts any gain", PY, 1, "close = abs(g_other - best[\"gain\"]) <= tie_rtol * abs(best[\"gain\"])", "close = True"),
+    ("judge: reported gains not compared", PY, 1, "elif abs(other[\"gain\"][node] - g_other) > _gain_atol(sides, G, H, lam, sum_rtol, atol) + 1e-300:", "elif False:"),
+    ("loss-guided judge: reported gains not compared", PY, 1,
+     "if abs(other[\"gain\"][node] - g_other) > _gain_atol(sides, G, H, lam, sum_rtol, sum_atol_per_row * (hi - lo)) + 1e-300:", "if False:"),
     ("judge: row counts not compared", PY, 1, 'if int(other["n_rows"][node]) != hi - lo:', "if False:"),
     ("judge: leaf weights not compared", PY, 1, 'if abs(other["weight"][node] - w) > w_tol + 1e-300:', "if False:"),
     ("judge: weight tolerance without the hessian's share", PY, 1, "    return (1.0 + abs(w)) * atol / (denom - atol) if denom > atol else np.inf",
