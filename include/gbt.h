@@ -267,6 +267,24 @@ GBT_API int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t bits
                       int32_t default_left, int32_t missing_sym, void *workspace,
                       size_t workspace_bytes, int64_t *n_left_out);
 
+/*
+ * gbt_partition for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments (without the workspace), same result, same
+ * kernels; the scratch memory is a static device array inside the library, sized
+ * for segments of at most GBT_PARTITION_STATIC_MAX_ROWS rows (about 17 MB, held
+ * by every GPU the library runs on until the process ends).  A longer segment
+ * is refused with GBT_EUNSUPPORTED and nothing is enqueued.  The call allocates
+ * nothing.  Every call on one GPU uses that GPU's one array: calls that overlap
+ * on one GPU (two contexts, two streams) race and must be serialised by the
+ * caller.  The array keeps the last call's contents; no call depends on them.
+ * Synchronises the stream.
+ */
+#define GBT_PARTITION_STATIC_MAX_ROWS (1 << 22)
+GBT_API int32_t gbt_partition_static(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                      uint32_t *row_idx, int64_t begin, int64_t end, int32_t feature, int32_t bin,
+                      int32_t default_left, int32_t missing_sym, int64_t *n_left_out);
+
 /* ---- Alg. 1 as a whole -------------------------------------------------- */
 
 GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits, int32_t max_bins,

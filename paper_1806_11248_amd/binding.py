@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgbt.so")
 
 OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4
+PARTITION_STATIC_MAX_ROWS = 1 << 22   # GBT_PARTITION_STATIC_MAX_ROWS
 OBJECTIVES = {"squared": 0, "logistic": 1}
 
 # every symbol include/gbt.h declares
@@ -25,6 +26,7 @@ SYMBOLS = [
     "gbt_quantise_workspace_bytes", "gbt_quantise", "gbt_bits", "gbt_packed_words", "gbt_compress",
     "gbt_gradients", "gbt_gpair_fixed", "gbt_sum_gpair", "gbt_build_hist", "gbt_hist_subtract",
     "gbt_hist_export_f64", "gbt_eval_split", "gbt_partition_workspace_bytes", "gbt_partition",
+    "gbt_partition_static",
     "gbt_grow_tree_workspace_bytes", "gbt_grow_tree_path", "gbt_grow_tree",
     "gbt_grow_tree_lossguide_workspace_bytes", "gbt_grow_tree_lossguide", "gbt_predict_workspace_bytes", "gbt_predict",
     "gbt_profile_enable", "gbt_profile_read",
@@ -111,6 +113,7 @@ def load():
     L.gbt_hist_export_f64.argtypes = [vp, vp, i32, i32, vp, vp]
     L.gbt_eval_split.argtypes = [vp, vp, vp, i32, i32, i64, i64, vp, vp, vp, vp, sz]
     L.gbt_partition.argtypes = [vp, vp, i32, i64, i32, vp, i64, i64, i32, i32, i32, i32, vp, sz, vp]
+    L.gbt_partition_static.argtypes = [vp, vp, i32, i64, i32, vp, i64, i64, i32, i32, i32, i32, vp]
     L.gbt_grow_tree.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
     L.gbt_grow_tree_lossguide.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz]
     L.gbt_predict.argtypes = [vp, vp, i32, vp, i32, i32, vp, i64, i32, f64, vp, vp, sz]
@@ -361,6 +364,14 @@ class Context:
         nl = C.c_int64()
         self._check(self.lib.gbt_partition(self.h, _ptr(packed), bits, n, F, _ptr(row_idx), begin, end, feature,
                                            bin_, default_left, missing_sym, _ptr(ws), ws.numel(), C.byref(nl)))
+        return nl.value
+
+    def partition_static(self, packed, bits, n, F, row_idx, begin, end, feature, bin_, default_left, missing_sym) -> int:
+        """gbt_partition_static: the same partition over the library's static scratch array (no workspace)."""
+        _need(row_idx, torch.int32, "row_idx")
+        nl = C.c_int64()
+        self._check(self.lib.gbt_partition_static(self.h, _ptr(packed), bits, n, F, _ptr(row_idx), begin, end, feature,
+                                                  bin_, default_left, missing_sym, C.byref(nl)))
         return nl.value
 
     # -- Alg. 1 --------------------------------------------------------------

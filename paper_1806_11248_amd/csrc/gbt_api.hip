@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <set>
 #include <vector>
@@ -23,6 +24,8 @@ int32_t gbt_fail(gbt_ctx *ctx, int32_t code, const char *fmt, ...) {
 }
 
 namespace {
+
+hipError_t part_static_address(int device, char **out);   // gbt_partition_static's scratch array, below
 
 constexpr size_t kUploadBytes = GBT_STAGING_BYTES / 2;   // first half of the pinned staging
 constexpr size_t kReadbackOff = GBT_STAGING_BYTES / 2;   // second half
@@ -230,10 +233,12 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->lds_per_block = lds;
         e = hipHostMalloc((void **)&c->pinned, GBT_STAGING_BYTES, hipHostMallocDefault);
         c->pinned_bytes = GBT_STAGING_BYTES;
+        if (e == hipSuccess) e = part_static_address(device, &c->part_static);
     }
     if (e != hipSuccess) {
         fprintf(stderr, "libgbt: gbt_create failed: %s\n", hipGetErrorString(e));
         (void)hipGetLastError();
+        if (c->pinned) (void)hipHostFree(c->pinned);
         delete c->spans;
         delete c->free_events;
         delete c;
@@ -485,8 +490,8 @@ namespace {
 struct PartLayout {
     size_t dst, masks, tile_left, jobs, n_left, total;
 };
-PartLayout part_layout(int64_t n_rows) {
-    PartLayout L;
+constexpr PartLayout part_layout(int64_t n_rows) {
+    PartLayout L{};
     int64_t tiles = (n_rows + GBT_PART_TILE - 1) / GBT_PART_TILE + 1;
     size_t o = 0;
     L.dst = o;       o += gbt_align((size_t)n_rows * 4);
@@ -497,32 +502,15 @@ PartLayout part_layout(int64_t n_rows) {
     L.total = o;
     return L;
 }
-}  // namespace
 
-extern "C" size_t gbt_partition_workspace_bytes(int64_t n_rows) {
-    return n_rows < 0 ? 0 : part_layout(n_rows).total;
-}
-
-extern "C" int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
-                                 uint32_t *row_idx, int64_t begin, int64_t end, int32_t feature, int32_t bin,
-                                 int32_t default_left, int32_t missing_sym, void *workspace,
-                                 size_t workspace_bytes, int64_t *n_left_out) {
-    if (!ctx) return GBT_EINVAL;
-    int32_t st = check_matrix(ctx, packed, bits, n, F);
-    if (st != GBT_OK) return st;
-    GBT_REQUIRE(ctx, row_idx && workspace && n_left_out, GBT_EINVAL, "NULL argument");
-    GBT_REQUIRE(ctx, 0 <= begin && begin <= end && end - begin <= n, GBT_EINVAL, "bad segment [%lld, %lld)",
-                (long long)begin, (long long)end);
-    GBT_REQUIRE(ctx, feature >= 0 && feature < F, GBT_EINVAL, "feature %d outside [0, %d)", feature, F);
-    GBT_REQUIRE(ctx, bin >= 0 && missing_sym >= 0, GBT_EINVAL, "negative bin or missing symbol");
-    int64_t len = end - begin;
-    PartLayout L = part_layout(len);
-    GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
-    if (len == 0) {
-        *n_left_out = 0;
-        return GBT_OK;
-    }
-    char *ws = (char *)workspace;
+// The stable three-launch partition of one segment over the scratch memory `ws` (part_layout(len).total
+// bytes, none of which has to hold anything on entry: every word a launch reads, an earlier launch of the
+// same call has written).
+int32_t partition_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F, uint32_t *row_idx,
+                       int64_t begin, int64_t end, int32_t feature, int32_t bin, int32_t default_left,
+                       int32_t missing_sym, char *ws, int64_t *n_left_out) {
+    const int64_t len = end - begin;
+    const PartLayout L = part_layout(len);
     PartJob job;
     job.seg_begin = 0;
     job.seg_len = (uint32_t)len;
@@ -532,7 +520,7 @@ extern "C" int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     job.tile_begin = 0;
     job.n_tiles = (uint32_t)((len + GBT_PART_TILE - 1) / GBT_PART_TILE);
     job.pad = 0;
-    st = upload(ctx, &job, sizeof job, ws + L.jobs);
+    int32_t st = upload(ctx, &job, sizeof job, ws + L.jobs);
     if (st != GBT_OK) return st;
     uint32_t *seg = row_idx + begin;
     GBT_HIP(ctx, gbt_launch_partition(ctx->stream, packed, bits, (int64_t)F * bits, n, (uint32_t)missing_sym, seg,
@@ -546,6 +534,92 @@ extern "C" int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t b
     memcpy(&nl, rb(ctx), 4);
     *n_left_out = nl;
     return GBT_OK;
+}
+
+int32_t check_partition_args(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                             const uint32_t *row_idx, int64_t begin, int64_t end, int32_t feature, int32_t bin,
+                             int32_t missing_sym, const int64_t *n_left_out) {
+    int32_t st = check_matrix(ctx, packed, bits, n, F);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, row_idx && n_left_out, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, 0 <= begin && begin <= end && end - begin <= n, GBT_EINVAL, "bad segment [%lld, %lld)",
+                (long long)begin, (long long)end);
+    GBT_REQUIRE(ctx, feature >= 0 && feature < F, GBT_EINVAL, "feature %d outside [0, %d)", feature, F);
+    GBT_REQUIRE(ctx, bin >= 0 && missing_sym >= 0, GBT_EINVAL, "negative bin or missing symbol");
+    return GBT_OK;
+}
+}  // namespace
+
+extern "C" size_t gbt_partition_workspace_bytes(int64_t n_rows) {
+    return n_rows < 0 ? 0 : part_layout(n_rows).total;
+}
+
+extern "C" int32_t gbt_partition(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                 uint32_t *row_idx, int64_t begin, int64_t end, int32_t feature, int32_t bin,
+                                 int32_t default_left, int32_t missing_sym, void *workspace,
+                                 size_t workspace_bytes, int64_t *n_left_out) {
+    if (!ctx) return GBT_EINVAL;
+    int32_t st = check_partition_args(ctx, packed, bits, n, F, row_idx, begin, end, feature, bin, missing_sym, n_left_out);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, workspace != nullptr, GBT_EINVAL, "NULL argument");
+    const size_t need = part_layout(end - begin).total;
+    GBT_REQUIRE(ctx, workspace_bytes >= need, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, need);
+    if (end == begin) {
+        *n_left_out = 0;
+        return GBT_OK;
+    }
+    return partition_impl(ctx, packed, bits, n, F, row_idx, begin, end, feature, bin, default_left, missing_sym,
+                          (char *)workspace, n_left_out);
+}
+
+// ---- the same partition for callers that cannot allocate ------------------------------------------
+// Its scratch memory (ballot masks, tile counts, the reordered ids) is a static device array instead of
+// a caller workspace.  In host code the array's name is only a stand-in: the address a kernel can use
+// is asked for once per device, with that device current (gbt_create does it), and kept.
+namespace {
+constexpr size_t kPartStaticBytes = part_layout(GBT_PARTITION_STATIC_MAX_ROWS).total;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kPartStaticBytes];
+namespace {
+char *g_part_static[kMaxDevices];   // per device: the address of its copy of `scratch`
+std::mutex g_part_static_mu;
+
+// Called with `device` current.  Returns hipSuccess and the device's address of the array.
+hipError_t part_static_address(int device, char **out) {
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_part_static_mu);
+    if (!g_part_static[device]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_part_static[device] = (char *)p;
+    }
+    *out = g_part_static[device];
+    return hipSuccess;
+}
+}  // namespace
+
+extern "C" int32_t gbt_partition_static(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                        uint32_t *row_idx, int64_t begin, int64_t end, int32_t feature,
+                                        int32_t bin, int32_t default_left, int32_t missing_sym,
+                                        int64_t *n_left_out) {
+    if (!ctx) return GBT_EINVAL;
+    int32_t st = check_partition_args(ctx, packed, bits, n, F, row_idx, begin, end, feature, bin, missing_sym, n_left_out);
+    if (st != GBT_OK) return st;
+    GBT_REQUIRE(ctx, end - begin <= (int64_t)GBT_PARTITION_STATIC_MAX_ROWS, GBT_EUNSUPPORTED,
+                "segment of %lld rows exceeds the static scratch of gbt_partition_static (%lld rows): use gbt_partition",
+                (long long)(end - begin), (long long)GBT_PARTITION_STATIC_MAX_ROWS);
+    GBT_REQUIRE(ctx, ctx->part_static != nullptr, GBT_EHIP, "the static scratch array has no address on device %d",
+                ctx->device);
+    if (end == begin) {
+        *n_left_out = 0;
+        return GBT_OK;
+    }
+    return partition_impl(ctx, packed, bits, n, F, row_idx, begin, end, feature, bin, default_left, missing_sym,
+                          ctx->part_static, n_left_out);
 }
 
 // ------------------------------------------------------------ histogram job --

@@ -36,6 +36,7 @@ struct gbt_ctx {
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
     int sparse_jobs_per_cu; // row pieces per compute unit and launch of the sparse-row histogram kernel
     int sparse_tiled;       // 1: keep the sparse-row LDS histogram under hist_lds_kb even where all ids would fit
+    char *part_static;      // this device's copy of the static partition scratch (gbt_partition_static), or NULL
     size_t up_off;          // next free byte of the upload ring (first half of `pinned`)
     char err[512];
     bool profiling;
@@ -65,7 +66,7 @@ int32_t gbt_fail(gbt_ctx *ctx, int32_t code, const char *fmt, ...);
         if (!(cond)) return gbt_fail((ctx), (code), __VA_ARGS__); \
     } while (0)
 
-static inline size_t gbt_align(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+static constexpr inline size_t gbt_align(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // ---- job descriptors (host-built, read by kernels) --------------------------
 // One workgroup of the histogram kernel: rows [row_begin, row_begin+n_rows) of
