@@ -208,6 +208,10 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->part_fused = 1;
         c->part_hist = 1;
         c->hist_fix = 1;
+        c->hist8 = 1;
+        c->hist8_stagger = 64;
+        if (const char *e17 = getenv("GBT_TUNE_HIST8")) c->hist8 = atoi(e17) != 0;
+        if (const char *e18 = getenv("GBT_TUNE_HIST8_STAGGER")) { int v = atoi(e18); if (v >= 0 && v <= 128) c->hist8_stagger = v; }
         c->sparse_jobs_per_cu = 1;
         if (const char *e12 = getenv("GBT_TUNE_SPARSE_JOBS")) { int v = atoi(e12); if (v >= 1 && v <= 64) c->sparse_jobs_per_cu = v; }
         if (const char *e13 = getenv("GBT_TUNE_SPARSE_TILED")) c->sparse_tiled = atoi(e13) != 0;
@@ -358,12 +362,14 @@ extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *m
 
 // ------------------------------------------------------- fixed-point gpair --
 // The scales alone (one pass for the largest |g| and h; synchronises).
-static int32_t gpair_scale_impl(gbt_ctx *ctx, const float *gpair, int64_t n, double *scale, void *ws) {
+// uniform_h (may be NULL): receives 1 and the common value when every row has the same |h| (n >= 1), else 0.
+static int32_t gpair_scale_impl(gbt_ctx *ctx, const float *gpair, int64_t n, double *scale, void *ws,
+                                int *uniform_h = nullptr, float *h_value = nullptr) {
     GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 12, hipMemcpyDeviceToHost, ctx->stream));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 16, hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
-    uint32_t bits2[3];
-    memcpy(bits2, rb(ctx), 12);
+    uint32_t bits2[4];
+    memcpy(bits2, rb(ctx), 16);
     GBT_REQUIRE(ctx, bits2[0] < 0x7f800000u && bits2[1] < 0x7f800000u, GBT_EINVAL,
                 "gradient pairs contain a non-finite value");
     GBT_REQUIRE(ctx, bits2[2] == 0, GBT_EINVAL, "gradient pairs contain a negative hessian");
@@ -372,6 +378,10 @@ static int32_t gpair_scale_impl(gbt_ctx *ctx, const float *gpair, int64_t n, dou
     memcpy(&mh, &bits2[1], 4);
     scale[0] = fixed_scale(mg, kGBits);
     scale[1] = fixed_scale(mh, kHBits);
+    if (uniform_h) {
+        *uniform_h = n >= 1 && ~bits2[3] == bits2[1];   // smallest |h| == largest |h| (and none is negative)
+        if (h_value) *h_value = mh;
+    }
     return GBT_OK;
 }
 
@@ -411,11 +421,13 @@ extern "C" int32_t gbt_sum_gpair(gbt_ctx *ctx, const int32_t *gq, const uint32_t
 // --------------------------------------------------------------- histogram --
 // Enqueues the histogram of one row range split uniformly into jobs that the
 // kernel derives from its block index (no job table).
-struct RootFix {   // the root histogram converts the fp32 pairs itself (gbt_launch_hist_fix)
+struct RootFix {   // the root histogram converts the fp32 pairs itself (gbt_launch_hist_fix, gbt_launch_hist8)
     const float *gpair;
     double sg, sh;
-    int32_t *gq_out;
+    int32_t *gq_out;      // where the rounded pairs go (gbt_launch_hist8: may be NULL)
     int64_t *sums_dev;
+    int uniform_h;        // every row has the same hessian ...
+    int32_t hq_uniform;   // ... this one, rounded
 };
 static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
@@ -631,6 +643,26 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
                 "max_bins = %d: one feature's bins (%d bytes) exceed the LDS budget", B, B * 16);
     GBT_HIP(ctx, gbt_launch_fill_u64(ctx->stream, (uint64_t *)hist_out, 0, (int64_t)F * B * 2));
     if (n_rows == 0) return GBT_OK;
+    if (ctx->hist8 && !row_idx && n_rows == n && gbt_hist8_ok(bits, F, pl.n_ftiles, n, gbt_packed_words(n, F, bits))) {
+        Hist8Pairs p{};
+        if (fix) {
+            p.gpair = fix->gpair;
+            p.gq_out = fix->gq_out;
+            p.sg = fix->sg;
+            p.sh = fix->sh;
+            p.mode = gbt_fix32_ok(fix->sg, fix->sh) ? 2 : 1;
+            p.uniform_h = fix->uniform_h;
+            p.hq_uniform = fix->hq_uniform;
+            p.sums = fix->sums_dev;
+            GBT_HIP(ctx, gbt_launch_fill_u64(ctx->stream, (uint64_t *)fix->sums_dev, 0, 2));
+        } else {
+            p.gq = gq;
+        }
+        gbt_prof_begin(ctx, GBT_PROF_HIST_ROOT, (double)n_rows * ((double)F * bits / 8.0 + 8.0));
+        GBT_HIP(ctx, gbt_launch_hist8(ctx, packed, n, F, B, (uint32_t)missing_sym, p, hist_out));
+        gbt_prof_end(ctx);
+        return GBT_OK;
+    }
     std::vector<HistJob> jobs;
     add_hist_jobs(jobs, 0, 0, (uint32_t)n_rows, F, pl, pick_rows_per_job(ctx, n_rows));
     // Without a caller workspace the job table is read straight from the pinned
@@ -876,8 +908,10 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     int64_t *sums_dev = (int64_t *)(ws + L.scratch + 256);
     const bool root_may_split = max_depth > 0 && (!lossguide || max_leaves > 1);
     const bool fix_in_hist = ctx->hist_fix && root_may_split && gbt_hist_fix_ok(bits, row_bits, pl.ft, pl.n_ftiles);
+    int uniform_h = 0;
+    float h_value = 0.0f;
     gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (fix_in_hist ? 8.0 : 24.0));
-    st = gpair_scale_impl(ctx, gpair, n, scale, ws + L.scratch);
+    st = gpair_scale_impl(ctx, gpair, n, scale, ws + L.scratch, &uniform_h, &h_value);
     if (st == GBT_OK && !fix_in_hist) {
         hipError_t e = gbt_launch_to_fixed(s, gpair, n, scale[0], scale[1], gq, sums_dev);
         if (e != hipSuccess) st = gbt_fail(ctx, GBT_EHIP, "gbt_launch_to_fixed: %s", hipGetErrorString(e));
@@ -889,8 +923,14 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
     if (path == 3 && root_may_split)   // the root's id list, read by the first partition
         GBT_HIP(ctx, gbt_launch_iota_u32(s, W[1].id_rw, n));
+    // Where the partition + histogram pass follows (path 2) and rounding in fp32 is exact, the fixed-point pairs
+    // are never stored: the root histogram and the first pass each round the fp32 pairs themselves, and from
+    // then on a row's pair travels inside its record.
+    const bool pairs_stay_fp32 = fix_in_hist && path == 2 && ctx->hist8 && gbt_fix32_ok(scale[0], scale[1]) &&
+                                 gbt_hist8_ok(bits, F, pl.n_ftiles, n, gbt_packed_words(n, F, bits));
     if (root_may_split) {
-        const RootFix fix{gpair, scale[0], scale[1], gq, sums_dev};
+        const RootFix fix{gpair, scale[0], scale[1], pairs_stay_fp32 ? nullptr : gq, sums_dev, uniform_h,
+                          (int32_t)llrint((double)h_value * scale[1])};
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
                           (HistJob *)(ws + L.jobs), fix_in_hist ? &fix : nullptr);
         if (st != GBT_OK) return st;
@@ -1305,7 +1345,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                                       wcur == 2 ? nullptr : W[wcur].sym, nomove ? nullptr : W[wnext].sym_rw, F, B,
                                                       (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
                                                       (int)pjobs.size(), (int)tile_cursor, part_tile,
-                                                      (unsigned long long *)(ws + L.state), pool, true));
+                                                      (unsigned long long *)(ws + L.state), pool, true,
+                                                      pairs_stay_fp32 ? gpair : nullptr, scale[0], scale[1]));
                 gbt_prof_end(ctx);
                 // the evaluation launch also hands the cursors (the left counts) to the host and clears them
                 // for the next pass: no copy and no fill launch of their own

@@ -34,6 +34,8 @@ struct gbt_ctx {
     int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
+    int hist8;              // 1: the root histogram of 8-bit symbols with at most 16 features takes kernels_hist8.hip
+    int hist8_stagger;      // its workgroups on one compute unit get unequal shares of rows: spread in 1/256ths
     int sparse_jobs_per_cu; // row pieces per compute unit and launch of the sparse-row histogram kernel
     int sparse_tiled;       // 1: keep the sparse-row LDS histogram under hist_lds_kb even where all ids would fit
     char *part_static;      // this device's copy of the static partition scratch (gbt_partition_static), or NULL
@@ -143,6 +145,7 @@ struct LeafSeg {
 // ---- kernel launchers (each returns the hipGetLastError of its launches) ---
 hipError_t gbt_launch_fill_u64(hipStream_t s, uint64_t *p, uint64_t v, int64_t count);
 hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count);
+// out2 [dev] uint32[4]: bits of the largest |g|, of the largest |h|, 1 if some h < 0, ~(bits of the smallest |h|)
 hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2);
 // sums_out (may be NULL): int64[2] [dev] receiving the exact totals of gq (zeroed by the launcher).
 hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, double sg, double sh,
@@ -225,6 +228,25 @@ bool gbt_hist_fix_ok(int bits, int64_t stride_bits, int max_ft, int n_ftiles);
 hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t stride_bits, int64_t n_words, int64_t n,
                                int B, uint32_t missing, const float *gpair, double sg, double sh, int32_t *gq_out,
                                int64_t *sums_out, int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft);
+// The histogram of ALL n rows of a packed matrix with 8-bit symbols and F <= 16 features (kernels_hist8.hip).
+// The pairs come as fixed-point gq (gpair == NULL), or as fp32 gpair, which the kernel rounds itself:
+// mode 1 through fp64, mode 2 in fp32 (only where gbt_fix32_ok(sg, sh)); gq_out (may be NULL) receives the
+// rounded pairs; sums (may be NULL) int64[2] is ADDED the totals of all rows (the caller clears it).  uniform_h: every
+// row's rounded h equals hq_uniform (the caller has checked that all fp32 h are equal).  hist_out must be zero.
+struct Hist8Pairs {
+    const float *gpair;
+    const int32_t *gq;
+    int32_t *gq_out;
+    double sg, sh;
+    int mode;
+    int uniform_h;
+    int32_t hq_uniform;
+    int64_t *sums;
+};
+bool gbt_hist8_ok(int bits, int F, int n_ftiles, int64_t n, int64_t n_words);
+bool gbt_fix32_ok(double sg, double sh);
+hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int F, int B, uint32_t missing,
+                            const Hist8Pairs &p, int64_t *hist_out);
 // Partition and the histogram of one child of every job in one pass (8-bit symbols, at most 16
 // features, the bins of all features in one LDS tile: gbt_part_hist_ok).  No ids, order inside a
 // child not kept.  Rows travel as records of gbt_part_hist_record_words(F) words (symbols, padding,
@@ -256,7 +278,10 @@ int gbt_part_hist_record_words(int F);
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
                                 const uint32_t *src_records, uint32_t *dst_records, int F, int B, uint32_t missing,
                                 const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
-                                unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false);
+                                unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false,
+                                // first level only: the pairs are these fp32 pairs (not gq), rounded in the pass with
+                                // the scales sg, sh, for which gbt_fix32_ok must hold
+                                const float *gpair_fp32 = nullptr, double sg = 1.0, double sh = 1.0);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,

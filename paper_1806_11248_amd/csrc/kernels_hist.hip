@@ -530,10 +530,12 @@ __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned l
     }
 }
 
-template <int NS, bool CHK>
+// F32: the pairs are still fp32 (src_gq then points at float2): each is rounded to fixed point here, in fp32
+// arithmetic, which is exact for the power-of-two scales sgf, shf the launcher accepts (gbt_fix32_ok)
+template <int NS, bool CHK, bool F32>
 __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
     const uint32_t *__restrict__ src, int64_t src_stride_bytes, int64_t src_words, const int2 *__restrict__ src_gq,
-    uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs,
+    float sgf, float shf, uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs,
     int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
     constexpr int SW = (NS + 3) / 4;        // words that hold symbols
     constexpr int RW = record_words(NS);    // words of a record
@@ -617,7 +619,14 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
 #pragma unroll
                     for (int k = 0; k < RW; ++k) row[j][k] = k < SW ? __builtin_amdgcn_alignbyte(x[k < SW ? k + 1 : 0], x[k < SW ? k : 0], sh) : 0u;
                     row[j][SW - 1] &= tail_mask;
-                    const int2 q = src_gq[p];
+                    int2 q;
+                    if (F32) {
+                        const float2 v = ((const float2 *)src_gq)[p];
+                        q.x = (int)rintf(v.x * sgf);
+                        q.y = (int)rintf(v.y * shf);
+                    } else {
+                        q = src_gq[p];
+                    }
                     const unsigned long long v56 = ((unsigned long long)(uint32_t)q.x & 0x0fffffffull) |
                                                    ((unsigned long long)(uint32_t)q.y << 28);
                     row[j][RW - 2] |= (uint32_t)(v56 << 8);          // bytes 1..3
@@ -1137,6 +1146,8 @@ struct PHArgs {
     const uint32_t *src;
     int64_t src_stride_bytes, src_words;
     const int2 *src_gq;
+    bool src_fp32;     // first level: src_gq holds fp32 pairs, to be rounded with sgf, shf
+    float sgf, shf;
     uint32_t *dst;
     int ft, B, Bp;
     uint32_t missing;
@@ -1146,19 +1157,23 @@ struct PHArgs {
     unsigned long long *cursor;
     int64_t *pool;
 };
-template <int NS, bool CHK>
-hipError_t launch_ph_first(const PHArgs &a) {
+template <int NS, bool CHK, bool F32>
+hipError_t launch_ph_first_as(const PHArgs &a) {
     static size_t configured = 0;
     if (a.lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)part_hist_first_kernel<NS, CHK>,
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_first_kernel<NS, CHK, F32>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
         configured = a.lds;
     }
-    part_hist_first_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
-                                                                         a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
-                                                                         a.rows_per_span, a.cursor, a.pool);
+    part_hist_first_kernel<NS, CHK, F32><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
+                                                                              a.sgf, a.shf, a.dst, a.ft, a.B, a.Bp, a.missing,
+                                                                              a.jobs, a.n_jobs, a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
+}
+template <int NS, bool CHK>
+hipError_t launch_ph_first(const PHArgs &a) {
+    return a.src_fp32 ? launch_ph_first_as<NS, CHK, true>(a) : launch_ph_first_as<NS, CHK, false>(a);
 }
 template <int NS, bool CHK>
 hipError_t launch_ph(const PHArgs &a) {
@@ -1250,7 +1265,8 @@ int gbt_part_hist_record_words(int F) { return record_words(slots_for(F)); }
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
                                 const uint32_t *src_records, uint32_t *dst_records, int F, int B, uint32_t missing,
                                 const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
-                                unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero) {
+                                unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero,
+                                const float *gpair_fp32, double sg, double sh) {
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
     if (!cursors_are_zero) {
         hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, n_jobs);
@@ -1258,9 +1274,10 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
     }
     const int Bp = padded_bins(B);
     const bool first = src_records == nullptr;
+    const bool fp32 = first && gpair_fp32 != nullptr;
     const PHArgs a{ctx->stream, n_spans, ((size_t)F * Bp + 256) * 12, first ? packed : src_records, first ? (int64_t)F : 0,
-                   packed_words, (const int2 *)gq, dst_records, F, B, Bp, missing, jobs, n_jobs, rows_per_span, cursor,
-                   hist_pool};
+                   packed_words, fp32 ? (const int2 *)gpair_fp32 : (const int2 *)gq, fp32, (float)sg, (float)sh, dst_records,
+                   F, B, Bp, missing, jobs, n_jobs, rows_per_span, cursor, hist_pool};
     const bool chk = missing < 256u || B < 256;
     if (first) return chk ? pick_ph<true, true>(F, a) : pick_ph<false, true>(F, a);
     return chk ? pick_ph<true, false>(F, a) : pick_ph<false, false>(F, a);

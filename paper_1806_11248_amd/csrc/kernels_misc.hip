@@ -35,12 +35,14 @@ __global__ void iota_u32_kernel(uint32_t *p, int64_t count) {
 constexpr int kStreamBatch = 4;
 // The pointers must be 16-byte aligned; `head` pairs (0 or 1) in front of them are taken singly,
 // which is how a caller's pointer that is only 8-byte aligned is served.
+// out2[3] receives ~(smallest |h| as bits), so that a zero-filled word is the neutral start of an atomicMax
 __global__ __launch_bounds__(kBlock) void absmax_kernel(const float2 *gp, int64_t n, int head, uint32_t *out2) {
-    uint32_t mg = 0, mh = 0, neg = 0;
+    uint32_t mg = 0, mh = 0, neg = 0, lh = 0xffffffffu;
     if (head && blockIdx.x == 0 && threadIdx.x == 1) {
         const float2 v = gp[-1];
         mg = __float_as_uint(v.x) & 0x7fffffffu;
         mh = __float_as_uint(v.y) & 0x7fffffffu;
+        lh = mh;
         neg = v.y < 0.0f ? 1u : 0u;
     }
     const float4 *gp4 = (const float4 *)gp;
@@ -50,6 +52,7 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const float2 *gp, int64_
         const uint32_t a1 = __float_as_uint(v.z) & 0x7fffffffu, b1 = __float_as_uint(v.w) & 0x7fffffffu;
         mg = max(mg, max(a0, a1));
         mh = max(mh, max(b0, b1));
+        lh = min(lh, min(b0, b1));
         neg |= (v.y < 0.0f || v.w < 0.0f) ? 1u : 0u;
     };
     // a workgroup takes contiguous chunks of kStreamBatch * kBlock pieces; whole chunks need no conditional load
@@ -67,20 +70,23 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const float2 *gp, int64_
         const float2 v = gp[n - 1];
         mg = max(mg, __float_as_uint(v.x) & 0x7fffffffu);
         mh = max(mh, __float_as_uint(v.y) & 0x7fffffffu);
+        lh = min(lh, __float_as_uint(v.y) & 0x7fffffffu);
         neg |= v.y < 0.0f ? 1u : 0u;
     }
     for (int o = 32; o > 0; o >>= 1) {
-        uint32_t a = __shfl_xor(mg, o), b = __shfl_xor(mh, o);
+        uint32_t a = __shfl_xor(mg, o), b = __shfl_xor(mh, o), c = __shfl_xor(lh, o);
         mg = a > mg ? a : mg;
         mh = b > mh ? b : mh;
+        lh = c < lh ? c : lh;
         neg |= __shfl_xor(neg, o);
     }
     // one set of atomics per workgroup: atomics on one address run one after the other
-    __shared__ uint32_t red[3][kBlock / 64];
+    __shared__ uint32_t red[4][kBlock / 64];
     if ((threadIdx.x & 63) == 0) {
         red[0][threadIdx.x >> 6] = mg;
         red[1][threadIdx.x >> 6] = mh;
         red[2][threadIdx.x >> 6] = neg;
+        red[3][threadIdx.x >> 6] = lh;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -88,10 +94,12 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const float2 *gp, int64_
             mg = max(mg, red[0][w]);
             mh = max(mh, red[1][w]);
             neg |= red[2][w];
+            lh = min(lh, red[3][w]);
         }
         atomicMax(&out2[0], mg);
         atomicMax(&out2[1], mh);
         if (neg) atomicOr(&out2[2], 1u);
+        atomicMax(&out2[3], ~lh);
     }
 }
 

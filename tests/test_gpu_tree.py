@@ -185,6 +185,32 @@ def test_byte_symbols_up_to_16_features(ctx, oracle, F, B, miss):
     grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F)
 
 
+@pytest.mark.parametrize("F,n,kind", [(1, 5_000, "general"), (4, 70_001, "uniform"), (5, 70_001, "general"), (8, 3_001, "tiny"),
+                                      (9, 70_001, "general"), (12, 70_001, "tiny-uniform"), (13, 2_300_003, "general"),
+                                      (13, 70_001, "huge"), (14, 70_001, "general"), (16, 2_300_003, "uniform"),
+                                      (16, 40_000, "general"), (13, 200, "general"), (7, 300, "uniform")])
+def test_root_histogram_forms(ctx, oracle, F, n, kind):
+    """The root's histogram kernel for byte symbols: every slot class (1..16 features), pairs with one common
+    hessian (count word, no tests) and without (packed word with carry / wrap bookkeeping), fp32 pairs rounded
+    in fp32 and, where the scales leave the range in which that is exact, through fp64; inputs short enough
+    for one workgroup and long enough for unequal slices per compute unit.  Judged through the tree: the
+    root's totals, its split and the gains reported come from that histogram."""
+    d = synth.make(4, max(n, 400))
+    rng = np.random.default_rng(31 * F + n % 1000)
+    X = d["X"][:n, rng.integers(0, d["X"].shape[1], F)].copy()
+    X += rng.normal(0, 0.01, X.shape).astype(np.float32)
+    p = dict(d["params"], max_bins=256, max_depth=2, min_child_weight=0.0 if "tiny" in kind else 1.0)
+    o, gdev = gpu_prep(ctx, oracle, dict(X=X, params=p))
+    g_ = rng.standard_normal(n) + (X[:, 0] > np.median(X[:, 0])) * 0.7
+    h_ = np.ones(n) if "uniform" in kind else rng.uniform(0.05, 1.0, n)
+    mag = {"tiny": 2.0 ** -100, "tiny-uniform": 2.0 ** -100, "huge": 2.0 ** 90}.get(kind, 1.0)
+    gp = np.stack([g_ * mag, h_ * mag], 1).astype(np.float32)
+    _say(f"root histogram forms: F={F} n={n} {kind} bits={gdev['bits']}")
+    if p["min_child_weight"] == 0.0:
+        p["lam"] = float(mag)
+    grow_and_judge(ctx, oracle, o, gdev, gp, p, n, F, grid_only=True)
+
+
 @pytest.mark.parametrize("F", [13, 16, 5])
 def test_pass_with_carries_and_wraps_everywhere(ctx, ctx_env, oracle, F):
     """Extreme same-sign pairs piled into few bins: in the partition + histogram pass the packed LDS
