@@ -421,11 +421,23 @@ GBT_API int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t 
 #define GBT_PROF_HIST_INPLACE 7 /* its last level where two levels stay in place (two histograms per workgroup) */
 #define GBT_PROF_CLASSES 8
 
+#define GBT_PROF_LEVELS 18 /* depths 0..16 of the nodes a launch builds histograms for, one spare */
 typedef struct gbt_profile {
     double ms[GBT_PROF_CLASSES];        /* device time between HIP events around the launches */
-    double bytes[GBT_PROF_CLASSES];     /* algorithmic HBM bytes of those launches (histogram:
-                                           rows * (F*bits/8 + 8 [+ 4 with a row-id list])) */
+    double bytes[GBT_PROF_CLASSES];     /* HBM bytes this library's design moves in those launches (whole records
+                                           read and written where rows move) */
     int64_t launches[GBT_PROF_CLASSES]; /* timed launch groups */
+    /* Bytes the method itself needs, whatever the design does: a histogram rows_built * (F*bits/8 + 8) for the
+     * symbols and the gradient pair, + 4 per row where the node is a subset of the rows (its row id); a
+     * repartition 4 + 4 + bits/8 per row of the split nodes (row id read and written, one symbol); a launch
+     * that does both, the sum; a launch that only counts rows, bits/8 per row. */
+    double alg_bytes[GBT_PROF_CLASSES];
+    /* The histogram-building launches once more, by the depth of the nodes built (0 = the root): time, method
+     * bytes, rows * features accumulated, launch groups. */
+    double level_ms[GBT_PROF_LEVELS];
+    double level_alg_bytes[GBT_PROF_LEVELS];
+    double level_row_features[GBT_PROF_LEVELS];
+    int64_t level_launches[GBT_PROF_LEVELS];
 } gbt_profile;
 
 /* Turns per-class device timing on or off (off by default).  While on, every
@@ -434,6 +446,14 @@ typedef struct gbt_profile {
  * was recorded since the last reset into *out [host] and resets. */
 GBT_API int32_t gbt_profile_enable(gbt_ctx *ctx, int32_t on);
 GBT_API int32_t gbt_profile_read(gbt_ctx *ctx, gbt_profile *out);
+
+/* The streaming-read ceiling of this GPU, measured here and now: a kernel that only reads `bytes` bytes of buf
+ * [dev, 16-byte aligned] (whole 16-byte pieces, every byte once, nothing written) is launched `reps` >= 1
+ * times on the context's stream between HIP events; *gbps_out [host] receives the best bytes / time in
+ * GB/s.  The figure to hold beside a histogram kernel's achieved bandwidth: what HBM gives a kernel that does
+ * nothing else.  workspace [dev] >= 4096 bytes.  Synchronises the stream. */
+GBT_API int32_t gbt_measure_stream_read(gbt_ctx *ctx, const void *buf, size_t bytes, int32_t reps,
+                                        double *gbps_out, void *workspace, size_t workspace_bytes);
 
 #ifdef __cplusplus
 }

@@ -29,11 +29,12 @@ SYMBOLS = [
     "gbt_partition_static",
     "gbt_grow_tree_workspace_bytes", "gbt_grow_tree_path", "gbt_grow_tree",
     "gbt_grow_tree_lossguide_workspace_bytes", "gbt_grow_tree_lossguide", "gbt_predict_workspace_bytes", "gbt_predict",
-    "gbt_profile_enable", "gbt_profile_read",
+    "gbt_profile_enable", "gbt_profile_read", "gbt_measure_stream_read",
     "gbt_sparse_capacity", "gbt_compress_sparse_workspace_bytes", "gbt_compress_sparse_count", "gbt_compress_sparse",
     "gbt_build_hist_sparse", "gbt_grow_tree_sparse_workspace_bytes", "gbt_grow_tree_sparse", "gbt_predict_sparse",
 ]
 
+PROF_LEVELS = 18   # GBT_PROF_LEVELS
 PROF_CLASSES = ["hist_root", "hist_node", "partition", "eval", "clear", "other", "hist_first", "hist_inplace"]
 
 
@@ -56,7 +57,10 @@ class Split(C.Structure):
 
 
 class Profile(C.Structure):
-    _fields_ = [("ms", C.c_double * 8), ("bytes", C.c_double * 8), ("launches", C.c_int64 * 8)]
+    _fields_ = [("ms", C.c_double * 8), ("bytes", C.c_double * 8), ("launches", C.c_int64 * 8),
+                ("alg_bytes", C.c_double * 8), ("level_ms", C.c_double * PROF_LEVELS),
+                ("level_alg_bytes", C.c_double * PROF_LEVELS), ("level_row_features", C.c_double * PROF_LEVELS),
+                ("level_launches", C.c_int64 * PROF_LEVELS)]
 
 
 class Tree(C.Structure):
@@ -130,6 +134,7 @@ def load():
     L.gbt_predict_sparse.argtypes = [vp, vp, i32, vp, vp, i64, i32, i32, f64, vp, vp, sz]
     L.gbt_profile_enable.argtypes = [vp, i32]
     L.gbt_profile_read.argtypes = [vp, vp]
+    L.gbt_measure_stream_read.argtypes = [vp, vp, sz, i32, vp, vp, sz]
     _lib = L
     return L
 
@@ -236,7 +241,20 @@ class Context:
     def profile_read(self) -> dict:
         p = Profile()
         self._check(self.lib.gbt_profile_read(self.h, C.byref(p)))
-        return {nm: dict(ms=p.ms[i], bytes=p.bytes[i], launches=p.launches[i]) for i, nm in enumerate(PROF_CLASSES)}
+        out = {nm: dict(ms=p.ms[i], bytes=p.bytes[i], alg_bytes=p.alg_bytes[i], launches=p.launches[i])
+               for i, nm in enumerate(PROF_CLASSES)}
+        self.last_profile_levels = [dict(level=k, ms=p.level_ms[k], alg_bytes=p.level_alg_bytes[k],
+                                         row_features=p.level_row_features[k], launches=p.level_launches[k])
+                                    for k in range(PROF_LEVELS) if p.level_launches[k]]
+        return out
+
+    def measure_stream_read(self, buf, reps: int = 5) -> float:
+        """GB/s of a kernel that only reads `buf` (a device tensor), best of `reps` launches."""
+        ws = self.workspace("small", 4096)
+        out = C.c_double()
+        self._check(self.lib.gbt_measure_stream_read(self.h, _ptr(buf), buf.numel() * buf.element_size(), reps,
+                                                     C.byref(out), _ptr(ws), ws.numel()))
+        return out.value
 
     # -- Sec. 2.1 ------------------------------------------------------------
     def quantise(self, X=None, csr=None, *, max_bins: int, n=None, F=None):

@@ -280,16 +280,26 @@ static hipEvent_t prof_event(gbt_ctx *ctx) {
     return e;
 }
 
-void gbt_prof_begin(gbt_ctx *ctx, int cls, double bytes) {
-    if (!ctx->profiling) return;
+int gbt_prof_begin(gbt_ctx *ctx, int cls, double bytes, double alg_bytes, int level, double row_features) {
+    if (!ctx->profiling) return -1;
     ProfSpan sp;
     sp.cls = cls;
     sp.bytes = bytes;
+    sp.alg_bytes = alg_bytes;
+    sp.level = level;
+    sp.row_features = row_features;
     sp.start = prof_event(ctx);
     sp.stop = prof_event(ctx);
-    if (!sp.start || !sp.stop) return;
+    if (!sp.start || !sp.stop) return -1;
     (void)hipEventRecord(sp.start, ctx->stream);
     ctx->spans->push_back(sp);
+    return (int)ctx->spans->size() - 1;
+}
+
+void gbt_prof_patch(gbt_ctx *ctx, int span, double alg_bytes, double row_features) {
+    if (!ctx->profiling || span < 0 || span >= (int)ctx->spans->size()) return;
+    (*ctx->spans)[(size_t)span].alg_bytes = alg_bytes;
+    (*ctx->spans)[(size_t)span].row_features = row_features;
 }
 
 void gbt_prof_end(gbt_ctx *ctx) {
@@ -313,13 +323,48 @@ extern "C" int32_t gbt_profile_read(gbt_ctx *ctx, gbt_profile *out) {
         if (hipEventElapsedTime(&ms, sp.start, sp.stop) == hipSuccess && sp.cls >= 0 && sp.cls < GBT_PROF_CLASSES) {
             out->ms[sp.cls] += ms;
             out->bytes[sp.cls] += sp.bytes;
+            out->alg_bytes[sp.cls] += sp.alg_bytes < 0.0 ? sp.bytes : sp.alg_bytes;
             out->launches[sp.cls] += 1;
+            if (sp.level >= 0 && sp.level < GBT_PROF_LEVELS) {
+                out->level_ms[sp.level] += ms;
+                out->level_alg_bytes[sp.level] += sp.alg_bytes < 0.0 ? sp.bytes : sp.alg_bytes;
+                out->level_row_features[sp.level] += sp.row_features;
+                out->level_launches[sp.level] += 1;
+            }
         }
         ctx->free_events->push_back(sp.start);
         ctx->free_events->push_back(sp.stop);
     }
     (void)hipGetLastError();
     ctx->spans->clear();
+    return GBT_OK;
+}
+
+extern "C" int32_t gbt_measure_stream_read(gbt_ctx *ctx, const void *buf, size_t bytes, int32_t reps, double *gbps_out,
+                                           void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, buf && gbps_out && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, ((uintptr_t)buf & 15u) == 0, GBT_EINVAL, "buf must be 16-byte aligned");
+    GBT_REQUIRE(ctx, bytes >= 16 && reps >= 1, GBT_EINVAL, "nothing to read");
+    GBT_REQUIRE(ctx, workspace_bytes >= 4096, GBT_ENOMEM, "workspace < 4096 bytes");
+    hipEvent_t e0 = prof_event(ctx), e1 = prof_event(ctx);
+    GBT_REQUIRE(ctx, e0 && e1, GBT_EHIP, "hipEventCreate failed");
+    double best_ms = 0.0;
+    int32_t st = GBT_OK;
+    for (int32_t r = 0; r <= reps && st == GBT_OK; ++r) {   // the first launch warms up and is not counted
+        hipError_t e = hipEventRecord(e0, ctx->stream);
+        if (e == hipSuccess) e = gbt_launch_stream_read(ctx->stream, buf, (int64_t)bytes, (uint32_t *)workspace);
+        if (e == hipSuccess) e = hipEventRecord(e1, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) st = gbt_fail(ctx, GBT_EHIP, "gbt_measure_stream_read: %s", hipGetErrorString(e));
+        else if (r > 0 && (best_ms == 0.0 || ms < best_ms)) best_ms = ms;
+    }
+    ctx->free_events->push_back(e0);
+    ctx->free_events->push_back(e1);
+    if (st != GBT_OK) return st;
+    *gbps_out = best_ms > 0.0 ? (double)(bytes / 16 * 16) / (best_ms * 1e-3) / 1e9 : 0.0;
     return GBT_OK;
 }
 
@@ -428,11 +473,15 @@ struct RootFix {   // the root histogram converts the fp32 pairs itself (gbt_lau
     int64_t *sums_dev;
     int uniform_h;        // every row has the same hessian ...
     int32_t hq_uniform;   // ... this one, rounded
+    // gbt_launch_hist8 leaves the totals as one pair per workgroup: where (room for gbt_hist8_max_jobs() pairs), and,
+    // on return, how many (0: the totals are in sums_dev as one pair)
+    int64_t *slot_sums;
+    int n_slots;
 };
 static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
                             const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs /* may be NULL */,
-                            const RootFix *fix = nullptr);
+                            RootFix *fix = nullptr);
 
 extern "C" int32_t gbt_build_hist(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                                   int32_t B, int32_t missing_sym, const uint32_t *row_idx,
@@ -637,7 +686,7 @@ extern "C" int32_t gbt_partition_static(gbt_ctx *ctx, const uint32_t *packed, in
 // ------------------------------------------------------------ histogram job --
 static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
-                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs, const RootFix *fix) {
+                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs, RootFix *fix) {
     HistPlan pl;
     GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins (%d bytes) exceed the LDS budget", B, B * 16);
@@ -653,14 +702,15 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
             p.mode = gbt_fix32_ok(fix->sg, fix->sh) ? 2 : 1;
             p.uniform_h = fix->uniform_h;
             p.hq_uniform = fix->hq_uniform;
-            p.sums = fix->sums_dev;
-            GBT_HIP(ctx, gbt_launch_fill_u64(ctx->stream, (uint64_t *)fix->sums_dev, 0, 2));
+            p.sums = fix->slot_sums;
         } else {
             p.gq = gq;
         }
-        gbt_prof_begin(ctx, GBT_PROF_HIST_ROOT, (double)n_rows * ((double)F * bits / 8.0 + 8.0));
-        GBT_HIP(ctx, gbt_launch_hist8(ctx, packed, n, F, B, (uint32_t)missing_sym, p, hist_out));
+        int n_jobs8 = 0;
+        gbt_prof_begin(ctx, GBT_PROF_HIST_ROOT, (double)n_rows * ((double)F * bits / 8.0 + 8.0), -1.0, 0, (double)n_rows * F);
+        GBT_HIP(ctx, gbt_launch_hist8(ctx, packed, n, F, B, (uint32_t)missing_sym, p, hist_out, &n_jobs8));
         gbt_prof_end(ctx);
+        if (fix) fix->n_slots = n_jobs8;
         return GBT_OK;
     }
     std::vector<HistJob> jobs;
@@ -678,7 +728,8 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
         dev_jobs = (HistJob *)slot;
     }
     gbt_prof_begin(ctx, row_idx ? GBT_PROF_HIST_NODE : GBT_PROF_HIST_ROOT,
-                   (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0)));
+                   (double)n_rows * ((double)F * bits / 8.0 + 8.0 + (row_idx ? 4.0 : 0.0)), -1.0, row_idx ? -1 : 0,
+                   (double)n_rows * F);
     if (fix)
         GBT_HIP(ctx, gbt_launch_hist_fix(ctx, packed, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
                                          (uint32_t)missing_sym, fix->gpair, fix->sg, fix->sh, fix->gq_out,
@@ -928,17 +979,30 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     // then on a row's pair travels inside its record.
     const bool pairs_stay_fp32 = fix_in_hist && path == 2 && ctx->hist8 && gbt_fix32_ok(scale[0], scale[1]) &&
                                  gbt_hist8_ok(bits, F, pl.n_ftiles, n, gbt_packed_words(n, F, bits));
+    int sum_slots = 0;   // > 0: the root's totals come as this many partial pairs (gbt_launch_hist8), in the job area
+    static_assert(kUploadBytes >= ((size_t)1 << 14) * 16, "room for the partial totals of gbt_launch_hist8");
     if (root_may_split) {
-        const RootFix fix{gpair, scale[0], scale[1], pairs_stay_fp32 ? nullptr : gq, sums_dev, uniform_h,
-                          (int32_t)llrint((double)h_value * scale[1])};
+        RootFix fix{gpair, scale[0], scale[1], pairs_stay_fp32 ? nullptr : gq, sums_dev, uniform_h,
+                    (int32_t)llrint((double)h_value * scale[1]), (int64_t *)(ws + L.jobs), 0};
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
                           (HistJob *)(ws + L.jobs), fix_in_hist ? &fix : nullptr);
         if (st != GBT_OK) return st;
+        sum_slots = fix_in_hist ? fix.n_slots : 0;
     }
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), sums_dev, 16, hipMemcpyDeviceToHost, s));
+    GBT_REQUIRE(ctx, sum_slots <= gbt_hist8_max_jobs() && (size_t)sum_slots * 16 <= kCutsRb, GBT_EHIP, "internal: partial totals");
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), sum_slots ? (const void *)(ws + L.jobs) : (const void *)sums_dev,
+                                sum_slots ? (size_t)sum_slots * 16 : 16, hipMemcpyDeviceToHost, s));
     GBT_SYNC(ctx);
-    int64_t root_sums[2];
-    memcpy(root_sums, rb(ctx), 16);
+    int64_t root_sums[2] = {0, 0};
+    if (sum_slots) {
+        const int64_t *ps = (const int64_t *)rb(ctx);
+        for (int j = 0; j < sum_slots; ++j) {
+            root_sums[0] += ps[2 * j];
+            root_sums[1] += ps[2 * j + 1];
+        }
+    } else {
+        memcpy(root_sums, rb(ctx), 16);
+    }
     if (cuts_via_pinned) memcpy(hcuts.data(), rb(ctx) + kCutsRb, hcuts.size() * sizeof(float));
 
     auto set_node_at = [&](int32_t at, const HNode &nd) {
@@ -1183,6 +1247,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         }
         next.clear();
         nl_of.assign(sel_nodes.size(), 0u);
+        int pass_span_of_round = -1;      // the profiler's span of this round's partition (+ histogram) pass ...
+        double pass_alg_of_round = 0.0;   // ... and the method bytes of its partition part
         const int what = path == 3            ? GBT_PART_IDS
                          : children_need_hist ? GBT_PART_RECORDS
                          : (tracked && path == 0) ? GBT_PART_IDS
@@ -1231,7 +1297,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             const int64_t stride8 = from_matrix ? (int64_t)F : 4 * (int64_t)gbt_part_hist_record_words(F);
             double crow = 0;
             for (const CountJob &cj : cjobs) crow += cj.seg_len;
-            gbt_prof_begin(ctx, GBT_PROF_PARTITION, crow * (double)stride8);
+            gbt_prof_begin(ctx, GBT_PROF_PARTITION, crow * (double)stride8, crow * count_levels * (bits / 8.0));
             GBT_HIP(ctx, gbt_launch_count2(s, rows8, stride8, (uint32_t)missing_sym, (const CountJob *)(ws + L.jobs),
                                            (int)cjobs.size(), (int)ctiles, (uint32_t *)(ws + L.state), count_levels,
                                            !from_matrix));
@@ -1321,7 +1387,10 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 gbt_prof_end(ctx);
             }
             const double rec_bytes = row_bits / 8.0 + 8.0;
-            gbt_prof_begin(ctx, nomove2 ? GBT_PROF_HIST_INPLACE : with_hist ? (wcur == 2 ? GBT_PROF_HIST_FIRST : GBT_PROF_HIST_NODE)
+            // what the method needs: a repartition is 4 + 4 + bits/8 bytes per row (where rows are only counted, the
+            // symbol alone); the histogram part of a pass is added below, once the built children's rows are known
+            const double part_alg = part_rows * ((nomove || nomove2 || what == GBT_PART_COUNT) ? bits / 8.0 : 8.0 + bits / 8.0);
+            const int pass_span = gbt_prof_begin(ctx, nomove2 ? GBT_PROF_HIST_INPLACE : with_hist ? (wcur == 2 ? GBT_PROF_HIST_FIRST : GBT_PROF_HIST_NODE)
                                                                             : GBT_PROF_PARTITION,
                            nomove2 ? (double)h2_rows * rec_bytes :
                            part_rows * (path == 3 ? 8.0 + 32.0   // ids read and written, one sector of symbols per row
@@ -1329,7 +1398,10 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                     : fused   ? 2.0 * rec_bytes
                                         : what == GBT_PART_RECORDS ? row_bits / 8.0 + 2.0 * (rec_bytes + 4.0)
                                         : what == GBT_PART_IDS     ? row_bits / 8.0 + 8.0
-                                                                   : row_bits / 8.0));
+                                                                   : row_bits / 8.0),
+                           part_alg, with_hist ? child_depth : -1);
+            pass_span_of_round = pass_span;
+            pass_alg_of_round = part_alg;
             if (with_hist) {
                 GBT_REQUIRE(ctx, pjobs.size() * 8 <= kSplitRb, GBT_EUNSUPPORTED, "level too wide");
                 if (!cursors_zero) {   // every cursor a level can have; from then on the evaluation launch keeps them clear
@@ -1456,6 +1528,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 leaves.push_back(LeafSeg{rc.begin, (uint32_t)rc.id, (uint32_t)child_buf, rc.len});
             }
         }
+        if (with_hist)   // the pass also built these children's histograms: rows * (symbols + pair + row id)
+            gbt_prof_patch(ctx, pass_span_of_round, pass_alg_of_round + (double)built_rows * ((double)row_bits / 8.0 + 12.0),
+                           (double)built_rows * F);
         if (children_need_hist && !with_hist) {
             // ---- BuildPartialHistograms for the smaller children (their rows are now one
             //      contiguous run of the working copy)
@@ -1472,7 +1547,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 st = upload(ctx, hjobs.data() + j0, nj * sizeof(HistJob), ws + L.jobs);
                 if (st != GBT_OK) return st;
                 gbt_prof_begin(ctx, GBT_PROF_HIST_NODE,
-                               j0 == 0 ? (double)built_rows * ((double)row_bits / 8.0 + 8.0) : 0.0);
+                               j0 == 0 ? (double)built_rows * ((double)row_bits / 8.0 + 8.0 + (path == 3 ? 4.0 : 0.0)) : 0.0,
+                               j0 == 0 ? (double)built_rows * ((double)row_bits / 8.0 + 12.0) : 0.0, child_depth,
+                               j0 == 0 ? (double)built_rows * F : 0.0);
                 if (path == 3)   // the rows by id from the caller's matrix, the pairs by id
                     GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, row_bits, gbt_packed_words(n, F, bits), n, B,
                                                  (uint32_t)missing_sym, W[wnext].id, gq, pool,

@@ -12,7 +12,10 @@
 
 struct ProfSpan {
     int cls;
-    double bytes;
+    double bytes;       // HBM bytes this library's design moves in the launch
+    double alg_bytes;   // bytes the method itself needs (see gbt_profile); < 0: the same as `bytes`
+    int level;          // depth of the nodes whose histograms the launch builds, -1: not a histogram launch
+    double row_features;   // rows * features accumulated into those histograms
     hipEvent_t start, stop;
 };
 
@@ -47,8 +50,13 @@ struct gbt_ctx {
 };
 
 // Brackets a launch group with events when profiling is on (no-ops otherwise).
-void gbt_prof_begin(gbt_ctx *ctx, int cls, double bytes);
+// bytes: what the design moves; alg_bytes: what the method needs (< 0: the same); level, row_features: for
+// launches that build histograms (see ProfSpan).  Returns the span's index for gbt_prof_patch, -1 when off.
+int gbt_prof_begin(gbt_ctx *ctx, int cls, double bytes, double alg_bytes = -1.0, int level = -1,
+                   double row_features = 0.0);
 void gbt_prof_end(gbt_ctx *ctx);
+// Figures of a span that are only known after its launch has been waited for (rows of the built children).
+void gbt_prof_patch(gbt_ctx *ctx, int span, double alg_bytes, double row_features);
 
 #define GBT_STAGING_BYTES (8u << 20)
 
@@ -145,6 +153,7 @@ struct LeafSeg {
 // ---- kernel launchers (each returns the hipGetLastError of its launches) ---
 hipError_t gbt_launch_fill_u64(hipStream_t s, uint64_t *p, uint64_t v, int64_t count);
 hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count);
+hipError_t gbt_launch_stream_read(hipStream_t s, const void *buf, int64_t bytes, uint32_t *sink);
 // out2 [dev] uint32[4]: bits of the largest |g|, of the largest |h|, 1 if some h < 0, ~(bits of the smallest |h|)
 hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2);
 // sums_out (may be NULL): int64[2] [dev] receiving the exact totals of gq (zeroed by the launcher).
@@ -231,7 +240,8 @@ hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t str
 // The histogram of ALL n rows of a packed matrix with 8-bit symbols and F <= 16 features (kernels_hist8.hip).
 // The pairs come as fixed-point gq (gpair == NULL), or as fp32 gpair, which the kernel rounds itself:
 // mode 1 through fp64, mode 2 in fp32 (only where gbt_fix32_ok(sg, sh)); gq_out (may be NULL) receives the
-// rounded pairs; sums (may be NULL) int64[2] is ADDED the totals of all rows (the caller clears it).  uniform_h: every
+// rounded pairs; sums (may be NULL) int64[gbt_hist8_max_jobs()][2] receives one pair of partial totals per
+// workgroup ([0, *n_jobs_out) are written; their sum is the total of all rows).  uniform_h: every
 // row's rounded h equals hq_uniform (the caller has checked that all fp32 h are equal).  hist_out must be zero.
 struct Hist8Pairs {
     const float *gpair;
@@ -245,8 +255,9 @@ struct Hist8Pairs {
 };
 bool gbt_hist8_ok(int bits, int F, int n_ftiles, int64_t n, int64_t n_words);
 bool gbt_fix32_ok(double sg, double sh);
+int gbt_hist8_max_jobs();
 hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int F, int B, uint32_t missing,
-                            const Hist8Pairs &p, int64_t *hist_out);
+                            const Hist8Pairs &p, int64_t *hist_out, int *n_jobs_out = nullptr);
 // Partition and the histogram of one child of every job in one pass (8-bit symbols, at most 16
 // features, the bins of all features in one LDS tile: gbt_part_hist_ok).  No ids, order inside a
 // child not kept.  Rows travel as records of gbt_part_hist_record_words(F) words (symbols, padding,

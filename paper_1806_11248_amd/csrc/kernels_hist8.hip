@@ -242,7 +242,7 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
         if (g != 0) atomicAdd((unsigned long long *)(a.out + 2 * (int64_t)i), (unsigned long long)g);
         if (h != 0) atomicAdd((unsigned long long *)(a.out + 2 * (int64_t)i + 1), (unsigned long long)h);
     }
-    if (a.sums) {   // totals of all rows: one pair of global atomics per wave
+    if (a.sums) {   // totals of this workgroup's rows into its own slot: same-address global atomics take turns
         long long G = sum_g, H = sum_h;
         if (UNI) {
             const long long rows = sum_g & (long long)kUniformMaxRows;
@@ -253,9 +253,19 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
             G += __shfl_xor(G, o);
             H += __shfl_xor(H, o);
         }
+        __shared__ long long red[2][BLOCK / 64];
         if (lane == 0) {
-            if (G) atomicAdd((unsigned long long *)&a.sums[0], (unsigned long long)G);
-            if (H) atomicAdd((unsigned long long *)&a.sums[1], (unsigned long long)H);
+            red[0][threadIdx.x >> 6] = G;
+            red[1][threadIdx.x >> 6] = H;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < BLOCK / 64; ++w) {
+                G += red[0][w];
+                H += red[1][w];
+            }
+            a.sums[2 * blockIdx.x] = G;
+            a.sums[2 * blockIdx.x + 1] = H;
         }
     }
 }
@@ -294,8 +304,11 @@ bool gbt_fix32_ok(double sg, double sh) {
     return ok(sg) && ok(sh);
 }
 
+int gbt_hist8_max_jobs() { return 1 << 14; }
+
 hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int F, int B, uint32_t missing,
-                            const Hist8Pairs &p, int64_t *hist_out) {
+                            const Hist8Pairs &p, int64_t *hist_out, int *n_jobs_out) {
+    if (n_jobs_out) *n_jobs_out = 0;
     if (n <= 0) return hipSuccess;
     const bool uni = p.uniform_h != 0;
     Hist8Args a;
@@ -328,6 +341,8 @@ hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int
     a.slots = (uint32_t)slots;
     a.stagger = stagger;
     const int grid = (int)(cols * slots);
+    if (grid > gbt_hist8_max_jobs()) return hipErrorInvalidValue;
+    if (n_jobs_out) *n_jobs_out = grid;
     const int mode = p.gpair ? p.mode : 0;
     if (uni) {
         if (mode == 0) return pick8<true, 0>(ctx->stream, a, grid);

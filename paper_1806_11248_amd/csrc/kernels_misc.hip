@@ -601,6 +601,34 @@ hipError_t gbt_launch_iota_u32(hipStream_t s, uint32_t *p, int64_t count) {
     iota_u32_kernel<<<grid_for(count, kBlock * 4, 8192), kBlock, 0, s>>>(p, count);
     return hipGetLastError();
 }
+// A plain streaming read of `n16` 16-byte pieces: what HBM delivers to a kernel that only reads (the yardstick
+// beside the histogram kernels' achieved bandwidth).  sink is written only if the xor of everything read
+// equals a magic word, which keeps the loads alive.
+namespace {
+__global__ __launch_bounds__(kBlock) void stream_read_kernel(const uint4 *__restrict__ p, int64_t n16, uint32_t *sink) {
+    uint32_t acc = 0;
+    const int64_t chunk = (int64_t)kStreamBatch * kBlock, n_whole = n16 / chunk;
+    for (int64_t c = blockIdx.x; c < n_whole; c += gridDim.x) {
+        uint4 v[kStreamBatch];
+#pragma unroll
+        for (int k = 0; k < kStreamBatch; ++k) v[k] = p[c * chunk + k * kBlock + threadIdx.x];
+#pragma unroll
+        for (int k = 0; k < kStreamBatch; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+    }
+    for (int64_t i = n_whole * chunk + (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kBlock) {
+        const uint4 v = p[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9E3779B9u) *sink = acc;
+}
+}  // namespace
+hipError_t gbt_launch_stream_read(hipStream_t s, const void *buf, int64_t bytes, uint32_t *sink) {
+    const int64_t n16 = bytes / 16;
+    if (n16 <= 0) return hipSuccess;
+    stream_read_kernel<<<grid_for(n16, kBlock * kStreamBatch, 4096), kBlock, 0, s>>>((const uint4 *)buf, n16, sink);
+    return hipGetLastError();
+}
+
 hipError_t gbt_launch_absmax(hipStream_t s, const float *gpair, int64_t n, uint32_t *out2) {
     hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)out2, 0, 2);
     if (e != hipSuccess || n <= 0) return e;
