@@ -252,8 +252,8 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
     # which kernels the classes of the library's profile stand for on this shape
     path = ctx.grow_tree_path(F, bits, p["max_bins"], track_rows=False)
     root8 = bits == 8 and F <= 16
-    hist_kernel = ("hist8_kernel" if root8 else "hist_b8_kernel") if bits == 8 else "hist_static_kernel"
-    node_hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_static_kernel"
+    hist_kernel = ("hist8_kernel" if root8 else "hist_b8_kernel") if bits == 8 else "hist_bits_kernel"
+    node_hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_bits_kernel"
     node_kernel = "part_hist_kernel (partition + one child's histogram in one pass)" if path == 2 else node_hist_kernel
     part_kernel = ("count2_kernel (row counts of the leaves)" if path == 2 and not lossguide else
                    "part_flag_kernel + part_scan_kernel (row counts of the last level)" if path == 2 else

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgbt.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["gbt_api.hip", "kernels_misc.hip", "kernels_hist.hip", "kernels_hist8.hip", "kernels_split.hip",
+SOURCES = ["gbt_api.hip", "kernels_misc.hip", "kernels_hist.hip", "kernels_hist8.hip", "kernels_histw.hip", "kernels_split.hip",
            "kernels_partition.hip", "kernels_quantise.hip", "kernels_order.hip", "kernels_sparse.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=off",

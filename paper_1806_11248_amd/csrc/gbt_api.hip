@@ -84,8 +84,11 @@ bool plan_tiles(const gbt_ctx *ctx, int F, int B, int bits, HistPlan *p) {
 }
 
 // Appends the jobs of one node; rows_per_job > 0.
+// A node covered by ONE row piece has exclusive jobs (HistJob.pad0 = 1: their bins are stored, not added); set
+// may_store = false where the histogram is not 16-byte aligned.
 void add_hist_jobs(std::vector<HistJob> &jobs, uint64_t hist_off, uint32_t begin, uint32_t len, int F,
-                   const HistPlan &pl, uint32_t rows_per_job) {
+                   const HistPlan &pl, uint32_t rows_per_job, bool may_store = true) {
+    const bool exclusive = may_store && len <= rows_per_job;
     for (uint32_t r0 = 0; r0 < len; r0 += rows_per_job) {
         uint32_t nr = std::min(rows_per_job, len - r0);
         for (int t = 0; t < pl.n_ftiles; ++t) {
@@ -95,17 +98,30 @@ void add_hist_jobs(std::vector<HistJob> &jobs, uint64_t hist_off, uint32_t begin
             j.n_rows = nr;
             j.f0 = (uint32_t)(t * pl.ft);
             j.ft = (uint32_t)std::min(pl.ft, F - t * pl.ft);
-            j.pad0 = j.pad1 = 0;
+            j.pad0 = exclusive ? 1u : 0u;
+            j.pad1 = 0;
             if (j.ft > 0) jobs.push_back(j);
         }
     }
 }
 
-uint32_t pick_rows_per_job(const gbt_ctx *ctx, int64_t total_rows) {
-    int64_t target_jobs = (int64_t)ctx->num_cu * ctx->hist_jobs_per_cu;
-    int64_t rpj = (total_rows + target_jobs - 1) / target_jobs;
+// max_rows: what a job of the kernel may hold (2^21: its per-bin event counters are 16 bits wide; fewer where
+// it counts rows in a narrow field, gbt_histw_max_rows)
+// Every job of a launch merges the bins of its feature tile into HBM with two 64-bit global atomics per non-zero
+// bin, and the chip retires only ~1e11 of those per second, some forty times fewer than LDS atomics: a row piece
+// is therefore long enough that a bin receives hist_merge_ratio LDS additions on average per value merged
+// (rows >= ratio * 2 * B), unless that would leave fewer than about one workgroup per compute unit.
+uint32_t pick_rows_per_job(const gbt_ctx *ctx, int64_t total_rows, int64_t max_rows = 1 << 21, int n_tiles = 1,
+                           int B = 0) {
+    int64_t pieces = std::max<int64_t>(1, (int64_t)ctx->num_cu * ctx->hist_jobs_per_cu / std::max(1, n_tiles));
+    if (B > 0) {
+        const int64_t by_merge = std::max<int64_t>(total_rows / ((int64_t)ctx->hist_merge_ratio * 2 * B),
+                                                   ((int64_t)ctx->num_cu + n_tiles - 1) / n_tiles);
+        pieces = std::min(pieces, std::max<int64_t>(1, by_merge));
+    }
+    int64_t rpj = (total_rows + pieces - 1) / pieces;
     if (rpj < 4096) rpj = 4096;
-    if (rpj > (1 << 21)) rpj = 1 << 21;   // the per-bin event counters of the histogram kernel are 16 bits wide
+    if (rpj > max_rows) rpj = max_rows;
     return (uint32_t)rpj;
 }
 
@@ -202,6 +218,7 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         c->num_cu = prop.multiProcessorCount;
         c->hist_block = 512;
         c->hist_jobs_per_cu = 8;
+        c->hist_merge_ratio = 96;
         c->hist_lds_kb = 64;   // two resident workgroups per CU hide the row-fetch latency better than one big tile
         if (const char *e1 = getenv("GBT_TUNE_HIST_BLOCK")) { int v = atoi(e1); if (v == 256 || v == 512 || v == 1024) c->hist_block = v; }
         if (const char *e3 = getenv("GBT_TUNE_HIST_RUNTIME_BITS")) c->hist_runtime_bits = atoi(e3) != 0;
@@ -227,6 +244,7 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (const char *e8 = getenv("GBT_TUNE_PART_HIST")) c->part_hist = atoi(e8) != 0;
         if (const char *e6 = getenv("GBT_TUNE_PART_FUSED")) c->part_fused = atoi(e6) != 0;
         if (const char *e5 = getenv("GBT_TUNE_HIST_LDS_KB")) { int v = atoi(e5); if (v >= 8 && v <= 128) c->hist_lds_kb = v; }
+        if (const char *e19 = getenv("GBT_TUNE_HIST_MERGE_RATIO")) { int v = atoi(e19); if (v >= 1 && v <= 100000) c->hist_merge_ratio = v; }
         if (const char *e2 = getenv("GBT_TUNE_HIST_JOBS")) { int v = atoi(e2); if (v >= 1 && v <= 64) c->hist_jobs_per_cu = v; }
         size_t lds = prop.sharedMemPerBlock;
         int optin = 0;
@@ -481,7 +499,7 @@ struct RootFix {   // the root histogram converts the fp32 pairs itself (gbt_lau
 static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
                             const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs /* may be NULL */,
-                            RootFix *fix = nullptr);
+                            RootFix *fix = nullptr, bool uniform_h = false, int32_t hq_uniform = 0);
 
 extern "C" int32_t gbt_build_hist(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                                   int32_t B, int32_t missing_sym, const uint32_t *row_idx,
@@ -686,7 +704,8 @@ extern "C" int32_t gbt_partition_static(gbt_ctx *ctx, const uint32_t *packed, in
 // ------------------------------------------------------------ histogram job --
 static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                             int32_t B, int32_t missing_sym, const uint32_t *row_idx, int64_t n_rows,
-                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs, RootFix *fix) {
+                            const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs, RootFix *fix, bool uniform_h,
+                            int32_t hq_uniform) {
     HistPlan pl;
     GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins (%d bytes) exceed the LDS budget", B, B * 16);
@@ -714,7 +733,10 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
         return GBT_OK;
     }
     std::vector<HistJob> jobs;
-    add_hist_jobs(jobs, 0, 0, (uint32_t)n_rows, F, pl, pick_rows_per_job(ctx, n_rows));
+    const bool uni_w = uniform_h && bits != 8 && !ctx->hist_runtime_bits;   // the kernels with a row-count form
+    add_hist_jobs(jobs, 0, 0, (uint32_t)n_rows, F, pl,
+                  pick_rows_per_job(ctx, n_rows, gbt_histw_max_rows(uni_w), pl.n_ftiles, B),
+                  ((uintptr_t)hist_out & 15u) == 0);
     // Without a caller workspace the job table is read straight from the pinned
     // staging, which the device can address; it is small (a few KB).
     size_t bytes = jobs.size() * sizeof(HistJob);
@@ -736,7 +758,8 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
                                          fix->sums_dev, hist_out, dev_jobs, (int)jobs.size(), pl.ft));
     else
         GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, (int64_t)F * bits, gbt_packed_words(n, F, bits), n, B,
-                                     (uint32_t)missing_sym, row_idx, gq, hist_out, dev_jobs, (int)jobs.size(), pl.ft));
+                                     (uint32_t)missing_sym, row_idx, gq, hist_out, dev_jobs, (int)jobs.size(), pl.ft,
+                                     uni_w, hq_uniform));
     gbt_prof_end(ctx);
     return GBT_OK;
 }
@@ -985,7 +1008,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         RootFix fix{gpair, scale[0], scale[1], pairs_stay_fp32 ? nullptr : gq, sums_dev, uniform_h,
                     (int32_t)llrint((double)h_value * scale[1]), (int64_t *)(ws + L.jobs), 0};
         st = hist_uniform(ctx, packed, bits, n, F, B, missing_sym, nullptr, n, gq, pool,
-                          (HistJob *)(ws + L.jobs), fix_in_hist ? &fix : nullptr);
+                          (HistJob *)(ws + L.jobs), fix_in_hist ? &fix : nullptr, uniform_h != 0, fix.hq_uniform);
         if (st != GBT_OK) return st;
         sum_slots = fix_in_hist ? fix.n_slots : 0;
     }
@@ -1539,7 +1562,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
                                              (int64_t)n_children * hist_len));
             gbt_prof_end(ctx);
-            const uint32_t rpj = pick_rows_per_job(ctx, built_rows);
+            const bool uni_w = uniform_h && bits != 8 && !ctx->hist_runtime_bits;   // the kernels with a row-count form
+            const int32_t hq_uniform = (int32_t)llrint((double)h_value * scale[1]);
+            const uint32_t rpj = pick_rows_per_job(ctx, built_rows, gbt_histw_max_rows(uni_w), pl.n_ftiles, B);
             for (const Built &b : built) add_hist_jobs(hjobs, b.off, b.begin, b.len, F, pl, rpj);
             const size_t per_launch = kUploadBytes / sizeof(HistJob);
             for (size_t j0 = 0; j0 < hjobs.size(); j0 += per_launch) {
@@ -1553,11 +1578,11 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 if (path == 3)   // the rows by id from the caller's matrix, the pairs by id
                     GBT_HIP(ctx, gbt_launch_hist(ctx, packed, bits, row_bits, gbt_packed_words(n, F, bits), n, B,
                                                  (uint32_t)missing_sym, W[wnext].id, gq, pool,
-                                                 (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
+                                                 (const HistJob *)(ws + L.jobs), (int)nj, pl.ft, uni_w, hq_uniform));
                 else
                     GBT_HIP(ctx, gbt_launch_hist(ctx, W[wnext].sym, bits, W[wnext].stride_bits, W[wnext].n_words, n, B,
                                                  (uint32_t)missing_sym, nullptr, W[wnext].gq, pool,
-                                                 (const HistJob *)(ws + L.jobs), (int)nj, pl.ft));
+                                                 (const HistJob *)(ws + L.jobs), (int)nj, pl.ft, uni_w, hq_uniform));
                 gbt_prof_end(ctx);
             }
         }

@@ -37,6 +37,7 @@ struct gbt_ctx {
     int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
+    int hist_merge_ratio;   // LDS additions a bin should receive, on average, per value a job merges into HBM
     int hist8;              // 1: the root histogram of 8-bit symbols with at most 16 features takes kernels_hist8.hip
     int hist8_stagger;      // its workgroups on one compute unit get unequal shares of rows: spread in 1/256ths
     int sparse_jobs_per_cu; // row pieces per compute unit and launch of the sparse-row histogram kernel
@@ -87,7 +88,8 @@ struct HistJob {
     uint32_t row_begin;
     uint32_t n_rows;
     uint32_t f0, ft;
-    uint32_t pad0, pad1;
+    uint32_t pad0;   // 1: this is the only job of its (node, feature tile): it may store its bins instead of adding them
+    uint32_t pad1;
 };
 
 // One node for the split kernel.
@@ -173,7 +175,16 @@ hipError_t gbt_launch_export(hipStream_t s, const int64_t *hist, int64_t count, 
 // n_words: readable 32-bit words of `packed`; row_idx NULL: job rows are matrix rows.
 hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n_words,
                            int64_t n, int B, uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
-                           int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft);
+                           int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft,
+                           // every row's rounded h equals hq_uniform: kernels that have a form for it (symbol widths
+                           // other than 8 bits) count rows instead of summing h; jobs then hold at most
+                           // gbt_histw_max_rows(true) rows
+                           bool uniform_h = false, int32_t hq_uniform = 0);
+int gbt_histw_max_rows(bool uniform_h);
+hipError_t gbt_launch_histw(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n_words,
+                            int64_t n, int B, uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
+                            int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft, bool uniform_h,
+                            int32_t hq_uniform);
 // Largest feature tile whose LDS histogram fits, and the per-job row count to aim for.
 int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B);
 

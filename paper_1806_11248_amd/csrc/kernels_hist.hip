@@ -23,40 +23,9 @@
 // indices of different features (e.g. the most frequent category of several
 // skewed columns) fall into different LDS banks.
 #include "gbt_internal.h"
+#include "hist_common.h"
 
 namespace {
-
-constexpr int kHistBlock = 1024;
-__device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long long old,
-                                         unsigned long long addv, uint32_t hq);
-
-__device__ __forceinline__ void pk_add(unsigned long long *main_, uint32_t *side, int idx,
-                                       unsigned long long addv, uint32_t hq) {
-    const unsigned long long old = atomicAdd(&main_[idx], addv);
-    pk_check(side, idx, old, addv, hq);
-}
-
-__device__ __forceinline__ unsigned long long pack_pair(int2 q) {
-    return ((unsigned long long)(long long)q.x << kHShift) + (unsigned long long)(uint32_t)q.y;
-}
-
-// Merge the workgroup's LDS histogram into the node's histogram in HBM.
-__device__ __forceinline__ void flush_tile(const unsigned long long *main_, const uint32_t *side, int ft, int B,
-                                           int Bp, int64_t *out, int block) {
-    for (int i = threadIdx.x; i < ft * B; i += block) {
-        const int t = i / B, b = i - t * B;
-        const int idx = t * Bp + b;
-        const unsigned long long w = main_[idx];
-        const uint32_t sc = side[idx];
-        if (w == 0 && sc == 0) continue;
-        const int64_t carry = (int64_t)(sc & 0xffffu);
-        const int64_t wraps = (int64_t)((int32_t)sc >> 16);
-        const int64_t g = ((int64_t)w >> kHShift) + wraps * ((int64_t)1 << (64 - kHShift)) - carry;
-        const int64_t h = (int64_t)(w & kHMask) + (carry << kHShift);
-        if (g != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i), (unsigned long long)g);
-        if (h != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i + 1), (unsigned long long)h);
-    }
-}
 
 // ---------------------------------------------------------------------------
 // Any bit width (run-time), any feature tile, optional row-id list.
@@ -125,7 +94,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
         }
     }
     __syncthreads();
-    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
+    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x, job.pad0 == 1u);
 }
 
 // ---------------------------------------------------------------------------
@@ -155,60 +124,6 @@ __global__ __launch_bounds__(kHistBlock) void hist_generic_kernel(
 //         itself, stores them for the later levels and adds up the root's totals,
 //         which saves the separate conversion pass over all rows
 // ---------------------------------------------------------------------------
-// The two quick tests on a returned word, as tight as the row's own pair allows (events are not
-// rare enough for loose ones: a heavy bin sees a carry every few hundred adds, and with 64 lanes
-// and 13 features some lane is near one most of the time):
-//   carry  iff  h field + hq >= 2^30        iff  (~low word & 2^30-1) < hq          (exact)
-//   wrap   only if the g field lies within |g| + 1 of the end it is moving towards.  In units of
-//          four (the high word is the g field >> 2, signed): its distance from that end is
-//          high ^ kind, kind = 0x7FFFFFFF going up, 0x80000000 going down, and the test is
-//          distance < reach, reach = |g| / 4 rounded up, plus one for the carry that may come along.
-// (everything is derived from the pair's own word where it is used, so that no register is held for it)
-__device__ __forceinline__ uint32_t pk_near_carry(unsigned long long old) { return ~(uint32_t)old & kHMask; }
-__device__ __forceinline__ uint32_t pk_near_wrap(unsigned long long old, unsigned long long addv) {
-    const uint32_t down = (uint32_t)((int32_t)(addv >> 32) >> 31);   // 0 going up, all ones going down
-    return (uint32_t)(old >> 32) ^ down ^ 0x7FFFFFFFu;
-}
-__device__ __forceinline__ uint32_t pk_reach(unsigned long long addv) {
-    const uint32_t ahi = (uint32_t)(addv >> 32);   // floor(g / 4), signed
-    return (ahi ^ (uint32_t)((int32_t)ahi >> 31)) + 2u;
-}
-
-__device__ __forceinline__ void pk_check(uint32_t *side, int idx, unsigned long long old,
-                                         unsigned long long addv, uint32_t hq) {
-    uint32_t olo = (uint32_t)old, ohi = (uint32_t)(old >> 32);
-    const bool danger = (pk_near_carry(old) < hq) | (pk_near_wrap(old, addv) < pk_reach(addv));
-    if (danger) {
-        asm volatile("" : "+v"(olo), "+v"(ohi));   // keep the rare bookkeeping inside the branch
-        const uint32_t carry = ((olo & kHMask) + hq) >> kHShift;
-        const uint32_t alo = (uint32_t)addv, ahi = (uint32_t)(addv >> 32);
-        const uint32_t nlo = olo + alo;
-        const uint32_t nhi = ohi + ahi + (nlo < olo ? 1u : 0u);
-        const int32_t ovf = (int32_t)((ohi ^ nhi) & (ahi ^ nhi));   // sign bit set: the g field wrapped
-        const int32_t delta = ovf < 0 ? ((int32_t)nhi < 0 ? 1 : -1) : 0;
-        if (carry != 0 || delta != 0) atomicAdd(&side[idx], (uint32_t)(delta * 65536 + (int32_t)carry));
-    }
-}
-
-// The returned words of a group of atomics (the first `live` of G) tested together: the smallest
-// distance of any of them from an event decides whether the per-word bookkeeping runs at all.
-template <int G>
-__device__ __forceinline__ void pk_check_group(uint32_t *side, const int (&idx)[G], const unsigned long long (&old)[G],
-                                               int live, unsigned long long addv, uint32_t hq) {
-    uint32_t near_carry = 0xffffffffu, near_wrap = 0xffffffffu;   // see pk_check for the two conditions
-#pragma unroll
-    for (int j = 0; j < G; ++j)
-        if (j < live) {
-            near_carry = min(near_carry, pk_near_carry(old[j]));
-            near_wrap = min(near_wrap, pk_near_wrap(old[j], addv));
-        }
-    if (near_carry < hq || near_wrap < pk_reach(addv)) {
-#pragma unroll
-        for (int j = 0; j < G; ++j)
-            if (j < live) pk_check(side, idx[j], old[j], addv, hq);
-    }
-}
-
 struct FixArgs {   // FIX only
     const float2 *gpair;
     double sg, sh;
@@ -327,7 +242,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
         }
     }
     __syncthreads();
-    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
+    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x, job.pad0 == 1u);
     if (FIX) {   // one pair of global atomics per workgroup
         __shared__ int64_t red[2][kHistBlock / 64];
         for (int o = 32; o > 0; o >>= 1) {
@@ -350,93 +265,6 @@ __global__ __launch_bounds__(kHistBlock) void hist_b8_kernel(
             atomicAdd((unsigned long long *)&fix.sums[1], (unsigned long long)sum_h);
         }
     }
-}
-
-// ---------------------------------------------------------------------------
-// Compile-time symbol width other than 8 bits.  lane = one row; the row slice is
-// consumed in register windows of E = min(128 / BITS, 32) whole elements: five
-// words are loaded, funnel-shifted (v_alignbit) so that the window starts at bit
-// 0, and every element is then cut out at a compile-time position.  Atomics are
-// issued in groups of up to 16 before their returned words are examined.  A slot
-// without a live feature, a missing symbol or a symbol >= B goes to a spare row
-// of 64 words indexed by the lane (conflict-free) instead of being predicated.
-// ---------------------------------------------------------------------------
-template <int BITS, bool LIST>
-__global__ __launch_bounds__(kHistBlock) void hist_static_kernel(
-    const uint32_t *__restrict__ packed, int64_t n_words, int64_t stride_bits, int64_t n, int B, int Bp,
-    uint32_t missing, const uint32_t *__restrict__ row_idx, const int2 *__restrict__ gq,
-    int64_t *__restrict__ pool, const HistJob *__restrict__ jobs) {
-    constexpr int E = (128 / BITS) < 32 ? (128 / BITS) : 32;   // elements per window
-    constexpr int G = E < 16 ? E : 16;                         // atomics in flight per lane
-    constexpr uint32_t MASK = (1u << BITS) - 1u;
-    extern __shared__ unsigned long long lds[];
-    const HistJob job = jobs[blockIdx.x];
-    const int ft = (int)job.ft;
-    const int trash = ft * Bp;
-    const int n_acc = trash + 256;
-    unsigned long long *main_ = lds;
-    uint32_t *side = (uint32_t *)(lds + n_acc);
-    for (int i = threadIdx.x; i < n_acc; i += (int)blockDim.x) {
-        main_[i] = 0;
-        side[i] = 0;
-    }
-    __syncthreads();
-
-    const int lane = threadIdx.x & 63;
-    const int my_trash = trash + lane;
-    const int nwin = (ft + E - 1) / E;
-    for (uint32_t i = threadIdx.x; i < job.n_rows; i += blockDim.x) {
-        const uint64_t pos_in = (uint64_t)job.row_begin + i;
-        const uint64_t r = LIST ? (uint64_t)row_idx[pos_in] : pos_in;
-        if (r >= (uint64_t)n) continue;
-        const int2 q = gq[r];
-        const unsigned long long addv = pack_pair(q);
-        const uint32_t hq = (uint32_t)q.y;
-        const uint64_t bit0 = r * (uint64_t)stride_bits + (uint64_t)job.f0 * BITS;
-        int c = (lane * nwin) >> 6;   // lanes of a wave start at different windows
-        for (int cc = 0; cc < nwin; ++cc) {
-            const uint64_t wb = bit0 + (uint64_t)c * (E * BITS);
-            const int64_t w0 = (int64_t)(wb >> 5);
-            const uint32_t sh = (uint32_t)(wb & 31);
-            uint32_t w[5], W[4];
-#pragma unroll
-            for (int k = 0; k < 5; ++k) {
-                const int64_t wi = w0 + k;
-                w[k] = packed[wi < n_words ? wi : n_words - 1];
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) W[k] = __builtin_amdgcn_alignbit(w[k + 1], w[k], sh);
-            const int tbase = c * E;
-#pragma unroll
-            for (int g0 = 0; g0 < E; g0 += G) {
-                int idx[G];
-                unsigned long long old[G];
-#pragma unroll
-                for (int jj = 0; jj < G; ++jj) {
-                    const int j = g0 + jj;
-                    if (j < E) {
-                        constexpr int dummy = 0;
-                        (void)dummy;
-                        const int pos = j * BITS, wd = pos >> 5, off = pos & 31;
-                        uint32_t sv;
-                        if (off + BITS <= 32)
-                            sv = (W[wd] >> off) & MASK;
-                        else
-                            sv = __builtin_amdgcn_alignbit(W[wd < 3 ? wd + 1 : 3], W[wd], (uint32_t)off) & MASK;
-                        const int t = tbase + j;
-                        const bool ok = (t < ft) & (sv != missing) & (sv < (uint32_t)B);
-                        idx[jj] = ok ? t * Bp + (int)sv : my_trash;
-                        old[jj] = atomicAdd(&main_[idx[jj]], addv);
-                    }
-                }
-                pk_check_group<G>(side, idx, old, E - g0, addv, hq);
-            }
-            ++c;
-            if (c == nwin) c = 0;
-        }
-    }
-    __syncthreads();
-    flush_tile(main_, side, ft, B, Bp, pool + job.hist_off + (uint64_t)job.f0 * (uint64_t)B * 2u, (int)blockDim.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -987,7 +815,6 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
     if (job.has[1]) flush_tile(main0 + n_acc, side0 + n_acc, ft, B, Bp, pool + job.hist_off[1], kH2Block);
 }
 
-inline int padded_bins(int B) { return B | 1; }   // odd stride: see the note on LDS banks above
 
 }  // namespace
 
@@ -1044,40 +871,6 @@ hipError_t pick_slots(int max_ft, const B8Args &a) {
     if (max_ft > 16) return launch_b8<LIST, 0, CHK, false>(a);
     return pick_slots_single<LIST, CHK, false>(max_ft, a);
 }
-template <int BITS, bool LIST>
-hipError_t launch_static(const B8Args &a, int64_t stride_bits) {
-    static size_t configured = 0;
-    if (a.lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)hist_static_kernel<BITS, LIST>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
-        if (e != hipSuccess) return e;
-        configured = a.lds;
-    }
-    hist_static_kernel<BITS, LIST><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, stride_bits, a.n, a.B, a.Bp,
-                                                                       a.missing, a.row_idx, a.gq, a.pool, a.jobs);
-    return hipGetLastError();
-}
-template <bool LIST>
-hipError_t pick_static(int bits, const B8Args &a, int64_t stride_bits) {
-    switch (bits) {
-        case 1: return launch_static<1, LIST>(a, stride_bits);
-        case 2: return launch_static<2, LIST>(a, stride_bits);
-        case 3: return launch_static<3, LIST>(a, stride_bits);
-        case 4: return launch_static<4, LIST>(a, stride_bits);
-        case 5: return launch_static<5, LIST>(a, stride_bits);
-        case 6: return launch_static<6, LIST>(a, stride_bits);
-        case 7: return launch_static<7, LIST>(a, stride_bits);
-        case 9: return launch_static<9, LIST>(a, stride_bits);
-        case 10: return launch_static<10, LIST>(a, stride_bits);
-        case 11: return launch_static<11, LIST>(a, stride_bits);
-        case 12: return launch_static<12, LIST>(a, stride_bits);
-        case 13: return launch_static<13, LIST>(a, stride_bits);
-        case 14: return launch_static<14, LIST>(a, stride_bits);
-        case 15: return launch_static<15, LIST>(a, stride_bits);
-        case 16: return launch_static<16, LIST>(a, stride_bits);
-        default: return hipErrorInvalidValue;
-    }
-}
 template <bool LIST>
 hipError_t launch_generic(hipStream_t s, int n_jobs, int block, size_t lds, const uint32_t *packed, int64_t n_words, int bits,
                           int64_t stride_bits, int64_t n, int B, int Bp, uint32_t missing,
@@ -1098,8 +891,12 @@ hipError_t launch_generic(hipStream_t s, int n_jobs, int block, size_t lds, cons
 
 hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64_t stride_bits, int64_t n_words,
                            int64_t n, int B, uint32_t missing, const uint32_t *row_idx, const int32_t *gq,
-                           int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft) {
+                           int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft, bool uniform_h,
+                           int32_t hq_uniform) {
     if (n_jobs <= 0) return hipSuccess;
+    if (!ctx->hist_runtime_bits && bits != 8)
+        return gbt_launch_histw(ctx, packed, bits, stride_bits, n_words, n, B, missing, row_idx, gq, hist_pool, jobs,
+                                n_jobs, max_ft, uniform_h, hq_uniform);
     const int Bp = padded_bins(B);
     const size_t lds = ((size_t)max_ft * Bp + 256) * 12;
     const int2 *g2 = (const int2 *)gq;
@@ -1109,10 +906,6 @@ hipError_t gbt_launch_hist(gbt_ctx *ctx, const uint32_t *packed, int bits, int64
         const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, stride_bits >> 3, n, B, Bp, missing, row_idx, g2, hist_pool, jobs, FixArgs{}};
         if (row_idx) return chk ? pick_slots<true, true>(max_ft, a) : pick_slots<true, false>(max_ft, a);
         return chk ? pick_slots<false, true>(max_ft, a) : pick_slots<false, false>(max_ft, a);
-    }
-    if (!ctx->hist_runtime_bits && bits != 8) {
-        const B8Args a{s, n_jobs, ctx->hist_block, lds, packed, n_words, 0, n, B, Bp, missing, row_idx, g2, hist_pool, jobs, FixArgs{}};
-        return row_idx ? pick_static<true>(bits, a, stride_bits) : pick_static<false>(bits, a, stride_bits);
     }
     if (row_idx)
         return launch_generic<true>(s, n_jobs, ctx->hist_block, lds, packed, n_words, bits, stride_bits, n, B, Bp, missing, row_idx, g2, hist_pool, jobs);
