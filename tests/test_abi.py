@@ -57,4 +57,5 @@ def test_struct_layouts_match_header():
     assert C.sizeof(g.binding.Split) == 72
     assert C.sizeof(g.binding.Params) == 48
     assert C.sizeof(g.binding.Tree) == 8 + 11 * 8
-    assert C.sizeof(g.binding.Profile) == 3 * 8 * len(g.binding.PROF_CLASSES) == 3 * 8 * 8   # GBT_PROF_CLASSES
+    # four 8-byte arrays over GBT_PROF_CLASSES = 8 classes, four over GBT_PROF_LEVELS = 18 depths
+    assert C.sizeof(g.binding.Profile) == 8 * (4 * len(g.binding.PROF_CLASSES) + 4 * g.binding.PROF_LEVELS) == 8 * (4 * 8 + 4 * 18)
