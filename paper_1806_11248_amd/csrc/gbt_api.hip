@@ -251,6 +251,7 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess &&
             (size_t)optin > lds)
             lds = (size_t)optin;
+        c->lds_max = lds;
         if (lds > 128u * 1024u) lds = 128u * 1024u;   // leave room for a second resident workgroup's statics
         c->lds_per_block = lds;
         e = hipHostMalloc((void **)&c->pinned, GBT_STAGING_BYTES, hipHostMallocDefault);

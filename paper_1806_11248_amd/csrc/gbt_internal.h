@@ -24,6 +24,7 @@ struct gbt_ctx {
     hipStream_t stream;
     int num_cu;
     size_t lds_per_block;   // largest dynamic LDS a workgroup may ask for
+    size_t lds_max;         // the most LDS one workgroup can be given (a kernel with one workgroup per CU and no static LDS)
     char *pinned;           // host staging for job tables and small read-backs
     size_t pinned_bytes;
     int hist_block;         // threads per histogram workgroup

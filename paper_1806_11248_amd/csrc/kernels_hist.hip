@@ -305,6 +305,7 @@ constexpr int kPHWords = kPHTile / 64;           // 64 ballot words
 static_assert(kPHWords == 64, "the ballot words are ranked by one wave");
 constexpr int kPHGroup = 7;                      // atomics of a row in flight together (registers for their results)
 constexpr int record_words(int ns) { return (ns + 7 + 3) / 4; }
+constexpr int slots_for(int ft) { return ft <= 4 ? 4 : ft <= 8 ? 8 : ft <= 12 ? 12 : ft == 13 ? 13 : 16; }
 
 __device__ inline int find_span_job(const PartJob *jobs, int n_jobs, uint32_t span) {
     int lo = 0, hi = n_jobs;
@@ -357,6 +358,43 @@ __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned l
         pk_check_group<GROUP>(side, idx, old, NS - t0, addv, hq);
     }
 }
+
+// Where rows stay in place only some lanes of a wave hold a row whose pair is added, and a wave's LDS atomic
+// costs about the same with 25 active lanes as with 64.  Such rows are therefore first packed: a wave appends
+// the records it takes to a ring of its own in LDS (ranks from the ballot), and as soon as 64 are waiting it
+// reads them back one per lane and adds them with every lane busy.  TAG: one more word travels with a record.
+// The ring is private to the wave, whose LDS instructions execute in program order: no barrier is involved.
+constexpr int kQueueSlots = 128;   // >= 63 waiting + 64 appended
+template <int RW, bool TAG>
+struct WaveQueue {
+    static constexpr int kWords = RW + (TAG ? 1 : 0);
+    uint32_t *q;           // kWords * kQueueSlots words, word-major: the lanes of a wave touch consecutive words
+    uint32_t head, tail;   // wave-uniform
+    __device__ __forceinline__ void push(bool take, const uint32_t (&row)[RW], uint32_t tag) {
+        const uint64_t m = __ballot(take);
+        if (take) {
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            const uint32_t s = (tail + rank) & (kQueueSlots - 1);
+#pragma unroll
+            for (int k = 0; k < RW; ++k) q[k * kQueueSlots + s] = row[k];
+            if (TAG) q[RW * kQueueSlots + s] = tag;
+        }
+        tail += (uint32_t)__popcll(m);
+        __builtin_amdgcn_wave_barrier();
+    }
+    __device__ __forceinline__ uint32_t waiting() const { return tail - head; }
+    // the record `lane` places after the head (the caller has checked that it exists); advance with drop()
+    __device__ __forceinline__ void peek(int lane, uint32_t (&row)[RW], uint32_t &tag) const {
+        const uint32_t s = (head + (uint32_t)lane) & (kQueueSlots - 1);
+#pragma unroll
+        for (int k = 0; k < RW; ++k) row[k] = q[k * kQueueSlots + s];
+        tag = TAG ? q[RW * kQueueSlots + s] : 0u;
+    }
+    __device__ __forceinline__ void drop(uint32_t n) {
+        head += n;
+        __builtin_amdgcn_wave_barrier();
+    }
+};
 
 // F32: the pairs are still fp32 (src_gq then points at float2): each is rounded to fixed point here, in fp32
 // arithmetic, which is exact for the power-of-two scales sgf, shf the launcher accepts (gbt_fix32_ok)
@@ -532,6 +570,8 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
 // Levels below the first: the source is records.  A thread holds two sets of kPFRows records, one
 // being ranked, added to the histogram and stored, the other (the next tile) on its way from HBM
 // meanwhile, so that the loads never start from an empty pipe behind a tile's barriers.
+// (The wave queue of the passes that keep rows in place does not pay here: its LDS leaves room for two workgroups
+// per CU instead of four, and the barriers of a moving tile then cost more than the packed atomics save.)
 template <int NS, bool CHK>
 __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing,
@@ -686,12 +726,124 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
 }
 
+// One split per segment, rows stay where they are (the last level but one that needs histograms, see
+// gbt_launch_part_hist): every record is read once, its side decided and counted, and the records of the side
+// to be built are added to the LDS histogram through the wave's queue.  No ranks, no stores, no barriers inside a
+// span; the next tile's records are on their way while the current one is handled.
+constexpr int kKeepBlock = 512;
+template <int NS, bool CHK>
+__global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
+    const uint32_t *__restrict__ src, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs, int n_jobs,
+    uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
+    constexpr int SW = (NS + 3) / 4;
+    constexpr int RW = record_words(NS);
+    constexpr int BLK = kKeepBlock, ROWS = kPFRows, TILE = BLK * ROWS, WAVES = BLK / 64;
+    extern __shared__ unsigned long long lds[];
+    const int ji = find_span_job(jobs, n_jobs, blockIdx.x);
+    const PartJob job = jobs[ji];
+    const uint32_t span_begin = (blockIdx.x - job.tile_begin) * rows_per_span;
+    const uint32_t span_rows = job.seg_len - span_begin < rows_per_span ? job.seg_len - span_begin : rows_per_span;
+    const bool build = job.pad != 2u, build_left = job.pad == 1u;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    const int trash = ft * Bp;
+    const int n_acc = trash + 256;
+    unsigned long long *main_ = lds;
+    uint32_t *side = (uint32_t *)(lds + n_acc);
+    for (int i = threadIdx.x; i < n_acc; i += BLK) {
+        main_[i] = 0;
+        side[i] = 0;
+    }
+    WaveQueue<RW, false> queue{side + n_acc + wave * (RW * kQueueSlots), 0u, 0u};
+    uint32_t selA[4], selB[4];
+    int pre[NS];
+    {
+        const int l0 = lane % ft;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            selA[k] = 0;
+            selB[k] = 0;
+        }
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            int t = j + l0;
+            t = t >= ft ? t - ft : t;
+            const bool live = j < ft;
+            pre[j] = live ? t * Bp : trash + lane;
+            const uint32_t a = (live && t < 8) ? (uint32_t)t : 0x0Cu;
+            const uint32_t b = (live && t >= 8) ? (uint32_t)(t - 8) : 0x0Cu;
+            selA[j >> 2] |= a << (8 * (j & 3));
+            selB[j >> 2] |= b << (8 * (j & 3));
+        }
+    }
+    const uint32_t fselA = 0x0C0C0C00u | (job.feature < 8u ? job.feature : 0x0Cu);
+    const uint32_t fselB = 0x0C0C0C00u | (job.feature >= 8u ? job.feature - 8u : 0x0Cu);
+    uint32_t my_lefts = 0;
+    const uint64_t span_first = (uint64_t)job.seg_begin + span_begin;
+    __syncthreads();
+
+    auto load_tile = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
+            if (in_tile < tile_rows) {
+                const uint32_t *rp = src + (span_first + done + in_tile) * RW;
+#pragma unroll
+                for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+            }
+        }
+    };
+    auto add_waiting = [&](uint32_t n) __attribute__((always_inline)) {   // n <= 64 records from the head of the queue
+        uint32_t rec[RW], tag;
+        if ((uint32_t)lane < n) {
+            queue.peek(lane, rec, tag);
+            ph_add_row<NS, CHK, RW>(rec, main_, side, pre, selA, selB, trash, lane, missing, B);
+        }
+        queue.drop(n);
+    };
+    auto process = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
+            bool left = false, take = false;
+            if (in_tile < tile_rows) {
+                const uint32_t sy = __builtin_amdgcn_perm(SW > 1 ? row[j][SW > 1 ? 1 : 0] : 0u, row[j][0], fselA) |
+                                    __builtin_amdgcn_perm(SW > 3 ? row[j][SW > 3 ? 3 : 0] : 0u,
+                                                          SW > 2 ? row[j][SW > 2 ? 2 : 0] : 0u, fselB);
+                left = (sy == missing) ? (job.default_left != 0) : (sy <= job.bin);
+                take = build && left == build_left;
+            }
+            my_lefts += (uint32_t)__popcll(__ballot(left));
+            queue.push(take, row[j], 0u);
+            if (queue.waiting() >= 64u) add_waiting(64u);
+        }
+    };
+
+    uint32_t rowA[ROWS][RW], rowB[ROWS][RW];
+    load_tile(rowA, 0);
+    for (uint32_t done = 0; done < span_rows;) {
+        if (done + TILE < span_rows) load_tile(rowB, done + TILE);
+        process(rowA, done);
+        done += TILE;
+        if (done >= span_rows) break;
+        if (done + TILE < span_rows) load_tile(rowA, done + TILE);
+        process(rowB, done);
+        done += TILE;
+    }
+    if (queue.waiting()) add_waiting(queue.waiting());
+    if (lane == 0 && my_lefts) atomicAdd(&cursor[ji], (unsigned long long)my_lefts);
+    __syncthreads();
+    if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
+}
+
 // Rows that were not moved at their segment's split and are not moved now: every row belongs to one
 // of the segment's two children, whose split (if it has one) sends it left or right; of each splitting
 // child's two children one histogram is built.  A workgroup keeps BOTH histograms in LDS and takes a
 // span of the segment tile by tile, the next tile's records on their way while the current one is
-// added; no ranks, no stores, no barriers inside the span.  Left rows of the children are counted in
-// the cursor words 2 * job and 2 * job + 1.
+// added (through the wave's queue, tagged with the histogram a record goes to); no ranks, no stores, no
+// barriers inside the span.  Left rows of the children are counted in the cursor words 2 * job and 2 * job + 1.
 constexpr int kH2Block = 1024;
 template <int NS, bool CHK>
 __global__ __launch_bounds__(kH2Block) void hist2_kernel(
@@ -721,6 +873,7 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
         main0[i] = 0;
         side0[i] = 0;
     }
+    WaveQueue<RW, true> queue{side0 + 2 * n_acc + wave * ((RW + 1) * kQueueSlots), 0u, 0u};
     uint32_t selA[4], selB[4];
     int pre[NS];
     {
@@ -769,6 +922,14 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
             }
         }
     };
+    auto add_waiting = [&](uint32_t n) __attribute__((always_inline)) {   // n <= 64 records from the head of the queue
+        uint32_t rec[RW], c;
+        if ((uint32_t)lane < n) {
+            queue.peek(lane, rec, c);
+            ph_add_row<NS, CHK, RW>(rec, main0 + c * n_acc, side0 + c * n_acc, pre, selA, selB, trash, lane, missing, B);
+        }
+        queue.drop(n);
+    };
     auto process = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
         const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
 #pragma unroll
@@ -790,8 +951,8 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
             my_lefts[0] += (uint32_t)__popcll(b0);
             my_lefts[1] += (uint32_t)__popcll(b1);
             const bool take = counted && (left1 == ((c == 0 ? job.build[0] : job.build[1]) == 1u));
-            if (take)
-                ph_add_row<NS, CHK, RW>(row[j], main0 + c * n_acc, side0 + c * n_acc, pre, selA, selB, trash, lane, missing, B);
+            queue.push(take, row[j], (uint32_t)c);
+            if (queue.waiting() >= 64u) add_waiting(64u);
         }
     };
 
@@ -806,6 +967,7 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
         process(rowB, done);
         done += TILE;
     }
+    if (queue.waiting()) add_waiting(queue.waiting());
     if (lane == 0) {
         if (my_lefts[0]) atomicAdd(&cursor[2 * ji], (unsigned long long)my_lefts[0]);
         if (my_lefts[1]) atomicAdd(&cursor[2 * ji + 1], (unsigned long long)my_lefts[1]);
@@ -970,16 +1132,29 @@ hipError_t launch_ph_first(const PHArgs &a) {
 }
 template <int NS, bool CHK>
 hipError_t launch_ph(const PHArgs &a) {
-    static size_t configured = 0;
-    if (a.lds > configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
-        if (e != hipSuccess) return e;
-        configured = a.lds;
-    }
+    hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)a.lds);
+    if (e != hipSuccess) return e;
     part_hist_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
                                                                    a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
+}
+template <int NS, bool CHK>
+hipError_t launch_keep(const PHArgs &a) {
+    hipError_t e = hipFuncSetAttribute((const void *)hist_keep_kernel<NS, CHK>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)a.lds);
+    if (e != hipSuccess) return e;
+    hist_keep_kernel<NS, CHK><<<a.n_spans, kKeepBlock, a.lds, a.s>>>(a.src, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
+                                                                     a.rows_per_span, a.cursor, a.pool);
+    return hipGetLastError();
+}
+template <bool CHK>
+hipError_t pick_keep(int ft, const PHArgs &a) {
+    if (ft <= 4) return launch_keep<4, CHK>(a);
+    if (ft <= 8) return launch_keep<8, CHK>(a);
+    if (ft <= 12) return launch_keep<12, CHK>(a);
+    if (ft == 13) return launch_keep<13, CHK>(a);
+    return launch_keep<16, CHK>(a);
 }
 template <bool CHK, bool FIRST>
 hipError_t pick_ph(int ft, const PHArgs &a) {
@@ -996,7 +1171,6 @@ hipError_t pick_ph(int ft, const PHArgs &a) {
     if (ft == 13) return launch_ph<13, CHK>(a);
     return launch_ph<16, CHK>(a);
 }
-int slots_for(int ft) { return ft <= 4 ? 4 : ft <= 8 ? 8 : ft <= 12 ? 12 : ft == 13 ? 13 : 16; }
 }  // namespace
 
 bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B) {
@@ -1007,9 +1181,20 @@ bool gbt_part_hist_ok(const gbt_ctx *ctx, int bits, int F, int B) {
 }
 int gbt_part_hist_tile() { return kPHTile; }
 
+namespace {
+// LDS of the two-histogram pass: both histograms, then a tagged queue per wave
+size_t hist2_lds(int F, int B) {
+    return 2 * ((size_t)F * padded_bins(B) + 256) * 12 +
+           (size_t)(kH2Block / 64) * (record_words(slots_for(F)) + 1) * kQueueSlots * 4;
+}
+// ... of the one-histogram pass over rows that stay
+size_t keep_lds(int F, int B) {
+    return ((size_t)F * padded_bins(B) + 256) * 12 + (size_t)(kKeepBlock / 64) * record_words(slots_for(F)) * kQueueSlots * 4;
+}
+}  // namespace
 bool gbt_hist2_ok(const gbt_ctx *ctx, int F, int B) {
     if (F > 16 || B > 256) return false;
-    return 2 * ((size_t)F * padded_bins(B) + 256) * 12 <= ctx->lds_per_block;
+    return hist2_lds(F, B) <= ctx->lds_max;   // one workgroup per CU, no static LDS
 }
 namespace {
 template <int NS, bool CHK>
@@ -1048,7 +1233,7 @@ hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B,
         if (e != hipSuccess) return e;
     }
     const int Bp = padded_bins(B);
-    const size_t lds = 2 * ((size_t)F * Bp + 256) * 12;
+    const size_t lds = hist2_lds(F, B);
     const bool chk = missing < 256u || B < 256;
     return chk ? pick_hist2<true>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool)
                : pick_hist2<false>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool);
@@ -1072,6 +1257,11 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
                    packed_words, fp32 ? (const int2 *)gpair_fp32 : (const int2 *)gq, fp32, (float)sg, (float)sh, dst_records,
                    F, B, Bp, missing, jobs, n_jobs, rows_per_span, cursor, hist_pool};
     const bool chk = missing < 256u || B < 256;
+    if (!first && dst_records == nullptr && keep_lds(F, B) <= ctx->lds_per_block) {   // records that stay in place
+        PHArgs k = a;
+        k.lds = keep_lds(F, B);
+        return chk ? pick_keep<true>(F, k) : pick_keep<false>(F, k);
+    }
     if (first) return chk ? pick_ph<true, true>(F, a) : pick_ph<false, true>(F, a);
     return chk ? pick_ph<true, false>(F, a) : pick_ph<false, false>(F, a);
 }
