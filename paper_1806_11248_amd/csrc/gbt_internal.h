@@ -38,6 +38,7 @@ struct gbt_ctx {
     int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
+    int move_max_words;     // rows of more 32-bit words than this are never moved: only their ids are partitioned
     int hist_merge_ratio;   // LDS additions a bin should receive, on average, per value a job merges into HBM
     int hist8;              // 1: the root histogram of 8-bit symbols with at most 16 features takes kernels_hist8.hip
     int hist8_stagger;      // its workgroups on one compute unit get unequal shares of rows: spread in 1/256ths

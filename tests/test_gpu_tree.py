@@ -98,7 +98,7 @@ def test_tree_matches_oracle(ctx, oracle, cfg, n, kw, csr):
     n, F = X.shape
     _say(f"tree C{cfg} n={n} F={F} depth={p['max_depth']}")
     o, gdev = gpu_prep(ctx, oracle, d, use_csr=csr)
-    wide = F * gdev["bits"] > 64 * 32      # such rows are not moved: id lists are partitioned instead
+    wide = F * gdev["bits"] > 8 * 32       # such rows are not moved: id lists are partitioned instead
     assert (ctx.grow_tree_path(F, gdev["bits"], p["max_bins"], track_rows=True) == 3) == wide
     if p["objective"] == "given":
         gp = np.stack([d["g"], d["h"]], 1)
@@ -149,7 +149,7 @@ def ctx_env(monkeypatch):
 
 @pytest.mark.parametrize("cfg,n,kw", [(4, 150_000, {}), (3, 40_000, {}), (5, 5_000, {"F": 200}), (5, 4_000, {"F": 500})])
 def test_three_launch_partition_path(ctx_env, oracle, cfg, n, kw):
-    """The record partition normally takes its one-launch form (rows wider than 64 words: only ids
+    """The record partition normally takes its one-launch form (rows wider than 8 words: only ids
     move); switched off, the flag / scan / move form that carries whole records must grow the same trees."""
     c = ctx_env(GBT_TUNE_PART_FUSED=0, GBT_TUNE_PART_IDS=0, GBT_TUNE_HIST_FIX=0)   # and the separate fixed-point conversion pass
     d = synth.make(cfg, n, **kw)
