@@ -266,11 +266,13 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
     r_root = roof(prof, ["hist_root"], hist_kernel)
     r_node = roof(prof, ["hist_node"], node_kernel)
     r_first = roof(prof, ["hist_first"], "part_hist_first_kernel (the same pass at level 0, from the packed matrix)")
-    r_inplace = roof(prof, ["hist_inplace"], "hist2_kernel (the pass at the last level: rows in place, two histograms per workgroup)")
+    r_inplace = roof(prof, ["hist_inplace"], "hist_keep_kernel + hist2_kernel (the passes of the last two levels: rows stay in place, "
+                                            "one and two histograms per workgroup)")
     r_part = roof(prof, ["partition"], part_kernel)
     traffic = None if sparse else committed_traffic(cfg)
     if traffic:
         for obj, key in ((r_root, "hist_root_launch_bytes"), (r_node, "hist_node_launch_avg_bytes"),
+                         (r_first, "hist_first_launch_bytes"), (r_inplace, "hist_inplace_launch_avg_bytes"),
                          (r_part, "partition_launch_avg_bytes")):
             if obj and traffic.get(key):
                 obj["traffic"] = traffic[key]
@@ -322,8 +324,14 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
         out["with_row_order_and_leaf_ids"] = {"ms_per_step": ms_per_step_outputs,
                                               "value": n * F / (ms_per_step_outputs * 1e-3)}
     if headline:
-        # what a kernel that only reads gets from HBM here and now (the packed matrix, 1.5 GB on C4)
-        out["stream_read_ceiling_GBps"] = ctx.measure_stream_read(packed, reps=5)
+        # what a kernel that only reads gets from HBM here and now: a buffer of 6 GB, many times the 256 MB the
+        # memory-side cache holds, so that a repetition finds nothing of the one before (on the 1.5 GB packed matrix
+        # the same call reads 6 TB/s, a tenth of it from that cache)
+        big = torch.empty(6 * 1024 ** 3 // 4, dtype=torch.int32, device=dev)
+        big.fill_(1)
+        out["stream_read_ceiling_GBps"] = ctx.measure_stream_read(big, reps=5)
+        out["stream_read_ceiling_bytes"] = big.numel() * 4
+        del big
         log(f"streaming-read ceiling: {out['stream_read_ceiling_GBps']:.0f} GB/s")
         if not given and not sparse:
             # the root histogram again with gradient pairs of a boosted model (every row its own hessian): the first
@@ -393,7 +401,8 @@ def main():
     ap.add_argument("--no-outputs-leg", action="store_true",
                     help="skip the extra timing of the steps with row order and leaf ids asked for")
     ap.add_argument("--no-other-workloads", action="store_true",
-                    help="skip the other four configurations (by default each is run at full size for 5 steps)")
+                    help="skip the other four configurations (by default each is run at full size: 20 steps for C1 and C2, "
+                         "5 for C3, packed and sparse, and C5)")
     ap.add_argument("--policy", choices=["depthwise", "lossguide"], default="depthwise",
                     help="node expansion order (Sec. 2.3); lossguide grows --max-leaves leaves, no depth cap")
     ap.add_argument("--max-leaves", type=int, default=0, help="lossguide: leaf budget (default 2^max_depth)")
@@ -439,7 +448,8 @@ def main():
     if not a.no_other_workloads and a.rows is None and a.config == 4 and a.layout == "dense" and a.policy == "depthwise":
         others = []
         for cfg, layout in ((1, "dense"), (2, "dense"), (3, "dense"), (3, "sparse"), (5, "dense")):
-            w = run_workload(g, a, cfg, None, 5, 1, layout=layout)
+            # (the two small workloads take a millisecond per step: more steps, so that one slow step does not decide)
+            w = run_workload(g, a, cfg, None, 20 if cfg <= 2 else 5, 3, layout=layout)
             others.append({k: w[k] for k in ("config", "steps", "ms_per_step", "seconds_per_tree", "value",
                                               "ms_per_step_without_event_records", "hist_root_ms",
                                               "hist_root_rows_features_per_s", "roofline_hist_root", "roofline",

@@ -415,10 +415,10 @@ GBT_API int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t 
 #define GBT_PROF_EVAL 3      /* split evaluation, sibling subtraction included */
 #define GBT_PROF_CLEAR 4     /* zero-fill of the children's histograms */
 #define GBT_PROF_OTHER 5     /* scale search, fixed-point conversion, tree walks (leaf ids, prediction), row order */
-/* The partition + histogram pass has three kernels; GBT_PROF_HIST_NODE holds the one that reads and writes
- * records (every level but the first, the second-to-last no-move level included), these two the others: */
+/* The partition + histogram pass has four kernels; GBT_PROF_HIST_NODE holds the one that reads and writes
+ * records (the levels that move rows, except the first), these two classes the others: */
 #define GBT_PROF_HIST_FIRST 6   /* its first level, whose source is the caller's packed matrix */
-#define GBT_PROF_HIST_INPLACE 7 /* its last level where two levels stay in place (two histograms per workgroup) */
+#define GBT_PROF_HIST_INPLACE 7 /* its last one or two levels, whose records stay in place (one, then two histograms per workgroup) */
 #define GBT_PROF_CLASSES 8
 
 #define GBT_PROF_LEVELS 18 /* depths 0..16 of the nodes a launch builds histograms for, one spare */

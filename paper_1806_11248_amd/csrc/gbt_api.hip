@@ -1416,7 +1416,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             // what the method needs: a repartition is 4 + 4 + bits/8 bytes per row (where rows are only counted, the
             // symbol alone); the histogram part of a pass is added below, once the built children's rows are known
             const double part_alg = part_rows * ((nomove || nomove2 || what == GBT_PART_COUNT) ? bits / 8.0 : 8.0 + bits / 8.0);
-            const int pass_span = gbt_prof_begin(ctx, nomove2 ? GBT_PROF_HIST_INPLACE : with_hist ? (wcur == 2 ? GBT_PROF_HIST_FIRST : GBT_PROF_HIST_NODE)
+            const bool keeps_records = nomove2 || (nomove && with_hist && wcur != 2);   // a pass over records that stay in place
+            const int pass_span = gbt_prof_begin(ctx, keeps_records ? GBT_PROF_HIST_INPLACE : with_hist ? (wcur == 2 ? GBT_PROF_HIST_FIRST : GBT_PROF_HIST_NODE)
                                                                             : GBT_PROF_PARTITION,
                            nomove2 ? (double)h2_rows * rec_bytes :
                            part_rows * (path == 3 ? 8.0 + 32.0   // ids read and written, one sector of symbols per row
