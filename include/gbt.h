@@ -105,7 +105,30 @@ typedef struct gbt_tree {
 
 /* Creates a context on HIP device `device`; `stream` is a hipStream_t (NULL =
  * the default stream).  Loads nothing lazily: a missing or wrong-architecture
- * GPU makes this call fail with GBT_EHIP. */
+ * GPU makes this call fail with GBT_EHIP.
+ *
+ * Environment switches, read here once per context.  None changes a result (every
+ * tree, histogram and partition is the same under all of them, which the tests
+ * check by creating contexts under them); they choose between kernels and launch
+ * shapes, for measurements and for covering the alternative code paths.  Unset =
+ * the default in brackets; values outside the stated range are ignored.
+ *   GBT_TUNE_PART_HIST          [1] 0: never fuse the partition with a child's histogram (grow path 2 off)
+ *   GBT_TUNE_PART_FUSED         [1] 0: no one-launch unordered partition (paths 1 and 2 off)
+ *   GBT_TUNE_PART_IDS           [1] 0: wide rows are moved as whole records instead of partitioning id lists (path 3 off)
+ *   GBT_TUNE_MOVE_MAX_WORDS     [8] 1..64: rows of more 32-bit words than this are listed (path 3), not moved
+ *   GBT_TUNE_ORDER_ROWS         [1] 0: row ids travel with the rows (path 0) instead of the order being rebuilt from the tree
+ *   GBT_TUNE_PART_NOMOVE        [2] 0..2: how many of the last levels of a depth-wise tree leave their rows in place (path 2)
+ *   GBT_TUNE_HIST_FIX           [1] 0: gradient pairs are rounded to fixed point in a pass of their own, not in the root histogram launch
+ *   GBT_TUNE_HIST8              [1] 0: the root histogram of byte symbols by the general byte-symbol kernel
+ *   GBT_TUNE_HIST8_STAGGER      [64] 0..128: in 1/1024 of a job's length, how unequal the jobs of that launch are
+ *   GBT_TUNE_HIST_RUNTIME_BITS  [0] 1: histogram kernel with a run-time symbol width instead of the compile-time ones
+ *   GBT_TUNE_HIST_BLOCK         [512] 256, 512, 1024: threads per histogram workgroup
+ *   GBT_TUNE_HIST_LDS_KB        [64] 8..128: cap on a workgroup's LDS histogram (smaller feature tiles, more workgroups per CU)
+ *   GBT_TUNE_HIST_JOBS          [8] 1..64: histogram workgroups to aim for per compute unit and launch
+ *   GBT_TUNE_HIST_MERGE_RATIO   [96] 1..100000: LDS additions a bin should receive per value a job merges into HBM (longer row pieces)
+ *   GBT_TUNE_LOSSGUIDE_BATCH    [16] 1..64: open leaves expanded per round of loss-guided growth
+ *   GBT_TUNE_SPARSE_JOBS        [1] 1..64: sparse-row histogram workgroups per compute unit
+ *   GBT_TUNE_SPARSE_TILED       [0] 1: sparse-row histogram in id-range tiles even where all ids fit one workgroup's LDS */
 GBT_API int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream);
 GBT_API int32_t gbt_destroy(gbt_ctx *ctx);
 /* Text of the last error of this context ("" if none).  [host], owned by ctx. */
@@ -201,8 +224,8 @@ GBT_API int32_t gbt_sum_gpair(gbt_ctx *ctx, const int32_t *gq, const uint32_t *r
 
 /*
  * hist_out[f][b] = (sum gq_g, sum gq_h) over the node's rows r with
- * sym(r,f) = b; the missing symbol is not accumulated (Sec. 2.1: tree
- * construction as gradient summation into histograms).
+ * sym(r,f) = b; the missing symbol is not accumulated (Sec. 2.1; Alg. 1
+ * BuildPartialHistograms).
  *   packed, bits, n, F : the packed matrix [dev]
  *   B                  : bin stride (max_bins); every non-missing symbol < B
  *   row_idx [dev]      : the node's rows (uint32 ids < n), NULL = all n rows

@@ -38,18 +38,29 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gbt_oracle.c")
 _LIB = os.path.join(_HERE, "libgbt_oracle.so")
+_LIB_SAN = os.path.join(_HERE, "libgbt_oracle_san.so")
 _lib = None
 
 GAIN_FLOOR = 1e-6   # a split needs gain > max(gamma, GAIN_FLOOR)
 
 
-def build(force: bool = False) -> str:
-    """Compile gbt_oracle.c with gcc (no fast-math, no FMA contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile gbt_oracle.c with gcc (no fast-math, no FMA contraction).
+
+    sanitize: a second library, libgbt_oracle_san.so, built with -fsanitize=address,undefined (any undefined
+    behaviour aborts).  `lib()` loads it instead of the plain one when GBT_ORACLE_SANITIZE=1 is in the environment;
+    the process then also needs ASAN_OPTIONS=verify_asan_link_order=0:detect_leaks=0, since the interpreter itself
+    is not instrumented (memory the oracle allocates is checked exactly, the caller's numpy buffers are not).  The
+    whole CPU suite under it: GBT_ORACLE_SANITIZE=1 ASAN_OPTIONS=verify_asan_link_order=0:detect_leaks=0
+    python -m pytest tests -m "not gpu"."""
+    out = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        flags = (["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                  "-fno-omit-frame-pointer"] if sanitize else ["-O2"])
         subprocess.check_call(
-            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-             "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+            ["gcc", *flags, "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", out, _SRC, "-lm"])
+    return out
 
 
 class Split(C.Structure):
@@ -65,8 +76,8 @@ def _p(a, t):
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        sanitize = os.environ.get("GBT_ORACLE_SANITIZE", "0") not in ("", "0")
+        L = C.CDLL(build(sanitize=sanitize))
         L.gbto_cuts.restype = C.c_int32
         L.gbto_bits.restype = C.c_int32
         L.gbto_packed_words.restype = C.c_int64

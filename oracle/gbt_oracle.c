@@ -13,11 +13,11 @@
  *   gbto_unpack              log2(max_value) bits, packed with bitwise ops)
  *   gbto_gradients           Sec. 2.5, Eq. 1 and Eq. 2 (logistic g and h) and
  *                            the linear-regression objective named there
- *   gbto_hist                Sec. 2.1 / Alg. 1 "BuildPartialHistograms":
- *                            gradient summation into per-feature bin histograms
- *   gbto_eval_split          Alg. 1 "EvaluateSplit" / Sec. 2.3: a scan over
- *                            the histogram gives the gain of every (feature,
- *                            quantile) candidate
+ *   gbto_hist                Sec. 2.1 / Alg. 1 BuildPartialHistograms: per
+ *                            (feature, bin), the sums of g and of h over the
+ *                            node's rows
+ *   gbto_eval_split          Alg. 1 EvaluateSplit / Sec. 2.3: running sums
+ *                            over a feature's bins price every candidate
  *   gbto_partition           Alg. 1 "RepartitionInstances"
  *   gbto_predict_*           Sec. 2.4 (one instance at a time, trees in order)
  *

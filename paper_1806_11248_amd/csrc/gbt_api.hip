@@ -23,6 +23,11 @@ int32_t gbt_fail(gbt_ctx *ctx, int32_t code, const char *fmt, ...) {
     return code;
 }
 
+std::recursive_mutex &gbt_lds_mutex() {
+    static std::recursive_mutex m;
+    return m;
+}
+
 namespace {
 
 hipError_t part_static_address(int device, char **out);   // gbt_partition_static's scratch array, below

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <stdint.h>
 #include <stdio.h>
 
@@ -256,6 +257,19 @@ hipError_t gbt_launch_hist_fix(gbt_ctx *ctx, const uint32_t *packed, int64_t str
 // rounded pairs; sums (may be NULL) int64[gbt_hist8_max_jobs()][2] receives one pair of partial totals per
 // workgroup ([0, *n_jobs_out) are written; their sum is the total of all rows).  uniform_h: every
 // row's rounded h equals hq_uniform (the caller has checked that all fp32 h are equal).  hist_out must be zero.
+// A launch that asks for more dynamic LDS than the default limit of a launch first raises the kernel's limit.
+// That limit is one value per kernel for the whole process, so the raise and the launch it serves happen under
+// one process-wide lock: a concurrent launch of the same kernel from another context cannot lower it in between.
+// Declare the guard before the attribute call and keep it alive until the kernel has been launched.
+std::recursive_mutex &gbt_lds_mutex();
+struct GbtLdsGuard {
+    bool needed;
+    std::unique_lock<std::recursive_mutex> lock;
+    explicit GbtLdsGuard(size_t lds) : needed(lds > 64u * 1024u) {
+        if (needed) lock = std::unique_lock<std::recursive_mutex>(gbt_lds_mutex());
+    }
+};
+
 struct Hist8Pairs {
     const float *gpair;
     const int32_t *gq;

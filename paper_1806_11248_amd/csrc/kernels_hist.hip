@@ -1,5 +1,5 @@
-// BuildPartialHistograms (Alg. 1; Sec. 2.1 "gradient summation into
-// histograms") for gfx950.
+// BuildPartialHistograms (Alg. 1; Sec. 2.1) for gfx950: the pairs of a node's rows are added up per
+// (feature, bin).
 //
 // Each workgroup owns a private histogram of one feature tile in LDS, streams
 // its share of the node's rows and merges the non-zero bins into the node's
@@ -1008,12 +1008,11 @@ struct B8Args {
 };
 template <bool LIST, int NS, bool CHK, bool FIX>
 hipError_t launch_b8(const B8Args &a) {
-    static size_t configured = 0;
-    if (a.lds > configured) {
+    GbtLdsGuard lds_guard(a.lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute((const void *)hist_b8_kernel<LIST, NS, CHK, FIX>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
-        configured = a.lds;
     }
     hist_b8_kernel<LIST, NS, CHK, FIX><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bytes, a.n,
                                                                               a.B, a.Bp, a.missing, a.row_idx, a.gq,
@@ -1037,12 +1036,11 @@ template <bool LIST>
 hipError_t launch_generic(hipStream_t s, int n_jobs, int block, size_t lds, const uint32_t *packed, int64_t n_words, int bits,
                           int64_t stride_bits, int64_t n, int B, int Bp, uint32_t missing,
                           const uint32_t *row_idx, const int2 *gq, int64_t *pool, const HistJob *jobs) {
-    static size_t configured = 0;
-    if (lds > configured) {
+    GbtLdsGuard lds_guard(lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute((const void *)hist_generic_kernel<LIST>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = lds;
     }
     const uint32_t inv_bits = (uint32_t)((((uint64_t)1 << 32) + (uint32_t)bits - 1) / (uint32_t)bits);
     hist_generic_kernel<LIST><<<n_jobs, block, lds, s>>>(packed, n_words, bits, inv_bits, stride_bits, n, B, Bp,
@@ -1114,12 +1112,11 @@ struct PHArgs {
 };
 template <int NS, bool CHK, bool F32>
 hipError_t launch_ph_first_as(const PHArgs &a) {
-    static size_t configured = 0;
-    if (a.lds > configured) {
+    GbtLdsGuard lds_guard(a.lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute((const void *)part_hist_first_kernel<NS, CHK, F32>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
-        configured = a.lds;
     }
     part_hist_first_kernel<NS, CHK, F32><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
                                                                               a.sgf, a.shf, a.dst, a.ft, a.B, a.Bp, a.missing,
@@ -1132,18 +1129,24 @@ hipError_t launch_ph_first(const PHArgs &a) {
 }
 template <int NS, bool CHK>
 hipError_t launch_ph(const PHArgs &a) {
-    hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)a.lds);
-    if (e != hipSuccess) return e;
+    GbtLdsGuard lds_guard(a.lds);
+    if (lds_guard.needed) {
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+        if (e != hipSuccess) return e;
+    }
     part_hist_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
                                                                    a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
 }
 template <int NS, bool CHK>
 hipError_t launch_keep(const PHArgs &a) {
-    hipError_t e = hipFuncSetAttribute((const void *)hist_keep_kernel<NS, CHK>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)a.lds);
-    if (e != hipSuccess) return e;
+    GbtLdsGuard lds_guard(a.lds);
+    if (lds_guard.needed) {
+        hipError_t e = hipFuncSetAttribute((const void *)hist_keep_kernel<NS, CHK>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+        if (e != hipSuccess) return e;
+    }
     hist_keep_kernel<NS, CHK><<<a.n_spans, kKeepBlock, a.lds, a.s>>>(a.src, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
                                                                      a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
@@ -1201,12 +1204,11 @@ template <int NS, bool CHK>
 hipError_t launch_hist2(gbt_ctx *ctx, size_t lds, const uint32_t *records, int ft, int B, int Bp, uint32_t missing,
                         const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
                         unsigned long long *cursor, int64_t *pool) {
-    static size_t configured = 0;
-    if (lds > configured) {
+    GbtLdsGuard lds_guard(lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute((const void *)hist2_kernel<NS, CHK>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds);
         if (e != hipSuccess) return e;
-        configured = lds;
     }
     hist2_kernel<NS, CHK><<<n_spans, kH2Block, lds, ctx->stream>>>(records, ft, B, Bp, missing, jobs, n_jobs, rows_per_span,
                                                                    cursor, pool);

@@ -217,7 +217,8 @@ struct WArgs {
 };
 template <int BITS, bool LIST, bool UNI>
 hipError_t launch_w(const WArgs &a) {
-    if (a.lds > 64u * 1024u) {   // beyond the default limit of a launch: ask for it (the same value on every call for a shape)
+    GbtLdsGuard lds_guard(a.lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute((const void *)hist_bits_kernel<BITS, LIST, UNI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;

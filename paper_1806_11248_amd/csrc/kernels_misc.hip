@@ -807,12 +807,11 @@ hipError_t gbt_launch_predict_raw_batched(hipStream_t s, const gbt_batch_node *n
     if (n <= 0 || n_groups <= 0) return hipSuccess;
     const int XS = F | 1;
     const size_t lds = (((size_t)kBatchRows * XS * 4 + 15) & ~(size_t)15) + (size_t)cap_nodes * 16;
-    static size_t configured = 0;
-    if (lds > configured) {
+    GbtLdsGuard lds_guard(lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute((const void *)predict_raw_batched_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = lds;
     }
     const int64_t grid = (n + kBatchRows - 1) / kBatchRows;
     predict_raw_batched_kernel<<<(unsigned)grid, kBatchRows, lds, s>>>(nodes, wts, tree_off, tree_depth, group_end,
@@ -828,34 +827,31 @@ hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *tree
     const size_t lds = (size_t)max_nodes * sizeof(LdsNode);
     static_assert(sizeof(LdsNode) >= 16, "the register-window kernel stages 16 bytes per node");
     if (lds <= 96u * 1024u) {
-        static size_t configured = 0;
-        if (lds > configured) {
+        GbtLdsGuard lds_guard(lds);
+        if (lds_guard.needed) {
             hipError_t e = hipFuncSetAttribute((const void *)predict_lds_kernel,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
-            configured = lds;
         }
         const int rows_per_block = 256 * 16;
         const int64_t grid = (n + rows_per_block - 1) / rows_per_block;
         if (packed && compact_ok && (int64_t)F * bits <= 128) {
-            static size_t configured_w = 0;
-            if (lds > configured_w) {
+            GbtLdsGuard lds_guard_w(lds);
+            if (lds_guard_w.needed) {
                 hipError_t e = hipFuncSetAttribute((const void *)predict_window_kernel,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                 if (e != hipSuccess) return e;
-                configured_w = lds;
             }
             const int64_t n_words = (n * (int64_t)F * bits + 31) / 32 + 1;
             if (bits == 8 && F <= 16 && max_nodes <= (1 << 20)) {   // node ids fit the 20-bit field
-                static size_t configured_b = 0;
-                if (lds > configured_b) {
+                GbtLdsGuard lds_guard_b(lds);
+                if (lds_guard_b.needed) {
                     hipError_t e = hipFuncSetAttribute((const void *)predict_b8_kernel<true>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                     if (e == hipSuccess)
                         e = hipFuncSetAttribute((const void *)predict_b8_kernel<false>,
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                     if (e != hipSuccess) return e;
-                    configured_b = lds;
                 }
                 if (missing < 256u)
                     predict_b8_kernel<true><<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, packed, n_words, missing,

@@ -709,12 +709,11 @@ hipError_t gbt_launch_partition_fused(hipStream_t s, const GbtRows &src, const G
     else {
         const int cap = staged_tile_rows(dst.stride_bits);
         const size_t lds = ((((size_t)cap * (size_t)src.stride_bits + 31) >> 5) + 2 + (size_t)cap) * 4;
-        static size_t configured = 0;
-        if (lds > configured) {
+        GbtLdsGuard lds_guard(lds);
+        if (lds_guard.needed) {
             e = hipFuncSetAttribute((const void *)part_staged_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds);
             if (e != hipSuccess) return e;
-            configured = lds;
         }
         part_staged_kernel<<<total_tiles, kFBlock, lds, s>>>(src.sym, src.stride_bits, src.n_words, dst.sym_rw, SW,
                                                              row_bits, bits, missing, (const int2 *)src.gq,

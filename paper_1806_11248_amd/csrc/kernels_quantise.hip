@@ -583,11 +583,10 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
         offsets_kernel<<<1, 1, 0, s>>>(nullptr, F, n, seg_off, blk_off, chk_off, kScanChunk);
         if (n > 0 && F <= 64) {
             const size_t lds = (size_t)kTrNarrowRows * (F | 1) * 4;   // at most 65 KB
-            static size_t configured = 0;
-            if (lds > configured) {
+            GbtLdsGuard lds_guard(lds);
+            if (lds_guard.needed) {
                 Q_HIP(hipFuncSetAttribute((const void *)dense_keys_narrow_kernel,
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-                configured = lds;
             }
             dense_keys_narrow_kernel<<<(unsigned)((n + kTrNarrowRows - 1) / kTrNarrowRows), 256, lds, s>>>(X, n, F,
                                                                                                            keys_a);
@@ -651,11 +650,10 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
         if (dense) {
             const size_t cut_bytes = ((size_t)F * (B - 1) + (size_t)F) * 4;
             if (cut_bytes <= 60u * 1024u) {
-                static size_t configured = 0;
-                if (cut_bytes > configured) {
+                GbtLdsGuard lds_guard(cut_bytes);
+                if (lds_guard.needed) {
                     Q_HIP(hipFuncSetAttribute((const void *)bin_dense_kernel<true>,
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)cut_bytes));
-                    configured = cut_bytes;
                 }
                 bin_dense_kernel<true><<<grid_for(n * (int64_t)F, 4096, 8192), 256, cut_bytes, s>>>(
                     X, n * (int64_t)F, F, B, cuts, nb, (uint32_t)miss, sym, misc);

@@ -546,12 +546,10 @@ hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const ui
     const bool big = lds > 64u * 1024u;   // one workgroup per compute unit: make it a large one
     const void *fn = big ? (tiled ? (const void *)sparse_hist_kernel<1024, true> : (const void *)sparse_hist_kernel<1024, false>)
                          : (tiled ? (const void *)sparse_hist_kernel<512, true> : (const void *)sparse_hist_kernel<512, false>);
-    static size_t configured[4] = {0, 0, 0, 0};
-    const int slot = (big ? 2 : 0) + (tiled ? 1 : 0);
-    if (lds > configured[slot]) {
+    GbtLdsGuard lds_guard(lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured[slot] = lds;
     }
     const uint32_t *words = (const uint32_t *)ent;
     const int2 *gq2 = (const int2 *)gq;
@@ -583,12 +581,11 @@ hipError_t gbt_launch_sparse_walk(hipStream_t s, const char *ws, const DevTree *
     if (n <= 0 || n_trees <= 0) return hipSuccess;
     if ((size_t)max_nodes * sizeof(SpNode) + 4 * kWalkWords * 4 > 120u * 1024u) max_nodes = 0;   // nodes stay in HBM / L2
     const size_t lds = (size_t)max_nodes * sizeof(SpNode) + 4 * kWalkWords * 4;
-    static size_t configured = 0;
-    if (lds > configured) {
+    GbtLdsGuard lds_guard(lds);
+    if (lds_guard.needed) {
         hipError_t e = hipFuncSetAttribute((const void *)sparse_walk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds);
         if (e != hipSuccess) return e;
-        configured = lds;
     }
     const int rows_per_block = 2048;
     const int64_t grid = (n + rows_per_block - 1) / rows_per_block;

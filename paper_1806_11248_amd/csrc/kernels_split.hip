@@ -1,6 +1,5 @@
-// EvaluateSplit (Alg. 1; Sec. 2.3: "the split gain may be calculated for each
-// feature and each quantile by performing a scan over the gradient histogram ...
-// a parallel prefix sum").
+// EvaluateSplit (Alg. 1; Sec. 2.3): every (feature, bin) candidate of a node is priced from running
+// sums over the node's histogram, which a wave forms with a prefix scan.
 //
 // One workgroup per (node, feature chunk); each wave takes whole features.  With several
 // chunks per node the caller merges the chunks' records (largest gain, first chunk on ties:

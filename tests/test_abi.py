@@ -59,3 +59,18 @@ def test_struct_layouts_match_header():
     assert C.sizeof(g.binding.Tree) == 8 + 11 * 8
     # four 8-byte arrays over GBT_PROF_CLASSES = 8 classes, four over GBT_PROF_LEVELS = 18 depths
     assert C.sizeof(g.binding.Profile) == 8 * (4 * len(g.binding.PROF_CLASSES) + 4 * g.binding.PROF_LEVELS) == 8 * (4 * 8 + 4 * 18)
+
+
+def test_every_environment_switch_is_documented_in_the_header():
+    """gbt_create reads GBT_TUNE_* switches; each has to be listed, with its default, in include/gbt.h."""
+    import glob
+    import re
+    here = os.path.dirname(os.path.abspath(__file__))
+    root = os.path.dirname(here)
+    read = set()
+    for path in glob.glob(os.path.join(root, "paper_1806_11248_amd", "csrc", "*")):
+        read |= set(re.findall(r'getenv\("([A-Z0-9_]+)"\)', open(path).read()))
+    assert read, "no switches found: has the source moved?"
+    header = open(os.path.join(root, "include", "gbt.h")).read()
+    missing = sorted(v for v in read if not re.search(r"\b%s\b\s+\[" % v, header))
+    assert not missing, f"undocumented environment switches: {missing}"
