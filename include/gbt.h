@@ -162,6 +162,25 @@ GBT_API int32_t gbt_quantise(gbt_ctx *ctx, const float *X, const int64_t *indptr
                      int32_t *nb_out, uint16_t *sym_out, int32_t *max_value_out,
                      int32_t *missing_sym_out, void *workspace, size_t workspace_bytes);
 
+/*
+ * gbt_quantise and gbt_compress in one call (Sec. 2.1 -> Sec. 2.2): the same cuts, and the same bit stream as
+ * packing the symbols gbt_quantise would write, but the symbols go from the binning straight into the stream and
+ * the uint16 matrix is never stored.
+ *   packed_out [dev] uint32[packed_capacity_words].  The width is only known once the cuts are (the largest symbol
+ *             is max_f nb[f] if any element is missing, one less otherwise), and it never exceeds
+ *             gbt_bits(max_bins): capacity gbt_packed_words(n, F, gbt_bits(max_bins)) always suffices.  Too small
+ *             for the width found: GBT_ENOMEM, nothing packed.
+ *   bits_out  [host] the width; max_value_out, missing_sym_out, cuts_out, nb_out, the inputs and the workspace
+ *             (gbt_quantise_workspace_bytes) as for gbt_quantise.
+ * CSR input whose rows have too many features for 32 of them to fit the packing tile in LDS (F above ~760) is
+ * refused with GBT_EUNSUPPORTED: take the two calls.  Synchronises the stream.
+ */
+GBT_API int32_t gbt_quantise_packed(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
+                                    const float *values, int64_t n, int32_t F, int32_t max_bins, float *cuts_out,
+                                    int32_t *nb_out, uint32_t *packed_out, int64_t packed_capacity_words,
+                                    int32_t *bits_out, int32_t *max_value_out, int32_t *missing_sym_out,
+                                    void *workspace, size_t workspace_bytes);
+
 /* ---- Sec. 2.2 data compression ----------------------------------------- */
 
 /* Bits per element for a largest symbol max_value: its bit length, at least 1. */

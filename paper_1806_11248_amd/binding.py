@@ -23,7 +23,7 @@ OBJECTIVES = {"squared": 0, "logistic": 1}
 # every symbol include/gbt.h declares
 SYMBOLS = [
     "gbt_create", "gbt_destroy", "gbt_last_error", "gbt_version",
-    "gbt_quantise_workspace_bytes", "gbt_quantise", "gbt_bits", "gbt_packed_words", "gbt_compress",
+    "gbt_quantise_workspace_bytes", "gbt_quantise", "gbt_quantise_packed", "gbt_bits", "gbt_packed_words", "gbt_compress",
     "gbt_gradients", "gbt_gpair_fixed", "gbt_sum_gpair", "gbt_build_hist", "gbt_hist_subtract",
     "gbt_hist_export_f64", "gbt_eval_split", "gbt_partition_workspace_bytes", "gbt_partition",
     "gbt_partition_static",
@@ -280,6 +280,33 @@ class Context:
                                           C.byref(mv), C.byref(ms), _ptr(ws), ws.numel()))
         self._ws.pop("quantise", None)   # large and used once
         return cuts, nb, sym, mv.value, ms.value
+
+    def quantise_packed(self, X=None, csr=None, *, max_bins: int, n=None, F=None):
+        """Cuts and the packed matrix in one call (no symbol matrix in between).
+        Returns (cuts [F][max_bins-1], nb [F], packed int32 words, bits, max_value, missing_sym)."""
+        if X is not None:
+            _need(X, torch.float32, "X")
+            n, F = X.shape
+            n_values = n * F
+            args = (_ptr(X), None, None, None)
+        else:
+            indptr, indices, values = csr
+            _need(indptr, torch.int64, "indptr"); _need(indices, torch.int32, "indices")
+            _need(values, torch.float32, "values")
+            n_values = values.numel()
+            args = (None, _ptr(indptr), _ptr(indices), _ptr(values))
+        cuts = self.empty((F, max_bins - 1), torch.float32)
+        nb = self.empty((F,), torch.int32)
+        cap = packed_words(n, F, bits_for(max_bins))      # no symbol exceeds max_bins
+        packed = self.empty((cap,), torch.int32)
+        ws_bytes = self.lib.gbt_quantise_workspace_bytes(n, F, n_values, max_bins)
+        ws = self.workspace("quantise", ws_bytes)
+        mv, ms, b = C.c_int32(), C.c_int32(), C.c_int32()
+        self._check(self.lib.gbt_quantise_packed(self.h, *args, n, F, max_bins, _ptr(cuts), _ptr(nb), _ptr(packed),
+                                                 C.c_int64(cap), C.byref(b), C.byref(mv), C.byref(ms), _ptr(ws),
+                                                 ws.numel()))
+        self._ws.pop("quantise", None)   # large and used once
+        return cuts, nb, packed[:packed_words(n, F, b.value)], b.value, mv.value, ms.value
 
     # -- Sec. 2.2 ------------------------------------------------------------
     def compress(self, sym, max_value: int):

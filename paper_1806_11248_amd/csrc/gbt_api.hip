@@ -2335,34 +2335,58 @@ extern "C" size_t gbt_quantise_workspace_bytes(int64_t n, int32_t F, int64_t n_v
     return gbt_quantise_ws(n, F, n_values, max_bins);
 }
 
-extern "C" int32_t gbt_quantise(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
-                                const float *values, int64_t n, int32_t F, int32_t max_bins, float *cuts_out,
-                                int32_t *nb_out, uint16_t *sym_out, int32_t *max_value_out,
-                                int32_t *missing_sym_out, void *workspace, size_t workspace_bytes) {
-    if (!ctx) return GBT_EINVAL;
+namespace {
+int32_t quantise_impl(gbt_ctx *ctx, const char *who, const float *X, const int64_t *indptr, const int32_t *indices,
+                      const float *values, int64_t n, int32_t F, int32_t max_bins, float *cuts_out, int32_t *nb_out,
+                      uint16_t *sym_out, uint32_t *packed_out, int64_t packed_capacity_words, int32_t *bits_out,
+                      int32_t *max_value_out, int32_t *missing_sym_out, void *workspace, size_t workspace_bytes) {
     const bool dense = X != nullptr;
-    GBT_REQUIRE(ctx, dense != (indptr != nullptr), GBT_EINVAL, "give exactly one of X and (indptr, indices, values)");
-    GBT_REQUIRE(ctx, cuts_out && nb_out && sym_out && max_value_out && missing_sym_out && workspace, GBT_EINVAL,
-                "NULL argument");
-    GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) && F >= 1 && F <= (1 << 20), GBT_EINVAL, "bad shape");
-    GBT_REQUIRE(ctx, max_bins >= 2 && max_bins <= 4096, GBT_EINVAL, "max_bins = %d outside 2..4096", max_bins);
+    GBT_REQUIRE(ctx, dense != (indptr != nullptr), GBT_EINVAL, "%s: give exactly one of X and (indptr, indices, values)", who);
+    GBT_REQUIRE(ctx, cuts_out && nb_out && (sym_out || (packed_out && bits_out)) && max_value_out && missing_sym_out &&
+                         workspace, GBT_EINVAL, "%s: NULL argument", who);
+    GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) && F >= 1 && F <= (1 << 20), GBT_EINVAL, "%s: bad shape", who);
+    GBT_REQUIRE(ctx, max_bins >= 2 && max_bins <= 4096, GBT_EINVAL, "%s: max_bins = %d outside 2..4096", who, max_bins);
+    GBT_REQUIRE(ctx, packed_capacity_words >= 0, GBT_EINVAL, "%s: negative capacity", who);
     int64_t n_values = n * (int64_t)F;
     if (!dense) {
         // the number of stored values is the last row pointer
         GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), indptr + n, 8, hipMemcpyDeviceToHost, ctx->stream));
         GBT_SYNC(ctx);
         memcpy(&n_values, rb(ctx), 8);
-        GBT_REQUIRE(ctx, n_values >= 0 && n_values <= n * (int64_t)F, GBT_EINVAL, "indptr[n] = %lld out of range",
+        GBT_REQUIRE(ctx, n_values >= 0 && n_values <= n * (int64_t)F, GBT_EINVAL, "%s: indptr[n] = %lld out of range", who,
                     (long long)n_values);
         // (a matrix with nothing stored has nothing to point at: every value is missing)
-        GBT_REQUIRE(ctx, n_values == 0 || (indices && values), GBT_EINVAL, "CSR input needs indices and values");
+        GBT_REQUIRE(ctx, n_values == 0 || (indices && values), GBT_EINVAL, "%s: CSR input needs indices and values", who);
     }
     GBT_REQUIRE(ctx, workspace_bytes >= gbt_quantise_ws(n, F, n_values, max_bins), GBT_ENOMEM,
-                "workspace %zu < %zu bytes", workspace_bytes, gbt_quantise_ws(n, F, n_values, max_bins));
+                "%s: workspace %zu < %zu bytes", who, workspace_bytes, gbt_quantise_ws(n, F, n_values, max_bins));
     int32_t status = GBT_OK;
     hipError_t e = gbt_quantise_run(ctx, X, indptr, indices, values, n, F, n_values, max_bins, cuts_out, nb_out,
                                     sym_out, max_value_out, missing_sym_out, (char *)workspace, workspace_bytes,
-                                    &status);
-    if (e != hipSuccess) return gbt_fail(ctx, GBT_EHIP, "gbt_quantise: %s", hipGetErrorString(e));
+                                    &status, packed_out, packed_capacity_words, bits_out);
+    if (e != hipSuccess) return gbt_fail(ctx, GBT_EHIP, "%s: %s", who, hipGetErrorString(e));
     return status;
+}
+}  // namespace
+
+extern "C" int32_t gbt_quantise(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
+                                const float *values, int64_t n, int32_t F, int32_t max_bins, float *cuts_out,
+                                int32_t *nb_out, uint16_t *sym_out, int32_t *max_value_out,
+                                int32_t *missing_sym_out, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, sym_out, GBT_EINVAL, "gbt_quantise: NULL argument");
+    return quantise_impl(ctx, "gbt_quantise", X, indptr, indices, values, n, F, max_bins, cuts_out, nb_out, sym_out,
+                         nullptr, 0, nullptr, max_value_out, missing_sym_out, workspace, workspace_bytes);
+}
+
+extern "C" int32_t gbt_quantise_packed(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
+                                       const float *values, int64_t n, int32_t F, int32_t max_bins, float *cuts_out,
+                                       int32_t *nb_out, uint32_t *packed_out, int64_t packed_capacity_words,
+                                       int32_t *bits_out, int32_t *max_value_out, int32_t *missing_sym_out,
+                                       void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, packed_out && bits_out, GBT_EINVAL, "gbt_quantise_packed: NULL argument");
+    return quantise_impl(ctx, "gbt_quantise_packed", X, indptr, indices, values, n, F, max_bins, cuts_out, nb_out,
+                         nullptr, packed_out, packed_capacity_words, bits_out, max_value_out, missing_sym_out,
+                         workspace, workspace_bytes);
 }

@@ -411,5 +411,6 @@ constexpr uint32_t kHMask = (1u << kHShift) - 1u;
 hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
                             const float *values, int64_t n, int F, int64_t n_values, int B, float *cuts,
                             int32_t *nb, uint16_t *sym, int32_t *max_value, int32_t *missing_sym,
-                            char *ws, size_t ws_bytes, int32_t *status);
+                            char *ws, size_t ws_bytes, int32_t *status, uint32_t *packed = nullptr,
+                            int64_t packed_cap_words = 0, int32_t *bits_out = nullptr);
 size_t gbt_quantise_ws(int64_t n, int F, int64_t n_values, int B);

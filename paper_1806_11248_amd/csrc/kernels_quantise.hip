@@ -427,7 +427,8 @@ __device__ inline uint64_t upper_bound_wave(const uint32_t *a, uint64_t lo, uint
 __global__ __launch_bounds__(64) void cuts_kernel(const uint32_t *__restrict__ keys_a, const uint32_t *__restrict__ keys_b,
                                                   const uint32_t *__restrict__ seg_flags,
                                                   const uint64_t *__restrict__ seg_off, int F, int B,
-                                                  float *__restrict__ cuts, int32_t *__restrict__ nb) {
+                                                  float *__restrict__ cuts, int32_t *__restrict__ nb,
+                                                  uint32_t *__restrict__ present) {
     const int f = blockIdx.x, lane = threadIdx.x;
     if (f >= F) return;
     const uint32_t *v = ((seg_flags[f] & kSegInB) ? keys_b : keys_a) + seg_off[f];
@@ -436,6 +437,7 @@ __global__ __launch_bounds__(64) void cuts_kernel(const uint32_t *__restrict__ k
     for (int k = lane; k < B - 1; k += 64) c[k] = __uint_as_float(0x7f800000u);   // +inf
     // present values = keys below the missing key
     const uint64_t m = len == 0 ? 0 : upper_bound_wave(v, 0, len, kMissingKey - 1u, lane);
+    if (lane == 0) present[f] = (uint32_t)m;
     if (m == 0) {
         if (lane == 0) nb[f] = 1;
         return;
@@ -562,8 +564,130 @@ __global__ void bin_csr_kernel(const int64_t *__restrict__ indptr, const int32_t
     if ((threadIdx.x & 63) == 0) atomicMax(max_out, mx);
 }
 
+// ---- 4b. binning and packing in one pass (Sec. 2.1 -> Sec. 2.2) ------------------
+// The symbols of a tile of elements are binned into LDS and leave as words of the bit stream: the uint16 symbol
+// matrix never exists.  A tile holds a multiple of 32 elements, so it starts on a word boundary whatever the width;
+// one thread assembles one word from the LDS symbols that overlap it.
+constexpr int kPackTile = 4096;   // elements per tile of the dense form
+
+__device__ inline void pack_tile(const uint16_t *lsym, int tile_elems, int bits, uint32_t *out) {
+    const int nw = (tile_elems * bits + 31) >> 5;
+    for (int w = threadIdx.x; w < nw; w += 256) {
+        const int bit0 = w * 32;
+        uint32_t word = 0;
+        for (int e = bit0 / bits; e < tile_elems; ++e) {
+            const int pos = e * bits - bit0;   // may be negative for the first element
+            if (pos >= 32) break;
+            const uint32_t sv = lsym[e];
+            word |= pos >= 0 ? (sv << pos) : (sv >> (-pos));
+        }
+        out[w] = word;
+    }
+}
+
+template <bool LDS_CUTS>
+__global__ __launch_bounds__(256) void bin_pack_dense_kernel(const float *__restrict__ X, int64_t n_elems, int F, int B,
+                                                             const float *__restrict__ cuts,
+                                                             const int32_t *__restrict__ nb, uint32_t missing, int bits,
+                                                             uint32_t *__restrict__ packed, int64_t n_words) {
+    extern __shared__ float lcuts[];
+    int32_t *lnb = (int32_t *)(lcuts + (LDS_CUTS ? F * (B - 1) : 0));
+    __shared__ uint16_t lsym[kPackTile];
+    if (LDS_CUTS) {
+        for (int i = threadIdx.x; i < F * (B - 1); i += 256) lcuts[i] = cuts[i];
+        for (int i = threadIdx.x; i < F; i += 256) lnb[i] = nb[i];
+        __syncthreads();
+    }
+    const float *ct = LDS_CUTS ? lcuts : cuts;
+    const int32_t *nbt = LDS_CUTS ? lnb : nb;
+    const int64_t n_tiles = (n_elems + kPackTile - 1) / kPackTile;
+    const int step_f = 256 % F;
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int64_t e0 = t * kPackTile;
+        const int tile_elems = n_elems - e0 < kPackTile ? (int)(n_elems - e0) : kPackTile;
+        int f = (int)((e0 + threadIdx.x) % F);
+        float x[kPackTile / 256];
+#pragma unroll
+        for (int j = 0; j < kPackTile / 256; ++j) {
+            const int i = j * 256 + (int)threadIdx.x;
+            x[j] = i < tile_elems ? X[e0 + i] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < kPackTile / 256; ++j) {
+            const int i = j * 256 + (int)threadIdx.x;
+            if (i < tile_elems)
+                lsym[i] = (uint16_t)((x[j] != x[j]) ? missing : bin_of(ct + f * (B - 1), nbt[f] - 1, x[j]));
+            f += step_f;
+            f = f >= F ? f - F : f;
+        }
+        __syncthreads();
+        pack_tile(lsym, tile_elems, bits, packed + e0 / 32 * bits);   // kPackTile * bits / 32 words per tile
+        __syncthreads();
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) packed[n_words - 1] = 0;   // the pad word (Sec. 2.2 layout)
+}
+
+// CSR input: a tile of rows (a multiple of 32) is laid out in LDS as missing symbols, the stored values of those
+// rows (one contiguous piece of the CSR arrays) are binned into their places, and the tile is packed.
+__global__ __launch_bounds__(256) void bin_pack_csr_kernel(const int64_t *__restrict__ indptr,
+                                                           const int32_t *__restrict__ indices,
+                                                           const float *__restrict__ values, int64_t n, int64_t nnz,
+                                                           int F, int B, const float *__restrict__ cuts,
+                                                           const int32_t *__restrict__ nb, uint32_t missing, int bits,
+                                                           int tile_rows, uint32_t *__restrict__ packed,
+                                                           int64_t n_words) {
+    extern __shared__ uint16_t lrow[];                       // tile_rows * F symbols
+    int64_t *lptr = (int64_t *)(lrow + (((size_t)tile_rows * F + 3) & ~(size_t)3));   // tile_rows + 1 row pointers
+    const int64_t n_tiles = (n + tile_rows - 1) / tile_rows;
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int64_t r0 = t * tile_rows;
+        const int rows = n - r0 < tile_rows ? (int)(n - r0) : tile_rows;
+        for (int i = threadIdx.x; i < rows * F; i += 256) lrow[i] = (uint16_t)missing;
+        for (int i = threadIdx.x; i <= rows; i += 256) {
+            int64_t p = indptr[r0 + i];
+            p = p < 0 ? 0 : p;
+            lptr[i] = p > nnz ? nnz : p;
+        }
+        __syncthreads();
+        const int64_t a0 = lptr[0], b0 = lptr[rows];
+        for (int64_t i = a0 + threadIdx.x; i < b0; i += 256) {
+            int lo = 0, hi = rows;   // last row whose first entry is at or before i
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (lptr[mid] <= i) lo = mid; else hi = mid;
+            }
+            const int f = indices[i];
+            if (f < 0 || f >= F) continue;
+            const float x = values[i];
+            lrow[lo * F + f] = (uint16_t)((x != x) ? missing : bin_of(cuts + (int64_t)f * (B - 1), nb[f] - 1, x));
+        }
+        __syncthreads();
+        pack_tile(lrow, rows * F, bits, packed + (r0 * F) / 32 * bits);   // r0 * F is a multiple of 32
+        __syncthreads();
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) packed[n_words - 1] = 0;
+}
+
+// Does any element lack a value?  A row with fewer than F stored entries, or a stored NaN.
+__global__ void csr_any_missing_kernel(const int64_t *__restrict__ indptr, const float *__restrict__ values, int64_t n,
+                                       int64_t nnz, int F, uint32_t *__restrict__ flag) {
+    bool any = false;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t r = i0; r < n; r += stride) {
+        int64_t a = indptr[r], b = indptr[r + 1];
+        a = a < 0 ? 0 : a;
+        b = b > nnz ? nnz : b;
+        any |= (b - a) < F;
+    }
+    for (int64_t i = i0; i < nnz; i += stride) {
+        const float x = values[i];
+        any |= x != x;
+    }
+    if (__ballot(any) != 0 && (threadIdx.x & 63) == 0) atomicOr(flag, 1u);
+}
+
 struct QLayout {
-    size_t keys_a, keys_b, tile_hist, chunk_tot, seg_off, blk_off, chk_off, counts, cursor, seg_flags, misc, total;
+    size_t keys_a, keys_b, tile_hist, chunk_tot, seg_off, blk_off, chk_off, counts, cursor, seg_flags, present, misc, total;
     int64_t max_tiles, max_chunks;
 };
 QLayout q_layout(int64_t n, int F, int64_t n_values) {
@@ -582,6 +706,7 @@ QLayout q_layout(int64_t n, int F, int64_t n_values) {
     L.counts = o;    o += gbt_align((size_t)F * 4);
     L.cursor = o;    o += gbt_align((size_t)F * 4);
     L.seg_flags = o; o += gbt_align((size_t)F * 4);
+    L.present = o;   o += gbt_align((size_t)F * 4);
     L.misc = o;      o += 256;
     L.total = o;
     return L;
@@ -610,7 +735,8 @@ size_t gbt_quantise_ws(int64_t n, int F, int64_t n_values, int B) {
 hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr, const int32_t *indices,
                             const float *values, int64_t n, int F, int64_t n_values, int B, float *cuts,
                             int32_t *nb, uint16_t *sym, int32_t *max_value, int32_t *missing_sym, char *ws,
-                            size_t ws_bytes, int32_t *status) {
+                            size_t ws_bytes, int32_t *status, uint32_t *packed, int64_t packed_cap_words,
+                            int32_t *bits_out) {
     (void)ws_bytes;
     *status = GBT_OK;
     hipStream_t s = ctx->stream;
@@ -624,6 +750,7 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     uint32_t *counts = (uint32_t *)(ws + L.counts), *cursor = (uint32_t *)(ws + L.cursor);
     uint32_t *misc = (uint32_t *)(ws + L.misc);
     uint32_t *seg_flags = (uint32_t *)(ws + L.seg_flags);
+    uint32_t *present = (uint32_t *)(ws + L.present);
     const bool dense = X != nullptr;
 
     // 1. key segments
@@ -679,7 +806,7 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     Q_HIP(hipGetLastError());
 
     // 3. cuts
-    cuts_kernel<<<F, 64, 0, s>>>(keys_a, keys_b, seg_flags, seg_off, F, B, cuts, nb);
+    cuts_kernel<<<F, 64, 0, s>>>(keys_a, keys_b, seg_flags, seg_off, F, B, cuts, nb, present);
     Q_HIP(hipGetLastError());
     std::vector<int32_t> hnb((size_t)F);
     Q_HIP(hipMemcpyAsync(hnb.data(), nb, (size_t)F * 4, hipMemcpyDeviceToHost, s));
@@ -688,6 +815,73 @@ hipError_t gbt_quantise_run(gbt_ctx *ctx, const float *X, const int64_t *indptr,
     for (int f = 0; f < F; ++f) miss = hnb[f] > miss ? hnb[f] : miss;
     if (miss > 65535) {
         *status = gbt_fail(ctx, GBT_EUNSUPPORTED, "gbt_quantise: %d bins do not fit a 16-bit symbol", miss);
+        return hipSuccess;
+    }
+
+    if (packed) {
+        // 4b. symbols straight into the bit stream.  Its width follows from the largest symbol, which is known
+        //     without binning: the largest present value of a feature falls into its last bin, and the missing
+        //     symbol (max_f nb[f]) occurs iff some element has no value.
+        bool any_missing;
+        if (dense) {
+            std::vector<uint32_t> hp((size_t)F);
+            Q_HIP(hipMemcpyAsync(hp.data(), present, (size_t)F * 4, hipMemcpyDeviceToHost, s));
+            Q_HIP(hipStreamSynchronize(s));
+            uint64_t tot = 0;
+            for (int f = 0; f < F; ++f) tot += hp[f];
+            any_missing = tot < (uint64_t)n * (uint64_t)F;
+        } else {
+            Q_HIP(gbt_launch_fill_u64(s, (uint64_t *)misc, 0, 1));
+            if (n > 0)
+                csr_any_missing_kernel<<<grid_for(n > n_values ? n : n_values, 256 * 8, 4096), 256, 0, s>>>(
+                    indptr, values, n, n_values, F, misc);
+            Q_HIP(hipGetLastError());
+            Q_HIP(hipMemcpyAsync(ctx->pinned + GBT_STAGING_BYTES / 2, misc, 4, hipMemcpyDeviceToHost, s));
+            Q_HIP(hipStreamSynchronize(s));
+            uint32_t fl;
+            memcpy(&fl, ctx->pinned + GBT_STAGING_BYTES / 2, 4);
+            any_missing = fl != 0;
+        }
+        const int32_t mx = n == 0 ? 0 : (any_missing ? miss : miss - 1);
+        const int bits = gbt_bits((uint32_t)mx);
+        if (bits > GBT_MAX_BITS) {
+            *status = gbt_fail(ctx, GBT_EUNSUPPORTED, "gbt_quantise_packed: symbols need %d bits", bits);
+            return hipSuccess;
+        }
+        const int64_t n_words = gbt_packed_words(n, F, bits);
+        if (n_words > packed_cap_words) {
+            *status = gbt_fail(ctx, GBT_ENOMEM, "gbt_quantise_packed: %lld words needed for %d-bit symbols, %lld given",
+                               (long long)n_words, bits, (long long)packed_cap_words);
+            return hipSuccess;
+        }
+        const int64_t n_elems = n * (int64_t)F;
+        if (dense) {
+            const size_t cut_bytes = ((size_t)F * (B - 1) + (size_t)F) * 4;
+            const int grid = grid_for(n_elems, kPackTile, 8192);
+            if (cut_bytes <= 48u * 1024u)
+                bin_pack_dense_kernel<true><<<grid, 256, cut_bytes, s>>>(X, n_elems, F, B, cuts, nb, (uint32_t)miss, bits,
+                                                                         packed, n_words);
+            else
+                bin_pack_dense_kernel<false><<<grid, 256, 0, s>>>(X, n_elems, F, B, cuts, nb, (uint32_t)miss, bits,
+                                                                  packed, n_words);
+        } else {
+            int tile_rows = 256;
+            while (tile_rows >= 32 && (size_t)tile_rows * F * 2 + 8 + ((size_t)tile_rows + 1) * 8 > 48u * 1024u) tile_rows -= 32;
+            if (tile_rows < 32) {
+                *status = gbt_fail(ctx, GBT_EUNSUPPORTED, "gbt_quantise_packed: CSR rows of %d features do not fit the "
+                                   "packing tile; use gbt_quantise and gbt_compress", F);
+                return hipSuccess;
+            }
+            const size_t lds = (((size_t)tile_rows * F + 3) & ~(size_t)3) * 2 + ((size_t)tile_rows + 1) * 8;
+            bin_pack_csr_kernel<<<grid_for(n, tile_rows, 8192), 256, lds, s>>>(indptr, indices, values, n, n_values, F, B,
+                                                                             cuts, nb, (uint32_t)miss, bits, tile_rows,
+                                                                             packed, n_words);
+        }
+        Q_HIP(hipGetLastError());
+        Q_HIP(hipStreamSynchronize(s));
+        *max_value = mx;
+        *missing_sym = miss;
+        *bits_out = bits;
         return hipSuccess;
     }
 

@@ -99,6 +99,51 @@ def test_quantise_csr_with_nothing_stored(ctx, oracle):
     assert np.array_equal(sym.cpu().numpy(), o["sym"])
 
 
+# ------------------------------------------------- quantise + compress in one call --
+@pytest.mark.parametrize("n,F,B,nan", [(5000, 8, 16, True), (70_001, 13, 256, True), (9_000, 70, 64, True),
+                                       (300, 3, 256, False), (1, 2, 4, False), (4096, 1, 2, False), (4097, 5, 255, False),
+                                       (12_289, 31, 1000, True), (2_000, 600, 8, False)])
+def test_quantise_packed_dense(ctx, oracle, n, F, B, nan):
+    """Cuts and bit stream of the one-call form: equal to the oracle's cuts, symbols and packing, bit for bit, and to
+    gbt_quantise followed by gbt_compress; with and without missing values (the width depends on whether the
+    missing symbol occurs), tiles that end inside a word."""
+    X = _quantise_case(n + F, n, F, B) if nan else np.random.default_rng(n + F).standard_normal((n, F)).astype(np.float32)
+    _say(f"quantise+pack dense n={n} F={F} B={B} missing={nan}")
+    cuts, nb, packed, bits, mv, ms = ctx.quantise_packed(dev(X), max_bins=B)
+    o = oracle_prep(oracle, X, B)
+    assert np.array_equal(nb.cpu().numpy(), o["nb"])
+    assert np.array_equal(cuts.cpu().numpy(), o["cuts"])
+    assert (mv, ms, bits) == (o["max_value"], o["missing"], o["bits"])
+    assert np.array_equal(host_u32(packed), oracle.pack(o["sym"], o["bits"]))
+    _, _, sym, mv2, _ = ctx.quantise(dev(X), max_bins=B)
+    packed2, bits2 = ctx.compress(sym, mv2)
+    assert bits2 == bits and torch.equal(packed2, packed)
+
+
+@pytest.mark.parametrize("cfg,n,kw", [(3, 30_011, {}), (3, 257, {}), (2, 5_000, {})])
+def test_quantise_packed_csr(ctx, oracle, cfg, n, kw):
+    d = synth.make(cfg, n, **kw)
+    X = d["X"]
+    indptr, indices, values = synth.dense_to_csr(X)
+    _say(f"quantise+pack csr n={X.shape[0]} F={X.shape[1]} nnz={len(values)}")
+    cuts, nb, packed, bits, mv, ms = ctx.quantise_packed(csr=(dev(indptr), dev(indices), dev(values)), max_bins=256,
+                                                         n=X.shape[0], F=X.shape[1])
+    o = oracle_prep(oracle, X, 256)
+    assert np.array_equal(nb.cpu().numpy(), o["nb"]) and np.array_equal(cuts.cpu().numpy(), o["cuts"])
+    assert (mv, ms, bits) == (o["max_value"], o["missing"], o["bits"])
+    assert np.array_equal(host_u32(packed), oracle.pack(o["sym"], o["bits"]))
+
+
+def test_quantise_packed_refuses_what_it_cannot_do(ctx):
+    import paper_1806_11248_amd as g
+    n, F = 64, 1200          # CSR rows too wide for the packing tile
+    X = np.random.default_rng(0).standard_normal((n, F)).astype(np.float32)
+    indptr, indices, values = synth.dense_to_csr(X)
+    with pytest.raises(g.GbtError) as e:
+        ctx.quantise_packed(csr=(dev(indptr), dev(indices), dev(values)), max_bins=16, n=n, F=F)
+    assert e.value.code == g.binding.EUNSUPPORTED
+
+
 # ------------------------------------------------------------------- compress --
 @pytest.mark.parametrize("bits", list(range(1, 17)))
 def test_compress(ctx, oracle, bits):
