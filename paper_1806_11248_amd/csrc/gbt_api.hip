@@ -1567,13 +1567,21 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             // ---- BuildPartialHistograms for the smaller children (their rows are now one
             //      contiguous run of the working copy)
             const int32_t n_children = n_nodes - first_child;
-            gbt_prof_begin(ctx, GBT_PROF_CLEAR, (double)n_children * (double)hist_len * 8.0);
-            GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
-                                             (int64_t)n_children * hist_len));
-            gbt_prof_end(ctx);
             const bool uni_w = uniform_h && bits != 8 && !ctx->hist_runtime_bits;   // the kernels with a row-count form
             const int32_t hq_uniform = (int32_t)llrint((double)h_value * scale[1]);
             const uint32_t rpj = pick_rows_per_job(ctx, built_rows, gbt_histw_max_rows(uni_w), pl.n_ftiles, B);
+            // Jobs add into a histogram that must start at zero, except where a node is one row piece: its jobs
+            // store every bin of their tile.  (The sibling's histogram is stored bin by bin by the evaluation's
+            // subtraction.)  Deep levels consist of such nodes only, and there the fill is the larger part of the
+            // level: 2 MB per node for 2000 features x 64 bins.
+            bool all_stored = true;
+            for (const Built &b : built) all_stored = all_stored && b.len > 0 && b.len <= rpj;
+            if (!all_stored) {
+                gbt_prof_begin(ctx, GBT_PROF_CLEAR, (double)n_children * (double)hist_len * 8.0);
+                GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
+                                                 (int64_t)n_children * hist_len));
+                gbt_prof_end(ctx);
+            }
             for (const Built &b : built) add_hist_jobs(hjobs, b.off, b.begin, b.len, F, pl, rpj);
             const size_t per_launch = kUploadBytes / sizeof(HistJob);
             for (size_t j0 = 0; j0 < hjobs.size(); j0 += per_launch) {
