@@ -50,7 +50,9 @@ __device__ __forceinline__ void pkw_check(uint32_t side_addr, unsigned long long
     }
 }
 
-template <int BITS, bool LIST, bool UNI>
+// CHK = false: every value the BITS can hold is a bin (B > 2^BITS - 1 and no missing symbol among them), so a
+// symbol is only tested for lying in a live slot of the window.
+template <int BITS, bool LIST, bool UNI, bool CHK>
 __global__ __launch_bounds__(kHistBlock) void hist_bits_kernel(
     const uint32_t *__restrict__ packed, int64_t n_words, int64_t stride_bits, int64_t n, int B, int Bp,
     uint32_t missing, const uint32_t *__restrict__ row_idx, const int2 *__restrict__ gq,
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(kHistBlock) void hist_bits_kernel(
                                     sv = (W[wd] >> off) & MASK;
                                 else
                                     sv = __builtin_amdgcn_alignbit(W[wd < 3 ? wd + 1 : 3], W[wd], (uint32_t)off) & MASK;
-                                const bool ok = (tbase + j < ft) & (sv != missing) & (sv < (uint32_t)B);
+                                const bool ok = CHK ? (tbase + j < ft) & (sv != missing) & (sv < (uint32_t)B) : (tbase + j < ft);
                                 addr[jj] = ok ? tb8 + 8u * (uint32_t)(j * Bp) + (sv << 3) : my_trash;
                                 if (UNI) ldsw_add(addr[jj], addv);
                                 else old[jj] = ldsw_add_rtn(addr[jj], addv);
@@ -215,23 +217,29 @@ struct WArgs {
     const HistJob *jobs;
     int32_t hq_uniform;
 };
-template <int BITS, bool LIST, bool UNI>
+template <int BITS, bool LIST, bool UNI, bool CHK>
 hipError_t launch_w(const WArgs &a) {
     GbtLdsGuard lds_guard(a.lds);
     if (lds_guard.needed) {
-        hipError_t e = hipFuncSetAttribute((const void *)hist_bits_kernel<BITS, LIST, UNI>,
+        hipError_t e = hipFuncSetAttribute((const void *)hist_bits_kernel<BITS, LIST, UNI, CHK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
     }
-    hist_bits_kernel<BITS, LIST, UNI><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bits, a.n, a.B, a.Bp,
+    hist_bits_kernel<BITS, LIST, UNI, CHK><<<a.n_jobs, a.block, a.lds, a.s>>>(a.packed, a.n_words, a.stride_bits, a.n, a.B, a.Bp,
                                                                           a.missing, a.row_idx, a.gq, a.pool, a.jobs,
                                                                           a.hq_uniform);
     return hipGetLastError();
 }
+template <int BITS, bool CHK>
+hipError_t pick_w2(const WArgs &a, bool uni) {
+    if (a.row_idx) return uni ? launch_w<BITS, true, true, CHK>(a) : launch_w<BITS, true, false, CHK>(a);
+    return uni ? launch_w<BITS, false, true, CHK>(a) : launch_w<BITS, false, false, CHK>(a);
+}
 template <int BITS>
 hipError_t pick_w(const WArgs &a, bool uni) {
-    if (a.row_idx) return uni ? launch_w<BITS, true, true>(a) : launch_w<BITS, true, false>(a);
-    return uni ? launch_w<BITS, false, true>(a) : launch_w<BITS, false, false>(a);
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    const bool chk = a.missing <= MASK || (uint32_t)a.B <= MASK;   // some value of the field is not a bin
+    return chk ? pick_w2<BITS, true>(a, uni) : pick_w2<BITS, false>(a, uni);
 }
 }  // namespace
 
