@@ -198,8 +198,13 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
     eta = p["eta"]
     trees = []
 
-    def step(outputs=False):
+    one_call = not (given or sparse or lossguide)   # gbt_boost_round: the three steps of an iteration in one call
+
+    def step(outputs=False, three_calls=False):
         # outputs: also the final row order and each row's leaf (nothing in the boosting loop reads them)
+        if one_call and not outputs and not three_calls:
+            trees.append(ctx.boost_round(packed, bits, n, F, ms, nb, cuts, y, margin_in, margin, gp, params))
+            return
         if not given:
             ctx.gradients(p["objective"], margin_in, y, out=gp)
         if sparse:
@@ -248,6 +253,19 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
         step()
     torch.cuda.synchronize()
     ms_per_step_plain = (time.perf_counter() - t0) * 1e3 / steps
+    # ... as three calls (gbt_gradients, gbt_grow_tree, gbt_predict) where the step above is gbt_boost_round
+    ms_per_step_three = None
+    if one_call:
+        keep = None if single_tree else margin.clone()
+        step(three_calls=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(three_calls=True)
+        torch.cuda.synchronize()
+        ms_per_step_three = (time.perf_counter() - t0) * 1e3 / steps
+        if keep is not None:
+            margin.copy_(keep)
     # ... and when the caller also asks for the row order and the leaf of every row
     ms_per_step_outputs = None
     if headline and not a.no_outputs_leg:
@@ -319,6 +337,8 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
         "steps": steps, "ms_per_step": ms_per_step, "value": n * F / (ms_per_step * 1e-3),
         "seconds_per_tree": ms_per_step * 1e-3,
         "ms_per_step_without_event_records": ms_per_step_plain,
+        "step_entry_point": "gbt_boost_round" if one_call else "gbt_gradients + gbt_grow_tree* + gbt_predict*",
+        **({"ms_per_step_as_three_calls": ms_per_step_three} if ms_per_step_three is not None else {}),
         "device_ms_sum_per_step": sum(v["ms"] for v in prof.values()) / steps,
         "hist_root_ms": root_ms,
         "hist_root_rows_features_per_s": (n * F / (root_ms * 1e-3)) if root_ms > 0 else None,

@@ -118,6 +118,7 @@ typedef struct gbt_tree {
  *   GBT_TUNE_MOVE_MAX_WORDS     [8] 1..64: rows of more 32-bit words than this are listed (path 3), not moved
  *   GBT_TUNE_ORDER_ROWS         [1] 0: row ids travel with the rows (path 0) instead of the order being rebuilt from the tree
  *   GBT_TUNE_PART_NOMOVE        [2] 0..2: how many of the last levels of a depth-wise tree leave their rows in place (path 2)
+ *   GBT_TUNE_PART_CYCLE         [0] 1: above those levels rows are moved only every third level (two levels in place, then one move over three levels of splits; path 2)
  *   GBT_TUNE_HIST_FIX           [1] 0: gradient pairs are rounded to fixed point in a pass of their own, not in the root histogram launch
  *   GBT_TUNE_HIST8              [1] 0: the root histogram of byte symbols by the general byte-symbol kernel
  *   GBT_TUNE_HIST8_STAGGER      [64] 0..128: in 1/1024 of a job's length, how unequal the jobs of that launch are
@@ -423,6 +424,26 @@ GBT_API int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const
                       int64_t nnz, int32_t F, const int32_t *nb, const float *cuts, const float *gpair,
                       const gbt_params *params, gbt_tree *tree_out, uint32_t *row_idx_out,
                       int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
+
+/*
+ * One boosting iteration as the loop of Fig. 1 runs it (Sec. 2.5, Alg. 1, Sec. 2.4 in
+ * one call): gpair[r] = gradient pair of (margin_in[r], label[r]) under
+ * params->objective (as gbt_gradients), one depth-wise tree on those pairs (as
+ * gbt_grow_tree with row_idx_out = leaf_of_row_out = NULL), and
+ * margin_out[r] = margin_in[r] + params->eta * weight[leaf(r)] (as gbt_predict with
+ * that one tree on the packed matrix).  Results are those of the three calls, bit
+ * for bit; done together they share two passes: the gradient kernel also finds the
+ * bounds the fixed-point scales are chosen from, and the walk that updates the
+ * margins also counts the rows of the last level's children (tree_out->n_rows).
+ *   label, margin_in [dev] float[n]; margin_out [dev] float[n], may be margin_in
+ *   gpair [dev] float2[n]  receives the iteration's gradient pairs
+ *   workspace              gbt_grow_tree_workspace_bytes(n, F, bits, max_bins, max_depth)
+ * Other arguments and errors as for gbt_grow_tree.  Synchronises the stream.
+ */
+GBT_API int32_t gbt_boost_round(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                      int32_t missing_sym, const int32_t *nb, const float *cuts, const float *label,
+                      const float *margin_in, float *margin_out, float *gpair, const gbt_params *params,
+                      gbt_tree *tree_out, void *workspace, size_t workspace_bytes);
 
 /* ---- Sec. 2.4 prediction ------------------------------------------------ */
 

@@ -28,7 +28,8 @@ SYMBOLS = [
     "gbt_hist_export_f64", "gbt_eval_split", "gbt_partition_workspace_bytes", "gbt_partition",
     "gbt_partition_static",
     "gbt_grow_tree_workspace_bytes", "gbt_grow_tree_path", "gbt_grow_tree",
-    "gbt_grow_tree_lossguide_workspace_bytes", "gbt_grow_tree_lossguide", "gbt_predict_workspace_bytes", "gbt_predict",
+    "gbt_grow_tree_lossguide_workspace_bytes", "gbt_grow_tree_lossguide", "gbt_boost_round",
+    "gbt_predict_workspace_bytes", "gbt_predict",
     "gbt_profile_enable", "gbt_profile_read", "gbt_measure_stream_read",
     "gbt_sparse_capacity", "gbt_compress_sparse_workspace_bytes", "gbt_compress_sparse_count", "gbt_compress_sparse",
     "gbt_build_hist_sparse", "gbt_grow_tree_sparse_workspace_bytes", "gbt_grow_tree_sparse", "gbt_predict_sparse",
@@ -120,6 +121,7 @@ def load():
     L.gbt_partition_static.argtypes = [vp, vp, i32, i64, i32, vp, i64, i64, i32, i32, i32, i32, vp]
     L.gbt_grow_tree.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
     L.gbt_grow_tree_lossguide.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz]
+    L.gbt_boost_round.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz]
     L.gbt_predict.argtypes = [vp, vp, i32, vp, i32, i32, vp, i64, i32, f64, vp, vp, sz]
     L.gbt_sparse_capacity.argtypes = [i64]
     L.gbt_sparse_capacity.restype = i64
@@ -441,6 +443,22 @@ class Context:
                                            _ptr(ws), ws.numel()))
         t["n_nodes"] = int(ts.n_nodes)
         return t, row_idx, leaf
+
+    def boost_round(self, packed, bits, n, F, missing_sym, nb, cuts, label, margin_in, margin_out, gpair, params: Params):
+        """Gradients of margin_in, one depth-wise tree, margin_out = margin_in + eta * leaf weight.  Returns the tree."""
+        for t_, nm in ((label, "label"), (margin_in, "margin_in"), (margin_out, "margin_out"), (gpair, "gpair")):
+            _need(t_, torch.float32, nm)
+        t = new_tree(params.max_depth)
+        ts = _tree_struct(t)
+        ws_bytes = self.lib.gbt_grow_tree_workspace_bytes(n, F, bits, params.max_bins, params.max_depth)
+        if ws_bytes == 0:
+            raise GbtError(EINVAL, "gbt_grow_tree_workspace_bytes rejected the shape")
+        ws = self.workspace("grow", ws_bytes)
+        self._check(self.lib.gbt_boost_round(self.h, _ptr(packed), bits, n, F, missing_sym, _ptr(nb), _ptr(cuts),
+                                             _ptr(label), _ptr(margin_in), _ptr(margin_out), _ptr(gpair),
+                                             C.byref(params), C.byref(ts), _ptr(ws), ws.numel()))
+        t["n_nodes"] = int(ts.n_nodes)
+        return t
 
     def grow_tree_sparse(self, rowptr, ent, n, nnz, F, nb, cuts, gpair, params: Params, want_leaf=True,
                          want_rows=True):

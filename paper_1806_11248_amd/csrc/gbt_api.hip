@@ -243,6 +243,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (const char *e16 = getenv("GBT_TUNE_LOSSGUIDE_BATCH")) { int v = atoi(e16); if (v >= 1 && v <= 64) c->lossguide_batch = v; }
         c->part_nomove = 2;
         if (const char *e15 = getenv("GBT_TUNE_PART_NOMOVE")) { int v = atoi(e15); if (v >= 0 && v <= 2) c->part_nomove = v; }
+        c->part_cycle = 0;
+        if (const char *e17 = getenv("GBT_TUNE_PART_CYCLE")) c->part_cycle = atoi(e17) != 0;
         c->part_ids = 1;
         if (const char *e14 = getenv("GBT_TUNE_PART_IDS")) c->part_ids = atoi(e14) != 0;
         c->order_rows = 1;
@@ -434,10 +436,13 @@ extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *m
 // ------------------------------------------------------- fixed-point gpair --
 // The scales alone (one pass for the largest |g| and h; synchronises).
 // uniform_h (may be NULL): receives 1 and the common value when every row has the same |h| (n >= 1), else 0.
+// bounds_dev (may be NULL): the four words gbt_launch_absmax would find, already on the device (left there by
+// gbt_launch_gradients when the same call made the pairs)
 static int32_t gpair_scale_impl(gbt_ctx *ctx, const float *gpair, int64_t n, double *scale, void *ws,
-                                int *uniform_h = nullptr, float *h_value = nullptr) {
-    GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws, 16, hipMemcpyDeviceToHost, ctx->stream));
+                                int *uniform_h = nullptr, float *h_value = nullptr, const uint32_t *bounds_dev = nullptr) {
+    if (!bounds_dev) GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), bounds_dev ? (const void *)bounds_dev : (const void *)ws, 16,
+                                hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
     uint32_t bits2[4];
     memcpy(bits2, rb(ctx), 16);
@@ -776,7 +781,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
 namespace {
 
 struct GrowLayout {
-    size_t tree_stage, tree_stage_bytes, gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, jobs, scratch, order, rank_tbl, total;
+    size_t tree_stage, tree_stage_bytes, gq, wsym[2], wgq[2], wid[2], masks, tile_left, n_left, state, pool, eval_nodes, jobs, scratch, order, rank_tbl, node_rows, total;
     int64_t hist_nodes, level_nodes, tiles, w_words;
     int sw;   // 32-bit words per row of the working copies
 };
@@ -819,6 +824,8 @@ GrowLayout grow_layout_nodes(int64_t n, int F, int bits, int B, int64_t hist_nod
     // row ids in leaf order after a growth that did not follow the rows
     L.order = o;      o += gbt_order_ws(n);
     L.rank_tbl = o;   o += gbt_align(cap_nodes * 4);
+    // one row counter per node, a 128-byte line each, for the walk that also counts (trees small enough for it)
+    L.node_rows = o;  o += gbt_align(std::min<size_t>(cap_nodes, 8192) * kNodeRowsStride * 4);
     L.total = o;
     return L;
 }
@@ -900,7 +907,8 @@ struct SparseRowsArg {   // rows in the sparse form instead of packed / X
 static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                             int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
                             float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes,
-                            const SparseRowsArg *sparse = nullptr, bool own_span = false);
+                            const SparseRowsArg *sparse = nullptr, bool own_span = false, uint32_t *node_rows = nullptr,
+                            const float *margin_src = nullptr);
 
 // Alg. 1 under either policy of Sec. 2.3.  Growth proceeds in rounds: the nodes created by the round
 // before are evaluated; depth-wise then splits every one of them that may split, loss-guided only
@@ -908,7 +916,12 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
 static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
                          int32_t missing_sym, const int32_t *nb, const float *cuts, const float *gpair,
                          const gbt_params *params, int policy, int32_t max_leaves, gbt_tree *tree,
-                         uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes) {
+                         uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes,
+                         float *margin_update = nullptr, const float *margin_src = nullptr,
+                         const uint32_t *bounds_dev = nullptr) {
+    // margin_update (may be NULL): margin_update[r] = margin_src[r] + eta * (weight of r's leaf), by a walk of the
+    // finished tree (margin_src NULL: margin_update itself)
+    // bounds_dev (may be NULL): see gpair_scale_impl
     if (!ctx) return GBT_EINVAL;
     int32_t st = check_matrix(ctx, packed, bits, n, F);
     if (st != GBT_OK) return st;
@@ -989,11 +1002,17 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     double scale[2];
     int64_t *sums_dev = (int64_t *)(ws + L.scratch + 256);
     const bool root_may_split = max_depth > 0 && (!lossguide || max_leaves > 1);
+    // With a margin to update the finished tree is walked over all rows anyway; that walk can count the rows of
+    // every node, so the children of the last level (leaves, of which only the row counts are wanted) need no
+    // counting pass of their own.
+    const bool defer_counts = margin_update && !tracked && !leaf_of_row_out && !lossguide && (path == 1 || path == 2) &&
+                              cap <= 8192 && gbt_predict_counts_ok(true, bits, F, (int)cap, true);
+    std::vector<int32_t> deferred_children;
     const bool fix_in_hist = ctx->hist_fix && root_may_split && gbt_hist_fix_ok(bits, row_bits, pl.ft, pl.n_ftiles);
     int uniform_h = 0;
     float h_value = 0.0f;
     gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (fix_in_hist ? 8.0 : 24.0));
-    st = gpair_scale_impl(ctx, gpair, n, scale, ws + L.scratch, &uniform_h, &h_value);
+    st = gpair_scale_impl(ctx, gpair, n, scale, ws + L.scratch, &uniform_h, &h_value, bounds_dev);
     if (st == GBT_OK && !fix_in_hist) {
         hipError_t e = gbt_launch_to_fixed(s, gpair, n, scale[0], scale[1], gq, sums_dev);
         if (e != hipSuccess) st = gbt_fail(ctx, GBT_EHIP, "gbt_launch_to_fixed: %s", hipGetErrorString(e));
@@ -1090,6 +1109,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     std::vector<UnmovedSeg> unmoved;
     std::vector<CountJob> cjobs;
     std::vector<Hist2Job> h2jobs;
+    std::vector<Move3Job> m3jobs;
+    std::vector<PartJob> kjobs;        // histogram jobs over the built children's records behind a three-level move
     std::vector<int> job_of;           // sel node -> its segment's job (count and two-histogram passes)
     uint32_t h2_spans = 0;
     int64_t h2_rows = 0;
@@ -1229,7 +1250,12 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             child_depth < max_depth && (!lossguide || n_leaves + 1 < max_leaves);
         const bool unordered = path == 1 || path == 2;
         const bool fused = children_need_hist && unordered;
-        const bool with_hist = children_need_hist && path == 2;
+        const bool in_place = sel_nodes[0].virt >= 0;   // this level's nodes were not moved when they were made
+        // Rows that have stayed in place for two levels (their nodes are grandchildren of the segment they lie in) are
+        // put in order again by a pass of its own, without a histogram: one child of each is then built from its
+        // contiguous records
+        const bool move3 = children_need_hist && path == 2 && in_place && sel_nodes[0].vpos >= 3;
+        const bool with_hist = children_need_hist && path == 2 && !move3;
         // Depth-wise, the last level that needs histograms: its children's children are leaves, of which only
         // the row counts are wanted.  The pass then builds the histograms and counts without moving a row,
         // and the counts one level down come from a two-level count over the parents' segments.
@@ -1237,10 +1263,15 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         // TWO histograms per workgroup (one for each of a segment's two children): the nodes of depth
         // max_depth - 3 are then the last whose rows were moved into place, and the leaves are counted over
         // three levels of splits.
-        const bool in_place = sel_nodes[0].virt >= 0;   // this level's nodes were not moved when they were made
+        // Further up the same three passes repeat (GBT_TUNE_PART_CYCLE): keep, keep again with two histograms, move
+        // three levels at once -- 20 + 20 + 40 (+ the built children's 20 * 1/2) bytes per row and three levels
+        // instead of 3 * 40 -- timed so that a cycle ends where the last two in-place levels begin.
+        const int levels_after = (max_depth - 1) - child_depth;   // histogram levels below this one
+        const bool cycle_start = ctx->part_cycle && ctx->part_nomove >= 2 && levels_after >= 4 && levels_after % 3 == 1;
         const bool nomove = with_hist && !lossguide && !in_place && ctx->part_nomove &&
                             (child_depth == max_depth - 1 ||
-                             (ctx->part_nomove >= 2 && child_depth == max_depth - 2 && wcur != 2 && gbt_hist2_ok(ctx, F, B)));
+                             (ctx->part_nomove >= 2 && (child_depth == max_depth - 2 || cycle_start) && wcur != 2 &&
+                              gbt_hist2_ok(ctx, F, B)));
         const bool nomove2 = with_hist && in_place;     // (their heap positions are 1 and 2)
         const bool two_level = !children_need_hist && in_place;
         const int count_levels = two_level && sel_nodes[0].vpos >= 3 ? 2 : 1;
@@ -1294,7 +1325,10 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 unmoved[(size_t)sel_nodes[k].virt].set(sel_nodes[k].vpos, sel_splits[k]);
             }
         }
-        if (two_level) {
+        const bool deferred = defer_counts && !children_need_hist;   // nl_of stays 0: see the walk at the end
+        if (deferred) {
+            // nothing is launched for these nodes
+        } else if (two_level) {
             cjobs.clear();
             uint32_t ctiles = 0;
             const uint32_t ct = (uint32_t)gbt_count2_tile();
@@ -1340,6 +1374,59 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             for (size_t k = 0; k < sel_nodes.size(); ++k)
                 nl_of[k] = count_levels == 2 ? cnt[4 * job_of[k] + (sel_nodes[k].vpos - 3)]
                                              : cnt[2 * job_of[k] + (sel_nodes[k].vpos - 1)];
+        } else if (move3) {
+            // one job per segment: the three levels of splits below it and where its grandchildren's rows go
+            GBT_REQUIRE(ctx, wcur != 2, GBT_EHIP, "internal: rows kept in the caller's matrix for two levels");
+            m3jobs.clear();
+            uint32_t m3_spans = 0;
+            double m3_rows = 0;
+            const uint32_t m3_span_rows = 4u * (uint32_t)gbt_move3_tile();
+            for (size_t k = 0; k < sel_nodes.size(); ++k) {
+                if (k > 0 && job_of[k] == job_of[k - 1]) continue;
+                const UnmovedSeg &u = unmoved[(size_t)sel_nodes[k].virt];
+                Move3Job mj{};
+                mj.seg_begin = u.begin;
+                mj.seg_len = u.len;
+                mj.tile_begin = m3_spans;
+                mj.n_tiles = (u.len + m3_span_rows - 1) / m3_span_rows;
+                m3_spans += mj.n_tiles;
+                m3_rows += u.len;
+                m3jobs.push_back(mj);
+            }
+            for (size_t k = 0; k < sel_nodes.size(); ++k) {   // (after every split of the level has been noted in its segment)
+                const UnmovedSeg &u = unmoved[(size_t)sel_nodes[k].virt];
+                Move3Job &mj = m3jobs[(size_t)job_of[k]];
+                memcpy(mj.feature, u.feature, sizeof mj.feature);
+                memcpy(mj.bin, u.bin, sizeof mj.bin);
+                memcpy(mj.default_left, u.default_left, sizeof mj.default_left);
+                memcpy(mj.has, u.has, sizeof mj.has);
+                const int gch = sel_nodes[k].vpos - 3;
+                GBT_REQUIRE(ctx, gch >= 0 && gch < 4, GBT_EHIP, "internal: heap position %d", sel_nodes[k].vpos);
+                mj.node_begin[gch] = sel_nodes[k].begin;
+                mj.node_len[gch] = sel_nodes[k].len;
+            }
+            GBT_REQUIRE(ctx, m3jobs.size() * sizeof(Move3Job) <= kUploadBytes && 4 * (int64_t)m3jobs.size() <= L.level_nodes &&
+                                 m3jobs.size() * 32 <= kSplitRb,
+                        GBT_EUNSUPPORTED, "level too wide");
+            st = upload(ctx, m3jobs.data(), m3jobs.size() * sizeof(Move3Job), ws + L.jobs);
+            if (st != GBT_OK) return st;
+            const double rec_bytes3 = 4.0 * gbt_part_hist_record_words(F);
+            gbt_prof_begin(ctx, GBT_PROF_PARTITION, m3_rows * 2.0 * rec_bytes3, m3_rows * (8.0 + bits / 8.0));
+            GBT_HIP(ctx, gbt_launch_move3(ctx, W[wcur].sym, W[wnext].sym_rw, n, F, (uint32_t)missing_sym,
+                                          (const Move3Job *)(ws + L.jobs), (int)m3jobs.size(), (int)m3_spans, m3_span_rows,
+                                          (unsigned long long *)(ws + L.state), cursors_zero));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, m3jobs.size() * 32, hipMemcpyDeviceToHost, s));
+            cursors_zero = false;
+            gbt_prof_end(ctx);
+            GBT_SYNC(ctx);
+            const unsigned long long *cur64 = (const unsigned long long *)rb(ctx);
+            for (size_t k = 0; k < sel_nodes.size(); ++k) {
+                const unsigned long long c = cur64[4 * (size_t)job_of[k] + (size_t)(sel_nodes[k].vpos - 3)];
+                const uint32_t lefts = (uint32_t)(c & 0xffffffffull), rights = (uint32_t)(c >> 32);
+                GBT_REQUIRE(ctx, (uint64_t)lefts + rights == sel_nodes[k].len, GBT_EHIP,
+                            "internal: node %d holds %u rows, %u + %u were moved", sel_nodes[k].id, sel_nodes[k].len, lefts, rights);
+                nl_of[k] = lefts;
+            }
         } else {
             // the three-launch form keeps ballots and counts per tile in the workspace
             GBT_REQUIRE(ctx, fused || (int64_t)tile_cursor <= L.tiles, GBT_ENOMEM, "internal: tile count");
@@ -1509,6 +1596,10 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
             HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, nd.depth + 1, child_buf};
             HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, nd.depth + 1, child_buf};
+            if (deferred) {   // their row counts (0 and everything, for now) come from the walk at the end
+                deferred_children.push_back(lc.id);
+                deferred_children.push_back(rc.id);
+            }
             if (nomove) {   // a new segment of rows that stay in place: the children are its heap positions 1 and 2
                 UnmovedSeg u{};
                 u.begin = nd.begin;
@@ -1563,7 +1654,49 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         if (with_hist)   // the pass also built these children's histograms: rows * (symbols + pair + row id)
             gbt_prof_patch(ctx, pass_span_of_round, pass_alg_of_round + (double)built_rows * ((double)row_bits / 8.0 + 12.0),
                            (double)built_rows * F);
-        if (children_need_hist && !with_hist) {
+        if (move3) {
+            // ---- BuildPartialHistograms for the smaller children from their records, now contiguous: the pass
+            //      that keeps rows in place, under a split that takes every row
+            if ((int64_t)n_nodes > pool_zero_end) {
+                const int32_t n_children = n_nodes - first_child;
+                gbt_prof_begin(ctx, GBT_PROF_CLEAR, (double)n_children * (double)hist_len * 8.0);
+                GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(pool + (int64_t)first_child * hist_len), 0,
+                                                 (int64_t)n_children * hist_len));
+                gbt_prof_end(ctx);
+            }
+            const uint32_t t = (uint32_t)gbt_part_hist_tile();
+            const double want = (double)built_rows / ((double)ctx->num_cu * ctx->hist_jobs_per_cu);
+            const uint32_t ktile = (uint32_t)std::min<double>(std::max<double>(std::ceil(want / t), 4.0), (double)((1u << 21) / t)) * t;
+            kjobs.clear();
+            uint32_t kspans = 0;
+            for (const Built &b : built) {
+                if (b.len == 0) continue;   // its histogram stays zero
+                PartJob j{};
+                j.seg_begin = b.begin;
+                j.seg_len = b.len;
+                j.feature = 0;
+                j.bin = 255u;             // every byte symbol goes left,
+                j.default_left = 1u;      // a missing one as well,
+                j.pad = 1u;               // and the left side is the one added up
+                j.tile_begin = kspans;
+                j.n_tiles = (b.len + ktile - 1) / ktile;
+                j.hist_off = b.off;
+                kspans += j.n_tiles;
+                kjobs.push_back(j);
+            }
+            GBT_REQUIRE(ctx, kjobs.size() * sizeof(PartJob) <= kUploadBytes && (int64_t)kjobs.size() <= L.level_nodes,
+                        GBT_EUNSUPPORTED, "level too wide");
+            if (!kjobs.empty()) {
+                st = upload(ctx, kjobs.data(), kjobs.size() * sizeof(PartJob), ws + L.jobs);
+                if (st != GBT_OK) return st;
+                gbt_prof_begin(ctx, GBT_PROF_HIST_NODE, (double)built_rows * 4.0 * gbt_part_hist_record_words(F),
+                               (double)built_rows * ((double)row_bits / 8.0 + 8.0), child_depth, (double)built_rows * F);
+                GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq, W[wnext].sym, nullptr, F, B,
+                                                  (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs), (int)kjobs.size(),
+                                                  (int)kspans, ktile, (unsigned long long *)(ws + L.state), pool, false));
+                gbt_prof_end(ctx);
+            }
+        } else if (children_need_hist && !with_hist) {
             // ---- BuildPartialHistograms for the smaller children (their rows are now one
             //      contiguous run of the working copy)
             const int32_t n_children = n_nodes - first_child;
@@ -1608,8 +1741,28 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     // whatever is still waiting when nothing splits any more is a leaf
     for (const HNode &nd : level) leaves.push_back(LeafSeg{nd.begin, (uint32_t)nd.id, (uint32_t)nd.buf, nd.len});
     const int32_t n_tree = lossguide ? n_logical : n_nodes;   // nodes of the caller's tree
+    // margin_update: one walk of the finished tree over the packed matrix adds eta * leaf weight to every row's
+    // margin, and counts the rows of the nodes whose counting was left to it
+    auto update_margin = [&]() -> int32_t {
+        if (!margin_update) return GBT_OK;
+        tree->n_nodes = n_tree;
+        uint32_t *node_rows = deferred_children.empty() ? nullptr : (uint32_t *)(ws + L.node_rows);
+        if (node_rows) GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)node_rows, 0, (int64_t)n_tree * kNodeRowsStride / 2));
+        gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (row_bits / 8.0 + 8.0));
+        const int32_t st2 = predict_impl(ctx, tree, 1, packed, bits, missing_sym, nullptr, n, F, params->eta, margin_update,
+                                         nullptr, ws + L.tree_stage, L.tree_stage_bytes, nullptr, false, node_rows, margin_src);
+        gbt_prof_end(ctx);
+        if (st2 != GBT_OK || !node_rows) return st2;
+        std::vector<uint32_t> counts((size_t)n_tree * kNodeRowsStride);
+        GBT_HIP(ctx, hipMemcpyAsync(counts.data(), node_rows, counts.size() * 4, hipMemcpyDeviceToHost, s));
+        GBT_SYNC(ctx);
+        for (const int32_t id : deferred_children) tree->n_rows[id] = (int64_t)counts[(size_t)id * kNodeRowsStride];
+        return GBT_OK;
+    };
     if (!tracked || path == 1 || path == 2 || lossguide) {
         tree->n_nodes = n_tree;
+        st = update_margin();
+        if (st != GBT_OK) return st;
         // the rows were not followed: one walk of the finished tree over the matrix names each row's leaf
         int32_t *leaf_ids = leaf_of_row_out ? leaf_of_row_out : (int32_t *)W[0].id_rw;
         if (leaf_of_row_out || tracked) {
@@ -1663,7 +1816,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     gbt_prof_end(ctx);
     GBT_SYNC(ctx);
     tree->n_nodes = n_nodes;
-    return GBT_OK;
+    return update_margin();
 }
 
 extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
@@ -1672,6 +1825,29 @@ extern "C" int32_t gbt_grow_tree(gbt_ctx *ctx, const uint32_t *packed, int32_t b
                                  int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes) {
     return grow_impl(ctx, packed, bits, n, F, missing_sym, nb, cuts, gpair, params, GBT_POLICY_DEPTHWISE, 0, tree,
                      row_idx_out, leaf_of_row_out, workspace, workspace_bytes);
+}
+
+// One boosting iteration (Fig. 1): gradient pairs of the current margins, one depth-wise tree, margins updated.
+// The three steps share what each of them finds on its way: the gradient kernel leaves the bounds the scale search
+// needs, and the walk that updates the margins counts the rows of the last level's children.
+extern "C" int32_t gbt_boost_round(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int64_t n, int32_t F,
+                                   int32_t missing_sym, const int32_t *nb, const float *cuts, const float *label,
+                                   const float *margin_in, float *margin_out, float *gpair, const gbt_params *params,
+                                   gbt_tree *tree, void *workspace, size_t workspace_bytes) {
+    if (!ctx) return GBT_EINVAL;
+    GBT_REQUIRE(ctx, params && label && margin_in && margin_out && gpair && workspace, GBT_EINVAL, "NULL argument");
+    GBT_REQUIRE(ctx, params->objective == GBT_OBJ_SQUARED || params->objective == GBT_OBJ_LOGISTIC, GBT_EINVAL,
+                "unknown objective %d", params->objective);
+    GBT_REQUIRE(ctx, n >= 1 && F >= 1 && bits >= 1 && bits <= GBT_MAX_BITS && params->max_bins >= 2 &&
+                         params->max_depth >= 0 && params->max_depth <= kMaxDepth, GBT_EINVAL, "bad shape");
+    const GrowLayout L = grow_layout(n, F, bits, params->max_bins, params->max_depth);
+    GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
+    uint32_t *bounds = (uint32_t *)((char *)workspace + L.scratch + 1024);
+    gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 16.0);
+    GBT_HIP(ctx, gbt_launch_gradients(ctx->stream, params->objective, margin_in, label, n, gpair, bounds));
+    gbt_prof_end(ctx);
+    return grow_impl(ctx, packed, bits, n, F, missing_sym, nb, cuts, gpair, params, GBT_POLICY_DEPTHWISE, 0, tree,
+                     nullptr, nullptr, workspace, workspace_bytes, margin_out, margin_in, bounds);
 }
 
 extern "C" size_t gbt_grow_tree_lossguide_workspace_bytes(int64_t n, int32_t F, int32_t bits, int32_t max_bins,
@@ -1734,7 +1910,9 @@ extern "C" size_t gbt_predict_workspace_bytes(const gbt_tree *trees, int32_t n_t
 static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
                             int32_t bits, int32_t missing_sym, const float *X, int64_t n, int32_t F, double eta,
                             float *margin, int32_t *leaf_out, void *workspace, size_t workspace_bytes,
-                            const SparseRowsArg *sparse, bool own_span) {
+                            const SparseRowsArg *sparse, bool own_span, uint32_t *node_rows, const float *margin_src) {
+    // node_rows: one tree over packed symbols; the walk also counts the rows per node (gbt_launch_predict)
+    // margin_src (one tree, margin != NULL): margin[r] = margin_src[r] + eta * weight instead of margin[r] += ...
     // own_span: the walk is a profile span of its own (class "other"); callers inside a span pass false
     GBT_REQUIRE(ctx, trees && (margin || leaf_out) && workspace, GBT_EINVAL, "NULL argument");
     GBT_REQUIRE(ctx, sparse || (packed != nullptr) != (X != nullptr), GBT_EINVAL, "give exactly one of packed and X");
@@ -1872,10 +2050,18 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
         if (own_span) gbt_prof_end(ctx);
         return GBT_OK;
     }
+    if (margin_src == margin) margin_src = nullptr;
+    if (margin_src) {
+        GBT_REQUIRE(ctx, n_trees == 1 && margin && !leaf_out && !sparse, GBT_EINVAL, "internal: margin_src");
+        if (!gbt_predict_counts_ok(packed != nullptr, bits, F, max_nodes, compact_ok)) {   // no kernel form reads it: copy first
+            GBT_HIP(ctx, hipMemcpyAsync(margin, margin_src, (size_t)n * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+            margin_src = nullptr;
+        }
+    }
     if (own_span) gbt_prof_begin(ctx, GBT_PROF_OTHER, 0.0);
     GBT_HIP(ctx, gbt_launch_predict(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees, packed,
                                     bits, (uint32_t)missing_sym, X, n, F, eta, margin, leaf_out, max_nodes,
-                                    compact_ok));
+                                    compact_ok, node_rows, margin_src));
     if (own_span) gbt_prof_end(ctx);
     return GBT_OK;
 }

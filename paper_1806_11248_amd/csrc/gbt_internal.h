@@ -33,6 +33,7 @@ struct gbt_ctx {
     int part_fused;         // 1: one-launch record partition where it applies
     int lossguide_batch;    // open leaves a round of loss-guided growth expands at once (1: only the one whose turn it is)
     int part_nomove;        // partition + histogram path, depth-wise: 1: the last histogram level is built without moving rows; 2: the last two
+    int part_cycle;         // same path: above the last two levels, rows are moved every third level only (keep, keep with two histograms, move three levels)
     int part_ids;           // 1: rows wider than 64 words are not moved: id lists are partitioned and the histogram kernel gathers
     int order_rows;         // 1: a caller's row order is made from the finished tree, so that it does not restrict the partition form
     int hist_fix;           // 1: the root histogram kernel also converts the gradient pairs where that applies
@@ -143,6 +144,19 @@ struct Hist2Job {
     uint64_t hist_off[2];
 };
 
+// One segment for the pass that puts rows in order again after two levels in place (gbt_launch_move3): the splits
+// below the segment in heap order as in CountJob (0 the segment's own, 1 and 2 its children's, 3..6 the
+// grandchildren's; has[p] = 0: node p does not split and its rows are dropped), and the row range of each
+// grandchild in the destination, inside which its left rows are stored from the front and its right rows from the
+// back.  Cursor word 4 * job + g counts grandchild g's left (low half) and right (high half) rows.
+struct Move3Job {
+    uint32_t seg_begin, seg_len;
+    uint32_t tile_begin, n_tiles;   // in spans of rows_per_span rows
+    uint32_t feature[7], bin[7], default_left[7];
+    uint32_t has[7];
+    uint32_t node_begin[4], node_len[4];
+};
+static_assert(sizeof(Move3Job) % 4 == 0 && sizeof(Move3Job) / 4 <= 64, "staged into LDS by the first wave");
 
 // One leaf segment for the final gather.
 struct LeafSeg {
@@ -167,7 +181,7 @@ hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, dou
 hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,
                              int64_t *out2 /* zeroed by the launcher */);
 hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margin, const float *label,
-                                int64_t n, float *gpair);
+                                int64_t n, float *gpair, uint32_t *bounds = nullptr);
 hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const int64_t *child,
                                    int64_t *out, int64_t count);
 hipError_t gbt_launch_export(hipStream_t s, const int64_t *hist, int64_t count, double inv_sg,
@@ -311,6 +325,13 @@ bool gbt_hist2_ok(const gbt_ctx *ctx, int F, int B);
 hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B, uint32_t missing,
                             const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
                             unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false);
+// The pass that moves the records of segments whose rows stayed in place for two levels to their grandchildren's
+// children (Move3Job); records of at most 16 byte symbols.  dst_rows: rows the destination holds (a store past it
+// is skipped).  cursor: 4 words per job, cleared here unless the caller says they are zero.
+int gbt_move3_tile();
+hipError_t gbt_launch_move3(gbt_ctx *ctx, const uint32_t *src_records, uint32_t *dst_records, int64_t dst_rows, int F,
+                            uint32_t missing, const Move3Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                            unsigned long long *cursor, bool cursors_are_zero = false);
 int gbt_part_hist_tile();
 int gbt_part_hist_record_words(int F);
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
@@ -368,7 +389,12 @@ struct DevTree {   // one tree's arrays inside the predict workspace (offsets in
 hipError_t gbt_launch_predict(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
                               const uint32_t *packed, int bits, uint32_t missing, const float *X,
                               int64_t n, int F, double eta, float *margin, int32_t *leaf_out, int max_nodes,
-                              bool compact_ok);   // leaf_out != NULL: store each row's leaf id instead of updating margin
+                              bool compact_ok, uint32_t *node_rows = nullptr,
+                              const float *margin_src = nullptr);   // leaf_out != NULL: store each row's leaf id instead of updating margin
+// node_rows, margin_src (one tree, and only where gbt_predict_counts_ok): count the rows that end in every node into
+// node_rows[node * kNodeRowsStride] (zeroed by the caller); margin[r] = margin_src[r] + eta * weight
+constexpr int kNodeRowsStride = 32;   // words between two nodes' row counters (gbt_launch_predict's node_rows)
+bool gbt_predict_counts_ok(bool packed, int bits, int F, int max_nodes, bool compact_ok);
 // compact_ok: every split node has right == left + 1, feature < 2^20 and bin < 4096
 
 // Many trees on raw floats in one pass over the rows (kernels_misc.hip).  A node is 8 bytes:

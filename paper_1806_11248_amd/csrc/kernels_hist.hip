@@ -977,6 +977,137 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
     if (job.has[1]) flush_tile(main0 + n_acc, side0 + n_acc, ft, B, Bp, pool + job.hist_off[1], kH2Block);
 }
 
+// Rows that stayed in place through two levels (hist_keep_kernel, hist2_kernel) are put in order again, three
+// levels at once: a row is taken down from its segment's split through the child's and the grandchild's (heap
+// positions 0; 1, 2; 3..6) and stored on the left or right side of the grandchild's range, left rows from the
+// front, right rows from the back, room reserved per tile with one 64-bit atomic per (grandchild, side) on the
+// grandchild's cursor (4 * job + grandchild: low word left rows handed out, high word right rows).  A row that
+// reaches a node without a split is dropped: nothing reads the rows of a leaf again.  No histogram here: four
+// grandchildren would need four of them in LDS; the built children are added up afterwards from their (then
+// contiguous) records.  Two tiles are in flight as in part_hist_kernel; wave k ranks category k = 2 * grandchild +
+// (0 left, 1 right).
+constexpr int kM3Block = 512;
+template <int NS>
+__global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
+    const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, uint64_t dst_rows, uint32_t missing,
+    const Move3Job *__restrict__ jobs, int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor) {
+    constexpr int SW = (NS + 3) / 4;
+    constexpr int RW = record_words(NS);
+    constexpr int BLK = kM3Block, ROWS = kPFRows, TILE = BLK * ROWS, WAVES = BLK / 64, NW = TILE / 64;
+    static_assert(WAVES == 8, "one wave per category");
+    static_assert(NW <= 64, "a category's tile counts are scanned by one wave");
+    __shared__ Move3Job sjob;
+    __shared__ uint32_t cnt[2][NW][8];
+    __shared__ uint32_t base_s[2][8];
+    int lo = 0, hi = n_jobs;   // last job with tile_begin <= this span
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (jobs[mid].tile_begin <= blockIdx.x) lo = mid; else hi = mid;
+    }
+    const int ji = lo;
+    if (threadIdx.x < (int)(sizeof(Move3Job) / 4)) ((uint32_t *)&sjob)[threadIdx.x] = ((const uint32_t *)&jobs[ji])[threadIdx.x];
+    __syncthreads();
+    const Move3Job &job = sjob;
+    const uint32_t span_begin = (blockIdx.x - job.tile_begin) * rows_per_span;
+    if (span_begin >= job.seg_len) return;   // (uniform: a span past its segment has nothing to do)
+    const uint32_t span_rows = job.seg_len - span_begin < rows_per_span ? job.seg_len - span_begin : rows_per_span;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t span_first = (uint64_t)job.seg_begin + span_begin;
+    const uint64_t below_me = (1ull << lane) - 1ull;
+
+    auto symbol = [&](const uint32_t (&row)[RW], uint32_t f) __attribute__((always_inline)) -> uint32_t {
+        const uint32_t sa = 0x0C0C0C00u | (f < 8u ? f : 0x0Cu), sb = 0x0C0C0C00u | (f >= 8u ? f - 8u : 0x0Cu);
+        return __builtin_amdgcn_perm(SW > 1 ? row[SW > 1 ? 1 : 0] : 0u, row[0], sa) |
+               __builtin_amdgcn_perm(SW > 3 ? row[SW > 3 ? 3 : 0] : 0u, SW > 2 ? row[SW > 2 ? 2 : 0] : 0u, sb);
+    };
+    auto goes_left = [&](const uint32_t (&row)[RW], uint32_t p) __attribute__((always_inline)) -> bool {
+        const uint32_t sy = symbol(row, job.feature[p]);
+        return sy == missing ? job.default_left[p] != 0 : sy <= job.bin[p];
+    };
+    auto load_tile = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
+            if (in_tile < tile_rows) {
+                const uint32_t *rp = src + (span_first + done + in_tile) * RW;
+#pragma unroll
+                for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+            }
+        }
+    };
+    auto process = [&](uint32_t (&row)[ROWS][RW], uint32_t done, int par) __attribute__((always_inline)) {
+        const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+        uint32_t cat[ROWS], rank[ROWS];
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const int w = j * WAVES + wave;
+            const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
+            uint32_t c = 8u;   // dropped
+            if (in_tile < tile_rows) {
+                const uint32_t p1 = goes_left(row[j], 0u) ? 1u : 2u;
+                if (job.has[p1]) {
+                    const uint32_t p2 = 2u * p1 + (goes_left(row[j], p1) ? 1u : 2u);
+                    if (job.has[p2]) c = 2u * (p2 - 3u) + (goes_left(row[j], p2) ? 0u : 1u);
+                }
+            }
+            uint32_t r = 0;
+#pragma unroll
+            for (uint32_t k = 0; k < 8u; ++k) {
+                const uint64_t b = __ballot(c == k);
+                if (c == k) r = (uint32_t)__popcll(b & below_me);
+                if (lane == 0) cnt[par][w][k] = (uint32_t)__popcll(b);
+            }
+            cat[j] = c;
+            rank[j] = r;
+        }
+        __syncthreads();
+        {   // wave k: places of category k's rows inside the tile, and the tile's room in the grandchild's range
+            const uint32_t v = lane < NW ? cnt[par][lane < NW ? lane : 0][wave] : 0u;
+            uint32_t x = v;
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t y = (uint32_t)__shfl_up((int)x, d);
+                if (lane >= d) x += y;
+            }
+            if (lane < NW) cnt[par][lane][wave] = x - v;
+            if (lane == 63) {
+                unsigned long long old = 0;
+                if (x) old = atomicAdd(&cursor[4 * ji + (wave >> 1)], (wave & 1) ? (unsigned long long)x << 32 : (unsigned long long)x);
+                base_s[par][wave] = (wave & 1) ? (uint32_t)(old >> 32) : (uint32_t)(old & 0xffffffffull);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const int w = j * WAVES + wave;
+            const uint32_t c = cat[j];
+            if (c < 8u) {
+                const uint32_t g = c >> 1;
+                const uint32_t off = base_s[par][c] + cnt[par][w][c] + rank[j];
+                const uint64_t q = (c & 1u) ? (uint64_t)job.node_begin[g] + job.node_len[g] - 1u - off : (uint64_t)job.node_begin[g] + off;
+                if (off < job.node_len[g] && q < dst_rows) {   // (always, when the ranges are the counts of these very splits)
+                    uint32_t *dp = dst + q * RW;
+#pragma unroll
+                    for (int k = 0; k < RW; ++k) dp[k] = row[j][k];
+                }
+            }
+        }
+        // cnt[par] and base_s[par] are rewritten two tiles from now, after two more barriers
+    };
+
+    uint32_t rowA[ROWS][RW], rowB[ROWS][RW];
+    load_tile(rowA, 0);
+    for (uint32_t done = 0; done < span_rows;) {
+        if (done + TILE < span_rows) load_tile(rowB, done + TILE);
+        process(rowA, done, 0);
+        done += TILE;
+        if (done >= span_rows) break;
+        if (done + TILE < span_rows) load_tile(rowA, done + TILE);
+        process(rowB, done, 1);
+        done += TILE;
+    }
+}
+
 
 }  // namespace
 
@@ -1240,6 +1371,28 @@ hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B,
     return chk ? pick_hist2<true>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool)
                : pick_hist2<false>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool);
 }
+int gbt_move3_tile() { return kM3Block * kPFRows; }
+hipError_t gbt_launch_move3(gbt_ctx *ctx, const uint32_t *src_records, uint32_t *dst_records, int64_t dst_rows, int F,
+                            uint32_t missing, const Move3Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                            unsigned long long *cursor, bool cursors_are_zero) {
+    if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
+    if (F < 1 || F > 16 || rows_per_span == 0 || dst_rows < 0) return hipErrorInvalidValue;
+    if (!cursors_are_zero) {
+        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 4 * (int64_t)n_jobs);
+        if (e != hipSuccess) return e;
+    }
+    const int ns = slots_for(F);
+#define GBT_M3(NS_) move3_kernel<NS_><<<n_spans, kM3Block, 0, ctx->stream>>>(src_records, dst_records, (uint64_t)dst_rows, missing, \
+                                                                             jobs, n_jobs, rows_per_span, cursor)
+    if (ns == 4) GBT_M3(4);
+    else if (ns == 8) GBT_M3(8);
+    else if (ns == 12) GBT_M3(12);
+    else if (ns == 13) GBT_M3(13);
+    else GBT_M3(16);
+#undef GBT_M3
+    return hipGetLastError();
+}
+
 int gbt_part_hist_record_words(int F) { return record_words(slots_for(F)); }
 
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
