@@ -118,7 +118,7 @@ typedef struct gbt_tree {
  *   GBT_TUNE_MOVE_MAX_WORDS     [8] 1..64: rows of more 32-bit words than this are listed (path 3), not moved
  *   GBT_TUNE_ORDER_ROWS         [1] 0: row ids travel with the rows (path 0) instead of the order being rebuilt from the tree
  *   GBT_TUNE_PART_NOMOVE        [2] 0..2: how many of the last levels of a depth-wise tree leave their rows in place (path 2)
- *   GBT_TUNE_PART_CYCLE         [0] 1: above those levels rows are moved only every third level (two levels in place, then one move over three levels of splits; path 2)
+ *   GBT_TUNE_PART_CYCLE         [1] 0: above those levels rows are moved at every level instead of every third (two levels in place, then one move over three levels of splits; path 2)
  *   GBT_TUNE_HIST_FIX           [1] 0: gradient pairs are rounded to fixed point in a pass of their own, not in the root histogram launch
  *   GBT_TUNE_HIST8              [1] 0: the root histogram of byte symbols by the general byte-symbol kernel
  *   GBT_TUNE_HIST8_STAGGER      [64] 0..128: in 1/1024 of a job's length, how unequal the jobs of that launch are

@@ -243,7 +243,7 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (const char *e16 = getenv("GBT_TUNE_LOSSGUIDE_BATCH")) { int v = atoi(e16); if (v >= 1 && v <= 64) c->lossguide_batch = v; }
         c->part_nomove = 2;
         if (const char *e15 = getenv("GBT_TUNE_PART_NOMOVE")) { int v = atoi(e15); if (v >= 0 && v <= 2) c->part_nomove = v; }
-        c->part_cycle = 0;
+        c->part_cycle = 1;
         if (const char *e17 = getenv("GBT_TUNE_PART_CYCLE")) c->part_cycle = atoi(e17) != 0;
         c->part_ids = 1;
         if (const char *e14 = getenv("GBT_TUNE_PART_IDS")) c->part_ids = atoi(e14) != 0;
@@ -811,7 +811,7 @@ GrowLayout grow_layout_nodes(int64_t n, int F, int bits, int B, int64_t hist_nod
     L.masks = o;      o += gbt_align((size_t)L.tiles * (GBT_PART_TILE / 64) * 8);
     L.tile_left = o;  o += gbt_align((size_t)L.tiles * 4);
     L.n_left = o;     o += gbt_align((size_t)L.level_nodes * 4 + 4);
-    L.state = o;      o += gbt_align((size_t)L.level_nodes * 8);
+    L.state = o;      o += gbt_align((size_t)L.level_nodes * 8 * kCursorStride);
     L.pool = o;       o += gbt_align((size_t)L.hist_nodes * F * B * 16);
     L.eval_nodes = o; o += gbt_align((size_t)L.level_nodes * 2 * sizeof(EvalNode));
     L.jobs = o;       o += gbt_align(kUploadBytes);
@@ -1267,7 +1267,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         // three levels at once -- 20 + 20 + 40 (+ the built children's 20 * 1/2) bytes per row and three levels
         // instead of 3 * 40 -- timed so that a cycle ends where the last two in-place levels begin.
         const int levels_after = (max_depth - 1) - child_depth;   // histogram levels below this one
-        const bool cycle_start = ctx->part_cycle && ctx->part_nomove >= 2 && levels_after >= 4 && levels_after % 3 == 1;
+        const bool cycle_start = ctx->part_cycle && ctx->part_nomove >= 2 && levels_after >= 4 && levels_after % 3 == 1 &&
+                                 sel_nodes.size() <= 512;   // (each becomes a segment with four cursors to read back)
         const bool nomove = with_hist && !lossguide && !in_place && ctx->part_nomove &&
                             (child_depth == max_depth - 1 ||
                              (ctx->part_nomove >= 2 && (child_depth == max_depth - 2 || cycle_start) && wcur != 2 &&
@@ -1406,7 +1407,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 mj.node_len[gch] = sel_nodes[k].len;
             }
             GBT_REQUIRE(ctx, m3jobs.size() * sizeof(Move3Job) <= kUploadBytes && 4 * (int64_t)m3jobs.size() <= L.level_nodes &&
-                                 m3jobs.size() * 32 <= kSplitRb,
+                                 m3jobs.size() * 32 * kCursorStride <= kSplitRb,
                         GBT_EUNSUPPORTED, "level too wide");
             st = upload(ctx, m3jobs.data(), m3jobs.size() * sizeof(Move3Job), ws + L.jobs);
             if (st != GBT_OK) return st;
@@ -1415,13 +1416,13 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             GBT_HIP(ctx, gbt_launch_move3(ctx, W[wcur].sym, W[wnext].sym_rw, n, F, (uint32_t)missing_sym,
                                           (const Move3Job *)(ws + L.jobs), (int)m3jobs.size(), (int)m3_spans, m3_span_rows,
                                           (unsigned long long *)(ws + L.state), cursors_zero));
-            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, m3jobs.size() * 32, hipMemcpyDeviceToHost, s));
+            GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, m3jobs.size() * 32 * kCursorStride, hipMemcpyDeviceToHost, s));
             cursors_zero = false;
             gbt_prof_end(ctx);
             GBT_SYNC(ctx);
             const unsigned long long *cur64 = (const unsigned long long *)rb(ctx);
             for (size_t k = 0; k < sel_nodes.size(); ++k) {
-                const unsigned long long c = cur64[4 * (size_t)job_of[k] + (size_t)(sel_nodes[k].vpos - 3)];
+                const unsigned long long c = cur64[(4 * (size_t)job_of[k] + (size_t)(sel_nodes[k].vpos - 3)) * kCursorStride];
                 const uint32_t lefts = (uint32_t)(c & 0xffffffffull), rights = (uint32_t)(c >> 32);
                 GBT_REQUIRE(ctx, (uint64_t)lefts + rights == sel_nodes[k].len, GBT_EHIP,
                             "internal: node %d holds %u rows, %u + %u were moved", sel_nodes[k].id, sel_nodes[k].len, lefts, rights);
@@ -1524,7 +1525,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             if (with_hist) {
                 GBT_REQUIRE(ctx, pjobs.size() * 8 <= kSplitRb, GBT_EUNSUPPORTED, "level too wide");
                 if (!cursors_zero) {   // every cursor a level can have; from then on the evaluation launch keeps them clear
-                    GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(ws + L.state), 0, L.level_nodes));
+                    GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)(ws + L.state), 0, L.level_nodes * kCursorStride));
                     cursors_zero = true;
                 }
                 if (nomove2)   // the segments' records once more, two histograms per workgroup
@@ -1547,7 +1548,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 const int64_t zero_end = more ? std::min<int64_t>(after + 2 * (int64_t)enodes.size(), L.hist_nodes) : 0;
                 st = enqueue_eval(enodes, &chunks, children_dev,
                                   EvalTail{(unsigned long long *)(ws + L.state), (unsigned long long *)rb(ctx),
-                                           nomove2 ? 2 * (int)h2jobs.size() : (int)pjobs.size(), 1, more ? after : -1, zero_end});
+                                           nomove2 ? 2 * (int)h2jobs.size() : (int)pjobs.size(), 1, more ? after : -1, zero_end,
+                                           kCursorStride});
                 if (st != GBT_OK) return st;
                 pool_zero_end = zero_end;
                 pre_eval = true;

@@ -218,7 +218,11 @@ struct EvalTail {
     unsigned long long *src, *dst;
     int n, clear;
     int64_t clear_slot, clear_slot_end;
+    int src_stride = 1;   // word i is src[i * src_stride]
 };
+// The cursors of the passes that partition and build histograms in one launch lie one per 128-byte line
+// (index * kCursorStride): atomics on words of one line take turns as if they were one address.
+constexpr int kCursorStride = 16;
 hipError_t gbt_launch_eval(hipStream_t s, int64_t *hist_pool, const EvalNode *nodes, int n_nodes,
                            const int32_t *nb, int F, int B, int n_chunks, double inv_sg, double inv_sh,
                            double lambda, double mcw, gbt_split *out, EvalTail tail = EvalTail{nullptr, nullptr, 0, 0, -1, 0});

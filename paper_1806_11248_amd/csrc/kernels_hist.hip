@@ -523,7 +523,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
             }
             lefts_before[par][lane] = x - c;
             if (lane == 63)
-                reserved = atomicAdd(&cursor[ji], (unsigned long long)x | ((unsigned long long)(tile_rows - x) << 32));
+                reserved = atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)x | ((unsigned long long)(tile_rows - x) << 32));
         }
 
         // ---- histogram of the rows on the side to be built
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
         }
         // words[par] is rewritten two tiles from now, after two more barriers: no third barrier needed
     }
-    if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[ji], (unsigned long long)my_lefts);
+    if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)my_lefts);
     __syncthreads();
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, kPHBlock);
 }
@@ -675,7 +675,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
             }
             if (lane < NW) lefts_before[par][lane] = x - c;
             if (lane == 63)
-                reserved = atomicAdd(&cursor[ji], (unsigned long long)x | ((unsigned long long)(tile_rows - x) << 32));
+                reserved = atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)x | ((unsigned long long)(tile_rows - x) << 32));
         }
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
@@ -721,7 +721,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
         process(rowB, done, 1);
         done += TILE;
     }
-    if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[ji], (unsigned long long)my_lefts);
+    if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)my_lefts);
     __syncthreads();
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
 }
@@ -833,7 +833,7 @@ __global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
         done += TILE;
     }
     if (queue.waiting()) add_waiting(queue.waiting());
-    if (lane == 0 && my_lefts) atomicAdd(&cursor[ji], (unsigned long long)my_lefts);
+    if (lane == 0 && my_lefts) atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)my_lefts);
     __syncthreads();
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
 }
@@ -969,8 +969,8 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
     }
     if (queue.waiting()) add_waiting(queue.waiting());
     if (lane == 0) {
-        if (my_lefts[0]) atomicAdd(&cursor[2 * ji], (unsigned long long)my_lefts[0]);
-        if (my_lefts[1]) atomicAdd(&cursor[2 * ji + 1], (unsigned long long)my_lefts[1]);
+        if (my_lefts[0]) atomicAdd(&cursor[(size_t)(2 * ji) * kCursorStride], (unsigned long long)my_lefts[0]);
+        if (my_lefts[1]) atomicAdd(&cursor[(size_t)(2 * ji + 1) * kCursorStride], (unsigned long long)my_lefts[1]);
     }
     __syncthreads();
     if (job.has[0]) flush_tile(main0, side0, ft, B, Bp, pool + job.hist_off[0], kH2Block);
@@ -984,7 +984,7 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
 // grandchild's cursor (4 * job + grandchild: low word left rows handed out, high word right rows).  A row that
 // reaches a node without a split is dropped: nothing reads the rows of a leaf again.  No histogram here: four
 // grandchildren would need four of them in LDS; the built children are added up afterwards from their (then
-// contiguous) records.  Two tiles are in flight as in part_hist_kernel; wave k ranks category k = 2 * grandchild +
+// contiguous) records.  Two tiles are in flight as in part_hist_kernel; a row's category is 2 * grandchild +
 // (0 left, 1 right).
 constexpr int kM3Block = 512;
 template <int NS>
@@ -994,8 +994,8 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
     constexpr int SW = (NS + 3) / 4;
     constexpr int RW = record_words(NS);
     constexpr int BLK = kM3Block, ROWS = kPFRows, TILE = BLK * ROWS, WAVES = BLK / 64, NW = TILE / 64;
-    static_assert(WAVES == 8, "one wave per category");
-    static_assert(NW <= 64, "a category's tile counts are scanned by one wave");
+    static_assert(WAVES >= 4, "one wave per grandchild");
+    static_assert(NW == 32, "a category's tile counts are scanned by half a wave");
     __shared__ Move3Job sjob;
     __shared__ uint32_t cnt[2][NW][8];
     __shared__ uint32_t base_s[2][8];
@@ -1062,18 +1062,23 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
             rank[j] = r;
         }
         __syncthreads();
-        {   // wave k: places of category k's rows inside the tile, and the tile's room in the grandchild's range
-            const uint32_t v = lane < NW ? cnt[par][lane < NW ? lane : 0][wave] : 0u;
+        if (wave < 4) {   // wave g: places of grandchild g's left rows (lanes 0..31) and right rows (lanes 32..63)
+                          // inside the tile, and the tile's room in the grandchild's range: one atomic for both sides
+            const int half = lane >> 5, wl = lane & 31;
+            const uint32_t v = cnt[par][wl][2 * wave + half];
             uint32_t x = v;
-            for (int d = 1; d < 64; d <<= 1) {
+            for (int d = 1; d < 32; d <<= 1) {
                 const uint32_t y = (uint32_t)__shfl_up((int)x, d);
-                if (lane >= d) x += y;
+                if (wl >= d) x += y;
             }
-            if (lane < NW) cnt[par][lane][wave] = x - v;
+            cnt[par][wl][2 * wave + half] = x - v;
+            const uint32_t lefts = (uint32_t)__shfl((int)x, 31), rights = (uint32_t)__shfl((int)x, 63);
             if (lane == 63) {
                 unsigned long long old = 0;
-                if (x) old = atomicAdd(&cursor[4 * ji + (wave >> 1)], (wave & 1) ? (unsigned long long)x << 32 : (unsigned long long)x);
-                base_s[par][wave] = (wave & 1) ? (uint32_t)(old >> 32) : (uint32_t)(old & 0xffffffffull);
+                if (lefts | rights)
+                    old = atomicAdd(&cursor[(size_t)(4 * ji + wave) * kCursorStride], (unsigned long long)lefts | ((unsigned long long)rights << 32));
+                base_s[par][2 * wave] = (uint32_t)(old & 0xffffffffull);
+                base_s[par][2 * wave + 1] = (uint32_t)(old >> 32);
             }
         }
         __syncthreads();
@@ -1362,7 +1367,7 @@ hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B,
                             unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero) {
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
     if (!cursors_are_zero) {
-        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 2 * (int64_t)n_jobs);
+        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 2 * (int64_t)n_jobs * kCursorStride);
         if (e != hipSuccess) return e;
     }
     const int Bp = padded_bins(B);
@@ -1378,7 +1383,7 @@ hipError_t gbt_launch_move3(gbt_ctx *ctx, const uint32_t *src_records, uint32_t 
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
     if (F < 1 || F > 16 || rows_per_span == 0 || dst_rows < 0) return hipErrorInvalidValue;
     if (!cursors_are_zero) {
-        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 4 * (int64_t)n_jobs);
+        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 4 * (int64_t)n_jobs * kCursorStride);
         if (e != hipSuccess) return e;
     }
     const int ns = slots_for(F);
@@ -1402,7 +1407,7 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
                                 const float *gpair_fp32, double sg, double sh) {
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
     if (!cursors_are_zero) {
-        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, n_jobs);
+        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, (int64_t)n_jobs * kCursorStride);
         if (e != hipSuccess) return e;
     }
     const int Bp = padded_bins(B);

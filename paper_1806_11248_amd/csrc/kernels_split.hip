@@ -61,8 +61,8 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     gbt_split *__restrict__ out, EvalTail tail) {
     if (blockIdx.x == 0 && blockIdx.y == 0) {   // the words handed back with the records (see gbt_launch_eval)
         for (int i = threadIdx.x; i < tail.n; i += kEvalBlock) {
-            tail.dst[i] = tail.src[i];
-            if (tail.clear) tail.src[i] = 0ull;
+            tail.dst[i] = tail.src[(size_t)i * tail.src_stride];
+            if (tail.clear) tail.src[(size_t)i * tail.src_stride] = 0ull;
         }
     }
     const EvalNode nd = nodes[blockIdx.x];

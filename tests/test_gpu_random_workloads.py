@@ -23,7 +23,7 @@ from test_gpu_tree import gpu_prep, grow_and_judge
 pytestmark = pytest.mark.gpu
 
 # Contexts are created under one of these settings in turn: every path the growers can take (the default
-# choices, rows moved at every level or not at the last one or two, the three-launch partition, histograms
+# choices, rows moved at every level or not at the last one or two or only every third level, the three-launch partition, histograms
 # apart from the partition, pairs rounded in a pass of their own, row ids carried along, one loss-guided
 # expansion per round, run-time bit widths, other workgroup shapes, rows of up to 64 words moved instead of listed,
 # the 8-bit root histogram by the general kernel, every histogram job a single merge-free piece or many short ones)
@@ -31,6 +31,7 @@ VARIANTS = [
     {},
     {"GBT_TUNE_PART_NOMOVE": "0"},
     {"GBT_TUNE_PART_NOMOVE": "1"},
+    {"GBT_TUNE_PART_CYCLE": "0"},
     {"GBT_TUNE_PART_FUSED": "0"},
     {"GBT_TUNE_PART_HIST": "0"},
     {"GBT_TUNE_HIST_FIX": "0"},

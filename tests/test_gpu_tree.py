@@ -325,13 +325,16 @@ def test_boosting_rounds_in_lock_step(ctx, oracle):
 
 
 @pytest.mark.parametrize("depth,F,miss", [(1, 13, 0.0), (2, 13, 0.0), (3, 13, 0.0), (4, 13, 0.0), (5, 13, 0.0),
-                                          (6, 13, 0.0), (8, 13, 0.0), (7, 16, 0.1), (6, 3, 0.0), (9, 8, 0.3)])
+                                          (6, 13, 0.0), (8, 13, 0.0), (7, 16, 0.1), (6, 3, 0.0), (9, 8, 0.3),
+                                          (10, 13, 0.0), (11, 5, 0.2), (13, 12, 0.0)])
 def test_last_levels_without_moving_rows(ctx, ctx_env, oracle, depth, F, miss):
     """Byte symbols, at most 16 features: the last two levels that need histograms are built without
     moving rows (the second of them with two histograms per workgroup over the first one's segments)
     and the leaves' row counts come from a count over up to three levels of splits (depth 2:
-    straight from the packed matrix).  Same trees as with one such level, and as with the rows moved
-    at every level."""
+    straight from the packed matrix).  From depth 7 on, levels further up also leave the rows in place two at a
+    time and a third pass moves them over three levels of splits at once (depth 10 and 13: twice and three times
+    in a tree).  Same trees as with one such level, as with the rows moved at every level, and as without those
+    cycles."""
     n = 120_000
     d = synth.make(4, n)
     rng = np.random.default_rng(100 * depth + F)
@@ -349,10 +352,10 @@ def test_last_levels_without_moving_rows(ctx, ctx_env, oracle, depth, F, miss):
     params = g.make_params(max_depth=depth, max_bins=p["max_bins"], lam=p["lam"], gamma=p["gamma"],
                            min_child_weight=p["min_child_weight"])
     nn = tree["n_nodes"]
-    for levels in (0, 1):
-        other, _, _ = ctx_env(GBT_TUNE_PART_NOMOVE=levels).grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"],
-                                                                    gdev["nb"], gdev["cuts"], dev(gp), params,
-                                                                    want_rows=False, want_leaf=False)
+    # (a variable stays set for the contexts made after it: the cycles need both in-place levels anyway)
+    for env in ({"GBT_TUNE_PART_CYCLE": 0}, {"GBT_TUNE_PART_NOMOVE": 0}, {"GBT_TUNE_PART_NOMOVE": 1}):
+        other, _, _ = ctx_env(**env).grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"], gdev["cuts"],
+                                               dev(gp), params, want_rows=False, want_leaf=False)
         assert other["n_nodes"] == nn
         for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "weight", "gain", "sumG", "sumH"):
-            assert np.array_equal(other[k][:nn], tree[k][:nn]), (levels, k)
+            assert np.array_equal(other[k][:nn], tree[k][:nn]), (env, k)
