@@ -288,8 +288,13 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
     root8 = bits == 8 and F <= 16
     hist_kernel = ("hist8_kernel" if root8 else "hist_b8_kernel") if bits == 8 else "hist_bits_kernel"
     node_hist_kernel = "hist_b8_kernel" if bits == 8 else "hist_bits_kernel"
-    node_kernel = "part_hist_kernel (partition + one child's histogram in one pass)" if path == 2 else node_hist_kernel
-    part_kernel = ("count2_kernel (row counts of the leaves)" if path == 2 and not lossguide else
+    # path 2, depth-wise: which levels a class covers depends on the depth (see gbt_grow_tree): with depth 8 the
+    # rows stay in place at levels 1, 3, 4, 6, 7 and are moved over several levels of splits at levels 2 and 5
+    node_kernel = ("part_hist_kernel (partition + one child's histogram in one pass) where rows move at every level; "
+                   "hist_keep_kernel over the built children's records behind a move over several levels"
+                   if path == 2 else node_hist_kernel)
+    part_kernel = ("move_levels_kernel (rows moved over two or three levels of splits at once)"
+                   + ("" if one_call else " + count2_kernel (row counts of the leaves)") if path == 2 and not lossguide else
                    "part_flag_kernel + part_scan_kernel (row counts of the last level)" if path == 2 else
                    ("part_fused_kernel" if (F * bits + 31) // 32 == 4 else "part_staged_kernel") if path == 1 else
                    "part_flag_kernel + part_scan_kernel + part_scatter_kernel (row-id lists)" if path == 3 else
@@ -299,9 +304,10 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
         part_kernel = "sparse_part_kernel"
     r_root = roof(prof, ["hist_root"], hist_kernel)
     r_node = roof(prof, ["hist_node"], node_kernel)
-    r_first = roof(prof, ["hist_first"], "part_hist_first_kernel (the same pass at level 0, from the packed matrix)")
-    r_inplace = roof(prof, ["hist_inplace"], "hist_keep_kernel + hist2_kernel (the passes of the last two levels: rows stay in place, "
-                                            "one and two histograms per workgroup)")
+    r_first = roof(prof, ["hist_first"], "the pass at level 1, from the packed matrix: hist_keep_kernel where the rows stay in place "
+                                        "(depth 5, 6, 8, 9, ...), else part_hist_first_kernel")
+    r_inplace = roof(prof, ["hist_inplace"], "hist_keep_kernel + hist2_kernel (passes over records that stay in place: one and two "
+                                            "histograms per workgroup)")
     r_part = roof(prof, ["partition"], part_kernel)
     traffic = None if sparse else committed_traffic(cfg)
     if traffic:

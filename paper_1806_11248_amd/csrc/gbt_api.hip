@@ -1254,7 +1254,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         // Rows that have stayed in place for two levels (their nodes are grandchildren of the segment they lie in) are
         // put in order again by a pass of its own, without a histogram: one child of each is then built from its
         // contiguous records
-        const bool move3 = children_need_hist && path == 2 && in_place && sel_nodes[0].vpos >= 3;
+        // (likewise rows that stayed in the caller's matrix at the root's split: two levels at once, into records)
+        const bool move3 = children_need_hist && path == 2 && in_place && (sel_nodes[0].vpos >= 3 || wcur == 2);
+        const int move_levels = sel_nodes[0].vpos >= 3 ? 3 : 2;
         const bool with_hist = children_need_hist && path == 2 && !move3;
         // Depth-wise, the last level that needs histograms: its children's children are leaves, of which only
         // the row counts are wanted.  The pass then builds the histograms and counts without moving a row,
@@ -1269,8 +1271,14 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         const int levels_after = (max_depth - 1) - child_depth;   // histogram levels below this one
         const bool cycle_start = ctx->part_cycle && ctx->part_nomove >= 2 && levels_after >= 4 && levels_after % 3 == 1 &&
                                  sel_nodes.size() <= 512;   // (each becomes a segment with four cursors to read back)
+        // At the root's split the rows stay in the matrix where the level below would otherwise move them a second
+        // time: the children's histogram is built in place (21 bytes per row instead of 41) and the next level moves
+        // the rows from the matrix straight to the grandchildren (41 + the built children's 10 instead of 40).
+        const int levels_after_next = levels_after - 1;
+        const bool first_keep = ctx->part_cycle && ctx->part_nomove >= 2 && wcur == 2 && child_depth == 1 &&
+                                levels_after_next >= 2 && !(levels_after_next >= 4 && levels_after_next % 3 == 1);
         const bool nomove = with_hist && !lossguide && !in_place && ctx->part_nomove &&
-                            (child_depth == max_depth - 1 ||
+                            (child_depth == max_depth - 1 || first_keep ||
                              (ctx->part_nomove >= 2 && (child_depth == max_depth - 2 || cycle_start) && wcur != 2 &&
                               gbt_hist2_ok(ctx, F, B)));
         const bool nomove2 = with_hist && in_place;     // (their heap positions are 1 and 2)
@@ -1377,7 +1385,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                              : cnt[2 * job_of[k] + (sel_nodes[k].vpos - 1)];
         } else if (move3) {
             // one job per segment: the three levels of splits below it and where its grandchildren's rows go
-            GBT_REQUIRE(ctx, wcur != 2, GBT_EHIP, "internal: rows kept in the caller's matrix for two levels");
+            GBT_REQUIRE(ctx, (move_levels == 2) == (wcur == 2), GBT_EHIP, "internal: %d levels of rows kept in buffer %d", move_levels, wcur);
             m3jobs.clear();
             uint32_t m3_spans = 0;
             double m3_rows = 0;
@@ -1401,8 +1409,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 memcpy(mj.bin, u.bin, sizeof mj.bin);
                 memcpy(mj.default_left, u.default_left, sizeof mj.default_left);
                 memcpy(mj.has, u.has, sizeof mj.has);
-                const int gch = sel_nodes[k].vpos - 3;
-                GBT_REQUIRE(ctx, gch >= 0 && gch < 4, GBT_EHIP, "internal: heap position %d", sel_nodes[k].vpos);
+                const int gch = sel_nodes[k].vpos - (move_levels == 3 ? 3 : 1);
+                GBT_REQUIRE(ctx, gch >= 0 && gch < (move_levels == 3 ? 4 : 2), GBT_EHIP, "internal: heap position %d", sel_nodes[k].vpos);
                 mj.node_begin[gch] = sel_nodes[k].begin;
                 mj.node_len[gch] = sel_nodes[k].len;
             }
@@ -1412,17 +1420,24 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             st = upload(ctx, m3jobs.data(), m3jobs.size() * sizeof(Move3Job), ws + L.jobs);
             if (st != GBT_OK) return st;
             const double rec_bytes3 = 4.0 * gbt_part_hist_record_words(F);
-            gbt_prof_begin(ctx, GBT_PROF_PARTITION, m3_rows * 2.0 * rec_bytes3, m3_rows * (8.0 + bits / 8.0));
-            GBT_HIP(ctx, gbt_launch_move3(ctx, W[wcur].sym, W[wnext].sym_rw, n, F, (uint32_t)missing_sym,
-                                          (const Move3Job *)(ws + L.jobs), (int)m3jobs.size(), (int)m3_spans, m3_span_rows,
-                                          (unsigned long long *)(ws + L.state), cursors_zero));
+            gbt_prof_begin(ctx, GBT_PROF_PARTITION, m3_rows * (rec_bytes3 + (wcur == 2 ? row_bits / 8.0 + 8.0 : rec_bytes3)),
+                           m3_rows * (8.0 + bits / 8.0));
+            if (wcur == 2)
+                GBT_HIP(ctx, gbt_launch_move2_first(ctx, packed, gbt_packed_words(n, F, bits), gq, pairs_stay_fp32 ? gpair : nullptr,
+                                                    scale[0], scale[1], W[wnext].sym_rw, n, F, (uint32_t)missing_sym,
+                                                    (const Move3Job *)(ws + L.jobs), (int)m3jobs.size(), (int)m3_spans,
+                                                    m3_span_rows, (unsigned long long *)(ws + L.state), cursors_zero));
+            else
+                GBT_HIP(ctx, gbt_launch_move3(ctx, W[wcur].sym, W[wnext].sym_rw, n, F, (uint32_t)missing_sym,
+                                              (const Move3Job *)(ws + L.jobs), (int)m3jobs.size(), (int)m3_spans, m3_span_rows,
+                                              (unsigned long long *)(ws + L.state), cursors_zero));
             GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, m3jobs.size() * 32 * kCursorStride, hipMemcpyDeviceToHost, s));
             cursors_zero = false;
             gbt_prof_end(ctx);
             GBT_SYNC(ctx);
             const unsigned long long *cur64 = (const unsigned long long *)rb(ctx);
             for (size_t k = 0; k < sel_nodes.size(); ++k) {
-                const unsigned long long c = cur64[(4 * (size_t)job_of[k] + (size_t)(sel_nodes[k].vpos - 3)) * kCursorStride];
+                const unsigned long long c = cur64[(4 * (size_t)job_of[k] + (size_t)(sel_nodes[k].vpos - (move_levels == 3 ? 3 : 1))) * kCursorStride];
                 const uint32_t lefts = (uint32_t)(c & 0xffffffffull), rights = (uint32_t)(c >> 32);
                 GBT_REQUIRE(ctx, (uint64_t)lefts + rights == sel_nodes[k].len, GBT_EHIP,
                             "internal: node %d holds %u rows, %u + %u were moved", sel_nodes[k].id, sel_nodes[k].len, lefts, rights);

@@ -336,6 +336,13 @@ int gbt_move3_tile();
 hipError_t gbt_launch_move3(gbt_ctx *ctx, const uint32_t *src_records, uint32_t *dst_records, int64_t dst_rows, int F,
                             uint32_t missing, const Move3Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
                             unsigned long long *cursor, bool cursors_are_zero = false);
+// The same over two levels of splits (the segment's own and its children's: Move3Job entries 0..2, targets 0 and 1)
+// with the rows taken from the caller's packed matrix and pair array (gq, or fp32 pairs rounded with sg, sh as in
+// gbt_launch_part_hist) and written as records: for a segment whose rows stayed in the matrix at its split.
+hipError_t gbt_launch_move2_first(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
+                                  const float *gpair_fp32, double sg, double sh, uint32_t *dst_records, int64_t dst_rows, int F,
+                                  uint32_t missing, const Move3Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                                  unsigned long long *cursor, bool cursors_are_zero = false);
 int gbt_part_hist_tile();
 int gbt_part_hist_record_words(int F);
 hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,

@@ -726,15 +726,56 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
 }
 
+// Rows still in the caller's packed matrix (byte symbols, row p at byte p * stride_bytes) with their pairs in an
+// array of their own: how the passes below that usually read records take them instead.
+struct MoveFirst {
+    int64_t stride_bytes, src_words;
+    const int2 *gq;   // or float2 pairs (F32), rounded with sgf, shf as in part_hist_first_kernel
+    float sgf, shf;
+    int ft;
+};
+// Row p as a record.  inside: every word the unaligned load can touch lies in the buffer (else the last word is read
+// instead); tail_mask: valid bits of the last symbol word.
+template <int NS, bool F32>
+__device__ __forceinline__ void load_first_row(uint32_t (&row)[record_words(NS)], const uint32_t *__restrict__ src, uint64_t p,
+                                               const MoveFirst &first, bool inside, uint32_t tail_mask) {
+    constexpr int SW = (NS + 3) / 4, RW = record_words(NS);
+    const uint64_t sb = p * (uint64_t)first.stride_bytes;
+    const int64_t s0 = (int64_t)(sb >> 2);
+    const uint32_t sh = (uint32_t)(sb & 3);
+    uint32_t x[SW + 1];
+    if (inside) {
+        load_words(x, src + s0);
+    } else {
+#pragma unroll
+        for (int k = 0; k <= SW; ++k) x[k] = src[s0 + k < first.src_words ? s0 + k : first.src_words - 1];
+    }
+#pragma unroll
+    for (int k = 0; k < RW; ++k) row[k] = k < SW ? __builtin_amdgcn_alignbyte(x[k < SW ? k + 1 : 0], x[k < SW ? k : 0], sh) : 0u;
+    row[SW - 1] &= tail_mask;
+    int2 q;
+    if (F32) {
+        const float2 v = ((const float2 *)first.gq)[p];
+        q.x = (int)rintf(v.x * first.sgf);
+        q.y = (int)rintf(v.y * first.shf);
+    } else {
+        q = first.gq[p];
+    }
+    const unsigned long long v56 = ((unsigned long long)(uint32_t)q.x & 0x0fffffffull) | ((unsigned long long)(uint32_t)q.y << 28);
+    row[RW - 2] |= (uint32_t)(v56 << 8);          // bytes 1..3
+    row[RW - 1] = (uint32_t)(v56 >> 24);
+}
+
 // One split per segment, rows stay where they are (the last level but one that needs histograms, see
 // gbt_launch_part_hist): every record is read once, its side decided and counted, and the records of the side
 // to be built are added to the LDS histogram through the wave's queue.  No ranks, no stores, no barriers inside a
 // span; the next tile's records are on their way while the current one is handled.
 constexpr int kKeepBlock = 512;
-template <int NS, bool CHK>
+// FIRST: the rows are read from the caller's matrix and pair array (load_first_row) instead of records.
+template <int NS, bool CHK, bool FIRST, bool F32>
 __global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
     const uint32_t *__restrict__ src, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs, int n_jobs,
-    uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
+    uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool, MoveFirst first) {
     constexpr int SW = (NS + 3) / 4;
     constexpr int RW = record_words(NS);
     constexpr int BLK = kKeepBlock, ROWS = kPFRows, TILE = BLK * ROWS, WAVES = BLK / 64;
@@ -780,17 +821,24 @@ __global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
     const uint32_t fselB = 0x0C0C0C00u | (job.feature >= 8u ? job.feature - 8u : 0x0Cu);
     uint32_t my_lefts = 0;
     const uint64_t span_first = (uint64_t)job.seg_begin + span_begin;
+    const uint32_t tail_bits = FIRST ? (uint32_t)(first.ft * 8 - 32 * (SW - 1)) : 32u;
+    const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
     __syncthreads();
 
     auto load_tile = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
         const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+        const bool tile_inside = FIRST && (int64_t)(((span_first + done + tile_rows) * (uint64_t)first.stride_bytes) >> 2) + SW + 1 <= first.src_words;
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
             const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
             if (in_tile < tile_rows) {
-                const uint32_t *rp = src + (span_first + done + in_tile) * RW;
+                if (FIRST) {
+                    load_first_row<NS, F32>(row[j], src, span_first + done + in_tile, first, tile_inside, tail_mask);
+                } else {
+                    const uint32_t *rp = src + (span_first + done + in_tile) * RW;
 #pragma unroll
-                for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+                    for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+                }
             }
         }
     };
@@ -977,28 +1025,34 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
     if (job.has[1]) flush_tile(main0 + n_acc, side0 + n_acc, ft, B, Bp, pool + job.hist_off[1], kH2Block);
 }
 
-// Rows that stayed in place through two levels (hist_keep_kernel, hist2_kernel) are put in order again, three
-// levels at once: a row is taken down from its segment's split through the child's and the grandchild's (heap
-// positions 0; 1, 2; 3..6) and stored on the left or right side of the grandchild's range, left rows from the
-// front, right rows from the back, room reserved per tile with one 64-bit atomic per (grandchild, side) on the
-// grandchild's cursor (4 * job + grandchild: low word left rows handed out, high word right rows).  A row that
-// reaches a node without a split is dropped: nothing reads the rows of a leaf again.  No histogram here: four
-// grandchildren would need four of them in LDS; the built children are added up afterwards from their (then
-// contiguous) records.  Two tiles are in flight as in part_hist_kernel; a row's category is 2 * grandchild +
-// (0 left, 1 right).
+// Rows that stayed in place below their segment's own split are put in order again, LEVELS levels at once: a row
+// is taken down from the segment's split through those of the nodes below (heap positions 0; 1, 2; 3..6) to a
+// target node -- a child (LEVELS = 2) or a grandchild (LEVELS = 3) of the segment -- and stored on the left or
+// right side of the target's range, left rows from the front, right rows from the back, room reserved per tile
+// with one 64-bit atomic per target on its cursor ((4 * job + target) * kCursorStride: low word left rows handed
+// out, high word right rows).  A row that reaches a node without a split is dropped: nothing reads the rows of a
+// leaf again.  No histogram here: several targets would need as many of them in LDS; the built children are added
+// up afterwards from their (then contiguous) records.  Two tiles are in flight as in part_hist_kernel; a row's
+// category is 2 * target + (0 left, 1 right).
+// FIRST: the rows come from the caller's packed matrix and the pair array (fp32 pairs where F32, rounded here as
+// in part_hist_first_kernel) and leave as records; else they are records already.
 constexpr int kM3Block = 512;
-template <int NS>
-__global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
+template <int NS, int LEVELS, bool FIRST, bool F32>
+__global__ __launch_bounds__(kM3Block, 2) void move_levels_kernel(
     const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, uint64_t dst_rows, uint32_t missing,
-    const Move3Job *__restrict__ jobs, int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor) {
+    const Move3Job *__restrict__ jobs, int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor,
+    MoveFirst first) {
     constexpr int SW = (NS + 3) / 4;
     constexpr int RW = record_words(NS);
     constexpr int BLK = kM3Block, ROWS = kPFRows, TILE = BLK * ROWS, WAVES = BLK / 64, NW = TILE / 64;
-    static_assert(WAVES >= 4, "one wave per grandchild");
+    constexpr int NT = 1 << (LEVELS - 1);   // targets per segment
+    constexpr int NC = 2 * NT;              // categories
+    static_assert(LEVELS == 2 || LEVELS == 3, "two or three levels of splits");
+    static_assert(WAVES >= NT, "one wave per target");
     static_assert(NW == 32, "a category's tile counts are scanned by half a wave");
     __shared__ Move3Job sjob;
-    __shared__ uint32_t cnt[2][NW][8];
-    __shared__ uint32_t base_s[2][8];
+    __shared__ uint32_t cnt[2][NW][NC];
+    __shared__ uint32_t base_s[2][NC];
     int lo = 0, hi = n_jobs;   // last job with tile_begin <= this span
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -1014,6 +1068,9 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t span_first = (uint64_t)job.seg_begin + span_begin;
     const uint64_t below_me = (1ull << lane) - 1ull;
+    // FIRST: valid bits of the last symbol word of a row
+    const uint32_t tail_bits = FIRST ? (uint32_t)(first.ft * 8 - 32 * (SW - 1)) : 32u;
+    const uint32_t tail_mask = tail_bits >= 32 ? 0xffffffffu : ((1u << tail_bits) - 1u);
 
     auto symbol = [&](const uint32_t (&row)[RW], uint32_t f) __attribute__((always_inline)) -> uint32_t {
         const uint32_t sa = 0x0C0C0C00u | (f < 8u ? f : 0x0Cu), sb = 0x0C0C0C00u | (f >= 8u ? f - 8u : 0x0Cu);
@@ -1026,13 +1083,20 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
     };
     auto load_tile = [&](uint32_t (&row)[ROWS][RW], uint32_t done) __attribute__((always_inline)) {
         const uint32_t tile_rows = span_rows - done < (uint32_t)TILE ? span_rows - done : (uint32_t)TILE;
+        // FIRST: every word an unaligned row load of this tile can touch lies inside the source buffer
+        const bool tile_inside = FIRST && (int64_t)(((span_first + done + tile_rows) * (uint64_t)first.stride_bytes) >> 2) + SW + 1 <= first.src_words;
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
             const uint32_t in_tile = (uint32_t)(j * WAVES + wave) * 64u + (uint32_t)lane;
             if (in_tile < tile_rows) {
-                const uint32_t *rp = src + (span_first + done + in_tile) * RW;
+                const uint64_t p = span_first + done + in_tile;
+                if (FIRST) {
+                    load_first_row<NS, F32>(row[j], src, p, first, tile_inside, tail_mask);
+                } else {
+                    const uint32_t *rp = src + p * RW;
 #pragma unroll
-                for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+                    for (int k = 0; k < RW; ++k) row[j][k] = rp[k];
+                }
             }
         }
     };
@@ -1043,17 +1107,21 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
         for (int j = 0; j < ROWS; ++j) {
             const int w = j * WAVES + wave;
             const uint32_t in_tile = (uint32_t)w * 64u + (uint32_t)lane;
-            uint32_t c = 8u;   // dropped
+            uint32_t c = (uint32_t)NC;   // dropped
             if (in_tile < tile_rows) {
                 const uint32_t p1 = goes_left(row[j], 0u) ? 1u : 2u;
                 if (job.has[p1]) {
-                    const uint32_t p2 = 2u * p1 + (goes_left(row[j], p1) ? 1u : 2u);
-                    if (job.has[p2]) c = 2u * (p2 - 3u) + (goes_left(row[j], p2) ? 0u : 1u);
+                    if (LEVELS == 2) {
+                        c = 2u * (p1 - 1u) + (goes_left(row[j], p1) ? 0u : 1u);
+                    } else {
+                        const uint32_t p2 = 2u * p1 + (goes_left(row[j], p1) ? 1u : 2u);
+                        if (job.has[p2]) c = 2u * (p2 - 3u) + (goes_left(row[j], p2) ? 0u : 1u);
+                    }
                 }
             }
             uint32_t r = 0;
 #pragma unroll
-            for (uint32_t k = 0; k < 8u; ++k) {
+            for (uint32_t k = 0; k < (uint32_t)NC; ++k) {
                 const uint64_t b = __ballot(c == k);
                 if (c == k) r = (uint32_t)__popcll(b & below_me);
                 if (lane == 0) cnt[par][w][k] = (uint32_t)__popcll(b);
@@ -1062,8 +1130,8 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
             rank[j] = r;
         }
         __syncthreads();
-        if (wave < 4) {   // wave g: places of grandchild g's left rows (lanes 0..31) and right rows (lanes 32..63)
-                          // inside the tile, and the tile's room in the grandchild's range: one atomic for both sides
+        if (wave < NT) {   // wave g: places of target g's left rows (lanes 0..31) and right rows (lanes 32..63)
+                           // inside the tile, and the tile's room in the target's range: one atomic for both sides
             const int half = lane >> 5, wl = lane & 31;
             const uint32_t v = cnt[par][wl][2 * wave + half];
             uint32_t x = v;
@@ -1086,7 +1154,7 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
         for (int j = 0; j < ROWS; ++j) {
             const int w = j * WAVES + wave;
             const uint32_t c = cat[j];
-            if (c < 8u) {
+            if (c < (uint32_t)NC) {
                 const uint32_t g = c >> 1;
                 const uint32_t off = base_s[par][c] + cnt[par][w][c] + rank[j];
                 const uint64_t q = (c & 1u) ? (uint64_t)job.node_begin[g] + job.node_len[g] - 1u - off : (uint64_t)job.node_begin[g] + off;
@@ -1112,7 +1180,6 @@ __global__ __launch_bounds__(kM3Block, 2) void move3_kernel(
         done += TILE;
     }
 }
-
 
 }  // namespace
 
@@ -1275,25 +1342,31 @@ hipError_t launch_ph(const PHArgs &a) {
                                                                    a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
 }
-template <int NS, bool CHK>
-hipError_t launch_keep(const PHArgs &a) {
+template <int NS, bool CHK, bool FIRST, bool F32>
+hipError_t launch_keep_as(const PHArgs &a) {
     GbtLdsGuard lds_guard(a.lds);
     if (lds_guard.needed) {
-        hipError_t e = hipFuncSetAttribute((const void *)hist_keep_kernel<NS, CHK>,
+        hipError_t e = hipFuncSetAttribute((const void *)hist_keep_kernel<NS, CHK, FIRST, F32>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
     }
-    hist_keep_kernel<NS, CHK><<<a.n_spans, kKeepBlock, a.lds, a.s>>>(a.src, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
-                                                                     a.rows_per_span, a.cursor, a.pool);
+    const MoveFirst mf{a.src_stride_bytes, a.src_words, a.src_gq, a.sgf, a.shf, a.ft};
+    hist_keep_kernel<NS, CHK, FIRST, F32><<<a.n_spans, kKeepBlock, a.lds, a.s>>>(a.src, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
+                                                                                 a.rows_per_span, a.cursor, a.pool, mf);
     return hipGetLastError();
 }
+template <int NS, bool CHK>
+hipError_t launch_keep(const PHArgs &a, bool first) {
+    if (!first) return launch_keep_as<NS, CHK, false, false>(a);
+    return a.src_fp32 ? launch_keep_as<NS, CHK, true, true>(a) : launch_keep_as<NS, CHK, true, false>(a);
+}
 template <bool CHK>
-hipError_t pick_keep(int ft, const PHArgs &a) {
-    if (ft <= 4) return launch_keep<4, CHK>(a);
-    if (ft <= 8) return launch_keep<8, CHK>(a);
-    if (ft <= 12) return launch_keep<12, CHK>(a);
-    if (ft == 13) return launch_keep<13, CHK>(a);
-    return launch_keep<16, CHK>(a);
+hipError_t pick_keep(int ft, const PHArgs &a, bool first) {
+    if (ft <= 4) return launch_keep<4, CHK>(a, first);
+    if (ft <= 8) return launch_keep<8, CHK>(a, first);
+    if (ft <= 12) return launch_keep<12, CHK>(a, first);
+    if (ft == 13) return launch_keep<13, CHK>(a, first);
+    return launch_keep<16, CHK>(a, first);
 }
 template <bool CHK, bool FIRST>
 hipError_t pick_ph(int ft, const PHArgs &a) {
@@ -1377,6 +1450,21 @@ hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B,
                : pick_hist2<false>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool);
 }
 int gbt_move3_tile() { return kM3Block * kPFRows; }
+namespace {
+template <int LEVELS, bool FIRST, bool F32>
+hipError_t launch_move(hipStream_t s, int ns, int n_spans, const uint32_t *src, uint32_t *dst, uint64_t dst_rows, uint32_t missing,
+                       const Move3Job *jobs, int n_jobs, uint32_t rows_per_span, unsigned long long *cursor, const MoveFirst &mf) {
+#define GBT_MV(NS_) move_levels_kernel<NS_, LEVELS, FIRST, F32><<<n_spans, kM3Block, 0, s>>>(src, dst, dst_rows, missing, jobs, n_jobs, \
+                                                                                             rows_per_span, cursor, mf)
+    if (ns == 4) GBT_MV(4);
+    else if (ns == 8) GBT_MV(8);
+    else if (ns == 12) GBT_MV(12);
+    else if (ns == 13) GBT_MV(13);
+    else GBT_MV(16);
+#undef GBT_MV
+    return hipGetLastError();
+}
+}  // namespace
 hipError_t gbt_launch_move3(gbt_ctx *ctx, const uint32_t *src_records, uint32_t *dst_records, int64_t dst_rows, int F,
                             uint32_t missing, const Move3Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
                             unsigned long long *cursor, bool cursors_are_zero) {
@@ -1386,16 +1474,25 @@ hipError_t gbt_launch_move3(gbt_ctx *ctx, const uint32_t *src_records, uint32_t 
         hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 4 * (int64_t)n_jobs * kCursorStride);
         if (e != hipSuccess) return e;
     }
-    const int ns = slots_for(F);
-#define GBT_M3(NS_) move3_kernel<NS_><<<n_spans, kM3Block, 0, ctx->stream>>>(src_records, dst_records, (uint64_t)dst_rows, missing, \
-                                                                             jobs, n_jobs, rows_per_span, cursor)
-    if (ns == 4) GBT_M3(4);
-    else if (ns == 8) GBT_M3(8);
-    else if (ns == 12) GBT_M3(12);
-    else if (ns == 13) GBT_M3(13);
-    else GBT_M3(16);
-#undef GBT_M3
-    return hipGetLastError();
+    return launch_move<3, false, false>(ctx->stream, slots_for(F), n_spans, src_records, dst_records, (uint64_t)dst_rows, missing,
+                                        jobs, n_jobs, rows_per_span, cursor, MoveFirst{});
+}
+hipError_t gbt_launch_move2_first(gbt_ctx *ctx, const uint32_t *packed, int64_t packed_words, const int32_t *gq,
+                                  const float *gpair_fp32, double sg, double sh, uint32_t *dst_records, int64_t dst_rows, int F,
+                                  uint32_t missing, const Move3Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                                  unsigned long long *cursor, bool cursors_are_zero) {
+    if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
+    if (F < 1 || F > 16 || rows_per_span == 0 || dst_rows < 0 || (!gq && !gpair_fp32)) return hipErrorInvalidValue;
+    if (!cursors_are_zero) {
+        hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 4 * (int64_t)n_jobs * kCursorStride);
+        if (e != hipSuccess) return e;
+    }
+    const MoveFirst mf{(int64_t)F, packed_words, gpair_fp32 ? (const int2 *)gpair_fp32 : (const int2 *)gq, (float)sg, (float)sh, F};
+    if (gpair_fp32)
+        return launch_move<2, true, true>(ctx->stream, slots_for(F), n_spans, packed, dst_records, (uint64_t)dst_rows, missing, jobs,
+                                          n_jobs, rows_per_span, cursor, mf);
+    return launch_move<2, true, false>(ctx->stream, slots_for(F), n_spans, packed, dst_records, (uint64_t)dst_rows, missing, jobs,
+                                       n_jobs, rows_per_span, cursor, mf);
 }
 
 int gbt_part_hist_record_words(int F) { return record_words(slots_for(F)); }
@@ -1417,10 +1514,10 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
                    packed_words, fp32 ? (const int2 *)gpair_fp32 : (const int2 *)gq, fp32, (float)sg, (float)sh, dst_records,
                    F, B, Bp, missing, jobs, n_jobs, rows_per_span, cursor, hist_pool};
     const bool chk = missing < 256u || B < 256;
-    if (!first && dst_records == nullptr && keep_lds(F, B) <= ctx->lds_per_block) {   // records that stay in place
+    if (dst_records == nullptr && keep_lds(F, B) <= ctx->lds_per_block) {   // rows that stay in place
         PHArgs k = a;
         k.lds = keep_lds(F, B);
-        return chk ? pick_keep<true>(F, k) : pick_keep<false>(F, k);
+        return chk ? pick_keep<true>(F, k, first) : pick_keep<false>(F, k, first);
     }
     if (first) return chk ? pick_ph<true, true>(F, a) : pick_ph<false, true>(F, a);
     return chk ? pick_ph<true, false>(F, a) : pick_ph<false, false>(F, a);
