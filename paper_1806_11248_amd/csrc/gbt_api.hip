@@ -441,11 +441,12 @@ extern "C" int32_t gbt_gradients(gbt_ctx *ctx, int32_t objective, const float *m
 static int32_t gpair_scale_impl(gbt_ctx *ctx, const float *gpair, int64_t n, double *scale, void *ws,
                                 int *uniform_h = nullptr, float *h_value = nullptr, const uint32_t *bounds_dev = nullptr) {
     if (!bounds_dev) GBT_HIP(ctx, gbt_launch_absmax(ctx->stream, gpair, n, (uint32_t *)ws));
-    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), bounds_dev ? (const void *)bounds_dev : (const void *)ws, 16,
+    const int stride = bounds_dev ? kBoundsStride : 1;   // (gbt_launch_gradients keeps its four words on lines of their own)
+    GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), bounds_dev ? (const void *)bounds_dev : (const void *)ws, (3 * stride + 1) * 4,
                                 hipMemcpyDeviceToHost, ctx->stream));
     GBT_SYNC(ctx);
     uint32_t bits2[4];
-    memcpy(bits2, rb(ctx), 16);
+    for (int k = 0; k < 4; ++k) memcpy(&bits2[k], rb(ctx) + (size_t)k * stride * 4, 4);
     GBT_REQUIRE(ctx, bits2[0] < 0x7f800000u && bits2[1] < 0x7f800000u, GBT_EINVAL,
                 "gradient pairs contain a non-finite value");
     GBT_REQUIRE(ctx, bits2[2] == 0, GBT_EINVAL, "gradient pairs contain a negative hessian");

@@ -180,6 +180,9 @@ hipError_t gbt_launch_to_fixed(hipStream_t s, const float *gpair, int64_t n, dou
                                int32_t *gq, int64_t *sums_out);
 hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *row_idx, int64_t n_rows,
                              int64_t *out2 /* zeroed by the launcher */);
+// bounds (may be NULL): 4 * kBoundsStride words, cleared here; word k * kBoundsStride receives what word k of
+// gbt_launch_absmax's output holds for these pairs
+constexpr int kBoundsStride = 32;
 hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margin, const float *label,
                                 int64_t n, float *gpair, uint32_t *bounds = nullptr);
 hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const int64_t *child,

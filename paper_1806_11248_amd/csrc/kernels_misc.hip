@@ -235,7 +235,7 @@ __device__ __forceinline__ float2 gradient_pair(int objective, float margin, flo
 // negative h, ~smallest |h|), reduced on the way so that the pairs need not be read again for them.
 __global__ __launch_bounds__(kBlock) void gradients_kernel(int objective, const float *__restrict__ margin,
                                                            const float *__restrict__ label, int64_t n,
-                                                           float2 *__restrict__ gp, int vec, uint32_t *bounds) {
+                                                           float2 *__restrict__ gp, int vec, uint32_t *bounds, int nt) {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, nthreads = (int64_t)gridDim.x * blockDim.x;
     uint32_t mg = 0, mh = 0, neg = 0, lh = 0xffffffffu;
     auto note = [&](const float2 &v) {
@@ -255,12 +255,18 @@ __global__ __launch_bounds__(kBlock) void gradients_kernel(int objective, const 
             const float4 m = m4[i], y = y4[i];
             const float2 a = gradient_pair(objective, m.x, y.x), b = gradient_pair(objective, m.y, y.y);
             const float2 c = gradient_pair(objective, m.z, y.z), d = gradient_pair(objective, m.w, y.w);
-            // Non-temporal stores: written the ordinary way, the last few hundred MB of pairs are still waiting in the
-            // memory-side cache when the kernel ends, and their write-back then competes with whatever streams next
-            // (measured: the root histogram launch right behind takes 0.52 ms instead of 0.48 on 115M rows).
-            const f4v s0 = {a.x, a.y, b.x, b.y}, s1 = {c.x, c.y, d.x, d.y};
-            __builtin_nontemporal_store(s0, (f4v *)&o4[2 * i]);
-            __builtin_nontemporal_store(s1, (f4v *)&o4[2 * i + 1]);
+            // nt: non-temporal stores.  Written the ordinary way, the last few hundred MB of an array much larger than
+            // the memory-side cache are still waiting there when the kernel ends, and their write-back then competes
+            // with whatever streams next (measured: the root histogram launch right behind takes 0.52 ms instead of
+            // 0.48 on 115M rows).  Pairs that fit the cache are better left in it for the launch that reads them.
+            if (nt) {
+                const f4v s0 = {a.x, a.y, b.x, b.y}, s1 = {c.x, c.y, d.x, d.y};
+                __builtin_nontemporal_store(s0, (f4v *)&o4[2 * i]);
+                __builtin_nontemporal_store(s1, (f4v *)&o4[2 * i + 1]);
+            } else {
+                o4[2 * i] = make_float4(a.x, a.y, b.x, b.y);
+                o4[2 * i + 1] = make_float4(c.x, c.y, d.x, d.y);
+            }
             note(a);
             note(b);
             note(c);
@@ -296,10 +302,11 @@ __global__ __launch_bounds__(kBlock) void gradients_kernel(int objective, const 
             neg |= red[2][w];
             lh = min(lh, red[3][w]);
         }
-        atomicMax(&bounds[0], mg);
-        atomicMax(&bounds[1], mh);
-        if (neg) atomicOr(&bounds[2], 1u);
-        atomicMax(&bounds[3], ~lh);
+        // (a word per 128-byte line: atomics on words of one line take turns like atomics on one address)
+        atomicMax(&bounds[0 * kBoundsStride], mg);
+        atomicMax(&bounds[1 * kBoundsStride], mh);
+        if (neg) atomicOr(&bounds[2 * kBoundsStride], 1u);
+        atomicMax(&bounds[3 * kBoundsStride], ~lh);
     }
 }
 
@@ -735,13 +742,15 @@ hipError_t gbt_launch_sum_gq(hipStream_t s, const int32_t *gq, const uint32_t *r
 hipError_t gbt_launch_gradients(hipStream_t s, int objective, const float *margin, const float *label,
                                 int64_t n, float *gpair, uint32_t *bounds) {
     if (bounds) {
-        hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)bounds, 0, 2);
+        hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)bounds, 0, 2 * kBoundsStride);
         if (e != hipSuccess) return e;
     }
     if (n <= 0) return hipSuccess;
     const int vec = ((((uintptr_t)margin | (uintptr_t)label | (uintptr_t)gpair) & 15u) == 0) ? 1 : 0;
-    gradients_kernel<<<grid_for(n, kBlock * 4, 8192), kBlock, 0, s>>>(objective, margin, label, n,
-                                                                      (float2 *)gpair, vec, bounds);
+    // with bounds: no more workgroups than are resident at once, each ends with one set of atomics
+    gradients_kernel<<<grid_for(n, kBlock * 4, bounds ? 2048 : 8192), kBlock, 0, s>>>(objective, margin, label, n,
+                                                                      (float2 *)gpair, vec, bounds,
+                                                                      (size_t)n * sizeof(float2) > ((size_t)192 << 20) ? 1 : 0);
     return hipGetLastError();
 }
 hipError_t gbt_launch_subtract_one(hipStream_t s, const int64_t *parent, const int64_t *child,
