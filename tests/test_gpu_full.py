@@ -133,6 +133,30 @@ def _full_case(ctx, oracle, cfg, csr, rounds, check_root_hist=True, sparse_rows=
         for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
                   "sumG", "sumH"):
             assert np.array_equal(bare[k][:nn], tree[k][:nn]), k
+        # ... and as bench.py calls it: the whole iteration in one call (gradients of the GPU's own margins, tree,
+        # margin update).  Its pairs are the GPU's; where those equal the oracle's bit for bit its tree must be the
+        # tree judged above, else the tree the separate calls grow on the same pairs.
+        t0 = time.time()
+        gp_b = torch.empty((n, 2), dtype=torch.float32, device="cuda")
+        m_b = torch.empty_like(margin_gpu)
+        bparams = g.make_params(max_depth=p["max_depth"], max_bins=B, lam=p["lam"], gamma=p["gamma"],
+                                min_child_weight=p["min_child_weight"], eta=p["eta"], objective=p["objective"])
+        tree_b = ctx.boost_round(packed, bits, n, F, ms, nb, cuts, y_t, margin_gpu, m_b, gp_b, bparams)
+        torch.cuda.synchronize()
+        same_pairs = bool(torch.equal(gp_b, gp_t))
+        assert np.array_equal(gp_b.cpu().numpy(), gp_gpu)
+        want = bare if same_pairs else ctx.grow_tree(packed, bits, n, F, ms, nb, cuts, gp_b, params, want_rows=False,
+                                                     want_leaf=False)[0]
+        assert tree_b["n_nodes"] == want["n_nodes"]
+        for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
+                  "sumG", "sumH"):
+            assert np.array_equal(tree_b[k][:want["n_nodes"]], want[k][:want["n_nodes"]]), k
+        m_want = margin_gpu.clone()
+        ctx.predict([want], m_want, p["eta"], packed=packed, bits=bits, missing_sym=ms, n=n, F=F)
+        assert torch.equal(m_b, m_want)
+        del gp_b, m_b, m_want
+        _say(f"  round {r}: the same iteration as one call in {(time.time() - t0) * 1e3:.1f} ms "
+             f"(pairs {'equal to' if same_pairs else 'differ in rounding from'} the oracle's)")
         if sparse_rows:   # the sparse-row kernels: the same tree, row order and leaves, the same margins
             t0 = time.time()
             st, s_rows, s_leaf = ctx.grow_tree_sparse(sp_rowptr, sp_ent, n, sp_nnz, F, nb, cuts, gp_t, params)
