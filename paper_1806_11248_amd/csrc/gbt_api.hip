@@ -1023,6 +1023,9 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
     const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
     const double lambda = params->lambda;
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
+    // every row has the same hessian (squared error always, the first tree of a logistic model): the passes over rows
+    // that stay in place then keep a row count per bin instead of a hessian sum (>= 0: that hessian in fixed point)
+    const int hq_uni = uniform_h ? (int)llrint((double)h_value * scale[1]) : -1;
     if (path == 3 && root_may_split)   // the root's id list, read by the first partition
         GBT_HIP(ctx, gbt_launch_iota_u32(s, W[1].id_rw, n));
     // Where the partition + histogram pass follows (path 2) and rounding in fp32 is exact, the fixed-point pairs
@@ -1547,14 +1550,14 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 if (nomove2)   // the segments' records once more, two histograms per workgroup
                     GBT_HIP(ctx, gbt_launch_hist2(ctx, W[wcur].sym, F, B, (uint32_t)missing_sym, (const Hist2Job *)(ws + L.jobs),
                                                   (int)h2jobs.size(), (int)h2_spans, part_tile,
-                                                  (unsigned long long *)(ws + L.state), pool, true));
+                                                  (unsigned long long *)(ws + L.state), pool, true, hq_uni));
                 else   // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
                     GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
                                                       wcur == 2 ? nullptr : W[wcur].sym, nomove ? nullptr : W[wnext].sym_rw, F, B,
                                                       (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),
                                                       (int)pjobs.size(), (int)tile_cursor, part_tile,
                                                       (unsigned long long *)(ws + L.state), pool, true,
-                                                      pairs_stay_fp32 ? gpair : nullptr, scale[0], scale[1]));
+                                                      pairs_stay_fp32 ? gpair : nullptr, scale[0], scale[1], hq_uni));
                 gbt_prof_end(ctx);
                 // the evaluation launch also hands the cursors (the left counts) to the host and clears them
                 // for the next pass: no copy and no fill launch of their own
@@ -1711,7 +1714,8 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                (double)built_rows * ((double)row_bits / 8.0 + 8.0), child_depth, (double)built_rows * F);
                 GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq, W[wnext].sym, nullptr, F, B,
                                                   (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs), (int)kjobs.size(),
-                                                  (int)kspans, ktile, (unsigned long long *)(ws + L.state), pool, false));
+                                                  (int)kspans, ktile, (unsigned long long *)(ws + L.state), pool, false,
+                                                  nullptr, 1.0, 1.0, hq_uni));
                 gbt_prof_end(ctx);
             }
         } else if (children_need_hist && !with_hist) {

@@ -331,7 +331,8 @@ hipError_t gbt_launch_count2(hipStream_t s, const uint8_t *rows, int64_t stride_
 bool gbt_hist2_ok(const gbt_ctx *ctx, int F, int B);
 hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B, uint32_t missing,
                             const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
-                            unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false);
+                            unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false,
+                            int hq_uniform = -1);   // >= 0: every row has this hessian (fixed point): bins count rows
 // The pass that moves the records of segments whose rows stayed in place for two levels to their grandchildren's
 // children (Move3Job); records of at most 16 byte symbols.  dst_rows: rows the destination holds (a store past it
 // is skipped).  cursor: 4 words per job, cleared here unless the caller says they are zero.
@@ -354,7 +355,10 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
                                 unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero = false,
                                 // first level only: the pairs are these fp32 pairs (not gq), rounded in the pass with
                                 // the scales sg, sh, for which gbt_fix32_ok must hold
-                                const float *gpair_fp32 = nullptr, double sg = 1.0, double sh = 1.0);
+                                const float *gpair_fp32 = nullptr, double sg = 1.0, double sh = 1.0,
+                                // >= 0: every row has this hessian (fixed point); the launches that keep the rows in
+                                // place (dst_records NULL) then count rows per bin instead of adding hessians
+                                int hq_uniform = -1);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,
                                   const LeafSeg *segs, int n_segs, int64_t n, uint32_t *row_idx_out,

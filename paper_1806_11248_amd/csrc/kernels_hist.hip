@@ -321,7 +321,12 @@ __device__ inline int find_span_job(const PartJob *jobs, int n_jobs, uint32_t sp
 // in groups; a group's returned words are tested together for an event (a carry out of the h field,
 // a wrap of the g field): the smallest distance of any of them from one decides whether the
 // per-word bookkeeping runs at all.
-template <int NS, bool CHK, int RW, int GROUP = kPHGroup>
+// UNI: every row of the tree has the same hessian.  A bin's word is then [ sum of g : 46 bits | rows : 18 bits ],
+// added to with an atomic whose result nobody waits for, and nothing is tested; the bin's H is rows times that
+// hessian (flush_tile_uniform).  A workgroup may add at most kUniRowsMax rows to one histogram.
+constexpr int kUniRowsShift = 18;
+constexpr uint32_t kUniRowsMax = (1u << kUniRowsShift) - 1u;
+template <int NS, bool CHK, int RW, int GROUP = kPHGroup, bool UNI = false>
 __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned long long *main_, uint32_t *side,
                                            const int (&pre)[NS], const uint32_t (&selA)[4], const uint32_t (&selB)[4],
                                            int trash, int lane, uint32_t missing, int B) {
@@ -332,7 +337,7 @@ __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned l
     int2 q;
     q.x = (int32_t)(qlo << 4) >> 4;                                  // 28 bits, sign-extended
     q.y = (int32_t)((qlo >> 28) | (qhi << 4));                       // 24 bits
-    const unsigned long long addv = pack_pair(q);
+    const unsigned long long addv = UNI ? ((unsigned long long)(long long)q.x << kUniRowsShift) + 1ull : pack_pair(q);
     const uint32_t hq = (uint32_t)q.y;
     uint32_t W[4], V[(NS + 3) / 4];
 #pragma unroll
@@ -340,6 +345,17 @@ __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned l
 #pragma unroll
     for (int k = 0; k < (NS + 3) / 4; ++k)
         V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
+    if (UNI) {
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            const uint32_t sv = (V[t >> 2] >> (8 * (t & 3))) & 0xffu;
+            bool bad = false;
+            if (CHK) bad = (sv == missing) | (sv >= (uint32_t)B);
+            (void)__hip_atomic_fetch_add(&main_[bad ? trash + lane : pre[t] + (int)sv], addv, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        return;
+    }
 #pragma unroll
     for (int t0 = 0; t0 < NS; t0 += GROUP) {
         int idx[GROUP];
@@ -356,6 +372,20 @@ __device__ __forceinline__ void ph_add_row(const uint32_t (&row)[RW], unsigned l
             }
         }
         pk_check_group<GROUP>(side, idx, old, NS - t0, addv, hq);
+    }
+}
+
+// The merge of a histogram kept in the uniform-hessian form (see ph_add_row) into the node's histogram in HBM.
+__device__ __forceinline__ void flush_tile_uniform(const unsigned long long *main_, int ft, int B, int Bp, int64_t *out,
+                                                   int block, int64_t hq_uniform) {
+    for (int i = threadIdx.x; i < ft * B; i += block) {
+        const int t = i / B, b = i - t * B;
+        const unsigned long long w = main_[t * Bp + b];
+        if (w == 0) continue;
+        const int64_t rows = (int64_t)(w & kUniRowsMax);
+        const int64_t g = ((int64_t)w - rows) >> kUniRowsShift, h = rows * hq_uniform;
+        if (g != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i), (unsigned long long)g);
+        if (h != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i + 1), (unsigned long long)h);
     }
 }
 
@@ -772,10 +802,13 @@ __device__ __forceinline__ void load_first_row(uint32_t (&row)[record_words(NS)]
 // span; the next tile's records are on their way while the current one is handled.
 constexpr int kKeepBlock = 512;
 // FIRST: the rows are read from the caller's matrix and pair array (load_first_row) instead of records.
-template <int NS, bool CHK, bool FIRST, bool F32>
+// UNI: the uniform-hessian form of the LDS histogram (ph_add_row), hq_uniform that hessian in fixed point; a span
+// then has at most kUniRowsMax rows.
+template <int NS, bool CHK, bool FIRST, bool F32, bool UNI>
 __global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
     const uint32_t *__restrict__ src, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs, int n_jobs,
-    uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool, MoveFirst first) {
+    uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool, MoveFirst first,
+    int hq_uniform) {
     constexpr int SW = (NS + 3) / 4;
     constexpr int RW = record_words(NS);
     constexpr int BLK = kKeepBlock, ROWS = kPFRows, TILE = BLK * ROWS, WAVES = BLK / 64;
@@ -846,7 +879,7 @@ __global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
         uint32_t rec[RW], tag;
         if ((uint32_t)lane < n) {
             queue.peek(lane, rec, tag);
-            ph_add_row<NS, CHK, RW>(rec, main_, side, pre, selA, selB, trash, lane, missing, B);
+            ph_add_row<NS, CHK, RW, kPHGroup, UNI>(rec, main_, side, pre, selA, selB, trash, lane, missing, B);
         }
         queue.drop(n);
     };
@@ -883,7 +916,10 @@ __global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
     if (queue.waiting()) add_waiting(queue.waiting());
     if (lane == 0 && my_lefts) atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)my_lefts);
     __syncthreads();
-    if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
+    if (build) {
+        if (UNI) flush_tile_uniform(main_, ft, B, Bp, pool + job.hist_off, BLK, (int64_t)hq_uniform);
+        else flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
+    }
 }
 
 // Rows that were not moved at their segment's split and are not moved now: every row belongs to one
@@ -893,10 +929,10 @@ __global__ __launch_bounds__(kKeepBlock, 2) void hist_keep_kernel(
 // added (through the wave's queue, tagged with the histogram a record goes to); no ranks, no stores, no
 // barriers inside the span.  Left rows of the children are counted in the cursor words 2 * job and 2 * job + 1.
 constexpr int kH2Block = 1024;
-template <int NS, bool CHK>
+template <int NS, bool CHK, bool UNI>
 __global__ __launch_bounds__(kH2Block) void hist2_kernel(
     const uint32_t *__restrict__ src, int ft, int B, int Bp, uint32_t missing, const Hist2Job *__restrict__ jobs,
-    int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
+    int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool, int hq_uniform) {
     constexpr int SW = (NS + 3) / 4;
     constexpr int RW = record_words(NS);
     constexpr int ROWS = kPFRows, TILE = kH2Block * ROWS, WAVES = kH2Block / 64;
@@ -974,7 +1010,7 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
         uint32_t rec[RW], c;
         if ((uint32_t)lane < n) {
             queue.peek(lane, rec, c);
-            ph_add_row<NS, CHK, RW>(rec, main0 + c * n_acc, side0 + c * n_acc, pre, selA, selB, trash, lane, missing, B);
+            ph_add_row<NS, CHK, RW, kPHGroup, UNI>(rec, main0 + c * n_acc, side0 + c * n_acc, pre, selA, selB, trash, lane, missing, B);
         }
         queue.drop(n);
     };
@@ -1021,8 +1057,13 @@ __global__ __launch_bounds__(kH2Block) void hist2_kernel(
         if (my_lefts[1]) atomicAdd(&cursor[(size_t)(2 * ji + 1) * kCursorStride], (unsigned long long)my_lefts[1]);
     }
     __syncthreads();
-    if (job.has[0]) flush_tile(main0, side0, ft, B, Bp, pool + job.hist_off[0], kH2Block);
-    if (job.has[1]) flush_tile(main0 + n_acc, side0 + n_acc, ft, B, Bp, pool + job.hist_off[1], kH2Block);
+    if (UNI) {
+        if (job.has[0]) flush_tile_uniform(main0, ft, B, Bp, pool + job.hist_off[0], kH2Block, (int64_t)hq_uniform);
+        if (job.has[1]) flush_tile_uniform(main0 + n_acc, ft, B, Bp, pool + job.hist_off[1], kH2Block, (int64_t)hq_uniform);
+    } else {
+        if (job.has[0]) flush_tile(main0, side0, ft, B, Bp, pool + job.hist_off[0], kH2Block);
+        if (job.has[1]) flush_tile(main0 + n_acc, side0 + n_acc, ft, B, Bp, pool + job.hist_off[1], kH2Block);
+    }
 }
 
 // Rows that stayed in place below their segment's own split are put in order again, LEVELS levels at once: a row
@@ -1312,6 +1353,7 @@ struct PHArgs {
     uint32_t rows_per_span;
     unsigned long long *cursor;
     int64_t *pool;
+    int hq_uniform = -1;   // >= 0: every row has this hessian (the passes that keep rows in place then count rows instead)
 };
 template <int NS, bool CHK, bool F32>
 hipError_t launch_ph_first_as(const PHArgs &a) {
@@ -1342,23 +1384,30 @@ hipError_t launch_ph(const PHArgs &a) {
                                                                    a.rows_per_span, a.cursor, a.pool);
     return hipGetLastError();
 }
-template <int NS, bool CHK, bool FIRST, bool F32>
+template <int NS, bool CHK, bool FIRST, bool F32, bool UNI>
 hipError_t launch_keep_as(const PHArgs &a) {
     GbtLdsGuard lds_guard(a.lds);
     if (lds_guard.needed) {
-        hipError_t e = hipFuncSetAttribute((const void *)hist_keep_kernel<NS, CHK, FIRST, F32>,
+        hipError_t e = hipFuncSetAttribute((const void *)hist_keep_kernel<NS, CHK, FIRST, F32, UNI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
     }
     const MoveFirst mf{a.src_stride_bytes, a.src_words, a.src_gq, a.sgf, a.shf, a.ft};
-    hist_keep_kernel<NS, CHK, FIRST, F32><<<a.n_spans, kKeepBlock, a.lds, a.s>>>(a.src, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
-                                                                                 a.rows_per_span, a.cursor, a.pool, mf);
+    hist_keep_kernel<NS, CHK, FIRST, F32, UNI><<<a.n_spans, kKeepBlock, a.lds, a.s>>>(a.src, a.ft, a.B, a.Bp, a.missing, a.jobs,
+                                                                                      a.n_jobs, a.rows_per_span, a.cursor, a.pool,
+                                                                                      mf, a.hq_uniform);
     return hipGetLastError();
+}
+template <int NS, bool CHK, bool UNI>
+hipError_t launch_keep_u(const PHArgs &a, bool first) {
+    if (!first) return launch_keep_as<NS, CHK, false, false, UNI>(a);
+    return a.src_fp32 ? launch_keep_as<NS, CHK, true, true, UNI>(a) : launch_keep_as<NS, CHK, true, false, UNI>(a);
 }
 template <int NS, bool CHK>
 hipError_t launch_keep(const PHArgs &a, bool first) {
-    if (!first) return launch_keep_as<NS, CHK, false, false>(a);
-    return a.src_fp32 ? launch_keep_as<NS, CHK, true, true>(a) : launch_keep_as<NS, CHK, true, false>(a);
+    // (the row count of a bin has 18 bits: longer spans take the general form)
+    if (a.hq_uniform >= 0 && a.rows_per_span <= kUniRowsMax) return launch_keep_u<NS, CHK, true>(a, first);
+    return launch_keep_u<NS, CHK, false>(a, first);
 }
 template <bool CHK>
 hipError_t pick_keep(int ft, const PHArgs &a, bool first) {
@@ -1409,35 +1458,43 @@ bool gbt_hist2_ok(const gbt_ctx *ctx, int F, int B) {
     return hist2_lds(F, B) <= ctx->lds_max;   // one workgroup per CU, no static LDS
 }
 namespace {
-template <int NS, bool CHK>
-hipError_t launch_hist2(gbt_ctx *ctx, size_t lds, const uint32_t *records, int ft, int B, int Bp, uint32_t missing,
-                        const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
-                        unsigned long long *cursor, int64_t *pool) {
+template <int NS, bool CHK, bool UNI>
+hipError_t launch_hist2_u(gbt_ctx *ctx, size_t lds, const uint32_t *records, int ft, int B, int Bp, uint32_t missing,
+                          const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                          unsigned long long *cursor, int64_t *pool, int hq_uniform) {
     GbtLdsGuard lds_guard(lds);
     if (lds_guard.needed) {
-        hipError_t e = hipFuncSetAttribute((const void *)hist2_kernel<NS, CHK>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void *)hist2_kernel<NS, CHK, UNI>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds);
         if (e != hipSuccess) return e;
     }
-    hist2_kernel<NS, CHK><<<n_spans, kH2Block, lds, ctx->stream>>>(records, ft, B, Bp, missing, jobs, n_jobs, rows_per_span,
-                                                                   cursor, pool);
+    hist2_kernel<NS, CHK, UNI><<<n_spans, kH2Block, lds, ctx->stream>>>(records, ft, B, Bp, missing, jobs, n_jobs, rows_per_span,
+                                                                        cursor, pool, hq_uniform);
     return hipGetLastError();
+}
+template <int NS, bool CHK>
+hipError_t launch_hist2(gbt_ctx *ctx, size_t lds, const uint32_t *records, int ft, int B, int Bp, uint32_t missing,
+                        const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
+                        unsigned long long *cursor, int64_t *pool, int hq_uniform) {
+    if (hq_uniform >= 0 && rows_per_span <= kUniRowsMax)
+        return launch_hist2_u<NS, CHK, true>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool, hq_uniform);
+    return launch_hist2_u<NS, CHK, false>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool, hq_uniform);
 }
 template <bool CHK>
 hipError_t pick_hist2(int ft, gbt_ctx *ctx, size_t lds, const uint32_t *records, int B, int Bp, uint32_t missing,
                       const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span, unsigned long long *cursor,
-                      int64_t *pool) {
-    if (ft <= 4) return launch_hist2<4, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
-    if (ft <= 8) return launch_hist2<8, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
-    if (ft <= 12) return launch_hist2<12, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
-    if (ft == 13) return launch_hist2<13, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
-    return launch_hist2<16, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool);
+                      int64_t *pool, int hq) {
+    if (ft <= 4) return launch_hist2<4, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool, hq);
+    if (ft <= 8) return launch_hist2<8, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool, hq);
+    if (ft <= 12) return launch_hist2<12, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool, hq);
+    if (ft == 13) return launch_hist2<13, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool, hq);
+    return launch_hist2<16, CHK>(ctx, lds, records, ft, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, pool, hq);
 }
 }  // namespace
 
 hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B, uint32_t missing,
                             const Hist2Job *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
-                            unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero) {
+                            unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero, int hq_uniform) {
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
     if (!cursors_are_zero) {
         hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, 2 * (int64_t)n_jobs * kCursorStride);
@@ -1446,8 +1503,8 @@ hipError_t gbt_launch_hist2(gbt_ctx *ctx, const uint32_t *records, int F, int B,
     const int Bp = padded_bins(B);
     const size_t lds = hist2_lds(F, B);
     const bool chk = missing < 256u || B < 256;
-    return chk ? pick_hist2<true>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool)
-               : pick_hist2<false>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool);
+    return chk ? pick_hist2<true>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool, hq_uniform)
+               : pick_hist2<false>(F, ctx, lds, records, B, Bp, missing, jobs, n_jobs, n_spans, rows_per_span, cursor, hist_pool, hq_uniform);
 }
 int gbt_move3_tile() { return kM3Block * kPFRows; }
 namespace {
@@ -1501,7 +1558,7 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
                                 const uint32_t *src_records, uint32_t *dst_records, int F, int B, uint32_t missing,
                                 const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span,
                                 unsigned long long *cursor, int64_t *hist_pool, bool cursors_are_zero,
-                                const float *gpair_fp32, double sg, double sh) {
+                                const float *gpair_fp32, double sg, double sh, int hq_uniform) {
     if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
     if (!cursors_are_zero) {
         hipError_t e = gbt_launch_fill_u64(ctx->stream, (uint64_t *)cursor, 0, (int64_t)n_jobs * kCursorStride);
@@ -1517,6 +1574,7 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
     if (dst_records == nullptr && keep_lds(F, B) <= ctx->lds_per_block) {   // rows that stay in place
         PHArgs k = a;
         k.lds = keep_lds(F, B);
+        k.hq_uniform = hq_uniform;
         return chk ? pick_keep<true>(F, k, first) : pick_keep<false>(F, k, first);
     }
     if (first) return chk ? pick_ph<true, true>(F, a) : pick_ph<false, true>(F, a);

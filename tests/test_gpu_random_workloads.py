@@ -14,6 +14,7 @@ import time
 
 import numpy as np
 import pytest
+import torch
 
 import grid
 from gpu_util import dev, host_u32, judge_on_grid, tree_kw
@@ -161,6 +162,22 @@ def check_steps_sparse_predict(ctx, oracle, seed):
         assert nl2 == nl and np.array_equal(host_u32(r2), out)
     else:   # nothing worth a split: the GPU may name a candidate without gain (it does not count rows), no more
         assert not sp["valid"] or not sp["gain"] > 0, (sp, spo)
+    # one boosting iteration as one call and as three: the same pairs, tree and margins to the last bit
+    objective = ("squared", "logistic")[seed % 2]
+    y_t = dev((rng.standard_normal(n) if objective == "squared" else (rng.random(n) < 0.4)).astype(np.float32))
+    m_in = dev((rng.standard_normal(n) * (3.0 if seed % 3 else 0.0)).astype(np.float32))
+    bparams = g.make_params(max_depth=p["max_depth"], max_bins=B, lam=p["lam"], gamma=p["gamma"],
+                            min_child_weight=p["min_child_weight"], eta=0.3, objective=objective)
+    gp3 = ctx.gradients(objective, m_in, y_t)
+    t3, _, _ = ctx.grow_tree(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"], gdev["cuts"], gp3, bparams,
+                             want_rows=False, want_leaf=False)
+    m3 = ctx.predict([t3], m_in.clone(), 0.3, packed=gdev["packed"], bits=gdev["bits"], missing_sym=gdev["missing"], n=n, F=F)
+    gp1, m1 = torch.empty_like(gp3), torch.empty_like(m_in)
+    t1 = ctx.boost_round(gdev["packed"], gdev["bits"], n, F, gdev["missing"], gdev["nb"], gdev["cuts"], y_t, m_in, m1, gp1,
+                         bparams)
+    assert torch.equal(gp1, gp3) and torch.equal(m1, m3) and t1["n_nodes"] == t3["n_nodes"]
+    for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain", "sumG", "sumH"):
+        assert np.array_equal(t1[k][:t3["n_nodes"]], t3[k][:t3["n_nodes"]]), k
     if F * B > 65535:   # beyond the 16-bit global bin ids of the sparse layout
         return
     # sparse rows: the same tree as the oracle's and as the dense layout's, to the last bit
