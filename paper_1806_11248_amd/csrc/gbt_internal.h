@@ -356,8 +356,7 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
                                 // first level only: the pairs are these fp32 pairs (not gq), rounded in the pass with
                                 // the scales sg, sh, for which gbt_fix32_ok must hold
                                 const float *gpair_fp32 = nullptr, double sg = 1.0, double sh = 1.0,
-                                // >= 0: every row has this hessian (fixed point); the launches that keep the rows in
-                                // place (dst_records NULL) then count rows per bin instead of adding hessians
+                                // >= 0: every row has this hessian (fixed point): bins count rows instead of adding hessians
                                 int hq_uniform = -1);
 // LeafSeg.buf: 0/1 = id buffers buf0/buf1, 2 = the id of position p is p.
 hipError_t gbt_launch_leaf_gather(hipStream_t s, const uint32_t *buf0, const uint32_t *buf1,

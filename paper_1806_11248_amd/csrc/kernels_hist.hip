@@ -428,11 +428,11 @@ struct WaveQueue {
 
 // F32: the pairs are still fp32 (src_gq then points at float2): each is rounded to fixed point here, in fp32
 // arithmetic, which is exact for the power-of-two scales sgf, shf the launcher accepts (gbt_fix32_ok)
-template <int NS, bool CHK, bool F32>
+template <int NS, bool CHK, bool F32, bool UNI>
 __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
     const uint32_t *__restrict__ src, int64_t src_stride_bytes, int64_t src_words, const int2 *__restrict__ src_gq,
     float sgf, float shf, uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing, const PartJob *__restrict__ jobs,
-    int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool) {
+    int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor, int64_t *__restrict__ pool, int hq_uniform) {
     constexpr int SW = (NS + 3) / 4;        // words that hold symbols
     constexpr int RW = record_words(NS);    // words of a record
     extern __shared__ unsigned long long lds[];
@@ -560,7 +560,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
 #pragma unroll
         for (int j = 0; j < kPHRows; ++j) {
             // (groups of 5 atomics here: with 8 rows of raw words per thread, 7 results in flight spill registers)
-            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW, 5>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
+            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW, 5, UNI>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
         }
         if (nomove) continue;
         if (wave == 0 && lane == 63) {
@@ -594,7 +594,10 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
     }
     if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)my_lefts);
     __syncthreads();
-    if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, kPHBlock);
+    if (build) {
+        if (UNI) flush_tile_uniform(main_, ft, B, Bp, pool + job.hist_off, kPHBlock, (int64_t)hq_uniform);
+        else flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, kPHBlock);
+    }
 }
 
 // Levels below the first: the source is records.  A thread holds two sets of kPFRows records, one
@@ -602,11 +605,11 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_first_kernel(
 // meanwhile, so that the loads never start from an empty pipe behind a tile's barriers.
 // (The wave queue of the passes that keep rows in place does not pay here: its LDS leaves room for two workgroups
 // per CU instead of four, and the barriers of a moving tile then cost more than the packed atomics save.)
-template <int NS, bool CHK>
+template <int NS, bool CHK, bool UNI>
 __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, int ft, int B, int Bp, uint32_t missing,
     const PartJob *__restrict__ jobs, int n_jobs, uint32_t rows_per_span, unsigned long long *__restrict__ cursor,
-    int64_t *__restrict__ pool) {
+    int64_t *__restrict__ pool, int hq_uniform) {
     constexpr int SW = (NS + 3) / 4;
     constexpr int RW = record_words(NS);
     constexpr int BLK = kPHBlock, ROWS = kPFRows;
@@ -709,7 +712,7 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
         }
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
-            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
+            if ((takebits >> j) & 1u) ph_add_row<NS, CHK, RW, kPHGroup, UNI>(row[j], main_, side, pre, selA, selB, trash, lane, missing, B);
         }
         if (nomove) return;
         if (wave == 0 && lane == 63) {
@@ -753,7 +756,10 @@ __global__ __launch_bounds__(kPHBlock, 4) void part_hist_kernel(
     }
     if (nomove && lane == 0 && my_lefts) atomicAdd(&cursor[(size_t)ji * kCursorStride], (unsigned long long)my_lefts);
     __syncthreads();
-    if (build) flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
+    if (build) {
+        if (UNI) flush_tile_uniform(main_, ft, B, Bp, pool + job.hist_off, BLK, (int64_t)hq_uniform);
+        else flush_tile(main_, side, ft, B, Bp, pool + job.hist_off, BLK);
+    }
 }
 
 // Rows still in the caller's packed matrix (byte symbols, row p at byte p * stride_bytes) with their pairs in an
@@ -1355,34 +1361,42 @@ struct PHArgs {
     int64_t *pool;
     int hq_uniform = -1;   // >= 0: every row has this hessian (the passes that keep rows in place then count rows instead)
 };
-template <int NS, bool CHK, bool F32>
+template <int NS, bool CHK, bool F32, bool UNI>
 hipError_t launch_ph_first_as(const PHArgs &a) {
     GbtLdsGuard lds_guard(a.lds);
     if (lds_guard.needed) {
-        hipError_t e = hipFuncSetAttribute((const void *)part_hist_first_kernel<NS, CHK, F32>,
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_first_kernel<NS, CHK, F32, UNI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
     }
-    part_hist_first_kernel<NS, CHK, F32><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
-                                                                              a.sgf, a.shf, a.dst, a.ft, a.B, a.Bp, a.missing,
-                                                                              a.jobs, a.n_jobs, a.rows_per_span, a.cursor, a.pool);
+    part_hist_first_kernel<NS, CHK, F32, UNI><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.src_stride_bytes, a.src_words, a.src_gq,
+                                                                                   a.sgf, a.shf, a.dst, a.ft, a.B, a.Bp, a.missing,
+                                                                                   a.jobs, a.n_jobs, a.rows_per_span, a.cursor, a.pool,
+                                                                                   a.hq_uniform);
     return hipGetLastError();
 }
 template <int NS, bool CHK>
 hipError_t launch_ph_first(const PHArgs &a) {
-    return a.src_fp32 ? launch_ph_first_as<NS, CHK, true>(a) : launch_ph_first_as<NS, CHK, false>(a);
+    const bool uni = a.hq_uniform >= 0 && a.rows_per_span <= kUniRowsMax;   // (a bin's row count has 18 bits)
+    if (uni) return a.src_fp32 ? launch_ph_first_as<NS, CHK, true, true>(a) : launch_ph_first_as<NS, CHK, false, true>(a);
+    return a.src_fp32 ? launch_ph_first_as<NS, CHK, true, false>(a) : launch_ph_first_as<NS, CHK, false, false>(a);
 }
-template <int NS, bool CHK>
-hipError_t launch_ph(const PHArgs &a) {
+template <int NS, bool CHK, bool UNI>
+hipError_t launch_ph_u(const PHArgs &a) {
     GbtLdsGuard lds_guard(a.lds);
     if (lds_guard.needed) {
-        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK>,
+        hipError_t e = hipFuncSetAttribute((const void *)part_hist_kernel<NS, CHK, UNI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
         if (e != hipSuccess) return e;
     }
-    part_hist_kernel<NS, CHK><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
-                                                                   a.rows_per_span, a.cursor, a.pool);
+    part_hist_kernel<NS, CHK, UNI><<<a.n_spans, kPHBlock, a.lds, a.s>>>(a.src, a.dst, a.ft, a.B, a.Bp, a.missing, a.jobs, a.n_jobs,
+                                                                        a.rows_per_span, a.cursor, a.pool, a.hq_uniform);
     return hipGetLastError();
+}
+template <int NS, bool CHK>
+hipError_t launch_ph(const PHArgs &a) {
+    if (a.hq_uniform >= 0 && a.rows_per_span <= kUniRowsMax) return launch_ph_u<NS, CHK, true>(a);
+    return launch_ph_u<NS, CHK, false>(a);
 }
 template <int NS, bool CHK, bool FIRST, bool F32, bool UNI>
 hipError_t launch_keep_as(const PHArgs &a) {
@@ -1569,12 +1583,11 @@ hipError_t gbt_launch_part_hist(gbt_ctx *ctx, const uint32_t *packed, int64_t pa
     const bool fp32 = first && gpair_fp32 != nullptr;
     const PHArgs a{ctx->stream, n_spans, ((size_t)F * Bp + 256) * 12, first ? packed : src_records, first ? (int64_t)F : 0,
                    packed_words, fp32 ? (const int2 *)gpair_fp32 : (const int2 *)gq, fp32, (float)sg, (float)sh, dst_records,
-                   F, B, Bp, missing, jobs, n_jobs, rows_per_span, cursor, hist_pool};
+                   F, B, Bp, missing, jobs, n_jobs, rows_per_span, cursor, hist_pool, hq_uniform};
     const bool chk = missing < 256u || B < 256;
     if (dst_records == nullptr && keep_lds(F, B) <= ctx->lds_per_block) {   // rows that stay in place
         PHArgs k = a;
         k.lds = keep_lds(F, B);
-        k.hq_uniform = hq_uniform;
         return chk ? pick_keep<true>(F, k, first) : pick_keep<false>(F, k, first);
     }
     if (first) return chk ? pick_ph<true, true>(F, a) : pick_ph<false, true>(F, a);
