@@ -392,6 +392,19 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
             pr2 = ctx.profile_read()
             ctx.profile_enable(False)
             out["roofline_hist_root_second_tree"] = roof(pr2, ["hist_root"], hist_kernel + " (pairs of the second boosting round: no common hessian)")
+            if one_call:
+                # ... and the whole step on those pairs: the second round of the same model, repeated (margins in: after
+                # one tree; out: an array of its own), so every launch takes its general form
+                m3 = torch.empty_like(m2)
+                ctx.boost_round(packed, bits, n, F, ms, nb, cuts, y, m2, m3, gp2, params)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    ctx.boost_round(packed, bits, n, F, ms, nb, cuts, y, m2, m3, gp2, params)
+                torch.cuda.synchronize()
+                out["ms_per_step_second_round"] = (time.perf_counter() - t0) * 1e3 / steps
+                log(f"second boosting round (no common hessian): {out['ms_per_step_second_round']:.3f} ms per step")
+                del m3
             del m2, gp2
     if a.predict_trees > 0 and not given and headline:
         # Sec. 2.4 with many trees: boost (untimed), then one gbt_predict call over the raw floats

@@ -124,7 +124,8 @@ typedef struct gbt_tree {
  *   GBT_TUNE_HIST8_STAGGER      [64] 0..128: in 1/1024 of a job's length, how unequal the jobs of that launch are
  *   GBT_TUNE_HIST_RUNTIME_BITS  [0] 1: histogram kernel with a run-time symbol width instead of the compile-time ones
  *   GBT_TUNE_HIST_BLOCK         [512] 256, 512, 1024: threads per histogram workgroup
- *   GBT_TUNE_HIST_LDS_KB        [64] 8..128: cap on a workgroup's LDS histogram (smaller feature tiles, more workgroups per CU)
+ *   GBT_TUNE_HIST_LDS_KB        [64] 8..128: cap on a workgroup's LDS histogram (smaller feature tiles, more workgroups per CU); unset, a shape
+ *                                    that needs two to four feature tiles takes twice the cap where that saves a tile
  *   GBT_TUNE_HIST_JOBS          [8] 1..64: histogram workgroups to aim for per compute unit and launch
  *   GBT_TUNE_HIST_MERGE_RATIO   [96] 1..100000: LDS additions a bin should receive per value a job merges into HBM (longer row pieces)
  *   GBT_TUNE_LOSSGUIDE_BATCH    [16] 1..64: open leaves expanded per round of loss-guided growth

@@ -70,8 +70,8 @@ struct HistPlan {
 // The kernels consume a row slice in register windows of E whole elements and issue an atomic for
 // every slot of a window, used or not.  More tiles than the LDS budget demands cost a pass over the
 // gradient pairs each, so they are taken only when they save at least a fifth of the slots.
-bool plan_tiles(const gbt_ctx *ctx, int F, int B, int bits, HistPlan *p) {
-    p->ft_max = gbt_hist_feature_tile(ctx, F, B);
+bool plan_tiles(const gbt_ctx *ctx, int F, int B, int bits, HistPlan *p, int64_t n_rows = 0) {
+    p->ft_max = gbt_hist_feature_tile(ctx, F, B, n_rows);
     if (p->ft_max < 1) return false;
     const int E = bits == 8 ? 16 : std::min(128 / std::max(bits, 1), 32);
     const int nt_min = (F + p->ft_max - 1) / p->ft_max;
@@ -252,7 +252,8 @@ extern "C" int32_t gbt_create(gbt_ctx **ctx_out, int32_t device, void *stream) {
         if (const char *e10 = getenv("GBT_TUNE_HIST_FIX")) c->hist_fix = atoi(e10) != 0;
         if (const char *e8 = getenv("GBT_TUNE_PART_HIST")) c->part_hist = atoi(e8) != 0;
         if (const char *e6 = getenv("GBT_TUNE_PART_FUSED")) c->part_fused = atoi(e6) != 0;
-        if (const char *e5 = getenv("GBT_TUNE_HIST_LDS_KB")) { int v = atoi(e5); if (v >= 8 && v <= 128) c->hist_lds_kb = v; }
+        c->hist_lds_auto = 1;
+        if (const char *e5 = getenv("GBT_TUNE_HIST_LDS_KB")) { int v = atoi(e5); if (v >= 8 && v <= 128) { c->hist_lds_kb = v; c->hist_lds_auto = 0; } }
         if (const char *e19 = getenv("GBT_TUNE_HIST_MERGE_RATIO")) { int v = atoi(e19); if (v >= 1 && v <= 100000) c->hist_merge_ratio = v; }
         if (const char *e2 = getenv("GBT_TUNE_HIST_JOBS")) { int v = atoi(e2); if (v >= 1 && v <= 64) c->hist_jobs_per_cu = v; }
         size_t lds = prop.sharedMemPerBlock;
@@ -721,7 +722,7 @@ static int32_t hist_uniform(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, 
                             const int32_t *gq, int64_t *hist_out, HistJob *dev_jobs, RootFix *fix, bool uniform_h,
                             int32_t hq_uniform) {
     HistPlan pl;
-    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl, n_rows), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins (%d bytes) exceed the LDS budget", B, B * 16);
     GBT_HIP(ctx, gbt_launch_fill_u64(ctx->stream, (uint64_t *)hist_out, 0, (int64_t)F * B * 2));
     if (n_rows == 0) return GBT_OK;
@@ -949,7 +950,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                                    : grow_layout(n, F, bits, B, max_depth);
     GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
     HistPlan pl;
-    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl), GBT_EUNSUPPORTED,
+    GBT_REQUIRE(ctx, plan_tiles(ctx, F, B, bits, &pl, n), GBT_EUNSUPPORTED,
                 "max_bins = %d: one feature's bins exceed the LDS budget", B);
 
     char *ws = (char *)workspace;

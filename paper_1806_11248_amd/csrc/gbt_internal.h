@@ -39,6 +39,7 @@ struct gbt_ctx {
     int hist_fix;           // 1: the root histogram kernel also converts the gradient pairs where that applies
     int part_hist;          // 1: and the children's histograms in the same pass where that applies
     int hist_lds_kb;        // 0, or a cap on the LDS histogram of one workgroup (more workgroups per CU)
+    int hist_lds_auto;      // 1: hist_lds_kb is the default, which a shape of two to four feature tiles may double to save a tile
     int hist_jobs_per_cu;   // histogram workgroups to aim for per compute unit and launch
     int move_max_words;     // rows of more 32-bit words than this are never moved: only their ids are partitioned
     int hist_merge_ratio;   // LDS additions a bin should receive, on average, per value a job merges into HBM
@@ -206,7 +207,7 @@ hipError_t gbt_launch_histw(gbt_ctx *ctx, const uint32_t *packed, int bits, int6
                             int64_t *hist_pool, const HistJob *jobs, int n_jobs, int max_ft, bool uniform_h,
                             int32_t hq_uniform);
 // Largest feature tile whose LDS histogram fits, and the per-job row count to aim for.
-int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B);
+int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B, int64_t n_rows = 0);   // n_rows: rows of the matrix the tiles are for (0: unknown)
 
 // out receives n_nodes * n_chunks records (node-major); gbt_eval_chunks picks n_chunks.
 int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes);

@@ -1230,7 +1230,8 @@ __global__ __launch_bounds__(kM3Block, 2) void move_levels_kernel(
 
 }  // namespace
 
-int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B) {
+constexpr int64_t kAutoTileMinRows = 4000000;
+int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B, int64_t n_rows) {
     const size_t per_feature = (size_t)padded_bins(B) * 12;   // 8-byte word + 4-byte side counter per bin
     size_t limit = ctx->lds_per_block;
     if (ctx->hist_lds_kb > 0 && (size_t)ctx->hist_lds_kb * 1024 < limit) limit = (size_t)ctx->hist_lds_kb * 1024;
@@ -1238,6 +1239,21 @@ int gbt_hist_feature_tile(const gbt_ctx *ctx, int F, int B) {
     const size_t budget = limit - 256 * 12;                    // the trash row
     int ft = (int)(budget / per_feature);
     if (ft > F) ft = F;
+    // A matrix that needs two to four tiles under the default cap pays for every tile with another pass over its rows
+    // and pairs: where twice the LDS saves a tile, that is worth the halved occupancy (10M x 50 x 257 bins: three tiles
+    // of 17 features -> two of 25, root 0.44 -> 0.35 ms, node histograms 1.21 -> 1.04 ms per tree).  With many tiles
+    // the atomics of a tile's features outweigh the row fetch and the smaller tile wins (2000 features: 25 tiles of
+    // 80 at 0.64 ms against 13 of 160 at 0.87 ms), and so it does on few rows, where workgroups are what is short
+    // (1M x 28: two tiles 0.056 ms, one 0.082 ms).
+    if (ctx->hist_lds_auto && ft >= 1 && n_rows >= kAutoTileMinRows) {
+        const int nt = (F + ft - 1) / ft;
+        const size_t limit2 = std::min<size_t>(ctx->lds_per_block, 2 * limit);
+        if (nt >= 2 && nt <= 4 && limit2 > limit) {
+            int ft2 = (int)((limit2 - 256 * 12) / per_feature);
+            if (ft2 > F) ft2 = F;
+            if (ft2 >= 1 && (F + ft2 - 1) / ft2 < nt) ft = ft2;
+        }
+    }
     return ft;   // 0: one feature's bins do not fit in LDS
 }
 

@@ -26,7 +26,7 @@ pytestmark = pytest.mark.gpu
 # Contexts are created under one of these settings in turn: every path the growers can take (the default
 # choices, rows moved at every level or not at the last one or two or only every third level, the three-launch partition, histograms
 # apart from the partition, pairs rounded in a pass of their own, row ids carried along, one loss-guided
-# expansion per round, run-time bit widths, other workgroup shapes, rows of up to 64 words moved instead of listed,
+# expansion per round, run-time bit widths, other workgroup shapes and LDS tile sizes, rows of up to 64 words moved instead of listed,
 # the 8-bit root histogram by the general kernel, every histogram job a single merge-free piece or many short ones)
 VARIANTS = [
     {},
@@ -40,6 +40,7 @@ VARIANTS = [
     {"GBT_TUNE_LOSSGUIDE_BATCH": "1"},
     {"GBT_TUNE_HIST_RUNTIME_BITS": "1"},
     {"GBT_TUNE_HIST_BLOCK": "256", "GBT_TUNE_HIST_LDS_KB": "16", "GBT_TUNE_HIST_JOBS": "3"},
+    {"GBT_TUNE_HIST_LDS_KB": "128"},
     {"GBT_TUNE_PART_IDS": "0"},
     {"GBT_TUNE_MOVE_MAX_WORDS": "64"},
     {"GBT_TUNE_HIST8": "0"},
