@@ -208,8 +208,12 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
         if not given:
             ctx.gradients(p["objective"], margin_in, y, out=gp)
         if sparse:
-            tree, _, _ = ctx.grow_tree_sparse(rowptr, ent, n, nnz, F, nb, cuts, gp, params, want_rows=outputs,
-                                              want_leaf=outputs)
+            if lossguide:
+                tree, _, _ = ctx.grow_tree_sparse_lossguide(rowptr, ent, n, nnz, F, nb, cuts, gp, lg_params, max_leaves,
+                                                            want_rows=outputs, want_leaf=outputs)
+            else:
+                tree, _, _ = ctx.grow_tree_sparse(rowptr, ent, n, nnz, F, nb, cuts, gp, params, want_rows=outputs,
+                                                  want_leaf=outputs)
             ctx.predict_sparse([tree], margin, eta, rowptr, ent, n, F, p["max_bins"])
             trees.append(tree)
             return

@@ -427,6 +427,19 @@ GBT_API int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const
                       int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
 
 /*
+ * gbt_grow_tree_lossguide over sparse rows: the loss-guided policy of Sec. 2.3 with the
+ * kernels of gbt_grow_tree_sparse; the same tree as gbt_grow_tree_lossguide grows on
+ * the packed matrix of the same symbols.  Arguments as for gbt_grow_tree_sparse plus
+ * max_leaves; tree_out needs capacity >= 2*max_leaves - 1.  Synchronises the stream.
+ */
+GBT_API size_t gbt_grow_tree_sparse_lossguide_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
+                                                              int32_t max_leaves);
+GBT_API int32_t gbt_grow_tree_sparse_lossguide(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                      int64_t nnz, int32_t F, const int32_t *nb, const float *cuts, const float *gpair,
+                      const gbt_params *params, int32_t max_leaves, gbt_tree *tree_out, uint32_t *row_idx_out,
+                      int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
+
+/*
  * One boosting iteration as the loop of Fig. 1 runs it (Sec. 2.5, Alg. 1, Sec. 2.4 in
  * one call): gpair[r] = gradient pair of (margin_in[r], label[r]) under
  * params->objective (as gbt_gradients), one depth-wise tree on those pairs (as

@@ -33,6 +33,7 @@ SYMBOLS = [
     "gbt_profile_enable", "gbt_profile_read", "gbt_measure_stream_read",
     "gbt_sparse_capacity", "gbt_compress_sparse_workspace_bytes", "gbt_compress_sparse_count", "gbt_compress_sparse",
     "gbt_build_hist_sparse", "gbt_grow_tree_sparse_workspace_bytes", "gbt_grow_tree_sparse", "gbt_predict_sparse",
+    "gbt_grow_tree_sparse_lossguide_workspace_bytes", "gbt_grow_tree_sparse_lossguide",
 ]
 
 PROF_LEVELS = 18   # GBT_PROF_LEVELS
@@ -133,6 +134,9 @@ def load():
     L.gbt_grow_tree_sparse_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
     L.gbt_grow_tree_sparse_workspace_bytes.restype = sz
     L.gbt_grow_tree_sparse.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
+    L.gbt_grow_tree_sparse_lossguide_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
+    L.gbt_grow_tree_sparse_lossguide_workspace_bytes.restype = sz
+    L.gbt_grow_tree_sparse_lossguide.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz]
     L.gbt_predict_sparse.argtypes = [vp, vp, i32, vp, vp, i64, i32, i32, f64, vp, vp, sz]
     L.gbt_profile_enable.argtypes = [vp, i32]
     L.gbt_profile_read.argtypes = [vp, vp]
@@ -474,6 +478,23 @@ class Context:
         self._check(self.lib.gbt_grow_tree_sparse(self.h, _ptr(rowptr), _ptr(ent), n, nnz, F, _ptr(nb), _ptr(cuts),
                                                   _ptr(gpair), C.byref(params), C.byref(ts), _ptr(row_idx),
                                                   _ptr(leaf), _ptr(ws), ws.numel()))
+        t["n_nodes"] = int(ts.n_nodes)
+        return t, row_idx, leaf
+
+    def grow_tree_sparse_lossguide(self, rowptr, ent, n, nnz, F, nb, cuts, gpair, params: Params, max_leaves,
+                                   want_leaf=True, want_rows=True):
+        """Loss-guided growth (Sec. 2.3) over sparse rows; returns what grow_tree returns."""
+        t = new_tree_leaves(max_leaves)
+        ts = _tree_struct(t)
+        row_idx = self.empty((n,), torch.int32) if want_rows else None
+        leaf = self.empty((n,), torch.int32) if want_leaf else None
+        ws_bytes = self.lib.gbt_grow_tree_sparse_lossguide_workspace_bytes(n, nnz, F, params.max_bins, max_leaves)
+        if ws_bytes == 0:
+            raise GbtError(EINVAL, "gbt_grow_tree_sparse_lossguide_workspace_bytes rejected the shape")
+        ws = self.workspace("grow", ws_bytes)
+        self._check(self.lib.gbt_grow_tree_sparse_lossguide(self.h, _ptr(rowptr), _ptr(ent), n, nnz, F, _ptr(nb),
+                                                            _ptr(cuts), _ptr(gpair), C.byref(params), max_leaves,
+                                                            C.byref(ts), _ptr(row_idx), _ptr(leaf), _ptr(ws), ws.numel()))
         t["n_nodes"] = int(ts.n_nodes)
         return t, row_idx, leaf
 

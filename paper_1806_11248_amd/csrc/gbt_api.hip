@@ -2226,10 +2226,11 @@ struct SparseGrowLayout {
         order, rank_tbl, total;
     int64_t hist_nodes, level_nodes;
 };
-SparseGrowLayout sparse_grow_layout(int64_t n, int64_t nnz, int F, int B, int max_depth) {
+// hist_nodes: nodes that may own a histogram (ids below it); level_nodes: most nodes split in one round
+SparseGrowLayout sparse_grow_layout_nodes(int64_t n, int64_t nnz, int F, int B, int64_t hist_nodes, int64_t level_nodes) {
     SparseGrowLayout L;
-    L.hist_nodes = max_depth == 0 ? 1 : (((int64_t)1 << max_depth) - 1);
-    L.level_nodes = (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0);
+    L.hist_nodes = hist_nodes;
+    L.level_nodes = level_nodes;
     size_t o = 0;
     L.gq = o; o += gbt_align((size_t)n * 8);
     for (int k = 0; k < 2; ++k) {
@@ -2250,6 +2251,10 @@ SparseGrowLayout sparse_grow_layout(int64_t n, int64_t nnz, int F, int B, int ma
     L.total = o;
     return L;
 }
+SparseGrowLayout sparse_grow_layout(int64_t n, int64_t nnz, int F, int B, int max_depth) {
+    return sparse_grow_layout_nodes(n, nnz, F, B, max_depth == 0 ? 1 : (((int64_t)1 << max_depth) - 1),
+                                    (int64_t)1 << (max_depth > 0 ? max_depth - 1 : 0));
+}
 }  // namespace
 
 extern "C" size_t gbt_grow_tree_sparse_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
@@ -2260,14 +2265,15 @@ extern "C" size_t gbt_grow_tree_sparse_workspace_bytes(int64_t n, int64_t nnz, i
     return sparse_grow_layout(n, nnz, F, max_bins, max_depth).total;
 }
 
-// Alg. 1, depth-wise, over sparse rows: the loop of gbt_grow_tree with the sparse-row kernels.  Rows
-// move without ids through one-launch unordered partitions; leaf ids come from a walk of the finished
-// tree, the row order from a stable sort by leaf rank.
-extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
-                                        int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
-                                        const float *gpair, const gbt_params *params, gbt_tree *tree,
-                                        uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace,
-                                        size_t workspace_bytes) {
+// Alg. 1 over sparse rows under either policy of Sec. 2.3: the loop of grow_impl with the sparse-row kernels (rounds,
+// and for loss-guided growth the physical and the logical tree, exactly as there).  Rows move without ids through
+// one-launch unordered partitions; leaf ids come from a walk of the finished tree, the row order from a stable sort
+// by leaf rank.
+static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                                int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
+                                const float *gpair, const gbt_params *params, int policy, int32_t max_leaves, gbt_tree *tree,
+                                uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace,
+                                size_t workspace_bytes) {
     if (!ctx) return GBT_EINVAL;
     GBT_REQUIRE(ctx, rowptr && ent && nb && cuts && gpair && params && tree && workspace, GBT_EINVAL, "NULL argument");
     const int B = params->max_bins, max_depth = params->max_depth;
@@ -2277,15 +2283,20 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
     if (st != GBT_OK) return st;
     GBT_REQUIRE(ctx, ((uintptr_t)ent & 3) == 0, GBT_EINVAL, "ent must be 4-byte aligned");
     GBT_REQUIRE(ctx, n >= 1 && nnz >= 0 && nnz < ((int64_t)1 << 32) - 64, GBT_EINVAL, "bad n or nnz");
+    const bool lossguide = policy == GBT_POLICY_LOSSGUIDE;
     GBT_REQUIRE(ctx, max_depth >= 0, GBT_EINVAL, "max_depth < 0");
-    GBT_REQUIRE(ctx, max_depth <= kMaxDepth, GBT_EUNSUPPORTED, "max_depth %d > %d", max_depth, kMaxDepth);
+    GBT_REQUIRE(ctx, lossguide || max_depth <= kMaxDepth, GBT_EUNSUPPORTED, "max_depth %d > %d", max_depth, kMaxDepth);
+    GBT_REQUIRE(ctx, !lossguide || (max_leaves >= 1 && max_leaves <= kMaxLeaves), lossguide && max_leaves >= 1 ? GBT_EUNSUPPORTED : GBT_EINVAL,
+                "max_leaves %d outside 1..%d", max_leaves, kMaxLeaves);
     GBT_REQUIRE(ctx, params->lambda >= 0.0, GBT_EINVAL, "lambda < 0");
-    const int64_t cap = ((int64_t)1 << (max_depth + 1)) - 1;
+    const int64_t cap = lossguide ? 2 * (int64_t)max_leaves - 1 : ((int64_t)1 << (max_depth + 1)) - 1;
     GBT_REQUIRE(ctx, tree->capacity >= cap, GBT_EINVAL, "tree capacity %d < %lld", tree->capacity, (long long)cap);
     GBT_REQUIRE(ctx, tree->feature && tree->bin && tree->default_left && tree->left && tree->right &&
                          tree->threshold && tree->weight && tree->gain && tree->sumG && tree->sumH && tree->n_rows,
                 GBT_EINVAL, "tree arrays must be allocated");
-    const SparseGrowLayout L = sparse_grow_layout(n, nnz, F, B, max_depth);
+    const int64_t cap_phys = lossguide ? lossguide_phys_nodes(max_leaves) : cap;
+    const SparseGrowLayout L = lossguide ? sparse_grow_layout_nodes(n, nnz, F, B, cap_phys, kLossguideBatchMax)
+                                         : sparse_grow_layout(n, nnz, F, B, max_depth);
     GBT_REQUIRE(ctx, workspace_bytes >= L.total, GBT_ENOMEM, "workspace %zu < %zu bytes", workspace_bytes, L.total);
 
     char *ws = (char *)workspace;
@@ -2333,7 +2344,8 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         return GBT_OK;
     };
 
-    if (max_depth > 0) {
+    const bool root_may_split = max_depth > 0 && (!lossguide || max_leaves > 1);
+    if (root_may_split) {
         GBT_HIP(ctx, gbt_launch_fill_u64(s, (uint64_t *)pool, 0, hist_len));
         hjobs.clear();
         add_sparse_hist_jobs(hjobs, 0, 0, (uint32_t)n, bins, glen, sparse_rows_per_job(ctx, n, bins, glen));
@@ -2365,48 +2377,122 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
     std::vector<PartJob> pjobs;
     HNode root{0, 0, (uint32_t)n, root_sums[0], root_sums[1], 0, 2};
     set_node(root);
-    if (max_depth > 0) level.push_back(root);
-    int32_t n_nodes = 1;
+    if (root_may_split) level.push_back(root);
+    int32_t n_nodes = 1, n_leaves = 1;
     constexpr size_t kSplitRb = 512u << 10;
+    // loss-guided growth: physical nodes are made in rounds, the caller's tree follows the sequential rule over
+    // what is known (see grow_impl)
+    struct Phys {
+        HNode nd;
+        gbt_split sp;
+        int32_t lc, rc;        // physical children, -1: not expanded
+        int32_t logical;       // id in the caller's tree, -1: not (yet) part of it
+        bool open;             // has a split that may be taken
+    };
+    std::vector<Phys> phys;
+    struct OpenKey {   // order of turns: larger gain first, smaller logical id on equal gains
+        double gain;
+        int32_t logical, pid;
+        bool operator<(const OpenKey &o) const { return gain > o.gain || (gain == o.gain && logical < o.logical); }
+    };
+    std::set<OpenKey> sim_open;
+    int32_t n_logical = 1;
+    if (lossguide) phys.push_back(Phys{root, gbt_split{}, -1, -1, 0, false});
+    const int batch_max = std::max(1, std::min(ctx->lossguide_batch, kLossguideBatchMax));
 
-    while (!level.empty()) {
-        // ---- EvaluateSplit for the level's nodes
-        enodes.resize(level.size());
-        for (size_t i = 0; i < level.size(); ++i)
-            enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq,
-                                 level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_parent * (uint64_t)hist_len : GBT_NO_HIST,
-                                 level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_built * (uint64_t)hist_len : GBT_NO_HIST};
-        st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
-        if (st != GBT_OK) return st;
-        const size_t budget = GBT_STAGING_BYTES - kReadbackOff - kSplitRb;
-        const int chunks = gbt_eval_chunks(F, (int)enodes.size(), budget);
-        const size_t sbytes = enodes.size() * (size_t)chunks * sizeof(gbt_split);
-        GBT_REQUIRE(ctx, sbytes <= budget, GBT_EUNSUPPORTED, "level too wide");
-        gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)enodes.size() * (double)hist_len * 8.0);
-        // (the records go straight into the pinned read-back buffer: no copy launch before the wait)
-        GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)enodes.size(), nb, F, B, chunks,
-                                     inv_sg, inv_sh, lambda, params->min_child_weight, (gbt_split *)(rb(ctx) + kSplitRb)));
-        gbt_prof_end(ctx);
-        GBT_SYNC(ctx);
-        sel_nodes.clear();
-        sel_splits.clear();
-        for (size_t i = 0; i < level.size(); ++i) {
-            const gbt_split sp = merge_chunks((const gbt_split *)(rb(ctx) + kSplitRb) + i * chunks, chunks);
-            const HNode &nd = level[i];
-            if (sp.valid && sp.gain > min_gain && sp.feature >= 0 && sp.feature < F && sp.bin >= 0 && sp.bin < B &&
-                nd.len > 0) {
-                sel_nodes.push_back(nd);
-                sel_splits.push_back(sp);
+    while (!level.empty() || !sim_open.empty()) {
+        if (!level.empty()) {
+            // ---- EvaluateSplit for the level's nodes
+            enodes.resize(level.size());
+            for (size_t i = 0; i < level.size(); ++i)
+                enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq,
+                                     level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_parent * (uint64_t)hist_len : GBT_NO_HIST,
+                                     level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_built * (uint64_t)hist_len : GBT_NO_HIST};
+            st = upload(ctx, enodes.data(), enodes.size() * sizeof(EvalNode), ws + L.eval_nodes);
+            if (st != GBT_OK) return st;
+            const size_t budget = GBT_STAGING_BYTES - kReadbackOff - kSplitRb;
+            const int chunks = gbt_eval_chunks(F, (int)enodes.size(), budget);
+            const size_t sbytes = enodes.size() * (size_t)chunks * sizeof(gbt_split);
+            GBT_REQUIRE(ctx, sbytes <= budget, GBT_EUNSUPPORTED, "level too wide");
+            gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)enodes.size() * (double)hist_len * 8.0);
+            // (the records go straight into the pinned read-back buffer: no copy launch before the wait)
+            GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)enodes.size(), nb, F, B, chunks,
+                                         inv_sg, inv_sh, lambda, params->min_child_weight, (gbt_split *)(rb(ctx) + kSplitRb)));
+            gbt_prof_end(ctx);
+            GBT_SYNC(ctx);
+            sel_nodes.clear();
+            sel_splits.clear();
+            for (size_t i = 0; i < level.size(); ++i) {
+                const gbt_split sp = merge_chunks((const gbt_split *)(rb(ctx) + kSplitRb) + i * chunks, chunks);
+                const HNode &nd = level[i];
+                const bool ok = sp.valid && sp.gain > min_gain && sp.feature >= 0 && sp.feature < F && sp.bin >= 0 &&
+                                sp.bin < B && nd.len > 0;
+                if (lossguide) {
+                    Phys &ph = phys[(size_t)nd.id];
+                    ph.sp = sp;
+                    ph.open = ok;
+                    if (ok && ph.logical >= 0) sim_open.insert(OpenKey{sp.gain, ph.logical, nd.id});   // the root
+                } else if (ok) {
+                    sel_nodes.push_back(nd);
+                    sel_splits.push_back(sp);
+                }
+            }
+            level.clear();
+        } else {
+            sel_nodes.clear();
+            sel_splits.clear();
+        }
+        if (lossguide) {
+            // the logical tree advances as far as the physical expansions reach
+            while (n_leaves < max_leaves && !sim_open.empty()) {
+                const int32_t pid = sim_open.begin()->pid;
+                Phys &ph = phys[(size_t)pid];
+                if (ph.lc < 0) break;   // its turn, but not expanded yet: a round is needed
+                sim_open.erase(sim_open.begin());
+                const int32_t at = ph.logical, lcl = n_logical, rcl = n_logical + 1;
+                GBT_REQUIRE(ctx, rcl < tree->capacity, GBT_EHIP, "internal: logical tree overflow");
+                n_logical += 2;
+                n_leaves += 1;
+                tree->feature[at] = ph.sp.feature;
+                tree->bin[at] = ph.sp.bin;
+                tree->default_left[at] = ph.sp.default_left;
+                tree->left[at] = lcl;
+                tree->right[at] = rcl;
+                tree->gain[at] = ph.sp.gain;
+                tree->threshold[at] = ph.sp.bin < B - 1 ? hcuts[(size_t)ph.sp.feature * (B - 1) + ph.sp.bin] : INFINITY;
+                for (int side = 0; side < 2; ++side) {
+                    const int32_t cid = side == 0 ? ph.lc : ph.rc;
+                    Phys &ch = phys[(size_t)cid];
+                    ch.logical = side == 0 ? lcl : rcl;
+                    set_node_at(ch.logical, ch.nd);
+                    if (ch.open) sim_open.insert(OpenKey{ch.sp.gain, ch.logical, cid});
+                }
+            }
+            if (n_leaves < max_leaves && !sim_open.empty()) {
+                // the leaf whose turn it is and the next ones in gain order that live in the same working copy and
+                // agree with it on whether their children can still split (see grow_impl)
+                const int64_t room = (cap_phys - n_nodes) / 2, budget = (int64_t)max_leaves - n_leaves;
+                const int64_t k_max = std::max<int64_t>(1, std::min<int64_t>({(int64_t)batch_max, budget, room - budget + 1}));
+                const HNode first = phys[(size_t)sim_open.begin()->pid].nd;
+                int looked = 0;
+                for (const OpenKey &key : sim_open) {
+                    if (++looked > 8 * kLossguideBatchMax) break;
+                    const Phys &ph = phys[(size_t)key.pid];
+                    if (ph.lc >= 0) continue;   // expanded ahead of its turn already
+                    if (ph.nd.buf != first.buf || (ph.nd.depth + 1 < max_depth) != (first.depth + 1 < max_depth)) continue;
+                    sel_nodes.push_back(ph.nd);
+                    sel_splits.push_back(ph.sp);
+                    if ((int64_t)sel_nodes.size() >= k_max) break;
+                }
             }
         }
-        level.clear();
         if (sel_nodes.empty()) break;
 
         // ---- RepartitionInstances: the whole level in one launch
         const int wcur = sel_nodes[0].buf, wnext = wcur == 0 ? 1 : 0;
         const Rows cur = rows_of(wcur);
-        const int child_depth = sel_nodes[0].depth + 1;
-        const bool children_need_hist = child_depth < max_depth;
+        const int child_depth = sel_nodes[0].depth + 1;   // loss-guided: of the first node; the others agree on "< max_depth"
+        const bool children_need_hist = child_depth < max_depth && (!lossguide || n_leaves + 1 < max_leaves);
         const uint32_t tile = (uint32_t)gbt_sparse_part_tile();
         pjobs.clear();
         uint32_t tile_cursor = 0;
@@ -2452,18 +2538,26 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
             const gbt_split &sp = sel_splits[k];
             const uint32_t nl = cur_words[4 * k];
             GBT_REQUIRE(ctx, nl <= nd.len, GBT_EHIP, "internal: n_left %u > %u", nl, nd.len);
-            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, child_depth, child_buf};
-            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, child_depth, child_buf};
+            HNode lc{n_nodes, nd.begin, nl, sp.GLq, sp.HLq, nd.depth + 1, child_buf};
+            HNode rc{n_nodes + 1, nd.begin + nl, nd.len - nl, nd.Gq - sp.GLq, nd.Hq - sp.HLq, nd.depth + 1, child_buf};
             n_nodes += 2;
-            tree->feature[nd.id] = sp.feature;
-            tree->bin[nd.id] = sp.bin;
-            tree->default_left[nd.id] = sp.default_left;
-            tree->left[nd.id] = lc.id;
-            tree->right[nd.id] = rc.id;
-            tree->gain[nd.id] = sp.gain;
-            tree->threshold[nd.id] = sp.bin < B - 1 ? hcuts[(size_t)sp.feature * (B - 1) + sp.bin] : INFINITY;
-            set_node(lc);
-            set_node(rc);
+            if (lossguide) {   // physical children; the caller's tree learns of them when their parent is popped
+                GBT_REQUIRE(ctx, n_nodes <= cap_phys, GBT_EHIP, "internal: physical node overflow");
+                phys[(size_t)nd.id].lc = lc.id;
+                phys[(size_t)nd.id].rc = rc.id;
+                phys.push_back(Phys{lc, gbt_split{}, -1, -1, -1, false});
+                phys.push_back(Phys{rc, gbt_split{}, -1, -1, -1, false});
+            } else {
+                tree->feature[nd.id] = sp.feature;
+                tree->bin[nd.id] = sp.bin;
+                tree->default_left[nd.id] = sp.default_left;
+                tree->left[nd.id] = lc.id;
+                tree->right[nd.id] = rc.id;
+                tree->gain[nd.id] = sp.gain;
+                tree->threshold[nd.id] = sp.bin < B - 1 ? hcuts[(size_t)sp.feature * (B - 1) + sp.bin] : INFINITY;
+                set_node(lc);
+                set_node(rc);
+            }
             if (children_need_hist) {
                 const bool left_small = lc.len <= rc.len;
                 const HNode &sm = left_small ? lc : rc;
@@ -2489,7 +2583,8 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         }
         level.swap(next);
     }
-    tree->n_nodes = n_nodes;
+    const int32_t n_tree = lossguide ? n_logical : n_nodes;   // nodes of the caller's tree
+    tree->n_nodes = n_tree;
 
     // ---- each row's leaf by a walk of the finished tree; the row order by a stable sort on leaf rank
     int32_t *leaf_ids = leaf_of_row_out ? leaf_of_row_out : (int32_t *)w_rowptr[0];
@@ -2502,7 +2597,7 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         if (st != GBT_OK) return st;
     }
     if (row_idx_out) {
-        std::vector<uint32_t> rank((size_t)n_nodes, 0u);
+        std::vector<uint32_t> rank((size_t)n_tree, 0u);
         std::vector<int32_t> stack{0};
         uint32_t n_ranks = 0;
         while (!stack.empty()) {
@@ -2523,12 +2618,37 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
         uint32_t *key_tmp[2] = {w_rowptr[1], (uint32_t *)w_gq[0] + n};
         uint32_t *val_tmp[2] = {(uint32_t *)w_gq[0], (uint32_t *)w_gq[1]};
         gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * 12.0);
-        GBT_HIP(ctx, gbt_launch_order_rows(s, leaf_ids, (const uint32_t *)(ws + L.rank_tbl), (uint32_t)n_nodes, n_ranks, n,
+        GBT_HIP(ctx, gbt_launch_order_rows(s, leaf_ids, (const uint32_t *)(ws + L.rank_tbl), (uint32_t)n_tree, n_ranks, n,
                                            key_tmp, val_tmp, ws + L.order, row_idx_out));
         gbt_prof_end(ctx);
     }
     GBT_SYNC(ctx);
     return GBT_OK;
+}
+
+extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                                        int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
+                                        const float *gpair, const gbt_params *params, gbt_tree *tree,
+                                        uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace,
+                                        size_t workspace_bytes) {
+    return sparse_grow_impl(ctx, rowptr, ent, n, nnz, F, nb, cuts, gpair, params, GBT_POLICY_DEPTHWISE, 0, tree, row_idx_out,
+                            leaf_of_row_out, workspace, workspace_bytes);
+}
+
+extern "C" size_t gbt_grow_tree_sparse_lossguide_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
+                                                                 int32_t max_leaves) {
+    if (n < 0 || nnz < 0 || F < 1 || max_bins < 2 || (int64_t)F * max_bins > 65536 || max_leaves < 1 || max_leaves > kMaxLeaves)
+        return 0;
+    return sparse_grow_layout_nodes(n, nnz, F, max_bins, lossguide_phys_nodes(max_leaves), kLossguideBatchMax).total;
+}
+
+extern "C" int32_t gbt_grow_tree_sparse_lossguide(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+                                                  int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
+                                                  const float *gpair, const gbt_params *params, int32_t max_leaves,
+                                                  gbt_tree *tree, uint32_t *row_idx_out, int32_t *leaf_of_row_out,
+                                                  void *workspace, size_t workspace_bytes) {
+    return sparse_grow_impl(ctx, rowptr, ent, n, nnz, F, nb, cuts, gpair, params, GBT_POLICY_LOSSGUIDE, max_leaves, tree,
+                            row_idx_out, leaf_of_row_out, workspace, workspace_bytes);
 }
 
 extern "C" int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *rowptr,

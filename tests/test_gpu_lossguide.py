@@ -47,6 +47,19 @@ def _judge(ctx, oracle, o, gdev, gp, p, n, F, max_leaves, grid_only=False):
     for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
               "sumG", "sumH"):
         assert np.array_equal(bare[k][:nn], tree[k][:nn]), k
+    # over sparse rows (where the global bin ids fit 16 bits): the same tree, row order and leaves
+    if F * p["max_bins"] <= 65536:
+        rowptr, ent, nnz = ctx.compress_sparse(dev(o["sym"]), p["max_bins"], gdev["missing"])
+        for want_rows in (True, False):
+            st, s_rows, s_leaf = ctx.grow_tree_sparse_lossguide(rowptr, ent, n, nnz, F, gdev["nb"], gdev["cuts"], gp_t,
+                                                                params, max_leaves, want_rows=want_rows)
+            assert st["n_nodes"] == nn
+            for k in ("feature", "bin", "default_left", "left", "right", "n_rows", "threshold", "weight", "gain",
+                      "sumG", "sumH"):
+                assert np.array_equal(st[k][:nn], tree[k][:nn]), ("sparse rows", k)
+            assert np.array_equal(s_leaf.cpu().numpy(), rep["leaf_of_row"])
+            if want_rows:
+                assert np.array_equal(host_u32(s_rows), rep["row_idx"])
     # an independently grown oracle tree is the same unless a legal tie intervened
     t_ref, rows_ref, leaf_ref = oracle.grow_tree_lossguide(o["sym"], o["nb"], o["cuts"], o["missing"], gp,
                                                            max_leaves=max_leaves, **tree_kw(p))
