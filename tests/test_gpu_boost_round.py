@@ -51,6 +51,8 @@ CASES = [
     (4, 150_001, None, None, 0.0, 8, 3),      # the 115M-row workload's shape: 13 byte symbols
     (4, 70_001, 16, 256, 0.1, 6, 2),          # a missing symbol, 16 features
     (4, 20_000, 5, 200, 0.0, 9, 2),           # deeper than the rows support everywhere: empty and unsplit nodes
+    (4, 60_000, 13, 256, 0.0, 10, 1),         # the deepest tree whose nodes the counting walk holds in LDS (2047)
+    (4, 60_000, 8, 256, 0.05, 11, 1),         # one level more: the leaves are counted by a pass of their own again
     (4, 9_000, 13, 256, 0.0, 1, 2),           # the root's children are the last level
     (4, 9_000, 13, 256, 0.0, 0, 1),           # no split at all
     (2, 50_000, None, None, 0.0, 6, 3),       # 28 byte symbols: rows of 7 words (path 1, plain walk)
