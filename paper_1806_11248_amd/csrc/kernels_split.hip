@@ -92,6 +92,89 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     best.GLq = 0;
     best.HLq = 0;
 
+    // one 64-bin piece of a feature's scan: the inclusive prefix over the piece's bins (carried in from cg, ch),
+    // then the gain of every (bin, direction) of the piece
+    auto scan_and_score = [&](int f, int nbf, int b0, int64_t pg, int64_t ph, int64_t &cg, int64_t &ch, int64_t Gm, int64_t Hm,
+                              bool has_missing) __attribute__((always_inline)) {
+        const int b = b0 + lane;
+        for (int d = 1; d < 64; d <<= 1) {
+            int64_t tg = shfl_up_i64(pg, d), th = shfl_up_i64(ph, d);
+            if (lane >= d) {
+                pg += tg;
+                ph += th;
+            }
+        }
+        pg += cg;
+        ph += ch;
+        cg = shfl_i64(pg, 63);
+        ch = shfl_i64(ph, 63);
+        if (b < nbf) {
+            for (int dir = 0; dir <= (has_missing ? 1 : 0); ++dir) {
+                if (b == nbf - 1 && (dir == 1 || !has_missing)) continue;   // right side empty
+                const int64_t GLq = pg + (dir ? Gm : 0), HLq = ph + (dir ? Hm : 0);
+                const double GL = (double)GLq * inv_sg, HL = (double)HLq * inv_sh;
+                const double GR = (double)(Gq - GLq) * inv_sg, HR = (double)(Hq - HLq) * inv_sh;
+                if (!(HL >= mcw) || !(HR >= mcw)) continue;
+                const double a = gain_term(GL, HL + lambda);
+                const double c = gain_term(GR, HR + lambda);
+                const double gain = (a + c) - parent;
+                if (gain > best.gain) {
+                    best.gain = gain;
+                    best.key = ((uint32_t)f * (uint32_t)B + (uint32_t)b) * 2u + (uint32_t)dir;
+                    best.GLq = GLq;
+                    best.HLq = HLq;
+                }
+            }
+        }
+    };
+
+    if (B <= 64) {
+        // Every feature's bins fit one per lane: a lane's bin stays in registers between the reduction and the scan,
+        // and the NEXT feature's words are asked for before this one's are worked on (a wave otherwise has one
+        // kilobyte in flight at a time, too little to keep HBM busy at a few waves per SIMD).  (Two features ahead, or
+        // one 16-byte load per bin instead of two of 8, measured the same.)
+        auto fetch = [&](int f, int64_t &g, int64_t &h) __attribute__((always_inline)) {
+            g = 0;
+            h = 0;
+            if (f < f_end) {
+                int nbf = nb[f];
+                if (nbf > B) nbf = B;
+                if (lane < nbf) {
+                    const int64_t o = (int64_t)f * B * 2 + 2 * lane;
+                    if (subtract) {
+                        g = hpar[o] - hblt[o];
+                        h = hpar[o + 1] - hblt[o + 1];
+                    } else {
+                        g = hist[o];
+                        h = hist[o + 1];
+                    }
+                }
+            }
+        };
+        int64_t g0, h0;
+        fetch(f_begin + wave, g0, h0);
+        for (int f = f_begin + wave; f < f_end; f += kEvalWaves) {
+            int64_t g1, h1;
+            fetch(f + kEvalWaves, g1, h1);
+            int nbf = nb[f];
+            if (nbf > B) nbf = B;
+            if (subtract && lane < nbf) {
+                int64_t *hf = hist + (int64_t)f * B * 2;
+                hf[2 * lane] = g0;
+                hf[2 * lane + 1] = h0;
+            }
+            int64_t sg = g0, sh = h0;
+            for (int o = 32; o > 0; o >>= 1) {
+                sg += shfl_xor_i64(sg, o);
+                sh += shfl_xor_i64(sh, o);
+            }
+            const int64_t Gm = Gq - sg, Hm = Hq - sh;
+            int64_t cg = 0, ch = 0;
+            if (nbf > 0) scan_and_score(f, nbf, 0, g0, h0, cg, ch, Gm, Hm, (Gm != 0) || (Hm != 0));
+            g0 = g1;
+            h0 = h1;
+        }
+    } else
     for (int f = f_begin + wave; f < f_end; f += kEvalWaves) {
         int nbf = nb[f];
         if (nbf > B) nbf = B;
@@ -123,37 +206,9 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
         int64_t cg = 0, ch = 0;
         for (int b0 = 0; b0 < nbf; b0 += 64) {
             const int b = b0 + lane;
-            int64_t pg = b < nbf ? hf[2 * b] : 0;
-            int64_t ph = b < nbf ? hf[2 * b + 1] : 0;
-            for (int d = 1; d < 64; d <<= 1) {
-                int64_t tg = shfl_up_i64(pg, d), th = shfl_up_i64(ph, d);
-                if (lane >= d) {
-                    pg += tg;
-                    ph += th;
-                }
-            }
-            pg += cg;
-            ph += ch;
-            cg = shfl_i64(pg, 63);
-            ch = shfl_i64(ph, 63);
-            if (b < nbf) {
-                for (int dir = 0; dir <= (has_missing ? 1 : 0); ++dir) {
-                    if (b == nbf - 1 && (dir == 1 || !has_missing)) continue;   // right side empty
-                    const int64_t GLq = pg + (dir ? Gm : 0), HLq = ph + (dir ? Hm : 0);
-                    const double GL = (double)GLq * inv_sg, HL = (double)HLq * inv_sh;
-                    const double GR = (double)(Gq - GLq) * inv_sg, HR = (double)(Hq - HLq) * inv_sh;
-                    if (!(HL >= mcw) || !(HR >= mcw)) continue;
-                    const double a = gain_term(GL, HL + lambda);
-                    const double c = gain_term(GR, HR + lambda);
-                    const double gain = (a + c) - parent;
-                    if (gain > best.gain) {
-                        best.gain = gain;
-                        best.key = ((uint32_t)f * (uint32_t)B + (uint32_t)b) * 2u + (uint32_t)dir;
-                        best.GLq = GLq;
-                        best.HLq = HLq;
-                    }
-                }
-            }
+            const int64_t pg = b < nbf ? hf[2 * b] : 0;
+            const int64_t ph = b < nbf ? hf[2 * b + 1] : 0;
+            scan_and_score(f, nbf, b0, pg, ph, cg, ch, Gm, Hm, has_missing);
         }
     }
 
