@@ -342,7 +342,11 @@ GBT_API size_t gbt_grow_tree_workspace_bytes(int64_t n, int32_t F, int32_t bits,
  *   1  one launch per level, order inside a node not kept, no ids (rows of at
  *      most 64 words)
  *   2  as 1, and the launch also builds one child's histogram of every split
- *      node (8-bit symbols, at most 16 features)
+ *      node (8-bit symbols, at most 16 features).  Depth-wise, most levels
+ *      then leave the rows where they are (a pass reads them in place and
+ *      adds up the rows of the children to be built, for up to two levels in
+ *      a row) and every third level moves them over three levels of splits
+ *      at once; see GBT_TUNE_PART_NOMOVE and GBT_TUNE_PART_CYCLE
  *   3  rows wider than 64 words are never moved: the nodes' row-id lists are
  *      partitioned (stable, three launches) and the histogram kernel gathers
  *      the rows by id from the packed matrix
