@@ -456,7 +456,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="headline workload 1..5 (default 4: 115M x 13)")
     ap.add_argument("--rows", type=int, default=None, help="fewer rows than the workload's own size")
     ap.add_argument("--data-cache", default=None, help="directory to keep the generated inputs in")
-    ap.add_argument("--cpu-sample-rows", type=int, default=4_000_000)
+    ap.add_argument("--cpu-sample-rows", type=int, default=40_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-outputs-leg", action="store_true",
                     help="skip the extra timing of the steps with row order and leaf ids asked for")
