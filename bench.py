@@ -308,8 +308,8 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
         part_kernel = "sparse_part_kernel"
     r_root = roof(prof, ["hist_root"], hist_kernel)
     r_node = roof(prof, ["hist_node"], node_kernel)
-    r_first = roof(prof, ["hist_first"], "the pass at level 1, from the packed matrix: hist_keep_kernel where the rows stay in place "
-                                        "(depth 5, 6, 8, 9, ...), else part_hist_first_kernel")
+    r_first = roof(prof, ["hist_first"], "the pass at level 1, from the packed matrix: where the rows stay in place (depth 5, 6, 8, 9, ...) "
+                                        "hist8_kernel adding one side of the root's split, else part_hist_first_kernel")
     r_inplace = roof(prof, ["hist_inplace"], "hist_keep_kernel + hist2_kernel (passes over records that stay in place: one and two "
                                             "histograms per workgroup)")
     r_part = roof(prof, ["partition"], part_kernel)

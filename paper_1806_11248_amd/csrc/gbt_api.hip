@@ -1552,7 +1552,26 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                     GBT_HIP(ctx, gbt_launch_hist2(ctx, W[wcur].sym, F, B, (uint32_t)missing_sym, (const Hist2Job *)(ws + L.jobs),
                                                   (int)h2jobs.size(), (int)h2_spans, part_tile,
                                                   (unsigned long long *)(ws + L.state), pool, true, hq_uni));
-                else   // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
+                else if (nomove && wcur == 2 && pjobs.size() == 1 && ctx->hist8 && pjobs[0].seg_begin == 0 &&
+                         (int64_t)pjobs[0].seg_len == n && gbt_hist8_ok(bits, F, pl.n_ftiles, n, gbt_packed_words(n, F, bits))) {
+                    // the root's rows stay in the matrix: the root histogram kernel once more, adding only the rows of
+                    // the child to be built and counting the rows that go left
+                    Hist8Pairs hp{};
+                    if (pairs_stay_fp32) {
+                        hp.gpair = gpair;
+                        hp.sg = scale[0];
+                        hp.sh = scale[1];
+                        hp.mode = 2;
+                    } else {
+                        hp.gq = gq;
+                    }
+                    hp.uniform_h = hq_uni >= 0;
+                    hp.hq_uniform = hq_uni >= 0 ? hq_uni : 0;
+                    const Hist8Filter flt{(int)pjobs[0].feature, (int)pjobs[0].bin, (int)pjobs[0].default_left,
+                                          pjobs[0].pad == 1u ? 1 : 0, (unsigned long long *)(ws + L.state)};
+                    GBT_HIP(ctx, gbt_launch_hist8(ctx, packed, n, F, B, (uint32_t)missing_sym, hp, pool + pjobs[0].hist_off,
+                                                  nullptr, &flt));
+                } else   // level 0 reads the caller's matrix and the pairs, later levels the records of the level before
                     GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq,
                                                       wcur == 2 ? nullptr : W[wcur].sym, nomove ? nullptr : W[wnext].sym_rw, F, B,
                                                       (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs),

@@ -305,8 +305,17 @@ struct Hist8Pairs {
 bool gbt_hist8_ok(int bits, int F, int n_ftiles, int64_t n, int64_t n_words);
 bool gbt_fix32_ok(double sg, double sh);
 int gbt_hist8_max_jobs();
+// filter (may be NULL): only the rows on one side of a split are added -- the histogram of one child of the root
+// with the rows staying in the matrix; hist_out must have been cleared; *lefts (device, cleared by the caller)
+// receives the number of rows that go left.  Pairs as fixed point (p.gq) or fp32 with mode 2.
+struct Hist8Filter {
+    int feature, bin, default_left;
+    int take_left;               // 1: the left rows are added, 0: the right rows
+    unsigned long long *lefts;
+};
 hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int F, int B, uint32_t missing,
-                            const Hist8Pairs &p, int64_t *hist_out, int *n_jobs_out = nullptr);
+                            const Hist8Pairs &p, int64_t *hist_out, int *n_jobs_out = nullptr,
+                            const Hist8Filter *filter = nullptr);
 // Partition and the histogram of one child of every job in one pass (8-bit symbols, at most 16
 // features, the bins of all features in one LDS tile: gbt_part_hist_ok).  No ids, order inside a
 // child not kept.  Rows travel as records of gbt_part_hist_record_words(F) words (symbols, padding,

@@ -61,6 +61,10 @@ struct Hist8Args {
     int32_t hq_uniform;
     int64_t *sums, *out;
     uint32_t cols, slots, stagger;   // job geometry: see job_rows()
+    // FILT: only the rows on one side of a split are added (the histogram of one child of the root, the rows
+    // staying where they are); the rows that go left are counted into *lefts
+    uint32_t split_feature, split_bin, split_default_left, take_left;
+    unsigned long long *lefts;
 };
 
 // Rows of workgroup (column c, slice k): the n rows are cut into `cols` equal columns, a column into
@@ -94,7 +98,8 @@ __device__ __forceinline__ void pk_check8(uint32_t side_addr, unsigned long long
 // NS  : unrolled slots = features of the tile rounded up to 4, 8, 12, 13, 16 (ft > NS - 4, or NS - 1 for 13)
 // UNI : the uniform-h word
 // FIX : 0 fixed-point pairs are read; 1 fp32 pairs rounded through fp64; 2 rounded in fp32
-template <int NS, bool UNI, int FIX, int BLOCK, int MINWG, int PF>
+// FILT: see Hist8Args
+template <int NS, bool UNI, int FIX, int BLOCK, int MINWG, int PF, bool FILT>
 __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) {
     constexpr int NW = (NS + 6) / 4;   // words a row of NS - 3 .. NS bytes can touch at any alignment
     constexpr int SW = (NS + 3) / 4;   // words of symbols after realignment
@@ -143,6 +148,10 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
     int2 *__restrict__ gqo = a.gq_out ? a.gq_out + job_row0 : nullptr;
 
     long long sum_g = 0, sum_h = 0;   // UNI: sum_g holds the sum of the packed words (G * 2^18 + rows)
+    // FILT: byte `split_feature` of the realigned row, and the rows seen going left
+    const uint32_t fselA = 0x0C0C0C00u | (a.split_feature < 8u ? a.split_feature : 0x0Cu);
+    const uint32_t fselB = 0x0C0C0C00u | (a.split_feature >= 8u ? a.split_feature - 8u : 0x0Cu);
+    uint32_t my_lefts = 0;
     // the words and the pair of the row PF iterations ahead are on their way while a row is processed
     uint32_t wq[PF + 1][NW];
     float2 vq[PF + 1];
@@ -187,6 +196,12 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
 #pragma unroll
         for (int k = 0; k < SW; ++k)
             V[k] = __builtin_amdgcn_perm(W[1], W[0], selA[k]) | __builtin_amdgcn_perm(W[3], W[2], selB[k]);
+        if (FILT) {
+            const uint32_t sy = __builtin_amdgcn_perm(W[1], W[0], fselA) | __builtin_amdgcn_perm(W[3], W[2], fselB);
+            const bool left = sy == a.missing ? a.split_default_left != 0 : sy <= a.split_bin;
+            my_lefts += left ? 1u : 0u;
+            if (left != (a.take_left != 0)) continue;
+        }
         if (!UNI) {
             const unsigned long long addv = ((unsigned long long)(long long)q.x << kHShift) + (unsigned long long)(uint32_t)q.y;
             const uint32_t hq = (uint32_t)q.y;
@@ -216,6 +231,17 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
                 const uint32_t s = (V[j >> 2] >> (8 * (j & 3))) & 0xffu;
                 if (j < NS - 3 || j < ft) lds_add((s << 7) + pre[j], addv);
             }
+        }
+    }
+    if (FILT) {   // one atomic per workgroup on a counter that has a line of its own
+        __shared__ uint32_t lred[BLOCK / 64];
+        for (int o = 32; o > 0; o >>= 1) my_lefts += (uint32_t)__shfl_xor((int)my_lefts, o);
+        if (lane == 0) lred[threadIdx.x >> 6] = my_lefts;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t t = 0;
+            for (int w = 0; w < BLOCK / 64; ++w) t += lred[w];
+            if (t) atomicAdd(a.lefts, (unsigned long long)t);
         }
     }
     __syncthreads();
@@ -270,20 +296,27 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
     }
 }
 
-template <int NS, bool UNI, int FIX>
+template <int NS, bool UNI, int FIX, bool FILT>
 hipError_t launch8(hipStream_t s, const Hist8Args &a, int grid) {
     constexpr int BLOCK = UNI ? 256 : 512, MINWG = UNI ? 4 : 2, PF = UNI ? 3 : 1;
     const size_t lds = (size_t)kLdsWords * (UNI ? 8 : 12);   // 32 or 48 KB: within the default limit of a launch
-    hist8_kernel<NS, UNI, FIX, BLOCK, MINWG, PF><<<grid, BLOCK, lds, s>>>(a);
+    hist8_kernel<NS, UNI, FIX, BLOCK, MINWG, PF, FILT><<<grid, BLOCK, lds, s>>>(a);
     return hipGetLastError();
+}
+template <bool UNI, int FIX, bool FILT>
+hipError_t pick8f(hipStream_t s, const Hist8Args &a, int grid) {
+    if (a.ft <= 4) return launch8<4, UNI, FIX, FILT>(s, a, grid);
+    if (a.ft <= 8) return launch8<8, UNI, FIX, FILT>(s, a, grid);
+    if (a.ft <= 12) return launch8<12, UNI, FIX, FILT>(s, a, grid);
+    if (a.ft == 13) return launch8<13, UNI, FIX, FILT>(s, a, grid);
+    return launch8<16, UNI, FIX, FILT>(s, a, grid);
 }
 template <bool UNI, int FIX>
 hipError_t pick8(hipStream_t s, const Hist8Args &a, int grid) {
-    if (a.ft <= 4) return launch8<4, UNI, FIX>(s, a, grid);
-    if (a.ft <= 8) return launch8<8, UNI, FIX>(s, a, grid);
-    if (a.ft <= 12) return launch8<12, UNI, FIX>(s, a, grid);
-    if (a.ft == 13) return launch8<13, UNI, FIX>(s, a, grid);
-    return launch8<16, UNI, FIX>(s, a, grid);
+    // (the filtered form reads fixed-point pairs or rounds fp32 pairs in fp32: the two ways its callers have them)
+    if (a.lefts != nullptr && FIX != 1) return pick8f<UNI, FIX == 1 ? 0 : FIX, true>(s, a, grid);
+    if (a.lefts != nullptr) return hipErrorInvalidValue;
+    return pick8f<UNI, FIX, false>(s, a, grid);
 }
 int slots_of(int ft) { return ft <= 4 ? 4 : ft <= 8 ? 8 : ft <= 12 ? 12 : ft == 13 ? 13 : 16; }
 }  // namespace
@@ -307,9 +340,11 @@ bool gbt_fix32_ok(double sg, double sh) {
 int gbt_hist8_max_jobs() { return 1 << 14; }
 
 hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int F, int B, uint32_t missing,
-                            const Hist8Pairs &p, int64_t *hist_out, int *n_jobs_out) {
+                            const Hist8Pairs &p, int64_t *hist_out, int *n_jobs_out, const Hist8Filter *filter) {
     if (n_jobs_out) *n_jobs_out = 0;
     if (n <= 0) return hipSuccess;
+    if (filter && (filter->lefts == nullptr || filter->feature < 0 || filter->feature >= F || (p.gpair && p.mode == 1)))
+        return hipErrorInvalidValue;
     const bool uni = p.uniform_h != 0;
     Hist8Args a;
     a.packed = packed;
@@ -327,6 +362,11 @@ hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int
     a.hq_uniform = p.hq_uniform;
     a.sums = p.sums;
     a.out = hist_out;
+    a.split_feature = filter ? (uint32_t)filter->feature : 0u;
+    a.split_bin = filter ? (uint32_t)filter->bin : 0u;
+    a.split_default_left = filter ? (uint32_t)filter->default_left : 0u;
+    a.take_left = filter ? (uint32_t)filter->take_left : 0u;
+    a.lefts = filter ? filter->lefts : nullptr;
     // about one column of rows per compute unit, cut into as many slices as workgroups share a unit; short
     // inputs take fewer, equal jobs; long ones more slices, so that no workgroup exceeds its row limit
     const int64_t block = uni ? 256 : 512;
