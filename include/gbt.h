@@ -198,9 +198,12 @@ GBT_API int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32
 
 /*
  * A second storage form of the quantised matrix for mostly-empty data: row r
- * keeps only its present elements (sym != missing_sym), each as the 16-bit
- * global bin id  gid = f * max_bins + sym  (needs F * max_bins <= 65536, else
- * GBT_EUNSUPPORTED), ascending, in ent[rowptr[r] .. rowptr[r+1]).  2*gid is the
+ * keeps only its present elements (sym != missing_sym), each as the global bin
+ * id  gid = f * max_bins + sym, ascending, in ent[rowptr[r] .. rowptr[r+1]).
+ * An entry is a uint16 where F * max_bins <= 65536 and a uint32 in a wider
+ * matrix: gbt_sparse_entry_bytes(F, max_bins) = 2 or 4 (0: not a valid shape;
+ * more than 2^28 ids are refused with GBT_EUNSUPPORTED), and every `ent`
+ * argument below is an array of that type.  2*gid is the
  * element's place in a [F][max_bins][2] histogram.  Two calls, because the
  * caller allocates the entry stream:
  *   gbt_compress_sparse_count  sym [dev] uint16[n][F] -> rowptr_out [dev]
@@ -211,13 +214,14 @@ GBT_API int32_t gbt_compress(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32
  *                              the stream as whole words, up to 32 entries past
  *                              the end.  Asynchronous.
  */
+GBT_API int32_t gbt_sparse_entry_bytes(int32_t F, int32_t max_bins);
 GBT_API int64_t gbt_sparse_capacity(int64_t nnz);
 GBT_API size_t gbt_compress_sparse_workspace_bytes(int64_t n);
 GBT_API int32_t gbt_compress_sparse_count(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F,
                       int32_t missing_sym, uint32_t *rowptr_out, int64_t *nnz_out, void *workspace,
                       size_t workspace_bytes);
 GBT_API int32_t gbt_compress_sparse(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, int32_t max_bins,
-                      int32_t missing_sym, const uint32_t *rowptr, int64_t nnz, uint16_t *ent_out,
+                      int32_t missing_sym, const uint32_t *rowptr, int64_t nnz, void *ent_out,
                       int64_t ent_capacity);
 
 /* ---- Sec. 2.5 gradient evaluation (Eq. 1, Eq. 2) ------------------------ */
@@ -263,7 +267,7 @@ GBT_API int32_t gbt_build_hist(gbt_ctx *ctx, const uint32_t *packed, int32_t bit
  * contiguous range [row_begin, row_begin + n_node_rows) of the n rows; absent
  * elements are missing and accumulate nowhere.  hist_out [dev] int64[F][B][2],
  * overwritten.  Asynchronous. */
-GBT_API int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+GBT_API int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int64_t n,
                        int32_t F, int32_t B, int64_t row_begin, int64_t n_node_rows, const int32_t *gq,
                        int64_t *hist_out);
 
@@ -425,7 +429,7 @@ GBT_API int32_t gbt_grow_tree_lossguide(gbt_ctx *ctx, const uint32_t *packed, in
  */
 GBT_API size_t gbt_grow_tree_sparse_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
                                                     int32_t max_depth);
-GBT_API int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+GBT_API int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int64_t n,
                       int64_t nnz, int32_t F, const int32_t *nb, const float *cuts, const float *gpair,
                       const gbt_params *params, gbt_tree *tree_out, uint32_t *row_idx_out,
                       int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
@@ -438,7 +442,7 @@ GBT_API int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const
  */
 GBT_API size_t gbt_grow_tree_sparse_lossguide_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
                                                               int32_t max_leaves);
-GBT_API int32_t gbt_grow_tree_sparse_lossguide(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+GBT_API int32_t gbt_grow_tree_sparse_lossguide(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int64_t n,
                       int64_t nnz, int32_t F, const int32_t *nb, const float *cuts, const float *gpair,
                       const gbt_params *params, int32_t max_leaves, gbt_tree *tree_out, uint32_t *row_idx_out,
                       int32_t *leaf_of_row_out, void *workspace, size_t workspace_bytes);
@@ -484,7 +488,7 @@ GBT_API int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
  * is <= bin, an absent element -> default child.  workspace as for gbt_predict.
  * Synchronises the stream. */
 GBT_API int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *rowptr,
-                      const uint16_t *ent, int64_t n, int32_t F, int32_t max_bins, double eta, float *margin,
+                      const void *ent, int64_t n, int32_t F, int32_t max_bins, double eta, float *margin,
                       void *workspace, size_t workspace_bytes);
 
 /* ---- measurement -------------------------------------------------------- */

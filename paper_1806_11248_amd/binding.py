@@ -31,7 +31,7 @@ SYMBOLS = [
     "gbt_grow_tree_lossguide_workspace_bytes", "gbt_grow_tree_lossguide", "gbt_boost_round",
     "gbt_predict_workspace_bytes", "gbt_predict",
     "gbt_profile_enable", "gbt_profile_read", "gbt_measure_stream_read",
-    "gbt_sparse_capacity", "gbt_compress_sparse_workspace_bytes", "gbt_compress_sparse_count", "gbt_compress_sparse",
+    "gbt_sparse_entry_bytes", "gbt_sparse_capacity", "gbt_compress_sparse_workspace_bytes", "gbt_compress_sparse_count", "gbt_compress_sparse",
     "gbt_build_hist_sparse", "gbt_grow_tree_sparse_workspace_bytes", "gbt_grow_tree_sparse", "gbt_predict_sparse",
     "gbt_grow_tree_sparse_lossguide_workspace_bytes", "gbt_grow_tree_sparse_lossguide",
 ]
@@ -124,6 +124,7 @@ def load():
     L.gbt_grow_tree_lossguide.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz]
     L.gbt_boost_round.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz]
     L.gbt_predict.argtypes = [vp, vp, i32, vp, i32, i32, vp, i64, i32, f64, vp, vp, sz]
+    L.gbt_sparse_entry_bytes.argtypes = [i32, i32]
     L.gbt_sparse_capacity.argtypes = [i64]
     L.gbt_sparse_capacity.restype = i64
     L.gbt_compress_sparse_workspace_bytes.argtypes = [i64]
@@ -325,7 +326,8 @@ class Context:
         return packed, b.value
 
     def compress_sparse(self, sym, max_bins: int, missing_sym: int):
-        """Sparse rows of sym[n][F]: (rowptr uint32[n+1] as int32 tensor, ent uint16[capacity], nnz)."""
+        """Sparse rows of sym[n][F]: (rowptr uint32[n+1] as int32 tensor, ent[capacity], nnz); the entries are
+        uint16 where F * max_bins <= 65536, else uint32."""
         _need(sym, torch.uint16, "sym")
         n, F = sym.shape
         rowptr = self.empty((n + 1,), torch.int32)
@@ -335,7 +337,10 @@ class Context:
         self._check(self.lib.gbt_compress_sparse_count(self.h, _ptr(sym), n, F, missing_sym, _ptr(rowptr),
                                                        C.byref(nnz), _ptr(ws), ws.numel()))
         cap = int(self.lib.gbt_sparse_capacity(nnz.value))
-        ent = self.empty((cap,), torch.uint16)
+        width = int(self.lib.gbt_sparse_entry_bytes(F, max_bins))
+        if width == 0:
+            raise GbtError(EUNSUPPORTED, f"gbt_sparse_entry_bytes rejected F = {F}, max_bins = {max_bins}")
+        ent = self.empty((cap,), torch.uint16 if width == 2 else torch.uint32)
         self._check(self.lib.gbt_compress_sparse(self.h, _ptr(sym), n, F, max_bins, missing_sym, _ptr(rowptr),
                                                  nnz.value, _ptr(ent), cap))
         return rowptr, ent, nnz.value

@@ -903,7 +903,8 @@ extern "C" int32_t gbt_grow_tree_path(gbt_ctx *ctx, int32_t F, int32_t bits, int
 
 struct SparseRowsArg {   // rows in the sparse form instead of packed / X
     const uint32_t *rowptr;
-    const uint16_t *ent;
+    const void *ent;
+    int32_t ent_bytes;
     int32_t B;
 };
 static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *packed,
@@ -2088,7 +2089,7 @@ static int32_t predict_impl(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees
     if (sparse) {
         if (own_span) gbt_prof_begin(ctx, GBT_PROF_OTHER, 0.0);
         GBT_HIP(ctx, gbt_launch_sparse_walk(ctx->stream, (const char *)workspace, (const DevTree *)workspace, n_trees,
-                                            sparse->rowptr, sparse->ent, n, sparse->B, eta, margin, leaf_out, max_nodes));
+                                            sparse->rowptr, sparse->ent, sparse->ent_bytes, n, sparse->B, eta, margin, leaf_out, max_nodes));
         if (own_span) gbt_prof_end(ctx);
         return GBT_OK;
     }
@@ -2123,14 +2124,17 @@ extern "C" int32_t gbt_predict(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_tr
 // ------------------------------------------------------------- sparse rows --
 namespace {
 constexpr int64_t kSparseSlack = 32;   // entries past the last one that word-wise readers may touch
+constexpr int64_t kSparseMaxIds = (int64_t)1 << 28;
 
 int32_t check_sparse_shape(gbt_ctx *ctx, int64_t n, int32_t F, int32_t B) {
     GBT_REQUIRE(ctx, n >= 0 && n < ((int64_t)1 << 32) - 1, GBT_EINVAL, "n = %lld out of range", (long long)n);
     GBT_REQUIRE(ctx, F >= 1 && B >= 2, GBT_EINVAL, "bad shape");
-    GBT_REQUIRE(ctx, (int64_t)F * B <= 65536, GBT_EUNSUPPORTED,
-                "F * max_bins = %lld global bin ids do not fit 16 bits", (long long)F * B);
+    GBT_REQUIRE(ctx, (int64_t)F * B <= kSparseMaxIds, GBT_EUNSUPPORTED,
+                "F * max_bins = %lld global bin ids, at most %lld", (long long)F * B, (long long)kSparseMaxIds);
     return GBT_OK;
 }
+// bytes of an entry: 16-bit ids where all of them fit, else 32-bit
+int sparse_ent_bytes(int64_t F, int64_t B) { return F * B <= 65536 ? 2 : 4; }
 
 // Rows per workgroup: every workgroup merges its whole id tile into HBM at the end with 64-bit global
 // atomics (about 10^11 of them per second, all compute units together), so a launch aims at few, long
@@ -2163,6 +2167,11 @@ void add_sparse_hist_jobs(std::vector<HistJob> &jobs, uint64_t hist_off, uint32_
     }
 }
 }  // namespace
+
+extern "C" int32_t gbt_sparse_entry_bytes(int32_t F, int32_t max_bins) {
+    if (F < 1 || max_bins < 2 || (int64_t)F * max_bins > kSparseMaxIds) return 0;
+    return sparse_ent_bytes(F, max_bins);
+}
 
 extern "C" int64_t gbt_sparse_capacity(int64_t nnz) {
     if (nnz < 0) return 0;
@@ -2197,7 +2206,7 @@ extern "C" int32_t gbt_compress_sparse_count(gbt_ctx *ctx, const uint16_t *sym, 
 }
 
 extern "C" int32_t gbt_compress_sparse(gbt_ctx *ctx, const uint16_t *sym, int64_t n, int32_t F, int32_t max_bins,
-                                       int32_t missing_sym, const uint32_t *rowptr, int64_t nnz, uint16_t *ent_out,
+                                       int32_t missing_sym, const uint32_t *rowptr, int64_t nnz, void *ent_out,
                                        int64_t ent_capacity) {
     if (!ctx) return GBT_EINVAL;
     GBT_REQUIRE(ctx, sym && rowptr && ent_out, GBT_EINVAL, "NULL argument");
@@ -2207,12 +2216,12 @@ extern "C" int32_t gbt_compress_sparse(gbt_ctx *ctx, const uint16_t *sym, int64_
     GBT_REQUIRE(ctx, nnz >= 0 && ent_capacity >= gbt_sparse_capacity(nnz), GBT_ENOMEM,
                 "ent_out holds %lld entries, %lld needed", (long long)ent_capacity, (long long)gbt_sparse_capacity(nnz));
     GBT_REQUIRE(ctx, ((uintptr_t)ent_out & 3) == 0, GBT_EINVAL, "ent_out must be 4-byte aligned");
-    GBT_HIP(ctx, gbt_launch_sparse_fill(ctx->stream, sym, n, F, max_bins, (uint32_t)missing_sym, rowptr, ent_out, nnz,
-                                        gbt_sparse_capacity(nnz)));
+    GBT_HIP(ctx, gbt_launch_sparse_fill(ctx->stream, sym, n, F, max_bins, (uint32_t)missing_sym, rowptr, ent_out,
+                                        sparse_ent_bytes(F, max_bins), nnz, gbt_sparse_capacity(nnz)));
     return GBT_OK;
 }
 
-extern "C" int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+extern "C" int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int64_t n,
                                          int32_t F, int32_t B, int64_t row_begin, int64_t n_node_rows,
                                          const int32_t *gq, int64_t *hist_out) {
     if (!ctx) return GBT_EINVAL;
@@ -2233,8 +2242,8 @@ extern "C" int32_t gbt_build_hist_sparse(gbt_ctx *ctx, const uint32_t *rowptr, c
     st = stage(ctx, jobs.data(), jobs.size() * sizeof(HistJob), &slot);
     if (st != GBT_OK) return st;
     gbt_prof_begin(ctx, row_begin == 0 && n_node_rows == n ? GBT_PROF_HIST_ROOT : GBT_PROF_HIST_NODE, 0.0);
-    GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, rowptr, ent, gq, hist_out, (const HistJob *)slot, (int)jobs.size(), glen,
-                                        glen < bins));
+    GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, rowptr, ent, sparse_ent_bytes(F, B), gq, hist_out, (const HistJob *)slot,
+                                        (int)jobs.size(), glen, glen < bins));
     gbt_prof_end(ctx);
     return GBT_OK;
 }
@@ -2254,7 +2263,7 @@ SparseGrowLayout sparse_grow_layout_nodes(int64_t n, int64_t nnz, int F, int B, 
     L.gq = o; o += gbt_align((size_t)n * 8);
     for (int k = 0; k < 2; ++k) {
         L.rowptr[k] = o; o += gbt_align((size_t)(n + 1) * 4);
-        L.ent[k] = o;    o += gbt_align((size_t)gbt_sparse_capacity(nnz) * 2);
+        L.ent[k] = o;    o += gbt_align((size_t)gbt_sparse_capacity(nnz) * sparse_ent_bytes(F, B));
         L.wgq[k] = o;    o += gbt_align((size_t)n * 8);
     }
     L.state = o;      o += gbt_align((size_t)L.level_nodes * 16);
@@ -2278,7 +2287,7 @@ SparseGrowLayout sparse_grow_layout(int64_t n, int64_t nnz, int F, int B, int ma
 
 extern "C" size_t gbt_grow_tree_sparse_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
                                                        int32_t max_depth) {
-    if (n < 0 || nnz < 0 || F < 1 || max_bins < 2 || (int64_t)F * max_bins > 65536 || max_depth < 0 ||
+    if (n < 0 || nnz < 0 || F < 1 || max_bins < 2 || (int64_t)F * max_bins > kSparseMaxIds || max_depth < 0 ||
         max_depth > kMaxDepth)
         return 0;
     return sparse_grow_layout(n, nnz, F, max_bins, max_depth).total;
@@ -2288,7 +2297,7 @@ extern "C" size_t gbt_grow_tree_sparse_workspace_bytes(int64_t n, int64_t nnz, i
 // and for loss-guided growth the physical and the logical tree, exactly as there).  Rows move without ids through
 // one-launch unordered partitions; leaf ids come from a walk of the finished tree, the row order from a stable sort
 // by leaf rank.
-static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int64_t n,
                                 int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
                                 const float *gpair, const gbt_params *params, int policy, int32_t max_leaves, gbt_tree *tree,
                                 uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace,
@@ -2324,10 +2333,11 @@ static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint
     int64_t *pool = (int64_t *)(ws + L.pool);
     const int64_t bins = (int64_t)F * B, hist_len = bins * 2;
     const int glen = gbt_sparse_hist_tile(ctx, bins);
-    struct Rows { const uint32_t *rowptr; const uint16_t *ent; const int32_t *gq; };
+    const int ent_bytes = sparse_ent_bytes(F, B);
+    struct Rows { const uint32_t *rowptr; const void *ent; const int32_t *gq; };
     const Rows canon{rowptr, ent, gq};
     uint32_t *w_rowptr[2] = {(uint32_t *)(ws + L.rowptr[0]), (uint32_t *)(ws + L.rowptr[1])};
-    uint16_t *w_ent[2] = {(uint16_t *)(ws + L.ent[0]), (uint16_t *)(ws + L.ent[1])};
+    void *w_ent[2] = {(void *)(ws + L.ent[0]), (void *)(ws + L.ent[1])};
     int32_t *w_gq[2] = {(int32_t *)(ws + L.wgq[0]), (int32_t *)(ws + L.wgq[1])};
     auto rows_of = [&](int buf) { return buf == 2 ? canon : Rows{w_rowptr[buf], w_ent[buf], w_gq[buf]}; };
     std::vector<float> hcuts((size_t)F * (B - 1));
@@ -2346,7 +2356,7 @@ static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint
     const double inv_sg = 1.0 / scale[0], inv_sh = 1.0 / scale[1];
     const double lambda = params->lambda;
     const double min_gain = std::max(params->gamma, (double)GBT_GAIN_FLOOR);
-    const double row_bytes = 12.0 + 2.0 * (double)nnz / (double)n;   // row pointer, pair, the average row's entries
+    const double row_bytes = 12.0 + (double)ent_bytes * (double)nnz / (double)n;   // row pointer, pair, the average row's entries
 
     std::vector<HistJob> hjobs;
     auto launch_hist = [&](const Rows &R, int cls, double bytes) -> int32_t {
@@ -2356,7 +2366,7 @@ static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint
             int32_t st2 = upload(ctx, hjobs.data() + j0, nj * sizeof(HistJob), ws + L.jobs);
             if (st2 != GBT_OK) return st2;
             gbt_prof_begin(ctx, cls, j0 == 0 ? bytes : 0.0);
-            GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, R.rowptr, R.ent, R.gq, pool, (const HistJob *)(ws + L.jobs), (int)nj,
+            GBT_HIP(ctx, gbt_launch_sparse_hist(ctx, R.rowptr, R.ent, ent_bytes, R.gq, pool, (const HistJob *)(ws + L.jobs), (int)nj,
                                                 glen, glen < bins));
             gbt_prof_end(ctx);
         }
@@ -2536,7 +2546,7 @@ static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint
         st = upload(ctx, pjobs.data(), pjobs.size() * sizeof(PartJob), ws + L.jobs);
         if (st != GBT_OK) return st;
         gbt_prof_begin(ctx, GBT_PROF_PARTITION, part_rows * (children_need_hist ? 2.0 * row_bytes : row_bytes - 8.0));
-        GBT_HIP(ctx, gbt_launch_sparse_partition(s, cur.rowptr, cur.ent, cur.gq, w_rowptr[wnext], w_ent[wnext], w_gq[wnext],
+        GBT_HIP(ctx, gbt_launch_sparse_partition(s, cur.rowptr, cur.ent, ent_bytes, cur.gq, w_rowptr[wnext], w_ent[wnext], w_gq[wnext],
                                                  B, children_need_hist, (const PartJob *)(ws + L.jobs), (int)pjobs.size(),
                                                  (int)tile_cursor, (unsigned long long *)(ws + L.state)));
         GBT_HIP(ctx, hipMemcpyAsync(rb(ctx), ws + L.state, pjobs.size() * 16, hipMemcpyDeviceToHost, s));
@@ -2608,7 +2618,7 @@ static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint
     // ---- each row's leaf by a walk of the finished tree; the row order by a stable sort on leaf rank
     int32_t *leaf_ids = leaf_of_row_out ? leaf_of_row_out : (int32_t *)w_rowptr[0];
     if (leaf_of_row_out || row_idx_out) {
-        const SparseRowsArg sr{rowptr, ent, B};
+        const SparseRowsArg sr{rowptr, ent, ent_bytes, B};
         gbt_prof_begin(ctx, GBT_PROF_OTHER, (double)n * (row_bytes - 8.0 + 4.0));
         st = predict_impl(ctx, tree, 1, nullptr, 1, 0, nullptr, n, F, 0.0, nullptr, leaf_ids, ws + L.tree_stage,
                           L.tree_stage_bytes, &sr);
@@ -2645,7 +2655,7 @@ static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const uint
     return GBT_OK;
 }
 
-extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int64_t n,
                                         int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
                                         const float *gpair, const gbt_params *params, gbt_tree *tree,
                                         uint32_t *row_idx_out, int32_t *leaf_of_row_out, void *workspace,
@@ -2656,12 +2666,12 @@ extern "C" int32_t gbt_grow_tree_sparse(gbt_ctx *ctx, const uint32_t *rowptr, co
 
 extern "C" size_t gbt_grow_tree_sparse_lossguide_workspace_bytes(int64_t n, int64_t nnz, int32_t F, int32_t max_bins,
                                                                  int32_t max_leaves) {
-    if (n < 0 || nnz < 0 || F < 1 || max_bins < 2 || (int64_t)F * max_bins > 65536 || max_leaves < 1 || max_leaves > kMaxLeaves)
+    if (n < 0 || nnz < 0 || F < 1 || max_bins < 2 || (int64_t)F * max_bins > kSparseMaxIds || max_leaves < 1 || max_leaves > kMaxLeaves)
         return 0;
     return sparse_grow_layout_nodes(n, nnz, F, max_bins, lossguide_phys_nodes(max_leaves), kLossguideBatchMax).total;
 }
 
-extern "C" int32_t gbt_grow_tree_sparse_lossguide(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, int64_t n,
+extern "C" int32_t gbt_grow_tree_sparse_lossguide(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int64_t n,
                                                   int64_t nnz, int32_t F, const int32_t *nb, const float *cuts,
                                                   const float *gpair, const gbt_params *params, int32_t max_leaves,
                                                   gbt_tree *tree, uint32_t *row_idx_out, int32_t *leaf_of_row_out,
@@ -2671,13 +2681,13 @@ extern "C" int32_t gbt_grow_tree_sparse_lossguide(gbt_ctx *ctx, const uint32_t *
 }
 
 extern "C" int32_t gbt_predict_sparse(gbt_ctx *ctx, const gbt_tree *trees, int32_t n_trees, const uint32_t *rowptr,
-                                      const uint16_t *ent, int64_t n, int32_t F, int32_t max_bins, double eta,
+                                      const void *ent, int64_t n, int32_t F, int32_t max_bins, double eta,
                                       float *margin, void *workspace, size_t workspace_bytes) {
     if (!ctx) return GBT_EINVAL;
     GBT_REQUIRE(ctx, rowptr && ent && margin, GBT_EINVAL, "NULL argument");
     int32_t st = check_sparse_shape(ctx, n, F, max_bins);
     if (st != GBT_OK) return st;
-    const SparseRowsArg sr{rowptr, ent, max_bins};
+    const SparseRowsArg sr{rowptr, ent, sparse_ent_bytes(F, max_bins), max_bins};
     st = predict_impl(ctx, trees, n_trees, nullptr, 1, 0, nullptr, n, F, eta, margin, nullptr, workspace, workspace_bytes,
                       &sr, true);
     if (st != GBT_OK) return st;

@@ -381,28 +381,28 @@ hipError_t gbt_launch_order_rows(hipStream_t s, const int32_t *leaf, const uint3
                                  uint32_t n_ranks, int64_t n, uint32_t *key_tmp[2], uint32_t *val_tmp[2], char *ws,
                                  uint32_t *row_idx_out);
 
-// sparse rows (kernels_sparse.hip): rowptr + 16-bit global bin ids, see there
+// sparse rows (kernels_sparse.hip): rowptr + global bin ids of ent_bytes = 2 or 4 bytes each, see there
 int64_t gbt_sparse_scan_tiles(int64_t n);
 hipError_t gbt_launch_sparse_rowptr(hipStream_t s, const uint16_t *sym, int64_t n, int F, uint32_t missing,
                                     uint32_t *rowptr, uint64_t *tile_ws, uint64_t *total_dev);
 hipError_t gbt_launch_sparse_fill(hipStream_t s, const uint16_t *sym, int64_t n, int F, int B, uint32_t missing,
-                                  const uint32_t *rowptr, uint16_t *ent, int64_t nnz, int64_t capacity);
+                                  const uint32_t *rowptr, void *ent, int ent_bytes, int64_t nnz, int64_t capacity);
 int gbt_sparse_hist_tile(const gbt_ctx *ctx, int64_t bins);
 // HistJob.f0 / ft: the job's range of global bin ids
-hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, const int32_t *gq,
+hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int ent_bytes, const int32_t *gq,
                                   int64_t *pool, const HistJob *jobs, int n_jobs, int max_glen, bool tiled);
 
 // Unordered partition of sparse rows, one launch per level (PartJob as for the dense forms; tiles of
 // gbt_sparse_part_tile() rows).  cursor: two 64-bit words per job, cleared here; afterwards the low
 // word of cursor[2 * j] is job j's number of left rows.  move == false: only that count.
 int gbt_sparse_part_tile();
-hipError_t gbt_launch_sparse_partition(hipStream_t s, const uint32_t *src_rowptr, const uint16_t *src_ent,
-                                       const int32_t *src_gq, uint32_t *dst_rowptr, uint16_t *dst_ent,
+hipError_t gbt_launch_sparse_partition(hipStream_t s, const uint32_t *src_rowptr, const void *src_ent, int ent_bytes,
+                                       const int32_t *src_gq, uint32_t *dst_rowptr, void *dst_ent,
                                        int32_t *dst_gq, int B, bool move, const PartJob *jobs, int n_jobs,
                                        int n_tiles, unsigned long long *cursor);
 struct DevTree;
 hipError_t gbt_launch_sparse_walk(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
-                                  const uint32_t *rowptr, const uint16_t *ent, int64_t n, int B, double eta,
+                                  const uint32_t *rowptr, const void *ent, int ent_bytes, int64_t n, int B, double eta,
                                   float *margin, int32_t *leaf_out, int max_nodes);
 
 hipError_t gbt_launch_compress(hipStream_t s, const uint16_t *sym, int64_t n_elems, int bits,

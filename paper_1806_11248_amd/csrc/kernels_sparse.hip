@@ -1,12 +1,14 @@
 // Sparse-native row layout (Sec. 1: sparse input is supported; Sec. 2.2: the quantised matrix is
-// stored compressed).  A row keeps only its present elements, each as a 16-bit global bin id
-//     gid = feature * B + symbol            (B = max_bins, F * B <= 65536),
-// ascending inside the row; rowptr[r] .. rowptr[r+1] delimit row r in the entry stream.  A missing
+// stored compressed).  A row keeps only its present elements, each as a global bin id
+//     gid = feature * B + symbol            (B = max_bins),
+// ascending inside the row; rowptr[r] .. rowptr[r+1] delimit row r in the entry stream.  An id takes 16 bits
+// where F * B <= 65536 and 32 bits in a wider matrix (gbt_sparse_entry_bytes; the kernels are templates over the
+// entry type E, the 16-bit histogram kernel is a form of its own).  A missing
 // element costs nothing instead of one symbol, so a matrix that is 80% empty moves about a third
 // of the bytes of its dense packing, and the histogram kernel issues atomics for present elements
 // only.  gid * 2 is also the element's place in the node's [F][B][2] histogram.
 //
-// The entry stream is read as aligned 32-bit words, nine words per row and step, so the buffer
+// The entry stream is read as aligned 32-bit words, up to nine words per row and step, so the buffer
 // must extend 32 entries past the last one (gbt_sparse_capacity).
 #include "gbt_internal.h"
 
@@ -125,20 +127,22 @@ __global__ __launch_bounds__(256) void scan_apply_u32_kernel(uint32_t *__restric
     }
 }
 
+template <typename E>
 __global__ __launch_bounds__(256) void sparse_fill_kernel(const uint16_t *__restrict__ sym, int64_t n, int F, int B,
                                                           uint32_t missing, const uint32_t *__restrict__ rowptr,
-                                                          uint16_t *__restrict__ ent) {
+                                                          E *__restrict__ ent) {
     for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < n; r += (int64_t)gridDim.x * 256) {
         const uint16_t *row = sym + r * F;
         uint32_t o = rowptr[r];
         for (int f = 0; f < F; ++f) {
             const uint32_t s = row[f];
-            if (s != missing) ent[o++] = (uint16_t)((uint32_t)f * (uint32_t)B + s);
+            if (s != missing) ent[o++] = (E)((uint32_t)f * (uint32_t)B + s);
         }
     }
 }
 
-__global__ __launch_bounds__(256) void fill_u16_tail_kernel(uint16_t *p, int count) {
+template <typename E>
+__global__ __launch_bounds__(256) void fill_tail_kernel(E *p, int count) {
     if ((int)threadIdx.x < count) p[threadIdx.x] = 0;
 }
 
@@ -217,6 +221,72 @@ __global__ __launch_bounds__(BLOCK) void sparse_hist_kernel(const uint32_t *__re
     }
 }
 
+// The same over 32-bit ids (a matrix of more than 65536 global bin ids, whose histogram never fits one LDS tile):
+// eight entries per step as two aligned four-word loads.  The ids of a row ascend, so a job that covers part of
+// the ids starts at the row's first entry inside its range (bisection) and leaves the row at the first step that
+// ends beyond it: a row's entries are visited about once over all the tiles, not once per tile.
+template <int BLOCK, bool TILED>
+__global__ __launch_bounds__(BLOCK) void sparse_hist32_kernel(const uint32_t *__restrict__ rowptr,
+                                                              const uint32_t *__restrict__ ent,
+                                                              const int2 *__restrict__ gq,
+                                                              int64_t *__restrict__ pool,
+                                                              const HistJob *__restrict__ jobs) {
+    extern __shared__ unsigned long long lds[];
+    const HistJob job = jobs[blockIdx.x];
+    const uint32_t g0 = job.f0, glen = job.ft;
+    int64_t *out = pool + job.hist_off + 2 * (int64_t)g0;
+    for (uint32_t i = threadIdx.x; i < glen; i += BLOCK) lds[i] = 0;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < job.n_rows; i += BLOCK) {
+        const uint64_t r = (uint64_t)job.row_begin + i;
+        const uint32_t s = rowptr[r], len = rowptr[r + 1] - s;
+        const int2 q = gq[r];
+        const unsigned long long addv = sp_pack_pair(q);
+        const uint32_t hq = (uint32_t)q.y;
+        const uint32_t *wp = ent + s;
+        uint32_t first = 0;
+        if (TILED) {   // first entry with an id >= g0
+            uint32_t b = len;
+            while (first < b) {
+                const uint32_t mid = first + ((b - first) >> 1);
+                if (wp[mid] < g0) first = mid + 1; else b = mid;
+            }
+        }
+        for (uint32_t k0 = first; k0 < len; k0 += 8) {
+            const Words4 lo = *(const Words4 *)(wp + k0);
+            const Words4 hi = *(const Words4 *)(wp + k0 + 4);
+            const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            const uint32_t rem = len - k0;
+            uint32_t rel[8];
+            unsigned long long old[8];
+            uint32_t live = 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                rel[k] = w[k] - g0;
+                bool in = (uint32_t)k < rem;
+                if (TILED) in = in && rel[k] < glen;
+                if (in) {
+                    live |= 1u << k;
+                    old[k] = atomicAdd(&lds[rel[k]], addv);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (live & (1u << k)) sp_check(out, rel[k], old[k], addv, hq);
+            if (TILED && rem > 7u && rel[7] >= glen) break;   // (rel >= 0 from `first` on: ascending ids)
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < glen; i += BLOCK) {
+        const unsigned long long w = lds[i];
+        if (w == 0) continue;
+        const int64_t g = (int64_t)w >> kHShift;
+        const int64_t h = (int64_t)(w & kHMask);
+        if (g != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i), (unsigned long long)g);
+        if (h != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i + 1), (unsigned long long)h);
+    }
+}
+
 // ---- RepartitionInstances over sparse rows ----------------------------------
 // One launch per level, order inside a child not kept.  A tile of kSpTile rows finds each row's
 // side (the row's entry of the split feature is looked up among its ascending ids; a row without
@@ -255,18 +325,19 @@ __device__ __forceinline__ uint32_t find_feature_entry(P ent, uint32_t s, uint32
 }
 
 // The entries of a tile's rows are one contiguous piece of the stream: it is fetched once, linearly,
-// into LDS (kSpStage entries; a tile with more falls back to reading and writing the stream row by
-// row), and the feature look-ups read it there.  The tile's left rows land in one contiguous piece of
+// into LDS (kSpStage / 2 words; a tile with more reads the stream in place and copies it row by row, a wave
+// at a time), and the feature look-ups read it there.  The tile's left rows land in one contiguous piece of
 // the destination stream and its right rows in another: both are put together inside LDS (a second
 // window, halfword-aligned like the destination) and leave as whole 32-bit words -- sub-word stores
 // retire about one lane per clock and compute unit, whatever their addresses.
 constexpr int kSpStage = 12288;
 
+template <typename E>
 __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *__restrict__ src_rowptr,
-                                                               const uint16_t *__restrict__ src_ent,
+                                                               const E *__restrict__ src_ent,
                                                                const int2 *__restrict__ src_gq,
                                                                uint32_t *__restrict__ dst_rowptr,
-                                                               uint16_t *__restrict__ dst_ent,
+                                                               E *__restrict__ dst_ent,
                                                                int2 *__restrict__ dst_gq, uint32_t B, int move,
                                                                const PartJob *__restrict__ jobs, int n_jobs,
                                                                unsigned long long *__restrict__ cursor) {
@@ -276,7 +347,8 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
     __shared__ uint32_t grp_ent[2][kSpGroups];
     __shared__ unsigned long long base[2];        // what the cursors returned
     __shared__ uint32_t tot[4];                   // rows L, rows R, entries L, entries R of the tile
-    const uint16_t *stage = (const uint16_t *)stage_w;
+    constexpr uint32_t EPW = 4 / sizeof(E), SH = EPW == 2 ? 1 : 0;   // entries per word, and its log2
+    const E *stage = (const E *)stage_w;
     const int j = find_part_job(jobs, n_jobs, blockIdx.x);
     const PartJob job = jobs[j];
     const uint32_t t_local = blockIdx.x - job.tile_begin;
@@ -288,13 +360,13 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
 
     // the tile's piece of the stream, from the word that holds its first entry
     const uint32_t e0 = src_rowptr[r0], e1 = src_rowptr[r1];
-    const uint32_t w0 = e0 >> 1, n_words = ((e1 + 1) >> 1) - w0;
+    const uint32_t w0 = e0 >> SH, n_words = ((e1 + EPW - 1) >> SH) - w0;
     const bool staged = n_words <= (uint32_t)(kSpStage / 2);
     if (staged) {
         const uint32_t *src_w = (const uint32_t *)src_ent + w0;
         for (uint32_t w = threadIdx.x; w < n_words; w += kSpBlock) stage_w[w] = src_w[w];
     }
-    const uint32_t sbase = w0 * 2;   // stream index of stage[0]
+    const uint32_t sbase = w0 << SH;   // stream index of stage[0]
 
     uint32_t rs[kSpRowsPerThread], rlen[kSpRowsPerThread], within_rows[kSpRowsPerThread], within_ent[kSpRowsPerThread];
     bool live[kSpRowsPerThread], left[kSpRowsPerThread];
@@ -373,26 +445,34 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
     const uint32_t row_l = job.seg_begin + (uint32_t)base[0], ent_l = ent_begin + (uint32_t)(base[0] >> 32);
     const uint32_t row_r = seg_end - (uint32_t)base[1] - tot[1], ent_r = ent_end - (uint32_t)(base[1] >> 32) - tot[3];
     if (t_local == 0 && threadIdx.x == 0) dst_rowptr[seg_end] = ent_end;   // the segment's closing row pointer
-    // where the two pieces sit in the output window: at the parity of their place in the stream
-    const uint32_t lds_l = ent_l & 1u;
-    const uint32_t lds_r = ((lds_l + tot[2] + 1u) & ~1u) + (ent_r & 1u);
-    uint16_t *out16 = (uint16_t *)out_w;
+    // where the two pieces sit in the output window: at the place inside a word that they have in the stream
+    const uint32_t lds_l = ent_l & (EPW - 1u);
+    const uint32_t lds_r = ((lds_l + tot[2] + EPW - 1u) & ~(EPW - 1u)) + (ent_r & (EPW - 1u));
+    E *outE = (E *)out_w;
 #pragma unroll
     for (int k = 0; k < kSpRowsPerThread; ++k) {
-        if (!live[k]) continue;
         const int grp = k * (kSpBlock / 64) + wave;
         const int side = left[k] ? 0 : 1;
         const uint32_t in_piece = grp_ent[side][grp] + within_ent[k];   // the row's place inside its side's piece
         const uint32_t drow = (left[k] ? row_l : row_r) + grp_rows[side][grp] + within_rows[k];
         const uint32_t dent = (left[k] ? ent_l : ent_r) + in_piece;
-        dst_rowptr[drow] = dent;
-        dst_gq[drow] = pair[k];
-        if (staged) {
-            const uint16_t *from = stage + (rs[k] - sbase);
-            uint16_t *to = out16 + (left[k] ? lds_l : lds_r) + in_piece;
-            for (uint32_t q = 0; q < rlen[k]; ++q) to[q] = from[q];
-        } else {
-            for (uint32_t q = 0; q < rlen[k]; ++q) dst_ent[dent + q] = src_ent[rs[k] + q];
+        if (live[k]) {
+            dst_rowptr[drow] = dent;
+            dst_gq[drow] = pair[k];
+            if (staged) {
+                const E *from = stage + (rs[k] - sbase);
+                E *to = outE + (left[k] ? lds_l : lds_r) + in_piece;
+                for (uint32_t q = 0; q < rlen[k]; ++q) to[q] = from[q];
+            }
+        }
+        if (!staged) {   // the wave copies its rows one after the other, 64 entries at a time (rlen is 0 off the tile)
+            for (int l = 0; l < 64; ++l) {
+                const uint32_t len_l = (uint32_t)__builtin_amdgcn_readlane((int)rlen[k], l);
+                if (len_l == 0) continue;
+                const uint32_t src_l = (uint32_t)__builtin_amdgcn_readlane((int)rs[k], l);
+                const uint32_t dst_l = (uint32_t)__builtin_amdgcn_readlane((int)dent, l);
+                for (uint32_t q = lane; q < len_l; q += 64) dst_ent[dst_l + q] = src_ent[src_l + q];
+            }
         }
     }
     if (!staged) return;
@@ -401,12 +481,13 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
         const uint32_t gs = side == 0 ? ent_l : ent_r, ge = gs + tot[2 + side];   // the piece in the stream
         const uint32_t ls = side == 0 ? lds_l : lds_r;                             // and in the window
         if (gs == ge) continue;
-        const uint32_t wfirst = (gs + 1) >> 1, wend = ge >> 1;                     // whole words [wfirst, wend)
-        const uint32_t lw = (ls + (gs & 1u)) >> 1;                                 // window word of stream word wfirst
+        const uint32_t wfirst = (gs + EPW - 1u) >> SH, wend = ge >> SH;            // whole words [wfirst, wend)
+        const uint32_t lw = (ls + (gs & (EPW - 1u))) >> SH;                        // window word of stream word wfirst
         uint32_t *dst_words = (uint32_t *)dst_ent;
         for (uint32_t w = threadIdx.x; wfirst + w < wend; w += kSpBlock) dst_words[wfirst + w] = out_w[lw + w];
-        if (threadIdx.x == 0 && (gs & 1u)) dst_ent[gs] = out16[ls];
-        if (threadIdx.x == 64 && (ge & 1u) && (ge - 1 >= gs)) dst_ent[ge - 1] = out16[ls + (ge - 1 - gs)];
+        // (16-bit ids: a piece may begin and end in the middle of a word)
+        if (threadIdx.x == 0 && (gs & (EPW - 1u))) dst_ent[gs] = outE[ls];
+        if (threadIdx.x == 64 && (ge & (EPW - 1u)) && (ge - 1 >= gs)) dst_ent[ge - 1] = outE[ls + (ge - 1 - gs)];
     }
 }
 
@@ -422,9 +503,10 @@ struct SpNode {
 // linearly into its own LDS window (kWalkWords words; a longer piece is read from the stream
 // directly) and every level's look-up bisects there.
 constexpr int kWalkWords = 1024;
+template <typename E>
 __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const DevTree *trees, int n_trees,
                                                           const uint32_t *__restrict__ rowptr,
-                                                          const uint16_t *__restrict__ ent, int64_t n, uint32_t B,
+                                                          const E *__restrict__ ent, int64_t n, uint32_t B,
                                                           double eta, float *margin, int32_t *leaf_out,
                                                           int rows_per_block, int max_nodes) {
     // max_nodes == 0: the trees are too large for LDS, their nodes are read from the staged arrays
@@ -432,7 +514,8 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
     extern __shared__ SpNode sp_nodes[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t *st = (uint32_t *)(sp_nodes + max_nodes) + wave * kWalkWords;
-    const uint16_t *st16 = (const uint16_t *)st;
+    constexpr uint32_t EPW = 4 / sizeof(E), SH = EPW == 2 ? 1 : 0;
+    const E *stE = (const E *)st;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
     for (int t = 0; t < n_trees; ++t) {
@@ -457,7 +540,7 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
             const int last = 63 - (int)__builtin_clzll(__ballot(live));   // lane 0 is live
             const uint32_t ws0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s);
             const uint32_t we = (uint32_t)__builtin_amdgcn_readlane((int)e, last);
-            const uint32_t word0 = ws0 >> 1, n_words = ((we + 1) >> 1) - word0;
+            const uint32_t word0 = ws0 >> SH, n_words = ((we + EPW - 1) >> SH) - word0;
             const bool fits = n_words <= (uint32_t)kWalkWords;
             if (fits) {
                 const uint32_t *src_w = (const uint32_t *)ent + word0;
@@ -467,7 +550,7 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             if (live) {
-                const uint32_t sb = word0 * 2;
+                const uint32_t sb = word0 << SH;
                 int node = 0;
                 for (int step = 0; step < T.n_nodes; ++step) {
                     SpNode nd;
@@ -482,7 +565,7 @@ __global__ __launch_bounds__(256) void sparse_walk_kernel(const char *ws, const 
                     }
                     if (nd.feature < 0) break;
                     const uint32_t lo = (uint32_t)nd.feature * B;
-                    const uint32_t g = fits ? find_feature_entry(st16, s - sb, e - sb, lo, B)
+                    const uint32_t g = fits ? find_feature_entry(stE, s - sb, e - sb, lo, B)
                                             : find_feature_entry(ent, s, e, lo, B);
                     const bool go_left = g == 0xffffffffu ? nd.dl != 0 : g <= lo + (uint32_t)nd.bin;
                     node = go_left ? nd.left : nd.right;
@@ -519,10 +602,16 @@ hipError_t gbt_launch_sparse_rowptr(hipStream_t s, const uint16_t *sym, int64_t 
 }
 
 hipError_t gbt_launch_sparse_fill(hipStream_t s, const uint16_t *sym, int64_t n, int F, int B, uint32_t missing,
-                                  const uint32_t *rowptr, uint16_t *ent, int64_t nnz, int64_t capacity) {
-    if (n > 0) sparse_fill_kernel<<<grid_rows(n), 256, 0, s>>>(sym, n, F, B, missing, rowptr, ent);
+                                  const uint32_t *rowptr, void *ent, int ent_bytes, int64_t nnz, int64_t capacity) {
     const int64_t tail = capacity - nnz;   // the slack that word-wise readers may touch: defined values
-    if (tail > 0) fill_u16_tail_kernel<<<1, 256, 0, s>>>(ent + nnz, (int)(tail < 256 ? tail : 256));
+    const int tail_n = (int)(tail < 256 ? tail : 256);
+    if (ent_bytes == 2) {
+        if (n > 0) sparse_fill_kernel<uint16_t><<<grid_rows(n), 256, 0, s>>>(sym, n, F, B, missing, rowptr, (uint16_t *)ent);
+        if (tail > 0) fill_tail_kernel<uint16_t><<<1, 256, 0, s>>>((uint16_t *)ent + nnz, tail_n);
+    } else {
+        if (n > 0) sparse_fill_kernel<uint32_t><<<grid_rows(n), 256, 0, s>>>(sym, n, F, B, missing, rowptr, (uint32_t *)ent);
+        if (tail > 0) fill_tail_kernel<uint32_t><<<1, 256, 0, s>>>((uint32_t *)ent + nnz, tail_n);
+    }
     return hipGetLastError();
 }
 
@@ -539,11 +628,27 @@ int gbt_sparse_hist_tile(const gbt_ctx *ctx, int64_t bins) {
 }
 
 // tiled: the jobs cover parts of the id range [0, bins)
-hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const uint16_t *ent, const int32_t *gq,
+hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const void *ent, int ent_bytes, const int32_t *gq,
                                   int64_t *pool, const HistJob *jobs, int n_jobs, int max_glen, bool tiled) {
     if (n_jobs <= 0) return hipSuccess;
     const size_t lds = (size_t)max_glen * 8;
     const bool big = lds > 64u * 1024u;   // one workgroup per compute unit: make it a large one
+    if (ent_bytes == 4) {
+        const void *fn32 = big ? (tiled ? (const void *)sparse_hist32_kernel<1024, true> : (const void *)sparse_hist32_kernel<1024, false>)
+                               : (tiled ? (const void *)sparse_hist32_kernel<512, true> : (const void *)sparse_hist32_kernel<512, false>);
+        GbtLdsGuard lds_guard(lds);
+        if (lds_guard.needed) {
+            hipError_t e = hipFuncSetAttribute(fn32, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        const uint32_t *e32 = (const uint32_t *)ent;
+        const int2 *g2 = (const int2 *)gq;
+        if (big && tiled) sparse_hist32_kernel<1024, true><<<n_jobs, 1024, lds, ctx->stream>>>(rowptr, e32, g2, pool, jobs);
+        else if (big) sparse_hist32_kernel<1024, false><<<n_jobs, 1024, lds, ctx->stream>>>(rowptr, e32, g2, pool, jobs);
+        else if (tiled) sparse_hist32_kernel<512, true><<<n_jobs, 512, lds, ctx->stream>>>(rowptr, e32, g2, pool, jobs);
+        else sparse_hist32_kernel<512, false><<<n_jobs, 512, lds, ctx->stream>>>(rowptr, e32, g2, pool, jobs);
+        return hipGetLastError();
+    }
     const void *fn = big ? (tiled ? (const void *)sparse_hist_kernel<1024, true> : (const void *)sparse_hist_kernel<1024, false>)
                          : (tiled ? (const void *)sparse_hist_kernel<512, true> : (const void *)sparse_hist_kernel<512, false>);
     GbtLdsGuard lds_guard(lds);
@@ -562,34 +667,44 @@ hipError_t gbt_launch_sparse_hist(gbt_ctx *ctx, const uint32_t *rowptr, const ui
 
 int gbt_sparse_part_tile() { return kSpTile; }
 
-hipError_t gbt_launch_sparse_partition(hipStream_t s, const uint32_t *src_rowptr, const uint16_t *src_ent,
-                                       const int32_t *src_gq, uint32_t *dst_rowptr, uint16_t *dst_ent,
+hipError_t gbt_launch_sparse_partition(hipStream_t s, const uint32_t *src_rowptr, const void *src_ent, int ent_bytes,
+                                       const int32_t *src_gq, uint32_t *dst_rowptr, void *dst_ent,
                                        int32_t *dst_gq, int B, bool move, const PartJob *jobs, int n_jobs,
                                        int n_tiles, unsigned long long *cursor) {
     if (n_jobs <= 0 || n_tiles <= 0) return hipSuccess;
     hipError_t e = gbt_launch_fill_u64(s, (uint64_t *)cursor, 0, 2 * (int64_t)n_jobs);
     if (e != hipSuccess) return e;
-    sparse_part_kernel<<<n_tiles, kSpBlock, 0, s>>>(src_rowptr, src_ent, (const int2 *)src_gq, dst_rowptr, dst_ent,
-                                                    (int2 *)dst_gq, (uint32_t)B, move ? 1 : 0, jobs, n_jobs, cursor);
+    if (ent_bytes == 2)
+        sparse_part_kernel<uint16_t><<<n_tiles, kSpBlock, 0, s>>>(src_rowptr, (const uint16_t *)src_ent, (const int2 *)src_gq,
+                                                                  dst_rowptr, (uint16_t *)dst_ent, (int2 *)dst_gq, (uint32_t)B,
+                                                                  move ? 1 : 0, jobs, n_jobs, cursor);
+    else
+        sparse_part_kernel<uint32_t><<<n_tiles, kSpBlock, 0, s>>>(src_rowptr, (const uint32_t *)src_ent, (const int2 *)src_gq,
+                                                                  dst_rowptr, (uint32_t *)dst_ent, (int2 *)dst_gq, (uint32_t)B,
+                                                                  move ? 1 : 0, jobs, n_jobs, cursor);
     return hipGetLastError();
 }
 
 // the trees staged as for gbt_launch_predict; a tree's nodes go through LDS (32 bytes each) when they fit
 hipError_t gbt_launch_sparse_walk(hipStream_t s, const char *ws, const DevTree *trees, int n_trees,
-                                  const uint32_t *rowptr, const uint16_t *ent, int64_t n, int B, double eta,
+                                  const uint32_t *rowptr, const void *ent, int ent_bytes, int64_t n, int B, double eta,
                                   float *margin, int32_t *leaf_out, int max_nodes) {
     if (n <= 0 || n_trees <= 0) return hipSuccess;
     if ((size_t)max_nodes * sizeof(SpNode) + 4 * kWalkWords * 4 > 120u * 1024u) max_nodes = 0;   // nodes stay in HBM / L2
     const size_t lds = (size_t)max_nodes * sizeof(SpNode) + 4 * kWalkWords * 4;
+    const void *fn = ent_bytes == 2 ? (const void *)sparse_walk_kernel<uint16_t> : (const void *)sparse_walk_kernel<uint32_t>;
     GbtLdsGuard lds_guard(lds);
     if (lds_guard.needed) {
-        hipError_t e = hipFuncSetAttribute((const void *)sparse_walk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     const int rows_per_block = 2048;
     const int64_t grid = (n + rows_per_block - 1) / rows_per_block;
-    sparse_walk_kernel<<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, rowptr, ent, n, (uint32_t)B, eta, margin,
-                                                        leaf_out, rows_per_block, max_nodes);
+    if (ent_bytes == 2)
+        sparse_walk_kernel<uint16_t><<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, rowptr, (const uint16_t *)ent, n,
+                                                                      (uint32_t)B, eta, margin, leaf_out, rows_per_block, max_nodes);
+    else
+        sparse_walk_kernel<uint32_t><<<(unsigned)grid, 256, lds, s>>>(ws, trees, n_trees, rowptr, (const uint32_t *)ent, n,
+                                                                      (uint32_t)B, eta, margin, leaf_out, rows_per_block, max_nodes);
     return hipGetLastError();
 }

@@ -41,7 +41,11 @@ def test_host_only_calls(lib):
     # sparse rows: an even number of entries plus the slack that word-wise readers may touch
     assert lib.gbt_sparse_capacity(0) == 32 and lib.gbt_sparse_capacity(5) == 38 and lib.gbt_sparse_capacity(-1) == 0
     assert lib.gbt_grow_tree_sparse_workspace_bytes(1000, 5000, 50, 256, 8) > 2 * 5000 * 2
-    assert lib.gbt_grow_tree_sparse_workspace_bytes(1000, 5000, 300, 256, 8) == 0   # 76,800 global bin ids
+    # 76,800 global bin ids take 32-bit entries; more than 2^28 ids are no valid shape
+    assert lib.gbt_grow_tree_sparse_workspace_bytes(1000, 5000, 300, 256, 8) > 2 * 5000 * 4
+    assert lib.gbt_grow_tree_sparse_workspace_bytes(1000, 5000, 5000, 60_000, 8) == 0
+    assert lib.gbt_sparse_entry_bytes(256, 256) == 2 and lib.gbt_sparse_entry_bytes(300, 256) == 4
+    assert lib.gbt_sparse_entry_bytes(5000, 60_000) == 0 and lib.gbt_sparse_entry_bytes(0, 256) == 0
     # loss-guided growth keeps histograms for the nodes it expands ahead of their turn
     assert (lib.gbt_grow_tree_lossguide_workspace_bytes(1000, 8, 4, 16, 64)
             > lib.gbt_grow_tree_workspace_bytes(1000, 8, 4, 16, 6))

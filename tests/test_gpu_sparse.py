@@ -47,7 +47,7 @@ def reference_rows(sym, B, missing):
     rowptr = np.zeros(n + 1, np.int64)
     np.cumsum(present.sum(1), out=rowptr[1:])
     gid = (np.arange(F, dtype=np.int64)[None, :] * B + sym.astype(np.int64))[present]   # row-major: ascending per row
-    return rowptr, gid.astype(np.uint16)
+    return rowptr, gid.astype(np.uint16 if F * B <= 65536 else np.uint32)   # wider matrices: 32-bit ids
 
 
 LAYOUT_CASES = [  # n, F, B, miss
@@ -57,6 +57,10 @@ LAYOUT_CASES = [  # n, F, B, miss
     (4_099, 7, 1000, 0.5),
     (1, 3, 4, 0.0),
     (70, 5, 16, 1.0),            # nothing present at all
+    (6_007, 300, 256, 0.9),      # 76,800 global bin ids: 32-bit entries, the histogram in id-range tiles
+    (2_500, 1100, 64, 0.97),     # 70,400 ids over many features
+    (1_201, 90, 1000, 0.0),      # 90,000 ids, every row with 90 entries
+    (40, 257, 256, 1.0),         # 32-bit entries, nothing present
 ]
 
 
@@ -68,7 +72,9 @@ def test_compress_sparse_and_hist(ctx, oracle, n, F, B, miss):
     ref_ptr, ref_ent = reference_rows(sym, B, missing)
     assert nnz == ref_ptr[-1]
     assert np.array_equal(host_u32(rowptr).astype(np.int64), ref_ptr)
-    assert np.array_equal(ent.cpu().numpy()[:nnz], ref_ent)
+    assert ent.element_size() == ref_ent.itemsize
+    assert np.array_equal(ent.cpu().view(torch.int16 if ref_ent.itemsize == 2 else torch.int32).numpy()[:nnz].view(ref_ent.dtype),
+                          ref_ent)
     gq, scale = ctx.gpair_fixed(dev(gp))
     for b, m in ((0, n), (n // 3, n - n // 3 - n // 5), (n // 2, 1 if n > 1 else 0), (0, 0)):
         rows = np.arange(b, b + m, dtype=np.uint32)
@@ -110,6 +116,8 @@ def test_sparse_hist_extreme_pile_up(ctx, oracle):
 
 
 TREE_CASES = [  # config, rows, kwargs, max_depth override
+    (3, 30_000, {"F": 300}, None),        # 300 x 256 = 76,800 global bin ids: 32-bit entries, 80% missing
+    (5, 6_000, {"F": 1200}, 6),           # 76,800 ids, nothing missing: rows of 1200 entries (no tile fits LDS)
     (3, 60_000, {}, None),                # the sparse workload: 50 features, 80% missing, depth 8
     (3, 9_000, {}, 11),                   # deep: more than 256 leaves, tiny nodes, many leaves above the last level
     (2, 40_000, {}, 13),                  # a tree too large for the walk's LDS: nodes are read from memory
@@ -182,7 +190,9 @@ def test_sparse_tree_depth_zero(ctx, oracle):
 def test_sparse_argument_errors(ctx):
     import paper_1806_11248_amd as g
     from paper_1806_11248_amd import binding
-    sym = dev(np.zeros((10, 300), np.uint16))
+    sym = dev(np.zeros((10, 5000), np.uint16))
     with pytest.raises(g.GbtError) as e:
-        ctx.compress_sparse(sym, 256, 256)          # 300 * 256 ids do not fit 16 bits
+        ctx.compress_sparse(sym, 60_000, 60_000)    # 3 * 10^8 global bin ids: more than the form takes
     assert e.value.code == binding.EUNSUPPORTED
+    assert ctx.lib.gbt_sparse_entry_bytes(256, 256) == 2 and ctx.lib.gbt_sparse_entry_bytes(257, 256) == 4
+    assert ctx.lib.gbt_sparse_entry_bytes(5000, 60_000) == 0
