@@ -1165,7 +1165,11 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 enodes[i] = EvalNode{(uint64_t)level[i].id * (uint64_t)hist_len, level[i].Gq, level[i].Hq,
                                      level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_parent * (uint64_t)hist_len : GBT_NO_HIST,
                                      level[i].sub_parent >= 0 ? (uint64_t)level[i].sub_built * (uint64_t)hist_len : GBT_NO_HIST};
-            st = enqueue_eval(enodes, &chunks);
+            // (depth-wise, the children of the deepest nodes that are evaluated are leaves: a histogram made by
+            // subtraction there is priced and forgotten)
+            EvalTail plain{nullptr, nullptr, 0, 0, -1, 0};
+            plain.skip_store = !lossguide && level[0].depth >= max_depth - 1 ? 1 : 0;
+            st = enqueue_eval(enodes, &chunks, nullptr, plain);
             if (st != GBT_OK) return st;
             GBT_SYNC(ctx);
         }
@@ -1589,7 +1593,7 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 st = enqueue_eval(enodes, &chunks, children_dev,
                                   EvalTail{(unsigned long long *)(ws + L.state), (unsigned long long *)rb(ctx),
                                            nomove2 ? 2 * (int)h2jobs.size() : (int)pjobs.size(), 1, more ? after : -1, zero_end,
-                                           kCursorStride});
+                                           kCursorStride, !lossguide && child_depth >= max_depth - 1 ? 1 : 0});
                 if (st != GBT_OK) return st;
                 pool_zero_end = zero_end;
                 pre_eval = true;
@@ -2445,8 +2449,11 @@ static int32_t sparse_grow_impl(gbt_ctx *ctx, const uint32_t *rowptr, const void
             GBT_REQUIRE(ctx, sbytes <= budget, GBT_EUNSUPPORTED, "level too wide");
             gbt_prof_begin(ctx, GBT_PROF_EVAL, (double)enodes.size() * (double)hist_len * 8.0);
             // (the records go straight into the pinned read-back buffer: no copy launch before the wait)
+            EvalTail plain{nullptr, nullptr, 0, 0, -1, 0};
+            plain.skip_store = !lossguide && level[0].depth >= max_depth - 1 ? 1 : 0;   // (their children are leaves)
             GBT_HIP(ctx, gbt_launch_eval(s, pool, (const EvalNode *)(ws + L.eval_nodes), (int)enodes.size(), nb, F, B, chunks,
-                                         inv_sg, inv_sh, lambda, params->min_child_weight, (gbt_split *)(rb(ctx) + kSplitRb)));
+                                         inv_sg, inv_sh, lambda, params->min_child_weight, (gbt_split *)(rb(ctx) + kSplitRb),
+                                         plain));
             gbt_prof_end(ctx);
             GBT_SYNC(ctx);
             sel_nodes.clear();

@@ -223,6 +223,8 @@ struct EvalTail {
     int n, clear;
     int64_t clear_slot, clear_slot_end;
     int src_stride = 1;   // word i is src[i * src_stride]
+    int skip_store = 0;   // 1: a histogram made by subtraction is evaluated but not stored (nothing below these nodes
+                          // will subtract from it: their children are leaves)
 };
 // The cursors of the passes that partition and build histograms in one launch lie one per 128-byte line
 // (index * kCursorStride): atomics on words of one line take turns as if they were one address.

@@ -80,6 +80,7 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     int64_t *hist = pool + nd.hist_off;
     // the larger sibling: its histogram is made here, as parent - built (exact: integers), and kept
     const bool subtract = nd.parent_off != GBT_NO_HIST;
+    const bool store = subtract && !tail.skip_store;
     const int64_t *hpar = pool + (subtract ? nd.parent_off : 0), *hblt = pool + (subtract ? nd.built_off : 0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t Gq = nd.Gq, Hq = nd.Hq;
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
             fetch(f + kEvalWaves, g1, h1);
             int nbf = nb[f];
             if (nbf > B) nbf = B;
-            if (subtract && lane < nbf) {
+            if (store && lane < nbf) {
                 int64_t *hf = hist + (int64_t)f * B * 2;
                 hf[2 * lane] = g0;
                 hf[2 * lane + 1] = h0;
@@ -181,12 +182,14 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
         int64_t *hf = hist + (int64_t)f * B * 2;
         // pass 1: the feature's present mass -> the node's missing mass
         int64_t sg = 0, sh = 0;
+        const int64_t *pf = hpar + (int64_t)f * B * 2, *bf = hblt + (int64_t)f * B * 2;
         if (subtract) {   // (the lane that stores bin b is the lane that reads it again in pass 2)
-            const int64_t *pf = hpar + (int64_t)f * B * 2, *bf = hblt + (int64_t)f * B * 2;
             for (int b = lane; b < nbf; b += 64) {
                 const int64_t g = pf[2 * b] - bf[2 * b], h = pf[2 * b + 1] - bf[2 * b + 1];
-                hf[2 * b] = g;
-                hf[2 * b + 1] = h;
+                if (store) {
+                    hf[2 * b] = g;
+                    hf[2 * b + 1] = h;
+                }
                 sg += g;
                 sh += h;
             }
@@ -206,8 +209,16 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
         int64_t cg = 0, ch = 0;
         for (int b0 = 0; b0 < nbf; b0 += 64) {
             const int b = b0 + lane;
-            const int64_t pg = b < nbf ? hf[2 * b] : 0;
-            const int64_t ph = b < nbf ? hf[2 * b + 1] : 0;
+            int64_t pg = 0, ph = 0;
+            if (b < nbf) {
+                if (subtract && !store) {   // nothing was stored: the difference once more (the words are cached)
+                    pg = pf[2 * b] - bf[2 * b];
+                    ph = pf[2 * b + 1] - bf[2 * b + 1];
+                } else {
+                    pg = hf[2 * b];
+                    ph = hf[2 * b + 1];
+                }
+            }
             scan_and_score(f, nbf, b0, pg, ph, cg, ch, Gm, Hm, has_missing);
         }
     }
