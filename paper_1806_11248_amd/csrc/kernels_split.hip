@@ -22,16 +22,6 @@ namespace {
 constexpr int kEvalBlock = 256;
 constexpr int kEvalWaves = kEvalBlock / 64;
 
-__device__ inline int64_t shfl_i64(int64_t v, int src) {
-    int lo = __shfl((int)(v & 0xffffffff), src);
-    int hi = __shfl((int)(v >> 32), src);
-    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
-}
-__device__ inline int64_t shfl_up_i64(int64_t v, int d) {
-    int lo = __shfl_up((int)(v & 0xffffffff), d);
-    int hi = __shfl_up((int)(v >> 32), d);
-    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
-}
 __device__ inline int64_t shfl_xor_i64(int64_t v, int m) {
     int lo = __shfl_xor((int)(v & 0xffffffff), m);
     int hi = __shfl_xor((int)(v >> 32), m);
@@ -39,6 +29,30 @@ __device__ inline int64_t shfl_xor_i64(int64_t v, int m) {
 }
 __device__ inline double shfl_xor_f64(double v, int m) {
     return __longlong_as_double(shfl_xor_i64(__double_as_longlong(v), m));
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (no LDS crossbar): shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes (a lane without a source adds 0), then lane 15 of rows 0 and 2 into rows 1
+// and 3, then lane 31 into rows 2 and 3.  A 64-bit value moves as its two halves.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int64_t dpp_i64(int64_t v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(v & 0xffffffff), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(v >> 32), CTRL, ROW_MASK, 0xf, false);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+__device__ __forceinline__ int64_t wave_scan_i64(int64_t x) {
+    x += dpp_i64<0x111, 0xf>(x);   // row_shr:1
+    x += dpp_i64<0x112, 0xf>(x);   // row_shr:2
+    x += dpp_i64<0x114, 0xf>(x);   // row_shr:4
+    x += dpp_i64<0x118, 0xf>(x);   // row_shr:8
+    x += dpp_i64<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
+    x += dpp_i64<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3
+    return x;
+}
+__device__ __forceinline__ int64_t last_lane_i64(int64_t v) {
+    const int lo = __builtin_amdgcn_readlane((int)(v & 0xffffffff), 63);
+    const int hi = __builtin_amdgcn_readlane((int)(v >> 32), 63);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
 }
 
 struct Best {
@@ -93,22 +107,17 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
     best.GLq = 0;
     best.HLq = 0;
 
-    // one 64-bin piece of a feature's scan: the inclusive prefix over the piece's bins (carried in from cg, ch),
-    // then the gain of every (bin, direction) of the piece
-    auto scan_and_score = [&](int f, int nbf, int b0, int64_t pg, int64_t ph, int64_t &cg, int64_t &ch, int64_t Gm, int64_t Hm,
-                              bool has_missing) __attribute__((always_inline)) {
+    // one 64-bin piece of a feature's scan: the inclusive prefix over the piece's bins (carried in from cg, ch) ...
+    auto scan = [&](int64_t &pg, int64_t &ph, int64_t &cg, int64_t &ch) __attribute__((always_inline)) {
+        pg = wave_scan_i64(pg) + cg;
+        ph = wave_scan_i64(ph) + ch;
+        cg = last_lane_i64(pg);
+        ch = last_lane_i64(ph);
+    };
+    // ... then the gain of every (bin, direction) of the piece; pg, ph: the inclusive sums of bin b0 + lane
+    auto score = [&](int f, int nbf, int b0, int64_t pg, int64_t ph, int64_t Gm, int64_t Hm, bool has_missing)
+                     __attribute__((always_inline)) {
         const int b = b0 + lane;
-        for (int d = 1; d < 64; d <<= 1) {
-            int64_t tg = shfl_up_i64(pg, d), th = shfl_up_i64(ph, d);
-            if (lane >= d) {
-                pg += tg;
-                ph += th;
-            }
-        }
-        pg += cg;
-        ph += ch;
-        cg = shfl_i64(pg, 63);
-        ch = shfl_i64(ph, 63);
         if (b < nbf) {
             for (int dir = 0; dir <= (has_missing ? 1 : 0); ++dir) {
                 if (b == nbf - 1 && (dir == 1 || !has_missing)) continue;   // right side empty
@@ -164,14 +173,11 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
                 hf[2 * lane] = g0;
                 hf[2 * lane + 1] = h0;
             }
-            int64_t sg = g0, sh = h0;
-            for (int o = 32; o > 0; o >>= 1) {
-                sg += shfl_xor_i64(sg, o);
-                sh += shfl_xor_i64(sh, o);
-            }
-            const int64_t Gm = Gq - sg, Hm = Hq - sh;
+            // the scan's last lane holds the feature's present mass (lanes past nbf hold zeros): no reduction of its own
             int64_t cg = 0, ch = 0;
-            if (nbf > 0) scan_and_score(f, nbf, 0, g0, h0, cg, ch, Gm, Hm, (Gm != 0) || (Hm != 0));
+            scan(g0, h0, cg, ch);
+            const int64_t Gm = Gq - cg, Hm = Hq - ch;
+            if (nbf > 0) score(f, nbf, 0, g0, h0, Gm, Hm, (Gm != 0) || (Hm != 0));
             g0 = g1;
             h0 = h1;
         }
@@ -199,10 +205,8 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
                 sh += hf[2 * b + 1];
             }
         }
-        for (int o = 32; o > 0; o >>= 1) {
-            sg += shfl_xor_i64(sg, o);
-            sh += shfl_xor_i64(sh, o);
-        }
+        sg = last_lane_i64(wave_scan_i64(sg));
+        sh = last_lane_i64(wave_scan_i64(sh));
         const int64_t Gm = Gq - sg, Hm = Hq - sh;
         const bool has_missing = (Gm != 0) || (Hm != 0);
         // pass 2: inclusive scan over bins, 64 at a time
@@ -219,7 +223,8 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
                     ph = hf[2 * b + 1];
                 }
             }
-            scan_and_score(f, nbf, b0, pg, ph, cg, ch, Gm, Hm, has_missing);
+            scan(pg, ph, cg, ch);
+            score(f, nbf, b0, pg, ph, Gm, Hm, has_missing);
         }
     }
 
