@@ -21,6 +21,7 @@ namespace {
 
 constexpr int kEvalBlock = 256;
 constexpr int kEvalWaves = kEvalBlock / 64;
+constexpr int kEvalGroups = 8192;
 
 __device__ inline int64_t shfl_xor_i64(int64_t v, int m) {
     int lo = __shfl_xor((int)(v & 0xffffffff), m);
@@ -279,6 +280,10 @@ __global__ __launch_bounds__(kEvalBlock) void eval_kernel(
 int gbt_eval_chunks(int F, int n_nodes, size_t record_budget_bytes) {
     int chunks = (F + 3) / 4;     // one feature per wave while that keeps the number of records small
     if (chunks > 64) chunks = 64;
+    // a level of many nodes fills the chip without chunks: about kEvalGroups workgroups per launch are enough, and
+    // every chunk more is a record the host reads back and merges
+    const int by_nodes = (kEvalGroups + n_nodes - 1) / (n_nodes > 0 ? n_nodes : 1);
+    if (chunks > by_nodes) chunks = by_nodes;
     while (chunks > 1 && (size_t)n_nodes * chunks * sizeof(gbt_split) > record_budget_bytes) --chunks;
     return chunks < 1 ? 1 : chunks;
 }
