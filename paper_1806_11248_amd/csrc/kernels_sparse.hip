@@ -11,6 +11,7 @@
 // The entry stream is read as aligned 32-bit words, up to nine words per row and step, so the buffer
 // must extend 32 entries past the last one (gbt_sparse_capacity).
 #include "gbt_internal.h"
+#include "wave_scan.h"
 
 namespace {
 
@@ -401,12 +402,7 @@ __global__ __launch_bounds__(kSpBlock) void sparse_part_kernel(const uint32_t *_
         const uint64_t below = (1ull << lane) - 1ull;
         within_rows[k] = (uint32_t)__popcll((left[k] ? bl : br) & below);
         unsigned long long x = !live[k] ? 0ull : left[k] ? (unsigned long long)rlen[k] : ((unsigned long long)rlen[k] << 32);
-        unsigned long long incl = x;
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t ylo = (uint32_t)__shfl_up((int)(uint32_t)incl, o);
-            const uint32_t yhi = (uint32_t)__shfl_up((int)(uint32_t)(incl >> 32), o);
-            if (lane >= o) incl += ((unsigned long long)yhi << 32) | ylo;
-        }
+        const unsigned long long incl = (unsigned long long)wave_scan_i64((int64_t)x);
         const unsigned long long excl = incl - x;
         within_ent[k] = left[k] ? (uint32_t)excl : (uint32_t)(excl >> 32);
         if (lane == 63) {
