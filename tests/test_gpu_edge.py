@@ -120,6 +120,43 @@ def test_predict_several_trees_in_order(ctx, oracle):
     assert np.array_equal(got, margin) and np.array_equal(got_raw, margin)
 
 
+# (rows, features, bins, missing): row widths on both sides of every switch between the walks over packed rows --
+# up to 128 bits in registers, 8-bit rows of at most 16 bytes by byte selectors, 33 to 128 bytes staged through LDS a
+# wave's 64 rows at a time, anything else gathered level by level -- and row counts around a wave and a block of rows
+PREDICT_WIDTHS = [
+    (1, 40, 300, 0.3), (63, 40, 300, 0.3), (65, 40, 300, 0.0), (4097, 40, 300, 0.5),     # 9 bits x 40 = 45 bytes
+    (5000, 29, 256, 0.0), (5000, 29, 257, 0.2),                                          # 29 and 33 bytes
+    (777, 100, 1000, 0.1), (3000, 102, 1000, 0.1), (2000, 103, 1000, 0.0),               # 125, 127.5, 128.75 bytes
+    (6000, 16, 256, 0.0), (6000, 17, 256, 0.1), (4000, 12, 700, 0.2),                    # 16, 17 bytes; 15 bytes of 10 bits
+]
+
+
+@pytest.mark.parametrize("n,F,B,miss", PREDICT_WIDTHS)
+def test_predict_over_packed_rows_of_every_width(ctx, oracle, n, F, B, miss):
+    import paper_1806_11248_amd as g
+    rng = np.random.default_rng(n * 131 + F)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    X[rng.random((n, F)) < miss] = np.nan
+    print(f"predict over packed rows n={n} F={F} B={B} miss={miss}", flush=True)
+    o = oracle_prep(oracle, X, B)
+    packed = dev(oracle.pack(o["sym"], o["bits"]).view(np.int32))
+    # two trees that need not be good, only deep and different: grown by the oracle on random pairs
+    trees = []
+    for k in range(2):
+        gp = np.stack([rng.standard_normal(n), rng.random(n) + 0.5], 1).astype(np.float32)
+        t, _, _ = oracle.grow_tree(o["sym"], o["nb"], o["cuts"], o["missing"], gp, max_depth=5 + k, max_bins=B, lam=1.0, gamma=0.0,
+                                   min_child_weight=0.0)
+        trees.append(t)
+    m0 = rng.standard_normal(n).astype(np.float32)
+    ref = m0
+    for t in trees:
+        ref = oracle.predict_sym(t, o["sym"], o["missing"], 0.3, ref)
+    got = ctx.predict(trees, dev(m0), 0.3, packed=packed, bits=o["bits"], missing_sym=o["missing"], n=n, F=F).cpu().numpy()
+    assert np.array_equal(got, ref)
+    one = ctx.predict(trees[:1], dev(m0), 0.3, packed=packed, bits=o["bits"], missing_sym=o["missing"], n=n, F=F).cpu().numpy()
+    assert np.array_equal(one, oracle.predict_sym(trees[0], o["sym"], o["missing"], 0.3, m0))
+
+
 @settings(max_examples=30, deadline=None, suppress_health_check=list(HealthCheck), derandomize=True)
 @given(seed=st.integers(0, 2 ** 31 - 1), n=st.integers(1, 3000), F=st.integers(1, 20),
        B=st.sampled_from([2, 5, 16, 33, 64, 256]), miss=st.sampled_from([0.0, 0.0, 0.3, 0.9]),
