@@ -1300,9 +1300,15 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
         // to be worth merging an LDS histogram into HBM for
         uint32_t part_tile = fused ? (uint32_t)gbt_partition_fused_tile(W[wnext]) : (uint32_t)GBT_PART_TILE;
         if (with_hist) {
-            // (the two-histogram pass merges two histograms per span and has one workgroup per CU: half the spans)
+            // Every span merges a whole histogram (two in the two-histogram pass, which has one workgroup per CU) into
+            // HBM at its end, 64-bit global atomics that the chip retires slowly: a pass that moves nothing has little
+            // else to wait for, so it takes half the spans -- and the two-histogram pass, while the level has few
+            // segments to balance, three eighths (measured per level on 115M x 13: 0.50 -> 0.45, 0.57 -> 0.53 ms; with
+            // 32 segments of unequal length fewer spans lose more to imbalance than they save: 0.51 -> 0.59 ms).
             const uint32_t t = (uint32_t)gbt_part_hist_tile();
-            const double want = part_rows / ((double)ctx->num_cu * (in_place ? std::max(1, ctx->hist_jobs_per_cu / 2) : ctx->hist_jobs_per_cu));
+            const int J = ctx->hist_jobs_per_cu;
+            const int per_cu = in_place ? std::max(1, sel_nodes.size() < 32 ? 3 * J / 8 : J / 2) : nomove ? std::max(1, J / 2) : J;
+            const double want = part_rows / ((double)ctx->num_cu * per_cu);
             part_tile = (uint32_t)std::min<double>(std::max<double>(std::ceil(want / t), 4.0), (double)((1u << 21) / t)) * t;
         }
         pjobs.clear();
@@ -1711,7 +1717,10 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 gbt_prof_end(ctx);
             }
             const uint32_t t = (uint32_t)gbt_part_hist_tile();
-            const double want = (double)built_rows / ((double)ctx->num_cu * ctx->hist_jobs_per_cu);
+            // (the root kernel's loop over records: as many spans as workgroups are resident, four per compute unit --
+            // every span merges a whole histogram into HBM at its end, and those atomics are what such a launch waits for)
+            const bool rec8 = ctx->hist8 && bits == 8 && F <= 16 && pl.n_ftiles == 1;
+            const double want = (double)built_rows / ((double)ctx->num_cu * (rec8 ? 4 : ctx->hist_jobs_per_cu));
             const uint32_t ktile = (uint32_t)std::min<double>(std::max<double>(std::ceil(want / t), 4.0), (double)((1u << 21) / t)) * t;
             kjobs.clear();
             uint32_t kspans = 0;
@@ -1737,10 +1746,15 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
                 if (st != GBT_OK) return st;
                 gbt_prof_begin(ctx, GBT_PROF_HIST_NODE, (double)built_rows * 4.0 * gbt_part_hist_record_words(F),
                                (double)built_rows * ((double)row_bits / 8.0 + 8.0), child_depth, (double)built_rows * F);
-                GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq, W[wnext].sym, nullptr, F, B,
-                                                  (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs), (int)kjobs.size(),
-                                                  (int)kspans, ktile, (unsigned long long *)(ws + L.state), pool, false,
-                                                  nullptr, 1.0, 1.0, hq_uni));
+                if (rec8)   // every row is added: the root kernel's loop, over records
+                    GBT_HIP(ctx, gbt_launch_hist8_records(ctx, W[wnext].sym, F, B, (uint32_t)missing_sym,
+                                                          (const PartJob *)(ws + L.jobs), (int)kjobs.size(), (int)kspans, ktile,
+                                                          pool, hq_uni));
+                else
+                    GBT_HIP(ctx, gbt_launch_part_hist(ctx, packed, gbt_packed_words(n, F, bits), gq, W[wnext].sym, nullptr, F, B,
+                                                      (uint32_t)missing_sym, (const PartJob *)(ws + L.jobs), (int)kjobs.size(),
+                                                      (int)kspans, ktile, (unsigned long long *)(ws + L.state), pool, false,
+                                                      nullptr, 1.0, 1.0, hq_uni));
                 gbt_prof_end(ctx);
             }
         } else if (children_need_hist && !with_hist) {

@@ -318,6 +318,9 @@ struct Hist8Filter {
 hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int F, int B, uint32_t missing,
                             const Hist8Pairs &p, int64_t *hist_out, int *n_jobs_out = nullptr,
                             const Hist8Filter *filter = nullptr);
+hipError_t gbt_launch_hist8_records(gbt_ctx *ctx, const uint32_t *records, int F, int B, uint32_t missing,
+                                    const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span, int64_t *pool,
+                                    int32_t hq_uniform);
 // Partition and the histogram of one child of every job in one pass (8-bit symbols, at most 16
 // features, the bins of all features in one LDS tile: gbt_part_hist_ok).  No ids, order inside a
 // child not kept.  Rows travel as records of gbt_part_hist_record_words(F) words (symbols, padding,

@@ -65,6 +65,14 @@ struct Hist8Args {
     // staying where they are); the rows that go left are counted into *lefts
     uint32_t split_feature, split_bin, split_default_left, take_left;
     unsigned long long *lefts;
+    // FIX == 3: the rows are records (symbols, padding, 7 bytes of fixed-point pair) of several nodes, each node's
+    // contiguous: workgroup = one span of rows_per_span rows of a job (PartJob: seg_begin, seg_len, tile_begin = its
+    // first span, hist_off = the node's histogram inside pool)
+    const uint32_t *records;
+    const PartJob *jobs;
+    int n_jobs;
+    uint32_t rows_per_span;
+    int64_t *pool;
 };
 
 // Rows of workgroup (column c, slice k): the n rows are cut into `cols` equal columns, a column into
@@ -97,12 +105,15 @@ __device__ __forceinline__ void pk_check8(uint32_t side_addr, unsigned long long
 
 // NS  : unrolled slots = features of the tile rounded up to 4, 8, 12, 13, 16 (ft > NS - 4, or NS - 1 for 13)
 // UNI : the uniform-h word
-// FIX : 0 fixed-point pairs are read; 1 fp32 pairs rounded through fp64; 2 rounded in fp32
+// FIX : 0 fixed-point pairs are read; 1 fp32 pairs rounded through fp64; 2 rounded in fp32; 3 the rows are records
+//       that carry their pair (Hist8Args)
 // FILT: see Hist8Args
 template <int NS, bool UNI, int FIX, int BLOCK, int MINWG, int PF, bool FILT>
 __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) {
-    constexpr int NW = (NS + 6) / 4;   // words a row of NS - 3 .. NS bytes can touch at any alignment
-    constexpr int SW = (NS + 3) / 4;   // words of symbols after realignment
+    constexpr bool REC = FIX == 3;
+    constexpr int RW = (NS + 7 + 3) / 4;                // words of a record
+    constexpr int NW = REC ? RW : (NS + 6) / 4;         // words a row of NS - 3 .. NS bytes can touch at any alignment
+    constexpr int SW = (NS + 3) / 4;                    // words of symbols after realignment
     extern __shared__ unsigned long long lds[];
     unsigned long long *main_ = lds;
     uint32_t *side = (uint32_t *)(lds + kLdsWords);
@@ -133,19 +144,36 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
     __syncthreads();
 
     // this workgroup's rows
-    const uint32_t c = blockIdx.x % a.cols, sl = blockIdx.x / a.cols;
-    const uint64_t col = ((uint64_t)a.n + a.cols - 1) / a.cols;
-    const uint64_t c0 = (uint64_t)c * col < (uint64_t)a.n ? (uint64_t)c * col : (uint64_t)a.n;
-    const uint64_t c1 = c0 + col < (uint64_t)a.n ? c0 + col : (uint64_t)a.n;
-    const uint64_t e0 = slice_edge(c1 - c0, sl, a.slots, a.stagger), e1 = slice_edge(c1 - c0, sl + 1, a.slots, a.stagger);
-    const uint64_t job_row0 = c0 + e0;
-    const uint32_t job_rows = (uint32_t)(e1 - e0);
-    const uint64_t job_byte0 = job_row0 * (uint64_t)ft;
+    uint64_t job_row0;
+    uint32_t job_rows;
+    int64_t *__restrict__ out = a.out;
+    if (REC) {
+        int lo = 0, hi = a.n_jobs;   // last job whose first span is <= this one
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (a.jobs[mid].tile_begin <= blockIdx.x) lo = mid; else hi = mid;
+        }
+        const PartJob job = a.jobs[lo];
+        const uint32_t span_begin = (blockIdx.x - job.tile_begin) * a.rows_per_span;
+        job_rows = job.seg_len - span_begin < a.rows_per_span ? job.seg_len - span_begin : a.rows_per_span;
+        job_row0 = (uint64_t)job.seg_begin + span_begin;
+        out = a.pool + job.hist_off;
+    } else {
+        const uint32_t c = blockIdx.x % a.cols, sl = blockIdx.x / a.cols;
+        const uint64_t col = ((uint64_t)a.n + a.cols - 1) / a.cols;
+        const uint64_t c0 = (uint64_t)c * col < (uint64_t)a.n ? (uint64_t)c * col : (uint64_t)a.n;
+        const uint64_t c1 = c0 + col < (uint64_t)a.n ? c0 + col : (uint64_t)a.n;
+        const uint64_t e0 = slice_edge(c1 - c0, sl, a.slots, a.stagger), e1 = slice_edge(c1 - c0, sl + 1, a.slots, a.stagger);
+        job_row0 = c0 + e0;
+        job_rows = (uint32_t)(e1 - e0);
+    }
+    const uint64_t job_byte0 = REC ? 0 : job_row0 * (uint64_t)ft;
     const char *__restrict__ pb = (const char *)(a.packed + (job_byte0 >> 2));
     const uint32_t a0 = (uint32_t)(job_byte0 & 3);
-    const float2 *__restrict__ gp = a.gpair + job_row0;
-    const int2 *__restrict__ gq = a.gq + job_row0;
-    int2 *__restrict__ gqo = a.gq_out ? a.gq_out + job_row0 : nullptr;
+    const float2 *__restrict__ gp = a.gpair + (REC ? 0 : job_row0);
+    const int2 *__restrict__ gq = a.gq + (REC ? 0 : job_row0);
+    int2 *__restrict__ gqo = (!REC && a.gq_out) ? a.gq_out + job_row0 : nullptr;
+    const uint32_t *__restrict__ recs = REC ? a.records + job_row0 * RW : nullptr;
 
     long long sum_g = 0, sum_h = 0;   // UNI: sum_g holds the sum of the packed words (G * 2^18 + rows)
     // FILT: byte `split_feature` of the realigned row, and the rows seen going left
@@ -158,11 +186,16 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
     int2 gqq[PF + 1];
     auto issue = [&](int slot, uint32_t i) __attribute__((always_inline)) {
         if (i < job_rows) {
-            const uint32_t b4 = (a0 + i * (uint32_t)ft) & ~3u;
+            if (REC) {
 #pragma unroll
-            for (int k = 0; k < NW; ++k) wq[slot][k] = *(const uint32_t *)(pb + b4 + 4 * k);
-            if (FIX != 0) vq[slot] = gp[i];
-            else gqq[slot] = gq[i];
+                for (int k = 0; k < NW; ++k) wq[slot][k] = recs[(size_t)i * RW + k];
+            } else {
+                const uint32_t b4 = (a0 + i * (uint32_t)ft) & ~3u;
+#pragma unroll
+                for (int k = 0; k < NW; ++k) wq[slot][k] = *(const uint32_t *)(pb + b4 + 4 * k);
+                if (FIX != 0) vq[slot] = gp[i];
+                else gqq[slot] = gq[i];
+            }
         }
     };
 #pragma unroll
@@ -187,9 +220,13 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
         } else if (FIX == 2) {
             q.x = (int)rintf(v.x * a.sgf);
             q.y = (int)rintf(v.y * a.shf);
+        } else if (REC) {   // the pair: bytes 1..3 of word RW - 2 and word RW - 1 (28 bits of g, signed, then 24 of h)
+            const uint32_t qlo = (w[RW - 2] >> 8) | (w[RW - 1] << 24), qhi = w[RW - 1] >> 8;
+            q.x = (int32_t)(qlo << 4) >> 4;
+            q.y = (int32_t)((qlo >> 28) | (qhi << 4));
         }
-        if (FIX != 0 && gqo) gqo[i] = q;
-        const uint32_t al = (a0 + i * (uint32_t)ft) & 3u;
+        if (FIX != 0 && !REC && gqo) gqo[i] = q;
+        const uint32_t al = REC ? 0u : (a0 + i * (uint32_t)ft) & 3u;
         uint32_t W[4] = {0, 0, 0, 0}, V[SW];
 #pragma unroll
         for (int k = 0; k < SW; ++k) W[k] = __builtin_amdgcn_alignbyte(w[k + 1 < NW ? k + 1 : NW - 1], w[k], al);
@@ -265,10 +302,10 @@ __global__ __launch_bounds__(BLOCK, MINWG) void hist8_kernel(const Hist8Args a) 
             g = ((int64_t)wv - rows) >> kRowsShift;
             h = rows * a.hq_uniform;
         }
-        if (g != 0) atomicAdd((unsigned long long *)(a.out + 2 * (int64_t)i), (unsigned long long)g);
-        if (h != 0) atomicAdd((unsigned long long *)(a.out + 2 * (int64_t)i + 1), (unsigned long long)h);
+        if (g != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i), (unsigned long long)g);
+        if (h != 0) atomicAdd((unsigned long long *)(out + 2 * (int64_t)i + 1), (unsigned long long)h);
     }
-    if (a.sums) {   // totals of this workgroup's rows into its own slot: same-address global atomics take turns
+    if (!REC && a.sums) {   // totals of this workgroup's rows into its own slot: same-address global atomics take turns
         long long G = sum_g, H = sum_h;
         if (UNI) {
             const long long rows = sum_g & (long long)kUniformMaxRows;
@@ -314,7 +351,9 @@ hipError_t pick8f(hipStream_t s, const Hist8Args &a, int grid) {
 template <bool UNI, int FIX>
 hipError_t pick8(hipStream_t s, const Hist8Args &a, int grid) {
     // (the filtered form reads fixed-point pairs or rounds fp32 pairs in fp32: the two ways its callers have them)
-    if (a.lefts != nullptr && FIX != 1) return pick8f<UNI, FIX == 1 ? 0 : FIX, true>(s, a, grid);
+    if constexpr (FIX == 0 || FIX == 2) {
+        if (a.lefts != nullptr) return pick8f<UNI, FIX, true>(s, a, grid);
+    }
     if (a.lefts != nullptr) return hipErrorInvalidValue;
     return pick8f<UNI, FIX, false>(s, a, grid);
 }
@@ -392,4 +431,27 @@ hipError_t gbt_launch_hist8(gbt_ctx *ctx, const uint32_t *packed, int64_t n, int
     if (mode == 0) return pick8<false, 0>(ctx->stream, a, grid);
     if (mode == 1) return pick8<false, 1>(ctx->stream, a, grid);
     return pick8<false, 2>(ctx->stream, a, grid);
+}
+
+// The same kernel over records: the histograms of several nodes, each from its contiguous records (every row of a
+// job's segment is added).  jobs [dev]: PartJob with seg_begin, seg_len, tile_begin (first span), hist_off; spans of
+// rows_per_span rows; the histograms (pool + hist_off) must have been cleared.  hq_uniform >= 0: every row has that
+// hessian (the row-count form, where a span is short enough for it).
+hipError_t gbt_launch_hist8_records(gbt_ctx *ctx, const uint32_t *records, int F, int B, uint32_t missing,
+                                    const PartJob *jobs, int n_jobs, int n_spans, uint32_t rows_per_span, int64_t *pool,
+                                    int32_t hq_uniform) {
+    if (n_jobs <= 0 || n_spans <= 0) return hipSuccess;
+    if (F < 1 || F > 16 || rows_per_span == 0 || rows_per_span > kGeneralMaxRows) return hipErrorInvalidValue;
+    Hist8Args a{};
+    a.ft = F;
+    a.B = B;
+    a.missing = missing;
+    a.hq_uniform = hq_uniform >= 0 ? hq_uniform : 0;
+    a.records = records;
+    a.jobs = jobs;
+    a.n_jobs = n_jobs;
+    a.rows_per_span = rows_per_span;
+    a.pool = pool;
+    if (hq_uniform >= 0 && rows_per_span <= kUniformMaxRows) return pick8<true, 3>(ctx->stream, a, n_spans);
+    return pick8<false, 3>(ctx->stream, a, n_spans);
 }
