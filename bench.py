@@ -10,7 +10,9 @@ the paper's pipeline, and are reported separately.
 
 Prints ONE JSON line.  `value` = rows*features per second of a whole step on the headline workload.
 Every `roofline*` object is stated on the bytes the METHOD needs (`algorithmic_bytes_per_launch`: a
-histogram rows_built * (F*bits/8 + 8 [+ 4 with a row id]), a repartition 4 + 4 + bits/8 per row), divided
+histogram rows_built * (F*bits/8 + 8 [+ 4 with a row id]), a repartition 4 + 4 + bits/8 per row and level -- a pass
+that leaves the rows where they are counts the symbol alone, the move that later puts them in order over L levels of
+splits at once counts the id traffic of those L levels, 8 L + bits/8 per row), divided
 by the launch time measured with HIP events on the library's stream inside the timed region; the bytes this
 library's design moves (whole records read and written) are given beside it as `design_bytes_per_launch`.
 `roofline` is the kernel the step spends most time in, `roofline_hist_root` the root-node launch (the
@@ -295,7 +297,7 @@ def run_workload(g, a, cfg, rows, steps, warmup, layout="dense", policy="depthwi
     # path 2, depth-wise: which levels a class covers depends on the depth (see gbt_grow_tree): with depth 8 the
     # rows stay in place at levels 1, 3, 4, 6, 7 and are moved over several levels of splits at levels 2 and 5
     node_kernel = ("part_hist_kernel (partition + one child's histogram in one pass) where rows move at every level; "
-                   "hist_keep_kernel over the built children's records behind a move over several levels"
+                   "hist8_kernel over the built children's records behind a move over several levels"
                    if path == 2 else node_hist_kernel)
     part_kernel = ("move_levels_kernel (rows moved over two or three levels of splits at once)"
                    + ("" if one_call else " + count2_kernel (row counts of the leaves)") if path == 2 and not lossguide else

@@ -1436,8 +1436,11 @@ static int32_t grow_impl(gbt_ctx *ctx, const uint32_t *packed, int32_t bits, int
             st = upload(ctx, m3jobs.data(), m3jobs.size() * sizeof(Move3Job), ws + L.jobs);
             if (st != GBT_OK) return st;
             const double rec_bytes3 = 4.0 * gbt_part_hist_record_words(F);
+            // What the method needs for this: it repartitions at every level, 4 bytes of row id read and 4 written per
+            // row, plus the symbol that decides.  A move over `move_levels` levels of splits is the repartition of that
+            // many levels (the passes that left the rows in place were credited with their symbol only).
             gbt_prof_begin(ctx, GBT_PROF_PARTITION, m3_rows * (rec_bytes3 + (wcur == 2 ? row_bits / 8.0 + 8.0 : rec_bytes3)),
-                           m3_rows * (8.0 + bits / 8.0));
+                           m3_rows * (8.0 * move_levels + bits / 8.0));
             if (wcur == 2)
                 GBT_HIP(ctx, gbt_launch_move2_first(ctx, packed, gbt_packed_words(n, F, bits), gq, pairs_stay_fp32 ? gpair : nullptr,
                                                     scale[0], scale[1], W[wnext].sym_rw, n, F, (uint32_t)missing_sym,
